@@ -1,0 +1,155 @@
+/*
+ * jz.h -- C ABI of libjz: the single-GPU hot path of mixed-precision CNN training
+ * with LARS (Jia et al. 2018, "Highly Scalable Deep Learning Training System with
+ * Mixed-Precision", Section 4.1) for AMD MI355X (gfx950).
+ *
+ * What the path is (Section 4.1, Fig. 2; Section 2.2's three techniques; Section 5.2):
+ *   forward / backward in FP16 storage with FP32 accumulation, result rounded to
+ *   FP16 before it is stored; an FP32 master copy of the weights; gradients that
+ *   carry a loss scale S; weights and gradients widened to FP32 before the layer-wise
+ *   adaptive rate of Eq. 1 is applied and narrowed to FP16 afterwards.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller and 16-byte aligned.
+ *     Descriptor / table pointers are HOST pointers unless said otherwise.
+ *   - "fp16" means IEEE binary16 bit patterns (2 bytes per element).
+ *   - Activations are NHWC, filters KRSC, conv outputs NPQK, innermost index
+ *     contiguous; P = floor((H + 2*pad_h - R)/stride_h) + 1, likewise Q.
+ *   - Convolution is cross-correlation (no filter flip), zero padding, dilation 1,
+ *     one group.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream); calls
+ *     return without synchronising.  Nothing is allocated or freed by the
+ *     library; scratch comes from the caller's workspace `ws` (size from the matching
+ *     *_workspace_bytes call; may be NULL when that size is 0).
+ *   - Return value: JZ_OK or a negative JZ_ERR_* code.  On error nothing was enqueued
+ *     and no output was touched.  Inf/NaN in data are not errors: they propagate per
+ *     IEEE in the GEMMs, and in the LARS update they raise the overflow flag.
+ *   - Outputs must not overlap inputs or the workspace (checked for the pointers
+ *     given; JZ_ERR_ALIAS), except the in-place state buffers of the LARS update.
+ *   - Same inputs give bit-identical outputs from run to run (no float atomics).
+ */
+#ifndef JZ_H_
+#define JZ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  JZ_OK = 0,
+  JZ_ERR_NULL = -1,        /* a required pointer is NULL */
+  JZ_ERR_SHAPE = -2,       /* non-positive dimension, empty output, pad >= filter size, bad offsets table */
+  JZ_ERR_UNSUPPORTED = -3, /* valid but not implemented (e.g. tensor with >= 2^31 elements) */
+  JZ_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than *_workspace_bytes reports */
+  JZ_ERR_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
+  JZ_ERR_ALIAS = -6,       /* an output overlaps an input or the workspace */
+  JZ_ERR_LAUNCH = -7,      /* the HIP runtime refused a launch or copy */
+  JZ_ERR_NOT_PREPARED = -8 /* LARS workspace was not prepared for this parameter set */
+};
+
+enum { JZ_FWD = 0, JZ_BWD_DATA = 1, JZ_BWD_WEIGHT = 2 };
+
+/* One convolution layer: x[N,H,W,C] (*) w[K,R,S,C] -> y[N,P,Q,K]. */
+typedef struct {
+  int N, H, W, C;
+  int K, R, S;
+  int stride_h, stride_w;
+  int pad_h, pad_w;
+} jz_conv_desc;
+
+/* Scratch bytes `op` (JZ_FWD / JZ_BWD_DATA / JZ_BWD_WEIGHT) needs for this layer. */
+int jz_conv2d_workspace_bytes(int op, const jz_conv_desc* desc, size_t* bytes);
+
+/* Forward pass of one layer (Section 4.1: forward propagation in FP16, FP32 accumulate):
+ *   y[n,p,q,k] = RNE16( sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c] )
+ * x16: in [N,H,W,C] fp16; w16: in [K,R,S,C] fp16 (the FP16 rounding of the master weights);
+ * y16: out [N,P,Q,K] fp16. */
+int jz_conv2d_fwd(const jz_conv_desc* desc, const void* x16, const void* w16, void* y16, void* ws, size_t ws_bytes,
+                  void* hip_stream);
+
+/* Backward pass w.r.t. the layer input (Section 4.1: backward propagation in FP16): the adjoint of the
+ * forward map in x,
+ *   dx[n,h,w,c] = RNE16( sum over (p,q,k,r,s) with p*stride_h - pad_h + r == h and q*stride_w - pad_w + s == w
+ *                        of dy[n,p,q,k] * w[k,r,s,c] ),
+ * input pixels no output reads get 0.
+ * dy16: in [N,P,Q,K] fp16 (loss-scaled); w16: in [K,R,S,C]; dx16: out [N,H,W,C] fp16, fully overwritten. */
+int jz_conv2d_bwd_data(const jz_conv_desc* desc, const void* dy16, const void* w16, void* dx16, void* ws,
+                       size_t ws_bytes, void* hip_stream);
+
+/* Backward pass w.r.t. the filter (the weight gradients Section 4.1 hands to LARS): the adjoint in w,
+ *   dw[k,r,s,c] = RNE16( sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] ),
+ * no division by N.  The sum over (n,p,q) is split across workgroups; the partial sums stay FP32 in `ws`
+ * and are added in a fixed order before the single rounding to FP16 (overflow gives +-Inf, which the
+ * LARS update reports through its flag).
+ * x16: in [N,H,W,C]; dy16: in [N,P,Q,K]; dw16: out [K,R,S,C] fp16 -- may point into a fused gradient buffer. */
+int jz_conv2d_bwd_weight(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16, void* ws,
+                         size_t ws_bytes, void* hip_stream);
+
+/* Fully connected layer, the classifier GEMMs of AlexNet / ResNet-50 (Table 3's models), same
+ * FP16-storage / FP32-accumulate rule.  Row-major x[batch,in], w[out,in], y[batch,out]:
+ *   JZ_FWD        out16 = y  = RNE16(x  * w^T)   a16 = x  [batch,in],  b16 = w [out,in]
+ *   JZ_BWD_DATA   out16 = dx = RNE16(dy * w)     a16 = dy [batch,out], b16 = w [out,in]
+ *   JZ_BWD_WEIGHT out16 = dw = RNE16(dy^T * x)   a16 = dy [batch,out], b16 = x [batch,in]   */
+int jz_gemm_fc_workspace_bytes(int mode, int batch, int in_features, int out_features, size_t* bytes);
+int jz_gemm_fc(int mode, int batch, int in_features, int out_features, const void* a16, const void* b16, void* out16,
+               void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---- mixed-precision LARS update (Section 4.1, Eq. 1, Fig. 2) -------------------------------------------- */
+
+enum {
+  JZ_PARAM_WEIGHT_DECAY = 1, /* tensor is regularised (Eq. 2); clear for bias and batch-norm gamma/beta (Section 4.2) */
+  JZ_PARAM_LARS = 2          /* tensor uses the local rate of Eq. 1; clear = plain momentum SGD (rho = 1) */
+};
+
+typedef struct {
+  float lr;           /* gamma of Eq. 1: global learning rate */
+  float momentum;     /* m; the paper's equations carry none, 0 reproduces them */
+  float weight_decay; /* lambda of Eq. 2 */
+  float trust_coef;   /* eta of Eq. 1, the LARS coefficient (0.001 in Section 5.2) */
+  float loss_scale;   /* S > 0: the gradients in grad16 are S times the true ones */
+} jz_lars_hparams;
+
+/* All trainable tensors of a model fused into flat buffers (the fused buffer of Section 4.3's tensor
+ * fusion, reused as the optimiser's layout).  Tensor t occupies elements [offsets[t], offsets[t+1]). */
+typedef struct {
+  int64_t num_tensors;    /* T >= 0 */
+  const int64_t* offsets; /* HOST [T+1], offsets[0] = 0, non-decreasing; offsets[T] = P */
+  const uint8_t* flags;   /* HOST [T], JZ_PARAM_* bits */
+  float* master_w;        /* DEVICE [P] fp32 master weights, updated in place */
+  float* momentum;        /* DEVICE [P] fp32 momentum buffer, updated in place */
+  const void* grad16;     /* DEVICE [P] fp16 gradients, loss-scaled, read only */
+  void* weight16;         /* DEVICE [P] fp16 weights for the next forward pass, written */
+} jz_param_set;
+
+/* Bytes of device workspace the update needs for this table (depends on offsets only). */
+int jz_lars_workspace_bytes(const jz_param_set* ps, size_t* bytes);
+
+/* Writes the tensor/chunk tables for `ps` into `ws` (a blocking host-to-device copy on `hip_stream`).
+ * Call once per parameter-set layout; `ws` must then be kept intact and passed to every update. */
+int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* One optimiser step over every tensor:
+ *   found_inf = any element of grad16 is +-Inf or NaN (anywhere in [0,P));  if so nothing else is written.
+ *   per tensor t:  g = float(g16) / S ;  rho_t = eta * ||w_t|| / ||g_t||  (Eq. 1; 1 if a norm is 0 or the LARS bit
+ *                  is clear) ;  lambda_t = weight_decay if the decay bit is set else 0
+ *   per element:   v <- m*v + lr * rho_t * (g + lambda_t * w) ;  w <- w - v ;  w16 <- RNE16(w)      (FP32 arithmetic,
+ *                  norms accumulated in FP64 in a fixed order)
+ * found_inf_dev: DEVICE int, set to 0 or 1; valid once the stream has been synchronised.
+ * Returns JZ_ERR_NOT_PREPARED if `ws` was prepared for a different table (checked on the host by a
+ * checksum kept beside the table, and again on the device before anything is written). */
+int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
+                      size_t ws_bytes, void* hip_stream);
+
+/* Human-readable name of a status code; static storage. */
+const char* jz_status_string(int status);
+
+/* Library version, e.g. 100 for 0.1.0. */
+int jz_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JZ_H_ */

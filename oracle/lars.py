@@ -72,6 +72,7 @@ def lars_mp_update(offsets, flags, master_w, momentum_buf, grad16, weight16, *, 
     S = float(loss_scale)
     w64_out = np.empty(P, np.float64)
     v64_out = np.empty(P, np.float64)
+    vmag = np.empty(P, np.float64)      # |m*v| + lr*rho*(|g| + |lam*w|): operand scale of v', for error bounds under cancellation
     rho = np.empty(T, np.float64)
     for t in range(T):
         a, b = int(offsets[t]), int(offsets[t + 1])
@@ -89,7 +90,8 @@ def lars_mp_update(offsets, flags, master_w, momentum_buf, grad16, weight16, *, 
         v_new = float(momentum) * v + float(lr) * rho[t] * u
         w64_out[a:b] = w - v_new
         v64_out[a:b] = v_new
+        vmag[a:b] = np.abs(float(momentum) * v) + np.abs(float(lr) * rho[t]) * (np.abs(g) + np.abs(lam * w))
     w32_out = w64_out.astype(np.float32)                # RNE to the fp32 master copy
     v32_out = v64_out.astype(np.float32)
     w16_out = w32_out.astype(np.float16)                # cast back from the fp32 value
-    return w32_out, v32_out, w16_out, 0, {"rho": rho, "w64": w64_out, "v64": v64_out}
+    return w32_out, v32_out, w16_out, 0, {"rho": rho, "w64": w64_out, "v64": v64_out, "vmag": vmag}

@@ -1,0 +1,225 @@
+"""Thin ctypes binding of libjz (include/jz.h): same entry-point names, argument marshalling only.
+
+torch is used for device memory and streams; every arithmetic step runs in the HIP kernels of
+libjz.so.  There is no CPU fallback: if the library has not been built, loading raises.
+"""
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libjz.so")
+
+JZ_OK = 0
+JZ_ERR_NULL, JZ_ERR_SHAPE, JZ_ERR_UNSUPPORTED, JZ_ERR_WORKSPACE = -1, -2, -3, -4
+JZ_ERR_ALIGN, JZ_ERR_ALIAS, JZ_ERR_LAUNCH, JZ_ERR_NOT_PREPARED = -5, -6, -7, -8
+JZ_FWD, JZ_BWD_DATA, JZ_BWD_WEIGHT = 0, 1, 2
+JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
+
+EXPORTS = [
+    "jz_conv2d_workspace_bytes", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
+    "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
+    "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update",
+    "jz_status_string", "jz_version",
+]
+
+
+class JzError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_string(status)))
+
+
+class jz_conv_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+    @property
+    def P(self):
+        return (self.H + 2 * self.pad_h - self.R) // self.stride_h + 1
+
+    @property
+    def Q(self):
+        return (self.W + 2 * self.pad_w - self.S) // self.stride_w + 1
+
+
+class jz_lars_hparams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("lr", "momentum", "weight_decay", "trust_coef", "loss_scale")]
+
+
+class jz_param_set(ctypes.Structure):
+    _fields_ = [
+        ("num_tensors", ctypes.c_int64),
+        ("offsets", ctypes.POINTER(ctypes.c_int64)),
+        ("flags", ctypes.POINTER(ctypes.c_uint8)),
+        ("master_w", ctypes.c_void_p),
+        ("momentum", ctypes.c_void_p),
+        ("grad16", ctypes.c_void_p),
+        ("weight16", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Open libjz.so; raises (never falls back) when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libjz.so is not built: run `python -m paper_1807_11205_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        dp = ctypes.POINTER(jz_conv_desc)
+        L.jz_conv2d_workspace_bytes.argtypes = [ci, dp, ctypes.POINTER(sz)]
+        for name in ("jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight"):
+            getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.jz_gemm_fc_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
+        L.jz_gemm_fc.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        pp = ctypes.POINTER(jz_param_set)
+        L.jz_lars_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+        L.jz_lars_prepare.argtypes = [pp, vp, sz, vp]
+        L.jz_lars_mp_update.argtypes = [pp, ctypes.POINTER(jz_lars_hparams), vp, vp, sz, vp]
+        L.jz_status_string.argtypes = [ci]
+        L.jz_status_string.restype = ctypes.c_char_p
+        L.jz_version.argtypes = []
+        for name in EXPORTS:
+            if name != "jz_status_string":
+                getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().jz_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != JZ_OK:
+        raise JzError(status, where)
+
+
+def conv_desc(N, H, W, C, K, R, S, stride=1, pad=0) -> jz_conv_desc:
+    sh, sw = (stride, stride) if isinstance(stride, int) else stride
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    return jz_conv_desc(N, H, W, C, K, R, S, sh, sw, ph, pw)
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype, numel=None, what="tensor") -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous %s tensor on the GPU" % (what, dtype))
+    if numel is not None and t.numel() != numel:
+        raise ValueError("%s has %d elements, expected %d" % (what, t.numel(), numel))
+    return t.data_ptr() if t.numel() else None
+
+
+def _ws(ws: Optional[torch.Tensor]):
+    if ws is None:
+        return None, 0
+    if not ws.is_cuda or not ws.is_contiguous():
+        raise TypeError("workspace must be a contiguous GPU tensor")
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def jz_version() -> int:
+    return lib().jz_version()
+
+
+def jz_conv2d_workspace_bytes(op: int, desc: jz_conv_desc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().jz_conv2d_workspace_bytes(op, ctypes.byref(desc), ctypes.byref(n)), "jz_conv2d_workspace_bytes")
+    return n.value
+
+
+def jz_conv2d_fwd(desc, x16, w16, y16, ws=None, stream=None):
+    d, h = desc, torch.float16
+    wp, wn = _ws(ws)
+    _check(lib().jz_conv2d_fwd(ctypes.byref(d), _dev_ptr(x16, h, d.N * d.H * d.W * d.C, "x16"),
+                               _dev_ptr(w16, h, d.K * d.R * d.S * d.C, "w16"),
+                               _dev_ptr(y16, h, d.N * d.P * d.Q * d.K, "y16"), wp, wn, _stream(stream)), "jz_conv2d_fwd")
+
+
+def jz_conv2d_bwd_data(desc, dy16, w16, dx16, ws=None, stream=None):
+    d, h = desc, torch.float16
+    wp, wn = _ws(ws)
+    _check(lib().jz_conv2d_bwd_data(ctypes.byref(d), _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
+                                    _dev_ptr(w16, h, d.K * d.R * d.S * d.C, "w16"),
+                                    _dev_ptr(dx16, h, d.N * d.H * d.W * d.C, "dx16"), wp, wn, _stream(stream)),
+           "jz_conv2d_bwd_data")
+
+
+def jz_conv2d_bwd_weight(desc, x16, dy16, dw16, ws=None, stream=None):
+    d, h = desc, torch.float16
+    wp, wn = _ws(ws)
+    _check(lib().jz_conv2d_bwd_weight(ctypes.byref(d), _dev_ptr(x16, h, d.N * d.H * d.W * d.C, "x16"),
+                                      _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
+                                      _dev_ptr(dw16, h, d.K * d.R * d.S * d.C, "dw16"), wp, wn, _stream(stream)),
+           "jz_conv2d_bwd_weight")
+
+
+def jz_gemm_fc_workspace_bytes(mode: int, batch: int, in_features: int, out_features: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().jz_gemm_fc_workspace_bytes(mode, batch, in_features, out_features, ctypes.byref(n)),
+           "jz_gemm_fc_workspace_bytes")
+    return n.value
+
+
+def jz_gemm_fc(mode, batch, in_features, out_features, a16, b16, out16, ws=None, stream=None):
+    B, I, O, h = batch, in_features, out_features, torch.float16
+    na, nb, no = {JZ_FWD: (B * I, O * I, B * O), JZ_BWD_DATA: (B * O, O * I, B * I), JZ_BWD_WEIGHT: (B * O, B * I, O * I)}[mode]
+    wp, wn = _ws(ws)
+    _check(lib().jz_gemm_fc(mode, B, I, O, _dev_ptr(a16, h, na, "a16"), _dev_ptr(b16, h, nb, "b16"),
+                            _dev_ptr(out16, h, no, "out16"), wp, wn, _stream(stream)), "jz_gemm_fc")
+
+
+class ParamSet:
+    """Keeps the host tables of a jz_param_set alive next to the device buffers it points at."""
+
+    def __init__(self, offsets: Sequence[int], flags: Sequence[int], master_w: torch.Tensor, momentum: torch.Tensor,
+                 grad16: torch.Tensor, weight16: torch.Tensor):
+        self.offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        self.flags = np.ascontiguousarray(flags, dtype=np.uint8)
+        T = len(self.flags)
+        if len(self.offsets) != T + 1:
+            raise ValueError("offsets must have num_tensors + 1 entries")
+        P = int(self.offsets[-1]) if T else 0
+        self.tensors = (master_w, momentum, grad16, weight16)
+        self.c = jz_param_set(
+            T, self.offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+            self.flags.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+            _dev_ptr(master_w, torch.float32, P, "master_w"), _dev_ptr(momentum, torch.float32, P, "momentum"),
+            _dev_ptr(grad16, torch.float16, P, "grad16"), _dev_ptr(weight16, torch.float16, P, "weight16"))
+        self.P, self.T = P, T
+
+
+def jz_lars_workspace_bytes(ps: ParamSet) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().jz_lars_workspace_bytes(ctypes.byref(ps.c), ctypes.byref(n)), "jz_lars_workspace_bytes")
+    return n.value
+
+
+def jz_lars_prepare(ps: ParamSet, ws: torch.Tensor, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().jz_lars_prepare(ctypes.byref(ps.c), wp, wn, _stream(stream)), "jz_lars_prepare")
+
+
+def jz_lars_mp_update(ps: ParamSet, hp: jz_lars_hparams, found_inf: torch.Tensor, ws: torch.Tensor, stream=None):
+    if not found_inf.is_cuda or found_inf.dtype != torch.int32 or found_inf.numel() != 1:
+        raise TypeError("found_inf must be a one-element int32 GPU tensor")
+    wp, wn = _ws(ws)
+    _check(lib().jz_lars_mp_update(ctypes.byref(ps.c), ctypes.byref(hp), found_inf.data_ptr(), wp, wn, _stream(stream)),
+           "jz_lars_mp_update")
+
+
+def lars_hparams(lr, momentum, weight_decay, trust_coef, loss_scale) -> jz_lars_hparams:
+    return jz_lars_hparams(lr, momentum, weight_decay, trust_coef, loss_scale)

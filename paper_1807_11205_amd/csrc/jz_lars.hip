@@ -1,0 +1,405 @@
+// Mixed-precision LARS update (Jia et al. 2018, Section 4.1, Eq. 1, Fig. 2) for gfx950.
+//
+// fp16 loss-scaled gradients and the fp32 master weights are widened, the layer-wise rate
+// rho_t = eta*||w_t||/||g_t|| is formed, the momentum step is taken on the fp32 master copy and the
+// result is narrowed to fp16 for the next forward pass.  The whole thing is HBM-bound (20 bytes per
+// parameter must move), so it is organised as three stream-ordered launches over a fused flat buffer:
+//
+//   lars_reduce    one workgroup per chunk (<= LARS_CH elements inside one tensor): fp64 partial sums of
+//                  w^2 and g16^2 and a non-finite flag, stored per chunk (no atomics => deterministic)
+//   lars_finalize  one workgroup per tensor: adds that tensor's chunk partials in index order, forms
+//                  lr*rho_t, ORs the chunk flags
+//   lars_update    one workgroup per chunk, walking the buffer in the opposite direction so that the
+//                  tail the reduce pass touched last is still in the last-level cache; skips everything
+//                  when any tensor raised the flag
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+#include <vector>
+
+#include "jz_internal.h"
+
+namespace {
+
+constexpr int LARS_CH = 4096;  // elements per chunk; a multiple of 8
+constexpr int LARS_THREADS = 256;
+constexpr uint64_t LARS_MAGIC = 0x4a5a4c4152533031ull;  // "JZLARS01"
+
+struct Layout {
+  int64_t T = 0, P = 0, n_chunks = 0;
+  size_t off_header = 0, off_offsets = 0, off_chunk_begin = 0, off_flags = 0, off_chunk_tensor = 0;
+  size_t static_bytes = 0;  // everything up to here is written by prepare
+  size_t off_psum_w = 0, off_psum_g = 0, off_pflag = 0, off_coef = 0, off_tflag = 0, total = 0;
+};
+
+size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int make_layout(const jz_param_set* ps, Layout* L) {
+  if (!ps) return JZ_ERR_NULL;
+  if (ps->num_tensors < 0) return JZ_ERR_SHAPE;
+  if (ps->num_tensors > 0 && (!ps->offsets || !ps->flags)) return JZ_ERR_NULL;
+  L->T = ps->num_tensors;
+  int64_t chunks = 0;
+  if (L->T > 0) {
+    if (ps->offsets[0] != 0) return JZ_ERR_SHAPE;
+    for (int64_t t = 0; t < L->T; ++t) {
+      int64_t n = ps->offsets[t + 1] - ps->offsets[t];
+      if (n < 0) return JZ_ERR_SHAPE;
+      if (n >= (int64_t(1) << 31)) return JZ_ERR_UNSUPPORTED;
+      chunks += (n + LARS_CH - 1) / LARS_CH;
+    }
+    L->P = ps->offsets[L->T];
+  }
+  if (L->T >= (int64_t(1) << 24) || chunks >= (int64_t(1) << 30)) return JZ_ERR_UNSUPPORTED;
+  L->n_chunks = chunks;
+  size_t o = 0;
+  L->off_header = o;        o = up256(o + 64);
+  L->off_offsets = o;       o = up256(o + sizeof(int64_t) * (L->T + 1));
+  L->off_chunk_begin = o;   o = up256(o + sizeof(int) * (L->T + 1));
+  L->off_flags = o;         o = up256(o + sizeof(int) * (L->T ? L->T : 1));
+  L->off_chunk_tensor = o;  o = up256(o + sizeof(int) * (chunks ? chunks : 1));
+  L->static_bytes = o;
+  L->off_psum_w = o;        o = up256(o + sizeof(double) * (chunks ? chunks : 1));
+  L->off_psum_g = o;        o = up256(o + sizeof(double) * (chunks ? chunks : 1));
+  L->off_pflag = o;         o = up256(o + sizeof(int) * (chunks ? chunks : 1));
+  L->off_coef = o;          o = up256(o + sizeof(float) * (L->T ? L->T : 1));
+  L->off_tflag = o;         o = up256(o + sizeof(int) * (L->T ? L->T : 1));
+  L->total = o;
+  return JZ_OK;
+}
+
+uint64_t table_checksum(const jz_param_set* ps) {  // FNV-1a over T, offsets and flags
+  uint64_t h = 1469598103934665603ull;
+  auto mix = [&](const void* p, size_t n) {
+    const unsigned char* b = static_cast<const unsigned char*>(p);
+    for (size_t i = 0; i < n; ++i) { h ^= b[i]; h *= 1099511628211ull; }
+  };
+  int64_t T = ps->num_tensors;
+  mix(&T, sizeof T);
+  if (T > 0) { mix(ps->offsets, sizeof(int64_t) * (T + 1)); mix(ps->flags, T); }
+  return h ? h : 1;
+}
+
+// host-side note of which workspace holds which table (the device header is checked as well)
+struct Prepared { void* ws; uint64_t sum; };
+std::mutex g_mu;
+Prepared g_prepared[64];
+int g_next = 0;
+
+void remember(void* ws, uint64_t sum) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  for (auto& e : g_prepared)
+    if (e.ws == ws) { e.sum = sum; return; }
+  g_prepared[g_next] = {ws, sum};
+  g_next = (g_next + 1) % 64;
+}
+bool is_prepared(void* ws, uint64_t sum) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  for (auto& e : g_prepared)
+    if (e.ws == ws) return e.sum == sum;
+  return false;
+}
+
+struct Tables {
+  const uint64_t* header;
+  const int64_t* offsets;
+  const int* chunk_begin;
+  const int* flags;
+  const int* chunk_tensor;
+  double* psum_w;
+  double* psum_g;
+  int* pflag;
+  float* coef;  // lr * rho_t
+  int* tflag;
+  int T, n_chunks;
+  uint64_t checksum;
+};
+
+__device__ __forceinline__ bool table_ok(const Tables& tb) { return tb.header[0] == LARS_MAGIC && tb.header[1] == tb.checksum; }
+
+__device__ __forceinline__ bool half_nonfinite(unsigned short h) { return (h & 0x7c00u) == 0x7c00u; }
+__device__ __forceinline__ float half_bits_to_float(unsigned short h) {
+  _Float16 x;
+  __builtin_memcpy(&x, &h, 2);
+  return (float)x;
+}
+__device__ __forceinline__ unsigned short float_to_half_bits(float f) {
+  _Float16 x = (_Float16)f;  // round to nearest even, overflow to Inf, subnormals kept
+  unsigned short h;
+  __builtin_memcpy(&h, &x, 2);
+  return h;
+}
+
+// Sum over the workgroup in a fixed order: lanes by shuffle tree, then the four waves left to right.
+__device__ __forceinline__ double block_sum(double v, double* lds4) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) lds4[wv] = v;
+  __syncthreads();
+  return ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+}
+
+__device__ __forceinline__ void chunk_range(const Tables& tb, int c, int* t_out, int64_t* start, int64_t* end) {
+  int t = tb.chunk_tensor[c];
+  int64_t s = tb.offsets[t] + (int64_t)(c - tb.chunk_begin[t]) * LARS_CH;
+  int64_t e = tb.offsets[t + 1];
+  *t_out = t;
+  *start = s;
+  *end = (s + LARS_CH < e) ? s + LARS_CH : e;
+}
+
+__global__ __launch_bounds__(LARS_THREADS) void lars_reduce(Tables tb, const float* __restrict__ w,
+                                                            const unsigned short* __restrict__ g16) {
+  __shared__ double red[4];
+  if (!table_ok(tb)) return;
+  const int c = blockIdx.x;
+  int t;
+  int64_t s, e;
+  chunk_range(tb, c, &t, &s, &e);
+  // [s,e) = unaligned head + 8-aligned body + tail
+  int64_t b0 = (s + 7) & ~int64_t(7);
+  if (b0 > e) b0 = e;
+  int64_t b1 = b0 + ((e - b0) & ~int64_t(7));
+  double sw = 0.0, sg = 0.0;
+  int bad = 0;
+  for (int64_t i = b0 + (int64_t)threadIdx.x * 8; i < b1; i += LARS_THREADS * 8) {
+    float4 w0 = *reinterpret_cast<const float4*>(w + i);
+    float4 w1 = *reinterpret_cast<const float4*>(w + i + 4);
+    uint4 gq = *reinterpret_cast<const uint4*>(g16 + i);
+    float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+    unsigned gw[4] = {gq.x, gq.y, gq.z, gq.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      unsigned short hb = (unsigned short)(gw[j >> 1] >> ((j & 1) * 16));
+      bad |= half_nonfinite(hb);
+      double wd = (double)wv[j], gd = (double)half_bits_to_float(hb);
+      sw = fma(wd, wd, sw);
+      sg = fma(gd, gd, sg);
+    }
+  }
+  {  // head and tail, at most 7 elements each
+    int64_t nh = b0 - s, nt = e - b1;
+    int64_t k = threadIdx.x;
+    if (k < nh + nt) {
+      int64_t i = (k < nh) ? s + k : b1 + (k - nh);
+      unsigned short hb = g16[i];
+      bad |= half_nonfinite(hb);
+      double wd = (double)w[i], gd = (double)half_bits_to_float(hb);
+      sw = fma(wd, wd, sw);
+      sg = fma(gd, gd, sg);
+    }
+  }
+  sw = block_sum(sw, red);
+  sg = block_sum(sg, red);
+  bad = __syncthreads_or(bad);
+  if (threadIdx.x == 0) {
+    tb.psum_w[c] = sw;
+    tb.psum_g[c] = sg;
+    tb.pflag[c] = bad ? 1 : 0;
+  }
+}
+
+__global__ __launch_bounds__(LARS_THREADS) void lars_finalize(Tables tb, float lr, float eta, float loss_scale) {
+  __shared__ double red[4];
+  if (!table_ok(tb)) return;
+  const int t = blockIdx.x;
+  const int c0 = tb.chunk_begin[t], c1 = tb.chunk_begin[t + 1];
+  double sw = 0.0, sg = 0.0;
+  int bad = 0;
+  for (int c = c0 + threadIdx.x; c < c1; c += LARS_THREADS) {
+    sw += tb.psum_w[c];
+    sg += tb.psum_g[c];
+    bad |= tb.pflag[c];
+  }
+  sw = block_sum(sw, red);
+  sg = block_sum(sg, red);
+  bad = __syncthreads_or(bad);
+  if (threadIdx.x == 0) {
+    double rho = 1.0;
+    if ((tb.flags[t] & JZ_PARAM_LARS) && sw > 0.0 && sg > 0.0)
+      rho = (double)eta * sqrt(sw) / (sqrt(sg) / (double)loss_scale);  // Eq. 1 on the un-scaled gradient
+    tb.coef[t] = (float)((double)lr * rho);
+    tb.tflag[t] = bad ? 1 : 0;
+  }
+}
+
+__device__ __forceinline__ void lars_step(float& w, float& v, unsigned short gbits, float coef, float lam, float m,
+                                          float inv_s, unsigned short& w16) {
+  float g = half_bits_to_float(gbits) * inv_s;  // un-scale
+  float u = fmaf(lam, w, g);                    // Eq. 2 differentiated: g + lambda*w
+  float vn = fmaf(m, v, coef * u);              // momentum step with the local rate lr*rho
+  float wn = w - vn;
+  v = vn;
+  w = wn;
+  w16 = float_to_half_bits(wn);                 // cast back for the next forward pass
+}
+
+__global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __restrict__ w, float* __restrict__ v,
+                                                            const unsigned short* __restrict__ g16,
+                                                            unsigned short* __restrict__ w16, float m, float wd,
+                                                            float inv_s, int* __restrict__ found_inf) {
+  if (!table_ok(tb)) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *found_inf = -1;
+    return;
+  }
+  int f = 0;
+  for (int t = threadIdx.x; t < tb.T; t += LARS_THREADS) f |= tb.tflag[t];
+  f = __syncthreads_or(f);
+  if (blockIdx.x == 0 && threadIdx.x == 0) *found_inf = f ? 1 : 0;
+  if (f) return;  // overflow under loss scaling: the step is skipped as a whole
+  if ((int)blockIdx.x >= tb.n_chunks) return;
+  const int c = tb.n_chunks - 1 - blockIdx.x;
+  int t;
+  int64_t s, e;
+  chunk_range(tb, c, &t, &s, &e);
+  const float coef = tb.coef[t];
+  const float lam = (tb.flags[t] & JZ_PARAM_WEIGHT_DECAY) ? wd : 0.0f;
+  int64_t b0 = (s + 7) & ~int64_t(7);
+  if (b0 > e) b0 = e;
+  int64_t b1 = b0 + ((e - b0) & ~int64_t(7));
+  for (int64_t i = b0 + (int64_t)threadIdx.x * 8; i < b1; i += LARS_THREADS * 8) {
+    float4 w0 = *reinterpret_cast<const float4*>(w + i);
+    float4 w1 = *reinterpret_cast<const float4*>(w + i + 4);
+    float4 v0 = *reinterpret_cast<const float4*>(v + i);
+    float4 v1 = *reinterpret_cast<const float4*>(v + i + 4);
+    uint4 gq = *reinterpret_cast<const uint4*>(g16 + i);
+    float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+    float vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    unsigned gw[4] = {gq.x, gq.y, gq.z, gq.w};
+    unsigned ow[4];
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      unsigned short h0, h1;
+      lars_step(wv[j], vv[j], (unsigned short)(gw[j >> 1] & 0xffffu), coef, lam, m, inv_s, h0);
+      lars_step(wv[j + 1], vv[j + 1], (unsigned short)(gw[j >> 1] >> 16), coef, lam, m, inv_s, h1);
+      ow[j >> 1] = (unsigned)h0 | ((unsigned)h1 << 16);
+    }
+    *reinterpret_cast<float4*>(w + i) = make_float4(wv[0], wv[1], wv[2], wv[3]);
+    *reinterpret_cast<float4*>(w + i + 4) = make_float4(wv[4], wv[5], wv[6], wv[7]);
+    *reinterpret_cast<float4*>(v + i) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    *reinterpret_cast<float4*>(v + i + 4) = make_float4(vv[4], vv[5], vv[6], vv[7]);
+    *reinterpret_cast<uint4*>(w16 + i) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+  }
+  {
+    int64_t nh = b0 - s, nt = e - b1;
+    int64_t k = threadIdx.x;
+    if (k < nh + nt) {
+      int64_t i = (k < nh) ? s + k : b1 + (k - nh);
+      float wi = w[i], vi = v[i];
+      unsigned short h;
+      lars_step(wi, vi, g16[i], coef, lam, m, inv_s, h);
+      w[i] = wi;
+      v[i] = vi;
+      w16[i] = h;
+    }
+  }
+}
+
+Tables make_tables(const Layout& L, void* ws, uint64_t sum) {
+  char* b = static_cast<char*>(ws);
+  Tables tb;
+  tb.header = reinterpret_cast<const uint64_t*>(b + L.off_header);
+  tb.offsets = reinterpret_cast<const int64_t*>(b + L.off_offsets);
+  tb.chunk_begin = reinterpret_cast<const int*>(b + L.off_chunk_begin);
+  tb.flags = reinterpret_cast<const int*>(b + L.off_flags);
+  tb.chunk_tensor = reinterpret_cast<const int*>(b + L.off_chunk_tensor);
+  tb.psum_w = reinterpret_cast<double*>(b + L.off_psum_w);
+  tb.psum_g = reinterpret_cast<double*>(b + L.off_psum_g);
+  tb.pflag = reinterpret_cast<int*>(b + L.off_pflag);
+  tb.coef = reinterpret_cast<float*>(b + L.off_coef);
+  tb.tflag = reinterpret_cast<int*>(b + L.off_tflag);
+  tb.T = (int)L.T;
+  tb.n_chunks = (int)L.n_chunks;
+  tb.checksum = sum;
+  return tb;
+}
+
+}  // namespace
+
+extern "C" int jz_lars_workspace_bytes(const jz_param_set* ps, size_t* bytes) {
+  if (!bytes) return JZ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(ps, &L);
+  if (rc != JZ_OK) return rc;
+  *bytes = L.total;
+  return JZ_OK;
+}
+
+extern "C" int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes, void* hip_stream) {
+  Layout L;
+  int rc = make_layout(ps, &L);
+  if (rc != JZ_OK) return rc;
+  if (!ws || ws_bytes < L.total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(ws)) return JZ_ERR_ALIGN;
+  std::vector<char> host(L.static_bytes, 0);
+  uint64_t sum = table_checksum(ps);
+  uint64_t* hdr = reinterpret_cast<uint64_t*>(host.data() + L.off_header);
+  hdr[0] = LARS_MAGIC;
+  hdr[1] = sum;
+  hdr[2] = (uint64_t)L.T;
+  hdr[3] = (uint64_t)L.n_chunks;
+  hdr[4] = (uint64_t)L.P;
+  int64_t* off = reinterpret_cast<int64_t*>(host.data() + L.off_offsets);
+  int* cb = reinterpret_cast<int*>(host.data() + L.off_chunk_begin);
+  int* fl = reinterpret_cast<int*>(host.data() + L.off_flags);
+  int* ct = reinterpret_cast<int*>(host.data() + L.off_chunk_tensor);
+  int c = 0;
+  off[0] = 0;
+  cb[0] = 0;
+  for (int64_t t = 0; t < L.T; ++t) {
+    off[t] = ps->offsets[t];
+    off[t + 1] = ps->offsets[t + 1];
+    fl[t] = ps->flags[t];
+    int64_t n = ps->offsets[t + 1] - ps->offsets[t];
+    int nc = (int)((n + LARS_CH - 1) / LARS_CH);
+    for (int k = 0; k < nc; ++k) ct[c + k] = (int)t;
+    c += nc;
+    cb[t + 1] = c;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (hipMemcpyAsync(ws, host.data(), L.static_bytes, hipMemcpyHostToDevice, st) != hipSuccess) return JZ_ERR_LAUNCH;
+  if (hipStreamSynchronize(st) != hipSuccess) return JZ_ERR_LAUNCH;
+  remember(ws, sum);
+  return JZ_OK;
+}
+
+extern "C" int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
+                                 size_t ws_bytes, void* hip_stream) {
+  if (!hp || !found_inf_dev) return JZ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(ps, &L);
+  if (rc != JZ_OK) return rc;
+  if (!(hp->loss_scale > 0.0f) || !(hp->loss_scale < 3.0e38f)) return JZ_ERR_SHAPE;
+  if (L.P > 0 && (!ps->master_w || !ps->momentum || !ps->grad16 || !ps->weight16)) return JZ_ERR_NULL;
+  if (!ws || ws_bytes < L.total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(ws) || !jz::aligned16(ps->master_w) || !jz::aligned16(ps->momentum) ||
+      !jz::aligned16(ps->grad16) || !jz::aligned16(ps->weight16) || (reinterpret_cast<uintptr_t>(found_inf_dev) & 3u))
+    return JZ_ERR_ALIGN;
+  const size_t P = (size_t)L.P;
+  const void* bufs[4] = {ps->master_w, ps->momentum, ps->grad16, ps->weight16};
+  const size_t lens[4] = {4 * P, 4 * P, 2 * P, 2 * P};
+  for (int i = 0; i < 4; ++i) {
+    if (jz::overlaps(bufs[i], lens[i], ws, L.total) || jz::overlaps(bufs[i], lens[i], found_inf_dev, sizeof(int)))
+      return JZ_ERR_ALIAS;
+    for (int j = i + 1; j < 4; ++j)
+      if (jz::overlaps(bufs[i], lens[i], bufs[j], lens[j])) return JZ_ERR_ALIAS;
+  }
+  if (jz::overlaps(found_inf_dev, sizeof(int), ws, L.total)) return JZ_ERR_ALIAS;
+  uint64_t sum = table_checksum(ps);
+  if (!is_prepared(ws, sum)) return JZ_ERR_NOT_PREPARED;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Tables tb = make_tables(L, ws, sum);
+  const unsigned short* g16 = static_cast<const unsigned short*>(ps->grad16);
+  if (L.n_chunks > 0)
+    hipLaunchKernelGGL(lars_reduce, dim3((unsigned)L.n_chunks), dim3(LARS_THREADS), 0, st, tb, ps->master_w, g16);
+  if (L.T > 0)
+    hipLaunchKernelGGL(lars_finalize, dim3((unsigned)L.T), dim3(LARS_THREADS), 0, st, tb, hp->lr, hp->trust_coef,
+                       hp->loss_scale);
+  // at least one workgroup so that the flag is always written
+  hipLaunchKernelGGL(lars_update, dim3((unsigned)(L.n_chunks > 0 ? L.n_chunks : 1)), dim3(LARS_THREADS), 0, st, tb,
+                     ps->master_w, ps->momentum, g16, static_cast<unsigned short*>(ps->weight16), hp->momentum,
+                     hp->weight_decay, 1.0f / hp->loss_scale, found_inf_dev);
+  return jz::launch_status();
+}
