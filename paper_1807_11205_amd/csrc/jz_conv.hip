@@ -1,7 +1,623 @@
+// FP16-storage / FP32-accumulate convolution forward, backward-data, backward-weight and the fully
+// connected GEMMs (Jia et al. 2018, Section 4.1) as one implicit-GEMM kernel family for gfx950.
+//
+// Workgroup = 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN output tile; each wavefront owns
+// (BM/2) x (BN/2) of it as 32x32 MFMA tiles (v_mfma_f32_32x32x16_f16, fp32 accumulators).  The reduction
+// is walked in k tiles of BK = 64 halves: wavefronts 0-1 fetch the A tile, wavefronts 2-3 the B tile, global ->
+// registers -> LDS, double buffered so the next tile's loads are in flight while the current one is multiplied.
+// Both tiles sit in LDS as [row][k] with k contiguous (row pitch BK+8 halves: every 16-byte MFMA operand read
+// and every 16-byte tile write is bank-conflict free).  Operands whose memory layout has the *other* index
+// contiguous (the filter in backward-data, both operands in backward-weight) are fetched as 8x8 blocks
+// and transposed in registers on their way into LDS.
+//
+// FAST kernels need channel counts that are multiples of 64 (resp. 8), which makes a k tile lie inside one filter
+// tap so that all tap arithmetic is wave-uniform.  Everything else (3-channel stems, odd sizes) goes through the
+// element-wise GENERIC loaders: same tiles, same MFMA loop, every element bounds-checked.
+#include "jz_igemm.h"
 #include "jz_internal.h"
-extern "C" int jz_conv2d_workspace_bytes(int, const jz_conv_desc*, size_t*) { return JZ_ERR_UNSUPPORTED; }
-extern "C" int jz_conv2d_fwd(const jz_conv_desc*, const void*, const void*, void*, void*, size_t, void*) { return JZ_ERR_UNSUPPORTED; }
-extern "C" int jz_conv2d_bwd_data(const jz_conv_desc*, const void*, const void*, void*, void*, size_t, void*) { return JZ_ERR_UNSUPPORTED; }
-extern "C" int jz_conv2d_bwd_weight(const jz_conv_desc*, const void*, const void*, void*, void*, size_t, void*) { return JZ_ERR_UNSUPPORTED; }
-extern "C" int jz_gemm_fc_workspace_bytes(int, int, int, int, size_t*) { return JZ_ERR_UNSUPPORTED; }
-extern "C" int jz_gemm_fc(int, int, int, int, const void*, const void*, void*, void*, size_t, void*) { return JZ_ERR_UNSUPPORTED; }
+
+namespace {
+using namespace jz;
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int THREADS = 256;
+constexpr int BK = 64;
+constexpr int LDK = BK + 8;  // LDS row pitch in halves
+constexpr int KCH = BK / 8;  // 16-byte chunks per tile row
+constexpr int LOADERS = 128; // threads per operand
+
+__device__ __forceinline__ unsigned xcd_remap(unsigned bid, unsigned nb) {
+  // consecutive workgroup ids land on different XCDs (each with its own L2); give every XCD one
+  // contiguous run of tiles instead so that neighbouring tiles share their operand rows in L2
+  const unsigned X = 8;
+  unsigned q = nb / X, rem = nb % X, xcd = bid % X, local = bid / X;
+  return xcd * q + (xcd < rem ? xcd : rem) + local;
+}
+
+__device__ __forceinline__ uint4 ldg16(const unsigned short* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// ---------------------------------------------------------------------------------------------
+// element-wise (generic) operand access: the plain index definitions, every bound checked
+// ---------------------------------------------------------------------------------------------
+template <int OP>
+__device__ __forceinline__ unsigned short elem_gather(const GemmArgs& a, const unsigned short* T, unsigned pix,
+                                                       unsigned tap, unsigned c) {
+  // value of the gathered tensor for output pixel `pix` of the (n,OH,OW) grid at filter tap `tap`, channel c
+  const ConvGeom& g = a.g;
+  unsigned n = fd_div(pix, g.d_ohow);
+  unsigned rem = pix - n * (unsigned)(g.OH * g.OW);
+  unsigned oh = fd_div(rem, g.d_ow);
+  unsigned ow = rem - oh * (unsigned)g.OW;
+  unsigned r = fd_div(tap, g.d_s);
+  unsigned s = tap - r * (unsigned)g.S;
+  int ih, iw;
+  if (OP == OP_BWD_DATA) {
+    int th = (int)oh + g.ph - (int)r, tw = (int)ow + g.pw - (int)s;
+    if (th < 0 || tw < 0) return 0;
+    ih = (int)fd_div((unsigned)th, g.d_sh);
+    iw = (int)fd_div((unsigned)tw, g.d_sw);
+    if (ih * g.sh != th || iw * g.sw != tw) return 0;  // no output pixel reads this input pixel through this tap
+  } else {
+    ih = (int)oh * g.sh - g.ph + (int)r;
+    iw = (int)ow * g.sw - g.pw + (int)s;
+  }
+  if ((unsigned)ih >= (unsigned)g.IH || (unsigned)iw >= (unsigned)g.IW) return 0;
+  return T[((size_t)(n * g.IH + ih) * g.IW + iw) * g.IC + c];
+}
+
+template <int OP>
+__device__ __forceinline__ unsigned short elemA(const GemmArgs& a, int m, int k) {
+  if (m >= a.M || k >= a.Kred) return 0;
+  if (OP == OP_BWD_WEIGHT) return a.A[(size_t)k * a.M + m];  // dy[(n,p,q)][k_out]
+  unsigned tap = fd_div((unsigned)k, a.g.d_ic);
+  unsigned c = (unsigned)k - tap * (unsigned)a.g.IC;
+  return elem_gather<OP>(a, a.A, (unsigned)m, tap, c);
+}
+
+template <int OP>
+__device__ __forceinline__ unsigned short elemB(const GemmArgs& a, int n, int k) {
+  if (n >= a.N || k >= a.Kred) return 0;
+  if (OP == OP_FWD) return a.B[(size_t)n * a.Kred + k];  // w[k_out][(r,s,c)]
+  if (OP == OP_BWD_DATA) {                                // w[k_out][r][s][c] read as B(c, (r,s,k_out))
+    unsigned tap = fd_div((unsigned)k, a.g.d_ic);
+    unsigned ko = (unsigned)k - tap * (unsigned)a.g.IC;
+    return a.B[((size_t)ko * (a.g.R * a.g.S) + tap) * a.N + n];
+  }
+  unsigned tap = fd_div((unsigned)n, a.g.d_ic);  // BWD_WEIGHT: n = (r,s,c), k = (n,p,q)
+  unsigned c = (unsigned)n - tap * (unsigned)a.g.IC;
+  return elem_gather<OP_FWD>(a, a.B, (unsigned)k, tap, c);
+}
+
+// 8x8 transpose of halves held as 8 rows of 4 dwords: out[e] gets element e of every row
+__device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
+  const unsigned* s = reinterpret_cast<const unsigned*>(in);
+  unsigned* d = reinterpret_cast<unsigned*>(out);
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      unsigned lo = s[(2 * j) * 4 + (e >> 1)], hi = s[(2 * j + 1) * 4 + (e >> 1)];
+      d[e * 4 + j] = __builtin_amdgcn_perm(hi, lo, (e & 1) ? 0x07060302u : 0x05040100u);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// the kernel
+// ---------------------------------------------------------------------------------------------
+template <int OP, bool FAST, int BM, int BN>
+__global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a) {
+  constexpr int TM = BM / 64, TN = BN / 64;              // 32x32 MFMA tiles per wavefront
+  constexpr int A_HALVES = BM * LDK, B_HALVES = BN * LDK;
+  constexpr int RPP = LOADERS / KCH;                     // rows one pass of 128 loader threads covers (16)
+  constexpr int PA = BM / RPP, PB = BN / RPP;            // passes over the A / B tile
+  constexpr int NREG = (PA > PB ? PA : PB) < 8 ? 8 : (PA > PB ? PA : PB);
+  extern __shared__ __align__(16) unsigned short lds[];
+
+  const ConvGeom& g = a.g;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const bool loadsA = wave < 2;
+  const int tt = tid & (LOADERS - 1);
+  const int kc = tt % KCH, rsub = tt / KCH;
+
+  unsigned L = xcd_remap(blockIdx.x, gridDim.x);
+  const int tiles_mn = a.tiles_m * a.tiles_n;
+  const int split = (int)(L / (unsigned)tiles_mn);
+  L -= (unsigned)split * (unsigned)tiles_mn;
+  const int m0 = (int)(L / (unsigned)a.tiles_n) * BM;
+  const int n0 = (int)(L % (unsigned)a.tiles_n) * BN;
+  const int kt_begin = split * a.kt_per_split;
+  const int kt_end = (kt_begin + a.kt_per_split < a.nkt) ? kt_begin + a.kt_per_split : a.nkt;
+
+  // ---- per-thread loader state (FAST paths) -------------------------------------------------
+  int st0[NREG], st1[NREG], st2[NREG];
+  (void)st0; (void)st1; (void)st2;
+  if (FAST) {
+    if (loadsA && OP != OP_BWD_WEIGHT) {  // gather rows of the pixel grid
+#pragma unroll
+      for (int i = 0; i < PA; ++i) {
+        int m = m0 + rsub + RPP * i;
+        if (m < a.M) {
+          unsigned n = fd_div((unsigned)m, g.d_ohow);
+          unsigned rem = (unsigned)m - n * (unsigned)(g.OH * g.OW);
+          unsigned oh = fd_div(rem, g.d_ow);
+          unsigned ow = rem - oh * (unsigned)g.OW;
+          if (OP == OP_FWD) {
+            st1[i] = (int)oh * g.sh - g.ph;
+            st2[i] = (int)ow * g.sw - g.pw;
+            st0[i] = (((int)n * g.IH + st1[i]) * g.IW + st2[i]) * g.IC;
+          } else {
+            st0[i] = (int)n * g.IH * g.IW;
+            st1[i] = (int)oh + g.ph;
+            st2[i] = (int)ow + g.pw;
+          }
+        } else {
+          st0[i] = 0;
+          st1[i] = -(1 << 28);  // fails every bounds check below
+          st2[i] = -(1 << 28);
+        }
+      }
+    }
+    if (!loadsA && OP == OP_BWD_WEIGHT) {  // this thread's 8 columns (r,s,c..c+7) are fixed
+      int nn = n0 + rsub * 8;
+      if (nn < a.N) {
+        unsigned tap = fd_div((unsigned)nn, g.d_ic);
+        unsigned r = fd_div(tap, g.d_s);
+        st0[0] = nn - (int)tap * g.IC;         // c0
+        st1[0] = (int)r - g.ph;                // ih = p*sh + st1
+        st2[0] = (int)(tap - r * g.S) - g.pw;  // iw = q*sw + st2
+      } else {
+        st0[0] = 0;
+        st1[0] = -(1 << 28);
+        st2[0] = -(1 << 28);
+      }
+    }
+  }
+
+  uint4 rg[NREG];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  // fetch k tile `kt` of this thread's operand into rg[]
+  auto fetch = [&](int kt) {
+    const int k0 = kt * BK;
+    if (!FAST) {
+      const int rows = loadsA ? PA : PB;
+#pragma unroll
+      for (int i = 0; i < NREG; ++i) {
+        if (i < rows) {
+          unsigned v[4];
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            int k = k0 + kc * 8 + e;
+            unsigned short lo, hi;
+            if (loadsA) {
+              lo = elemA<OP>(a, m0 + rsub + RPP * i, k);
+              hi = elemA<OP>(a, m0 + rsub + RPP * i, k + 1);
+            } else {
+              lo = elemB<OP>(a, n0 + rsub + RPP * i, k);
+              hi = elemB<OP>(a, n0 + rsub + RPP * i, k + 1);
+            }
+            v[e >> 1] = (unsigned)lo | ((unsigned)hi << 16);
+          }
+          rg[i] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+      }
+      return;
+    }
+    if (OP != OP_BWD_WEIGHT) {
+      // the whole k tile lies inside one filter tap (IC % BK == 0): tap arithmetic is wave-uniform
+      const unsigned tap = fd_div((unsigned)k0, g.d_ic);
+      const int c0 = k0 - (int)tap * g.IC;
+      const int r = (int)fd_div(tap, g.d_s);
+      const int s = (int)tap - r * g.S;
+      if (loadsA) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+          bool ok;
+          int off;
+          if (OP == OP_FWD) {
+            int ih = st1[i] + r, iw = st2[i] + s;
+            ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+            off = st0[i] + (r * g.IW + s) * g.IC + c0 + kc * 8;
+          } else {
+            int th = st1[i] - r, tw = st2[i] - s;
+            int ih = th, iw = tw;
+            ok = th >= 0 && tw >= 0;
+            if (g.sh != 1 || g.sw != 1) {
+              ih = (int)fd_div((unsigned)(th < 0 ? 0 : th), g.d_sh);
+              iw = (int)fd_div((unsigned)(tw < 0 ? 0 : tw), g.d_sw);
+              ok = ok && ih * g.sh == th && iw * g.sw == tw;
+            }
+            ok = ok && ih < g.IH && iw < g.IW;
+            off = (st0[i] + ih * g.IW + iw) * g.IC + c0 + kc * 8;
+          }
+          rg[i] = ok ? ldg16(a.A + off) : zero4;
+        }
+      } else if (OP == OP_FWD) {  // filter rows, k contiguous
+#pragma unroll
+        for (int i = 0; i < PB; ++i) {
+          int nn = n0 + rsub + RPP * i;
+          rg[i] = nn < a.N ? ldg16(a.B + (size_t)nn * a.Kred + k0 + kc * 8) : zero4;
+        }
+      } else {  // BWD_DATA filter: B(c, (tap,ko)) = w[ko][tap][c]; 8 ko rows x 8 c, transposed later
+        int nn = n0 + rsub * 8;
+        bool ok = rsub * 8 < BN && nn < a.N;
+        int RS = g.R * g.S;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          int ko = c0 + kc * 8 + i;
+          rg[i] = ok ? ldg16(a.B + ((size_t)ko * RS + tap) * a.N + nn) : zero4;
+        }
+      }
+    } else {
+      if (loadsA) {  // dy[(n,p,q)][k_out]: 8 reduction rows x 8 k_out
+        int mm = m0 + rsub * 8;
+        bool okm = rsub * 8 < BM && mm < a.M;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          int j = k0 + kc * 8 + i;
+          rg[i] = (okm && j < a.Kred) ? ldg16(a.A + (size_t)j * a.M + mm) : zero4;
+        }
+      } else {  // x gathered at this thread's tap for 8 consecutive output pixels
+        bool okn = rsub * 8 < BN;
+        int j = k0 + kc * 8;
+        unsigned n = fd_div((unsigned)j, g.d_ohow);
+        unsigned rem = (unsigned)j - n * (unsigned)(g.OH * g.OW);
+        int p = (int)fd_div(rem, g.d_ow);
+        int q = (int)rem - p * g.OW;
+        int nb = (int)n;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          int ih = p * g.sh + st1[0], iw = q * g.sw + st2[0];
+          bool ok = okn && (j + i) < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+          rg[i] = ok ? ldg16(a.B + ((size_t)(nb * g.IH + ih) * g.IW + iw) * g.IC + st0[0]) : zero4;
+          if (++q == g.OW) {
+            q = 0;
+            if (++p == g.OH) { p = 0; ++nb; }
+          }
+        }
+      }
+    }
+  };
+
+  // put rg[] into LDS buffer `buf`
+  auto stash = [&](int buf) {
+    unsigned short* base = lds + buf * (A_HALVES + B_HALVES) + (loadsA ? 0 : A_HALVES);
+    const bool transposed = FAST && ((OP == OP_BWD_WEIGHT) || (OP == OP_BWD_DATA && !loadsA));
+    if (!transposed) {
+      const int rows = loadsA ? PA : PB;
+#pragma unroll
+      for (int i = 0; i < NREG; ++i)
+        if (i < rows) *reinterpret_cast<uint4*>(base + (rsub + RPP * i) * LDK + kc * 8) = rg[i];
+    } else {
+      const int rows = loadsA ? BM : BN;
+      if (rsub * 8 < rows) {
+        uint4 in[8], out[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) in[i] = rg[i];
+        transpose8x8(in, out);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) *reinterpret_cast<uint4*>(base + (rsub * 8 + e) * LDK + kc * 8) = out[e];
+      }
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  if (kt_begin < kt_end) {
+    fetch(kt_begin);
+    stash(0);
+  }
+  __syncthreads();
+  int buf = 0;
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    const bool more = kt + 1 < kt_end;
+    if (more) fetch(kt + 1);
+    const unsigned short* sA = lds + buf * (A_HALVES + B_HALVES);
+    const unsigned short* sB = sA + A_HALVES;
+    const int arow = wm * (BM / 2) + (lane & 31), brow = wn * (BN / 2) + (lane & 31);
+    const int kofs = (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      half8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const half8*>(sA + (arow + 32 * i) * LDK + ks * 16 + kofs);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const half8*>(sB + (brow + 32 * j) * LDK + ks * 16 + kofs);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          // n operand in the first slot: each lane then owns 4 consecutive n for one m (row = lane % 32)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (more) stash(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // ---- epilogue ------------------------------------------------------------------------------
+  // accumulator register r of tile (i,j): m = wm*BM/2 + 32 i + lane%32, n = wn*BN/2 + 32 j + 8 (r/4) + 4 (lane/32) + r%4
+  if (a.splits > 1) {
+    float* P = a.Dpart + (size_t)split * a.M * a.N;
+    const bool vec = (a.N & 3) == 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      int m = m0 + wm * (BM / 2) + 32 * i + (lane & 31);
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          int n = n0 + wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
+          float* dst = P + (size_t)m * a.N + n;
+          if (vec && n + 3 < a.N) {
+            *reinterpret_cast<float4*>(dst) =
+                make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < a.N) dst[e] = acc[i][j][4 * q4 + e];
+          }
+        }
+    }
+    return;
+  }
+  // single rounding fp32 -> fp16 (round to nearest even), staged through LDS for 16-byte coalesced stores
+  constexpr int LDC = BN + 8;
+  unsigned short* sC = lds;  // the k loop ended with a barrier: the tile buffers are free
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        int row = wm * (BM / 2) + 32 * i + (lane & 31);
+        int col = wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
+        _Float16 h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[i][j][4 * q4 + e];
+        uint2 pk;
+        __builtin_memcpy(&pk, h, 8);
+        *reinterpret_cast<uint2*>(sC + row * LDC + col) = pk;
+      }
+  __syncthreads();
+  constexpr int CCH = BN / 8;             // 16-byte chunks per output row
+  constexpr int CRPP = THREADS / CCH;     // rows per pass
+  const int cch = tid % CCH, crow = tid / CCH;
+  const bool nvec = (a.N & 7) == 0;
+#pragma unroll
+  for (int i = 0; i < BM / CRPP; ++i) {
+    int row = crow + CRPP * i;
+    int m = m0 + row, n = n0 + cch * 8;
+    if (m >= a.M || n >= a.N) continue;
+    const unsigned short* src = sC + row * LDC + cch * 8;
+    unsigned short* dst = a.D16 + (size_t)m * a.N + n;
+    if (nvec) {
+      *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+    } else {
+      for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = src[e];
+    }
+  }
+}
+
+// D16[i] = RNE16( sum_s part[s][i] ), splits added in index order (deterministic)
+__global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ part, unsigned short* __restrict__ out,
+                                                     long long MN, int splits) {
+  long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= MN) return;
+  if (i + 3 < MN) {
+    float4 s = *reinterpret_cast<const float4*>(part + i);
+    for (int k = 1; k < splits; ++k) {
+      float4 t = *reinterpret_cast<const float4*>(part + (size_t)k * MN + i);
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    _Float16 h[4] = {(_Float16)s.x, (_Float16)s.y, (_Float16)s.z, (_Float16)s.w};
+    uint2 pk;
+    __builtin_memcpy(&pk, h, 8);
+    *reinterpret_cast<uint2*>(out + i) = pk;
+  } else {
+    for (long long e = i; e < MN; ++e) {
+      float s = part[e];
+      for (int k = 1; k < splits; ++k) s += part[(size_t)k * MN + e];
+      _Float16 h = (_Float16)s;
+      unsigned short b;
+      __builtin_memcpy(&b, &h, 2);
+      out[e] = b;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side: plan (tile shape, fast/generic, split-K) and launch
+// ---------------------------------------------------------------------------------------------
+struct Plan {
+  int op = 0;
+  bool fast = false;
+  int BM = 128, BN = 128;
+  GemmArgs args{};
+  size_t ws_bytes = 0;
+  size_t bytesA = 0, bytesB = 0, bytesD = 0;  // operand sizes in bytes, for the overlap checks
+};
+
+int out_dim(int in, int pad, int f, int st) { return (in + 2 * pad - f) / st + 1; }
+
+int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
+  if (!d) return JZ_ERR_NULL;
+  if (op != JZ_FWD && op != JZ_BWD_DATA && op != JZ_BWD_WEIGHT) return JZ_ERR_UNSUPPORTED;
+  if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->stride_h <= 0 ||
+      d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+    return JZ_ERR_SHAPE;
+  if (d->pad_h >= d->R || d->pad_w >= d->S) return JZ_ERR_SHAPE;
+  if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return JZ_ERR_SHAPE;
+  const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
+  if (P <= 0 || Q <= 0) return JZ_ERR_SHAPE;
+  const long long lim = (1ll << 31) - 1;
+  const long long nx = (long long)d->N * d->H * d->W * d->C, ny = (long long)d->N * P * Q * d->K,
+                  nw = (long long)d->K * d->R * d->S * d->C;
+  if (nx > lim || ny > lim || nw > lim) return JZ_ERR_UNSUPPORTED;
+  if ((long long)d->N * P * Q > lim / 2 || (long long)d->N * d->H * d->W > lim / 2) return JZ_ERR_UNSUPPORTED;
+
+  GemmArgs& a = pl->args;
+  ConvGeom& g = a.g;
+  pl->op = op;
+  g.R = d->R; g.S = d->S; g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
+  if (op == JZ_FWD) {
+    a.M = d->N * P * Q; a.N = d->K; a.Kred = d->R * d->S * d->C;
+    g.IH = d->H; g.IW = d->W; g.IC = d->C; g.OH = P; g.OW = Q;
+    pl->fast = d->C % BK == 0;
+    pl->bytesA = 2 * nx; pl->bytesB = 2 * nw; pl->bytesD = 2 * ny;
+  } else if (op == JZ_BWD_DATA) {
+    a.M = d->N * d->H * d->W; a.N = d->C; a.Kred = d->R * d->S * d->K;
+    g.IH = P; g.IW = Q; g.IC = d->K; g.OH = d->H; g.OW = d->W;
+    pl->fast = d->K % BK == 0 && d->C % 8 == 0;
+    pl->bytesA = 2 * ny; pl->bytesB = 2 * nw; pl->bytesD = 2 * nx;
+  } else {
+    a.M = d->K; a.N = d->R * d->S * d->C; a.Kred = d->N * P * Q;
+    g.IH = d->H; g.IW = d->W; g.IC = d->C; g.OH = P; g.OW = Q;
+    pl->fast = d->K % 8 == 0 && d->C % 8 == 0;
+    pl->bytesA = 2 * ny; pl->bytesB = 2 * nx; pl->bytesD = 2 * nw;  // A = dy, B = x
+  }
+  g.d_ohow = make_fastdiv((unsigned)(g.OH * g.OW));
+  g.d_ow = make_fastdiv((unsigned)g.OW);
+  g.d_ic = make_fastdiv((unsigned)g.IC);
+  g.d_s = make_fastdiv((unsigned)g.S);
+  g.d_sh = make_fastdiv((unsigned)g.sh);
+  g.d_sw = make_fastdiv((unsigned)g.sw);
+
+  pl->BM = (pl->fast && a.M <= 64) ? 64 : 128;
+  pl->BN = (pl->fast && a.N <= 64) ? 64 : 128;
+  a.tiles_m = (a.M + pl->BM - 1) / pl->BM;
+  a.tiles_n = (a.N + pl->BN - 1) / pl->BN;
+  a.nkt = (a.Kred + BK - 1) / BK;
+  // split the reduction when the output alone cannot fill the 256 compute units
+  const long long tiles = (long long)a.tiles_m * a.tiles_n;
+  int splits = 1;
+  const int want = (op == JZ_BWD_WEIGHT) ? 512 : 256;
+  if (tiles * 2 <= want) {
+    long long s = (want + tiles - 1) / tiles;
+    long long by_k = a.nkt / 4;  // at least 4 k tiles per split
+    if (s > by_k) s = by_k;
+    if (s > 128) s = 128;
+    if (s >= 2) splits = (int)s;
+  }
+  a.kt_per_split = (a.nkt + splits - 1) / splits;
+  splits = (a.nkt + a.kt_per_split - 1) / a.kt_per_split;  // drop empty splits
+  a.splits = splits;
+  pl->ws_bytes = splits > 1 ? (size_t)splits * a.M * a.N * sizeof(float) : 0;
+  return JZ_OK;
+}
+
+template <int OP, bool FAST, int BM, int BN>
+int launch_one(const GemmArgs& a, hipStream_t st) {
+  constexpr size_t tile_bytes = 2 * (size_t)(BM + BN) * LDK * sizeof(unsigned short);
+  constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(unsigned short);
+  constexpr size_t smem = tile_bytes > epi_bytes ? tile_bytes : epi_bytes;
+  static bool attr_set = false;  // per instantiation; setting it twice is harmless
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<OP, FAST, BM, BN>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+      return JZ_ERR_LAUNCH;
+    attr_set = true;
+  }
+  unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.splits;
+  hipLaunchKernelGGL((igemm_kernel<OP, FAST, BM, BN>), dim3(grid), dim3(THREADS), smem, st, a);
+  return jz::launch_status();
+}
+
+template <int OP>
+int launch_op(const Plan& pl, hipStream_t st) {
+  const GemmArgs& a = pl.args;
+  if (!pl.fast) return launch_one<OP, false, 128, 128>(a, st);
+  if (pl.BM == 128 && pl.BN == 128) return launch_one<OP, true, 128, 128>(a, st);
+  if (pl.BM == 128 && pl.BN == 64) return launch_one<OP, true, 128, 64>(a, st);
+  if (pl.BM == 64 && pl.BN == 128) return launch_one<OP, true, 64, 128>(a, st);
+  return launch_one<OP, true, 64, 64>(a, st);
+}
+
+int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(op, d, &pl);
+  if (rc != JZ_OK) return rc;
+  if (!A || !B || !D) return JZ_ERR_NULL;
+  if (!aligned16(A) || !aligned16(B) || !aligned16(D) || (ws && !aligned16(ws))) return JZ_ERR_ALIGN;
+  if (overlaps(D, pl.bytesD, A, pl.bytesA) || overlaps(D, pl.bytesD, B, pl.bytesB)) return JZ_ERR_ALIAS;
+  if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes)) return JZ_ERR_WORKSPACE;
+  if (pl.ws_bytes > 0 && (overlaps(ws, pl.ws_bytes, A, pl.bytesA) || overlaps(ws, pl.ws_bytes, B, pl.bytesB) ||
+                          overlaps(ws, pl.ws_bytes, D, pl.bytesD)))
+    return JZ_ERR_ALIAS;
+  pl.args.A = static_cast<const unsigned short*>(A);
+  pl.args.B = static_cast<const unsigned short*>(B);
+  pl.args.D16 = static_cast<unsigned short*>(D);
+  pl.args.Dpart = static_cast<float*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (op == JZ_FWD) rc = launch_op<OP_FWD>(pl, st);
+  else if (op == JZ_BWD_DATA) rc = launch_op<OP_BWD_DATA>(pl, st);
+  else rc = launch_op<OP_BWD_WEIGHT>(pl, st);
+  if (rc != JZ_OK) return rc;
+  if (pl.args.splits > 1) {
+    long long MN = (long long)pl.args.M * pl.args.N;
+    unsigned blocks = (unsigned)((MN + 1023) / 1024);
+    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, pl.args.Dpart, pl.args.D16, MN, pl.args.splits);
+    rc = jz::launch_status();
+  }
+  return rc;
+}
+
+int fc_desc(int mode, int batch, int in_features, int out_features, jz_conv_desc* d) {
+  if (mode != JZ_FWD && mode != JZ_BWD_DATA && mode != JZ_BWD_WEIGHT) return JZ_ERR_UNSUPPORTED;
+  if (batch <= 0 || in_features <= 0 || out_features <= 0) return JZ_ERR_SHAPE;
+  // a fully connected layer is a 1x1 convolution over a 1x1 image
+  *d = jz_conv_desc{batch, 1, 1, in_features, out_features, 1, 1, 1, 1, 0, 0};
+  return JZ_OK;
+}
+
+}  // namespace
+
+extern "C" int jz_conv2d_workspace_bytes(int op, const jz_conv_desc* desc, size_t* bytes) {
+  if (!bytes) return JZ_ERR_NULL;
+  Plan pl;
+  int rc = make_plan(op, desc, &pl);
+  if (rc != JZ_OK) return rc;
+  *bytes = pl.ws_bytes;
+  return JZ_OK;
+}
+
+extern "C" int jz_conv2d_fwd(const jz_conv_desc* desc, const void* x16, const void* w16, void* y16, void* ws,
+                             size_t ws_bytes, void* hip_stream) {
+  return run(JZ_FWD, desc, x16, w16, y16, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int jz_conv2d_bwd_data(const jz_conv_desc* desc, const void* dy16, const void* w16, void* dx16, void* ws,
+                                  size_t ws_bytes, void* hip_stream) {
+  return run(JZ_BWD_DATA, desc, dy16, w16, dx16, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int jz_conv2d_bwd_weight(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16, void* ws,
+                                    size_t ws_bytes, void* hip_stream) {
+  return run(JZ_BWD_WEIGHT, desc, dy16, x16, dw16, ws, ws_bytes, hip_stream);  // A = dy, B = x
+}
+
+extern "C" int jz_gemm_fc_workspace_bytes(int mode, int batch, int in_features, int out_features, size_t* bytes) {
+  jz_conv_desc d;
+  int rc = fc_desc(mode, batch, in_features, out_features, &d);
+  if (rc != JZ_OK) return rc;
+  return jz_conv2d_workspace_bytes(mode, &d, bytes);
+}
+
+extern "C" int jz_gemm_fc(int mode, int batch, int in_features, int out_features, const void* a16, const void* b16,
+                          void* out16, void* ws, size_t ws_bytes, void* hip_stream) {
+  jz_conv_desc d;
+  int rc = fc_desc(mode, batch, in_features, out_features, &d);
+  if (rc != JZ_OK) return rc;
+  // FWD: (x, w) ; BWD_DATA: (dy, w) ; BWD_WEIGHT: (dy, x) -- already the kernel's (A, B) order in every mode
+  return run(mode, &d, a16, b16, out16, ws, ws_bytes, hip_stream);
+}

@@ -1,0 +1,59 @@
+// Implicit-GEMM core shared by the convolution and fully connected entry points of libjz (gfx950).
+//
+// Every operation of the FP16 forward/backward pass (Jia et al. 2018, Section 4.1: FP16 storage, FP32
+// accumulation, one rounding to FP16 at the end) is a contraction D[m][n] = sum_k A(m,k) * B(n,k):
+//
+//   op          m            n          k (reduction)   A(m,k)                         B(n,k)
+//   FWD         (n,p,q)      k_out      (r,s,c)         x gathered at the tap          w[k_out][r][s][c]
+//   BWD_DATA    (n,h,w)      c          (r,s,k_out)     dy gathered at the tap         w[k_out][r][s][c]
+//   BWD_WEIGHT  k_out        (r,s,c)    (n,p,q)         dy[(n,p,q)][k_out]             x gathered at the tap
+//
+// A fully connected layer is the 1x1 case on a 1x1 image.  D is always a plain row-major [M][N] matrix
+// (y, dx and dw are all stored with the n index innermost), so one epilogue serves all three.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace jz {
+
+enum { OP_FWD = 0, OP_BWD_DATA = 1, OP_BWD_WEIGHT = 2 };
+
+// Division by a run-time constant through multiply-high (Granlund-Montgomery style), exact for n < 2^31.
+struct FastDiv {
+  unsigned mult, shift, d;
+};
+inline FastDiv make_fastdiv(unsigned d) {
+  FastDiv f{0u, 0u, d};
+  if (d <= 1) return f;
+  unsigned lg = 0;
+  while ((1ull << lg) < d) ++lg;  // ceil(log2 d) >= 1
+  unsigned p = 31 + lg;
+  f.mult = (unsigned)(((1ull << p) + d - 1) / d);
+  f.shift = p - 32;
+  return f;
+}
+__device__ __forceinline__ unsigned fd_div(unsigned n, const FastDiv& f) {
+  return f.d <= 1 ? n : (__umulhi(n, f.mult) >> f.shift);
+}
+
+struct ConvGeom {
+  int IH, IW, IC;  // the tensor that is gathered (x for FWD / BWD_WEIGHT, dy for BWD_DATA): spatial size, channels
+  int OH, OW;      // the pixel grid the GEMM's m index (FWD, BWD_DATA) or k index (BWD_WEIGHT) runs over
+  int R, S, sh, sw, ph, pw;
+  FastDiv d_ohow, d_ow, d_ic, d_s, d_sh, d_sw;
+};
+
+struct GemmArgs {
+  const unsigned short* A;
+  const unsigned short* B;
+  unsigned short* D16;  // [M][N] fp16, written when splits == 1
+  float* Dpart;         // [splits][M][N] fp32 partial sums, written when splits > 1
+  int M, N, Kred;
+  int nkt;           // number of k tiles = ceil(Kred / BK)
+  int kt_per_split;  // k tiles each split handles
+  int splits;
+  int tiles_m, tiles_n;
+  ConvGeom g;
+};
+
+}  // namespace jz

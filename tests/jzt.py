@@ -93,3 +93,104 @@ def check_lars_against_oracle(ps: inputs.ParamSet, got, loss_scale=None, rtol=1e
     return dict(flag=0, n_boundary=int(diff.size), max_rel_w=float(np.max(ew / (wscale + 1e-300), initial=0.0)),
                 max_rel_v=float(np.max(ev / (vscale + 1e-300), initial=0.0)),
                 max_rel_w_plain=float(np.max(ew / (np.abs(w64) + 1e-300), initial=0.0)))
+
+
+# ---------------------------------------------------------------------------------------------
+# convolution / fully connected
+# ---------------------------------------------------------------------------------------------
+def _ws_tensor(nbytes):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=DEV) if nbytes else None
+
+
+def desc_of(c) -> "api.jz_conv_desc":
+    return api.conv_desc(c.N, c.H, c.W, c.C, c.K, c.R, c.S, c.stride, c.pad)
+
+
+def odesc_of(c):
+    return oracle.conv_desc(c.N, c.H, c.W, c.C, c.K, c.R, c.S, c.stride, c.pad)
+
+
+def run_conv(op, d, a: np.ndarray, b: np.ndarray, out_shape):
+    """Call one conv entry point through the C ABI; a, b are the two fp16 inputs in the order the entry point takes."""
+    ta, tb = to_dev(a), to_dev(b)
+    out = torch.full(out_shape, float("nan"), dtype=torch.float16, device=DEV)   # poison: every element must be written
+    ws = _ws_tensor(api.jz_conv2d_workspace_bytes(op, d))
+    fn = {api.JZ_FWD: api.jz_conv2d_fwd, api.JZ_BWD_DATA: api.jz_conv2d_bwd_data, api.JZ_BWD_WEIGHT: api.jz_conv2d_bwd_weight}[op]
+    fn(d, ta, tb, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def run_fc(mode, B, I, O, a, b, out_shape):
+    ta, tb = to_dev(a), to_dev(b)
+    out = torch.full(out_shape, float("nan"), dtype=torch.float16, device=DEV)
+    ws = _ws_tensor(api.jz_gemm_fc_workspace_bytes(mode, B, I, O))
+    api.jz_gemm_fc(mode, B, I, O, ta, tb, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+FP16_OVERFLOW = 65520.0      # |v| >= this rounds to +-Inf
+
+
+def check_half_output(got16: np.ndarray, ref64: np.ndarray, tol=1e-3, what=""):
+    """The conv/FC parity bar: relative L2 error <= tol against the fp64 oracle over every entry that is finite in
+    the oracle's fp16 rounding, and the +-Inf pattern of fp16 overflow must match exactly, except for entries whose
+    exact magnitude lies within 2^-10 (relative) of the overflow threshold 65520, where fp32 accumulation order may
+    legitimately tip the rounding either way (such an entry must then be +-Inf or within 2^-9 of the exact value)."""
+    got = np.asarray(got16).astype(np.float64).ravel()
+    ref = np.asarray(ref64, dtype=np.float64).ravel()
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert not np.any(np.isnan(got)) or np.any(np.isnan(ref)), what + ": NaN in output (element never written?)"
+    mag = np.abs(ref)
+    band = np.abs(mag - FP16_OVERFLOW) <= FP16_OVERFLOW * 2.0 ** -10
+    ref_inf = mag >= FP16_OVERFLOW
+    got_inf = np.isinf(got)
+    strict = ~band
+    assert np.array_equal(got_inf[strict], ref_inf[strict]), what + ": fp16 overflow pattern differs"
+    assert np.all(np.sign(got[ref_inf & strict]) == np.sign(ref[ref_inf & strict])), what + ": sign of overflow"
+    if np.any(band):
+        ok = got_inf[band] | (np.abs(got[band] - ref[band]) <= 2.0 ** -9 * mag[band])
+        assert np.all(ok), what + ": near-threshold entry is neither Inf nor the neighbouring finite value"
+    fin = ~ref_inf & ~got_inf
+    err = rel_l2(got[fin], ref[fin]) if np.any(fin) else 0.0
+    assert err <= tol, "%s: relative L2 error %.3e > %.1e" % (what, err, tol)
+    return dict(rel_l2=err, n_inf=int(np.count_nonzero(ref_inf)), n_band=int(np.count_nonzero(band)))
+
+
+def conv_all_ops_full(case, tol=1e-3, ops=(0, 1, 2)):
+    """fwd / bwd_data / bwd_weight of one layer against the full-tensor oracle."""
+    d, od = desc_of(case), odesc_of(case)
+    res = {}
+    if api.JZ_FWD in ops:
+        y = run_conv(api.JZ_FWD, d, case.x, case.w16, (case.N, case.P, case.Q, case.K))
+        res["fwd"] = check_half_output(y, oracle.conv_fwd(od, case.x, case.w16), tol, "fwd")
+    if api.JZ_BWD_DATA in ops:
+        dx = run_conv(api.JZ_BWD_DATA, d, case.dy, case.w16, (case.N, case.H, case.W, case.C))
+        res["bwd_data"] = check_half_output(dx, oracle.conv_bwd_data(od, case.dy, case.w16), tol, "bwd_data")
+    if api.JZ_BWD_WEIGHT in ops:
+        dw = run_conv(api.JZ_BWD_WEIGHT, d, case.x, case.dy, (case.K, case.R, case.S, case.C))
+        res["bwd_weight"] = check_half_output(dw, oracle.conv_bwd_weight(od, case.x, case.dy), tol, "bwd_weight")
+    return res
+
+
+def conv_all_ops_sampled(case, n_fwd=65536, n_bwd_data=65536, work_bwd_weight=6e8, seed=0, tol=1e-3, skip_bwd_data=False):
+    """Full-size layer: the GPU computes whole tensors, the oracle a seeded sample of output elements one by one."""
+    d, od = desc_of(case), odesc_of(case)
+    rng = np.random.default_rng(seed)
+    res = {}
+    y = run_conv(api.JZ_FWD, d, case.x, case.w16, (case.N, case.P, case.Q, case.K))
+    assert not np.any(np.isnan(y)), "fwd: unwritten output"
+    idx = rng.integers(0, y.size, size=min(n_fwd, y.size))
+    res["fwd"] = check_half_output(y.ravel()[idx], oracle.conv_fwd_at(od, case.x, case.w16, idx), tol, "fwd")
+    if not skip_bwd_data:
+        dx = run_conv(api.JZ_BWD_DATA, d, case.dy, case.w16, (case.N, case.H, case.W, case.C))
+        assert not np.any(np.isnan(dx)), "bwd_data: unwritten output"
+        idx = rng.integers(0, dx.size, size=min(n_bwd_data, dx.size))
+        res["bwd_data"] = check_half_output(dx.ravel()[idx], oracle.conv_bwd_data_at(od, case.dy, case.w16, idx), tol, "bwd_data")
+    dw = run_conv(api.JZ_BWD_WEIGHT, d, case.x, case.dy, (case.K, case.R, case.S, case.C))
+    assert not np.any(np.isnan(dw)), "bwd_weight: unwritten output"
+    n = int(max(256, min(dw.size, work_bwd_weight // (case.N * case.P * case.Q))))
+    idx = rng.integers(0, dw.size, size=n)
+    res["bwd_weight"] = check_half_output(dw.ravel()[idx], oracle.conv_bwd_weight_at(od, case.x, case.dy, idx), tol, "bwd_weight")
+    return res

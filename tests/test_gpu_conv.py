@@ -1,0 +1,191 @@
+"""GPU parity of the convolution and fully connected entry points (through the C ABI) against the fp64 oracle.
+Tolerance: relative L2 error <= 1e-3 (fp16 rounding of the result alone contributes about 2e-4)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1807_11205_amd import inputs, shapes
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jz():
+    from paper_1807_11205_amd import api
+    api.lib()
+    assert torch.cuda.is_available()
+    return api
+
+
+def test_config0_layer_literal_loss_scale(jz):
+    # 3x3, stride 1, pad 1, [2,14,14,16] -> 16 channels, dy ~ N(0,1) * 1024: the weight gradient overflows fp16 in a
+    # few entries; the overflow pattern has to match the oracle's
+    import jzt
+    c = inputs.conv_case((0,), 2, 14, 14, 16, 16, 3, 3, 1, 1, loss_scale=1024.0)
+    res = jzt.conv_all_ops_full(c)
+    print(res)
+
+
+def test_config0_layer_backed_off_loss_scale(jz):
+    import jzt
+    c = inputs.conv_case((0,), 2, 14, 14, 16, 16, 3, 3, 1, 1, loss_scale=256.0)
+    res = jzt.conv_all_ops_full(c)
+    assert res["bwd_weight"]["n_inf"] == 0
+    print(res)
+
+
+GENERIC = [
+    # N, H, W, C, K, R, S, stride, pad   -- none of these meets the vector paths' channel multiples
+    (2, 9, 7, 3, 5, 3, 2, (2, 1), (1, 0)),
+    (1, 8, 11, 4, 2, 1, 3, (1, 2), (0, 2)),
+    (2, 10, 9, 1, 3, 5, 4, (3, 2), (2, 3)),
+    (1, 23, 23, 3, 64, 7, 7, 2, 3),          # stem-like: 3 input channels, 7x7 stride 2
+    (2, 35, 35, 3, 96, 11, 11, 4, 0),        # AlexNet conv1-like
+    (3, 6, 6, 24, 40, 3, 3, 1, 1),           # channels multiple of 8 but not of 64
+    (1, 1, 1, 5, 7, 1, 1, 1, 0),             # a single dot product per output
+    (5, 4, 4, 130, 129, 1, 1, 1, 0),         # just over one tile in n and k
+]
+
+
+@pytest.mark.parametrize("cfg", GENERIC)
+def test_generic_shapes(jz, cfg):
+    import jzt
+    N, H, W, C, K, R, S, st, pad = cfg
+    c = inputs.conv_case((10, abs(hash(cfg)) % 10000), N, H, W, C, K, R, S, 1, 0)
+    # conv_case only knows symmetric stride/pad: build asymmetric descriptors by hand
+    sh, sw = (st, st) if isinstance(st, int) else st
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    rng = inputs.rng_for(10, 1, abs(hash(cfg)) % 10000)
+    import oracle
+    od = oracle.conv_desc(N, H, W, C, K, R, S, (sh, sw), (ph, pw))
+    d = jz.conv_desc(N, H, W, C, K, R, S, (sh, sw), (ph, pw))
+    x = inputs.normal_f16(rng, (N, H, W, C))
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=4.0)
+    jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
+    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+
+
+VECTOR = [
+    # N, H, W, C, K, R, S, stride, pad  -- channel counts that take the vector loaders; several tiles and ragged tails
+    (2, 13, 13, 64, 192, 3, 3, 1, 1),      # M = 338 (2.6 tiles), N = 192 (1.5 tiles)
+    (3, 14, 14, 128, 64, 1, 1, 1, 0),      # 1x1, 64 output channels (narrow tile)
+    (2, 14, 14, 256, 128, 1, 1, 2, 0),     # 1x1 stride 2 (ResNet downsample): backward-data leaves odd pixels zero
+    (1, 15, 15, 64, 64, 5, 5, 1, 2),       # 5x5 pad 2
+    (2, 9, 9, 64, 128, 3, 3, 2, 1),        # 3x3 stride 2 (the v1.5 placement)
+    (4, 7, 7, 192, 320, 3, 3, 1, 1),       # deep reduction, few pixels: split-K in fwd / bwd_data
+    (1, 8, 8, 64, 8, 1, 1, 1, 0),          # K = 8: vector path of backward-weight with a tiny m
+    (2, 6, 10, 128, 200, 3, 1, 1, (1, 0)), # R != S, H != W, K not a multiple of 64 (bwd_data falls back)
+]
+
+
+@pytest.mark.parametrize("cfg", VECTOR)
+def test_vector_path_shapes(jz, cfg):
+    import jzt
+    import oracle
+    N, H, W, C, K, R, S, st, pad = cfg
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, (ph, pw))
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, (ph, pw))
+    rng = inputs.rng_for(11, abs(hash(cfg)) % 10000)
+    x = inputs.normal_f16(rng, (N, H, W, C))
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+    r1 = jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+    r2 = jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
+    r3 = jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+    print(r1["rel_l2"], r2["rel_l2"], r3["rel_l2"])
+
+
+def test_delta_filter_copies_the_input_bit_exactly(jz):
+    import jzt
+    rng = inputs.rng_for(12)
+    N, H, W, C = 2, 10, 9, 64
+    x = inputs.normal_f16(rng, (N, H, W, C), std=30.0)
+    w = np.zeros((C, 3, 3, C), np.float16)
+    w[np.arange(C), 1, 1, np.arange(C)] = 1.0
+    y = jzt.run_conv(jz.JZ_FWD, jz.conv_desc(N, H, W, C, C, 3, 3, 1, 1), x, w, (N, H, W, C))
+    assert np.array_equal(y.view(np.uint16), x.view(np.uint16))
+
+
+def test_subnormal_inputs_and_outputs_are_kept(jz):
+    # 2^-24 (the paper's underflow threshold) times 1, 2, 3 ... must come out as the exact subnormal, not zero
+    import jzt
+    C = 64
+    x = np.zeros((1, 1, 1, C), np.float16)
+    x[0, 0, 0, 0] = np.float16(2.0 ** -24)
+    w = np.zeros((8, 1, 1, C), np.float16)
+    w[:, 0, 0, 0] = np.arange(1, 9)
+    y = jzt.run_conv(jz.JZ_FWD, jz.conv_desc(1, 1, 1, C, 8, 1, 1), x, w, (1, 1, 1, 8))
+    assert np.array_equal(y.ravel().view(np.uint16), np.arange(1, 9, dtype=np.uint16))
+
+
+def test_adjoint_identities_on_gpu_outputs(jz):
+    import jzt
+    c = inputs.conv_case((13,), 2, 12, 12, 64, 128, 3, 3, 1, 1, loss_scale=1.0)
+    d = jzt.desc_of(c)
+    y = jzt.run_conv(jz.JZ_FWD, d, c.x, c.w16, (c.N, c.P, c.Q, c.K)).astype(np.float64)
+    dx = jzt.run_conv(jz.JZ_BWD_DATA, d, c.dy, c.w16, (c.N, c.H, c.W, c.C)).astype(np.float64)
+    dw = jzt.run_conv(jz.JZ_BWD_WEIGHT, d, c.x, c.dy, (c.K, c.R, c.S, c.C)).astype(np.float64)
+    a = np.sum(y * c.dy.astype(np.float64))
+    b = np.sum(c.x.astype(np.float64) * dx)
+    e = np.sum(c.w16.astype(np.float64) * dw)
+    scale = np.linalg.norm(y) * np.linalg.norm(c.dy.astype(np.float64))
+    assert abs(a - b) <= 1e-3 * scale and abs(a - e) <= 1e-3 * scale
+
+
+def test_same_inputs_give_identical_bits(jz):
+    import jzt
+    c = inputs.conv_case((14,), 4, 7, 7, 192, 320, 3, 3, 1, 1, loss_scale=16.0)   # split-K in every op
+    d = jzt.desc_of(c)
+    for op, a, b, shp in ((jz.JZ_FWD, c.x, c.w16, (c.N, c.P, c.Q, c.K)), (jz.JZ_BWD_DATA, c.dy, c.w16, (c.N, c.H, c.W, c.C)),
+                          (jz.JZ_BWD_WEIGHT, c.x, c.dy, (c.K, c.R, c.S, c.C))):
+        r1 = jzt.run_conv(op, d, a, b, shp)
+        r2 = jzt.run_conv(op, d, a, b, shp)
+        assert np.array_equal(r1.view(np.uint16), r2.view(np.uint16))
+
+
+@pytest.mark.parametrize("B,I,O", [(64, 2048, 1000), (128, 1024, 520), (5, 24, 7), (1, 64, 64), (130, 192, 72)])
+def test_fully_connected_modes(jz, B, I, O):
+    import jzt
+    import oracle
+    c = inputs.fc_case((15, B, I, O), B, I, O, loss_scale=32.0)
+    jzt.check_half_output(jzt.run_fc(jz.JZ_FWD, B, I, O, c.x, c.w16, (B, O)), oracle.fc_fwd(B, I, O, c.x, c.w16), what="fc fwd")
+    jzt.check_half_output(jzt.run_fc(jz.JZ_BWD_DATA, B, I, O, c.dy, c.w16, (B, I)), oracle.fc_bwd_data(B, I, O, c.dy, c.w16), what="fc bwd_data")
+    jzt.check_half_output(jzt.run_fc(jz.JZ_BWD_WEIGHT, B, I, O, c.dy, c.x, (O, I)), oracle.fc_bwd_weight(B, I, O, c.dy, c.x), what="fc bwd_weight")
+
+
+def test_fc_equals_one_by_one_conv_bit_for_bit(jz):
+    import jzt
+    c = inputs.fc_case((16,), 96, 256, 192)
+    y1 = jzt.run_fc(jz.JZ_FWD, 96, 256, 192, c.x, c.w16, (96, 192))
+    y2 = jzt.run_conv(jz.JZ_FWD, jz.conv_desc(96, 1, 1, 256, 192, 1, 1), c.x, c.w16, (96, 1, 1, 192))
+    assert np.array_equal(y1.view(np.uint16).ravel(), y2.view(np.uint16).ravel())
+
+
+def test_argument_errors(jz):
+    import jzt
+    api = jz
+    d = api.conv_desc(2, 8, 8, 64, 64, 3, 3, 1, 1)
+    x = torch.zeros(2 * 8 * 8 * 64, dtype=torch.float16, device=jzt.DEV)
+    w = torch.zeros(64 * 9 * 64, dtype=torch.float16, device=jzt.DEV)
+    y = torch.zeros(2 * 8 * 8 * 64, dtype=torch.float16, device=jzt.DEV)
+    L = api.lib()
+    import ctypes
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert L.jz_conv2d_fwd(ctypes.byref(d), None, w.data_ptr(), y.data_ptr(), None, 0, st) == api.JZ_ERR_NULL
+    assert L.jz_conv2d_fwd(ctypes.byref(d), x.data_ptr() + 2, w.data_ptr(), y.data_ptr(), None, 0, st) == api.JZ_ERR_ALIGN
+    assert L.jz_conv2d_fwd(ctypes.byref(d), x.data_ptr(), w.data_ptr(), x.data_ptr(), None, 0, st) == api.JZ_ERR_ALIAS
+    bad = api.conv_desc(2, 8, 8, 64, 64, 3, 3, 1, 3)     # pad >= filter size
+    assert L.jz_conv2d_fwd(ctypes.byref(bad), x.data_ptr(), w.data_ptr(), y.data_ptr(), None, 0, st) == api.JZ_ERR_SHAPE
+    bad = api.conv_desc(2, 2, 2, 64, 64, 5, 5, 1, 0)     # filter larger than the padded image
+    assert L.jz_conv2d_fwd(ctypes.byref(bad), x.data_ptr(), w.data_ptr(), y.data_ptr(), None, 0, st) == api.JZ_ERR_SHAPE
+    dw = api.conv_desc(64, 7, 7, 64, 64, 3, 3, 1, 1)     # backward-weight needs a split-K workspace here
+    need = api.jz_conv2d_workspace_bytes(api.JZ_BWD_WEIGHT, dw)
+    assert need > 0
+    xx = torch.zeros(64 * 49 * 64, dtype=torch.float16, device=jzt.DEV)
+    assert L.jz_conv2d_bwd_weight(ctypes.byref(dw), xx.data_ptr(), xx.data_ptr() , w.data_ptr(), None, 0, st) == api.JZ_ERR_WORKSPACE
+    assert L.jz_gemm_fc(7, 4, 4, 4, x.data_ptr(), w.data_ptr(), y.data_ptr(), None, 0, st) == api.JZ_ERR_UNSUPPORTED
+    assert L.jz_gemm_fc(0, 0, 4, 4, x.data_ptr(), w.data_ptr(), y.data_ptr(), None, 0, st) == api.JZ_ERR_SHAPE
+    torch.cuda.synchronize()
