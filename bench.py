@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X: ResNet-50 (v1) N=64, fp16 storage / fp32 accumulate.
+
+One step = forward of all 53 convolutions and the classifier, then backward-data (not for the stem) and
+backward-weight of every layer in reverse order with the weight gradients written straight into the fused flat
+gradient buffer, then one mixed-precision LARS update over all 161 tensors (25,557,032 parameters).  Batch norm,
+ReLU, pooling and the residual adds are not part of this path, so every layer has its own seeded synthetic input
+and output gradient of the right shape (a chained stack without normalisation would overflow fp16).
+
+Prints ONE JSON line.  `value` is images/s of the whole step with all inputs resident in HBM; `roofline` is for
+the implicit-GEMM kernel family (all conv/FC launches of a step, algorithmic flops / their time between HIP events
+on the launch stream); `lars` gives the update's GB/s against HBM; `cpu_baseline` times the fp64 oracle on the
+host cores on a two-image sample of the same stack.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+from paper_1807_11205_amd import api, inputs, shapes
+
+FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
+LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32 4 + w16 2
+
+
+class ResNet50Step:
+    """All device buffers of one ResNet-50 N=batch step and the launch sequence."""
+
+    def __init__(self, batch=64, loss_scale=1024.0, seed=180711205, variant="v1", device="cuda:0"):
+        self.N = batch
+        self.dev = device
+        self.loss_scale = float(loss_scale)
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+        self.gen = gen
+        self.convs = shapes.resnet50_convs(variant)
+        self.fc = shapes.RESNET50_FC
+        tensors = shapes.resnet50_param_tensors(variant)
+        self.offsets = shapes.offsets_of(tensors)
+        self.flags = [t[3] for t in tensors]
+        P = self.offsets[-1]
+        h = torch.float16
+
+        def randn(n, std=1.0):
+            return (torch.randn(n, generator=gen, device=device, dtype=torch.float32) * std).to(h)
+
+        # fused flat parameter state: fp32 master (He-normal filters, gamma 1, beta 0, bias 0), momentum 0, fp16 copies
+        self.master = torch.zeros(P, dtype=torch.float32, device=device)
+        for i, (_, shp, kind, _) in enumerate(tensors):
+            a, b = self.offsets[i], self.offsets[i + 1]
+            if kind in ("conv", "fc"):
+                fan_in = shp[1] * shp[2] * shp[3] if kind == "conv" else shp[1]
+                self.master[a:b] = torch.randn(b - a, generator=gen, device=device) * float(np.sqrt(2.0 / fan_in))
+            elif kind == "gamma":
+                self.master[a:b] = 1.0
+        self.momentum = torch.zeros(P, dtype=torch.float32, device=device)
+        self.w16 = self.master.to(h)
+        # gradients of batch-norm and bias tensors are not produced on this path: fixed synthetic values ~ N(0,1e-3)*S
+        self.grad = randn(P, 1e-3 * self.loss_scale)
+        self.master0, self.w16_0 = self.master.clone(), self.w16.clone()
+
+        self.layers = []
+        ws_bytes = 0
+        self.flops = 0
+        for li, cs in enumerate(self.convs):
+            d = api.conv_desc(batch, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+            ti = 3 * li
+            a, b = self.offsets[ti], self.offsets[ti + 1]
+            L = dict(kind="conv", name=cs.name, d=d, first=cs.first,
+                     x=randn(batch * cs.H * cs.H * cs.C), dy=randn(batch * cs.P * cs.P * cs.K, self.loss_scale),
+                     y=torch.empty(batch * cs.P * cs.P * cs.K, dtype=h, device=device),
+                     dx=None if cs.first else torch.empty(batch * cs.H * cs.H * cs.C, dtype=h, device=device),
+                     w=self.w16[a:b], dw=self.grad[a:b])
+            for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
+                ws_bytes = max(ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
+            self.flops += 2 * cs.macs(batch) * (2 if cs.first else 3)
+            self.layers.append(L)
+        ti = 3 * len(self.convs)
+        a, b = self.offsets[ti], self.offsets[ti + 1]
+        B, I, O = batch, self.fc.I, self.fc.O
+        self.layers.append(dict(kind="fc", name="fc", x=randn(B * I), dy=randn(B * O, self.loss_scale),
+                                y=torch.empty(B * O, dtype=h, device=device), dx=torch.empty(B * I, dtype=h, device=device),
+                                w=self.w16[a:b], dw=self.grad[a:b]))
+        for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
+            ws_bytes = max(ws_bytes, api.jz_gemm_fc_workspace_bytes(op, B, I, O))
+        self.flops += 2 * self.fc.macs(batch) * 3
+        self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)
+
+        self.found_inf = torch.zeros(1, dtype=torch.int32, device=device)
+        self.ps = api.ParamSet(self.offsets, self.flags, self.master, self.momentum, self.grad, self.w16)
+        self.lars_ws = torch.zeros(api.jz_lars_workspace_bytes(self.ps), dtype=torch.uint8, device=device)
+        api.jz_lars_prepare(self.ps, self.lars_ws)
+        self.P = P
+        self.n_gemm_launches = 0
+
+    def hparams(self):
+        hp = inputs.HPARAMS
+        return api.lars_hparams(hp["lr"], hp["momentum"], hp["weight_decay"], hp["trust_coef"], self.loss_scale)
+
+    def run_gemms(self):
+        B, I, O = self.N, self.fc.I, self.fc.O
+        for L in self.layers:                                   # forward
+            if L["kind"] == "conv":
+                api.jz_conv2d_fwd(L["d"], L["x"], L["w"], L["y"], self.ws)
+            else:
+                api.jz_gemm_fc(api.JZ_FWD, B, I, O, L["x"], L["w"], L["y"], self.ws)
+        for L in reversed(self.layers):                         # backward
+            if L["kind"] == "conv":
+                if not L["first"]:
+                    api.jz_conv2d_bwd_data(L["d"], L["dy"], L["w"], L["dx"], self.ws)
+                api.jz_conv2d_bwd_weight(L["d"], L["x"], L["dy"], L["dw"], self.ws)
+            else:
+                api.jz_gemm_fc(api.JZ_BWD_DATA, B, I, O, L["dy"], L["w"], L["dx"], self.ws)
+                api.jz_gemm_fc(api.JZ_BWD_WEIGHT, B, I, O, L["dy"], L["x"], L["dw"], self.ws)
+
+    def run_lars(self):
+        api.jz_lars_mp_update(self.ps, self.hparams(), self.found_inf, self.lars_ws)
+
+    def step(self):
+        self.run_gemms()
+        self.run_lars()
+
+    def halve_loss_scale(self):
+        """Back off after an overflow: every loss-scaled quantity is halved (exact in fp16 short of underflow)."""
+        self.loss_scale *= 0.5
+        for L in self.layers:
+            L["dy"].mul_(0.5)
+        self.grad.mul_(0.5)
+
+    def reset_state(self):
+        self.master.copy_(self.master0)
+        self.w16.copy_(self.w16_0)
+        self.momentum.zero_()
+
+
+def cpu_baseline(sample_batch=2):
+    """The fp64 oracle, as it stands, on the host cores: the same 53-conv + FC stack at a small batch, plus LARS."""
+    import oracle
+    gemm_s = 0.0
+    for li, cs in enumerate(shapes.resnet50_convs()):
+        c = inputs.conv_case_for(cs, sample_batch, (77, li), loss_scale=1.0)
+        od = oracle.conv_desc(c.N, c.H, c.W, c.C, c.K, c.R, c.S, c.stride, c.pad)
+        t1 = time.perf_counter()
+        oracle.conv_fwd(od, c.x, c.w16)
+        if not cs.first:
+            oracle.conv_bwd_data(od, c.dy, c.w16)
+        oracle.conv_bwd_weight(od, c.x, c.dy)
+        gemm_s += time.perf_counter() - t1
+    fc = shapes.RESNET50_FC
+    f = inputs.fc_case((77, 99), sample_batch, fc.I, fc.O)
+    t1 = time.perf_counter()
+    oracle.fc_fwd(sample_batch, fc.I, fc.O, f.x, f.w16)
+    oracle.fc_bwd_data(sample_batch, fc.I, fc.O, f.dy, f.w16)
+    oracle.fc_bwd_weight(sample_batch, fc.I, fc.O, f.dy, f.x)
+    gemm_s += time.perf_counter() - t1
+    ps = inputs.resnet50_param_set(loss_scale=1024.0)
+    t1 = time.perf_counter()
+    oracle.lars_mp_update(ps.offsets, ps.flags, ps.master_w, ps.momentum, ps.grad16, ps.weight16, loss_scale=1024.0, **inputs.HPARAMS)
+    lars_s = time.perf_counter() - t1
+    total = gemm_s + lars_s
+    return {"value": sample_batch / total, "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "fp64 oracle, all 53 convs + FC fwd/bwd_data/bwd_weight at N=%d (%.1f s; its backward-data routine "
+                      "threads over images only) plus one LARS update over all 25,557,032 parameters (%.2f s); input "
+                      "generation not timed" % (sample_batch, gemm_s, lars_s),
+            "lars_gbps": LARS_BYTES_PER_PARAM * ps.P / lars_s / 1e9}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", type=int, default=1, help="replay the step from a HIP graph (1) or launch eagerly (0)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    api.lib()
+    torch.cuda.set_device(0)
+    wl = ResNet50Step(batch=args.batch)
+
+    # loss-scale back-off: halve S until the weight gradients stay inside fp16 and the update is not skipped
+    for _ in range(12):
+        wl.step()
+        torch.cuda.synchronize()
+        if int(wl.found_inf.item()) == 0:
+            break
+        wl.halve_loss_scale()
+    assert int(wl.found_inf.item()) == 0, "loss-scale back-off did not clear the overflow flag"
+    wl.reset_state()
+
+    stream = torch.cuda.Stream()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    with torch.cuda.stream(stream):
+        for _ in range(max(args.warmup, 1)):
+            wl.step()
+        stream.synchronize()
+        graphs = None
+        if args.graph:
+            # two graphs (GEMM phase, LARS phase) so that HIP events can separate the phases between replays
+            g1, g2 = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g1, stream=stream):
+                wl.run_gemms()
+            with torch.cuda.graph(g2, stream=stream):
+                wl.run_lars()
+            graphs = (g1, g2)
+            for _ in range(2):
+                g1.replay(); g2.replay()
+            stream.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            ev[k][0].record(stream)
+            if graphs:
+                graphs[0].replay()
+            else:
+                wl.run_gemms()
+            ev[k][1].record(stream)
+            if graphs:
+                graphs[1].replay()
+            else:
+                wl.run_lars()
+            ev[k][2].record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    assert int(wl.found_inf.item()) == 0
+    gemm_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    lars_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    ms_per_step = wall * 1e3 / args.steps
+    n_gemm = 0
+    for L in wl.layers:
+        n_gemm += 3 if not L.get("first") else 2
+    tflops = wl.flops / (gemm_ms * 1e-3) / 1e12
+    lars_gbps = LARS_BYTES_PER_PARAM * wl.P / (lars_ms * 1e-3) / 1e9
+    out = {
+        "metric": "ResNet-50 N=64 fp16 fwd+bwd images/s",
+        "value": args.batch / (ms_per_step * 1e-3),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 storage, f32 accumulate (LARS in f32, norms f64)",
+        "data": "synthetic",
+        "config": {"workload": "configs[4]: ResNet-50 v1, 53 convs + FC, fwd + bwd_data + bwd_weight per layer on "
+                               "independent seeded N(0,1) inputs, then fused LARS over 161 tensors / 25,557,032 params",
+                   "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "launch": "hip graph" if graphs else "eager"},
+        "pct_fp16_mfma_peak": 100.0 * (wl.flops / (ms_per_step * 1e-3) / 1e12) / FP16_MFMA_PEAK_TFLOPS,
+        "roofline": {"kernel": "igemm_kernel (all %d conv/FC launches of a step)" % n_gemm, "bound": "mfma",
+                     "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "flop_per_step": wl.flops, "ms_per_step_gemm_phase": gemm_ms, "avg_launch_us": gemm_ms * 1e3 / n_gemm},
+        "lars": {"bound": "hbm", "achieved": lars_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": lars_gbps / HBM_PEAK_GBPS,
+                 "bytes_per_param": LARS_BYTES_PER_PARAM, "params": wl.P, "us_per_update": lars_ms * 1e3, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
