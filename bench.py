@@ -137,6 +137,55 @@ class ResNet50Step:
         self.momentum.zero_()
 
 
+def per_layer_report(wl, iters=20):
+    """Time every launch of the step on its own (HIP events, `iters` back-to-back repeats) and print one line per
+    layer and op: time, TFLOP/s, the layer's own roofline min(MFMA peak, flop / compulsory bytes * HBM peak) and the
+    fraction of it reached.  Compulsory bytes = both inputs read once + the output written once."""
+    B, I, O = wl.N, wl.fc.I, wl.fc.O
+    rows = []
+
+    def timeit(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    for L in wl.layers:
+        if L["kind"] == "conv":
+            d = L["d"]
+            macs = d.N * d.P * d.Q * d.K * d.R * d.S * d.C
+            ops = [("fwd", lambda: api.jz_conv2d_fwd(d, L["x"], L["w"], L["y"], wl.ws))]
+            if not L["first"]:
+                ops.append(("bwd_data", lambda: api.jz_conv2d_bwd_data(d, L["dy"], L["w"], L["dx"], wl.ws)))
+            ops.append(("bwd_weight", lambda: api.jz_conv2d_bwd_weight(d, L["x"], L["dy"], L["dw"], wl.ws)))
+            nbytes = 2 * (L["x"].numel() + L["w"].numel() + L["y"].numel())
+            desc = "%dx%d %d->%d %dx%d s%d" % (d.H, d.W, d.C, d.K, d.R, d.S, d.stride_h)
+        else:
+            macs = B * I * O
+            ops = [("fwd", lambda: api.jz_gemm_fc(api.JZ_FWD, B, I, O, L["x"], L["w"], L["y"], wl.ws)),
+                   ("bwd_data", lambda: api.jz_gemm_fc(api.JZ_BWD_DATA, B, I, O, L["dy"], L["w"], L["dx"], wl.ws)),
+                   ("bwd_weight", lambda: api.jz_gemm_fc(api.JZ_BWD_WEIGHT, B, I, O, L["dy"], L["x"], L["dw"], wl.ws))]
+            nbytes = 2 * (L["x"].numel() + L["w"].numel() + L["y"].numel())
+            desc = "fc %d->%d" % (I, O)
+        for name, fn in ops:
+            ms = timeit(fn)
+            tf = 2 * macs / (ms * 1e-3) / 1e12
+            roof = min(FP16_MFMA_PEAK_TFLOPS, 2 * macs / nbytes * HBM_PEAK_GBPS / 1e3)
+            rows.append((L["name"], desc, name, ms, tf, roof, tf / roof))
+            print("%-7s %-24s %-10s %8.1f us %8.1f TFLOP/s  roofline %7.1f  frac %.3f" % (L["name"], desc, name, ms * 1e3, tf, roof, tf / roof),
+                  file=sys.stderr, flush=True)
+    tot = sum(r[3] for r in rows)
+    print("sum of per-launch times: %.3f ms" % tot, file=sys.stderr)
+    for opn in ("fwd", "bwd_data", "bwd_weight"):
+        print("  %-10s %.3f ms" % (opn, sum(r[3] for r in rows if r[2] == opn)), file=sys.stderr)
+    return rows
+
+
 def cpu_baseline(sample_batch=2):
     """The fp64 oracle, as it stands, on the host cores: the same 53-conv + FC stack at a small batch, plus LARS."""
     import oracle
@@ -176,6 +225,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
     ap.add_argument("--graph", type=int, default=1, help="replay the step from a HIP graph (1) or launch eagerly (0)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -194,6 +244,10 @@ def main():
         wl.halve_loss_scale()
     assert int(wl.found_inf.item()) == 0, "loss-scale back-off did not clear the overflow flag"
     wl.reset_state()
+
+    if args.per_layer:
+        per_layer_report(wl)
+        wl.reset_state()
 
     stream = torch.cuda.Stream()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]

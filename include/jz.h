@@ -42,7 +42,7 @@ enum {
   JZ_OK = 0,
   JZ_ERR_NULL = -1,        /* a required pointer is NULL */
   JZ_ERR_SHAPE = -2,       /* non-positive dimension, empty output, pad >= filter size, bad offsets table */
-  JZ_ERR_UNSUPPORTED = -3, /* valid but not implemented (e.g. tensor with >= 2^31 elements) */
+  JZ_ERR_UNSUPPORTED = -3, /* valid but not implemented (e.g. a conv tensor with >= 2^30 elements) */
   JZ_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than *_workspace_bytes reports */
   JZ_ERR_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
   JZ_ERR_ALIAS = -6,       /* an output overlaps an input or the workspace */

@@ -13,6 +13,10 @@
 // FAST kernels need channel counts that are multiples of 64 (resp. 8), which makes a k tile lie inside one filter
 // tap so that all tap arithmetic is wave-uniform.  Everything else (3-channel stems, odd sizes) goes through the
 // element-wise GENERIC loaders: same tiles, same MFMA loop, every element bounds-checked.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "jz_igemm.h"
 #include "jz_internal.h"
 
@@ -101,6 +105,83 @@ __device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[
       unsigned lo = s[(2 * j) * 4 + (e >> 1)], hi = s[(2 * j + 1) * 4 + (e >> 1)];
       d[e * 4 + j] = __builtin_amdgcn_perm(hi, lo, (e & 1) ? 0x07060302u : 0x05040100u);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// epilogue shared by both kernels: fp32 partial sums (split-K) or the single rounding to fp16
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN, int TM, int TN>
+__device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&acc)[TM][TN], unsigned short* lds, int m0,
+                                                    int n0, int split, int tid, int lane, int wm, int wn) {
+  // ---- epilogue ------------------------------------------------------------------------------
+  // accumulator register r of tile (i,j): m = wm*BM/2 + 32 i + lane%32, n = wn*BN/2 + 32 j + 8 (r/4) + 4 (lane/32) + r%4
+  if (a.splits > 1) {
+    float* P = a.Dpart + (size_t)split * a.M * a.N;
+    const bool vec = (a.N & 3) == 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      int m = m0 + wm * (BM / 2) + 32 * i + (lane & 31);
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          int n = n0 + wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
+          float* dst = P + (size_t)m * a.N + n;
+          if (vec && n + 3 < a.N) {
+            *reinterpret_cast<float4*>(dst) =
+                make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < a.N) dst[e] = acc[i][j][4 * q4 + e];
+          }
+        }
+    }
+    return;
+  }
+  // single rounding fp32 -> fp16 (round to nearest even), staged through LDS for 16-byte coalesced stores
+  constexpr int LDC = BN + 8;
+  unsigned short* sC = lds;  // the k loop ended with a barrier: the tile buffers are free
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        int row = wm * (BM / 2) + 32 * i + (lane & 31);
+        int col = wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
+        _Float16 h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[i][j][4 * q4 + e];
+        uint2 pk;
+        __builtin_memcpy(&pk, h, 8);
+        *reinterpret_cast<uint2*>(sC + row * LDC + col) = pk;
+      }
+  __syncthreads();
+  constexpr int CCH = BN / 8;             // 16-byte chunks per output row
+  constexpr int CRPP = THREADS / CCH;     // rows per pass
+  const int cch = tid % CCH, crow = tid / CCH;
+  const bool nvec = (a.N & 7) == 0;
+#pragma unroll
+  for (int i = 0; i < BM / CRPP; ++i) {
+    int row = crow + CRPP * i;
+    int m = m0 + row, n = n0 + cch * 8;
+    if (m >= a.M || n >= a.N) continue;
+    const unsigned short* src = sC + row * LDC + cch * 8;
+    unsigned short* dst = a.D16 + (size_t)m * a.N + n;
+    if (nvec) {
+      *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+    } else {
+      for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = src[e];
+    }
+  }
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void igemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / 64][BN / 64], unsigned short* lds,
+                                               int m0, int n0, int split, int tid, int lane, int wm, int wn) {
+  igemm_epilogue_impl<BM, BN, BM / 64, BN / 64>(a, acc, lds, m0, n0, split, tid, lane, wm, wn);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -344,70 +425,10 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a) {
     buf ^= 1;
   }
 
-  // ---- epilogue ------------------------------------------------------------------------------
-  // accumulator register r of tile (i,j): m = wm*BM/2 + 32 i + lane%32, n = wn*BN/2 + 32 j + 8 (r/4) + 4 (lane/32) + r%4
-  if (a.splits > 1) {
-    float* P = a.Dpart + (size_t)split * a.M * a.N;
-    const bool vec = (a.N & 3) == 0;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      int m = m0 + wm * (BM / 2) + 32 * i + (lane & 31);
-      if (m >= a.M) continue;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          int n = n0 + wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
-          float* dst = P + (size_t)m * a.N + n;
-          if (vec && n + 3 < a.N) {
-            *reinterpret_cast<float4*>(dst) =
-                make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (n + e < a.N) dst[e] = acc[i][j][4 * q4 + e];
-          }
-        }
-    }
-    return;
-  }
-  // single rounding fp32 -> fp16 (round to nearest even), staged through LDS for 16-byte coalesced stores
-  constexpr int LDC = BN + 8;
-  unsigned short* sC = lds;  // the k loop ended with a barrier: the tile buffers are free
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        int row = wm * (BM / 2) + 32 * i + (lane & 31);
-        int col = wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
-        _Float16 h[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[i][j][4 * q4 + e];
-        uint2 pk;
-        __builtin_memcpy(&pk, h, 8);
-        *reinterpret_cast<uint2*>(sC + row * LDC + col) = pk;
-      }
-  __syncthreads();
-  constexpr int CCH = BN / 8;             // 16-byte chunks per output row
-  constexpr int CRPP = THREADS / CCH;     // rows per pass
-  const int cch = tid % CCH, crow = tid / CCH;
-  const bool nvec = (a.N & 7) == 0;
-#pragma unroll
-  for (int i = 0; i < BM / CRPP; ++i) {
-    int row = crow + CRPP * i;
-    int m = m0 + row, n = n0 + cch * 8;
-    if (m >= a.M || n >= a.N) continue;
-    const unsigned short* src = sC + row * LDC + cch * 8;
-    unsigned short* dst = a.D16 + (size_t)m * a.N + n;
-    if (nvec) {
-      *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
-    } else {
-      for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = src[e];
-    }
-  }
+  igemm_epilogue<BM, BN>(a, acc, lds, m0, n0, split, tid, lane, wm, wn);
 }
+
+#include "jz_igemm_dma.h"
 
 // D16[i] = RNE16( sum_s part[s][i] ), splits added in index order (deterministic)
 __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ part, unsigned short* __restrict__ out,
@@ -460,7 +481,7 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return JZ_ERR_SHAPE;
   const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
   if (P <= 0 || Q <= 0) return JZ_ERR_SHAPE;
-  const long long lim = (1ll << 31) - 1;
+  const long long lim = (1ll << 31) - 1;  // byte offsets are formed in unsigned 32-bit integers
   const long long nx = (long long)d->N * d->H * d->W * d->C, ny = (long long)d->N * P * Q * d->K,
                   nw = (long long)d->K * d->R * d->S * d->C;
   if (nx > lim || ny > lim || nw > lim) return JZ_ERR_UNSUPPORTED;
@@ -533,10 +554,42 @@ int launch_one(const GemmArgs& a, hipStream_t st) {
   return jz::launch_status();
 }
 
+template <int OP, int BM, int BN, int NST>
+int launch_dma(const GemmArgs& a, hipStream_t st) {
+  constexpr size_t ring_bytes = (size_t)NST * (BM + BN) * 128;
+  constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(unsigned short);
+  constexpr size_t smem = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, NST>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+      return JZ_ERR_LAUNCH;
+    attr_set = true;
+  }
+  unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.splits;
+  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, NST>), dim3(grid), dim3(THREADS), smem, st, a);
+  return jz::launch_status();
+}
+
+bool use_register_path() {  // debugging aid: JZ_IGEMM_PATH=reg selects the register-staged vector kernels
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("JZ_IGEMM_PATH");
+    v = (e && e[0] == 'r') ? 1 : 0;
+  }
+  return v == 1;
+}
+
 template <int OP>
 int launch_op(const Plan& pl, hipStream_t st) {
   const GemmArgs& a = pl.args;
   if (!pl.fast) return launch_one<OP, false, 128, 128>(a, st);
+  if (!use_register_path()) {
+    if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 4>(a, st);
+    if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 4>(a, st);
+    if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 4>(a, st);
+    return launch_dma<OP, 64, 64, 4>(a, st);
+  }
   if (pl.BM == 128 && pl.BN == 128) return launch_one<OP, true, 128, 128>(a, st);
   if (pl.BM == 128 && pl.BN == 64) return launch_one<OP, true, 128, 64>(a, st);
   if (pl.BM == 64 && pl.BN == 128) return launch_one<OP, true, 64, 128>(a, st);
@@ -558,6 +611,8 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
   pl.args.B = static_cast<const unsigned short*>(B);
   pl.args.D16 = static_cast<unsigned short*>(D);
   pl.args.Dpart = static_cast<float*>(ws);
+  pl.args.bytesA = (unsigned)pl.bytesA;
+  pl.args.bytesB = (unsigned)pl.bytesB;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (op == JZ_FWD) rc = launch_op<OP_FWD>(pl, st);
   else if (op == JZ_BWD_DATA) rc = launch_op<OP_BWD_DATA>(pl, st);

@@ -48,6 +48,7 @@ struct GemmArgs {
   const unsigned short* B;
   unsigned short* D16;  // [M][N] fp16, written when splits == 1
   float* Dpart;         // [splits][M][N] fp32 partial sums, written when splits > 1
+  unsigned bytesA, bytesB;  // sizes of the A / B tensors: the bounds of their buffer descriptors
   int M, N, Kred;
   int nkt;           // number of k tiles = ceil(Kred / BK)
   int kt_per_split;  // k tiles each split handles

@@ -1,0 +1,388 @@
+// Implicit-GEMM kernel with LDS-direct loads and a multi-stage ring, for channel counts that allow 16-byte
+// vector access (see the table in jz_igemm.h for what A, B, m, n, k are in each op).  Included by jz_conv.hip.
+//
+// Why this shape.  One k tile of a 128x128 output tile is 512 MFMA cycles per wavefront but an HBM round trip
+// is several thousand cycles, so a tile's operands have to be requested three tiles ahead.  Staging that much
+// through registers costs the occupancy it is meant to buy, so the tiles never touch registers on the way in:
+// `buffer_load_dwordx4 ... lds` writes 64 lanes x 16 bytes straight into LDS (wave-uniform base + lane*16), out of
+// range offsets deliver zeros (padding taps, rows beyond M/N, the reduction tail), and NST stages of
+// (BM+BN) x 128 bytes form a ring.  Each iteration: wait until the oldest stage has landed (vmcnt), one
+// workgroup barrier, request the tile NST-1 ahead into the stage that was just consumed, multiply.
+//
+// LDS layouts (one stage = A tile then B tile, both BK = 64 deep):
+//   k-contiguous operand  ("KC": x / dy gathered per pixel, the forward filter): [row][8 chunks of 16 B], row pitch
+//       128 B, chunk c of row r stored at position c ^ (r & 7); MFMA operands are plain ds_read_b128.
+//   mn-contiguous operand ("MC": the filter in backward-data, dy and x in backward-weight): [k][ROWS/8 chunks],
+//       stored exactly as it sits in memory, chunk c of k-row k at position c ^ swz(k); MFMA operands come from
+//       ds_read_b64_tr_b16, which hands each lane four consecutive k of one mn out of such a layout (within 16
+//       lanes: lanes 4j..4j+3 supply 16 consecutive mn of k-row j, lane i receives rows 0..3 at mn i).
+// The swizzles make both the 1 KB DMA writes and the operand reads bank-conflict free.
+//
+// The operand reads are issued through inline assembly with hand-placed s_waitcnt: the compiler cannot tell which
+// ring stage an LDS read touches and would otherwise wait for every outstanding LDS-direct load (vmcnt(0)) before
+// each read, which would serialise the ring.
+#pragma once
+
+typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+#define JZ_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// The host pass of hipcc parses these bodies too and has no AMDGPU register constraints, hence the guards.
+template <int OFF>
+__device__ __forceinline__ half8 lds_read_b128(unsigned addr) {
+  half8 v = {};
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+#endif
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ half4v lds_read_tr16_b64(unsigned addr) {
+  half4v v = {};
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+#endif
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+#endif
+}
+// Wait until at most KEEP LDS reads are outstanding.  The operands about to be consumed are named as in/out so that
+// the MFMAs using them cannot be scheduled above the wait.
+template <int KEEP>
+__device__ __forceinline__ void lds_settle(half8& a, half8& b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(KEEP));
+#endif
+}
+template <int KEEP>
+__device__ __forceinline__ void lds_settle(half8& a, half8& b, half8& c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(KEEP));
+#endif
+}
+template <int KEEP>
+__device__ __forceinline__ void lds_settle(half8& a, half8& b, half8& c, half8& d) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(KEEP));
+#endif
+}
+
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+// one LDS-direct load: 64 lanes x 16 bytes from `rsrc` at per-lane byte offset `voff` to LDS at dst + lane * 16
+__device__ __forceinline__ void jz_dma16(__amdgpu_buffer_rsrc_t rsrc, lds_byte* dst, unsigned voff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, (int)voff, 0, 0, 0);
+}
+
+template <int OP, int BM, int BN, int NST>
+__global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
+  constexpr bool A_KC = OP != OP_BWD_WEIGHT;  // A has k contiguous in memory
+  constexpr bool B_KC = OP == OP_FWD;
+  constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA tiles per wavefront (2x2 wavefronts per workgroup)
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  constexpr int LA = BM / 32, LB = BN / 32;   // LDS-direct loads per thread per tile and operand
+  constexpr int LPT = LA + LB;
+  extern __shared__ __align__(16) unsigned short lds[];
+  lds_byte* const ldsb = (lds_byte*)lds;  // LDS-direct loads take an LDS-address-space pointer
+  const unsigned lds_base = (unsigned)(uintptr_t)JZ_LDS_PTR(lds);
+
+  const ConvGeom& g = a.g;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  unsigned L = xcd_remap(blockIdx.x, gridDim.x);
+  const int tiles_mn = a.tiles_m * a.tiles_n;
+  const int split = (int)(L / (unsigned)tiles_mn);
+  L -= (unsigned)split * (unsigned)tiles_mn;
+  const int m0 = (int)(L / (unsigned)a.tiles_n) * BM;
+  const int n0 = (int)(L % (unsigned)a.tiles_n) * BN;
+  const int kt_begin = split * a.kt_per_split;
+  const int kt_end = (kt_begin + a.kt_per_split < a.nkt) ? kt_begin + a.kt_per_split : a.nkt;
+  const int nk = kt_end - kt_begin;
+
+  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, (int)a.bytesA, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)a.B, 0, (int)a.bytesB, 0x00020000);
+  constexpr unsigned OOB = 0xffffffffu;
+
+  // ---- loader geometry ---------------------------------------------------------------------
+  // KC tile: load ii of wave w covers rows (4 ii + w) * 8 + lane / 8; the lane's LDS slot is chunk position lane % 8,
+  // so it fetches global chunk (lane % 8) ^ (row & 7) = (lane % 8) ^ (lane / 8).
+  const int kc_row = lane >> 3, kc_chunk = (lane & 7) ^ (lane >> 3);
+  // MC tile with ROWS mn: CPR = ROWS / 8 chunks per k-row, 64 / CPR k-rows per load
+  auto mc_k = [&](int rows, int ii) { int cpr = rows / 8; return (4 * ii + wave) * (64 / cpr) + lane / cpr; };
+  auto mc_chunk = [&](int rows, int k) {
+    int cpr = rows / 8;
+    int swz = cpr == 16 ? 2 * (k & 7) : 2 * (k & 3);
+    return (lane % cpr) ^ swz;
+  };
+
+  // per-thread gather state
+  unsigned sa0[LA];
+  int sa1[LA], sa2[LA];
+  (void)sa0; (void)sa1; (void)sa2;
+  if (OP != OP_BWD_WEIGHT) {  // A rows are pixels of the (n, OH, OW) grid
+#pragma unroll
+    for (int ii = 0; ii < LA; ++ii) {
+      int m = m0 + (4 * ii + wave) * 8 + kc_row;
+      if (m < a.M) {
+        unsigned n = fd_div((unsigned)m, g.d_ohow);
+        unsigned rem = (unsigned)m - n * (unsigned)(g.OH * g.OW);
+        unsigned oh = fd_div(rem, g.d_ow);
+        unsigned ow = rem - oh * (unsigned)g.OW;
+        if (OP == OP_FWD) {
+          sa1[ii] = (int)oh * g.sh - g.ph;
+          sa2[ii] = (int)ow * g.sw - g.pw;
+          // byte offset of tap (0,0) plus this lane's chunk; may wrap below zero for padded rows, the tap offset
+          // brings every in-range access back (unsigned arithmetic)
+          sa0[ii] = (unsigned)((((int)n * g.IH + sa1[ii]) * g.IW + sa2[ii]) * g.IC + kc_chunk * 8) * 2u;
+        } else {
+          sa0[ii] = n * (unsigned)(g.IH * g.IW);
+          sa1[ii] = (int)oh + g.ph;
+          sa2[ii] = (int)ow + g.pw;
+        }
+      } else {
+        sa0[ii] = 0;
+        sa1[ii] = -(1 << 28);  // fails every bounds check
+        sa2[ii] = -(1 << 28);
+      }
+    }
+  }
+  // B-side state
+  unsigned sb0[LB];
+  int sb1 = 0, sb2 = 0, sbc = 0;
+  (void)sb0; (void)sb1; (void)sb2; (void)sbc;
+  if (OP == OP_FWD) {
+#pragma unroll
+    for (int ii = 0; ii < LB; ++ii) {
+      int nn = n0 + (4 * ii + wave) * 8 + kc_row;
+      sb0[ii] = nn < a.N ? (unsigned)(nn * a.Kred + kc_chunk * 8) * 2u : OOB;
+    }
+  } else if (OP == OP_BWD_DATA) {
+    // filter w[ko][tap][c]: k-row = ko (within the tap), chunk = 8 consecutive c
+#pragma unroll
+    for (int ii = 0; ii < LB; ++ii) {
+      int k = mc_k(BN, ii);
+      int nn = n0 + mc_chunk(BN, k) * 8;
+      sb0[ii] = nn < a.N ? (unsigned)((k * g.R * g.S) * a.N + nn) * 2u : OOB;  // + (c0 * R * S + tap) * N * 2 per tile
+    }
+  } else {
+    // x gathered: this lane's 8 columns (tap, c..c+7) are the same for every load (k & 7 does not depend on ii)
+    int nn = n0 + mc_chunk(BN, mc_k(BN, 0)) * 8;
+    if (nn < a.N) {
+      unsigned tap = fd_div((unsigned)nn, g.d_ic);
+      unsigned r = fd_div(tap, g.d_s);
+      sbc = nn - (int)tap * g.IC;
+      sb1 = (int)r - g.ph;
+      sb2 = (int)(tap - r * g.S) - g.pw;
+    } else {
+      sb1 = -(1 << 28);
+      sb2 = -(1 << 28);
+    }
+  }
+  unsigned sam = 0;  // BWD_WEIGHT A: dy[(n,p,q)][k_out], chunk = 8 consecutive k_out
+  if (OP == OP_BWD_WEIGHT) {
+    int mm = m0 + mc_chunk(BM, mc_k(BM, 0)) * 8;
+    sam = mm < a.M ? (unsigned)mm * 2u : OOB;
+  }
+
+  // request k tile kt into ring stage st
+  auto issue = [&](int kt, int st) {
+    const int k0 = kt * BK;
+    lds_byte* sA = ldsb + st * STAGE;
+    lds_byte* sB = sA + A_BYTES;
+    if (OP != OP_BWD_WEIGHT) {
+      const unsigned tap = fd_div((unsigned)k0, g.d_ic);  // the whole tile lies inside one tap (IC % 64 == 0)
+      const int c0 = k0 - (int)tap * g.IC;
+      const int r = (int)fd_div(tap, g.d_s);
+      const int s = (int)tap - r * g.S;
+      const unsigned tapoff = (unsigned)((r * g.IW + s) * g.IC + c0) * 2u;
+#pragma unroll
+      for (int ii = 0; ii < LA; ++ii) {
+        bool ok;
+        unsigned off;
+        if (OP == OP_FWD) {
+          int ih = sa1[ii] + r, iw = sa2[ii] + s;
+          ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+          off = sa0[ii] + tapoff;
+        } else {
+          int th = sa1[ii] - r, tw = sa2[ii] - s;
+          int ih = th, iw = tw;
+          ok = th >= 0 && tw >= 0;
+          if (g.sh != 1 || g.sw != 1) {
+            ih = (int)fd_div((unsigned)(th < 0 ? 0 : th), g.d_sh);
+            iw = (int)fd_div((unsigned)(tw < 0 ? 0 : tw), g.d_sw);
+            ok = ok && ih * g.sh == th && iw * g.sw == tw;
+          }
+          ok = ok && ih < g.IH && iw < g.IW;
+          off = ((sa0[ii] + (unsigned)(ih * g.IW + iw)) * (unsigned)g.IC + (unsigned)(c0 + kc_chunk * 8)) * 2u;
+        }
+        jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? off : OOB);
+      }
+      if (OP == OP_FWD) {
+#pragma unroll
+        for (int ii = 0; ii < LB; ++ii)
+          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + (unsigned)k0 * 2u);
+      } else {
+        const unsigned tileoff = (unsigned)((c0 * g.R * g.S + (int)tap) * a.N) * 2u;
+#pragma unroll
+        for (int ii = 0; ii < LB; ++ii)
+          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + tileoff);
+      }
+    } else {
+#pragma unroll
+      for (int ii = 0; ii < LA; ++ii) {  // dy rows j = k0 + k
+        int j = k0 + mc_k(BM, ii);
+        unsigned off = (sam != OOB && j < a.Kred) ? sam + (unsigned)(j * a.M) * 2u : OOB;
+        jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, off);
+      }
+#pragma unroll
+      for (int ii = 0; ii < LB; ++ii) {  // x at this lane's tap for output pixel j
+        int j = k0 + mc_k(BN, ii);
+        unsigned n = fd_div((unsigned)j, g.d_ohow);
+        unsigned rem = (unsigned)j - n * (unsigned)(g.OH * g.OW);
+        int p = (int)fd_div(rem, g.d_ow);
+        int q = (int)rem - p * g.OW;
+        int ih = p * g.sh + sb1, iw = q * g.sw + sb2;
+        bool ok = j < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+        unsigned off = (unsigned)((((int)n * g.IH + ih) * g.IW + iw) * g.IC + sbc) * 2u;
+        jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? off : OOB);
+      }
+    }
+  };
+
+  // ---- MFMA operand read addresses (byte offsets inside a stage) --------------------------------
+  // KC: row = base + 32 t + lane % 32, chunk (2 ks + lane / 32) at position chunk ^ (row & 7); one address per ks,
+  //     the 32-row sub-tiles t are 4096 bytes apart (immediate offset).
+  // MC: 16-lane group gi = lane / 16 handles mn half gi % 2 and k block gi / 2 of the 32x16 operand; lane 4 j + c4
+  //     of the group addresses k-row j, the 8-byte piece c4 of those 16 mn.  One address per (sub-tile t, k half),
+  //     ks advances by 16 k-rows (immediate offset).
+  unsigned adA[4], adB[4];
+  {
+    const int r31 = lane & 31, hi = lane >> 5;
+    const int gi = lane >> 4, j = (lane >> 2) & 3, c4 = lane & 3;
+    if (A_KC) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        adA[ks] = (unsigned)((wm * (BM / 2) + r31) * 128 + (((2 * ks + hi) ^ (r31 & 7)) * 16));
+    } else {
+      constexpr int CPR = BM / 8;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          int k = 8 * (gi >> 1) + 4 * hf + j;
+          int c = (wm * (BM / 2) + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
+          int swz = CPR == 16 ? 2 * (k & 7) : 2 * (k & 3);
+          adA[t * 2 + hf] = (unsigned)(k * (BM * 2) + ((c ^ swz) * 16) + (c4 & 1) * 8);
+        }
+    }
+    if (B_KC) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        adB[ks] = (unsigned)(A_BYTES + (wn * (BN / 2) + r31) * 128 + (((2 * ks + hi) ^ (r31 & 7)) * 16));
+    } else {
+      constexpr int CPR = BN / 8;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          int k = 8 * (gi >> 1) + 4 * hf + j;
+          int c = (wn * (BN / 2) + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
+          int swz = CPR == 16 ? 2 * (k & 7) : 2 * (k & 3);
+          adB[t * 2 + hf] = (unsigned)(A_BYTES + k * (BN * 2) + ((c ^ swz) * 16) + (c4 & 1) * 8);
+        }
+    }
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // read the operands of k step KS of the stage at byte address sb
+  auto read_frags = [&](unsigned sb, auto ks_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
+    constexpr int KS = decltype(ks_tag)::value;
+    if (A_KC) {
+      fa[0] = lds_read_b128<0>(sb + adA[KS]);
+      if (TM > 1) fa[TM - 1] = lds_read_b128<4096>(sb + adA[KS]);
+    } else {
+#pragma unroll
+      for (int t = 0; t < TM; ++t) {
+        half4v lo = lds_read_tr16_b64<KS * 16 * BM * 2>(sb + adA[t * 2]);
+        half4v hi = lds_read_tr16_b64<KS * 16 * BM * 2>(sb + adA[t * 2 + 1]);
+        fa[t] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    }
+    if (B_KC) {
+      fb[0] = lds_read_b128<0>(sb + adB[KS]);
+      if (TN > 1) fb[TN - 1] = lds_read_b128<4096>(sb + adB[KS]);
+    } else {
+#pragma unroll
+      for (int t = 0; t < TN; ++t) {
+        half4v lo = lds_read_tr16_b64<KS * 16 * BN * 2>(sb + adB[t * 2]);
+        half4v hi = lds_read_tr16_b64<KS * 16 * BN * 2>(sb + adB[t * 2 + 1]);
+        fb[t] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    }
+  };
+  auto mma = [&](half8 (&fa)[TM], half8 (&fb)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        // n operand in the first slot: each lane then owns 4 consecutive n for one m (row = lane % 32)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  };
+  auto settle = [&](auto keep_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
+    constexpr int KEEP = decltype(keep_tag)::value;
+    if constexpr (TM == 2 && TN == 2) lds_settle<KEEP>(fa[0], fa[1], fb[0], fb[1]);
+    else if constexpr (TM == 2) lds_settle<KEEP>(fa[0], fa[1], fb[0]);
+    else if constexpr (TN == 2) lds_settle<KEEP>(fa[0], fb[0], fb[1]);
+    else lds_settle<KEEP>(fa[0], fb[0]);
+  };
+  constexpr int READS = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);  // LDS reads per k step
+  static_assert(READS <= 15, "lgkmcnt is a 4-bit counter");
+
+  auto compute = [&](int st) {
+    const unsigned sb = lds_base + (unsigned)(st * STAGE);
+    half8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    read_frags(sb, std::integral_constant<int, 0>{}, fa0, fb0);
+    read_frags(sb, std::integral_constant<int, 1>{}, fa1, fb1);
+    settle(std::integral_constant<int, READS>{}, fa0, fb0);
+    mma(fa0, fb0);
+    read_frags(sb, std::integral_constant<int, 2>{}, fa0, fb0);
+    settle(std::integral_constant<int, READS>{}, fa1, fb1);
+    mma(fa1, fb1);
+    read_frags(sb, std::integral_constant<int, 3>{}, fa1, fb1);
+    settle(std::integral_constant<int, READS>{}, fa0, fb0);
+    mma(fa0, fb0);
+    settle(std::integral_constant<int, 0>{}, fa1, fb1);
+    mma(fa1, fb1);
+  };
+
+  // ---- the ring ---------------------------------------------------------------------------------
+#pragma unroll
+  for (int s = 0; s < NST - 1; ++s)
+    if (s < nk) issue(kt_begin + s, s);
+  for (int i = 0; i < nk; ++i) {
+    // tile i must have landed; up to NST-2 younger tiles may still be in flight
+    const int younger = nk - 1 - i;
+    if (younger >= NST - 2) wait_vmcnt<(NST - 2) * LPT>();
+    else if (NST > 3 && younger == 1) wait_vmcnt<LPT>();
+    else wait_vmcnt<0>();
+    // Bare barrier, no fence: a fenced barrier makes the compiler drain every LDS-direct load first (vmcnt(0)).  The
+    // ordering that matters is spelled out by hand: each wavefront has waited for its own share of tile i above and
+    // for its LDS reads of tile i-1 (lgkmcnt(0) before its last MFMAs) before it arrives here.
+    __builtin_amdgcn_s_barrier();
+    if (i + NST - 1 < nk) issue(kt_begin + i + NST - 1, (i + NST - 1) % NST);
+    compute(i % NST);
+  }
+  __syncthreads();  // the epilogue reuses the ring as its staging tile
+
+  igemm_epilogue<BM, BN>(a, acc, lds, m0, n0, split, tid, lane, wm, wn);
+}
