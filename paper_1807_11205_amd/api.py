@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libjz.so")
+LIB_PATH = os.environ.get("JZ_LIB_PATH", os.path.join(_PKG, "libjz.so"))
 
 JZ_OK = 0
 JZ_ERR_NULL, JZ_ERR_SHAPE, JZ_ERR_UNSUPPORTED, JZ_ERR_WORKSPACE = -1, -2, -3, -4

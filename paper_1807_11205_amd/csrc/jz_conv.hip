@@ -460,10 +460,29 @@ __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ p
 // ---------------------------------------------------------------------------------------------
 // host side: plan (tile shape, fast/generic, split-K) and launch
 // ---------------------------------------------------------------------------------------------
+bool use_register_path() {  // debugging aid: JZ_IGEMM_PATH=reg selects the register-staged vector kernels
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("JZ_IGEMM_PATH");
+    v = (e && e[0] == 'r') ? 1 : 0;
+  }
+  return v == 1;
+}
+
+int igemm_bk_override() {  // debugging aid: JZ_IGEMM_BK=64
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("JZ_IGEMM_BK");
+    v = e ? atoi(e) : 0;
+  }
+  return v;
+}
+
 struct Plan {
   int op = 0;
   bool fast = false;
   int BM = 128, BN = 128;
+  int bk = BK;  // k tile depth of the kernel that will run
   GemmArgs args{};
   size_t ws_bytes = 0;
   size_t bytesA = 0, bytesB = 0, bytesD = 0;  // operand sizes in bytes, for the overlap checks
@@ -490,16 +509,19 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   GemmArgs& a = pl->args;
   ConvGeom& g = a.g;
   pl->op = op;
+  // k tile depth: 32 lets two workgroups share a compute unit (64 KB ring each), which hides one workgroup's
+  // barrier and LDS-latency bubbles behind the other's MFMAs; JZ_IGEMM_BK=64 selects the deeper tile for experiments
+  int bk = (use_register_path() || igemm_bk_override() == 64) ? 64 : 32;
   g.R = d->R; g.S = d->S; g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
   if (op == JZ_FWD) {
     a.M = d->N * P * Q; a.N = d->K; a.Kred = d->R * d->S * d->C;
     g.IH = d->H; g.IW = d->W; g.IC = d->C; g.OH = P; g.OW = Q;
-    pl->fast = d->C % BK == 0;
+    pl->fast = d->C % bk == 0;
     pl->bytesA = 2 * nx; pl->bytesB = 2 * nw; pl->bytesD = 2 * ny;
   } else if (op == JZ_BWD_DATA) {
     a.M = d->N * d->H * d->W; a.N = d->C; a.Kred = d->R * d->S * d->K;
     g.IH = P; g.IW = Q; g.IC = d->K; g.OH = d->H; g.OW = d->W;
-    pl->fast = d->K % BK == 0 && d->C % 8 == 0;
+    pl->fast = d->K % bk == 0 && d->C % 8 == 0;
     pl->bytesA = 2 * ny; pl->bytesB = 2 * nw; pl->bytesD = 2 * nx;
   } else {
     a.M = d->K; a.N = d->R * d->S * d->C; a.Kred = d->N * P * Q;
@@ -518,7 +540,9 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   pl->BN = (pl->fast && a.N <= 64) ? 64 : 128;
   a.tiles_m = (a.M + pl->BM - 1) / pl->BM;
   a.tiles_n = (a.N + pl->BN - 1) / pl->BN;
-  a.nkt = (a.Kred + BK - 1) / BK;
+  if (!pl->fast) bk = BK;  // the element-wise kernel walks 64-deep tiles
+  pl->bk = bk;
+  a.nkt = (a.Kred + bk - 1) / bk;
   // split the reduction when the output alone cannot fill the 256 compute units
   const long long tiles = (long long)a.tiles_m * a.tiles_n;
   int splits = 1;
@@ -554,30 +578,21 @@ int launch_one(const GemmArgs& a, hipStream_t st) {
   return jz::launch_status();
 }
 
-template <int OP, int BM, int BN, int NST>
+template <int OP, int BM, int BN, int TBK, int NST>
 int launch_dma(const GemmArgs& a, hipStream_t st) {
-  constexpr size_t ring_bytes = (size_t)NST * (BM + BN) * 128;
+  constexpr size_t ring_bytes = (size_t)NST * (BM + BN) * 2 * TBK;
   constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(unsigned short);
   constexpr size_t smem = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, NST>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, TBK, NST>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return JZ_ERR_LAUNCH;
     attr_set = true;
   }
   unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.splits;
-  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, NST>), dim3(grid), dim3(THREADS), smem, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, TBK, NST>), dim3(grid), dim3(THREADS), smem, st, a);
   return jz::launch_status();
-}
-
-bool use_register_path() {  // debugging aid: JZ_IGEMM_PATH=reg selects the register-staged vector kernels
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("JZ_IGEMM_PATH");
-    v = (e && e[0] == 'r') ? 1 : 0;
-  }
-  return v == 1;
 }
 
 template <int OP>
@@ -585,10 +600,16 @@ int launch_op(const Plan& pl, hipStream_t st) {
   const GemmArgs& a = pl.args;
   if (!pl.fast) return launch_one<OP, false, 128, 128>(a, st);
   if (!use_register_path()) {
-    if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 4>(a, st);
-    if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 4>(a, st);
-    if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 4>(a, st);
-    return launch_dma<OP, 64, 64, 4>(a, st);
+    if (pl.bk == 64) {
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 64, 4>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 64, 4>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 64, 4>(a, st);
+      return launch_dma<OP, 64, 64, 64, 4>(a, st);
+    }
+    if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4>(a, st);
+    if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4>(a, st);
+    if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 4>(a, st);
+    return launch_dma<OP, 64, 64, 32, 4>(a, st);
   }
   if (pl.BM == 128 && pl.BN == 128) return launch_one<OP, true, 128, 128>(a, st);
   if (pl.BM == 128 && pl.BN == 64) return launch_one<OP, true, 128, 64>(a, st);

@@ -9,9 +9,9 @@
 // (BM+BN) x 128 bytes form a ring.  Each iteration: wait until the oldest stage has landed (vmcnt), one
 // workgroup barrier, request the tile NST-1 ahead into the stage that was just consumed, multiply.
 //
-// LDS layouts (one stage = A tile then B tile, both BK = 64 deep):
-//   k-contiguous operand  ("KC": x / dy gathered per pixel, the forward filter): [row][8 chunks of 16 B], row pitch
-//       128 B, chunk c of row r stored at position c ^ (r & 7); MFMA operands are plain ds_read_b128.
+// LDS layouts (one stage = A tile then B tile, both TBK = 32 or 64 deep):
+//   k-contiguous operand  ("KC": x / dy gathered per pixel, the forward filter): [row][TBK/8 chunks of 16 B], rows
+//       packed back to back, chunk c of row r stored at position c ^ swizzle(r); MFMA operands are plain ds_read_b128.
 //   mn-contiguous operand ("MC": the filter in backward-data, dy and x in backward-weight): [k][ROWS/8 chunks],
 //       stored exactly as it sits in memory, chunk c of k-row k at position c ^ swz(k); MFMA operands come from
 //       ds_read_b64_tr_b16, which hands each lane four consecutive k of one mn out of such a layout (within 16
@@ -73,16 +73,27 @@ __device__ __forceinline__ void lds_settle(half8& a, half8& b, half8& c, half8& 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 // one LDS-direct load: 64 lanes x 16 bytes from `rsrc` at per-lane byte offset `voff` to LDS at dst + lane * 16
 __device__ __forceinline__ void jz_dma16(__amdgpu_buffer_rsrc_t rsrc, lds_byte* dst, unsigned voff) {
+#ifdef JZ_EXPERIMENT_NO_LOADS  // timing experiment only: every load is out of range (returns zeros, touches no memory)
+  voff = 0xffffffffu;
+#endif
+#ifdef JZ_EXPERIMENT_NO_ISSUE  // timing experiment only: no load instructions at all
+  return;
+#endif
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, (int)voff, 0, 0, 0);
 }
 
-template <int OP, int BM, int BN, int NST>
+template <int OP, int BM, int BN, int TBK, int NST>
 __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
+  static_assert(TBK == 32 || TBK == 64, "k tile depth");
   constexpr bool A_KC = OP != OP_BWD_WEIGHT;  // A has k contiguous in memory
   constexpr bool B_KC = OP == OP_FWD;
   constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA tiles per wavefront (2x2 wavefronts per workgroup)
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  constexpr int LA = BM / 32, LB = BN / 32;   // LDS-direct loads per thread per tile and operand
+  constexpr int NKS = TBK / 16;               // MFMA k steps per tile
+  constexpr int RB = 2 * TBK;                 // bytes per row of a KC tile
+  constexpr int CR = TBK / 8;                 // 16-byte chunks per row of a KC tile
+  constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
+  constexpr int LA = BM * CR / 256, LB = BN * CR / 256;  // LDS-direct loads per thread per tile and operand
+  static_assert(LA >= 1 && LB >= 1, "tile too small for the loader");
   constexpr int LPT = LA + LB;
   extern __shared__ __align__(16) unsigned short lds[];
   lds_byte* const ldsb = (lds_byte*)lds;  // LDS-direct loads take an LDS-address-space pointer
@@ -107,9 +118,13 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   constexpr unsigned OOB = 0xffffffffu;
 
   // ---- loader geometry ---------------------------------------------------------------------
-  // KC tile: load ii of wave w covers rows (4 ii + w) * 8 + lane / 8; the lane's LDS slot is chunk position lane % 8,
-  // so it fetches global chunk (lane % 8) ^ (row & 7) = (lane % 8) ^ (lane / 8).
-  const int kc_row = lane >> 3, kc_chunk = (lane & 7) ^ (lane >> 3);
+  // KC tile: one load covers 64 / CR rows; load ii of wave w covers rows (4 ii + w) * (64 / CR) + lane / CR and the
+  // lane's LDS slot is chunk position lane % CR, so it fetches global chunk (lane % CR) ^ swizzle(row).  The swizzle
+  // ((row >> 1) & 7 for 128-byte rows, (row >> 2) & 3 for 64-byte rows) is the same for every ii and sends any 16
+  // consecutive rows' copies of one chunk to 16 different 16-byte bank groups.
+  constexpr int KC_RPI = 64 / CR;
+  const int kc_row = wave * KC_RPI + lane / CR;  // + 4 * KC_RPI * ii
+  const int kc_chunk = (lane % CR) ^ (TBK == 64 ? ((kc_row >> 1) & 7) : ((kc_row >> 2) & 3));
   // MC tile with ROWS mn: CPR = ROWS / 8 chunks per k-row, 64 / CPR k-rows per load
   auto mc_k = [&](int rows, int ii) { int cpr = rows / 8; return (4 * ii + wave) * (64 / cpr) + lane / cpr; };
   auto mc_chunk = [&](int rows, int k) {
@@ -125,7 +140,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   if (OP != OP_BWD_WEIGHT) {  // A rows are pixels of the (n, OH, OW) grid
 #pragma unroll
     for (int ii = 0; ii < LA; ++ii) {
-      int m = m0 + (4 * ii + wave) * 8 + kc_row;
+      int m = m0 + 4 * KC_RPI * ii + kc_row;
       if (m < a.M) {
         unsigned n = fd_div((unsigned)m, g.d_ohow);
         unsigned rem = (unsigned)m - n * (unsigned)(g.OH * g.OW);
@@ -156,7 +171,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   if (OP == OP_FWD) {
 #pragma unroll
     for (int ii = 0; ii < LB; ++ii) {
-      int nn = n0 + (4 * ii + wave) * 8 + kc_row;
+      int nn = n0 + 4 * KC_RPI * ii + kc_row;
       sb0[ii] = nn < a.N ? (unsigned)(nn * a.Kred + kc_chunk * 8) * 2u : OOB;
     }
   } else if (OP == OP_BWD_DATA) {
@@ -187,74 +202,93 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     sam = mm < a.M ? (unsigned)mm * 2u : OOB;
   }
 
-  // request k tile kt into ring stage st
-  auto issue = [&](int kt, int st) {
-    const int k0 = kt * BK;
-    lds_byte* sA = ldsb + st * STAGE;
-    lds_byte* sB = sA + A_BYTES;
-    if (OP != OP_BWD_WEIGHT) {
-      const unsigned tap = fd_div((unsigned)k0, g.d_ic);  // the whole tile lies inside one tap (IC % 64 == 0)
-      const int c0 = k0 - (int)tap * g.IC;
-      const int r = (int)fd_div(tap, g.d_s);
-      const int s = (int)tap - r * g.S;
-      const unsigned tapoff = (unsigned)((r * g.IW + s) * g.IC + c0) * 2u;
-#pragma unroll
-      for (int ii = 0; ii < LA; ++ii) {
-        bool ok;
-        unsigned off;
-        if (OP == OP_FWD) {
-          int ih = sa1[ii] + r, iw = sa2[ii] + s;
-          ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
-          off = sa0[ii] + tapoff;
-        } else {
-          int th = sa1[ii] - r, tw = sa2[ii] - s;
-          int ih = th, iw = tw;
-          ok = th >= 0 && tw >= 0;
-          if (g.sh != 1 || g.sw != 1) {
-            ih = (int)fd_div((unsigned)(th < 0 ? 0 : th), g.d_sh);
-            iw = (int)fd_div((unsigned)(tw < 0 ? 0 : tw), g.d_sw);
-            ok = ok && ih * g.sh == th && iw * g.sw == tw;
-          }
-          ok = ok && ih < g.IH && iw < g.IW;
-          off = ((sa0[ii] + (unsigned)(ih * g.IW + iw)) * (unsigned)g.IC + (unsigned)(c0 + kc_chunk * 8)) * 2u;
+  // Requesting k tile kt into ring stage st = LPT loads per thread (LA for A, then LB for B).  They are issued one
+  // at a time, in between the MFMA groups of the tile being multiplied, so that their address arithmetic runs in
+  // the shadow of the matrix pipe instead of in front of it.
+  struct TileCtx {
+    int k0, c0, r, s;
+    unsigned tap, tapoff, tileoff;
+  };
+  auto tile_ctx = [&](int kt) {
+    TileCtx c;
+    c.k0 = kt * TBK;
+    c.tap = 0; c.c0 = 0; c.r = 0; c.s = 0; c.tapoff = 0; c.tileoff = 0;
+    if (OP != OP_BWD_WEIGHT) {  // the whole tile lies inside one filter tap (IC % TBK == 0): wave-uniform values
+      c.tap = fd_div((unsigned)c.k0, g.d_ic);
+      c.c0 = c.k0 - (int)c.tap * g.IC;
+      c.r = (int)fd_div(c.tap, g.d_s);
+      c.s = (int)c.tap - c.r * g.S;
+      c.tapoff = (unsigned)((c.r * g.IW + c.s) * g.IC + c.c0) * 2u;
+      c.tileoff = (unsigned)((c.c0 * g.R * g.S + (int)c.tap) * a.N) * 2u;
+    }
+    return c;
+  };
+  auto issue_load = [&](const TileCtx& c, int st, auto l_tag) {
+    constexpr int Lidx = decltype(l_tag)::value;
+    if constexpr (Lidx < LPT) {
+      lds_byte* sA = ldsb + st * STAGE;
+      lds_byte* sB = sA + A_BYTES;
+      if constexpr (Lidx < LA) {
+        constexpr int ii = Lidx;
+        if constexpr (OP == OP_FWD) {
+          int ih = sa1[ii] + c.r, iw = sa2[ii] + c.s;
+          bool ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+          jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? sa0[ii] + c.tapoff : OOB);
+        } else if constexpr (OP == OP_BWD_DATA) {
+          // input pixel (h,w) receives from output pixel ((h + pad - r) / stride, ...) when the division is exact
+          int th = sa1[ii] - c.r, tw = sa2[ii] - c.s;
+          int ih = (int)fd_div((unsigned)(th < 0 ? 0 : th), g.d_sh);
+          int iw = (int)fd_div((unsigned)(tw < 0 ? 0 : tw), g.d_sw);
+          bool ok = ih * g.sh == th && iw * g.sw == tw && ih < g.IH && iw < g.IW;  // false for negative th / tw too
+          unsigned off = ((sa0[ii] + (unsigned)(ih * g.IW + iw)) * (unsigned)g.IC + (unsigned)(c.c0 + kc_chunk * 8)) * 2u;
+          jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? off : OOB);
+        } else {  // dy rows j = k0 + k
+          int j = c.k0 + mc_k(BM, ii);
+          unsigned off = (sam != OOB && j < a.Kred) ? sam + (unsigned)(j * a.M) * 2u : OOB;
+          jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, off);
         }
-        jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? off : OOB);
-      }
-      if (OP == OP_FWD) {
-#pragma unroll
-        for (int ii = 0; ii < LB; ++ii)
-          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + (unsigned)k0 * 2u);
       } else {
-        const unsigned tileoff = (unsigned)((c0 * g.R * g.S + (int)tap) * a.N) * 2u;
-#pragma unroll
-        for (int ii = 0; ii < LB; ++ii)
-          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + tileoff);
+        constexpr int ii = Lidx - LA;
+        if constexpr (OP == OP_FWD) {
+          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + (unsigned)c.k0 * 2u);
+        } else if constexpr (OP == OP_BWD_DATA) {
+          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + c.tileoff);
+        } else {  // x at this lane's tap for output pixel j
+          int j = c.k0 + mc_k(BN, ii);
+          unsigned n = fd_div((unsigned)j, g.d_ohow);
+          unsigned rem = (unsigned)j - n * (unsigned)(g.OH * g.OW);
+          int p = (int)fd_div(rem, g.d_ow);
+          int q = (int)rem - p * g.OW;
+          int ih = p * g.sh + sb1, iw = q * g.sw + sb2;
+          bool ok = j < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+          unsigned off = (unsigned)((((int)n * g.IH + ih) * g.IW + iw) * g.IC + sbc) * 2u;
+          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? off : OOB);
+        }
       }
-    } else {
-#pragma unroll
-      for (int ii = 0; ii < LA; ++ii) {  // dy rows j = k0 + k
-        int j = k0 + mc_k(BM, ii);
-        unsigned off = (sam != OOB && j < a.Kred) ? sam + (unsigned)(j * a.M) * 2u : OOB;
-        jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, off);
-      }
-#pragma unroll
-      for (int ii = 0; ii < LB; ++ii) {  // x at this lane's tap for output pixel j
-        int j = k0 + mc_k(BN, ii);
-        unsigned n = fd_div((unsigned)j, g.d_ohow);
-        unsigned rem = (unsigned)j - n * (unsigned)(g.OH * g.OW);
-        int p = (int)fd_div(rem, g.d_ow);
-        int q = (int)rem - p * g.OW;
-        int ih = p * g.sh + sb1, iw = q * g.sw + sb2;
-        bool ok = j < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
-        unsigned off = (unsigned)((((int)n * g.IH + ih) * g.IW + iw) * g.IC + sbc) * 2u;
-        jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? off : OOB);
-      }
+    }
+  };
+  // loads PART, PART + NKS, ... of the tile (PART in 0..NKS-1): one share per MFMA group
+  auto issue_part = [&](const TileCtx& c, int st, auto part_tag) {
+    constexpr int PART = decltype(part_tag)::value;
+    issue_load(c, st, std::integral_constant<int, PART>{});
+    issue_load(c, st, std::integral_constant<int, PART + NKS>{});
+    issue_load(c, st, std::integral_constant<int, PART + 2 * NKS>{});
+    issue_load(c, st, std::integral_constant<int, PART + 3 * NKS>{});
+  };
+  static_assert(LPT <= 4 * NKS, "issue_part covers at most 4 loads per MFMA group");
+  auto issue = [&](int kt, int st) {
+    TileCtx c = tile_ctx(kt);
+    issue_part(c, st, std::integral_constant<int, 0>{});
+    issue_part(c, st, std::integral_constant<int, 1>{});
+    if constexpr (NKS == 4) {
+      issue_part(c, st, std::integral_constant<int, 2>{});
+      issue_part(c, st, std::integral_constant<int, 3>{});
     }
   };
 
   // ---- MFMA operand read addresses (byte offsets inside a stage) --------------------------------
-  // KC: row = base + 32 t + lane % 32, chunk (2 ks + lane / 32) at position chunk ^ (row & 7); one address per ks,
-  //     the 32-row sub-tiles t are 4096 bytes apart (immediate offset).
+  // KC: row = base + 32 t + lane % 32, chunk (2 ks + lane / 32) at position chunk ^ swizzle(row); one address per ks,
+  //     the 32-row sub-tiles t are 32 * RB bytes apart and share the swizzle (immediate offset).
   // MC: 16-lane group gi = lane / 16 handles mn half gi % 2 and k block gi / 2 of the 32x16 operand; lane 4 j + c4
   //     of the group addresses k-row j, the 8-byte piece c4 of those 16 mn.  One address per (sub-tile t, k half),
   //     ks advances by 16 k-rows (immediate offset).
@@ -262,10 +296,11 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   {
     const int r31 = lane & 31, hi = lane >> 5;
     const int gi = lane >> 4, j = (lane >> 2) & 3, c4 = lane & 3;
+    const int kc_swz = TBK == 64 ? ((r31 >> 1) & 7) : ((r31 >> 2) & 3);
     if (A_KC) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        adA[ks] = (unsigned)((wm * (BM / 2) + r31) * 128 + (((2 * ks + hi) ^ (r31 & 7)) * 16));
+      for (int ks = 0; ks < NKS; ++ks)
+        adA[ks] = (unsigned)((wm * (BM / 2) + r31) * RB + (((2 * ks + hi) ^ kc_swz) * 16));
     } else {
       constexpr int CPR = BM / 8;
 #pragma unroll
@@ -280,8 +315,8 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     }
     if (B_KC) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        adB[ks] = (unsigned)(A_BYTES + (wn * (BN / 2) + r31) * 128 + (((2 * ks + hi) ^ (r31 & 7)) * 16));
+      for (int ks = 0; ks < NKS; ++ks)
+        adB[ks] = (unsigned)(A_BYTES + (wn * (BN / 2) + r31) * RB + (((2 * ks + hi) ^ kc_swz) * 16));
     } else {
       constexpr int CPR = BN / 8;
 #pragma unroll
@@ -307,9 +342,14 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   // read the operands of k step KS of the stage at byte address sb
   auto read_frags = [&](unsigned sb, auto ks_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
     constexpr int KS = decltype(ks_tag)::value;
+#ifdef JZ_EXPERIMENT_NO_LDSREAD  // timing experiment only
+    for (int t = 0; t < TM; ++t) for (int e = 0; e < 8; ++e) fa[t][e] = (_Float16)(float)(lane + KS);
+    for (int t = 0; t < TN; ++t) for (int e = 0; e < 8; ++e) fb[t][e] = (_Float16)(float)(lane - KS);
+    return;
+#endif
     if (A_KC) {
       fa[0] = lds_read_b128<0>(sb + adA[KS]);
-      if (TM > 1) fa[TM - 1] = lds_read_b128<4096>(sb + adA[KS]);
+      if (TM > 1) fa[TM - 1] = lds_read_b128<32 * RB>(sb + adA[KS]);
     } else {
 #pragma unroll
       for (int t = 0; t < TM; ++t) {
@@ -320,7 +360,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     }
     if (B_KC) {
       fb[0] = lds_read_b128<0>(sb + adB[KS]);
-      if (TN > 1) fb[TN - 1] = lds_read_b128<4096>(sb + adB[KS]);
+      if (TN > 1) fb[TN - 1] = lds_read_b128<32 * RB>(sb + adB[KS]);
     } else {
 #pragma unroll
       for (int t = 0; t < TN; ++t) {
@@ -331,6 +371,10 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     }
   };
   auto mma = [&](half8 (&fa)[TM], half8 (&fb)[TN]) {
+#ifdef JZ_EXPERIMENT_NO_MFMA  // timing experiment only: one MFMA per k step instead of TM*TN
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[TN - 1], fa[TM - 1], acc[0][0], 0, 0, 0);
+    return;
+#endif
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -348,39 +392,57 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   constexpr int READS = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);  // LDS reads per k step
   static_assert(READS <= 15, "lgkmcnt is a 4-bit counter");
 
-  auto compute = [&](int st) {
+  // multiply the tile in stage st; when ISSUE, request tile `c` into stage ist between the MFMA groups
+  auto compute = [&](int st, auto issue_tag, const TileCtx& c, int ist) {
+    constexpr bool ISSUE = decltype(issue_tag)::value;
     const unsigned sb = lds_base + (unsigned)(st * STAGE);
     half8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     read_frags(sb, std::integral_constant<int, 0>{}, fa0, fb0);
     read_frags(sb, std::integral_constant<int, 1>{}, fa1, fb1);
+    if (ISSUE) issue_part(c, ist, std::integral_constant<int, 0>{});
     settle(std::integral_constant<int, READS>{}, fa0, fb0);
     mma(fa0, fb0);
-    read_frags(sb, std::integral_constant<int, 2>{}, fa0, fb0);
-    settle(std::integral_constant<int, READS>{}, fa1, fb1);
-    mma(fa1, fb1);
-    read_frags(sb, std::integral_constant<int, 3>{}, fa1, fb1);
-    settle(std::integral_constant<int, READS>{}, fa0, fb0);
-    mma(fa0, fb0);
+    if constexpr (NKS == 4) {
+      read_frags(sb, std::integral_constant<int, 2>{}, fa0, fb0);
+      if (ISSUE) issue_part(c, ist, std::integral_constant<int, 1>{});
+      settle(std::integral_constant<int, READS>{}, fa1, fb1);
+      mma(fa1, fb1);
+      read_frags(sb, std::integral_constant<int, NKS - 1>{}, fa1, fb1);
+      if (ISSUE) issue_part(c, ist, std::integral_constant<int, 2>{});
+      settle(std::integral_constant<int, READS>{}, fa0, fb0);
+      mma(fa0, fb0);
+      if (ISSUE) issue_part(c, ist, std::integral_constant<int, NKS - 1>{});
+    } else {
+      if (ISSUE) issue_part(c, ist, std::integral_constant<int, 1>{});
+    }
     settle(std::integral_constant<int, 0>{}, fa1, fb1);
     mma(fa1, fb1);
   };
 
   // ---- the ring ---------------------------------------------------------------------------------
+  // Barriers are bare (no fence): a fenced barrier makes the compiler drain every LDS-direct load first (vmcnt(0)).
+  // The ordering that matters is spelled out by hand: before a wavefront arrives at the barrier of iteration i it has
+  // waited for its own share of tile i (vmcnt) and for its LDS reads of tile i-1 (lgkmcnt(0) before its last MFMAs).
 #pragma unroll
   for (int s = 0; s < NST - 1; ++s)
     if (s < nk) issue(kt_begin + s, s);
-  for (int i = 0; i < nk; ++i) {
-    // tile i must have landed; up to NST-2 younger tiles may still be in flight
+  int i = 0;
+  for (; i + NST - 1 < nk; ++i) {  // steady state, branch-free body: NST-2 younger tiles stay in flight
+    wait_vmcnt<(NST - 2) * LPT>();
+#ifndef JZ_EXPERIMENT_NO_BARRIER
+    __builtin_amdgcn_s_barrier();
+#endif
+    TileCtx c = tile_ctx(kt_begin + i + NST - 1);
+    compute(i % NST, std::true_type{}, c, (i + NST - 1) % NST);
+  }
+  for (; i < nk; ++i) {  // drain
     const int younger = nk - 1 - i;
     if (younger >= NST - 2) wait_vmcnt<(NST - 2) * LPT>();
     else if (NST > 3 && younger == 1) wait_vmcnt<LPT>();
     else wait_vmcnt<0>();
-    // Bare barrier, no fence: a fenced barrier makes the compiler drain every LDS-direct load first (vmcnt(0)).  The
-    // ordering that matters is spelled out by hand: each wavefront has waited for its own share of tile i above and
-    // for its LDS reads of tile i-1 (lgkmcnt(0) before its last MFMAs) before it arrives here.
     __builtin_amdgcn_s_barrier();
-    if (i + NST - 1 < nk) issue(kt_begin + i + NST - 1, (i + NST - 1) % NST);
-    compute(i % NST);
+    TileCtx c{};
+    compute(i % NST, std::false_type{}, c, 0);
   }
   __syncthreads();  // the epilogue reuses the ring as its staging tile
 
