@@ -25,6 +25,7 @@ using namespace jz;
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int THREADS = 256;
 constexpr int BK = 64;
@@ -430,6 +431,56 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a) {
 
 #include "jz_igemm_dma.h"
 
+// ---------------------------------------------------------------------------------------------
+// small-channel layers (C <= 4: the 3-channel stems of ResNet-50 and AlexNet)
+// ---------------------------------------------------------------------------------------------
+// With 3 channels a filter tap is 6 bytes: nothing to vectorise.  But in NHWC the S taps of one filter row are
+// adjacent in memory, so the input is copied once into a zero-padded 4-channel image xp[N][H+2ph][Wp][4]; one filter
+// row of an output pixel is then ONE contiguous, 16-byte aligned run of 4*S halves starting at pixel q*stride_w
+// (needs an even stride_w), and the layer becomes an ordinary implicit GEMM whose "taps" are the R filter rows and
+// whose "channels" are that run, rounded up to the k tile (32 or 64).  The filter is repacked to match
+// (w'[k][r][4 s + c], zeros elsewhere); for backward-weight the GEMM produces dw' in that layout and the real
+// entries are copied out.
+
+__global__ __launch_bounds__(256) void pad_to_c4(const unsigned short* __restrict__ x, unsigned short* __restrict__ xp,
+                                                 int N, int H, int W, int C, int Hp, int Wp, int ph, int pw) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;  // one padded pixel per thread
+  long long total = (long long)N * Hp * Wp;
+  if (i >= total) return;
+  int wp = (int)(i % Wp);
+  long long t = i / Wp;
+  int hp = (int)(t % Hp);
+  int n = (int)(t / Hp);
+  int h = hp - ph, w = wp - pw;
+  unsigned short v[4] = {0, 0, 0, 0};
+  if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
+    const unsigned short* src = x + (((size_t)n * H + h) * W + w) * C;
+    for (int c = 0; c < C; ++c) v[c] = src[c];
+  }
+  uint2 pk = make_uint2((unsigned)v[0] | ((unsigned)v[1] << 16), (unsigned)v[2] | ((unsigned)v[3] << 16));
+  *reinterpret_cast<uint2*>(xp + i * 4) = pk;
+}
+
+// w[K][R][S][C] -> wp[K][R][KT] with wp[k][r][4 s + c] = w[k][r][s][c], zero elsewhere
+__global__ __launch_bounds__(256) void pack_filter_c4(const unsigned short* __restrict__ w, unsigned short* __restrict__ wp,
+                                                      int K, int R, int S, int C, int KT) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= K * R * KT) return;
+  int j = i % KT, kr = i / KT;
+  int s = j >> 2, c = j & 3;
+  wp[i] = (s < S && c < C) ? w[((size_t)kr * S + s) * C + c] : (unsigned short)0;
+}
+
+// dwp[K][R][KT] -> dw[K][R][S][C]
+__global__ __launch_bounds__(256) void unpack_filter_c4(const unsigned short* __restrict__ dwp, unsigned short* __restrict__ dw,
+                                                        int K, int R, int S, int C, int KT) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= K * R * S * C) return;
+  int c = i % C, t = i / C;
+  int s = t % S, kr = t / S;
+  dw[i] = dwp[(size_t)kr * KT + 4 * s + c];
+}
+
 // D16[i] = RNE16( sum_s part[s][i] ), splits added in index order (deterministic)
 __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ part, unsigned short* __restrict__ out,
                                                      long long MN, int splits) {
@@ -468,27 +519,83 @@ bool use_register_path() {  // debugging aid: JZ_IGEMM_PATH=reg selects the regi
   }
   return v == 1;
 }
-
-int igemm_bk_override() {  // debugging aid: JZ_IGEMM_BK=64
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("JZ_IGEMM_BK");
-    v = e ? atoi(e) : 0;
-  }
-  return v;
+int env_int(const char* name) {
+  const char* e = getenv(name);
+  return e ? atoi(e) : 0;
 }
+// debugging aids: JZ_IGEMM_BK=64, JZ_IGEMM_TILE=<BM*1000+BN>, JZ_IGEMM_SPLITS=<n> override the planner
+int igemm_bk_override() { static int v = env_int("JZ_IGEMM_BK"); return v; }
+int igemm_tile_override() { static int v = env_int("JZ_IGEMM_TILE"); return v; }
+int igemm_splits_override() { static int v = env_int("JZ_IGEMM_SPLITS"); return v; }
 
 struct Plan {
   int op = 0;
-  bool fast = false;
+  bool fast = false;    // vector (16-byte) operand access possible
+  bool packed = false;  // small-channel layer run on a 4-channel padded copy
   int BM = 128, BN = 128;
   int bk = BK;  // k tile depth of the kernel that will run
   GemmArgs args{};
-  size_t ws_bytes = 0;
-  size_t bytesA = 0, bytesB = 0, bytesD = 0;  // operand sizes in bytes, for the overlap checks
+  size_t ws_bytes = 0;       // total workspace
+  size_t part_offset = 0;    // where the split-K partial sums start inside it
+  size_t bytesA = 0, bytesB = 0, bytesD = 0;  // caller's operand sizes in bytes, for the overlap checks
+  // packed mode
+  int Hp = 0, Wp = 0, KT = 0;
+  size_t xp_bytes = 0, wp_bytes = 0;
 };
 
 int out_dim(int in, int pad, int f, int st) { return (in + 2 * pad - f) / st + 1; }
+size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// Pick the output tile and the split of the reduction with a small cost model (times in microseconds):
+//   GEMM part   = rounds of resident workgroups * k tiles per workgroup * time per k tile of that tile shape
+//   split part  = writing and re-reading the fp32 partial sums, plus one more launch
+// Two workgroups fit a compute unit, so 512 are resident at once.
+void choose_tiling(Plan* pl) {
+  GemmArgs& a = pl->args;
+  const int bk = pl->bk;
+  a.nkt = (a.Kred + bk - 1) / bk;
+  if (!pl->fast) {  // the element-wise kernel exists for one shape only
+    pl->BM = pl->BN = 128;
+  }
+  static const int shapes[4][2] = {{128, 128}, {128, 64}, {64, 128}, {64, 64}};
+  static const double t_tile32[4] = {0.60, 0.36, 0.36, 0.22};  // per 32-deep k tile at two workgroups per CU
+  static const int split_opts[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128};
+  double best = 1e30;
+  int bBM = 128, bBN = 128, bS = 1;
+  for (int si = 0; si < 4; ++si) {
+    int BM_ = shapes[si][0], BN_ = shapes[si][1];
+    if (!pl->fast && si != 0) break;
+    if (pl->packed && pl->op == JZ_FWD && BM_ != 128) continue;  // the masked kernels exist for BM = 128 only
+    if (igemm_tile_override() && igemm_tile_override() != BM_ * 1000 + BN_ && pl->fast) continue;
+    long long tm = (a.M + BM_ - 1) / BM_, tn = (a.N + BN_ - 1) / BN_;
+    double tt = t_tile32[si] * (bk / 32.0) * (pl->fast ? 1.0 : 8.0);
+    for (int sp : split_opts) {
+      if (sp > 1 && a.nkt / sp < 4) break;
+      if (igemm_splits_override() && sp != igemm_splits_override() && !(sp == 1 && a.nkt / igemm_splits_override() < 4)) continue;
+      long long blocks = tm * tn * sp;
+      long long rounds = (blocks + 511) / 512;
+      double kps = (double)((a.nkt + sp - 1) / sp);
+      double gemm = rounds * kps * tt * (blocks <= 256 ? 0.7 : 1.0) + 3.0;
+      double split = sp > 1 ? (2.0 * sp * (double)a.M * a.N * 4.0) / 3.0e6 + 4.0 : 0.0;
+      double t = gemm + split;
+      if (t < best) { best = t; bBM = BM_; bBN = BN_; bS = sp; }
+    }
+  }
+  pl->BM = bBM; pl->BN = bBN;
+  a.tiles_m = (a.M + bBM - 1) / bBM;
+  a.tiles_n = (a.N + bBN - 1) / bBN;
+  a.kt_per_split = (a.nkt + bS - 1) / bS;
+  a.splits = (a.nkt + a.kt_per_split - 1) / a.kt_per_split;  // drop empty splits
+}
+
+void finish_geometry(ConvGeom& g) {
+  g.d_ohow = make_fastdiv((unsigned)(g.OH * g.OW));
+  g.d_ow = make_fastdiv((unsigned)g.OW);
+  g.d_ic = make_fastdiv((unsigned)g.IC);
+  g.d_s = make_fastdiv((unsigned)g.S);
+  g.d_sh = make_fastdiv((unsigned)g.sh);
+  g.d_sw = make_fastdiv((unsigned)g.sw);
+}
 
 int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   if (!d) return JZ_ERR_NULL;
@@ -510,9 +617,10 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   ConvGeom& g = a.g;
   pl->op = op;
   // k tile depth: 32 lets two workgroups share a compute unit (64 KB ring each), which hides one workgroup's
-  // barrier and LDS-latency bubbles behind the other's MFMAs; JZ_IGEMM_BK=64 selects the deeper tile for experiments
+  // barrier and LDS-latency bubbles behind the other's MFMAs
   int bk = (use_register_path() || igemm_bk_override() == 64) ? 64 : 32;
   g.R = d->R; g.S = d->S; g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
+  g.kvalid = 0;
   if (op == JZ_FWD) {
     a.M = d->N * P * Q; a.N = d->K; a.Kred = d->R * d->S * d->C;
     g.IH = d->H; g.IW = d->W; g.IC = d->C; g.OH = P; g.OW = Q;
@@ -529,35 +637,42 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
     pl->fast = d->K % 8 == 0 && d->C % 8 == 0;
     pl->bytesA = 2 * ny; pl->bytesB = 2 * nx; pl->bytesD = 2 * nw;  // A = dy, B = x
   }
-  g.d_ohow = make_fastdiv((unsigned)(g.OH * g.OW));
-  g.d_ow = make_fastdiv((unsigned)g.OW);
-  g.d_ic = make_fastdiv((unsigned)g.IC);
-  g.d_s = make_fastdiv((unsigned)g.S);
-  g.d_sh = make_fastdiv((unsigned)g.sh);
-  g.d_sw = make_fastdiv((unsigned)g.sw);
+  g.row_pitch = g.IW * g.IC;
+  g.pix_step = g.IC;
+  g.s_step = g.IC;
 
-  pl->BM = (pl->fast && a.M <= 64) ? 64 : 128;
-  pl->BN = (pl->fast && a.N <= 64) ? 64 : 128;
-  a.tiles_m = (a.M + pl->BM - 1) / pl->BM;
-  a.tiles_n = (a.N + pl->BN - 1) / pl->BN;
+  // small-channel layers: gather from a zero-padded 4-channel copy (see pad_to_c4)
+  if (!pl->fast && !use_register_path() && op != JZ_BWD_DATA && d->C <= 4 && d->stride_w % 2 == 0 && 4 * d->S <= 64 &&
+      (op == JZ_FWD || d->K % 8 == 0)) {
+    const int KT = 4 * d->S <= 32 ? 32 : 64;
+    int Hp = d->H + 2 * d->pad_h, Wp = d->W + 2 * d->pad_w;
+    if (Wp < (Q - 1) * d->stride_w + KT / 4) Wp = (Q - 1) * d->stride_w + KT / 4;
+    Wp = (Wp + 1) & ~1;  // rows stay 16-byte aligned
+    const long long nxp = (long long)d->N * Hp * Wp * 4;
+    if (nxp <= lim) {
+      pl->packed = true;
+      pl->fast = true;
+      pl->Hp = Hp; pl->Wp = Wp; pl->KT = KT;
+      pl->xp_bytes = up256((size_t)nxp * 2);
+      pl->wp_bytes = up256((size_t)d->K * d->R * KT * 2);
+      g.IH = Hp; g.IW = Wp; g.IC = KT; g.S = 1; g.ph = 0; g.pw = 0;
+      g.row_pitch = Wp * 4; g.pix_step = 4; g.s_step = 0;
+      if (op == JZ_FWD) {
+        a.Kred = d->R * KT;
+        g.kvalid = 4 * d->S;
+        bk = KT;
+      } else {
+        a.N = d->R * KT;
+      }
+    }
+  }
+  finish_geometry(g);
   if (!pl->fast) bk = BK;  // the element-wise kernel walks 64-deep tiles
   pl->bk = bk;
-  a.nkt = (a.Kred + bk - 1) / bk;
-  // split the reduction when the output alone cannot fill the 256 compute units
-  const long long tiles = (long long)a.tiles_m * a.tiles_n;
-  int splits = 1;
-  const int want = (op == JZ_BWD_WEIGHT) ? 512 : 256;
-  if (tiles * 2 <= want) {
-    long long s = (want + tiles - 1) / tiles;
-    long long by_k = a.nkt / 4;  // at least 4 k tiles per split
-    if (s > by_k) s = by_k;
-    if (s > 128) s = 128;
-    if (s >= 2) splits = (int)s;
-  }
-  a.kt_per_split = (a.nkt + splits - 1) / splits;
-  splits = (a.nkt + a.kt_per_split - 1) / a.kt_per_split;  // drop empty splits
-  a.splits = splits;
-  pl->ws_bytes = splits > 1 ? (size_t)splits * a.M * a.N * sizeof(float) : 0;
+  choose_tiling(pl);
+  const size_t part = a.splits > 1 ? (size_t)a.splits * a.M * a.N * sizeof(float) : 0;
+  pl->part_offset = pl->packed ? pl->xp_bytes + pl->wp_bytes : 0;
+  pl->ws_bytes = pl->part_offset + part;
   return JZ_OK;
 }
 
@@ -578,20 +693,20 @@ int launch_one(const GemmArgs& a, hipStream_t st) {
   return jz::launch_status();
 }
 
-template <int OP, int BM, int BN, int TBK, int NST>
+template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false>
 int launch_dma(const GemmArgs& a, hipStream_t st) {
   constexpr size_t ring_bytes = (size_t)NST * (BM + BN) * 2 * TBK;
   constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(unsigned short);
   constexpr size_t smem = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, TBK, NST>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return JZ_ERR_LAUNCH;
     attr_set = true;
   }
   unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.splits;
-  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, TBK, NST>), dim3(grid), dim3(THREADS), smem, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA>), dim3(grid), dim3(THREADS), smem, st, a);
   return jz::launch_status();
 }
 
@@ -599,6 +714,16 @@ template <int OP>
 int launch_op(const Plan& pl, hipStream_t st) {
   const GemmArgs& a = pl.args;
   if (!pl.fast) return launch_one<OP, false, 128, 128>(a, st);
+  if (pl.packed && OP == OP_FWD) {  // small-channel forward: tail of every gathered run is masked
+    if (pl.bk == 32) {
+      if (pl.BN == 64 && pl.BM == 128) return launch_dma<OP_FWD, 128, 64, 32, 4, true>(a, st);
+      if (pl.BN == 128 && pl.BM == 128) return launch_dma<OP_FWD, 128, 128, 32, 4, true>(a, st);
+    } else {
+      if (pl.BN == 64 && pl.BM == 128) return launch_dma<OP_FWD, 128, 64, 64, 4, true>(a, st);
+      if (pl.BN == 128 && pl.BM == 128) return launch_dma<OP_FWD, 128, 128, 64, 4, true>(a, st);
+    }
+    return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
+  }
   if (!use_register_path()) {
     if (pl.bk == 64) {
       if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 64, 4>(a, st);
@@ -617,6 +742,7 @@ int launch_op(const Plan& pl, hipStream_t st) {
   return launch_one<OP, true, 64, 64>(a, st);
 }
 
+// A, B in the kernel's order: FWD (x, w), BWD_DATA (dy, w), BWD_WEIGHT (dy, x)
 int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, void* ws, size_t ws_bytes, void* stream) {
   Plan pl;
   int rc = make_plan(op, d, &pl);
@@ -628,21 +754,49 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
   if (pl.ws_bytes > 0 && (overlaps(ws, pl.ws_bytes, A, pl.bytesA) || overlaps(ws, pl.ws_bytes, B, pl.bytesB) ||
                           overlaps(ws, pl.ws_bytes, D, pl.bytesD)))
     return JZ_ERR_ALIAS;
-  pl.args.A = static_cast<const unsigned short*>(A);
-  pl.args.B = static_cast<const unsigned short*>(B);
-  pl.args.D16 = static_cast<unsigned short*>(D);
-  pl.args.Dpart = static_cast<float*>(ws);
-  pl.args.bytesA = (unsigned)pl.bytesA;
-  pl.args.bytesB = (unsigned)pl.bytesB;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  GemmArgs& a = pl.args;
+  a.A = static_cast<const unsigned short*>(A);
+  a.B = static_cast<const unsigned short*>(B);
+  a.D16 = static_cast<unsigned short*>(D);
+  a.bytesA = (unsigned)pl.bytesA;
+  a.bytesB = (unsigned)pl.bytesB;
+  a.Dpart = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_offset);
+  unsigned short* dwp = nullptr;
+  if (pl.packed) {
+    unsigned short* xp = static_cast<unsigned short*>(ws);
+    unsigned short* wp = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + pl.xp_bytes);
+    const unsigned short* x = static_cast<const unsigned short*>(op == JZ_FWD ? A : B);
+    long long npix = (long long)d->N * pl.Hp * pl.Wp;
+    hipLaunchKernelGGL(pad_to_c4, dim3((unsigned)((npix + 255) / 256)), dim3(256), 0, st, x, xp, d->N, d->H, d->W, d->C,
+                       pl.Hp, pl.Wp, d->pad_h, d->pad_w);
+    if (op == JZ_FWD) {
+      int nwp = d->K * d->R * pl.KT;
+      hipLaunchKernelGGL(pack_filter_c4, dim3((unsigned)((nwp + 255) / 256)), dim3(256), 0, st,
+                         static_cast<const unsigned short*>(B), wp, d->K, d->R, d->S, d->C, pl.KT);
+      a.A = xp; a.bytesA = (unsigned)pl.xp_bytes;
+      a.B = wp; a.bytesB = (unsigned)pl.wp_bytes;
+    } else {
+      a.B = xp; a.bytesB = (unsigned)pl.xp_bytes;
+      dwp = wp;
+      a.D16 = dwp;
+    }
+    if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  }
   if (op == JZ_FWD) rc = launch_op<OP_FWD>(pl, st);
   else if (op == JZ_BWD_DATA) rc = launch_op<OP_BWD_DATA>(pl, st);
   else rc = launch_op<OP_BWD_WEIGHT>(pl, st);
   if (rc != JZ_OK) return rc;
-  if (pl.args.splits > 1) {
-    long long MN = (long long)pl.args.M * pl.args.N;
+  if (a.splits > 1) {
+    long long MN = (long long)a.M * a.N;
     unsigned blocks = (unsigned)((MN + 1023) / 1024);
-    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, pl.args.Dpart, pl.args.D16, MN, pl.args.splits);
+    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, a.Dpart, a.D16, MN, a.splits);
+    if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  }
+  if (dwp) {
+    int ndw = d->K * d->R * d->S * d->C;
+    hipLaunchKernelGGL(unpack_filter_c4, dim3((unsigned)((ndw + 255) / 256)), dim3(256), 0, st, dwp,
+                       static_cast<unsigned short*>(D), d->K, d->R, d->S, d->C, pl.KT);
     rc = jz::launch_status();
   }
   return rc;

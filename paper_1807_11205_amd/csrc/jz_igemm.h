@@ -40,6 +40,13 @@ struct ConvGeom {
   int IH, IW, IC;  // the tensor that is gathered (x for FWD / BWD_WEIGHT, dy for BWD_DATA): spatial size, channels
   int OH, OW;      // the pixel grid the GEMM's m index (FWD, BWD_DATA) or k index (BWD_WEIGHT) runs over
   int R, S, sh, sw, ph, pw;
+  // Addressing of the gathered tensor, in elements: pixel (n, ih, iw), tap column s, channel c sits at
+  //   (n * IH + ih) * row_pitch + iw * pix_step + s_extra + c      with s_extra = 0 here and s * s_step added per tap.
+  // A plain NHWC tensor has row_pitch = IW * IC and pix_step = s_step = IC.  The small-channel path (3-channel
+  // stems) gathers from a zero-padded 4-channel copy in which one filter row of S taps is a single contiguous run:
+  // there IC is the length of that run (the k tile), S = 1, pix_step = 4 and runs of neighbouring pixels overlap.
+  int row_pitch, pix_step, s_step;
+  int kvalid;  // small-channel forward only: elements of a k tile beyond this are not part of the filter row
   FastDiv d_ohow, d_ow, d_ic, d_s, d_sh, d_sw;
 };
 

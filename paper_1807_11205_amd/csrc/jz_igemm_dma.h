@@ -82,7 +82,7 @@ __device__ __forceinline__ void jz_dma16(__amdgpu_buffer_rsrc_t rsrc, lds_byte* 
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, (int)voff, 0, 0, 0);
 }
 
-template <int OP, int BM, int BN, int TBK, int NST>
+template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false>
 __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   static_assert(TBK == 32 || TBK == 64, "k tile depth");
   constexpr bool A_KC = OP != OP_BWD_WEIGHT;  // A has k contiguous in memory
@@ -151,9 +151,9 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
           sa2[ii] = (int)ow * g.sw - g.pw;
           // byte offset of tap (0,0) plus this lane's chunk; may wrap below zero for padded rows, the tap offset
           // brings every in-range access back (unsigned arithmetic)
-          sa0[ii] = (unsigned)((((int)n * g.IH + sa1[ii]) * g.IW + sa2[ii]) * g.IC + kc_chunk * 8) * 2u;
+          sa0[ii] = (unsigned)(((int)n * g.IH + sa1[ii]) * g.row_pitch + sa2[ii] * g.pix_step + kc_chunk * 8) * 2u;
         } else {
-          sa0[ii] = n * (unsigned)(g.IH * g.IW);
+          sa0[ii] = n * (unsigned)(g.IH * g.row_pitch);
           sa1[ii] = (int)oh + g.ph;
           sa2[ii] = (int)ow + g.pw;
         }
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
       c.c0 = c.k0 - (int)c.tap * g.IC;
       c.r = (int)fd_div(c.tap, g.d_s);
       c.s = (int)c.tap - c.r * g.S;
-      c.tapoff = (unsigned)((c.r * g.IW + c.s) * g.IC + c.c0) * 2u;
+      c.tapoff = (unsigned)(c.r * g.row_pitch + c.s * g.s_step + c.c0) * 2u;
       c.tileoff = (unsigned)((c.c0 * g.R * g.S + (int)c.tap) * a.N) * 2u;
     }
     return c;
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
           int ih = (int)fd_div((unsigned)(th < 0 ? 0 : th), g.d_sh);
           int iw = (int)fd_div((unsigned)(tw < 0 ? 0 : tw), g.d_sw);
           bool ok = ih * g.sh == th && iw * g.sw == tw && ih < g.IH && iw < g.IW;  // false for negative th / tw too
-          unsigned off = ((sa0[ii] + (unsigned)(ih * g.IW + iw)) * (unsigned)g.IC + (unsigned)(c.c0 + kc_chunk * 8)) * 2u;
+          unsigned off = (sa0[ii] + (unsigned)(ih * g.row_pitch + iw * g.pix_step + c.c0 + kc_chunk * 8)) * 2u;
           jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? off : OOB);
         } else {  // dy rows j = k0 + k
           int j = c.k0 + mc_k(BM, ii);
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
           int q = (int)rem - p * g.OW;
           int ih = p * g.sh + sb1, iw = q * g.sw + sb2;
           bool ok = j < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
-          unsigned off = (unsigned)((((int)n * g.IH + ih) * g.IW + iw) * g.IC + sbc) * 2u;
+          unsigned off = (unsigned)(((int)n * g.IH + ih) * g.row_pitch + iw * g.pix_step + sbc) * 2u;
           jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? off : OOB);
         }
       }
@@ -370,7 +370,21 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
       }
     }
   };
-  auto mma = [&](half8 (&fa)[TM], half8 (&fb)[TN]) {
+  auto mma = [&](auto ks_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
+    if constexpr (MASKA) {
+      // small-channel forward: the tail of each gathered run belongs to the next pixel, not to this filter row;
+      // clear it so that it cannot contribute (its weights are zero, but 0 * Inf would not be)
+      constexpr int KS = decltype(ks_tag)::value;
+#pragma unroll
+      for (int t = 0; t < TM; ++t) {
+        u32x4 w;
+        __builtin_memcpy(&w, &fa[t], 16);
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd)
+          if (16 * KS + 8 * (lane >> 5) + 2 * dd >= g.kvalid) w[dd] = 0u;
+        __builtin_memcpy(&fa[t], &w, 16);
+      }
+    }
 #ifdef JZ_EXPERIMENT_NO_MFMA  // timing experiment only: one MFMA per k step instead of TM*TN
     acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[TN - 1], fa[TM - 1], acc[0][0], 0, 0, 0);
     return;
@@ -401,22 +415,22 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     read_frags(sb, std::integral_constant<int, 1>{}, fa1, fb1);
     if (ISSUE) issue_part(c, ist, std::integral_constant<int, 0>{});
     settle(std::integral_constant<int, READS>{}, fa0, fb0);
-    mma(fa0, fb0);
+    mma(std::integral_constant<int, 0>{}, fa0, fb0);
     if constexpr (NKS == 4) {
       read_frags(sb, std::integral_constant<int, 2>{}, fa0, fb0);
       if (ISSUE) issue_part(c, ist, std::integral_constant<int, 1>{});
       settle(std::integral_constant<int, READS>{}, fa1, fb1);
-      mma(fa1, fb1);
+      mma(std::integral_constant<int, 1>{}, fa1, fb1);
       read_frags(sb, std::integral_constant<int, NKS - 1>{}, fa1, fb1);
       if (ISSUE) issue_part(c, ist, std::integral_constant<int, 2>{});
       settle(std::integral_constant<int, READS>{}, fa0, fb0);
-      mma(fa0, fb0);
+      mma(std::integral_constant<int, 2>{}, fa0, fb0);
       if (ISSUE) issue_part(c, ist, std::integral_constant<int, NKS - 1>{});
     } else {
       if (ISSUE) issue_part(c, ist, std::integral_constant<int, 1>{});
     }
     settle(std::integral_constant<int, 0>{}, fa1, fb1);
-    mma(fa1, fb1);
+    mma(std::integral_constant<int, NKS - 1>{}, fa1, fb1);
   };
 
   // ---- the ring ---------------------------------------------------------------------------------
