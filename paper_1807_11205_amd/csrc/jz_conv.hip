@@ -170,7 +170,26 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
     int m = m0 + row, n = n0 + cch * 8;
     if (m >= a.M || n >= a.N) continue;
     const unsigned short* src = sC + row * LDC + cch * 8;
-    unsigned short* dst = a.D16 + (size_t)m * a.N + n;
+    size_t drow = (size_t)m;
+    if (a.sc_on) {  // row m = (n, p, q) of the strided grid goes to input pixel (n, p * sh, q * sw)
+      unsigned nimg = fd_div((unsigned)m, a.g.d_ohow);
+      unsigned rem = (unsigned)m - nimg * (unsigned)(a.g.OH * a.g.OW);
+      unsigned p = fd_div(rem, a.g.d_ow);
+      unsigned q = rem - p * (unsigned)a.g.OW;
+      drow = ((size_t)nimg * a.sc_H + p * a.sc_sh) * a.sc_W + q * a.sc_sw;
+      // the other pixels of this sh x sw cell are read by no output pixel: their gradient is zero
+      for (int i2 = 0; i2 < a.sc_sh; ++i2)
+        for (int j2 = 0; j2 < a.sc_sw; ++j2) {
+          if ((i2 | j2) == 0 || (int)(p * a.sc_sh) + i2 >= a.sc_H || (int)(q * a.sc_sw) + j2 >= a.sc_W) continue;
+          unsigned short* z = a.D16 + (drow + (size_t)i2 * a.sc_W + j2) * a.N + n;
+          if (nvec) {
+            *reinterpret_cast<uint4*>(z) = make_uint4(0, 0, 0, 0);
+          } else {
+            for (int e = 0; e < 8 && n + e < a.N; ++e) z[e] = 0;
+          }
+        }
+    }
+    unsigned short* dst = a.D16 + drow * a.N + n;
     if (nvec) {
       *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
     } else {
@@ -524,9 +543,10 @@ int env_int(const char* name) {
   return e ? atoi(e) : 0;
 }
 // debugging aids: JZ_IGEMM_BK=64, JZ_IGEMM_TILE=<BM*1000+BN>, JZ_IGEMM_SPLITS=<n> override the planner
-int igemm_bk_override() { static int v = env_int("JZ_IGEMM_BK"); return v; }
-int igemm_tile_override() { static int v = env_int("JZ_IGEMM_TILE"); return v; }
-int igemm_splits_override() { static int v = env_int("JZ_IGEMM_SPLITS"); return v; }
+// (read on every call so that a tuning sweep can change them inside one process)
+int igemm_bk_override() { return env_int("JZ_IGEMM_BK"); }
+int igemm_tile_override() { return env_int("JZ_IGEMM_TILE"); }
+int igemm_splits_override() { return env_int("JZ_IGEMM_SPLITS"); }
 
 struct Plan {
   int op = 0;
@@ -574,6 +594,7 @@ void choose_tiling(Plan* pl) {
       if (igemm_splits_override() && sp != igemm_splits_override() && !(sp == 1 && a.nkt / igemm_splits_override() < 4)) continue;
       long long blocks = tm * tn * sp;
       long long rounds = (blocks + 511) / 512;
+      if (a.sc_on && sp > 1) break;  // the scatter lives in the fp16 epilogue
       double kps = (double)((a.nkt + sp - 1) / sp);
       double gemm = rounds * kps * tt * (blocks <= 256 ? 0.7 : 1.0) + 3.0;
       double split = sp > 1 ? (2.0 * sp * (double)a.M * a.N * 4.0) / 3.0e6 + 4.0 : 0.0;
@@ -636,6 +657,15 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
     g.IH = d->H; g.IW = d->W; g.IC = d->C; g.OH = P; g.OW = Q;
     pl->fast = d->K % 8 == 0 && d->C % 8 == 0;
     pl->bytesA = 2 * ny; pl->bytesB = 2 * nx; pl->bytesD = 2 * nw;  // A = dy, B = x
+  }
+  a.sc_on = 0; a.sc_H = a.sc_W = 0; a.sc_sh = a.sc_sw = 1;
+  if (op == JZ_BWD_DATA && pl->fast && !use_register_path() && d->R == 1 && d->S == 1 && d->pad_h == 0 && d->pad_w == 0 &&
+      (d->stride_h > 1 || d->stride_w > 1)) {
+    // strided 1x1 layer (the ResNet downsampling convs): only input pixels (p*sh, q*sw) receive gradient, so the GEMM
+    // runs over the N*P*Q output pixels as a stride-1 problem and the epilogue scatters its rows (and the zeros)
+    a.M = d->N * P * Q;
+    g.OH = P; g.OW = Q; g.sh = 1; g.sw = 1;
+    a.sc_on = 1; a.sc_H = d->H; a.sc_W = d->W; a.sc_sh = d->stride_h; a.sc_sw = d->stride_w;
   }
   g.row_pitch = g.IW * g.IC;
   g.pix_step = g.IC;

@@ -276,6 +276,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     issue_load(c, st, std::integral_constant<int, PART + 3 * NKS>{});
   };
   static_assert(LPT <= 4 * NKS, "issue_part covers at most 4 loads per MFMA group");
+  static_assert(NST >= 3 && NST <= 8 && (NST - 2) * LPT <= 63, "ring depth: vmcnt is a 6-bit counter");
   auto issue = [&](int kt, int st) {
     TileCtx c = tile_ctx(kt);
     issue_part(c, st, std::integral_constant<int, 0>{});
@@ -449,10 +450,15 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     TileCtx c = tile_ctx(kt_begin + i + NST - 1);
     compute(i % NST, std::true_type{}, c, (i + NST - 1) % NST);
   }
-  for (; i < nk; ++i) {  // drain
+  for (; i < nk; ++i) {  // drain: fewer and fewer younger tiles remain in flight
     const int younger = nk - 1 - i;
     if (younger >= NST - 2) wait_vmcnt<(NST - 2) * LPT>();
-    else if (NST > 3 && younger == 1) wait_vmcnt<LPT>();
+    else if (NST - 2 > 6 && younger == 6) wait_vmcnt<6 * LPT>();
+    else if (NST - 2 > 5 && younger == 5) wait_vmcnt<5 * LPT>();
+    else if (NST - 2 > 4 && younger == 4) wait_vmcnt<4 * LPT>();
+    else if (NST - 2 > 3 && younger == 3) wait_vmcnt<3 * LPT>();
+    else if (NST - 2 > 2 && younger == 2) wait_vmcnt<2 * LPT>();
+    else if (NST - 2 > 1 && younger == 1) wait_vmcnt<LPT>();
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     TileCtx c{};
