@@ -13,6 +13,7 @@
 // FAST kernels need channel counts that are multiples of 64 (resp. 8), which makes a k tile lie inside one filter
 // tap so that all tap arithmetic is wave-uniform.  Everything else (3-channel stems, odd sizes) goes through the
 // element-wise GENERIC loaders: same tiles, same MFMA loop, every element bounds-checked.
+#include <stdio.h>
 #include <stdlib.h>
 
 #include <type_traits>
@@ -703,6 +704,10 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   const size_t part = a.splits > 1 ? (size_t)a.splits * a.M * a.N * sizeof(float) : 0;
   pl->part_offset = pl->packed ? pl->xp_bytes + pl->wp_bytes : 0;
   pl->ws_bytes = pl->part_offset + part;
+  if (env_int("JZ_IGEMM_VERBOSE"))  // debugging aid: show what the planner chose
+    fprintf(stderr, "jz igemm op %d M %d N %d K %d: %s tile %dx%dx%d, %d x %d tiles, %d splits of %d k tiles%s%s\n", op, a.M,
+            a.N, a.Kred, pl->fast ? "vector" : "element-wise", pl->BM, pl->BN, pl->bk, a.tiles_m, a.tiles_n, a.splits,
+            a.kt_per_split, pl->packed ? ", 4-channel padded copy" : "", a.sc_on ? ", scatter epilogue" : "");
   return JZ_OK;
 }
 

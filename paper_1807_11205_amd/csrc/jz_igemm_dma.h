@@ -407,12 +407,36 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   constexpr int READS = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);  // LDS reads per k step
   static_assert(READS <= 15, "lgkmcnt is a 4-bit counter");
 
-  // multiply the tile in stage st; when ISSUE, request tile `c` into stage ist between the MFMA groups
-  auto compute = [&](int st, auto issue_tag, const TileCtx& c, int ist) {
-    constexpr bool ISSUE = decltype(issue_tag)::value;
+  // wait until at most `younger` later tiles (capped at NST-2) are still in flight
+  auto wait_tiles = [&](int younger) {
+    if (younger >= NST - 2) wait_vmcnt<(NST - 2) * LPT>();
+    else if (NST - 2 > 6 && younger == 6) wait_vmcnt<6 * LPT>();
+    else if (NST - 2 > 5 && younger == 5) wait_vmcnt<5 * LPT>();
+    else if (NST - 2 > 4 && younger == 4) wait_vmcnt<4 * LPT>();
+    else if (NST - 2 > 3 && younger == 3) wait_vmcnt<3 * LPT>();
+    else if (NST - 2 > 2 && younger == 2) wait_vmcnt<2 * LPT>();
+    else if (NST - 2 > 1 && younger == 1) wait_vmcnt<LPT>();
+    else wait_vmcnt<0>();
+  };
+
+  // ---- the ring ---------------------------------------------------------------------------------
+  // One iteration multiplies tile i out of stage i % NST.  Its first operands (k step 0) were already read at the end
+  // of the previous iteration, so the matrix pipe never waits for an LDS round trip at the top of an iteration:
+  //
+  //     read k step 1 .. ; request part of tile i+NST-1 ; MFMA k step 0 ; ... ; all reads of tile i are in registers
+  //     wait until tile i+1 has landed ; BARRIER ; read k step 0 of tile i+1 ; MFMA last k step of tile i
+  //
+  // The barrier therefore sits between two MFMA groups.  It says two things: every wavefront's share of tile i+1
+  // is in LDS, and every wavefront has finished reading tile i (its operands are in registers), so stage i % NST
+  // may be overwritten by the loads requested in the next iteration.  Barriers are bare (no fence): a fenced
+  // barrier makes the compiler drain every LDS-direct load first (vmcnt(0)); the ordering that matters is spelled
+  // out by hand with vmcnt / lgkmcnt waits.
+  half8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  // STEADY: request tile c into stage ist while multiplying; NEXT: there is a tile after this one
+  auto iteration = [&](int st, auto steady_tag, const TileCtx& c, int ist, bool has_next, int younger_after_next) {
+    constexpr bool ISSUE = decltype(steady_tag)::value;
     const unsigned sb = lds_base + (unsigned)(st * STAGE);
-    half8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    read_frags(sb, std::integral_constant<int, 0>{}, fa0, fb0);
+    const unsigned sb_next = lds_base + (unsigned)(((st + 1) % NST) * STAGE);
     read_frags(sb, std::integral_constant<int, 1>{}, fa1, fb1);
     if (ISSUE) issue_part(c, ist, std::integral_constant<int, 0>{});
     settle(std::integral_constant<int, READS>{}, fa0, fb0);
@@ -430,39 +454,34 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     } else {
       if (ISSUE) issue_part(c, ist, std::integral_constant<int, 1>{});
     }
-    settle(std::integral_constant<int, 0>{}, fa1, fb1);
+    settle(std::integral_constant<int, 0>{}, fa1, fb1);  // every LDS read of this tile has completed
+    if (ISSUE || has_next) {
+      if (ISSUE) wait_vmcnt<(NST - 2) * LPT>();
+      else wait_tiles(younger_after_next);
+#ifndef JZ_EXPERIMENT_NO_BARRIER
+      __builtin_amdgcn_s_barrier();
+#endif
+      read_frags(sb_next, std::integral_constant<int, 0>{}, fa0, fb0);
+    }
     mma(std::integral_constant<int, NKS - 1>{}, fa1, fb1);
   };
 
-  // ---- the ring ---------------------------------------------------------------------------------
-  // Barriers are bare (no fence): a fenced barrier makes the compiler drain every LDS-direct load first (vmcnt(0)).
-  // The ordering that matters is spelled out by hand: before a wavefront arrives at the barrier of iteration i it has
-  // waited for its own share of tile i (vmcnt) and for its LDS reads of tile i-1 (lgkmcnt(0) before its last MFMAs).
 #pragma unroll
   for (int s = 0; s < NST - 1; ++s)
     if (s < nk) issue(kt_begin + s, s);
+  if (nk > 0) {
+    wait_tiles(nk - 1);
+    __builtin_amdgcn_s_barrier();
+    read_frags(lds_base, std::integral_constant<int, 0>{}, fa0, fb0);
+  }
   int i = 0;
   for (; i + NST - 1 < nk; ++i) {  // steady state, branch-free body: NST-2 younger tiles stay in flight
-    wait_vmcnt<(NST - 2) * LPT>();
-#ifndef JZ_EXPERIMENT_NO_BARRIER
-    __builtin_amdgcn_s_barrier();
-#endif
     TileCtx c = tile_ctx(kt_begin + i + NST - 1);
-    compute(i % NST, std::true_type{}, c, (i + NST - 1) % NST);
+    iteration(i % NST, std::true_type{}, c, (i + NST - 1) % NST, true, 0);
   }
-  for (; i < nk; ++i) {  // drain: fewer and fewer younger tiles remain in flight
-    const int younger = nk - 1 - i;
-    if (younger >= NST - 2) wait_vmcnt<(NST - 2) * LPT>();
-    else if (NST - 2 > 6 && younger == 6) wait_vmcnt<6 * LPT>();
-    else if (NST - 2 > 5 && younger == 5) wait_vmcnt<5 * LPT>();
-    else if (NST - 2 > 4 && younger == 4) wait_vmcnt<4 * LPT>();
-    else if (NST - 2 > 3 && younger == 3) wait_vmcnt<3 * LPT>();
-    else if (NST - 2 > 2 && younger == 2) wait_vmcnt<2 * LPT>();
-    else if (NST - 2 > 1 && younger == 1) wait_vmcnt<LPT>();
-    else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
+  for (; i < nk; ++i) {  // drain: nothing left to request
     TileCtx c{};
-    compute(i % NST, std::false_type{}, c, 0);
+    iteration(i % NST, std::false_type{}, c, 0, i + 1 < nk, nk - 2 - i);
   }
   __syncthreads();  // the epilogue reuses the ring as its staging tile
 
