@@ -89,6 +89,7 @@ class ResNet50Step:
             ws_bytes = max(ws_bytes, api.jz_gemm_fc_workspace_bytes(op, B, I, O))
         self.flops += 2 * self.fc.macs(batch) * 3
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)
+        self.ws2 = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)   # for the side stream
 
         self.found_inf = torch.zeros(1, dtype=torch.int32, device=device)
         self.ps = api.ParamSet(self.offsets, self.flags, self.master, self.momentum, self.grad, self.w16)
@@ -101,21 +102,47 @@ class ResNet50Step:
         hp = inputs.HPARAMS
         return api.lars_hparams(hp["lr"], hp["momentum"], hp["weight_decay"], hp["trust_coef"], self.loss_scale)
 
-    def run_gemms(self):
+    def _bwd_data(self, L, ws):
+        B, I, O = self.N, self.fc.I, self.fc.O
+        if L["kind"] == "conv":
+            if not L["first"]:
+                api.jz_conv2d_bwd_data(L["d"], L["dy"], L["w"], L["dx"], ws)
+        else:
+            api.jz_gemm_fc(api.JZ_BWD_DATA, B, I, O, L["dy"], L["w"], L["dx"], ws)
+
+    def _bwd_weight(self, L, ws):
+        B, I, O = self.N, self.fc.I, self.fc.O
+        if L["kind"] == "conv":
+            api.jz_conv2d_bwd_weight(L["d"], L["x"], L["dy"], L["dw"], ws)
+        else:
+            api.jz_gemm_fc(api.JZ_BWD_WEIGHT, B, I, O, L["dy"], L["x"], L["dw"], ws)
+
+    def run_gemms(self, side=None):
+        """Forward of every layer, then the backward pass.  With a side stream, backward-weight of a layer runs there,
+        concurrently with the backward-data chain on the current stream, ordered the way a real network orders them:
+        dW of layer l needs only dy of layer l, which the backward-data of layer l+1 produces."""
         B, I, O = self.N, self.fc.I, self.fc.O
         for L in self.layers:                                   # forward
             if L["kind"] == "conv":
                 api.jz_conv2d_fwd(L["d"], L["x"], L["w"], L["y"], self.ws)
             else:
                 api.jz_gemm_fc(api.JZ_FWD, B, I, O, L["x"], L["w"], L["y"], self.ws)
-        for L in reversed(self.layers):                         # backward
-            if L["kind"] == "conv":
-                if not L["first"]:
-                    api.jz_conv2d_bwd_data(L["d"], L["dy"], L["w"], L["dx"], self.ws)
-                api.jz_conv2d_bwd_weight(L["d"], L["x"], L["dy"], L["dw"], self.ws)
-            else:
-                api.jz_gemm_fc(api.JZ_BWD_DATA, B, I, O, L["dy"], L["w"], L["dx"], self.ws)
-                api.jz_gemm_fc(api.JZ_BWD_WEIGHT, B, I, O, L["dy"], L["x"], L["dw"], self.ws)
+        if side is None:
+            for L in reversed(self.layers):                     # backward, one stream
+                self._bwd_data(L, self.ws)
+                self._bwd_weight(L, self.ws)
+            return
+        cur = torch.cuda.current_stream()
+        ready = torch.cuda.Event()
+        ready.record(cur)                                       # the loss gradient exists
+        for L in reversed(self.layers):
+            side.wait_event(ready)
+            with torch.cuda.stream(side):
+                self._bwd_weight(L, self.ws2)
+            self._bwd_data(L, self.ws)
+            ready = torch.cuda.Event()
+            ready.record(cur)                                   # dy of the layer below exists
+        cur.wait_stream(side)
 
     def run_lars(self):
         api.jz_lars_mp_update(self.ps, self.hparams(), self.found_inf, self.lars_ws)
@@ -226,7 +253,8 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
-    ap.add_argument("--graph", type=int, default=1, help="replay the step from a HIP graph (1) or launch eagerly (0)")
+    ap.add_argument("--streams", type=int, default=2, help="2: backward-weight runs on a second stream beside backward-data")
+    ap.add_argument("--graph", type=int, default=0, help="replay the step from a HIP graph (1) or launch eagerly (0); eager launches measured faster here")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
@@ -250,17 +278,19 @@ def main():
         wl.reset_state()
 
     stream = torch.cuda.Stream()
+    side = torch.cuda.Stream() if args.streams == 2 else None
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     with torch.cuda.stream(stream):
         for _ in range(max(args.warmup, 1)):
-            wl.step()
+            wl.run_gemms(side)
+            wl.run_lars()
         stream.synchronize()
         graphs = None
         if args.graph:
             # two graphs (GEMM phase, LARS phase) so that HIP events can separate the phases between replays
             g1, g2 = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
             with torch.cuda.graph(g1, stream=stream):
-                wl.run_gemms()
+                wl.run_gemms(side)
             with torch.cuda.graph(g2, stream=stream):
                 wl.run_lars()
             graphs = (g1, g2)
@@ -274,7 +304,7 @@ def main():
             if graphs:
                 graphs[0].replay()
             else:
-                wl.run_gemms()
+                wl.run_gemms(side)
             ev[k][1].record(stream)
             if graphs:
                 graphs[1].replay()
@@ -305,7 +335,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[4]: ResNet-50 v1, 53 convs + FC, fwd + bwd_data + bwd_weight per layer on "
                                "independent seeded N(0,1) inputs, then fused LARS over 161 tensors / 25,557,032 params",
-                   "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "launch": "hip graph" if graphs else "eager"},
+                   "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "launch": "hip graph" if graphs else "eager", "streams": args.streams},
         "pct_fp16_mfma_peak": 100.0 * (wl.flops / (ms_per_step * 1e-3) / 1e12) / FP16_MFMA_PEAK_TFLOPS,
         "roofline": {"kernel": "igemm_kernel (all %d conv/FC launches of a step)" % n_gemm, "bound": "mfma",
                      "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
