@@ -138,8 +138,9 @@ int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes, void* hip
  *   per element:   v <- m*v + lr * rho_t * (g + lambda_t * w) ;  w <- w - v ;  w16 <- RNE16(w)      (FP32 arithmetic,
  *                  norms accumulated in FP64 in a fixed order)
  * found_inf_dev: DEVICE int, set to 0 or 1; valid once the stream has been synchronised.
- * Returns JZ_ERR_NOT_PREPARED if `ws` was prepared for a different table (checked on the host by a
- * checksum kept beside the table, and again on the device before anything is written). */
+ * Returns JZ_ERR_NOT_PREPARED if `ws` was not prepared for this table by jz_lars_prepare (the host keeps a
+ * checksum of the offsets/flags per prepared workspace pointer).  The kernels check the table header in `ws`
+ * again on the device before anything is written; if it does not match, *found_inf_dev = -1 and no state changes. */
 int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
                       size_t ws_bytes, void* hip_stream);
 
