@@ -128,7 +128,11 @@ typedef struct {
 int jz_lars_workspace_bytes(const jz_param_set* ps, size_t* bytes);
 
 /* Writes the tensor/chunk tables for `ps` into `ws` (a blocking host-to-device copy on `hip_stream`).
- * Call once per parameter-set layout; `ws` must then be kept intact and passed to every update. */
+ * Call once per parameter-set layout; `ws` must then be kept intact and passed to every update.
+ * The workspace also carries state from one update to the next: while an update writes the new master weights it
+ * accumulates each tensor's sum of squares, so the next update does not have to read the weights to get ||w_t||.
+ * Consequently, if master_w is written by anything other than jz_lars_mp_update (initialisation, a checkpoint
+ * restore), call jz_lars_prepare again before the next update; it discards the carried sums. */
 int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* One optimiser step over every tensor:

@@ -1,18 +1,21 @@
 // FP16-storage / FP32-accumulate convolution forward, backward-data, backward-weight and the fully
 // connected GEMMs (Jia et al. 2018, Section 4.1) as one implicit-GEMM kernel family for gfx950.
 //
-// Workgroup = 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN output tile; each wavefront owns
-// (BM/2) x (BN/2) of it as 32x32 MFMA tiles (v_mfma_f32_32x32x16_f16, fp32 accumulators).  The reduction
-// is walked in k tiles of BK = 64 halves: wavefronts 0-1 fetch the A tile, wavefronts 2-3 the B tile, global ->
-// registers -> LDS, double buffered so the next tile's loads are in flight while the current one is multiplied.
-// Both tiles sit in LDS as [row][k] with k contiguous (row pitch BK+8 halves: every 16-byte MFMA operand read
-// and every 16-byte tile write is bank-conflict free).  Operands whose memory layout has the *other* index
-// contiguous (the filter in backward-data, both operands in backward-weight) are fetched as 8x8 blocks
-// and transposed in registers on their way into LDS.
+// This file holds the host side (planner: tile shape, split of the reduction, which kernel; argument checks; the
+// extern "C" entry points), the epilogue shared by all kernels, the small helper kernels (split-K reduction, the
+// 4-channel padded copy for 3-channel stems), and the register-staged kernel `igemm_kernel`:
 //
-// FAST kernels need channel counts that are multiples of 64 (resp. 8), which makes a k tile lie inside one filter
-// tap so that all tap arithmetic is wave-uniform.  Everything else (3-channel stems, odd sizes) goes through the
-// element-wise GENERIC loaders: same tiles, same MFMA loop, every element bounds-checked.
+//   igemm_kernel<OP, FAST=false>  element-wise, fully bounds-checked operand access.  Runs every shape that allows
+//                                 no 16-byte vector access (channel counts that are not multiples of 8 or 32).
+//   igemm_kernel<OP, FAST=true>   16-byte loads global -> registers -> LDS, double buffered.  Kept as a second,
+//                                 independent implementation for debugging (JZ_IGEMM_PATH=reg); not used otherwise.
+//
+// The production kernel, igemm_dma_kernel (LDS-direct loads, multi-stage ring), lives in jz_igemm_dma.h.
+//
+// All kernels: workgroup = 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN output tile; each wavefront owns
+// (BM/2) x (BN/2) of it as 32x32 MFMA tiles (v_mfma_f32_32x32x16_f16, fp32 accumulators).  The register-staged kernel
+// keeps both tiles in LDS as [row][k] with k contiguous (row pitch BK+8 halves: conflict-free 16-byte accesses);
+// operands whose memory layout has the other index contiguous are fetched as 8x8 blocks and transposed in registers.
 #include <stdio.h>
 #include <stdlib.h>
 

@@ -6,12 +6,14 @@
 // parameter must move), so it is organised as three stream-ordered launches over a fused flat buffer:
 //
 //   lars_reduce    one workgroup per chunk (<= LARS_CH elements inside one tensor): fp64 partial sums of
-//                  w^2 and g16^2 and a non-finite flag, stored per chunk (no atomics => deterministic)
+//                  g16^2 (and of w^2, unless the workspace still holds them from the previous update) and a
+//                  non-finite flag, stored per chunk (no atomics => deterministic)
 //   lars_finalize  one workgroup per tensor: adds that tensor's chunk partials in index order, forms
 //                  lr*rho_t, ORs the chunk flags
 //   lars_update    one workgroup per chunk, walking the buffer in the opposite direction so that the
 //                  tail the reduce pass touched last is still in the last-level cache; skips everything
-//                  when any tensor raised the flag
+//                  when any tensor raised the flag.  While writing w it accumulates the chunk's sum of w^2,
+//                  which the next update's reduce pass then need not read w for.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -21,13 +23,18 @@
 
 namespace {
 
-constexpr int LARS_CH = 4096;  // elements per chunk; a multiple of 8
+#ifndef JZ_LARS_CH
+#define JZ_LARS_CH 4096
+#endif
+constexpr int LARS_CH = JZ_LARS_CH;  // elements per chunk; a multiple of 2048 (8 per thread and pass)
 constexpr int LARS_THREADS = 256;
+constexpr int LARS_WAVES = LARS_THREADS / 64;  // every wavefront of a chunk keeps its own partial sums
 constexpr uint64_t LARS_MAGIC = 0x4a5a4c4152533031ull;  // "JZLARS01"
 
 struct Layout {
   int64_t T = 0, P = 0, n_chunks = 0;
   size_t off_header = 0, off_offsets = 0, off_chunk_begin = 0, off_flags = 0, off_chunk_tensor = 0;
+  size_t off_state = 0;
   size_t static_bytes = 0;  // everything up to here is written by prepare
   size_t off_psum_w = 0, off_psum_g = 0, off_pflag = 0, off_coef = 0, off_tflag = 0, total = 0;
 };
@@ -58,10 +65,12 @@ int make_layout(const jz_param_set* ps, Layout* L) {
   L->off_chunk_begin = o;   o = up256(o + sizeof(int) * (L->T + 1));
   L->off_flags = o;         o = up256(o + sizeof(int) * (L->T ? L->T : 1));
   L->off_chunk_tensor = o;  o = up256(o + sizeof(int) * (chunks ? chunks : 1));
+  L->off_state = o;         o = up256(o + 64);
   L->static_bytes = o;
-  L->off_psum_w = o;        o = up256(o + sizeof(double) * (chunks ? chunks : 1));
-  L->off_psum_g = o;        o = up256(o + sizeof(double) * (chunks ? chunks : 1));
-  L->off_pflag = o;         o = up256(o + sizeof(int) * (chunks ? chunks : 1));
+  const size_t parts = (size_t)(chunks ? chunks : 1) * LARS_WAVES;
+  L->off_psum_w = o;        o = up256(o + sizeof(double) * parts);
+  L->off_psum_g = o;        o = up256(o + sizeof(double) * parts);
+  L->off_pflag = o;         o = up256(o + sizeof(int) * parts);
   L->off_coef = o;          o = up256(o + sizeof(float) * (L->T ? L->T : 1));
   L->off_tflag = o;         o = up256(o + sizeof(int) * (L->T ? L->T : 1));
   L->total = o;
@@ -106,9 +115,10 @@ struct Tables {
   const int* chunk_begin;
   const int* flags;
   const int* chunk_tensor;
-  double* psum_w;
-  double* psum_g;
-  int* pflag;
+  int* state;    // [0]: 1 when psum_w holds the sums of squares of the current master weights
+  double* psum_w;  // [n_chunks][LARS_WAVES] partial sums of w^2: one per wavefront, so that no kernel needs a barrier
+  double* psum_g;  // same for the (loss-scaled) gradient
+  int* pflag;      // same: non-finite gradient seen
   float* coef;  // lr * rho_t
   int* tflag;
   int T, n_chunks;
@@ -140,6 +150,12 @@ __device__ __forceinline__ double block_sum(double v, double* lds4) {
   return ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
 }
 
+// Sum over the 64 lanes of a wavefront by a fixed shuffle tree; the total ends up in lane 0.
+__device__ __forceinline__ double wave_sum(double v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
 __device__ __forceinline__ void chunk_range(const Tables& tb, int c, int* t_out, int64_t* start, int64_t* end) {
   int t = tb.chunk_tensor[c];
   int64_t s = tb.offsets[t] + (int64_t)(c - tb.chunk_begin[t]) * LARS_CH;
@@ -149,33 +165,93 @@ __device__ __forceinline__ void chunk_range(const Tables& tb, int c, int* t_out,
   *end = (s + LARS_CH < e) ? s + LARS_CH : e;
 }
 
+constexpr int LARS_IT = LARS_CH / (LARS_THREADS * 8);  // 8-element groups per thread and chunk
+
+// 16-byte accesses of the update pass.  Non-temporal variants (JZ_LARS_NT) were measured slower on MI355X (the
+// last-level cache then no longer serves the gradient the reduce pass just read), so plain accesses are the default.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream_f4(const float* p) {
+#ifndef JZ_LARS_NT
+  return *reinterpret_cast<const float4*>(p);
+#else
+  f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
+#endif
+}
+__device__ __forceinline__ uint4 load_stream_u4(const unsigned short* p) {
+#ifndef JZ_LARS_NT
+  return *reinterpret_cast<const uint4*>(p);
+#else
+  u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+#endif
+}
+__device__ __forceinline__ void store_stream_f4(float* p, float a, float b, float c, float d) {
+#ifndef JZ_LARS_NT
+  *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+#else
+  f32x4_t t = {a, b, c, d};
+  __builtin_nontemporal_store(t, reinterpret_cast<f32x4_t*>(p));
+#endif
+}
+__device__ __forceinline__ void store_stream_u4(unsigned short* p, unsigned a, unsigned b, unsigned c, unsigned d) {
+#ifndef JZ_LARS_NT
+  *reinterpret_cast<uint4*>(p) = make_uint4(a, b, c, d);
+#else
+  u32x4_t t = {a, b, c, d};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
+#endif
+}
+
+// the 8-aligned body [b0,b1) of a chunk [s,e); the rest is at most 7 head and 7 tail elements
+__device__ __forceinline__ void chunk_body(int64_t s, int64_t e, int64_t* b0, int64_t* b1) {
+  int64_t a = (s + 7) & ~int64_t(7);
+  if (a > e) a = e;
+  *b0 = a;
+  *b1 = a + ((e - a) & ~int64_t(7));
+}
+
 __global__ __launch_bounds__(LARS_THREADS) void lars_reduce(Tables tb, const float* __restrict__ w,
                                                             const unsigned short* __restrict__ g16) {
-  __shared__ double red[4];
   if (!table_ok(tb)) return;
   const int c = blockIdx.x;
+  const bool have_w = tb.state[0] != 0;  // written by the previous update, i.e. by an earlier launch
   int t;
-  int64_t s, e;
+  int64_t s, e, b0, b1;
   chunk_range(tb, c, &t, &s, &e);
-  // [s,e) = unaligned head + 8-aligned body + tail
-  int64_t b0 = (s + 7) & ~int64_t(7);
-  if (b0 > e) b0 = e;
-  int64_t b1 = b0 + ((e - b0) & ~int64_t(7));
+  chunk_body(s, e, &b0, &b1);
   double sw = 0.0, sg = 0.0;
   int bad = 0;
-  for (int64_t i = b0 + (int64_t)threadIdx.x * 8; i < b1; i += LARS_THREADS * 8) {
-    float4 w0 = *reinterpret_cast<const float4*>(w + i);
-    float4 w1 = *reinterpret_cast<const float4*>(w + i + 4);
-    uint4 gq = *reinterpret_cast<const uint4*>(g16 + i);
-    float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-    unsigned gw[4] = {gq.x, gq.y, gq.z, gq.w};
+  uint4 gq[LARS_IT];
+  float4 w0[LARS_IT], w1[LARS_IT];
+#pragma unroll
+  for (int k = 0; k < LARS_IT; ++k) {
+    int64_t i = b0 + (int64_t)(k * LARS_THREADS + threadIdx.x) * 8;
+    gq[k] = make_uint4(0, 0, 0, 0);
+    w0[k] = w1[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < b1) {
+      gq[k] = *reinterpret_cast<const uint4*>(g16 + i);
+      if (!have_w) {
+        w0[k] = *reinterpret_cast<const float4*>(w + i);
+        w1[k] = *reinterpret_cast<const float4*>(w + i + 4);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < LARS_IT; ++k) {  // zeros of the groups beyond b1 add nothing
+    float wv[8] = {w0[k].x, w0[k].y, w0[k].z, w0[k].w, w1[k].x, w1[k].y, w1[k].z, w1[k].w};
+    unsigned gw[4] = {gq[k].x, gq[k].y, gq[k].z, gq[k].w};
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       unsigned short hb = (unsigned short)(gw[j >> 1] >> ((j & 1) * 16));
       bad |= half_nonfinite(hb);
-      double wd = (double)wv[j], gd = (double)half_bits_to_float(hb);
-      sw = fma(wd, wd, sw);
+      double gd = (double)half_bits_to_float(hb);
       sg = fma(gd, gd, sg);
+    }
+    if (!have_w) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sw = fma((double)wv[j], (double)wv[j], sw);
     }
   }
   {  // head and tail, at most 7 elements each
@@ -185,18 +261,19 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_reduce(Tables tb, const flo
       int64_t i = (k < nh) ? s + k : b1 + (k - nh);
       unsigned short hb = g16[i];
       bad |= half_nonfinite(hb);
-      double wd = (double)w[i], gd = (double)half_bits_to_float(hb);
+      double wd = have_w ? 0.0 : (double)w[i], gd = (double)half_bits_to_float(hb);
       sw = fma(wd, wd, sw);
       sg = fma(gd, gd, sg);
     }
   }
-  sw = block_sum(sw, red);
-  sg = block_sum(sg, red);
-  bad = __syncthreads_or(bad);
-  if (threadIdx.x == 0) {
-    tb.psum_w[c] = sw;
-    tb.psum_g[c] = sg;
-    tb.pflag[c] = bad ? 1 : 0;
+  sw = wave_sum(sw);
+  sg = wave_sum(sg);
+  bad = __any(bad);
+  if ((threadIdx.x & 63) == 0) {
+    const int slot = c * LARS_WAVES + (threadIdx.x >> 6);
+    if (!have_w) tb.psum_w[slot] = sw;
+    tb.psum_g[slot] = sg;
+    tb.pflag[slot] = bad ? 1 : 0;
   }
 }
 
@@ -204,7 +281,7 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_finalize(Tables tb, float l
   __shared__ double red[4];
   if (!table_ok(tb)) return;
   const int t = blockIdx.x;
-  const int c0 = tb.chunk_begin[t], c1 = tb.chunk_begin[t + 1];
+  const int c0 = tb.chunk_begin[t] * LARS_WAVES, c1 = tb.chunk_begin[t + 1] * LARS_WAVES;
   double sw = 0.0, sg = 0.0;
   int bad = 0;
   for (int c = c0 + threadIdx.x; c < c1; c += LARS_THREADS) {
@@ -243,43 +320,59 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
     if (blockIdx.x == 0 && threadIdx.x == 0) *found_inf = -1;
     return;
   }
-  int f = 0;
-  for (int t = threadIdx.x; t < tb.T; t += LARS_THREADS) f |= tb.tflag[t];
-  f = __syncthreads_or(f);
-  if (blockIdx.x == 0 && threadIdx.x == 0) *found_inf = f ? 1 : 0;
+  int f = 0;  // every wavefront looks at all tensor flags itself: no barrier anywhere in this kernel
+  for (int t = threadIdx.x & 63; t < tb.T; t += 64) f |= tb.tflag[t];
+  f = __any(f);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *found_inf = f ? 1 : 0;
+    tb.state[0] = 1;  // skipped or not, psum_w describes the master weights as this launch leaves them
+  }
   if (f) return;  // overflow under loss scaling: the step is skipped as a whole
   if ((int)blockIdx.x >= tb.n_chunks) return;
   const int c = tb.n_chunks - 1 - blockIdx.x;
   int t;
-  int64_t s, e;
+  int64_t s, e, b0, b1;
   chunk_range(tb, c, &t, &s, &e);
+  chunk_body(s, e, &b0, &b1);
   const float coef = tb.coef[t];
   const float lam = (tb.flags[t] & JZ_PARAM_WEIGHT_DECAY) ? wd : 0.0f;
-  int64_t b0 = (s + 7) & ~int64_t(7);
-  if (b0 > e) b0 = e;
-  int64_t b1 = b0 + ((e - b0) & ~int64_t(7));
-  for (int64_t i = b0 + (int64_t)threadIdx.x * 8; i < b1; i += LARS_THREADS * 8) {
-    float4 w0 = *reinterpret_cast<const float4*>(w + i);
-    float4 w1 = *reinterpret_cast<const float4*>(w + i + 4);
-    float4 v0 = *reinterpret_cast<const float4*>(v + i);
-    float4 v1 = *reinterpret_cast<const float4*>(v + i + 4);
-    uint4 gq = *reinterpret_cast<const uint4*>(g16 + i);
-    float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-    float vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-    unsigned gw[4] = {gq.x, gq.y, gq.z, gq.w};
-    unsigned ow[4];
+  float4 w0[LARS_IT], w1[LARS_IT], v0[LARS_IT], v1[LARS_IT];
+  uint4 gq[LARS_IT];
 #pragma unroll
-    for (int j = 0; j < 8; j += 2) {
-      unsigned short h0, h1;
-      lars_step(wv[j], vv[j], (unsigned short)(gw[j >> 1] & 0xffffu), coef, lam, m, inv_s, h0);
-      lars_step(wv[j + 1], vv[j + 1], (unsigned short)(gw[j >> 1] >> 16), coef, lam, m, inv_s, h1);
-      ow[j >> 1] = (unsigned)h0 | ((unsigned)h1 << 16);
+  for (int k = 0; k < LARS_IT; ++k) {  // every load of the chunk is in flight before the first use
+    int64_t i = b0 + (int64_t)(k * LARS_THREADS + threadIdx.x) * 8;
+    if (i < b1) {
+      gq[k] = load_stream_u4(g16 + i);
+      w0[k] = load_stream_f4(w + i);
+      w1[k] = load_stream_f4(w + i + 4);
+      v0[k] = load_stream_f4(v + i);
+      v1[k] = load_stream_f4(v + i + 4);
     }
-    *reinterpret_cast<float4*>(w + i) = make_float4(wv[0], wv[1], wv[2], wv[3]);
-    *reinterpret_cast<float4*>(w + i + 4) = make_float4(wv[4], wv[5], wv[6], wv[7]);
-    *reinterpret_cast<float4*>(v + i) = make_float4(vv[0], vv[1], vv[2], vv[3]);
-    *reinterpret_cast<float4*>(v + i + 4) = make_float4(vv[4], vv[5], vv[6], vv[7]);
-    *reinterpret_cast<uint4*>(w16 + i) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+  }
+  double sw = 0.0;  // sum of squares of the new weights, in the order lars_reduce would add them
+#pragma unroll
+  for (int k = 0; k < LARS_IT; ++k) {
+    int64_t i = b0 + (int64_t)(k * LARS_THREADS + threadIdx.x) * 8;
+    if (i < b1) {
+      float wv[8] = {w0[k].x, w0[k].y, w0[k].z, w0[k].w, w1[k].x, w1[k].y, w1[k].z, w1[k].w};
+      float vv[8] = {v0[k].x, v0[k].y, v0[k].z, v0[k].w, v1[k].x, v1[k].y, v1[k].z, v1[k].w};
+      unsigned gw[4] = {gq[k].x, gq[k].y, gq[k].z, gq[k].w};
+      unsigned ow[4];
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        unsigned short h0, h1;
+        lars_step(wv[j], vv[j], (unsigned short)(gw[j >> 1] & 0xffffu), coef, lam, m, inv_s, h0);
+        lars_step(wv[j + 1], vv[j + 1], (unsigned short)(gw[j >> 1] >> 16), coef, lam, m, inv_s, h1);
+        ow[j >> 1] = (unsigned)h0 | ((unsigned)h1 << 16);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sw = fma((double)wv[j], (double)wv[j], sw);
+      store_stream_f4(w + i, wv[0], wv[1], wv[2], wv[3]);
+      store_stream_f4(w + i + 4, wv[4], wv[5], wv[6], wv[7]);
+      store_stream_f4(v + i, vv[0], vv[1], vv[2], vv[3]);
+      store_stream_f4(v + i + 4, vv[4], vv[5], vv[6], vv[7]);
+      store_stream_u4(w16 + i, ow[0], ow[1], ow[2], ow[3]);
+    }
   }
   {
     int64_t nh = b0 - s, nt = e - b1;
@@ -292,8 +385,11 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
       w[i] = wi;
       v[i] = vi;
       w16[i] = h;
+      sw = fma((double)wi, (double)wi, sw);
     }
   }
+  sw = wave_sum(sw);
+  if ((threadIdx.x & 63) == 0) tb.psum_w[c * LARS_WAVES + (threadIdx.x >> 6)] = sw;
 }
 
 Tables make_tables(const Layout& L, void* ws, uint64_t sum) {
@@ -304,6 +400,7 @@ Tables make_tables(const Layout& L, void* ws, uint64_t sum) {
   tb.chunk_begin = reinterpret_cast<const int*>(b + L.off_chunk_begin);
   tb.flags = reinterpret_cast<const int*>(b + L.off_flags);
   tb.chunk_tensor = reinterpret_cast<const int*>(b + L.off_chunk_tensor);
+  tb.state = reinterpret_cast<int*>(b + L.off_state);
   tb.psum_w = reinterpret_cast<double*>(b + L.off_psum_w);
   tb.psum_g = reinterpret_cast<double*>(b + L.off_psum_g);
   tb.pflag = reinterpret_cast<int*>(b + L.off_pflag);

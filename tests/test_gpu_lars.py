@@ -122,6 +122,43 @@ def test_three_steps_with_momentum(jz):
     assert np.count_nonzero(ps.momentum) > 0.99 * ps.P
 
 
+def test_carried_weight_norms_match_recomputed_ones_bit_for_bit(jz):
+    # The workspace carries sum(w^2) per tensor from one update to the next.  A run that re-prepares its workspace
+    # before every update (so that the norms are recomputed from the weights) must give identical bits, also across
+    # a skipped step (Inf in the gradient: nothing may change, and the carried sums must still be right afterwards).
+    import jzt
+    ps = inputs.random_param_set((0, 13), [70000, 64, 9000, 64], loss_scale=1024.0, flags=[3, 2, 3, 2], momentum_std=1e-3)
+    a, b = jzt.LarsRun(ps), jzt.LarsRun(ps)
+    for step in range(4):
+        g = inputs.normal_f16(inputs.rng_for(0, 13, step), (ps.P,), std=1e-3 * 1024.0)
+        if step == 1:
+            g[12345] = np.float16(np.inf)
+        for r in (a, b):
+            r.g.copy_(torch.from_numpy(g))
+        jz.jz_lars_prepare(b.ps, b.ws)
+        ga, gb = a.step(), b.step()
+        assert ga[3] == gb[3] == (1 if step == 1 else 0)
+        for x, y in zip(ga[:3], gb[:3]):
+            assert np.array_equal(x.view(np.uint8), y.view(np.uint8)), "step %d" % step
+        ps.grad16 = g
+        jzt.check_lars_against_oracle(ps, ga)
+        ps.master_w, ps.momentum, ps.weight16 = ga[0].copy(), ga[1].copy(), ga[2].copy()
+
+
+def test_prepare_again_after_an_outside_write_of_the_master_weights(jz):
+    import jzt
+    ps = inputs.random_param_set((0, 14), [50000, 64], loss_scale=1024.0, flags=[3, 2])
+    r = jzt.LarsRun(ps)
+    got = r.step()
+    jzt.check_lars_against_oracle(ps, got)
+    # restore different weights from outside, as a checkpoint load would, then prepare again as the header demands
+    ps2 = inputs.random_param_set((0, 15), [50000, 64], loss_scale=1024.0, flags=[3, 2])
+    r.w.copy_(torch.from_numpy(ps2.master_w)); r.v.copy_(torch.from_numpy(ps2.momentum))
+    r.g.copy_(torch.from_numpy(ps2.grad16)); r.w16.copy_(torch.from_numpy(ps2.weight16))
+    jz.jz_lars_prepare(r.ps, r.ws)
+    jzt.check_lars_against_oracle(ps2, r.step())
+
+
 def test_same_inputs_give_identical_bits(jz):
     import jzt
     ps = inputs.random_param_set((0, 11), [123457, 64, 2048], momentum_std=1e-3)
