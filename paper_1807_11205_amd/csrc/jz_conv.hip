@@ -504,29 +504,61 @@ __global__ __launch_bounds__(256) void unpack_filter_c4(const unsigned short* __
   dw[i] = dwp[(size_t)kr * KT + 4 * s + c];
 }
 
-// D16[i] = RNE16( sum_s part[s][i] ), splits added in index order (deterministic)
+// D16[i] = RNE16( sum_s part[s][i] ).  A workgroup owns 256 / G groups of four consecutive outputs and G = 2^lg
+// "split lanes": lane g adds splits g, g + G, g + 2G, ... in that order, then the G lane sums are added in lane order.
+// The order depends only on (splits, G), so the result is deterministic.  Splitting the reduction over lanes matters
+// for the small outputs that need many splits: with one thread per output group those launches were latency-bound.
 __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ part, unsigned short* __restrict__ out,
-                                                     long long MN, int splits) {
-  long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
-  if (i >= MN) return;
-  if (i + 3 < MN) {
-    float4 s = *reinterpret_cast<const float4*>(part + i);
-    for (int k = 1; k < splits; ++k) {
-      float4 t = *reinterpret_cast<const float4*>(part + (size_t)k * MN + i);
+                                                     long long MN, int splits, int lg) {
+  __shared__ float4 red[256];
+  const int G = 1 << lg, Q = 256 >> lg;
+  const int q = threadIdx.x & (Q - 1), g = threadIdx.x >> (8 - lg);
+  const long long i = ((long long)blockIdx.x * Q + q) * 4;
+  const bool full = i + 3 < MN;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < MN) {
+    if (full) {
+      int k = g;
+      for (; k + 3 * G < splits; k += 4 * G) {  // four loads in flight per thread
+        float4 t0 = *reinterpret_cast<const float4*>(part + (size_t)k * MN + i);
+        float4 t1 = *reinterpret_cast<const float4*>(part + (size_t)(k + G) * MN + i);
+        float4 t2 = *reinterpret_cast<const float4*>(part + (size_t)(k + 2 * G) * MN + i);
+        float4 t3 = *reinterpret_cast<const float4*>(part + (size_t)(k + 3 * G) * MN + i);
+        s.x += t0.x; s.y += t0.y; s.z += t0.z; s.w += t0.w;
+        s.x += t1.x; s.y += t1.y; s.z += t1.z; s.w += t1.w;
+        s.x += t2.x; s.y += t2.y; s.z += t2.z; s.w += t2.w;
+        s.x += t3.x; s.y += t3.y; s.z += t3.z; s.w += t3.w;
+      }
+      for (; k < splits; k += G) {
+        float4 t = *reinterpret_cast<const float4*>(part + (size_t)k * MN + i);
+        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+      }
+    } else {  // ragged end of the matrix: element-wise
+      float* sv = reinterpret_cast<float*>(&s);
+      for (int k = g; k < splits; k += G)
+        for (int e = 0; e < 4 && i + e < MN; ++e) sv[e] += part[(size_t)k * MN + i + e];
+    }
+  }
+  if (G > 1) {
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (g != 0) return;
+    for (int gg = 1; gg < G; ++gg) {
+      float4 t = red[gg * Q + q];
       s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
-    _Float16 h[4] = {(_Float16)s.x, (_Float16)s.y, (_Float16)s.z, (_Float16)s.w};
+  }
+  if (i >= MN) return;
+  _Float16 h[4] = {(_Float16)s.x, (_Float16)s.y, (_Float16)s.z, (_Float16)s.w};
+  if (full) {
     uint2 pk;
     __builtin_memcpy(&pk, h, 8);
     *reinterpret_cast<uint2*>(out + i) = pk;
   } else {
-    for (long long e = i; e < MN; ++e) {
-      float s = part[e];
-      for (int k = 1; k < splits; ++k) s += part[(size_t)k * MN + e];
-      _Float16 h = (_Float16)s;
-      unsigned short b;
-      __builtin_memcpy(&b, &h, 2);
-      out[e] = b;
+    for (int e = 0; e < 4 && i + e < MN; ++e) {
+      unsigned short bts;
+      __builtin_memcpy(&bts, &h[e], 2);
+      out[i + e] = bts;
     }
   }
 }
@@ -646,15 +678,17 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   int bk = (use_register_path() || igemm_bk_override() == 64) ? 64 : 32;
   g.R = d->R; g.S = d->S; g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
   g.kvalid = 0;
+  // a single filter tap: the reduction is one contiguous channel run, whose ragged last k tile the vector kernel can mask
+  const bool one_tap = d->R == 1 && d->S == 1 && !use_register_path();
   if (op == JZ_FWD) {
     a.M = d->N * P * Q; a.N = d->K; a.Kred = d->R * d->S * d->C;
     g.IH = d->H; g.IW = d->W; g.IC = d->C; g.OH = P; g.OW = Q;
-    pl->fast = d->C % bk == 0;
+    pl->fast = d->C % bk == 0 || (one_tap && d->C % 8 == 0);
     pl->bytesA = 2 * nx; pl->bytesB = 2 * nw; pl->bytesD = 2 * ny;
   } else if (op == JZ_BWD_DATA) {
     a.M = d->N * d->H * d->W; a.N = d->C; a.Kred = d->R * d->S * d->K;
     g.IH = P; g.IW = Q; g.IC = d->K; g.OH = d->H; g.OW = d->W;
-    pl->fast = d->K % bk == 0 && d->C % 8 == 0;
+    pl->fast = (d->K % bk == 0 || (one_tap && d->K % 8 == 0)) && d->C % 8 == 0;
     pl->bytesA = 2 * ny; pl->bytesB = 2 * nw; pl->bytesD = 2 * nx;
   } else {
     a.M = d->K; a.N = d->R * d->S * d->C; a.Kred = d->N * P * Q;
@@ -827,8 +861,12 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
   if (rc != JZ_OK) return rc;
   if (a.splits > 1) {
     long long MN = (long long)a.M * a.N;
-    unsigned blocks = (unsigned)((MN + 1023) / 1024);
-    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, a.Dpart, a.D16, MN, a.splits);
+    // split lanes per output group: enough workgroups to cover the chip first, then shorten each thread's chain
+    int lg = 0;
+    while (lg < 5 && (2 << lg) <= a.splits && ((MN + 3) / 4 + (256 >> lg) - 1) / (256 >> lg) < 1024) ++lg;
+    const long long per_block = 256 >> lg;
+    unsigned blocks = (unsigned)(((MN + 3) / 4 + per_block - 1) / per_block);
+    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, a.Dpart, a.D16, MN, a.splits, lg);
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
   }
   if (dwp) {

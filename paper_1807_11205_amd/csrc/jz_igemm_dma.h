@@ -213,7 +213,9 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     TileCtx c;
     c.k0 = kt * TBK;
     c.tap = 0; c.c0 = 0; c.r = 0; c.s = 0; c.tapoff = 0; c.tileoff = 0;
-    if (OP != OP_BWD_WEIGHT) {  // the whole tile lies inside one filter tap (IC % TBK == 0): wave-uniform values
+    // the whole tile lies inside one filter tap: wave-uniform values.  Either IC % TBK == 0, or there is only one tap
+    // (1x1 layers, fully connected) and the last tile is ragged: chunks at or beyond IC are then not requested.
+    if (OP != OP_BWD_WEIGHT) {
       c.tap = fd_div((unsigned)c.k0, g.d_ic);
       c.c0 = c.k0 - (int)c.tap * g.IC;
       c.r = (int)fd_div(c.tap, g.d_s);
@@ -232,14 +234,15 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
         constexpr int ii = Lidx;
         if constexpr (OP == OP_FWD) {
           int ih = sa1[ii] + c.r, iw = sa2[ii] + c.s;
-          bool ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+          bool ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW && c.c0 + kc_chunk * 8 < g.IC;
           jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? sa0[ii] + c.tapoff : OOB);
         } else if constexpr (OP == OP_BWD_DATA) {
           // input pixel (h,w) receives from output pixel ((h + pad - r) / stride, ...) when the division is exact
           int th = sa1[ii] - c.r, tw = sa2[ii] - c.s;
           int ih = (int)fd_div((unsigned)(th < 0 ? 0 : th), g.d_sh);
           int iw = (int)fd_div((unsigned)(tw < 0 ? 0 : tw), g.d_sw);
-          bool ok = ih * g.sh == th && iw * g.sw == tw && ih < g.IH && iw < g.IW;  // false for negative th / tw too
+          bool ok = ih * g.sh == th && iw * g.sw == tw && ih < g.IH && iw < g.IW &&  // false for negative th / tw too
+                    c.c0 + kc_chunk * 8 < g.IC;
           unsigned off = (sa0[ii] + (unsigned)(ih * g.row_pitch + iw * g.pix_step + c.c0 + kc_chunk * 8)) * 2u;
           jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? off : OOB);
         } else {  // dy rows j = k0 + k
@@ -250,9 +253,11 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
       } else {
         constexpr int ii = Lidx - LA;
         if constexpr (OP == OP_FWD) {
-          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + (unsigned)c.k0 * 2u);
+          const bool ok = sb0[ii] != OOB && c.k0 + kc_chunk * 8 < a.Kred;
+          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? sb0[ii] + (unsigned)c.k0 * 2u : OOB);
         } else if constexpr (OP == OP_BWD_DATA) {
-          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, sb0[ii] == OOB ? OOB : sb0[ii] + c.tileoff);
+          const bool ok = sb0[ii] != OOB && c.c0 + mc_k(BN, ii) < g.IC;
+          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? sb0[ii] + c.tileoff : OOB);
         } else {  // x at this lane's tap for output pixel j
           int j = c.k0 + mc_k(BN, ii);
           unsigned n = fd_div((unsigned)j, g.d_ohow);

@@ -77,6 +77,9 @@ VECTOR = [
     (4, 7, 7, 192, 320, 3, 3, 1, 1),       # deep reduction, few pixels: split-K in fwd / bwd_data
     (1, 8, 8, 64, 8, 1, 1, 1, 0),          # K = 8: vector path of backward-weight with a tiny m
     (2, 6, 10, 128, 200, 3, 1, 1, (1, 0)), # R != S, H != W, K not a multiple of 64 (bwd_data falls back)
+    (3, 10, 10, 40, 24, 1, 1, 1, 0),       # 1x1 with channel counts that are multiples of 8 only: ragged last k tile
+    (2, 9, 9, 72, 40, 1, 1, 2, 0),         # the same with stride 2 (scatter epilogue in backward-data)
+    (2, 5, 5, 1000, 136, 1, 1, 1, 0),      # long ragged reduction (31 full k tiles + 8 channels)
 ]
 
 
