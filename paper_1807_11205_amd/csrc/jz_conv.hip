@@ -115,23 +115,25 @@ __device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[
 // ---------------------------------------------------------------------------------------------
 // epilogue shared by both kernels: fp32 partial sums (split-K) or the single rounding to fp16
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int TM, int TN>
+// wrow / wcol: first row / column of this wavefront's share inside the BM x BN tile; NTHREADS: workgroup size;
+// EPASS: the fp16 tile is staged through LDS in EPASS slabs of BM / EPASS rows (a 256x256 tile is larger than the ring)
+template <int BM, int BN, int TM, int TN, int NTHREADS, int EPASS = 1>
 __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&acc)[TM][TN], unsigned short* lds, int m0,
-                                                    int n0, int split, int tid, int lane, int wm, int wn) {
+                                                    int n0, int split, int tid, int lane, int wrow, int wcol) {
   // ---- epilogue ------------------------------------------------------------------------------
-  // accumulator register r of tile (i,j): m = wm*BM/2 + 32 i + lane%32, n = wn*BN/2 + 32 j + 8 (r/4) + 4 (lane/32) + r%4
+  // accumulator register r of tile (i,j): m = wrow + 32 i + lane%32, n = wcol + 32 j + 8 (r/4) + 4 (lane/32) + r%4
   if (a.splits > 1) {
     float* P = a.Dpart + (size_t)split * a.M * a.N;
     const bool vec = (a.N & 3) == 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      int m = m0 + wm * (BM / 2) + 32 * i + (lane & 31);
+      int m = m0 + wrow + 32 * i + (lane & 31);
       if (m >= a.M) continue;
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          int n = n0 + wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
+          int n = n0 + wcol + 32 * j + 8 * q4 + 4 * (lane >> 5);
           float* dst = P + (size_t)m * a.N + n;
           if (vec && n + 3 < a.N) {
             *reinterpret_cast<float4*>(dst) =
@@ -147,57 +149,66 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
   }
   // single rounding fp32 -> fp16 (round to nearest even), staged through LDS for 16-byte coalesced stores
   constexpr int LDC = BN + 8;
+  constexpr int RPB = BM / EPASS;  // rows per slab
+  static_assert(RPB * EPASS == BM && RPB % (32 * TM) == 0, "a wavefront's rows must lie inside one slab");
   unsigned short* sC = lds;  // the k loop ended with a barrier: the tile buffers are free
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        int row = wm * (BM / 2) + 32 * i + (lane & 31);
-        int col = wn * (BN / 2) + 32 * j + 8 * q4 + 4 * (lane >> 5);
-        _Float16 h[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[i][j][4 * q4 + e];
-        uint2 pk;
-        __builtin_memcpy(&pk, h, 8);
-        *reinterpret_cast<uint2*>(sC + row * LDC + col) = pk;
-      }
-  __syncthreads();
   constexpr int CCH = BN / 8;             // 16-byte chunks per output row
-  constexpr int CRPP = THREADS / CCH;     // rows per pass
+  constexpr int CRPP = NTHREADS / CCH;    // rows per pass
+  static_assert(RPB % CRPP == 0, "slab rows must divide among the store passes");
   const int cch = tid % CCH, crow = tid / CCH;
   const bool nvec = (a.N & 7) == 0;
 #pragma unroll
-  for (int i = 0; i < BM / CRPP; ++i) {
-    int row = crow + CRPP * i;
-    int m = m0 + row, n = n0 + cch * 8;
-    if (m >= a.M || n >= a.N) continue;
-    const unsigned short* src = sC + row * LDC + cch * 8;
-    size_t drow = (size_t)m;
-    if (a.sc_on) {  // row m = (n, p, q) of the strided grid goes to input pixel (n, p * sh, q * sw)
-      unsigned nimg = fd_div((unsigned)m, a.g.d_ohow);
-      unsigned rem = (unsigned)m - nimg * (unsigned)(a.g.OH * a.g.OW);
-      unsigned p = fd_div(rem, a.g.d_ow);
-      unsigned q = rem - p * (unsigned)a.g.OW;
-      drow = ((size_t)nimg * a.sc_H + p * a.sc_sh) * a.sc_W + q * a.sc_sw;
-      // the other pixels of this sh x sw cell are read by no output pixel: their gradient is zero
-      for (int i2 = 0; i2 < a.sc_sh; ++i2)
-        for (int j2 = 0; j2 < a.sc_sw; ++j2) {
-          if ((i2 | j2) == 0 || (int)(p * a.sc_sh) + i2 >= a.sc_H || (int)(q * a.sc_sw) + j2 >= a.sc_W) continue;
-          unsigned short* z = a.D16 + (drow + (size_t)i2 * a.sc_W + j2) * a.N + n;
-          if (nvec) {
-            *reinterpret_cast<uint4*>(z) = make_uint4(0, 0, 0, 0);
-          } else {
-            for (int e = 0; e < 8 && n + e < a.N; ++e) z[e] = 0;
+  for (int ps = 0; ps < EPASS; ++ps) {
+    if (ps > 0) __syncthreads();  // the previous slab has been stored
+    if (EPASS == 1 || wrow / RPB == ps) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            int row = wrow - ps * RPB + 32 * i + (lane & 31);
+            int col = wcol + 32 * j + 8 * q4 + 4 * (lane >> 5);
+            _Float16 h[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[i][j][4 * q4 + e];
+            uint2 pk;
+            __builtin_memcpy(&pk, h, 8);
+            *reinterpret_cast<uint2*>(sC + row * LDC + col) = pk;
           }
-        }
     }
-    unsigned short* dst = a.D16 + drow * a.N + n;
-    if (nvec) {
-      *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
-    } else {
-      for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = src[e];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < RPB / CRPP; ++i) {
+      int row = crow + CRPP * i;
+      int m = m0 + ps * RPB + row, n = n0 + cch * 8;
+      if (m >= a.M || n >= a.N) continue;
+      const unsigned short* src = sC + row * LDC + cch * 8;
+      size_t drow = (size_t)m;
+      if (a.sc_on) {  // row m = (n, p, q) of the strided grid goes to input pixel (n, p * sh, q * sw)
+        unsigned nimg = fd_div((unsigned)m, a.g.d_ohow);
+        unsigned rem = (unsigned)m - nimg * (unsigned)(a.g.OH * a.g.OW);
+        unsigned p = fd_div(rem, a.g.d_ow);
+        unsigned q = rem - p * (unsigned)a.g.OW;
+        drow = ((size_t)nimg * a.sc_H + p * a.sc_sh) * a.sc_W + q * a.sc_sw;
+        // the other pixels of this sh x sw cell are read by no output pixel: their gradient is zero
+        for (int i2 = 0; i2 < a.sc_sh; ++i2)
+          for (int j2 = 0; j2 < a.sc_sw; ++j2) {
+            if ((i2 | j2) == 0 || (int)(p * a.sc_sh) + i2 >= a.sc_H || (int)(q * a.sc_sw) + j2 >= a.sc_W) continue;
+            unsigned short* z = a.D16 + (drow + (size_t)i2 * a.sc_W + j2) * a.N + n;
+            if (nvec) {
+              *reinterpret_cast<uint4*>(z) = make_uint4(0, 0, 0, 0);
+            } else {
+              for (int e = 0; e < 8 && n + e < a.N; ++e) z[e] = 0;
+            }
+          }
+      }
+      unsigned short* dst = a.D16 + drow * a.N + n;
+      if (nvec) {
+        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+      } else {
+        for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = src[e];
+      }
     }
   }
 }
@@ -205,7 +216,7 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
 template <int BM, int BN>
 __device__ __forceinline__ void igemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / 64][BN / 64], unsigned short* lds,
                                                int m0, int n0, int split, int tid, int lane, int wm, int wn) {
-  igemm_epilogue_impl<BM, BN, BM / 64, BN / 64>(a, acc, lds, m0, n0, split, tid, lane, wm, wn);
+  igemm_epilogue_impl<BM, BN, BM / 64, BN / 64, THREADS>(a, acc, lds, m0, n0, split, tid, lane, wm * (BM / 2), wn * (BN / 2));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -590,6 +601,7 @@ struct Plan {
   bool packed = false;  // small-channel layer run on a 4-channel padded copy
   int BM = 128, BN = 128;
   int bk = BK;  // k tile depth of the kernel that will run
+  int waves = 4, nst = 4;  // wavefronts per workgroup and ring depth (large tiles come in several variants)
   GemmArgs args{};
   size_t ws_bytes = 0;       // total workspace
   size_t part_offset = 0;    // where the split-K partial sums start inside it
@@ -602,45 +614,72 @@ struct Plan {
 int out_dim(int in, int pad, int f, int st) { return (in + 2 * pad - f) / st + 1; }
 size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
-// Pick the output tile and the split of the reduction with a small cost model (times in microseconds):
-//   GEMM part   = rounds of resident workgroups * k tiles per workgroup * time per k tile of that tile shape
-//   split part  = writing and re-reading the fp32 partial sums, plus one more launch
-// Two workgroups fit a compute unit, so 512 are resident at once.
-void choose_tiling(Plan* pl) {
+// Pick the kernel variant (output tile, k tile depth, wavefronts per workgroup) and the split of the reduction with a
+// small cost model, in microseconds:
+//   time = fixed + rounds of resident workgroups * k tiles per workgroup * time per k tile of that variant
+//          + (split > 1: writing and re-reading the fp32 partial sums, plus one more launch)
+// The per-k-tile constants are least-squares fits to timings of the ResNet-50 layer shapes at batch 64 with cold
+// caches; the fixed part is kept the same for all variants (per-variant fits of it were noise and chose worse).  The
+// 4-wavefront variants run two workgroups per compute unit (512 resident), the 8-wavefront ones a single workgroup
+// that owns the whole LDS (256 resident); the latter win when the grid cannot fill 512 slots anyway.
+struct Variant {
+  int BM, BN, bk, waves, resident;
+  double tt[3];  // per k tile: forward, backward-data, backward-weight
+  double c0[3];  // fixed part
+};
+const Variant kVariants[] = {
+    {128, 128, 32, 4, 512, {0.387, 0.525, 0.450}, {8.0, 8.0, 6.0}},
+    {128, 64, 32, 4, 512, {0.310, 0.356, 0.306}, {8.0, 8.0, 6.0}},
+    {64, 128, 32, 4, 512, {0.292, 0.310, 0.354}, {8.0, 8.0, 6.0}},
+    {64, 64, 32, 4, 512, {0.218, 0.217, 0.240}, {8.0, 8.0, 6.0}},
+    {128, 128, 64, 8, 256, {0.516, 0.667, 0.615}, {8.0, 8.0, 6.0}},
+    {256, 128, 64, 8, 256, {0.785, 1.001, 0.918}, {8.0, 8.0, 6.0}},
+    {256, 128, 32, 8, 256, {0.500, 0.567, 0.504}, {8.0, 8.0, 6.0}},
+    {256, 256, 32, 8, 256, {0.813, 0.919, 0.724}, {8.0, 8.0, 6.0}},
+};
+
+// bk64_ok: the 64-deep k tile is usable for this layer; forced_bk: the k tile depth is fixed (register path, packed mode)
+void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk) {
   GemmArgs& a = pl->args;
-  const int bk = pl->bk;
-  a.nkt = (a.Kred + bk - 1) / bk;
-  if (!pl->fast) {  // the element-wise kernel exists for one shape only
-    pl->BM = pl->BN = 128;
-  }
-  static const int shapes[4][2] = {{128, 128}, {128, 64}, {64, 128}, {64, 64}};
-  static const double t_tile32[4] = {0.60, 0.36, 0.36, 0.22};  // per 32-deep k tile at two workgroups per CU
   static const int split_opts[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128};
+  const int oi = pl->op == JZ_FWD ? 0 : pl->op == JZ_BWD_DATA ? 1 : 2;
   double best = 1e30;
-  int bBM = 128, bBN = 128, bS = 1;
-  for (int si = 0; si < 4; ++si) {
-    int BM_ = shapes[si][0], BN_ = shapes[si][1];
-    if (!pl->fast && si != 0) break;
-    if (pl->packed && pl->op == JZ_FWD && BM_ != 128) continue;  // the masked kernels exist for BM = 128 only
-    if (igemm_tile_override() && igemm_tile_override() != BM_ * 1000 + BN_ && pl->fast) continue;
-    long long tm = (a.M + BM_ - 1) / BM_, tn = (a.N + BN_ - 1) / BN_;
-    double tt = t_tile32[si] * (bk / 32.0) * (pl->fast ? 1.0 : 8.0);
-    for (int sp : split_opts) {
-      if (sp > 1 && a.nkt / sp < 4) break;
-      if (igemm_splits_override() && sp != igemm_splits_override() && !(sp == 1 && a.nkt / igemm_splits_override() < 4)) continue;
-      long long blocks = tm * tn * sp;
-      long long rounds = (blocks + 511) / 512;
-      if (a.sc_on && sp > 1) break;  // the scatter lives in the fp16 epilogue
-      double kps = (double)((a.nkt + sp - 1) / sp);
-      double gemm = rounds * kps * tt * (blocks <= 256 ? 0.7 : 1.0) + 3.0;
-      double split = sp > 1 ? (2.0 * sp * (double)a.M * a.N * 4.0) / 3.0e6 + 4.0 : 0.0;
-      double t = gemm + split;
-      if (t < best) { best = t; bBM = BM_; bBN = BN_; bS = sp; }
+  const Variant* bv = &kVariants[0];
+  int bS = 1;
+  if (!pl->fast) forced_bk = BK;  // the element-wise kernel: one shape (the first variant's), 64-deep tiles, ~8x slower
+  {
+    for (const Variant& v : kVariants) {
+      if (!pl->fast && &v != &kVariants[0]) break;
+      if (forced_bk && (v.waves != 4 || v.bk != 32)) continue;  // those kernels exist as 4-wavefront variants only
+      if (pl->packed && pl->op == JZ_FWD && v.BM != 128) continue;  // the masked kernels exist for BM = 128 only
+      if (!forced_bk && v.bk == 64 && !bk64_ok) continue;
+      if (!forced_bk && igemm_bk_override() && igemm_bk_override() != v.bk) continue;
+      if (igemm_tile_override() && igemm_tile_override() != v.BM * 1000 + v.BN) continue;
+      if (env_int("JZ_IGEMM_WAVES") && env_int("JZ_IGEMM_WAVES") != v.waves) continue;
+      const int vbk = forced_bk ? forced_bk : v.bk;
+      const int nkt = (a.Kred + vbk - 1) / vbk;
+      long long tm = (a.M + v.BM - 1) / v.BM, tn = (a.N + v.BN - 1) / v.BN;
+      for (int sp : split_opts) {
+        if (sp > 1 && nkt / sp < 4) break;
+        if (a.sc_on && sp > 1) break;  // the scatter lives in the fp16 epilogue
+        if (igemm_splits_override() && sp != igemm_splits_override() && !(sp == 1 && nkt / igemm_splits_override() < 4)) continue;
+        const int kps = (nkt + sp - 1) / sp;
+        long long blocks = tm * tn * ((nkt + kps - 1) / kps);
+        long long rounds = (blocks + v.resident - 1) / v.resident;
+        double t = v.c0[oi] + rounds * kps * v.tt[oi] * (vbk / (double)v.bk) * (pl->fast ? 1.0 : 8.0);
+        if (sp > 1) t += 0.16 * (2.0 * sp * (double)a.M * a.N * 4.0) / 1.0e6 + 4.0;
+        if (t < best) { best = t; bv = &v; bS = sp; }
+      }
     }
+    if (best == 1e30) bv = &kVariants[0];  // contradictory overrides: fall back to the default variant
+    pl->BM = bv->BM; pl->BN = bv->BN;
+    pl->bk = forced_bk ? forced_bk : bv->bk;
+    pl->waves = bv->waves;
+    pl->nst = bv->bk == 64 && bv->BM == 256 ? 3 : 4;
   }
-  pl->BM = bBM; pl->BN = bBN;
-  a.tiles_m = (a.M + bBM - 1) / bBM;
-  a.tiles_n = (a.N + bBN - 1) / bBN;
+  a.nkt = (a.Kred + pl->bk - 1) / pl->bk;
+  a.tiles_m = (a.M + pl->BM - 1) / pl->BM;
+  a.tiles_n = (a.N + pl->BN - 1) / pl->BN;
   a.kt_per_split = (a.nkt + bS - 1) / bS;
   a.splits = (a.nkt + a.kt_per_split - 1) / a.kt_per_split;  // drop empty splits
 }
@@ -675,7 +714,11 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   pl->op = op;
   // k tile depth: 32 lets two workgroups share a compute unit (64 KB ring each), which hides one workgroup's
   // barrier and LDS-latency bubbles behind the other's MFMAs
-  int bk = (use_register_path() || igemm_bk_override() == 64) ? 64 : 32;
+  // k tile depth for the applicability checks: the register path walks 64-deep tiles; the LDS-direct kernels come
+  // 32 and 64 deep (chosen by the planner when the layer allows both)
+  int bk = use_register_path() ? 64 : 32;
+  bool bk64_ok = true;
+  int forced_bk = use_register_path() ? 64 : 0;
   g.R = d->R; g.S = d->S; g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
   g.kvalid = 0;
   // a single filter tap: the reduction is one contiguous channel run, whose ragged last k tile the vector kernel can mask
@@ -684,11 +727,13 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
     a.M = d->N * P * Q; a.N = d->K; a.Kred = d->R * d->S * d->C;
     g.IH = d->H; g.IW = d->W; g.IC = d->C; g.OH = P; g.OW = Q;
     pl->fast = d->C % bk == 0 || (one_tap && d->C % 8 == 0);
+    bk64_ok = d->C % 64 == 0 || (one_tap && d->C % 8 == 0);
     pl->bytesA = 2 * nx; pl->bytesB = 2 * nw; pl->bytesD = 2 * ny;
   } else if (op == JZ_BWD_DATA) {
     a.M = d->N * d->H * d->W; a.N = d->C; a.Kred = d->R * d->S * d->K;
     g.IH = P; g.IW = Q; g.IC = d->K; g.OH = d->H; g.OW = d->W;
     pl->fast = (d->K % bk == 0 || (one_tap && d->K % 8 == 0)) && d->C % 8 == 0;
+    bk64_ok = d->K % 64 == 0 || (one_tap && d->K % 8 == 0);
     pl->bytesA = 2 * ny; pl->bytesB = 2 * nw; pl->bytesD = 2 * nx;
   } else {
     a.M = d->K; a.N = d->R * d->S * d->C; a.Kred = d->N * P * Q;
@@ -729,6 +774,7 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
         a.Kred = d->R * KT;
         g.kvalid = 4 * d->S;
         bk = KT;
+        forced_bk = KT;
       } else {
         a.N = d->R * KT;
       }
@@ -737,7 +783,8 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   finish_geometry(g);
   if (!pl->fast) bk = BK;  // the element-wise kernel walks 64-deep tiles
   pl->bk = bk;
-  choose_tiling(pl);
+  if (pl->packed && !forced_bk) forced_bk = 32;  // small-channel backward-weight: 4-wavefront 32-deep kernels
+  choose_tiling(pl, bk64_ok, forced_bk);
   const size_t part = a.splits > 1 ? (size_t)a.splits * a.M * a.N * sizeof(float) : 0;
   pl->part_offset = pl->packed ? pl->xp_bytes + pl->wp_bytes : 0;
   pl->ws_bytes = pl->part_offset + part;
@@ -765,20 +812,21 @@ int launch_one(const GemmArgs& a, hipStream_t st) {
   return jz::launch_status();
 }
 
-template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false>
+template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2>
 int launch_dma(const GemmArgs& a, hipStream_t st) {
   constexpr size_t ring_bytes = (size_t)NST * (BM + BN) * 2 * TBK;
-  constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(unsigned short);
+  constexpr size_t epi_bytes = (size_t)BM / dma_epass(BM, BN) * (BN + 8) * sizeof(unsigned short);
   constexpr size_t smem = ring_bytes > epi_bytes ? ring_bytes : epi_bytes;
+  static_assert(smem <= 160 * 1024, "more LDS than a compute unit has");
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA, WGM, WGN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return JZ_ERR_LAUNCH;
     attr_set = true;
   }
   unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.splits;
-  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA>), dim3(grid), dim3(THREADS), smem, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA, WGM, WGN>), dim3(grid), dim3(64 * WGM * WGN), smem, st, a);
   return jz::launch_status();
 }
 
@@ -797,6 +845,17 @@ int launch_op(const Plan& pl, hipStream_t st) {
     return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
   }
   if (!use_register_path()) {
+    // large tiles, one workgroup of 8 wavefronts per compute unit with (nearly) the whole LDS as its ring
+    if (pl.BM == 256 && pl.BN == 256 && pl.bk == 32) {  // 2x4 wavefronts of 128x64
+      if (pl.nst == 5) return launch_dma<OP, 256, 256, 32, 5, false, 2, 4>(a, st);
+      return launch_dma<OP, 256, 256, 32, 4, false, 2, 4>(a, st);
+    }
+    if (pl.BM == 256 && pl.BN == 128 && pl.bk == 64) return launch_dma<OP, 256, 128, 64, 3, false, 4, 2>(a, st);
+    if (pl.BM == 128 && pl.BN == 128 && pl.bk == 64 && pl.waves == 8) return launch_dma<OP, 128, 128, 64, 4, false, 4, 2>(a, st);
+    if (pl.BM == 256 && pl.BN == 128 && pl.bk == 32) {  // 4x2 wavefronts of 64x64
+      if (pl.nst == 4) return launch_dma<OP, 256, 128, 32, 4, false, 4, 2>(a, st);
+      return launch_dma<OP, 256, 128, 32, 6, false, 4, 2>(a, st);
+    }
     if (pl.bk == 64) {
       if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 64, 4>(a, st);
       if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 64, 4>(a, st);

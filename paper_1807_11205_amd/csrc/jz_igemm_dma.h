@@ -49,24 +49,18 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 #endif
 }
-// Wait until at most KEEP LDS reads are outstanding.  The operands about to be consumed are named as in/out so that
-// the MFMAs using them cannot be scheduled above the wait.
+// Wait until at most KEEP LDS reads are outstanding ...
 template <int KEEP>
-__device__ __forceinline__ void lds_settle(half8& a, half8& b) {
+__device__ __forceinline__ void lds_wait() {
 #if defined(__HIP_DEVICE_COMPILE__)
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(KEEP));
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(KEEP));
 #endif
 }
-template <int KEEP>
-__device__ __forceinline__ void lds_settle(half8& a, half8& b, half8& c) {
+// ... and tie an operand to that point: volatile asm statements keep their order, and an MFMA that consumes the
+// "output" of this empty statement cannot be scheduled above it (hence not above the wait either).
+__device__ __forceinline__ void lds_pin(half8& v) {
 #if defined(__HIP_DEVICE_COMPILE__)
-  asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(KEEP));
-#endif
-}
-template <int KEEP>
-__device__ __forceinline__ void lds_settle(half8& a, half8& b, half8& c, half8& d) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(KEEP));
+  asm volatile("" : "+v"(v));
 #endif
 }
 
@@ -82,17 +76,27 @@ __device__ __forceinline__ void jz_dma16(__amdgpu_buffer_rsrc_t rsrc, lds_byte* 
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, (int)voff, 0, 0, 0);
 }
 
-template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false>
-__global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
+// slabs the epilogue stages the fp16 tile in: its staging buffer has to fit the ring
+constexpr int dma_epass(int bm, int bn) { return bm * (bn + 8) * 2 > 128 * 1024 ? 2 : 1; }
+
+// WGM x WGN wavefronts share a BM x BN output tile; each owns (BM / WGM) x (BN / WGN) of it.  The larger a
+// wavefront's share, the fewer LDS bytes it reads per MFMA (a 128x64 share: 6 operand reads for 8 MFMAs per k step,
+// a 64x64 share: 4 for 4), and the larger the workgroup's tile, the fewer bytes come in from L2 per flop.
+template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2>
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   static_assert(TBK == 32 || TBK == 64, "k tile depth");
   constexpr bool A_KC = OP != OP_BWD_WEIGHT;  // A has k contiguous in memory
   constexpr bool B_KC = OP == OP_FWD;
-  constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA tiles per wavefront (2x2 wavefronts per workgroup)
+  constexpr int NW = WGM * WGN, NT = 64 * NW;  // wavefronts, threads
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // a wavefront's share of the tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;    // ... as 32x32 MFMA tiles
+  static_assert(TM >= 1 && TN >= 1 && TM * 32 * WGM == BM && TN * 32 * WGN == BN, "tile / wavefront grid mismatch");
   constexpr int NKS = TBK / 16;               // MFMA k steps per tile
   constexpr int RB = 2 * TBK;                 // bytes per row of a KC tile
   constexpr int CR = TBK / 8;                 // 16-byte chunks per row of a KC tile
   constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
-  constexpr int LA = BM * CR / 256, LB = BN * CR / 256;  // LDS-direct loads per thread per tile and operand
+  constexpr int LA = BM * CR / NT, LB = BN * CR / NT;  // LDS-direct loads per thread per tile and operand
+  static_assert(LA * NT == BM * CR && LB * NT == BN * CR, "tile does not divide among the loaders");
   static_assert(LA >= 1 && LB >= 1, "tile too small for the loader");
   constexpr int LPT = LA + LB;
   extern __shared__ __align__(16) unsigned short lds[];
@@ -101,7 +105,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
 
   const ConvGeom& g = a.g;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   unsigned L = xcd_remap(blockIdx.x, gridDim.x);
   const int tiles_mn = a.tiles_m * a.tiles_n;
@@ -118,18 +122,19 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   constexpr unsigned OOB = 0xffffffffu;
 
   // ---- loader geometry ---------------------------------------------------------------------
-  // KC tile: one load covers 64 / CR rows; load ii of wave w covers rows (4 ii + w) * (64 / CR) + lane / CR and the
+  // KC tile: one load covers 64 / CR rows; load ii of wave w covers rows (NW ii + w) * (64 / CR) + lane / CR and the
   // lane's LDS slot is chunk position lane % CR, so it fetches global chunk (lane % CR) ^ swizzle(row).  The swizzle
   // ((row >> 1) & 7 for 128-byte rows, (row >> 2) & 3 for 64-byte rows) is the same for every ii and sends any 16
   // consecutive rows' copies of one chunk to 16 different 16-byte bank groups.
   constexpr int KC_RPI = 64 / CR;
-  const int kc_row = wave * KC_RPI + lane / CR;  // + 4 * KC_RPI * ii
+  const int kc_row = wave * KC_RPI + lane / CR;  // + NW * KC_RPI * ii
   const int kc_chunk = (lane % CR) ^ (TBK == 64 ? ((kc_row >> 1) & 7) : ((kc_row >> 2) & 3));
   // MC tile with ROWS mn: CPR = ROWS / 8 chunks per k-row, 64 / CPR k-rows per load
-  auto mc_k = [&](int rows, int ii) { int cpr = rows / 8; return (4 * ii + wave) * (64 / cpr) + lane / cpr; };
+  // (k & 7 is the same for every load ii of a lane: NW * (64 / cpr) is a multiple of 8)
+  auto mc_k = [&](int rows, int ii) { int cpr = rows / 8; return (NW * ii + wave) * (64 / cpr) + lane / cpr; };
   auto mc_chunk = [&](int rows, int k) {
     int cpr = rows / 8;
-    int swz = cpr == 16 ? 2 * (k & 7) : 2 * (k & 3);
+    int swz = cpr >= 16 ? 2 * (k & 7) : 2 * (k & 3);
     return (lane % cpr) ^ swz;
   };
 
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   if (OP != OP_BWD_WEIGHT) {  // A rows are pixels of the (n, OH, OW) grid
 #pragma unroll
     for (int ii = 0; ii < LA; ++ii) {
-      int m = m0 + 4 * KC_RPI * ii + kc_row;
+      int m = m0 + NW * KC_RPI * ii + kc_row;
       if (m < a.M) {
         unsigned n = fd_div((unsigned)m, g.d_ohow);
         unsigned rem = (unsigned)m - n * (unsigned)(g.OH * g.OW);
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   if (OP == OP_FWD) {
 #pragma unroll
     for (int ii = 0; ii < LB; ++ii) {
-      int nn = n0 + 4 * KC_RPI * ii + kc_row;
+      int nn = n0 + NW * KC_RPI * ii + kc_row;
       sb0[ii] = nn < a.N ? (unsigned)(nn * a.Kred + kc_chunk * 8) * 2u : OOB;
     }
   } else if (OP == OP_BWD_DATA) {
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
         if constexpr (OP == OP_FWD) {
           int ih = sa1[ii] + c.r, iw = sa2[ii] + c.s;
           bool ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW && c.c0 + kc_chunk * 8 < g.IC;
-          jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? sa0[ii] + c.tapoff : OOB);
+          jz_dma16(rsrcA, sA + (NW * ii + wave) * 1024, ok ? sa0[ii] + c.tapoff : OOB);
         } else if constexpr (OP == OP_BWD_DATA) {
           // input pixel (h,w) receives from output pixel ((h + pad - r) / stride, ...) when the division is exact
           int th = sa1[ii] - c.r, tw = sa2[ii] - c.s;
@@ -244,20 +249,20 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
           bool ok = ih * g.sh == th && iw * g.sw == tw && ih < g.IH && iw < g.IW &&  // false for negative th / tw too
                     c.c0 + kc_chunk * 8 < g.IC;
           unsigned off = (sa0[ii] + (unsigned)(ih * g.row_pitch + iw * g.pix_step + c.c0 + kc_chunk * 8)) * 2u;
-          jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, ok ? off : OOB);
+          jz_dma16(rsrcA, sA + (NW * ii + wave) * 1024, ok ? off : OOB);
         } else {  // dy rows j = k0 + k
           int j = c.k0 + mc_k(BM, ii);
           unsigned off = (sam != OOB && j < a.Kred) ? sam + (unsigned)(j * a.M) * 2u : OOB;
-          jz_dma16(rsrcA, sA + (4 * ii + wave) * 1024, off);
+          jz_dma16(rsrcA, sA + (NW * ii + wave) * 1024, off);
         }
       } else {
         constexpr int ii = Lidx - LA;
         if constexpr (OP == OP_FWD) {
           const bool ok = sb0[ii] != OOB && c.k0 + kc_chunk * 8 < a.Kred;
-          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? sb0[ii] + (unsigned)c.k0 * 2u : OOB);
+          jz_dma16(rsrcB, sB + (NW * ii + wave) * 1024, ok ? sb0[ii] + (unsigned)c.k0 * 2u : OOB);
         } else if constexpr (OP == OP_BWD_DATA) {
           const bool ok = sb0[ii] != OOB && c.c0 + mc_k(BN, ii) < g.IC;
-          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? sb0[ii] + c.tileoff : OOB);
+          jz_dma16(rsrcB, sB + (NW * ii + wave) * 1024, ok ? sb0[ii] + c.tileoff : OOB);
         } else {  // x at this lane's tap for output pixel j
           int j = c.k0 + mc_k(BN, ii);
           unsigned n = fd_div((unsigned)j, g.d_ohow);
@@ -267,7 +272,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
           int ih = p * g.sh + sb1, iw = q * g.sw + sb2;
           bool ok = j < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
           unsigned off = (unsigned)(((int)n * g.IH + ih) * g.row_pitch + iw * g.pix_step + sbc) * 2u;
-          jz_dma16(rsrcB, sB + (4 * ii + wave) * 1024, ok ? off : OOB);
+          jz_dma16(rsrcB, sB + (NW * ii + wave) * 1024, ok ? off : OOB);
         }
       }
     }
@@ -298,7 +303,7 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   // MC: 16-lane group gi = lane / 16 handles mn half gi % 2 and k block gi / 2 of the 32x16 operand; lane 4 j + c4
   //     of the group addresses k-row j, the 8-byte piece c4 of those 16 mn.  One address per (sub-tile t, k half),
   //     ks advances by 16 k-rows (immediate offset).
-  unsigned adA[4], adB[4];
+  unsigned adA[(A_KC ? NKS : 2 * TM)], adB[(B_KC ? NKS : 2 * TN)];
   {
     const int r31 = lane & 31, hi = lane >> 5;
     const int gi = lane >> 4, j = (lane >> 2) & 3, c4 = lane & 3;
@@ -306,32 +311,32 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     if (A_KC) {
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks)
-        adA[ks] = (unsigned)((wm * (BM / 2) + r31) * RB + (((2 * ks + hi) ^ kc_swz) * 16));
+        adA[ks] = (unsigned)((wm * WTM + r31) * RB + (((2 * ks + hi) ^ kc_swz) * 16));
     } else {
       constexpr int CPR = BM / 8;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < TM; ++t)
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
           int k = 8 * (gi >> 1) + 4 * hf + j;
-          int c = (wm * (BM / 2) + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
-          int swz = CPR == 16 ? 2 * (k & 7) : 2 * (k & 3);
+          int c = (wm * WTM + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
+          int swz = CPR >= 16 ? 2 * (k & 7) : 2 * (k & 3);
           adA[t * 2 + hf] = (unsigned)(k * (BM * 2) + ((c ^ swz) * 16) + (c4 & 1) * 8);
         }
     }
     if (B_KC) {
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks)
-        adB[ks] = (unsigned)(A_BYTES + (wn * (BN / 2) + r31) * RB + (((2 * ks + hi) ^ kc_swz) * 16));
+        adB[ks] = (unsigned)(A_BYTES + (wn * WTN + r31) * RB + (((2 * ks + hi) ^ kc_swz) * 16));
     } else {
       constexpr int CPR = BN / 8;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < TN; ++t)
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
           int k = 8 * (gi >> 1) + 4 * hf + j;
-          int c = (wn * (BN / 2) + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
-          int swz = CPR == 16 ? 2 * (k & 7) : 2 * (k & 3);
+          int c = (wn * WTN + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
+          int swz = CPR >= 16 ? 2 * (k & 7) : 2 * (k & 3);
           adB[t * 2 + hf] = (unsigned)(A_BYTES + k * (BN * 2) + ((c ^ swz) * 16) + (c4 & 1) * 8);
         }
     }
@@ -355,7 +360,9 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
 #endif
     if (A_KC) {
       fa[0] = lds_read_b128<0>(sb + adA[KS]);
-      if (TM > 1) fa[TM - 1] = lds_read_b128<32 * RB>(sb + adA[KS]);
+      if constexpr (TM > 1) fa[1] = lds_read_b128<32 * RB>(sb + adA[KS]);
+      if constexpr (TM > 2) fa[2] = lds_read_b128<64 * RB>(sb + adA[KS]);
+      if constexpr (TM > 3) fa[3] = lds_read_b128<96 * RB>(sb + adA[KS]);
     } else {
 #pragma unroll
       for (int t = 0; t < TM; ++t) {
@@ -366,7 +373,9 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
     }
     if (B_KC) {
       fb[0] = lds_read_b128<0>(sb + adB[KS]);
-      if (TN > 1) fb[TN - 1] = lds_read_b128<32 * RB>(sb + adB[KS]);
+      if constexpr (TN > 1) fb[1] = lds_read_b128<32 * RB>(sb + adB[KS]);
+      if constexpr (TN > 2) fb[2] = lds_read_b128<64 * RB>(sb + adB[KS]);
+      if constexpr (TN > 3) fb[3] = lds_read_b128<96 * RB>(sb + adB[KS]);
     } else {
 #pragma unroll
       for (int t = 0; t < TN; ++t) {
@@ -404,10 +413,11 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   };
   auto settle = [&](auto keep_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
     constexpr int KEEP = decltype(keep_tag)::value;
-    if constexpr (TM == 2 && TN == 2) lds_settle<KEEP>(fa[0], fa[1], fb[0], fb[1]);
-    else if constexpr (TM == 2) lds_settle<KEEP>(fa[0], fa[1], fb[0]);
-    else if constexpr (TN == 2) lds_settle<KEEP>(fa[0], fb[0], fb[1]);
-    else lds_settle<KEEP>(fa[0], fb[0]);
+    lds_wait<KEEP>();
+#pragma unroll
+    for (int t = 0; t < TM; ++t) lds_pin(fa[t]);
+#pragma unroll
+    for (int t = 0; t < TN; ++t) lds_pin(fb[t]);
   };
   constexpr int READS = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);  // LDS reads per k step
   static_assert(READS <= 15, "lgkmcnt is a 4-bit counter");
@@ -490,5 +500,5 @@ __global__ __launch_bounds__(THREADS) void igemm_dma_kernel(GemmArgs a) {
   }
   __syncthreads();  // the epilogue reuses the ring as its staging tile
 
-  igemm_epilogue<BM, BN>(a, acc, lds, m0, n0, split, tid, lane, wm, wn);
+  igemm_epilogue_impl<BM, BN, TM, TN, NT, dma_epass(BM, BN)>(a, acc, lds, m0, n0, split, tid, lane, wm * WTM, wn * WTN);
 }
