@@ -5,12 +5,14 @@ One step = forward of all 53 convolutions and the classifier, then backward-data
 backward-weight of every layer in reverse order with the weight gradients written straight into the fused flat
 gradient buffer, then one mixed-precision LARS update over all 161 tensors (25,557,032 parameters).  Batch norm,
 ReLU, pooling and the residual adds are not part of this path, so every layer has its own seeded synthetic input
-and output gradient of the right shape (a chained stack without normalisation would overflow fp16).
+and output gradient of the right shape (a chained stack without normalisation would overflow fp16).  Launches are
+eager (replaying the step from a HIP graph measured slower here) and follow the network's dependency graph: the
+projection shortcuts and the backward-weight launches run on side streams (--streams).
 
 Prints ONE JSON line.  `value` is images/s of the whole step with all inputs resident in HBM; `roofline` is for
 the implicit-GEMM kernel family (all conv/FC launches of a step, algorithmic flops / their time between HIP events
 on the launch stream); `lars` gives the update's GB/s against HBM; `cpu_baseline` times the fp64 oracle on the
-host cores on a two-image sample of the same stack.
+host cores on an eight-image sample of the same stack.
 """
 import argparse
 import json
@@ -25,6 +27,10 @@ from paper_1807_11205_amd import api, inputs, shapes
 FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
 HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
 LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32 4 + w16 2
+# HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very workload (default batch and
+# variant), scaled by the same counters' readings for a 1 GiB copy; the runs are summarised under profiles/.
+MEASURED_GEMM_HBM_BYTES_PER_STEP = 10.48e9   # all conv/FC launches with their split-K reductions and packing kernels
+MEASURED_LARS_HBM_BYTES_PER_UPDATE = 562e6   # gradient norm pass 51 MB + update pass 511 MB
 
 
 class ResNet50Step:
@@ -89,7 +95,7 @@ class ResNet50Step:
             ws_bytes = max(ws_bytes, api.jz_gemm_fc_workspace_bytes(op, B, I, O))
         self.flops += 2 * self.fc.macs(batch) * 3
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)
-        self.ws2 = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)   # for the side stream
+        self.side_ws = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device) for _ in range(3)]
 
         self.found_inf = torch.zeros(1, dtype=torch.int32, device=device)
         self.ps = api.ParamSet(self.offsets, self.flags, self.master, self.momentum, self.grad, self.w16)
@@ -117,32 +123,53 @@ class ResNet50Step:
         else:
             api.jz_gemm_fc(api.JZ_BWD_WEIGHT, B, I, O, L["dy"], L["x"], L["dw"], ws)
 
-    def run_gemms(self, side=None):
-        """Forward of every layer, then the backward pass.  With a side stream, backward-weight of a layer runs there,
-        concurrently with the backward-data chain on the current stream, ordered the way a real network orders them:
-        dW of layer l needs only dy of layer l, which the backward-data of layer l+1 produces."""
+    def run_gemms(self, sides=()):
+        """Forward of every layer, then the backward pass, launched the way the network's own dependency graph allows
+        (every layer has independent buffers here, but nothing is started earlier than a real ResNet-50 could start it).
+        Forward: the projection shortcut of a stage's first block reads the block input, like conv a of that block, so it
+        runs on a side stream beside a-b-c.  Backward: dW of layer l needs only dy of layer l, which the backward-data
+        of layer l+1 produces, so the backward-weight launches go round-robin to the side streams while the
+        backward-data chain stays on the current stream.  Each side stream has its own workspace."""
         B, I, O = self.N, self.fc.I, self.fc.O
+        cur = torch.cuda.current_stream()
+        block_in = None
+        pending = False
         for L in self.layers:                                   # forward
             if L["kind"] == "conv":
+                if sides and L["name"].endswith("p"):
+                    sides[0].wait_event(block_in)
+                    with torch.cuda.stream(sides[0]):
+                        api.jz_conv2d_fwd(L["d"], L["x"], L["w"], L["y"], self.side_ws[0])
+                    pending = True
+                    continue
+                if sides and L["name"].endswith("a"):
+                    if pending:                                 # the residual add of the previous block needs its shortcut
+                        cur.wait_stream(sides[0])
+                        pending = False
+                    block_in = torch.cuda.Event()
+                    block_in.record(cur)
                 api.jz_conv2d_fwd(L["d"], L["x"], L["w"], L["y"], self.ws)
             else:
                 api.jz_gemm_fc(api.JZ_FWD, B, I, O, L["x"], L["w"], L["y"], self.ws)
-        if side is None:
+        if pending:
+            cur.wait_stream(sides[0])
+        if not sides:
             for L in reversed(self.layers):                     # backward, one stream
                 self._bwd_data(L, self.ws)
                 self._bwd_weight(L, self.ws)
             return
-        cur = torch.cuda.current_stream()
         ready = torch.cuda.Event()
         ready.record(cur)                                       # the loss gradient exists
-        for L in reversed(self.layers):
+        for k, L in enumerate(reversed(self.layers)):
+            side = sides[k % len(sides)]
             side.wait_event(ready)
             with torch.cuda.stream(side):
-                self._bwd_weight(L, self.ws2)
+                self._bwd_weight(L, self.side_ws[k % len(sides)])
             self._bwd_data(L, self.ws)
             ready = torch.cuda.Event()
             ready.record(cur)                                   # dy of the layer below exists
-        cur.wait_stream(side)
+        for side in sides:
+            cur.wait_stream(side)
 
     def run_lars(self):
         api.jz_lars_mp_update(self.ps, self.hparams(), self.found_inf, self.lars_ws)
@@ -213,7 +240,7 @@ def per_layer_report(wl, iters=20):
     return rows
 
 
-def cpu_baseline(sample_batch=2):
+def cpu_baseline(sample_batch=8):
     """The fp64 oracle, as it stands, on the host cores: the same 53-conv + FC stack at a small batch, plus LARS."""
     import oracle
     gemm_s = 0.0
@@ -253,9 +280,21 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
-    ap.add_argument("--streams", type=int, default=2, help="2: backward-weight runs on a second stream beside backward-data")
+    ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
+                    "for the projection shortcuts (forward) and the backward-weight launches (at most 4)")
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a HIP graph (1) or launch eagerly (0); eager launches measured faster here")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run ten 1 GiB device-to-device copies and exit: the known-size kernel that the HBM byte counters "
+                         "(FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc) are scaled by")
     args = ap.parse_args()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "copies": 10}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -278,7 +317,7 @@ def main():
         wl.reset_state()
 
     stream = torch.cuda.Stream()
-    side = torch.cuda.Stream() if args.streams == 2 else None
+    side = [torch.cuda.Stream() for _ in range(max(0, min(args.streams, 4) - 1))]
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     with torch.cuda.stream(stream):
         for _ in range(max(args.warmup, 1)):
@@ -321,6 +360,7 @@ def main():
     n_gemm = 0
     for L in wl.layers:
         n_gemm += 3 if not L.get("first") else 2
+    default_workload = args.batch == 64
     tflops = wl.flops / (gemm_ms * 1e-3) / 1e12
     lars_gbps = LARS_BYTES_PER_PARAM * wl.P / (lars_ms * 1e-3) / 1e9
     out = {
@@ -339,10 +379,14 @@ def main():
         "pct_fp16_mfma_peak": 100.0 * (wl.flops / (ms_per_step * 1e-3) / 1e12) / FP16_MFMA_PEAK_TFLOPS,
         "roofline": {"kernel": "igemm_kernel (all %d conv/FC launches of a step)" % n_gemm, "bound": "mfma",
                      "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "frac": tflops / FP16_MFMA_PEAK_TFLOPS,
+                     "traffic": MEASURED_GEMM_HBM_BYTES_PER_STEP if default_workload else None,
+                     "traffic_note": "HBM bytes per step of all these launches (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-"
+                                     "kernel scaled); algorithmic 2(|x|+|w|+|y|) per pass is 7.99e9",
                      "flop_per_step": wl.flops, "ms_per_step_gemm_phase": gemm_ms, "avg_launch_us": gemm_ms * 1e3 / n_gemm},
         "lars": {"bound": "hbm", "achieved": lars_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": lars_gbps / HBM_PEAK_GBPS,
-                 "bytes_per_param": LARS_BYTES_PER_PARAM, "params": wl.P, "us_per_update": lars_ms * 1e3, "traffic": None},
+                 "bytes_per_param": LARS_BYTES_PER_PARAM, "params": wl.P, "us_per_update": lars_ms * 1e3,
+                 "traffic": MEASURED_LARS_HBM_BYTES_PER_UPDATE if default_workload else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
