@@ -149,6 +149,42 @@ def test_same_inputs_give_identical_bits(jz):
         assert np.array_equal(r1.view(np.uint16), r2.view(np.uint16))
 
 
+KERNEL_VARIANTS = [
+    # (JZ_IGEMM_TILE, JZ_IGEMM_BK, JZ_IGEMM_WAVES): every LDS-direct kernel variant, forced through the planner's
+    # debugging overrides so that each one is compared with the oracle whatever the planner would have picked
+    ("128128", "32", "4"), ("128064", "32", "4"), ("64128", "32", "4"), ("64064", "32", "4"),
+    ("128128", "64", "4"), ("128064", "64", "4"), ("64128", "64", "4"), ("64064", "64", "4"),
+    ("128128", "64", "8"), ("256128", "64", "8"), ("256128", "32", "8"), ("256256", "32", "8"),
+]
+
+
+@pytest.mark.parametrize("tile,bk,waves", KERNEL_VARIANTS)
+def test_every_kernel_variant_against_the_oracle(jz, monkeypatch, tile, bk, waves):
+    import jzt
+    import oracle
+    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
+    monkeypatch.setenv("JZ_IGEMM_BK", bk)
+    monkeypatch.setenv("JZ_IGEMM_WAVES", waves)
+    # M = 675 pixels (2.6 tiles of 256 rows), 128 -> 320 channels (1.25 tiles of 256 columns), 3x3 with padding
+    N, H, W, C, K, R, S, st, pad = 3, 15, 15, 128, 320, 3, 3, 1, 1
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
+    rng = inputs.rng_for(16, int(tile), int(bk), int(waves))
+    x = inputs.normal_f16(rng, (N, H, W, C))
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+    jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
+    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+    # a strided 1x1 layer: the scatter epilogue of backward-data, also in its slabbed form
+    N, H, W, C, K = 2, 14, 14, 256, 128
+    od = oracle.conv_desc(N, H, W, C, K, 1, 1, 2, (0, 0))
+    d = jz.conv_desc(N, H, W, C, K, 1, 1, 2, (0, 0))
+    w = inputs.he_normal_f32(rng, (K, 1, 1, C), C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data 1x1 s2")
+
+
 @pytest.mark.parametrize("B,I,O", [(64, 2048, 1000), (128, 1024, 520), (5, 24, 7), (1, 64, 64), (130, 192, 72)])
 def test_fully_connected_modes(jz, B, I, O):
     import jzt
