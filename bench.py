@@ -80,7 +80,7 @@ class ResNet50Step:
                      x=randn(batch * cs.H * cs.H * cs.C), dy=randn(batch * cs.P * cs.P * cs.K, self.loss_scale),
                      y=torch.empty(batch * cs.P * cs.P * cs.K, dtype=h, device=device),
                      dx=None if cs.first else torch.empty(batch * cs.H * cs.H * cs.C, dtype=h, device=device),
-                     w=self.w16[a:b], dw=self.grad[a:b])
+                     w=self.w16[a:b], dw=self.grad[a:b], calls={})
             for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
                 ws_bytes = max(ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
             self.flops += 2 * cs.macs(batch) * (2 if cs.first else 3)
@@ -90,7 +90,7 @@ class ResNet50Step:
         B, I, O = batch, self.fc.I, self.fc.O
         self.layers.append(dict(kind="fc", name="fc", x=randn(B * I), dy=randn(B * O, self.loss_scale),
                                 y=torch.empty(B * O, dtype=h, device=device), dx=torch.empty(B * I, dtype=h, device=device),
-                                w=self.w16[a:b], dw=self.grad[a:b]))
+                                w=self.w16[a:b], dw=self.grad[a:b], calls={}))
         for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
             ws_bytes = max(ws_bytes, api.jz_gemm_fc_workspace_bytes(op, B, I, O))
         self.flops += 2 * self.fc.macs(batch) * 3
@@ -102,74 +102,86 @@ class ResNet50Step:
         self.lars_ws = torch.zeros(api.jz_lars_workspace_bytes(self.ps), dtype=torch.uint8, device=device)
         api.jz_lars_prepare(self.ps, self.lars_ws)
         self.P = P
-        self.n_gemm_launches = 0
+        self.programs = {}
 
     def hparams(self):
         hp = inputs.HPARAMS
         return api.lars_hparams(hp["lr"], hp["momentum"], hp["weight_decay"], hp["trust_coef"], self.loss_scale)
 
-    def _bwd_data(self, L, ws):
+    def _bound(self, L, op, ws):
+        """The layer's forward / backward-data / backward-weight call with its arguments marshalled once."""
         B, I, O = self.N, self.fc.I, self.fc.O
-        if L["kind"] == "conv":
-            if not L["first"]:
-                api.jz_conv2d_bwd_data(L["d"], L["dy"], L["w"], L["dx"], ws)
-        else:
-            api.jz_gemm_fc(api.JZ_BWD_DATA, B, I, O, L["dy"], L["w"], L["dx"], ws)
+        key = (op, ws.data_ptr())
+        if key not in L["calls"]:
+            if L["kind"] == "conv":
+                a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("x", "dy", "dw")}[op]
+                L["calls"][key] = api.bind_conv2d(op, L["d"], L[a], L[b], L[o], ws)
+            else:
+                a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("dy", "x", "dw")}[op]
+                L["calls"][key] = api.bind_gemm_fc(op, B, I, O, L[a], L[b], L[o], ws)
+        return L["calls"][key]
 
-    def _bwd_weight(self, L, ws):
-        B, I, O = self.N, self.fc.I, self.fc.O
-        if L["kind"] == "conv":
-            api.jz_conv2d_bwd_weight(L["d"], L["x"], L["dy"], L["dw"], ws)
-        else:
-            api.jz_gemm_fc(api.JZ_BWD_WEIGHT, B, I, O, L["dy"], L["x"], L["dw"], ws)
+    def build_program(self, n_side):
+        """The launch sequence of the GEMM phase as a flat list of (kind, object, stream index) with kind in
+        launch / record / wait; stream 0 is the caller's stream, 1 .. n_side the side streams.
 
-    def run_gemms(self, sides=()):
-        """Forward of every layer, then the backward pass, launched the way the network's own dependency graph allows
+        Forward of every layer, then the backward pass, ordered the way the network's own dependency graph allows
         (every layer has independent buffers here, but nothing is started earlier than a real ResNet-50 could start it).
         Forward: the projection shortcut of a stage's first block reads the block input, like conv a of that block, so it
         runs on a side stream beside a-b-c.  Backward: dW of layer l needs only dy of layer l, which the backward-data
         of layer l+1 produces, so the backward-weight launches go round-robin to the side streams while the
-        backward-data chain stays on the current stream.  Each side stream has its own workspace."""
-        B, I, O = self.N, self.fc.I, self.fc.O
-        cur = torch.cuda.current_stream()
+        backward-data chain stays on stream 0.  Each side stream has its own workspace."""
+        prog = []
+        ev = lambda: torch.cuda.Event()
+        pending = None
         block_in = None
-        pending = False
         for L in self.layers:                                   # forward
-            if L["kind"] == "conv":
-                if sides and L["name"].endswith("p"):
-                    sides[0].wait_event(block_in)
-                    with torch.cuda.stream(sides[0]):
-                        api.jz_conv2d_fwd(L["d"], L["x"], L["w"], L["y"], self.side_ws[0])
-                    pending = True
-                    continue
-                if sides and L["name"].endswith("a"):
-                    if pending:                                 # the residual add of the previous block needs its shortcut
-                        cur.wait_stream(sides[0])
-                        pending = False
-                    block_in = torch.cuda.Event()
-                    block_in.record(cur)
-                api.jz_conv2d_fwd(L["d"], L["x"], L["w"], L["y"], self.ws)
-            else:
-                api.jz_gemm_fc(api.JZ_FWD, B, I, O, L["x"], L["w"], L["y"], self.ws)
-        if pending:
-            cur.wait_stream(sides[0])
-        if not sides:
+            if n_side and L["kind"] == "conv" and L["name"].endswith("p"):
+                prog += [("wait", block_in, 1), ("launch", self._bound(L, api.JZ_FWD, self.side_ws[0]), 1)]
+                pending = ev()
+                prog.append(("record", pending, 1))
+                continue
+            if n_side and L["kind"] == "conv" and L["name"].endswith("a"):
+                if pending is not None:                         # the residual add of the previous block needs its shortcut
+                    prog.append(("wait", pending, 0))
+                    pending = None
+                block_in = ev()
+                prog.append(("record", block_in, 0))
+            prog.append(("launch", self._bound(L, api.JZ_FWD, self.ws), 0))
+        if pending is not None:
+            prog.append(("wait", pending, 0))
+        if not n_side:
             for L in reversed(self.layers):                     # backward, one stream
-                self._bwd_data(L, self.ws)
-                self._bwd_weight(L, self.ws)
-            return
-        ready = torch.cuda.Event()
-        ready.record(cur)                                       # the loss gradient exists
+                if not L.get("first"):
+                    prog.append(("launch", self._bound(L, api.JZ_BWD_DATA, self.ws), 0))
+                prog.append(("launch", self._bound(L, api.JZ_BWD_WEIGHT, self.ws), 0))
+            return prog
+        ready = ev()
+        prog.append(("record", ready, 0))                       # the loss gradient exists
         for k, L in enumerate(reversed(self.layers)):
-            side = sides[k % len(sides)]
-            side.wait_event(ready)
-            with torch.cuda.stream(side):
-                self._bwd_weight(L, self.side_ws[k % len(sides)])
-            self._bwd_data(L, self.ws)
-            ready = torch.cuda.Event()
-            ready.record(cur)                                   # dy of the layer below exists
-        for side in sides:
-            cur.wait_stream(side)
+            si = 1 + k % n_side
+            prog += [("wait", ready, si), ("launch", self._bound(L, api.JZ_BWD_WEIGHT, self.side_ws[si - 1]), si)]
+            if not L.get("first"):
+                prog.append(("launch", self._bound(L, api.JZ_BWD_DATA, self.ws), 0))
+                ready = ev()
+                prog.append(("record", ready, 0))               # dy of the layer below exists
+        for si in range(1, n_side + 1):
+            done = ev()
+            prog += [("record", done, si), ("wait", done, 0)]
+        return prog
+
+    def run_gemms(self, sides=()):
+        n_side = len(sides)
+        if n_side not in self.programs:
+            self.programs[n_side] = self.build_program(n_side)
+        streams = [torch.cuda.current_stream(), *sides]
+        for kind, obj, si in self.programs[n_side]:
+            if kind == "launch":
+                obj(streams[si])
+            elif kind == "record":
+                obj.record(streams[si])
+            else:
+                streams[si].wait_event(obj)
 
     def run_lars(self):
         api.jz_lars_mp_update(self.ps, self.hparams(), self.found_inf, self.lars_ws)

@@ -167,6 +167,42 @@ def jz_conv2d_bwd_weight(desc, x16, dy16, dw16, ws=None, stream=None):
            "jz_conv2d_bwd_weight")
 
 
+class BoundCall:
+    """One entry-point call with its arguments already marshalled: `call(stream)` enqueues it again without
+    re-validating the tensors (they are kept alive here).  For launch loops that repeat the same calls every step."""
+
+    __slots__ = ("fn", "args", "where", "keep")
+
+    def __init__(self, fn, args, where, keep):
+        self.fn, self.args, self.where, self.keep = fn, args, where, keep
+
+    def __call__(self, stream=None):
+        st = self.fn(*self.args, _stream(stream))
+        if st != JZ_OK:
+            raise JzError(st, self.where)
+
+
+def bind_conv2d(op: int, desc, a16, b16, out16, ws=None) -> BoundCall:
+    """Pre-marshalled jz_conv2d_fwd (x, w -> y), jz_conv2d_bwd_data (dy, w -> dx) or jz_conv2d_bwd_weight (x, dy -> dw)."""
+    d, h = desc, torch.float16
+    nx, nw, ny = d.N * d.H * d.W * d.C, d.K * d.R * d.S * d.C, d.N * d.P * d.Q * d.K
+    name, na, nb, no = {JZ_FWD: ("jz_conv2d_fwd", nx, nw, ny), JZ_BWD_DATA: ("jz_conv2d_bwd_data", ny, nw, nx),
+                        JZ_BWD_WEIGHT: ("jz_conv2d_bwd_weight", nx, ny, nw)}[op]
+    wp, wn = _ws(ws)
+    args = (ctypes.byref(d), _dev_ptr(a16, h, na, "first operand"), _dev_ptr(b16, h, nb, "second operand"),
+            _dev_ptr(out16, h, no, "output"), wp, wn)
+    return BoundCall(getattr(lib(), name), args, name, (d, a16, b16, out16, ws))
+
+
+def bind_gemm_fc(mode, batch, in_features, out_features, a16, b16, out16, ws=None) -> BoundCall:
+    """Pre-marshalled jz_gemm_fc."""
+    B, I, O, h = batch, in_features, out_features, torch.float16
+    na, nb, no = {JZ_FWD: (B * I, O * I, B * O), JZ_BWD_DATA: (B * O, O * I, B * I), JZ_BWD_WEIGHT: (B * O, B * I, O * I)}[mode]
+    wp, wn = _ws(ws)
+    args = (mode, B, I, O, _dev_ptr(a16, h, na, "a16"), _dev_ptr(b16, h, nb, "b16"), _dev_ptr(out16, h, no, "out16"), wp, wn)
+    return BoundCall(lib().jz_gemm_fc, args, "jz_gemm_fc", (a16, b16, out16, ws))
+
+
 def jz_gemm_fc_workspace_bytes(mode: int, batch: int, in_features: int, out_features: int) -> int:
     n = ctypes.c_size_t(0)
     _check(lib().jz_gemm_fc_workspace_bytes(mode, batch, in_features, out_features, ctypes.byref(n)),

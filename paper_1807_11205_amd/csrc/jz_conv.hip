@@ -589,16 +589,22 @@ int env_int(const char* name) {
   const char* e = getenv(name);
   return e ? atoi(e) : 0;
 }
-// debugging aids: JZ_IGEMM_BK=64, JZ_IGEMM_TILE=<BM*1000+BN>, JZ_IGEMM_SPLITS=<n> override the planner
-// (read on every call so that a tuning sweep can change them inside one process)
-int igemm_bk_override() { return env_int("JZ_IGEMM_BK"); }
-int igemm_tile_override() { return env_int("JZ_IGEMM_TILE"); }
-int igemm_splits_override() { return env_int("JZ_IGEMM_SPLITS"); }
+// debugging aids: JZ_IGEMM_BK=64, JZ_IGEMM_TILE=<BM*1000+BN>, JZ_IGEMM_SPLITS=<n>, JZ_IGEMM_WAVES=<4|8> override the
+// planner, JZ_IGEMM_VERBOSE=1 prints its choice (read once per call, not per candidate: the environment is searched
+// linearly, and a tuning sweep may change them inside one process)
+struct Overrides {
+  int bk, tile, splits, waves, verbose;
+};
+Overrides read_overrides() {
+  return Overrides{env_int("JZ_IGEMM_BK"), env_int("JZ_IGEMM_TILE"), env_int("JZ_IGEMM_SPLITS"), env_int("JZ_IGEMM_WAVES"),
+                   env_int("JZ_IGEMM_VERBOSE")};
+}
 
 struct Plan {
   int op = 0;
   bool fast = false;    // vector (16-byte) operand access possible
   bool packed = false;  // small-channel layer run on a 4-channel padded copy
+  bool gen = false;     // gather with per-load tap arithmetic (more than 32 taps, strided multi-tap backward-data)
   int BM = 128, BN = 128;
   int bk = BK;  // k tile depth of the kernel that will run
   int waves = 4, nst = 4;  // wavefronts per workgroup and ring depth (large tiles come in several variants)
@@ -639,7 +645,7 @@ const Variant kVariants[] = {
 };
 
 // bk64_ok: the 64-deep k tile is usable for this layer; forced_bk: the k tile depth is fixed (register path, packed mode)
-void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk) {
+void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   GemmArgs& a = pl->args;
   static const int split_opts[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128};
   const int oi = pl->op == JZ_FWD ? 0 : pl->op == JZ_BWD_DATA ? 1 : 2;
@@ -650,19 +656,19 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk) {
   {
     for (const Variant& v : kVariants) {
       if (!pl->fast && &v != &kVariants[0]) break;
-      if (forced_bk && (v.waves != 4 || v.bk != 32)) continue;  // those kernels exist as 4-wavefront variants only
+      if ((forced_bk || pl->gen) && (v.waves != 4 || v.bk != 32)) continue;  // those kernels exist as 4-wavefront variants only
       if (pl->packed && pl->op == JZ_FWD && v.BM != 128) continue;  // the masked kernels exist for BM = 128 only
       if (!forced_bk && v.bk == 64 && !bk64_ok) continue;
-      if (!forced_bk && igemm_bk_override() && igemm_bk_override() != v.bk) continue;
-      if (igemm_tile_override() && igemm_tile_override() != v.BM * 1000 + v.BN) continue;
-      if (env_int("JZ_IGEMM_WAVES") && env_int("JZ_IGEMM_WAVES") != v.waves) continue;
+      if (!forced_bk && ov.bk && ov.bk != v.bk) continue;
+      if (ov.tile && ov.tile != v.BM * 1000 + v.BN) continue;
+      if (ov.waves && ov.waves != v.waves) continue;
       const int vbk = forced_bk ? forced_bk : v.bk;
       const int nkt = (a.Kred + vbk - 1) / vbk;
       long long tm = (a.M + v.BM - 1) / v.BM, tn = (a.N + v.BN - 1) / v.BN;
       for (int sp : split_opts) {
         if (sp > 1 && nkt / sp < 4) break;
         if (a.sc_on && sp > 1) break;  // the scatter lives in the fp16 epilogue
-        if (igemm_splits_override() && sp != igemm_splits_override() && !(sp == 1 && nkt / igemm_splits_override() < 4)) continue;
+        if (ov.splits && sp != ov.splits && !(sp == 1 && nkt / ov.splits < 4)) continue;
         const int kps = (nkt + sp - 1) / sp;
         long long blocks = tm * tn * ((nkt + kps - 1) / kps);
         long long rounds = (blocks + v.resident - 1) / v.resident;
@@ -756,7 +762,7 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
 
   // small-channel layers: gather from a zero-padded 4-channel copy (see pad_to_c4)
   if (!pl->fast && !use_register_path() && op != JZ_BWD_DATA && d->C <= 4 && d->stride_w % 2 == 0 && 4 * d->S <= 64 &&
-      (op == JZ_FWD || d->K % 8 == 0)) {
+      d->R <= 32 && (op == JZ_FWD || d->K % 8 == 0)) {
     const int KT = 4 * d->S <= 32 ? 32 : 64;
     int Hp = d->H + 2 * d->pad_h, Wp = d->W + 2 * d->pad_w;
     if (Wp < (Q - 1) * d->stride_w + KT / 4) Wp = (Q - 1) * d->stride_w + KT / 4;
@@ -780,15 +786,20 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
       }
     }
   }
+  // the vector kernel marks padding taps with a 32-bit mask per row and, for backward-data, needs the source pixel to
+  // be an affine function of the tap (unit stride); other shapes take its variant with per-load tap arithmetic
+  pl->gen = pl->fast && !pl->packed && op != JZ_BWD_WEIGHT &&
+            (g.R * g.S > 32 || (op == JZ_BWD_DATA && (g.sh != 1 || g.sw != 1)));
   finish_geometry(g);
   if (!pl->fast) bk = BK;  // the element-wise kernel walks 64-deep tiles
   pl->bk = bk;
   if (pl->packed && !forced_bk) forced_bk = 32;  // small-channel backward-weight: 4-wavefront 32-deep kernels
-  choose_tiling(pl, bk64_ok, forced_bk);
+  const Overrides ov = read_overrides();
+  choose_tiling(pl, bk64_ok, forced_bk, ov);
   const size_t part = a.splits > 1 ? (size_t)a.splits * a.M * a.N * sizeof(float) : 0;
   pl->part_offset = pl->packed ? pl->xp_bytes + pl->wp_bytes : 0;
   pl->ws_bytes = pl->part_offset + part;
-  if (env_int("JZ_IGEMM_VERBOSE"))  // debugging aid: show what the planner chose
+  if (ov.verbose)  // debugging aid: show what the planner chose
     fprintf(stderr, "jz igemm op %d M %d N %d K %d: %s tile %dx%dx%d, %d x %d tiles, %d splits of %d k tiles%s%s\n", op, a.M,
             a.N, a.Kred, pl->fast ? "vector" : "element-wise", pl->BM, pl->BN, pl->bk, a.tiles_m, a.tiles_n, a.splits,
             a.kt_per_split, pl->packed ? ", 4-channel padded copy" : "", a.sc_on ? ", scatter epilogue" : "");
@@ -812,7 +823,7 @@ int launch_one(const GemmArgs& a, hipStream_t st) {
   return jz::launch_status();
 }
 
-template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2>
+template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2, bool GEN = false>
 int launch_dma(const GemmArgs& a, hipStream_t st) {
   constexpr size_t ring_bytes = (size_t)NST * (BM + BN) * 2 * TBK;
   constexpr size_t epi_bytes = (size_t)BM / dma_epass(BM, BN) * (BN + 8) * sizeof(unsigned short);
@@ -820,13 +831,13 @@ int launch_dma(const GemmArgs& a, hipStream_t st) {
   static_assert(smem <= 160 * 1024, "more LDS than a compute unit has");
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA, WGM, WGN>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA, WGM, WGN, GEN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return JZ_ERR_LAUNCH;
     attr_set = true;
   }
   unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.splits;
-  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA, WGM, WGN>), dim3(grid), dim3(64 * WGM * WGN), smem, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<OP, BM, BN, TBK, NST, MASKA, WGM, WGN, GEN>), dim3(grid), dim3(64 * WGM * WGN), smem, st, a);
   return jz::launch_status();
 }
 
@@ -843,6 +854,14 @@ int launch_op(const Plan& pl, hipStream_t st) {
       if (pl.BN == 128 && pl.BM == 128) return launch_dma<OP_FWD, 128, 128, 64, 4, true>(a, st);
     }
     return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
+  }
+  if constexpr (OP != OP_BWD_WEIGHT) {
+    if (pl.gen && !use_register_path()) {  // the planner offers the 4-wavefront 32-deep tiles in this mode
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4, false, 2, 2, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4, false, 2, 2, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 4, false, 2, 2, true>(a, st);
+      return launch_dma<OP, 64, 64, 32, 4, false, 2, 2, true>(a, st);
+    }
   }
   if (!use_register_path()) {
     // large tiles, one workgroup of 8 wavefronts per compute unit with (nearly) the whole LDS as its ring

@@ -80,12 +80,47 @@ __device__ __forceinline__ void jz_dma16(__amdgpu_buffer_rsrc_t rsrc, lds_byte* 
 // slabs the epilogue stages the fp16 tile in: its staging buffer has to fit the ring
 constexpr int dma_epass(int bm, int bn) { return bm * (bn + 8) * 2 > 128 * 1024 ? 2 : 1; }
 
+// compile-time loop: f(std::integral_constant<int, I>{}) for I = B .. E-1 (immediates of inline assembly and the
+// slot arithmetic of the schedule need constant expressions)
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+// nothing may be moved across this point by the instruction scheduler
+__device__ __forceinline__ void sched_fence() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+}
+// one LDS-direct load with the wave-uniform part of the offset in a scalar register
+__device__ __forceinline__ void jz_dma16s(__amdgpu_buffer_rsrc_t rsrc, lds_byte* dst, unsigned voff, unsigned soff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, (int)voff, (int)soff, 0, 0);
+}
+
 // WGM x WGN wavefronts share a BM x BN output tile; each owns (BM / WGM) x (BN / WGN) of it.  The larger a
 // wavefront's share, the fewer LDS bytes it reads per MFMA (a 128x64 share: 6 operand reads for 8 MFMAs per k step,
 // a 64x64 share: 4 for 4), and the larger the workgroup's tile, the fewer bytes come in from L2 per flop.
-template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2>
+//
+// Instruction budget.  A wavefront issues in order, and the matrix pipe accepts one 32x32x16 MFMA every 32 cycles,
+// so everything that is not an MFMA has to fit into the ~8 issue slots between two MFMAs or the pipe idles.  Hence:
+//   * a load's address is  descriptor base + per-lane offset (VGPR, fixed for the whole k loop) + per-tile offset
+//     (SGPR: filter tap and channel block).  Padding taps and rows beyond M are handled by a per-row bit mask of
+//     invalid taps built once in the prologue: one v_bfe_i32 turns the tap's bit into 0 / -1 and an OR sends the
+//     lane's offset out of the descriptor's range, which makes the load deliver zeros.  Two VALU instructions per
+//     load instead of a dozen, and no divergent control flow inside the loop.
+//   * gathered operands whose in-range taps can start before the tensor (padding) use a descriptor whose base is
+//     moved down by that margin, so that the per-lane offset is never negative.
+//   * the loop body is laid out MFMA by MFMA in the source and fenced (sched_fence) so that the loads and LDS reads
+//     sit between the MFMAs instead of in one block in front of them.
+// GEN = true keeps the plain per-load tap arithmetic for the shapes the masks do not cover (more than 32 taps;
+// strided multi-tap backward-data, whose source pixel is not an affine function of the tap).
+template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2, bool GEN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   static_assert(TBK == 32 || TBK == 64, "k tile depth");
+  static_assert(!GEN || OP != OP_BWD_WEIGHT, "backward-weight has no generic variant");
   constexpr bool A_KC = OP != OP_BWD_WEIGHT;  // A has k contiguous in memory
   constexpr bool B_KC = OP == OP_FWD;
   constexpr int NW = WGM * WGN, NT = 64 * NW;  // wavefronts, threads
@@ -93,6 +128,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   constexpr int TM = WTM / 32, TN = WTN / 32;    // ... as 32x32 MFMA tiles
   static_assert(TM >= 1 && TN >= 1 && TM * 32 * WGM == BM && TN * 32 * WGN == BN, "tile / wavefront grid mismatch");
   constexpr int NKS = TBK / 16;               // MFMA k steps per tile
+  constexpr int G = TM * TN;                  // MFMAs per k step
   constexpr int RB = 2 * TBK;                 // bytes per row of a KC tile
   constexpr int CR = TBK / 8;                 // 16-byte chunks per row of a KC tile
   constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
@@ -105,7 +141,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   const unsigned lds_base = (unsigned)(uintptr_t)JZ_LDS_PTR(lds);
 
   const ConvGeom& g = a.g;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // the wavefront index as a scalar: everything derived from it (LDS destinations, M0) then stays in SGPRs
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
 
   unsigned L = xcd_remap(blockIdx.x, gridDim.x);
@@ -118,9 +156,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   const int kt_end = (kt_begin + a.kt_per_split < a.nkt) ? kt_begin + a.kt_per_split : a.nkt;
   const int nk = kt_end - kt_begin;
 
-  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, (int)a.bytesA, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)a.B, 0, (int)a.bytesB, 0x00020000);
   constexpr unsigned OOB = 0xffffffffu;
+  // Margin by which the descriptor of the gathered operand A starts before the tensor (bytes).  Forward: tap (0,0) of
+  // a padded row lies up to (ph, pw) pixels before the row's first pixel.  Backward-data (unit stride): the per-tile
+  // offset counts taps from the far corner (R-1-r, S-1-s), see below.
+  unsigned biasA = 0;
+  if (!GEN) {
+    if (OP == OP_FWD) biasA = (unsigned)(g.ph * g.row_pitch + g.pw * g.pix_step) * 2u;
+    if (OP == OP_BWD_DATA) biasA = (unsigned)((g.R - 1) * g.row_pitch + (g.S - 1) * g.pix_step) * 2u;
+  }
+  const __amdgpu_buffer_rsrc_t rsrcA =
+      __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)a.A - biasA), 0, (int)(a.bytesA + biasA), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)a.B, 0, (int)a.bytesB, 0x00020000);
 
   // ---- loader geometry ---------------------------------------------------------------------
   // KC tile: one load covers 64 / CR rows; load ii of wave w covers rows (NW ii + w) * (64 / CR) + lane / CR and the
@@ -139,46 +186,62 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
     return (lane % cpr) ^ swz;
   };
 
-  // per-thread gather state
-  unsigned sa0[LA];
-  int sa1[LA], sa2[LA];
-  (void)sa0; (void)sa1; (void)sa2;
+  // ---- per-thread loader state ---------------------------------------------------------------
+  // vA / vB: byte offset of load ii that does not change over the k loop (OOB: the row or column does not exist);
+  // invA: bit t set when filter tap t reads outside the image for this row (all bits set for rows beyond M).
+  unsigned vA[LA], invA[LA], vB[LB];
+  int ga1[LA], ga2[LA];  // GEN: the row's pixel coordinates, as the per-load arithmetic wants them
+  (void)invA; (void)ga1; (void)ga2;
   if (OP != OP_BWD_WEIGHT) {  // A rows are pixels of the (n, OH, OW) grid
 #pragma unroll
     for (int ii = 0; ii < LA; ++ii) {
       int m = m0 + NW * KC_RPI * ii + kc_row;
+      vA[ii] = 0; invA[ii] = OOB; ga1[ii] = -(1 << 28); ga2[ii] = -(1 << 28);
       if (m < a.M) {
         unsigned n = fd_div((unsigned)m, g.d_ohow);
         unsigned rem = (unsigned)m - n * (unsigned)(g.OH * g.OW);
-        unsigned oh = fd_div(rem, g.d_ow);
-        unsigned ow = rem - oh * (unsigned)g.OW;
-        if (OP == OP_FWD) {
-          sa1[ii] = (int)oh * g.sh - g.ph;
-          sa2[ii] = (int)ow * g.sw - g.pw;
-          // byte offset of tap (0,0) plus this lane's chunk; may wrap below zero for padded rows, the tap offset
-          // brings every in-range access back (unsigned arithmetic)
-          sa0[ii] = (unsigned)(((int)n * g.IH + sa1[ii]) * g.row_pitch + sa2[ii] * g.pix_step + kc_chunk * 8) * 2u;
+        int oh = (int)fd_div(rem, g.d_ow);
+        int ow = (int)rem - oh * g.OW;
+        if (GEN) {
+          if (OP == OP_FWD) {
+            ga1[ii] = oh * g.sh - g.ph;
+            ga2[ii] = ow * g.sw - g.pw;
+            vA[ii] = (unsigned)(((int)n * g.IH + ga1[ii]) * g.row_pitch + ga2[ii] * g.pix_step + kc_chunk * 8) * 2u;
+          } else {
+            vA[ii] = n * (unsigned)(g.IH * g.row_pitch);
+            ga1[ii] = oh + g.ph;
+            ga2[ii] = ow + g.pw;
+          }
         } else {
-          sa0[ii] = n * (unsigned)(g.IH * g.row_pitch);
-          sa1[ii] = (int)oh + g.ph;
-          sa2[ii] = (int)ow + g.pw;
+          // first source row / column and their step per filter tap: forward reads (oh sh - ph + r, ow sw - pw + s),
+          // backward-data with unit stride reads (oh + ph - r, ow + pw - s)
+          const int ih0 = OP == OP_FWD ? oh * g.sh - g.ph : oh + g.ph;
+          const int iw0 = OP == OP_FWD ? ow * g.sw - g.pw : ow + g.pw;
+          const int dir = OP == OP_FWD ? 1 : -1;
+          // offset of the pixel the per-tile scalar offset counts from: tap (0,0) for forward, tap (R-1,S-1) for
+          // backward-data; both plus the descriptor margin, which makes it non-negative
+          if (OP == OP_FWD)
+            vA[ii] = (unsigned)(((int)n * g.IH + ih0) * g.row_pitch + iw0 * g.pix_step + kc_chunk * 8) * 2u + biasA;
+          else
+            vA[ii] = (unsigned)(((int)n * g.IH + ih0) * g.row_pitch + iw0 * g.pix_step + kc_chunk * 8) * 2u;
+          unsigned cm = 0;  // columns: bit s set when tap column s is outside
+          for (int s = 0; s < g.S; ++s) cm |= ((unsigned)(iw0 + dir * s) >= (unsigned)g.IW ? 1u : 0u) << s;
+          const unsigned full = g.S >= 32 ? OOB : (1u << g.S) - 1u;
+          unsigned inv = 0;
+          for (int r = 0; r < g.R; ++r)
+            inv |= ((unsigned)(ih0 + dir * r) >= (unsigned)g.IH ? full : cm) << (r * g.S);
+          invA[ii] = inv;
         }
-      } else {
-        sa0[ii] = 0;
-        sa1[ii] = -(1 << 28);  // fails every bounds check
-        sa2[ii] = -(1 << 28);
       }
     }
   }
-  // B-side state
-  unsigned sb0[LB];
   int sb1 = 0, sb2 = 0, sbc = 0;
-  (void)sb0; (void)sb1; (void)sb2; (void)sbc;
+  (void)sb1; (void)sb2; (void)sbc;
   if (OP == OP_FWD) {
 #pragma unroll
     for (int ii = 0; ii < LB; ++ii) {
       int nn = n0 + NW * KC_RPI * ii + kc_row;
-      sb0[ii] = nn < a.N ? (unsigned)(nn * a.Kred + kc_chunk * 8) * 2u : OOB;
+      vB[ii] = nn < a.N ? (unsigned)(nn * a.Kred + kc_chunk * 8) * 2u : OOB;
     }
   } else if (OP == OP_BWD_DATA) {
     // filter w[ko][tap][c]: k-row = ko (within the tap), chunk = 8 consecutive c
@@ -186,7 +249,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
     for (int ii = 0; ii < LB; ++ii) {
       int k = mc_k(BN, ii);
       int nn = n0 + mc_chunk(BN, k) * 8;
-      sb0[ii] = nn < a.N ? (unsigned)((k * g.R * g.S) * a.N + nn) * 2u : OOB;  // + (c0 * R * S + tap) * N * 2 per tile
+      vB[ii] = nn < a.N ? (unsigned)((k * g.R * g.S) * a.N + nn) * 2u : OOB;  // + (c0 * R * S + tap) * N * 2 per tile
     }
   } else {
     // x gathered: this lane's 8 columns (tap, c..c+7) are the same for every load (k & 7 does not depend on ii)
@@ -201,24 +264,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
       sb1 = -(1 << 28);
       sb2 = -(1 << 28);
     }
-  }
-  unsigned sam = 0;  // BWD_WEIGHT A: dy[(n,p,q)][k_out], chunk = 8 consecutive k_out
-  if (OP == OP_BWD_WEIGHT) {
+#pragma unroll
+    for (int ii = 0; ii < LB; ++ii) vB[ii] = 0;
+    // dy[(n,p,q)][k_out], chunk = 8 consecutive k_out: row j = k0 + k of the tile at (mm + j M) * 2
     int mm = m0 + mc_chunk(BM, mc_k(BM, 0)) * 8;
-    sam = mm < a.M ? (unsigned)mm * 2u : OOB;
+#pragma unroll
+    for (int ii = 0; ii < LA; ++ii) vA[ii] = mm < a.M ? (unsigned)(mm + mc_k(BM, ii) * a.M) * 2u : OOB;
   }
 
-  // Requesting k tile kt into ring stage st = LPT loads per thread (LA for A, then LB for B).  They are issued one
-  // at a time, in between the MFMA groups of the tile being multiplied, so that their address arithmetic runs in
-  // the shadow of the matrix pipe instead of in front of it.
+  // Requesting k tile kt into ring stage st = LPT loads per thread (LA for A, then LB for B), spread over the MFMA
+  // slots of the tile being multiplied.  TileCtx holds what is the same for the whole wavefront.
   struct TileCtx {
     int k0, c0, r, s;
-    unsigned tap, tapoff, tileoff;
+    unsigned tap, soffA, soffB;
+    unsigned rag;  // per lane: -1 when this lane's chunk of a ragged last k tile lies beyond the channel count
   };
   auto tile_ctx = [&](int kt) {
     TileCtx c;
     c.k0 = kt * TBK;
-    c.tap = 0; c.c0 = 0; c.r = 0; c.s = 0; c.tapoff = 0; c.tileoff = 0;
+    c.tap = 0; c.c0 = 0; c.r = 0; c.s = 0; c.soffA = 0; c.soffB = 0; c.rag = 0;
     // the whole tile lies inside one filter tap: wave-uniform values.  Either IC % TBK == 0, or there is only one tap
     // (1x1 layers, fully connected) and the last tile is ragged: chunks at or beyond IC are then not requested.
     if (OP != OP_BWD_WEIGHT) {
@@ -226,8 +290,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
       c.c0 = c.k0 - (int)c.tap * g.IC;
       c.r = (int)fd_div(c.tap, g.d_s);
       c.s = (int)c.tap - c.r * g.S;
-      c.tapoff = (unsigned)(c.r * g.row_pitch + c.s * g.s_step + c.c0) * 2u;
-      c.tileoff = (unsigned)((c.c0 * g.R * g.S + (int)c.tap) * a.N) * 2u;
+      if (GEN) {
+        c.soffA = (unsigned)(c.r * g.row_pitch + c.s * g.s_step + c.c0) * 2u;  // forward only
+      } else if (OP == OP_FWD) {
+        c.soffA = (unsigned)(c.r * g.row_pitch + c.s * g.s_step + c.c0) * 2u;
+      } else {
+        c.soffA = (unsigned)((g.R - 1 - c.r) * g.row_pitch + (g.S - 1 - c.s) * g.pix_step + c.c0) * 2u;
+      }
+      c.soffB = OP == OP_FWD ? (unsigned)c.k0 * 2u : (unsigned)((c.c0 * g.R * g.S + (int)c.tap) * a.N) * 2u;
+      c.rag = c.c0 + kc_chunk * 8 < g.IC ? 0u : OOB;
+    } else {
+      c.soffA = (unsigned)(c.k0 * a.M) * 2u;
     }
     return c;
   };
@@ -238,32 +311,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
       lds_byte* sB = sA + A_BYTES;
       if constexpr (Lidx < LA) {
         constexpr int ii = Lidx;
-        if constexpr (OP == OP_FWD) {
-          int ih = sa1[ii] + c.r, iw = sa2[ii] + c.s;
-          bool ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW && c.c0 + kc_chunk * 8 < g.IC;
-          jz_dma16(rsrcA, sA + (NW * ii + wave) * 1024, ok ? sa0[ii] + c.tapoff : OOB);
-        } else if constexpr (OP == OP_BWD_DATA) {
+        lds_byte* dst = sA + (NW * ii + wave) * 1024;
+        if constexpr (GEN && OP == OP_FWD) {
+          int ih = ga1[ii] + c.r, iw = ga2[ii] + c.s;
+          bool ok = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+          jz_dma16(rsrcA, dst, ok ? (vA[ii] + c.soffA) | c.rag : OOB);
+        } else if constexpr (GEN && OP == OP_BWD_DATA) {
           // input pixel (h,w) receives from output pixel ((h + pad - r) / stride, ...) when the division is exact
-          int th = sa1[ii] - c.r, tw = sa2[ii] - c.s;
+          int th = ga1[ii] - c.r, tw = ga2[ii] - c.s;
           int ih = (int)fd_div((unsigned)(th < 0 ? 0 : th), g.d_sh);
           int iw = (int)fd_div((unsigned)(tw < 0 ? 0 : tw), g.d_sw);
-          bool ok = ih * g.sh == th && iw * g.sw == tw && ih < g.IH && iw < g.IW &&  // false for negative th / tw too
-                    c.c0 + kc_chunk * 8 < g.IC;
-          unsigned off = (sa0[ii] + (unsigned)(ih * g.row_pitch + iw * g.pix_step + c.c0 + kc_chunk * 8)) * 2u;
-          jz_dma16(rsrcA, sA + (NW * ii + wave) * 1024, ok ? off : OOB);
-        } else {  // dy rows j = k0 + k
-          int j = c.k0 + mc_k(BM, ii);
-          unsigned off = (sam != OOB && j < a.Kred) ? sam + (unsigned)(j * a.M) * 2u : OOB;
-          jz_dma16(rsrcA, sA + (NW * ii + wave) * 1024, off);
+          bool ok = ih * g.sh == th && iw * g.sw == tw && ih < g.IH && iw < g.IW;  // false for negative th / tw too
+          unsigned off = (vA[ii] + (unsigned)(ih * g.row_pitch + iw * g.pix_step + c.c0 + kc_chunk * 8)) * 2u;
+          jz_dma16(rsrcA, dst, ok ? off | c.rag : OOB);
+        } else if constexpr (OP != OP_BWD_WEIGHT) {
+          // bit `tap` of the row's mask -> 0 / -1; an offset of -1 is outside every descriptor
+          const unsigned bad = (unsigned)__builtin_amdgcn_sbfe(invA[ii], c.tap, 1);
+          jz_dma16s(rsrcA, dst, vA[ii] | bad | c.rag, c.soffA);
+        } else {  // dy rows j = k0 + k; rows at or beyond the reduction length are not requested
+          const bool ok = c.k0 + mc_k(BM, ii) < a.Kred;
+          jz_dma16s(rsrcA, dst, ok ? vA[ii] : OOB, c.soffA);
         }
       } else {
         constexpr int ii = Lidx - LA;
+        lds_byte* dst = sB + (NW * ii + wave) * 1024;
         if constexpr (OP == OP_FWD) {
-          const bool ok = sb0[ii] != OOB && c.k0 + kc_chunk * 8 < a.Kred;
-          jz_dma16(rsrcB, sB + (NW * ii + wave) * 1024, ok ? sb0[ii] + (unsigned)c.k0 * 2u : OOB);
+          jz_dma16s(rsrcB, dst, vB[ii] | c.rag, c.soffB);
         } else if constexpr (OP == OP_BWD_DATA) {
-          const bool ok = sb0[ii] != OOB && c.c0 + mc_k(BN, ii) < g.IC;
-          jz_dma16(rsrcB, sB + (NW * ii + wave) * 1024, ok ? sb0[ii] + c.tileoff : OOB);
+          const bool ok = c.c0 + mc_k(BN, ii) < g.IC;
+          jz_dma16s(rsrcB, dst, ok ? vB[ii] : OOB, c.soffB);
         } else {  // x at this lane's tap for output pixel j
           int j = c.k0 + mc_k(BN, ii);
           unsigned n = fd_div((unsigned)j, g.d_ohow);
@@ -273,29 +349,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
           int ih = p * g.sh + sb1, iw = q * g.sw + sb2;
           bool ok = j < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
           unsigned off = (unsigned)(((int)n * g.IH + ih) * g.row_pitch + iw * g.pix_step + sbc) * 2u;
-          jz_dma16(rsrcB, sB + (NW * ii + wave) * 1024, ok ? off : OOB);
+          jz_dma16(rsrcB, dst, ok ? off : OOB);
         }
       }
     }
   };
-  // loads PART, PART + NKS, ... of the tile (PART in 0..NKS-1): one share per MFMA group
-  auto issue_part = [&](const TileCtx& c, int st, auto part_tag) {
-    constexpr int PART = decltype(part_tag)::value;
-    issue_load(c, st, std::integral_constant<int, PART>{});
-    issue_load(c, st, std::integral_constant<int, PART + NKS>{});
-    issue_load(c, st, std::integral_constant<int, PART + 2 * NKS>{});
-    issue_load(c, st, std::integral_constant<int, PART + 3 * NKS>{});
-  };
-  static_assert(LPT <= 4 * NKS, "issue_part covers at most 4 loads per MFMA group");
   static_assert(NST >= 3 && NST <= 8 && (NST - 2) * LPT <= 63, "ring depth: vmcnt is a 6-bit counter");
-  auto issue = [&](int kt, int st) {
+  auto issue = [&](int kt, int st) {  // all loads of a tile at once (prologue)
     TileCtx c = tile_ctx(kt);
-    issue_part(c, st, std::integral_constant<int, 0>{});
-    issue_part(c, st, std::integral_constant<int, 1>{});
-    if constexpr (NKS == 4) {
-      issue_part(c, st, std::integral_constant<int, 2>{});
-      issue_part(c, st, std::integral_constant<int, 3>{});
-    }
+    static_for<0, LPT>([&](auto l) { issue_load(c, st, l); });
   };
 
   // ---- MFMA operand read addresses (byte offsets inside a stage) --------------------------------
@@ -381,7 +443,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
       }
     }
   };
-  auto mma = [&](auto ks_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
+  // wait until at most KEEP LDS reads are outstanding and tie the operands of the coming MFMAs to that point
+  auto settle = [&](auto keep_tag, auto ks_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
+    constexpr int KEEP = decltype(keep_tag)::value;
+    lds_wait<KEEP>();
+#pragma unroll
+    for (int t = 0; t < TM; ++t) lds_pin(fa[t]);
+#pragma unroll
+    for (int t = 0; t < TN; ++t) lds_pin(fb[t]);
     if constexpr (MASKA) {
       // small-channel forward: the tail of each gathered run belongs to the next pixel, not to this filter row;
       // clear it so that it cannot contribute (its weights are zero, but 0 * Inf would not be)
@@ -396,20 +465,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
         __builtin_memcpy(&fa[t], &w, 16);
       }
     }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        // n operand in the first slot: each lane then owns 4 consecutive n for one m (row = lane % 32)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-  };
-  auto settle = [&](auto keep_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
-    constexpr int KEEP = decltype(keep_tag)::value;
-    lds_wait<KEEP>();
-#pragma unroll
-    for (int t = 0; t < TM; ++t) lds_pin(fa[t]);
-#pragma unroll
-    for (int t = 0; t < TN; ++t) lds_pin(fb[t]);
   };
   constexpr int READS = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);  // LDS reads per k step
   static_assert(READS <= 15, "lgkmcnt is a 4-bit counter");
@@ -427,48 +482,73 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   };
 
   // ---- the ring ---------------------------------------------------------------------------------
-  // One iteration multiplies tile i out of stage i % NST.  Its first operands (k step 0) were already read at the end
-  // of the previous iteration, so the matrix pipe never waits for an LDS round trip at the top of an iteration:
+  // One iteration multiplies tile i out of stage i % NST, k step by k step (NKS groups of G MFMAs).  The operands of
+  // a k step are read two steps ahead, right after the last MFMA of the group that used the same registers, so an
+  // LDS round trip has a whole group of MFMAs to hide behind:
   //
-  //     read k step 1 .. ; request part of tile i+NST-1 ; MFMA k step 0 ; ... ; all reads of tile i are in registers
-  //     wait until tile i+1 has landed ; BARRIER ; read k step 0 of tile i+1 ; MFMA last k step of tile i
+  //   group ks:  wait for the reads of step ks ; MFMA 0 ; [loads] ; MFMA 1 ; [loads] ; ... ; MFMA G-1 ;
+  //              (ks == NKS-2: wait until tile i+1 has landed and my reads of tile i are complete ; BARRIER)
+  //              read step ks+2 (of tile i+1 when ks+2 >= NKS) into the registers this group multiplied from
   //
-  // The barrier therefore sits between two MFMA groups.  It says two things: every wavefront's share of tile i+1
-  // is in LDS, and every wavefront has finished reading tile i (its operands are in registers), so stage i % NST
-  // may be overwritten by the loads requested in the next iteration.  Barriers are bare (no fence): a fenced
-  // barrier makes the compiler drain every LDS-direct load first (vmcnt(0)); the ordering that matters is spelled
-  // out by hand with vmcnt / lgkmcnt waits.
+  // The barrier says two things: every wavefront's share of tile i+1 is in LDS, and every wavefront holds the whole of
+  // tile i in registers, so stage i % NST may be overwritten by the loads requested in the next iteration.  Barriers
+  // are bare (no fence): a fenced barrier makes the compiler drain every LDS-direct load first (vmcnt(0)); the
+  // ordering that matters is spelled out by hand with vmcnt / lgkmcnt waits.
+  //
+  // Loads of tile i+NST-1: load l goes behind MFMA slot l * NSL / LPT of the NSL = NKS * max(G-1, 1) slots that carry
+  // no LDS reads.  LBAR of them are issued before the barrier of the iteration, the rest after it.
+  constexpr int SPG = G > 1 ? G - 1 : 1;   // load slots per group
+  constexpr int NSL = NKS * SPG;
+  constexpr int LBAR = []() constexpr {
+    int n = 0;
+    for (int l = 0; l < LPT; ++l) n += ((l * NSL / LPT) / SPG <= NKS - 2) ? 1 : 0;
+    return n;
+  }();
+  static_assert((NST - 3) * LPT + LBAR <= 63 && (NST - 3) * LPT + LBAR >= 0, "vmcnt range");
   half8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  // STEADY: request tile c into stage ist while multiplying; NEXT: there is a tile after this one
+  // STEADY: request tile c into stage ist while multiplying; has_next: there is a tile after this one
   auto iteration = [&](int st, auto steady_tag, const TileCtx& c, int ist, bool has_next, int younger_after_next) {
     constexpr bool ISSUE = decltype(steady_tag)::value;
     const unsigned sb = lds_base + (unsigned)(st * STAGE);
     const unsigned sb_next = lds_base + (unsigned)(((st + 1) % NST) * STAGE);
-    read_frags(sb, std::integral_constant<int, 1>{}, fa1, fb1);
-    if (ISSUE) issue_part(c, ist, std::integral_constant<int, 0>{});
-    settle(std::integral_constant<int, READS>{}, fa0, fb0);
-    mma(std::integral_constant<int, 0>{}, fa0, fb0);
-    if constexpr (NKS == 4) {
-      read_frags(sb, std::integral_constant<int, 2>{}, fa0, fb0);
-      if (ISSUE) issue_part(c, ist, std::integral_constant<int, 1>{});
-      settle(std::integral_constant<int, READS>{}, fa1, fb1);
-      mma(std::integral_constant<int, 1>{}, fa1, fb1);
-      read_frags(sb, std::integral_constant<int, NKS - 1>{}, fa1, fb1);
-      if (ISSUE) issue_part(c, ist, std::integral_constant<int, 2>{});
-      settle(std::integral_constant<int, READS>{}, fa0, fb0);
-      mma(std::integral_constant<int, 2>{}, fa0, fb0);
-      if (ISSUE) issue_part(c, ist, std::integral_constant<int, NKS - 1>{});
-    } else {
-      if (ISSUE) issue_part(c, ist, std::integral_constant<int, 1>{});
-    }
-    settle(std::integral_constant<int, 0>{}, fa1, fb1);  // every LDS read of this tile has completed
-    if (ISSUE || has_next) {
-      if (ISSUE) wait_vmcnt<(NST - 2) * LPT>();
-      else wait_tiles(younger_after_next);
-      __builtin_amdgcn_s_barrier();
-      read_frags(sb_next, std::integral_constant<int, 0>{}, fa0, fb0);
-    }
-    mma(std::integral_constant<int, NKS - 1>{}, fa1, fb1);
+    static_for<0, NKS>([&](auto ks_tag) {
+      constexpr int KS = decltype(ks_tag)::value;
+      half8(&fa)[TM] = (KS % 2 == 0) ? fa0 : fa1;
+      half8(&fb)[TN] = (KS % 2 == 0) ? fb0 : fb1;
+      // steady state: the reads of the following step (READS of them) may still be in flight; while draining the
+      // following step may not have been requested, so wait for everything
+      if constexpr (ISSUE) settle(std::integral_constant<int, READS>{}, ks_tag, fa, fb);
+      else settle(std::integral_constant<int, 0>{}, ks_tag, fa, fb);
+      sched_fence();
+      static_for<0, G>([&](auto q_tag) {
+        constexpr int Q = decltype(q_tag)::value;
+        constexpr int I = Q / TN, J = Q % TN;
+        // n operand in the first slot: each lane then owns 4 consecutive n for one m (row = lane % 32)
+        acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[J], fa[I], acc[I][J], 0, 0, 0);
+        sched_fence();
+        if constexpr (ISSUE && (Q < G - 1 || G == 1)) {
+          static_for<0, LPT>([&](auto l_tag) {
+            constexpr int Lx = decltype(l_tag)::value;
+            if constexpr ((Lx * NSL / LPT) / SPG == KS && (Lx * NSL / LPT) % SPG == Q) issue_load(c, ist, l_tag);
+          });
+          sched_fence();
+        }
+      });
+      if constexpr (KS + 2 < NKS) {
+        read_frags(sb, std::integral_constant<int, (KS + 2 < NKS ? KS + 2 : 0)>{}, fa, fb);
+      } else {
+        if (ISSUE || has_next) {
+          if constexpr (KS == NKS - 2) {
+            lds_wait<0>();  // the whole of this tile is in registers
+            if (ISSUE) wait_vmcnt<(NST - 3) * LPT + LBAR>();
+            else wait_tiles(younger_after_next);
+            __builtin_amdgcn_s_barrier();
+          }
+          read_frags(sb_next, std::integral_constant<int, (KS + 2 >= NKS ? KS + 2 - NKS : 0)>{}, fa, fb);
+        }
+      }
+      sched_fence();
+    });
   };
 
 #pragma unroll
@@ -478,6 +558,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
     wait_tiles(nk - 1);
     __builtin_amdgcn_s_barrier();
     read_frags(lds_base, std::integral_constant<int, 0>{}, fa0, fb0);
+    read_frags(lds_base, std::integral_constant<int, 1>{}, fa1, fb1);
   }
   int i = 0;
   for (; i + NST - 1 < nk; ++i) {  // steady state, branch-free body: NST-2 younger tiles stay in flight
