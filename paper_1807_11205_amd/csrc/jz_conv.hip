@@ -590,14 +590,14 @@ int env_int(const char* name) {
   return e ? atoi(e) : 0;
 }
 // debugging aids: JZ_IGEMM_BK=64, JZ_IGEMM_TILE=<BM*1000+BN>, JZ_IGEMM_SPLITS=<n>, JZ_IGEMM_WAVES=<4|8> override the
-// planner, JZ_IGEMM_VERBOSE=1 prints its choice (read once per call, not per candidate: the environment is searched
+// planner, JZ_IGEMM_NOTABLE=1 skips the table of measured choices, JZ_IGEMM_VERBOSE=1 prints the choice (read once per call, not per candidate: the environment is searched
 // linearly, and a tuning sweep may change them inside one process)
 struct Overrides {
-  int bk, tile, splits, waves, verbose;
+  int bk, tile, splits, waves, verbose, notable;
 };
 Overrides read_overrides() {
   return Overrides{env_int("JZ_IGEMM_BK"), env_int("JZ_IGEMM_TILE"), env_int("JZ_IGEMM_SPLITS"), env_int("JZ_IGEMM_WAVES"),
-                   env_int("JZ_IGEMM_VERBOSE")};
+                   env_int("JZ_IGEMM_VERBOSE"), env_int("JZ_IGEMM_NOTABLE")};
 }
 
 struct Plan {
@@ -634,14 +634,27 @@ struct Variant {
   double c0[3];  // fixed part
 };
 const Variant kVariants[] = {
-    {128, 128, 32, 4, 512, {0.387, 0.525, 0.450}, {8.0, 8.0, 6.0}},
-    {128, 64, 32, 4, 512, {0.310, 0.356, 0.306}, {8.0, 8.0, 6.0}},
-    {64, 128, 32, 4, 512, {0.292, 0.310, 0.354}, {8.0, 8.0, 6.0}},
-    {64, 64, 32, 4, 512, {0.218, 0.217, 0.240}, {8.0, 8.0, 6.0}},
-    {128, 128, 64, 8, 256, {0.516, 0.667, 0.615}, {8.0, 8.0, 6.0}},
-    {256, 128, 64, 8, 256, {0.785, 1.001, 0.918}, {8.0, 8.0, 6.0}},
-    {256, 128, 32, 8, 256, {0.500, 0.567, 0.504}, {8.0, 8.0, 6.0}},
-    {256, 256, 32, 8, 256, {0.813, 0.919, 0.724}, {8.0, 8.0, 6.0}},
+    {128, 128, 32, 4, 512, {0.306, 0.284, 0.415}, {8.3, 10.3, 8.0}},
+    {128, 64, 32, 4, 512, {0.243, 0.220, 0.307}, {8.3, 10.3, 8.0}},
+    {64, 128, 32, 4, 512, {0.246, 0.214, 0.336}, {8.3, 10.3, 8.0}},
+    {64, 64, 32, 4, 512, {0.202, 0.179, 0.272}, {8.3, 10.3, 8.0}},
+    {128, 128, 64, 8, 256, {0.441, 0.433, 0.534}, {8.3, 10.3, 8.0}},
+    {256, 128, 64, 8, 256, {0.664, 0.649, 0.822}, {8.3, 10.3, 8.0}},
+    {256, 128, 32, 8, 256, {0.380, 0.363, 0.415}, {8.3, 10.3, 8.0}},
+    {256, 256, 32, 8, 256, {0.623, 0.597, 0.824}, {8.3, 10.3, 8.0}},
+    {128, 128, 64, 4, 256, {0.501, 0.526, 0.721}, {8.3, 10.3, 8.0}},
+    {128, 64, 64, 4, 256, {0.395, 0.393, 0.463}, {8.3, 10.3, 8.0}},
+    {64, 128, 64, 4, 256, {0.378, 0.428, 0.583}, {8.3, 10.3, 8.0}},
+    {64, 64, 64, 4, 512, {0.374, 0.381, 0.374}, {8.3, 10.3, 8.0}},
+};
+
+// Measured choices for known GEMM shapes (written by `python -m paper_1807_11205_amd.tune --write`): the per-k-tile model
+// below ranks variants that differ by a few percent poorly, a table of cold-cache timings does not.
+struct Tuned {
+  int op, M, N, K, taps, scatter, BM, BN, bk, waves, splits;
+};
+const Tuned kTuned[] = {
+#include "jz_tuned.inc"
 };
 
 // bk64_ok: the 64-deep k tile is usable for this layer; forced_bk: the k tile depth is fixed (register path, packed mode)
@@ -653,7 +666,23 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   const Variant* bv = &kVariants[0];
   int bS = 1;
   if (!pl->fast) forced_bk = BK;  // the element-wise kernel: one shape (the first variant's), 64-deep tiles, ~8x slower
-  {
+  const Tuned* hit = nullptr;
+  if (pl->fast && !pl->packed && !pl->gen && !forced_bk && !ov.bk && !ov.tile && !ov.splits && !ov.waves && !ov.notable) {
+    const int taps = a.g.R * a.g.S;
+    for (const Tuned& t : kTuned)
+      if (t.op == oi && t.M == a.M && t.N == a.N && t.K == a.Kred && t.taps == taps && t.scatter == a.sc_on &&
+          (t.bk == 32 || bk64_ok)) {
+        hit = &t;
+        break;
+      }
+  }
+  if (hit) {
+    pl->BM = hit->BM; pl->BN = hit->BN; pl->bk = hit->bk; pl->waves = hit->waves;
+    pl->nst = hit->bk == 64 && hit->BM == 256 ? 3 : 4;
+    bS = hit->splits;
+    const int nkt_h = (a.Kred + hit->bk - 1) / hit->bk;
+    if (bS > 1 && (nkt_h / bS < 4 || a.sc_on)) bS = 1;  // the same admissibility rules as the search below
+  } else {
     for (const Variant& v : kVariants) {
       if (!pl->fast && &v != &kVariants[0]) break;
       if ((forced_bk || pl->gen) && (v.waves != 4 || v.bk != 32)) continue;  // those kernels exist as 4-wavefront variants only
@@ -673,7 +702,7 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
         long long blocks = tm * tn * ((nkt + kps - 1) / kps);
         long long rounds = (blocks + v.resident - 1) / v.resident;
         double t = v.c0[oi] + rounds * kps * v.tt[oi] * (vbk / (double)v.bk) * (pl->fast ? 1.0 : 8.0);
-        if (sp > 1) t += 0.16 * (2.0 * sp * (double)a.M * a.N * 4.0) / 1.0e6 + 4.0;
+        if (sp > 1) t += 0.185 * (2.0 * sp * (double)a.M * a.N * 4.0) / 1.0e6 + 1.8;
         if (t < best) { best = t; bv = &v; bS = sp; }
       }
     }

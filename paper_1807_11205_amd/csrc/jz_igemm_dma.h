@@ -360,6 +360,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
     static_for<0, LPT>([&](auto l) { issue_load(c, st, l); });
   };
 
+  // the first NST-1 tiles are requested before anything else is set up: their round trip to memory is the longest
+  // latency of the prologue, and the accumulator and read-address set-up below fits into it
+#pragma unroll
+  for (int s = 0; s < NST - 1; ++s)
+    if (s < nk) issue(kt_begin + s, s);
+  sched_fence();
+
   // ---- MFMA operand read addresses (byte offsets inside a stage) --------------------------------
   // KC: row = base + 32 t + lane % 32, chunk (2 ks + lane / 32) at position chunk ^ swizzle(row); one address per ks,
   //     the 32-row sub-tiles t are 32 * RB bytes apart and share the swizzle (immediate offset).
@@ -551,9 +558,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
     });
   };
 
-#pragma unroll
-  for (int s = 0; s < NST - 1; ++s)
-    if (s < nk) issue(kt_begin + s, s);
   if (nk > 0) {
     wait_tiles(nk - 1);
     __builtin_amdgcn_s_barrier();

@@ -1,0 +1,141 @@
+"""Tuning sweep for the implicit-GEMM planner: python -m paper_1807_11205_amd.tune [--json FILE] [--write]
+
+For every distinct convolution shape of ResNet-50 (batch 64) and each of forward / backward-data / backward-weight it
+times every kernel variant (output tile, k tile depth, wavefronts per workgroup) at every admissible split of the
+reduction, through the planner's JZ_IGEMM_* overrides, with the caches flushed before each timed launch (inside a
+training step every layer finds them cold).  `--write` turns the measurements into csrc/jz_tuned.inc, the table the
+planner consults before its cost model; `--json FILE` re-uses saved measurements instead of running on the GPU.
+"""
+import argparse
+import json
+import os
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+VARIANTS = [(128128, 32, 4), (128064, 32, 4), (64128, 32, 4), (64064, 32, 4), (128128, 64, 8), (256128, 64, 8),
+            (256128, 32, 8), (256256, 32, 8), (128128, 64, 4), (128064, 64, 4), (64128, 64, 4), (64064, 64, 4)]
+SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128]
+OPS = ("fwd", "bwd_data", "bwd_weight")
+BATCH = 64
+
+
+def gemm_dims(rec):
+    """(M, N, K, taps, scatter) of the GEMM the library runs for this record (see jz_igemm.h)."""
+    H, C, K, R, st = rec["H"], rec["C"], rec["K"], rec["R"], rec["stride"]
+    pad = (R - 1) // 2
+    P = (H + 2 * pad - R) // st + 1
+    if rec["op"] == "fwd":
+        return BATCH * P * P, K, R * R * C, R * R, 0
+    if rec["op"] == "bwd_data":
+        if R == 1 and st > 1:
+            return BATCH * P * P, C, K, 1, 1
+        return BATCH * H * H, C, R * R * K, R * R, 0
+    return K, R * R * C, BATCH * P * P, R * R, 0
+
+
+def sweep(path):
+    import torch
+    from . import api, shapes
+    h, dev = torch.float16, "cuda:0"
+    seen, layers = set(), []
+    for c in shapes.resnet50_convs():
+        key = (c.H, c.C, c.K, c.R, c.stride)
+        if key in seen or c.first:
+            continue
+        seen.add(key)
+        layers.append(c)
+    junk = torch.zeros(192 << 20, dtype=torch.float32, device=dev)
+    ws = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+
+    def timeit(fn, iters=3):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e9
+        for _ in range(iters):
+            junk.sum()  # read-only pass over 768 MB: evicts L2 and the last-level cache without leaving dirty lines
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best * 1e3
+
+    out = []
+    names = ("JZ_IGEMM_TILE", "JZ_IGEMM_BK", "JZ_IGEMM_WAVES", "JZ_IGEMM_SPLITS", "JZ_IGEMM_NOTABLE")
+    for cs in layers:
+        d = api.conv_desc(BATCH, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+        x = torch.randn(BATCH * cs.H * cs.H * cs.C, device=dev).to(h)
+        w = (torch.randn(cs.K * cs.R * cs.R * cs.C, device=dev) * 0.05).to(h)
+        dy = torch.randn(BATCH * cs.P * cs.P * cs.K, device=dev).to(h)
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        for opn, op in zip(OPS, (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)):
+            def run():
+                if opn == "fwd":
+                    api.jz_conv2d_fwd(d, x, w, y, ws)
+                elif opn == "bwd_data":
+                    api.jz_conv2d_bwd_data(d, dy, w, dx, ws)
+                else:
+                    api.jz_conv2d_bwd_weight(d, x, dy, dw, ws)
+            for k in names:
+                os.environ.pop(k, None)
+            res = {"planner": round(timeit(run), 1)}
+            os.environ["JZ_IGEMM_NOTABLE"] = "1"
+            res["model"] = round(timeit(run), 1)
+            for (t, bk, wv) in VARIANTS:
+                os.environ["JZ_IGEMM_TILE"], os.environ["JZ_IGEMM_BK"], os.environ["JZ_IGEMM_WAVES"] = str(t), str(bk), str(wv)
+                prev_need = None
+                for sp in SPLITS:
+                    os.environ["JZ_IGEMM_SPLITS"] = str(sp)
+                    try:
+                        need = api.jz_conv2d_workspace_bytes(op, d)
+                    except api.JzError:
+                        continue
+                    if need > ws.numel() or (sp > 1 and need in (0, prev_need)):
+                        continue  # too large, or the planner could not honour this split count
+                    prev_need = need
+                    res["%d.%d.%d/%d" % (t, bk, wv, sp)] = round(timeit(run), 1)
+            cands = [k for k in res if k not in ("planner", "model")]
+            best = min(cands, key=res.get)
+            out.append(dict(layer=cs.name, H=cs.H, C=cs.C, K=cs.K, R=cs.R, stride=cs.stride, op=opn, best=best,
+                            best_us=res[best], all=res))
+            print(cs.name, opn, "planner", res["planner"], "model", res["model"], "best", best, res[best], flush=True)
+            with open(path, "w") as f:
+                json.dump(out, f)
+    for k in names:
+        os.environ.pop(k, None)
+    return out
+
+
+def write_table(recs, path):
+    lines = ["// Generated by `python -m paper_1807_11205_amd.tune --write` from cold-cache timings on one MI355X (ResNet-50 layer",
+             "// shapes at batch 64).  {op, M, N, K, taps, scatter, BM, BN, k tile, wavefronts, splits}; the planner looks a GEMM",
+             "// up here first and falls back to its cost model."]
+    for r in recs:
+        cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
+        best = min(cands, key=cands.get)
+        fam, sp = best.split("/")
+        tile, bk, wv = (int(v) for v in fam.split("."))
+        M, N, K, taps, sc = gemm_dims(r)
+        lines.append("{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s},  // %s %s: %.1f us" % (
+            OPS.index(r["op"]), M, N, K, taps, sc, tile // 1000, tile % 1000, bk, wv, sp, r["layer"], r["op"], cands[best]))
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--json", default=None, help="saved measurements to use instead of running the sweep")
+    ap.add_argument("--out-json", default="gpurun_out/tune_sweep.json")
+    ap.add_argument("--write", action="store_true", help="write csrc/jz_tuned.inc")
+    a = ap.parse_args()
+    recs = json.load(open(a.json)) if a.json else sweep(a.out_json)
+    if a.write:
+        write_table(recs, os.path.join(PKG, "csrc", "jz_tuned.inc"))
+    tp = sum(r["all"]["planner"] for r in recs)
+    tb = sum(r["best_us"] for r in recs)
+    print("sum over distinct layer shapes: planner %.0f us, best variant %.0f us" % (tp, tb), file=sys.stderr)
+
+
+if __name__ == "__main__":
+    main()

@@ -80,6 +80,9 @@ VECTOR = [
     (3, 10, 10, 40, 24, 1, 1, 1, 0),       # 1x1 with channel counts that are multiples of 8 only: ragged last k tile
     (2, 9, 9, 72, 40, 1, 1, 2, 0),         # the same with stride 2 (scatter epilogue in backward-data)
     (2, 5, 5, 1000, 136, 1, 1, 1, 0),      # long ragged reduction (31 full k tiles + 8 channels)
+    (1, 12, 12, 32, 64, 7, 7, 1, 3),       # 49 taps: more than the 32-bit tap mask holds (per-load tap arithmetic)
+    (2, 11, 11, 64, 64, 3, 3, 1, 0),       # no padding: backward-data reads outside dy on every border
+    (2, 12, 12, 64, 96, 4, 4, 2, 1),       # even filter, stride 2
 ]
 
 
