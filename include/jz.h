@@ -148,6 +148,11 @@ int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes, void* hip
 int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
                       size_t ws_bytes, void* hip_stream);
 
+/* Writes into `text` (HOST, NUL-terminated, at most text_bytes) one line saying how the library would run this
+ * operation: GEMM dimensions, kernel variant (output tile, k tile depth, wavefronts), tiles, split of the reduction.
+ * For tuning and bug reports; the wording is not part of the contract.  Same status codes as the workspace query. */
+int jz_conv2d_describe_plan(int op, const jz_conv_desc* desc, char* text, size_t text_bytes);
+
 /* Human-readable name of a status code; static storage. */
 const char* jz_status_string(int status);
 

@@ -20,7 +20,7 @@ JZ_FWD, JZ_BWD_DATA, JZ_BWD_WEIGHT = 0, 1, 2
 JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
 
 EXPORTS = [
-    "jz_conv2d_workspace_bytes", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
+    "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update",
     "jz_status_string", "jz_version",
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
         vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         dp = ctypes.POINTER(jz_conv_desc)
         L.jz_conv2d_workspace_bytes.argtypes = [ci, dp, ctypes.POINTER(sz)]
+        L.jz_conv2d_describe_plan.argtypes = [ci, dp, ctypes.c_char_p, sz]
         for name in ("jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight"):
             getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.jz_gemm_fc_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
@@ -139,6 +140,12 @@ def jz_conv2d_workspace_bytes(op: int, desc: jz_conv_desc) -> int:
     n = ctypes.c_size_t(0)
     _check(lib().jz_conv2d_workspace_bytes(op, ctypes.byref(desc), ctypes.byref(n)), "jz_conv2d_workspace_bytes")
     return n.value
+
+
+def jz_conv2d_describe_plan(op: int, desc: jz_conv_desc) -> str:
+    buf = ctypes.create_string_buffer(256)
+    _check(lib().jz_conv2d_describe_plan(op, ctypes.byref(desc), buf, 256), "jz_conv2d_describe_plan")
+    return buf.value.decode()
 
 
 def jz_conv2d_fwd(desc, x16, w16, y16, ws=None, stream=None):

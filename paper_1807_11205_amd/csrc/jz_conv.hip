@@ -728,6 +728,14 @@ void finish_geometry(ConvGeom& g) {
   g.d_sw = make_fastdiv((unsigned)g.sw);
 }
 
+void plan_text(const Plan& pl, char* buf, size_t n) {
+  const GemmArgs& a = pl.args;
+  snprintf(buf, n, "op %d M %d N %d K %d: %s tile %dx%dx%d, %d wavefronts, %d x %d tiles, %d splits of %d k tiles%s%s", pl.op, a.M,
+           a.N, a.Kred, pl.fast ? "vector" : "element-wise", pl.BM, pl.BN, pl.bk, pl.fast ? pl.waves : 4, a.tiles_m, a.tiles_n,
+           a.splits, a.kt_per_split, pl.packed ? ", 4-channel padded copy" : "",
+           a.sc_on ? ", scatter epilogue" : pl.gen ? ", per-load tap arithmetic" : "");
+}
+
 int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   if (!d) return JZ_ERR_NULL;
   if (op != JZ_FWD && op != JZ_BWD_DATA && op != JZ_BWD_WEIGHT) return JZ_ERR_UNSUPPORTED;
@@ -828,10 +836,11 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   const size_t part = a.splits > 1 ? (size_t)a.splits * a.M * a.N * sizeof(float) : 0;
   pl->part_offset = pl->packed ? pl->xp_bytes + pl->wp_bytes : 0;
   pl->ws_bytes = pl->part_offset + part;
-  if (ov.verbose)  // debugging aid: show what the planner chose
-    fprintf(stderr, "jz igemm op %d M %d N %d K %d: %s tile %dx%dx%d, %d x %d tiles, %d splits of %d k tiles%s%s\n", op, a.M,
-            a.N, a.Kred, pl->fast ? "vector" : "element-wise", pl->BM, pl->BN, pl->bk, a.tiles_m, a.tiles_n, a.splits,
-            a.kt_per_split, pl->packed ? ", 4-channel padded copy" : "", a.sc_on ? ", scatter epilogue" : "");
+  if (ov.verbose) {  // debugging aid: show what the planner chose
+    char line[256];
+    plan_text(*pl, line, sizeof line);
+    fprintf(stderr, "jz igemm %s\n", line);
+  }
   return JZ_OK;
 }
 
@@ -883,6 +892,14 @@ int launch_op(const Plan& pl, hipStream_t st) {
       if (pl.BN == 128 && pl.BM == 128) return launch_dma<OP_FWD, 128, 128, 64, 4, true>(a, st);
     }
     return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
+  }
+  if constexpr (OP != OP_BWD_WEIGHT) {
+    if (pl.gen && !use_register_path()) {  // the planner offers the 4-wavefront 32-deep tiles in this mode
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4, false, 2, 2, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4, false, 2, 2, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 4, false, 2, 2, true>(a, st);
+      return launch_dma<OP, 64, 64, 32, 4, false, 2, 2, true>(a, st);
+    }
   }
   if constexpr (OP != OP_BWD_WEIGHT) {
     if (pl.gen && !use_register_path()) {  // the planner offers the 4-wavefront 32-deep tiles in this mode
@@ -1001,6 +1018,15 @@ extern "C" int jz_conv2d_workspace_bytes(int op, const jz_conv_desc* desc, size_
   int rc = make_plan(op, desc, &pl);
   if (rc != JZ_OK) return rc;
   *bytes = pl.ws_bytes;
+  return JZ_OK;
+}
+
+extern "C" int jz_conv2d_describe_plan(int op, const jz_conv_desc* desc, char* text, size_t text_bytes) {
+  if (!text || text_bytes == 0) return JZ_ERR_NULL;
+  Plan pl;
+  int rc = make_plan(op, desc, &pl);
+  if (rc != JZ_OK) return rc;
+  plan_text(pl, text, text_bytes);
   return JZ_OK;
 }
 

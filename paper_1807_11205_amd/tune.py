@@ -12,6 +12,7 @@ import os
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
+# (tile, k tile depth, wavefronts)
 VARIANTS = [(128128, 32, 4), (128064, 32, 4), (64128, 32, 4), (64064, 32, 4), (128128, 64, 8), (256128, 64, 8),
             (256128, 32, 8), (256256, 32, 8), (128128, 64, 4), (128064, 64, 4), (64128, 64, 4), (64064, 64, 4)]
 SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128]
@@ -94,6 +95,10 @@ def sweep(path):
                     if need > ws.numel() or (sp > 1 and need in (0, prev_need)):
                         continue  # too large, or the planner could not honour this split count
                     prev_need = need
+                    plan = api.jz_conv2d_describe_plan(op, d)
+                    want = "tile %dx%dx%d, %d wavefronts" % (t // 1000, t % 1000, bk, wv)
+                    if want not in plan:
+                        continue  # the planner could not honour this combination for this layer
                     res["%d.%d.%d/%d" % (t, bk, wv, sp)] = round(timeit(run), 1)
             cands = [k for k in res if k not in ("planner", "model")]
             best = min(cands, key=res.get)
@@ -115,7 +120,7 @@ def write_table(recs, path):
         cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
         best = min(cands, key=cands.get)
         fam, sp = best.split("/")
-        tile, bk, wv = (int(v) for v in fam.split("."))
+        tile, bk, wv = (int(v) for v in fam.split(".")[:3])
         M, N, K, taps, sc = gemm_dims(r)
         lines.append("{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s},  // %s %s: %.1f us" % (
             OPS.index(r["op"]), M, N, K, taps, sc, tile // 1000, tile % 1000, bk, wv, sp, r["layer"], r["op"], cands[best]))
