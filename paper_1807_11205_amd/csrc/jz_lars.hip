@@ -31,9 +31,17 @@ constexpr int LARS_THREADS = 256;
 constexpr int LARS_WAVES = LARS_THREADS / 64;  // every wavefront of a chunk keeps its own partial sums
 constexpr uint64_t LARS_MAGIC = 0x4a5a4c4152533031ull;  // "JZLARS01"
 
+// Everything a workgroup needs to know about its chunk in one 16-byte record: a kernel's first loads then depend on
+// one table look-up, not on a chain of three (chunk -> tensor -> offsets), each a cold round trip to memory.
+struct ChunkRec {
+  int64_t start;  // first element
+  int count;      // elements (<= LARS_CH)
+  int tensor;
+};
+
 struct Layout {
   int64_t T = 0, P = 0, n_chunks = 0;
-  size_t off_header = 0, off_offsets = 0, off_chunk_begin = 0, off_flags = 0, off_chunk_tensor = 0;
+  size_t off_header = 0, off_offsets = 0, off_chunk_begin = 0, off_flags = 0, off_chunk_tensor = 0, off_chunk_rec = 0;
   size_t off_state = 0;
   size_t static_bytes = 0;  // everything up to here is written by prepare
   size_t off_psum_w = 0, off_psum_g = 0, off_pflag = 0, off_coef = 0, off_tflag = 0, total = 0;
@@ -65,6 +73,7 @@ int make_layout(const jz_param_set* ps, Layout* L) {
   L->off_chunk_begin = o;   o = up256(o + sizeof(int) * (L->T + 1));
   L->off_flags = o;         o = up256(o + sizeof(int) * (L->T ? L->T : 1));
   L->off_chunk_tensor = o;  o = up256(o + sizeof(int) * (chunks ? chunks : 1));
+  L->off_chunk_rec = o;     o = up256(o + sizeof(ChunkRec) * (chunks ? chunks : 1));
   L->off_state = o;         o = up256(o + 64);
   L->static_bytes = o;
   const size_t parts = (size_t)(chunks ? chunks : 1) * LARS_WAVES;
@@ -115,6 +124,7 @@ struct Tables {
   const int* chunk_begin;
   const int* flags;
   const int* chunk_tensor;
+  const ChunkRec* chunk_rec;
   int* state;    // [0]: 1 when psum_w holds the sums of squares of the current master weights
   double* psum_w;  // [n_chunks][LARS_WAVES] partial sums of w^2: one per wavefront, so that no kernel needs a barrier
   double* psum_g;  // same for the (loss-scaled) gradient
@@ -156,13 +166,10 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-__device__ __forceinline__ void chunk_range(const Tables& tb, int c, int* t_out, int64_t* start, int64_t* end) {
-  int t = tb.chunk_tensor[c];
-  int64_t s = tb.offsets[t] + (int64_t)(c - tb.chunk_begin[t]) * LARS_CH;
-  int64_t e = tb.offsets[t + 1];
-  *t_out = t;
-  *start = s;
-  *end = (s + LARS_CH < e) ? s + LARS_CH : e;
+__device__ __forceinline__ void chunk_range(const ChunkRec& r, int* t_out, int64_t* start, int64_t* end) {
+  *t_out = r.tensor;
+  *start = r.start;
+  *end = r.start + r.count;
 }
 
 constexpr int LARS_IT = LARS_CH / (LARS_THREADS * 8);  // 8-element groups per thread and chunk
@@ -214,12 +221,13 @@ __device__ __forceinline__ void chunk_body(int64_t s, int64_t e, int64_t* b0, in
 
 __global__ __launch_bounds__(LARS_THREADS) void lars_reduce(Tables tb, const float* __restrict__ w,
                                                             const unsigned short* __restrict__ g16) {
-  if (!table_ok(tb)) return;
   const int c = blockIdx.x;
+  const ChunkRec rec = tb.chunk_rec[c];  // requested together with the header: garbage if the header is, but then unused
   const bool have_w = tb.state[0] != 0;  // written by the previous update, i.e. by an earlier launch
+  if (!table_ok(tb)) return;
   int t;
   int64_t s, e, b0, b1;
-  chunk_range(tb, c, &t, &s, &e);
+  chunk_range(rec, &t, &s, &e);
   chunk_body(s, e, &b0, &b1);
   double sw = 0.0, sg = 0.0;
   int bad = 0;
@@ -329,12 +337,16 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
                                                             const unsigned short* __restrict__ g16,
                                                             unsigned short* __restrict__ w16, float m, float wd,
                                                             float inv_s, int* __restrict__ found_inf) {
+  // the header, this workgroup's chunk record and the tensor flags are requested together; nothing read through the
+  // tables is used before the header has been checked
+  const int cidx = (int)blockIdx.x < tb.n_chunks ? tb.n_chunks - 1 - (int)blockIdx.x : 0;
+  const ChunkRec rec = tb.n_chunks > 0 ? tb.chunk_rec[cidx] : ChunkRec{0, 0, 0};
+  int f = 0;  // every wavefront looks at all tensor flags itself: no barrier anywhere in this kernel
+  for (int t = threadIdx.x & 63; t < tb.T; t += 64) f |= tb.tflag[t];
   if (!table_ok(tb)) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *found_inf = -1;
     return;
   }
-  int f = 0;  // every wavefront looks at all tensor flags itself: no barrier anywhere in this kernel
-  for (int t = threadIdx.x & 63; t < tb.T; t += 64) f |= tb.tflag[t];
   f = __any(f);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *found_inf = f ? 1 : 0;
@@ -342,10 +354,10 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   }
   if (f) return;  // overflow under loss scaling: the step is skipped as a whole
   if ((int)blockIdx.x >= tb.n_chunks) return;
-  const int c = tb.n_chunks - 1 - blockIdx.x;
+  const int c = cidx;
   int t;
   int64_t s, e, b0, b1;
-  chunk_range(tb, c, &t, &s, &e);
+  chunk_range(rec, &t, &s, &e);
   chunk_body(s, e, &b0, &b1);
   const float coef = tb.coef[t];
   const float lam = (tb.flags[t] & JZ_PARAM_WEIGHT_DECAY) ? wd : 0.0f;
@@ -413,6 +425,7 @@ Tables make_tables(const Layout& L, void* ws, uint64_t sum) {
   tb.chunk_begin = reinterpret_cast<const int*>(b + L.off_chunk_begin);
   tb.flags = reinterpret_cast<const int*>(b + L.off_flags);
   tb.chunk_tensor = reinterpret_cast<const int*>(b + L.off_chunk_tensor);
+  tb.chunk_rec = reinterpret_cast<const ChunkRec*>(b + L.off_chunk_rec);
   tb.state = reinterpret_cast<int*>(b + L.off_state);
   tb.psum_w = reinterpret_cast<double*>(b + L.off_psum_w);
   tb.psum_g = reinterpret_cast<double*>(b + L.off_psum_g);
@@ -454,6 +467,7 @@ extern "C" int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes
   int* cb = reinterpret_cast<int*>(host.data() + L.off_chunk_begin);
   int* fl = reinterpret_cast<int*>(host.data() + L.off_flags);
   int* ct = reinterpret_cast<int*>(host.data() + L.off_chunk_tensor);
+  ChunkRec* cr = reinterpret_cast<ChunkRec*>(host.data() + L.off_chunk_rec);
   int c = 0;
   off[0] = 0;
   cb[0] = 0;
@@ -463,7 +477,12 @@ extern "C" int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes
     fl[t] = ps->flags[t];
     int64_t n = ps->offsets[t + 1] - ps->offsets[t];
     int nc = (int)((n + LARS_CH - 1) / LARS_CH);
-    for (int k = 0; k < nc; ++k) ct[c + k] = (int)t;
+    for (int k = 0; k < nc; ++k) {
+      ct[c + k] = (int)t;
+      const int64_t st0 = ps->offsets[t] + (int64_t)k * LARS_CH;
+      const int64_t en = st0 + LARS_CH < ps->offsets[t + 1] ? st0 + LARS_CH : ps->offsets[t + 1];
+      cr[c + k] = ChunkRec{st0, (int)(en - st0), (int)t};
+    }
     c += nc;
     cb[t + 1] = c;
   }
