@@ -117,11 +117,58 @@ __device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[
 // ---------------------------------------------------------------------------------------------
 // wrow / wcol: first row / column of this wavefront's share inside the BM x BN tile; NTHREADS: workgroup size;
 // EPASS: the fp16 tile is staged through LDS in EPASS slabs of BM / EPASS rows (a 256x256 tile is larger than the ring)
-template <int BM, int BN, int TM, int TN, int NTHREADS, int EPASS = 1>
+// slabs of rows the fp32 tile of a split reduction is staged in: the slab has to fit LDS_BYTES and hold whole wavefront
+// shares (WTM rows); 0 when no such slab exists (the partial sums are then stored straight from the registers)
+constexpr int fp32_slabs(int bm, int bn, int wtm, int lds_bytes) {
+  for (int s = 1; bm / s >= wtm; s *= 2)
+    if ((bm / s) * (bn + 4) * 4 <= lds_bytes) return s;
+  return 0;
+}
+
+template <int BM, int BN, int TM, int TN, int NTHREADS, int EPASS = 1, int LDS_BYTES = 0>
 __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&acc)[TM][TN], unsigned short* lds, int m0,
                                                     int n0, int split, int tid, int lane, int wrow, int wcol) {
   // ---- epilogue ------------------------------------------------------------------------------
   // accumulator register r of tile (i,j): m = wrow + 32 i + lane%32, n = wcol + 32 j + 8 (r/4) + 4 (lane/32) + r%4
+  constexpr int FSL = fp32_slabs(BM, BN, 32 * TM, LDS_BYTES);
+  if (a.splits > 1 && FSL > 0 && (a.N & 3) == 0) {
+    // fp32 partial sums, staged through LDS slab by slab so that a store instruction writes whole 512-byte row pieces
+    // (from the registers a wavefront would write 32 rows x 32 bytes per instruction)
+    float* P = a.Dpart + (size_t)split * a.M * a.N;
+    constexpr int LDF = BN + 4;            // floats per staged row: 16-byte aligned, rows 16 bytes apart in the banks
+    constexpr int RPB = BM / (FSL > 0 ? FSL : 1);  // rows per slab
+    constexpr int FCH = BN / 4;            // 16-byte chunks per row
+    constexpr int FRPP = NTHREADS / FCH;   // rows per store pass
+    static_assert(FRPP >= 1 && RPB % FRPP == 0, "slab rows must divide among the store passes");
+    float* sF = reinterpret_cast<float*>(lds);
+    const int fch = tid % FCH, frow = tid / FCH;
+#pragma unroll
+    for (int ps = 0; ps < FSL; ++ps) {
+      if (ps > 0) __syncthreads();  // the previous slab has been stored
+      if (FSL == 1 || wrow / RPB == ps) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              int row = wrow - ps * RPB + 32 * i + (lane & 31);
+              int col = wcol + 32 * j + 8 * q4 + 4 * (lane >> 5);
+              *reinterpret_cast<float4*>(sF + row * LDF + col) =
+                  make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
+            }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < RPB / FRPP; ++i) {
+        int row = frow + FRPP * i;
+        int m = m0 + ps * RPB + row, n = n0 + fch * 4;
+        if (m >= a.M || n >= a.N) continue;
+        *reinterpret_cast<float4*>(P + (size_t)m * a.N + n) = *reinterpret_cast<const float4*>(sF + row * LDF + fch * 4);
+      }
+    }
+    return;
+  }
   if (a.splits > 1) {
     float* P = a.Dpart + (size_t)split * a.M * a.N;
     const bool vec = (a.N & 3) == 0;
@@ -216,7 +263,9 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
 template <int BM, int BN>
 __device__ __forceinline__ void igemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / 64][BN / 64], unsigned short* lds,
                                                int m0, int n0, int split, int tid, int lane, int wm, int wn) {
-  igemm_epilogue_impl<BM, BN, BM / 64, BN / 64, THREADS>(a, acc, lds, m0, n0, split, tid, lane, wm * (BM / 2), wn * (BN / 2));
+  constexpr int tile_bytes = 2 * (BM + BN) * LDK * 2, epi_bytes = BM * (BN + 8) * 2;
+  igemm_epilogue_impl<BM, BN, BM / 64, BN / 64, THREADS, 1, (tile_bytes > epi_bytes ? tile_bytes : epi_bytes)>(
+      a, acc, lds, m0, n0, split, tid, lane, wm * (BM / 2), wn * (BN / 2));
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -575,5 +575,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   }
   __syncthreads();  // the epilogue reuses the ring as its staging tile
 
-  igemm_epilogue_impl<BM, BN, TM, TN, NT, dma_epass(BM, BN)>(a, acc, lds, m0, n0, split, tid, lane, wm * WTM, wn * WTN);
+  constexpr int ring_bytes = NST * STAGE, epi_bytes = BM / dma_epass(BM, BN) * (BN + 8) * 2;
+  igemm_epilogue_impl<BM, BN, TM, TN, NT, dma_epass(BM, BN), (ring_bytes > epi_bytes ? ring_bytes : epi_bytes)>(
+      a, acc, lds, m0, n0, split, tid, lane, wm * WTM, wn * WTN);
 }

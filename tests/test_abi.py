@@ -63,3 +63,44 @@ def test_lars_table_validation_on_the_host(jzlib):
     assert L.jz_lars_workspace_bytes(ctypes.byref(ps([0, 2 ** 31], [3])), ctypes.byref(n)) == jzlib.JZ_ERR_UNSUPPORTED
     assert L.jz_lars_workspace_bytes(None, ctypes.byref(n)) == jzlib.JZ_ERR_NULL
     assert L.jz_lars_workspace_bytes(ctypes.byref(ps([0, 8], [3])), None) == jzlib.JZ_ERR_NULL
+
+
+def test_describe_plan_for_every_resnet50_and_alexnet_layer(jzlib):
+    # host logic only: the planner must produce a runnable plan (a kernel variant that exists, a workspace size) for
+    # every layer of the two models of the paper's Table 3, with and without its table of measured choices
+    import re
+    from paper_1807_11205_amd import shapes
+    known = {(128, 128, 32, 4), (128, 64, 32, 4), (64, 128, 32, 4), (64, 64, 32, 4), (128, 128, 64, 8), (256, 128, 64, 8),
+             (256, 128, 32, 8), (256, 256, 32, 8), (128, 128, 64, 4), (128, 64, 64, 4), (64, 128, 64, 4), (64, 64, 64, 4)}
+    layers = [(64, c) for c in shapes.resnet50_convs()] + [(128, c) for c in shapes.alexnet_convs()]
+    for notable in ("0", "1"):
+        os.environ["JZ_IGEMM_NOTABLE"] = notable
+        try:
+            for batch, cs in layers:
+                d = jzlib.conv_desc(batch, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+                for op in (jzlib.JZ_FWD, jzlib.JZ_BWD_DATA, jzlib.JZ_BWD_WEIGHT):
+                    text = jzlib.jz_conv2d_describe_plan(op, d)
+                    m = re.search(r"(vector|element-wise) tile (\d+)x(\d+)x(\d+), (\d+) wavefronts, (\d+) x (\d+) tiles, (\d+) splits of (\d+) k tiles", text)
+                    assert m, text
+                    bm, bn, bk, wv, tm, tn, sp, kps = (int(v) for v in m.groups()[1:])
+                    if m.group(1) == "vector":
+                        assert (bm, bn, bk, wv) in known, text
+                    assert tm >= 1 and tn >= 1 and sp >= 1 and kps >= 1
+                    ws = jzlib.jz_conv2d_workspace_bytes(op, d)
+                    assert (ws > 0) == (sp > 1 or "padded copy" in text), text
+        finally:
+            os.environ.pop("JZ_IGEMM_NOTABLE", None)
+
+
+def test_tuned_table_is_used_for_the_benchmark_shapes(jzlib):
+    # a stage-4 3x3 layer of ResNet-50 at batch 64 is in the table of measured choices; switching the table off must be
+    # able to change the plan, switching it on must give the table's entry
+    d = jzlib.conv_desc(64, 14, 14, 256, 256, 3, 3, 1, 1)
+    with_table = jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, d)
+    assert "M 256 N 2304 K 12544" in with_table
+    os.environ["JZ_IGEMM_TILE"] = "64064"
+    try:
+        forced = jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, d)
+    finally:
+        os.environ.pop("JZ_IGEMM_TILE", None)
+    assert "tile 64x64x" in forced      # an override bypasses the table
