@@ -834,6 +834,8 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
     pl->bytesA = 2 * ny; pl->bytesB = 2 * nx; pl->bytesD = 2 * nw;  // A = dy, B = x
   }
   a.sc_on = 0; a.sc_H = a.sc_W = 0; a.sc_sh = a.sc_sw = 1;
+  a.bw_linear = (op == JZ_BWD_WEIGHT && d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 &&
+                 d->pad_w == 0) ? 1 : 0;
   if (op == JZ_BWD_DATA && pl->fast && !use_register_path() && d->R == 1 && d->S == 1 && d->pad_h == 0 && d->pad_w == 0 &&
       (d->stride_h > 1 || d->stride_w > 1)) {
     // strided 1x1 layer (the ResNet downsampling convs): only input pixels (p*sh, q*sw) receive gradient, so the GEMM

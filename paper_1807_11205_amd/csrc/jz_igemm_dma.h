@@ -264,8 +264,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
       sb1 = -(1 << 28);
       sb2 = -(1 << 28);
     }
+    // 1x1, unit stride, no padding: pixel j of x is row j of a plain [Kred][IC] matrix, so the load needs no pixel
+    // arithmetic at all (per-lane offset fixed, per-tile offset scalar)
 #pragma unroll
-    for (int ii = 0; ii < LB; ++ii) vB[ii] = 0;
+    for (int ii = 0; ii < LB; ++ii) vB[ii] = (a.bw_linear && nn < a.N) ? (unsigned)(mc_k(BN, ii) * g.IC + nn) * 2u : OOB;
     // dy[(n,p,q)][k_out], chunk = 8 consecutive k_out: row j = k0 + k of the tile at (mm + j M) * 2
     int mm = m0 + mc_chunk(BM, mc_k(BM, 0)) * 8;
 #pragma unroll
@@ -301,6 +303,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
       c.rag = c.c0 + kc_chunk * 8 < g.IC ? 0u : OOB;
     } else {
       c.soffA = (unsigned)(c.k0 * a.M) * 2u;
+      c.soffB = (unsigned)(c.k0 * g.IC) * 2u;  // used by the plain-matrix case only
     }
     return c;
   };
@@ -339,6 +342,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
           jz_dma16s(rsrcB, dst, vB[ii] | c.rag, c.soffB);
         } else if constexpr (OP == OP_BWD_DATA) {
           const bool ok = c.c0 + mc_k(BN, ii) < g.IC;
+          jz_dma16s(rsrcB, dst, ok ? vB[ii] : OOB, c.soffB);
+        } else if (a.bw_linear) {  // x rows j = k0 + k of a plain matrix
+          const bool ok = c.k0 + mc_k(BN, ii) < a.Kred;
           jz_dma16s(rsrcB, dst, ok ? vB[ii] : OOB, c.soffB);
         } else {  // x at this lane's tap for output pixel j
           int j = c.k0 + mc_k(BN, ii);
