@@ -638,15 +638,15 @@ int env_int(const char* name) {
   const char* e = getenv(name);
   return e ? atoi(e) : 0;
 }
-// debugging aids: JZ_IGEMM_BK=64, JZ_IGEMM_TILE=<BM*1000+BN>, JZ_IGEMM_SPLITS=<n>, JZ_IGEMM_WAVES=<4|8> override the
+// debugging aids: JZ_IGEMM_BK=64, JZ_IGEMM_TILE=<BM*1000+BN>, JZ_IGEMM_SPLITS=<n>, JZ_IGEMM_WAVES=<4|8>, JZ_IGEMM_NST=<ring depth> override the
 // planner, JZ_IGEMM_NOTABLE=1 skips the table of measured choices, JZ_IGEMM_VERBOSE=1 prints the choice (read once per call, not per candidate: the environment is searched
 // linearly, and a tuning sweep may change them inside one process)
 struct Overrides {
-  int bk, tile, splits, waves, verbose, notable;
+  int bk, tile, splits, waves, verbose, notable, nst;
 };
 Overrides read_overrides() {
   return Overrides{env_int("JZ_IGEMM_BK"), env_int("JZ_IGEMM_TILE"), env_int("JZ_IGEMM_SPLITS"), env_int("JZ_IGEMM_WAVES"),
-                   env_int("JZ_IGEMM_VERBOSE"), env_int("JZ_IGEMM_NOTABLE")};
+                   env_int("JZ_IGEMM_VERBOSE"), env_int("JZ_IGEMM_NOTABLE"), env_int("JZ_IGEMM_NST")};
 }
 
 struct Plan {
@@ -681,26 +681,34 @@ struct Variant {
   int BM, BN, bk, waves, resident;
   double tt[3];  // per k tile: forward, backward-data, backward-weight
   double c0[3];  // fixed part
+  int nst;       // ring depth
 };
 const Variant kVariants[] = {
-    {128, 128, 32, 4, 512, {0.306, 0.284, 0.415}, {8.3, 10.3, 8.0}},
-    {128, 64, 32, 4, 512, {0.243, 0.220, 0.307}, {8.3, 10.3, 8.0}},
-    {64, 128, 32, 4, 512, {0.246, 0.214, 0.336}, {8.3, 10.3, 8.0}},
-    {64, 64, 32, 4, 512, {0.202, 0.179, 0.272}, {8.3, 10.3, 8.0}},
-    {128, 128, 64, 8, 256, {0.441, 0.433, 0.534}, {8.3, 10.3, 8.0}},
-    {256, 128, 64, 8, 256, {0.664, 0.649, 0.822}, {8.3, 10.3, 8.0}},
-    {256, 128, 32, 8, 256, {0.380, 0.363, 0.415}, {8.3, 10.3, 8.0}},
-    {256, 256, 32, 8, 256, {0.623, 0.597, 0.824}, {8.3, 10.3, 8.0}},
-    {128, 128, 64, 4, 256, {0.501, 0.526, 0.721}, {8.3, 10.3, 8.0}},
-    {128, 64, 64, 4, 256, {0.395, 0.393, 0.463}, {8.3, 10.3, 8.0}},
-    {64, 128, 64, 4, 256, {0.378, 0.428, 0.583}, {8.3, 10.3, 8.0}},
-    {64, 64, 64, 4, 512, {0.374, 0.381, 0.374}, {8.3, 10.3, 8.0}},
+    {128, 128, 32, 4, 512, {0.306, 0.284, 0.415}, {8.3, 10.3, 8.0}, 4},
+    {128, 64, 32, 4, 512, {0.243, 0.220, 0.307}, {8.3, 10.3, 8.0}, 4},
+    {64, 128, 32, 4, 512, {0.246, 0.214, 0.336}, {8.3, 10.3, 8.0}, 4},
+    {64, 64, 32, 4, 512, {0.202, 0.179, 0.272}, {8.3, 10.3, 8.0}, 4},
+    {128, 128, 64, 8, 256, {0.441, 0.433, 0.534}, {8.3, 10.3, 8.0}, 4},
+    {256, 128, 64, 8, 256, {0.664, 0.649, 0.822}, {8.3, 10.3, 8.0}, 3},
+    {256, 128, 32, 8, 256, {0.380, 0.363, 0.415}, {8.3, 10.3, 8.0}, 4},
+    {256, 256, 32, 8, 256, {0.623, 0.597, 0.824}, {8.3, 10.3, 8.0}, 4},
+    {128, 128, 64, 4, 256, {0.501, 0.526, 0.721}, {8.3, 10.3, 8.0}, 4},
+    {128, 64, 64, 4, 256, {0.395, 0.393, 0.463}, {8.3, 10.3, 8.0}, 4},
+    {64, 128, 64, 4, 256, {0.378, 0.428, 0.583}, {8.3, 10.3, 8.0}, 4},
+    {64, 64, 64, 4, 512, {0.374, 0.381, 0.374}, {8.3, 10.3, 8.0}, 4},
+    // three-stage rings for the 4-wavefront 32-deep tiles: 48 / 36 / 24 KB of LDS, three to six workgroups per compute
+    // unit, for layers whose reduction is only a few k tiles long (a workgroup's prologue and epilogue then overlap
+    // with the loops of more neighbours)
+    {128, 128, 32, 4, 768, {0.306, 0.284, 0.415}, {8.3, 10.3, 8.0}, 3},
+    {128, 64, 32, 4, 1024, {0.243, 0.220, 0.307}, {8.3, 10.3, 8.0}, 3},
+    {64, 128, 32, 4, 1024, {0.246, 0.214, 0.336}, {8.3, 10.3, 8.0}, 3},
+    {64, 64, 32, 4, 1536, {0.202, 0.179, 0.272}, {8.3, 10.3, 8.0}, 3},
 };
 
 // Measured choices for known GEMM shapes (written by `python -m paper_1807_11205_amd.tune --write`): the per-k-tile model
 // below ranks variants that differ by a few percent poorly, a table of cold-cache timings does not.
 struct Tuned {
-  int op, M, N, K, taps, scatter, BM, BN, bk, waves, splits;
+  int op, M, N, K, taps, scatter, BM, BN, bk, waves, nst, splits;
 };
 const Tuned kTuned[] = {
 #include "jz_tuned.inc"
@@ -716,7 +724,7 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   int bS = 1;
   if (!pl->fast) forced_bk = BK;  // the element-wise kernel: one shape (the first variant's), 64-deep tiles, ~8x slower
   const Tuned* hit = nullptr;
-  if (pl->fast && !pl->packed && !pl->gen && !forced_bk && !ov.bk && !ov.tile && !ov.splits && !ov.waves && !ov.notable) {
+  if (pl->fast && !pl->packed && !pl->gen && !forced_bk && !ov.bk && !ov.tile && !ov.splits && !ov.waves && !ov.nst && !ov.notable) {
     const int taps = a.g.R * a.g.S;
     for (const Tuned& t : kTuned)
       if (t.op == oi && t.M == a.M && t.N == a.N && t.K == a.Kred && t.taps == taps && t.scatter == a.sc_on &&
@@ -727,7 +735,7 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   }
   if (hit) {
     pl->BM = hit->BM; pl->BN = hit->BN; pl->bk = hit->bk; pl->waves = hit->waves;
-    pl->nst = hit->bk == 64 && hit->BM == 256 ? 3 : 4;
+    pl->nst = hit->nst;
     bS = hit->splits;
     const int nkt_h = (a.Kred + hit->bk - 1) / hit->bk;
     if (bS > 1 && (nkt_h / bS < 4 || a.sc_on)) bS = 1;  // the same admissibility rules as the search below
@@ -740,6 +748,8 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
       if (!forced_bk && ov.bk && ov.bk != v.bk) continue;
       if (ov.tile && ov.tile != v.BM * 1000 + v.BN) continue;
       if (ov.waves && ov.waves != v.waves) continue;
+      if (ov.nst && ov.nst != v.nst) continue;
+      if (v.nst == 3 && v.bk == 32 && ov.nst != 3) continue;  // short rings: from the table of measured choices or on request
       const int vbk = forced_bk ? forced_bk : v.bk;
       const int nkt = (a.Kred + vbk - 1) / vbk;
       long long tm = (a.M + v.BM - 1) / v.BM, tn = (a.N + v.BN - 1) / v.BN;
@@ -759,7 +769,7 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
     pl->BM = bv->BM; pl->BN = bv->BN;
     pl->bk = forced_bk ? forced_bk : bv->bk;
     pl->waves = bv->waves;
-    pl->nst = bv->bk == 64 && bv->BM == 256 ? 3 : 4;
+    pl->nst = bv->nst;
   }
   a.nkt = (a.Kred + pl->bk - 1) / pl->bk;
   a.tiles_m = (a.M + pl->BM - 1) / pl->BM;
@@ -779,8 +789,9 @@ void finish_geometry(ConvGeom& g) {
 
 void plan_text(const Plan& pl, char* buf, size_t n) {
   const GemmArgs& a = pl.args;
-  snprintf(buf, n, "op %d M %d N %d K %d: %s tile %dx%dx%d, %d wavefronts, %d x %d tiles, %d splits of %d k tiles%s%s", pl.op, a.M,
-           a.N, a.Kred, pl.fast ? "vector" : "element-wise", pl.BM, pl.BN, pl.bk, pl.fast ? pl.waves : 4, a.tiles_m, a.tiles_n,
+  snprintf(buf, n, "op %d M %d N %d K %d: %s tile %dx%dx%d, %d wavefronts, ring %d, %d x %d tiles, %d splits of %d k tiles%s%s", pl.op, a.M,
+           a.N, a.Kred, pl.fast ? "vector" : "element-wise", pl.BM, pl.BN, pl.bk, pl.fast ? pl.waves : 4,
+           pl.fast ? pl.nst : 2, a.tiles_m, a.tiles_n,
            a.splits, a.kt_per_split, pl.packed ? ", 4-channel padded copy" : "",
            a.sc_on ? ", scatter epilogue" : pl.gen ? ", per-load tap arithmetic" : "");
 }
@@ -977,6 +988,12 @@ int launch_op(const Plan& pl, hipStream_t st) {
       if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 64, 4>(a, st);
       if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 64, 4>(a, st);
       return launch_dma<OP, 64, 64, 64, 4>(a, st);
+    }
+    if (pl.nst == 3) {
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 3>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 3>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 3>(a, st);
+      return launch_dma<OP, 64, 64, 32, 3>(a, st);
     }
     if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4>(a, st);
     if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4>(a, st);

@@ -12,9 +12,10 @@ import os
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
-# (tile, k tile depth, wavefronts)
-VARIANTS = [(128128, 32, 4), (128064, 32, 4), (64128, 32, 4), (64064, 32, 4), (128128, 64, 8), (256128, 64, 8),
-            (256128, 32, 8), (256256, 32, 8), (128128, 64, 4), (128064, 64, 4), (64128, 64, 4), (64064, 64, 4)]
+# (tile, k tile depth, wavefronts, ring depth)
+VARIANTS = [(128128, 32, 4, 4), (128064, 32, 4, 4), (64128, 32, 4, 4), (64064, 32, 4, 4), (128128, 64, 8, 4), (256128, 64, 8, 3),
+            (256128, 32, 8, 4), (256256, 32, 8, 4), (128128, 64, 4, 4), (128064, 64, 4, 4), (64128, 64, 4, 4), (64064, 64, 4, 4),
+            (128128, 32, 4, 3), (128064, 32, 4, 3), (64128, 32, 4, 3), (64064, 32, 4, 3)]
 SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128]
 OPS = ("fwd", "bwd_data", "bwd_weight")
 BATCH = 64
@@ -63,7 +64,7 @@ def sweep(path):
         return best * 1e3
 
     out = []
-    names = ("JZ_IGEMM_TILE", "JZ_IGEMM_BK", "JZ_IGEMM_WAVES", "JZ_IGEMM_SPLITS", "JZ_IGEMM_NOTABLE")
+    names = ("JZ_IGEMM_TILE", "JZ_IGEMM_BK", "JZ_IGEMM_WAVES", "JZ_IGEMM_SPLITS", "JZ_IGEMM_NOTABLE", "JZ_IGEMM_NST")
     for cs in layers:
         d = api.conv_desc(BATCH, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
         x = torch.randn(BATCH * cs.H * cs.H * cs.C, device=dev).to(h)
@@ -83,8 +84,9 @@ def sweep(path):
             res = {"planner": round(timeit(run), 1)}
             os.environ["JZ_IGEMM_NOTABLE"] = "1"
             res["model"] = round(timeit(run), 1)
-            for (t, bk, wv) in VARIANTS:
+            for (t, bk, wv, nst) in VARIANTS:
                 os.environ["JZ_IGEMM_TILE"], os.environ["JZ_IGEMM_BK"], os.environ["JZ_IGEMM_WAVES"] = str(t), str(bk), str(wv)
+                os.environ["JZ_IGEMM_NST"] = str(nst)
                 prev_need = None
                 for sp in SPLITS:
                     os.environ["JZ_IGEMM_SPLITS"] = str(sp)
@@ -96,10 +98,10 @@ def sweep(path):
                         continue  # too large, or the planner could not honour this split count
                     prev_need = need
                     plan = api.jz_conv2d_describe_plan(op, d)
-                    want = "tile %dx%dx%d, %d wavefronts" % (t // 1000, t % 1000, bk, wv)
+                    want = "tile %dx%dx%d, %d wavefronts, ring %d," % (t // 1000, t % 1000, bk, wv, nst)
                     if want not in plan:
                         continue  # the planner could not honour this combination for this layer
-                    res["%d.%d.%d/%d" % (t, bk, wv, sp)] = round(timeit(run), 1)
+                    res["%d.%d.%d.%d/%d" % (t, bk, wv, nst, sp)] = round(timeit(run), 1)
             cands = [k for k in res if k not in ("planner", "model")]
             best = min(cands, key=res.get)
             out.append(dict(layer=cs.name, H=cs.H, C=cs.C, K=cs.K, R=cs.R, stride=cs.stride, op=opn, best=best,
@@ -114,16 +116,16 @@ def sweep(path):
 
 def write_table(recs, path):
     lines = ["// Generated by `python -m paper_1807_11205_amd.tune --write` from cold-cache timings on one MI355X (ResNet-50 layer",
-             "// shapes at batch 64).  {op, M, N, K, taps, scatter, BM, BN, k tile, wavefronts, splits}; the planner looks a GEMM",
+             "// shapes at batch 64).  {op, M, N, K, taps, scatter, BM, BN, k tile, wavefronts, ring depth, splits}; the planner looks a GEMM",
              "// up here first and falls back to its cost model."]
     for r in recs:
         cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
         best = min(cands, key=cands.get)
         fam, sp = best.split("/")
-        tile, bk, wv = (int(v) for v in fam.split(".")[:3])
+        tile, bk, wv, nst = (int(v) for v in fam.split(".")[:4])
         M, N, K, taps, sc = gemm_dims(r)
-        lines.append("{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s},  // %s %s: %.1f us" % (
-            OPS.index(r["op"]), M, N, K, taps, sc, tile // 1000, tile % 1000, bk, wv, sp, r["layer"], r["op"], cands[best]))
+        lines.append("{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s},  // %s %s: %.1f us" % (
+            OPS.index(r["op"]), M, N, K, taps, sc, tile // 1000, tile % 1000, bk, wv, nst, sp, r["layer"], r["op"], cands[best]))
     with open(path, "w") as f:
         f.write("\n".join(lines) + "\n")
 

@@ -80,7 +80,7 @@ def test_describe_plan_for_every_resnet50_and_alexnet_layer(jzlib):
                 d = jzlib.conv_desc(batch, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
                 for op in (jzlib.JZ_FWD, jzlib.JZ_BWD_DATA, jzlib.JZ_BWD_WEIGHT):
                     text = jzlib.jz_conv2d_describe_plan(op, d)
-                    m = re.search(r"(vector|element-wise) tile (\d+)x(\d+)x(\d+), (\d+) wavefronts, (\d+) x (\d+) tiles, (\d+) splits of (\d+) k tiles", text)
+                    m = re.search(r"(vector|element-wise) tile (\d+)x(\d+)x(\d+), (\d+) wavefronts, ring \d+, (\d+) x (\d+) tiles, (\d+) splits of (\d+) k tiles", text)
                     assert m, text
                     bm, bn, bk, wv, tm, tn, sp, kps = (int(v) for v in m.groups()[1:])
                     if m.group(1) == "vector":

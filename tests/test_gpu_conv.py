@@ -188,6 +188,28 @@ def test_every_kernel_variant_against_the_oracle(jz, monkeypatch, tile, bk, wave
     jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data 1x1 s2")
 
 
+@pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
+def test_three_stage_ring_variants_against_the_oracle(jz, monkeypatch, tile):
+    # the short-ring variants (three stages, three to six workgroups per compute unit), on a short and a long reduction
+    import jzt
+    import oracle
+    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
+    monkeypatch.setenv("JZ_IGEMM_BK", "32")
+    monkeypatch.setenv("JZ_IGEMM_WAVES", "4")
+    monkeypatch.setenv("JZ_IGEMM_NST", "3")
+    for (N, H, W, C, K, R, pad) in ((5, 12, 12, 64, 192, 1, 0), (2, 13, 13, 128, 192, 3, 1), (1, 9, 9, 32, 64, 1, 0)):
+        od = oracle.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
+        d = jz.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
+        assert "ring 3" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+        rng = inputs.rng_for(18, int(tile), C, R)
+        x = inputs.normal_f16(rng, (N, H, W, C))
+        w = inputs.he_normal_f32(rng, (K, R, R, C), R * R * C).astype(np.float16)
+        dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
+        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+
+
 @pytest.mark.parametrize("B,I,O", [(64, 2048, 1000), (128, 1024, 520), (5, 24, 7), (1, 64, 64), (130, 192, 72)])
 def test_fully_connected_modes(jz, B, I, O):
     import jzt
