@@ -626,13 +626,9 @@ __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ p
 // ---------------------------------------------------------------------------------------------
 // host side: plan (tile shape, fast/generic, split-K) and launch
 // ---------------------------------------------------------------------------------------------
-bool use_register_path() {  // debugging aid: JZ_IGEMM_PATH=reg selects the register-staged vector kernels
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("JZ_IGEMM_PATH");
-    v = (e && e[0] == 'r') ? 1 : 0;
-  }
-  return v == 1;
+bool use_register_path() {  // debugging aid: JZ_IGEMM_PATH=reg selects the register-staged vector kernels (read per call)
+  const char* e = getenv("JZ_IGEMM_PATH");
+  return e && e[0] == 'r';
 }
 int env_int(const char* name) {
   const char* e = getenv(name);
@@ -963,26 +959,12 @@ int launch_op(const Plan& pl, hipStream_t st) {
       return launch_dma<OP, 64, 64, 32, 4, false, 2, 2, true>(a, st);
     }
   }
-  if constexpr (OP != OP_BWD_WEIGHT) {
-    if (pl.gen && !use_register_path()) {  // the planner offers the 4-wavefront 32-deep tiles in this mode
-      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4, false, 2, 2, true>(a, st);
-      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4, false, 2, 2, true>(a, st);
-      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 4, false, 2, 2, true>(a, st);
-      return launch_dma<OP, 64, 64, 32, 4, false, 2, 2, true>(a, st);
-    }
-  }
   if (!use_register_path()) {
     // large tiles, one workgroup of 8 wavefronts per compute unit with (nearly) the whole LDS as its ring
-    if (pl.BM == 256 && pl.BN == 256 && pl.bk == 32) {  // 2x4 wavefronts of 128x64
-      if (pl.nst == 5) return launch_dma<OP, 256, 256, 32, 5, false, 2, 4>(a, st);
-      return launch_dma<OP, 256, 256, 32, 4, false, 2, 4>(a, st);
-    }
+    if (pl.BM == 256 && pl.BN == 256 && pl.bk == 32) return launch_dma<OP, 256, 256, 32, 4, false, 2, 4>(a, st);  // 2x4 wavefronts of 128x64
     if (pl.BM == 256 && pl.BN == 128 && pl.bk == 64) return launch_dma<OP, 256, 128, 64, 3, false, 4, 2>(a, st);
     if (pl.BM == 128 && pl.BN == 128 && pl.bk == 64 && pl.waves == 8) return launch_dma<OP, 128, 128, 64, 4, false, 4, 2>(a, st);
-    if (pl.BM == 256 && pl.BN == 128 && pl.bk == 32) {  // 4x2 wavefronts of 64x64
-      if (pl.nst == 4) return launch_dma<OP, 256, 128, 32, 4, false, 4, 2>(a, st);
-      return launch_dma<OP, 256, 128, 32, 6, false, 4, 2>(a, st);
-    }
+    if (pl.BM == 256 && pl.BN == 128 && pl.bk == 32) return launch_dma<OP, 256, 128, 32, 4, false, 4, 2>(a, st);  // 4x2 wavefronts of 64x64
     if (pl.bk == 64) {
       if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 64, 4>(a, st);
       if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 64, 4>(a, st);

@@ -189,6 +189,26 @@ def test_every_kernel_variant_against_the_oracle(jz, monkeypatch, tile, bk, wave
 
 
 @pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
+def test_register_staged_kernels_against_the_oracle(jz, monkeypatch, tile):
+    # the second, independent implementation of the vector path (global -> registers -> LDS, register transposes), kept
+    # for debugging behind JZ_IGEMM_PATH=reg: it has to agree with the oracle like the production kernels
+    import jzt
+    import oracle
+    monkeypatch.setenv("JZ_IGEMM_PATH", "reg")
+    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
+    N, H, W, C, K, R, S, st, pad = 3, 13, 13, 128, 192, 3, 3, 1, 1
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
+    rng = inputs.rng_for(19, int(tile))
+    x = inputs.normal_f16(rng, (N, H, W, C))
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+    jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
+    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+
+
+@pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
 def test_three_stage_ring_variants_against_the_oracle(jz, monkeypatch, tile):
     # the short-ring variants (three stages, three to six workgroups per compute unit), on a short and a long reduction
     import jzt
