@@ -772,6 +772,8 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   a.tiles_n = (a.N + pl->BN - 1) / pl->BN;
   a.kt_per_split = (a.nkt + bS - 1) / bS;
   a.splits = (a.nkt + a.kt_per_split - 1) / a.kt_per_split;  // drop empty splits
+  a.d_tiles_mn = make_fastdiv((unsigned)(a.tiles_m * a.tiles_n));
+  a.d_tiles_n = make_fastdiv((unsigned)a.tiles_n);
 }
 
 void finish_geometry(ConvGeom& g) {

@@ -61,6 +61,7 @@ struct GemmArgs {
   int kt_per_split;  // k tiles each split handles
   int splits;
   int tiles_m, tiles_n;
+  FastDiv d_tiles_mn, d_tiles_n;  // workgroup id -> (split, tile row, tile column) without integer division code
   // strided 1x1 backward-data: output row m = (n,p,q) is written to pixel (n, p*sc_sh, q*sc_sw) of an sc_H x sc_W image
   int sc_on, sc_H, sc_W, sc_sh, sc_sw;
   // backward-weight of a 1x1 unit-stride unpadded layer: reduction row j (a pixel) of x starts at j * IC, no gather

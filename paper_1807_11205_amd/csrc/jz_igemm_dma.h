@@ -148,10 +148,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
 
   unsigned L = xcd_remap(blockIdx.x, gridDim.x);
   const int tiles_mn = a.tiles_m * a.tiles_n;
-  const int split = (int)(L / (unsigned)tiles_mn);
+  const int split = (int)fd_div(L, a.d_tiles_mn);
   L -= (unsigned)split * (unsigned)tiles_mn;
-  const int m0 = (int)(L / (unsigned)a.tiles_n) * BM;
-  const int n0 = (int)(L % (unsigned)a.tiles_n) * BN;
+  const unsigned trow = fd_div(L, a.d_tiles_n);
+  const int m0 = (int)trow * BM;
+  const int n0 = (int)(L - trow * (unsigned)a.tiles_n) * BN;
   const int kt_begin = split * a.kt_per_split;
   const int kt_end = (kt_begin + a.kt_per_split < a.nkt) ? kt_begin + a.kt_per_split : a.nkt;
   const int nk = kt_end - kt_begin;
@@ -224,12 +225,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
             vA[ii] = (unsigned)(((int)n * g.IH + ih0) * g.row_pitch + iw0 * g.pix_step + kc_chunk * 8) * 2u + biasA;
           else
             vA[ii] = (unsigned)(((int)n * g.IH + ih0) * g.row_pitch + iw0 * g.pix_step + kc_chunk * 8) * 2u;
-          unsigned cm = 0;  // columns: bit s set when tap column s is outside
-          for (int s = 0; s < g.S; ++s) cm |= ((unsigned)(iw0 + dir * s) >= (unsigned)g.IW ? 1u : 0u) << s;
-          const unsigned full = g.S >= 32 ? OOB : (1u << g.S) - 1u;
           unsigned inv = 0;
-          for (int r = 0; r < g.R; ++r)
-            inv |= ((unsigned)(ih0 + dir * r) >= (unsigned)g.IH ? full : cm) << (r * g.S);
+          if (g.R * g.S > 1 || g.ph != 0 || g.pw != 0) {  // a single unpadded tap is always inside
+            unsigned cm = 0;  // columns: bit s set when tap column s is outside
+            for (int s = 0; s < g.S; ++s) cm |= ((unsigned)(iw0 + dir * s) >= (unsigned)g.IW ? 1u : 0u) << s;
+            const unsigned full = g.S >= 32 ? OOB : (1u << g.S) - 1u;
+            for (int r = 0; r < g.R; ++r)
+              inv |= ((unsigned)(ih0 + dir * r) >= (unsigned)g.IH ? full : cm) << (r * g.S);
+          }
           invA[ii] = inv;
         }
       }
