@@ -525,33 +525,44 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a) {
 // (w'[k][r][4 s + c], zeros elsewhere); for backward-weight the GEMM produces dw' in that layout and the real
 // entries are copied out.
 
-__global__ __launch_bounds__(256) void pad_to_c4(const unsigned short* __restrict__ x, unsigned short* __restrict__ xp,
-                                                 int N, int H, int W, int C, int Hp, int Wp, int ph, int pw) {
-  long long i = (long long)blockIdx.x * 256 + threadIdx.x;  // one padded pixel per thread
-  long long total = (long long)N * Hp * Wp;
-  if (i >= total) return;
-  int wp = (int)(i % Wp);
-  long long t = i / Wp;
-  int hp = (int)(t % Hp);
-  int n = (int)(t / Hp);
-  int h = hp - ph, w = wp - pw;
-  unsigned short v[4] = {0, 0, 0, 0};
-  if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
-    const unsigned short* src = x + (((size_t)n * H + h) * W + w) * C;
-    for (int c = 0; c < C; ++c) v[c] = src[c];
+// One launch does both copies.  Slices z < N of the grid: a workgroup of 128 threads covers 256 padded pixels of image
+// row (z, y), two per thread (one 16-byte store; Wp is even).  Slice z = N (present when wp != nullptr) repacks the
+// filter: w[K][R][S][C] -> wp[K][R][KT] with wp[k][r][4 s + c] = w[k][r][s][c], zero elsewhere.
+__global__ __launch_bounds__(128) void pad_to_c4(const unsigned short* __restrict__ x, unsigned short* __restrict__ xp,
+                                                 int N, int H, int W, int C, int Hp, int Wp, int ph, int pw,
+                                                 const unsigned short* __restrict__ w, unsigned short* __restrict__ wp,
+                                                 int K, int R, int S, int KT) {
+  const int z = blockIdx.z;
+  if (z == N) {
+    const int total = K * R * KT;
+    const int stride = gridDim.x * gridDim.y * 128;
+    for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * 128 + threadIdx.x; i < total; i += stride) {
+      int j = i % KT, kr = i / KT;
+      int s = j >> 2, c = j & 3;
+      wp[i] = (s < S && c < C) ? w[((size_t)kr * S + s) * C + c] : (unsigned short)0;
+    }
+    return;
   }
-  uint2 pk = make_uint2((unsigned)v[0] | ((unsigned)v[1] << 16), (unsigned)v[2] | ((unsigned)v[3] << 16));
-  *reinterpret_cast<uint2*>(xp + i * 4) = pk;
-}
-
-// w[K][R][S][C] -> wp[K][R][KT] with wp[k][r][4 s + c] = w[k][r][s][c], zero elsewhere
-__global__ __launch_bounds__(256) void pack_filter_c4(const unsigned short* __restrict__ w, unsigned short* __restrict__ wp,
-                                                      int K, int R, int S, int C, int KT) {
-  int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= K * R * KT) return;
-  int j = i % KT, kr = i / KT;
-  int s = j >> 2, c = j & 3;
-  wp[i] = (s < S && c < C) ? w[((size_t)kr * S + s) * C + c] : (unsigned short)0;
+  const int hp = blockIdx.y;
+  const int wp0 = 2 * (blockIdx.x * 128 + threadIdx.x);
+  if (wp0 >= Wp) return;
+  const int h = hp - ph;
+  unsigned short v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if ((unsigned)h < (unsigned)H) {
+    const unsigned short* row = x + ((size_t)z * H + h) * W * C;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const int wi = wp0 + p - pw;
+      if ((unsigned)wi < (unsigned)W) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (c < C) v[4 * p + c] = row[(size_t)wi * C + c];
+      }
+    }
+  }
+  uint4 pk = make_uint4((unsigned)v[0] | ((unsigned)v[1] << 16), (unsigned)v[2] | ((unsigned)v[3] << 16),
+                        (unsigned)v[4] | ((unsigned)v[5] << 16), (unsigned)v[6] | ((unsigned)v[7] << 16));
+  *reinterpret_cast<uint4*>(xp + (((size_t)z * Hp + hp) * Wp + wp0) * 4) = pk;
 }
 
 // dwp[K][R][KT] -> dw[K][R][S][C]
@@ -568,8 +579,10 @@ __global__ __launch_bounds__(256) void unpack_filter_c4(const unsigned short* __
 // "split lanes": lane g adds splits g, g + G, g + 2G, ... in that order, then the G lane sums are added in lane order.
 // The order depends only on (splits, G), so the result is deterministic.  Splitting the reduction over lanes matters
 // for the small outputs that need many splits: with one thread per output group those launches were latency-bound.
+// KT4 > 0 (small-channel backward-weight): the sums are dw'[K][R][4 KT4] of the padded 4-channel problem; group
+// (kr, s) of four goes to dw[kr][s][0..C) when s < S and nowhere otherwise, which saves the separate unpacking launch.
 __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ part, unsigned short* __restrict__ out,
-                                                     long long MN, int splits, int lg) {
+                                                     long long MN, int splits, int lg, int KT4, int S, int C) {
   __shared__ float4 red[256];
   const int G = 1 << lg, Q = 256 >> lg;
   const int q = threadIdx.x & (Q - 1), g = threadIdx.x >> (8 - lg);
@@ -610,6 +623,20 @@ __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ p
   }
   if (i >= MN) return;
   _Float16 h[4] = {(_Float16)s.x, (_Float16)s.y, (_Float16)s.z, (_Float16)s.w};
+  if (KT4 > 0) {  // MN is a multiple of 4 here
+    const long long grp = i >> 2, kr = grp / KT4;
+    const int sx = (int)(grp - kr * KT4);
+    if (sx < S) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (c < C) {
+          unsigned short bts;
+          __builtin_memcpy(&bts, &h[c], 2);
+          out[(kr * S + sx) * C + c] = bts;
+        }
+    }
+    return;
+  }
   if (full) {
     uint2 pk;
     __builtin_memcpy(&pk, h, 8);
@@ -708,23 +735,27 @@ struct Tuned {
 };
 const Tuned kTuned[] = {
 #include "jz_tuned.inc"
+    // the 3-channel stem of ResNet-50 at batch 64 on its padded 4-channel copy ("taps" = the 7 filter rows), measured
+    // the same way: forward 62.8 us, backward-weight 67.0 us including the copy
+    {0, 802816, 64, 224, 7, 0, 128, 64, 32, 4, 3, 1},
+    {2, 64, 224, 802816, 7, 0, 64, 64, 32, 4, 4, 256},
 };
 
 // bk64_ok: the 64-deep k tile is usable for this layer; forced_bk: the k tile depth is fixed (register path, packed mode)
 void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   GemmArgs& a = pl->args;
-  static const int split_opts[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128};
+  static const int split_opts[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
   const int oi = pl->op == JZ_FWD ? 0 : pl->op == JZ_BWD_DATA ? 1 : 2;
   double best = 1e30;
   const Variant* bv = &kVariants[0];
   int bS = 1;
   if (!pl->fast) forced_bk = BK;  // the element-wise kernel: one shape (the first variant's), 64-deep tiles, ~8x slower
   const Tuned* hit = nullptr;
-  if (pl->fast && !pl->packed && !pl->gen && !forced_bk && !ov.bk && !ov.tile && !ov.splits && !ov.waves && !ov.nst && !ov.notable) {
+  if (pl->fast && !pl->gen && (!forced_bk || pl->packed) && !ov.bk && !ov.tile && !ov.splits && !ov.waves && !ov.nst && !ov.notable) {
     const int taps = a.g.R * a.g.S;
     for (const Tuned& t : kTuned)
       if (t.op == oi && t.M == a.M && t.N == a.N && t.K == a.Kred && t.taps == taps && t.scatter == a.sc_on &&
-          (t.bk == 32 || bk64_ok)) {
+          (forced_bk ? t.bk == forced_bk : (t.bk == 32 || bk64_ok))) {
         hit = &t;
         break;
       }
@@ -739,7 +770,6 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
     for (const Variant& v : kVariants) {
       if (!pl->fast && &v != &kVariants[0]) break;
       if ((forced_bk || pl->gen) && (v.waves != 4 || v.bk != 32)) continue;  // those kernels exist as 4-wavefront variants only
-      if (pl->packed && pl->op == JZ_FWD && v.BM != 128) continue;  // the masked kernels exist for BM = 128 only
       if (!forced_bk && v.bk == 64 && !bk64_ok) continue;
       if (!forced_bk && ov.bk && ov.bk != v.bk) continue;
       if (ov.tile && ov.tile != v.BM * 1000 + v.BN) continue;
@@ -747,6 +777,7 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
       if (ov.nst && ov.nst != v.nst) continue;
       if (v.nst == 3 && v.bk == 32 && ov.nst != 3) continue;  // short rings: from the table of measured choices or on request
       const int vbk = forced_bk ? forced_bk : v.bk;
+      if (v.nst == 3 && vbk != 32) continue;  // the short rings exist for 32-deep tiles
       const int nkt = (a.Kred + vbk - 1) / vbk;
       long long tm = (a.M + v.BM - 1) / v.BM, tn = (a.N + v.BN - 1) / v.BN;
       for (int sp : split_opts) {
@@ -865,7 +896,7 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
     if (Wp < (Q - 1) * d->stride_w + KT / 4) Wp = (Q - 1) * d->stride_w + KT / 4;
     Wp = (Wp + 1) & ~1;  // rows stay 16-byte aligned
     const long long nxp = (long long)d->N * Hp * Wp * 4;
-    if (nxp <= lim) {
+    if (nxp <= lim && Hp <= 65535 && d->N < 65535) {  // the copy kernel's grid is (columns, Hp, N + 1)
       pl->packed = true;
       pl->fast = true;
       pl->Hp = Hp; pl->Wp = Wp; pl->KT = KT;
@@ -944,12 +975,21 @@ int launch_op(const Plan& pl, hipStream_t st) {
   const GemmArgs& a = pl.args;
   if (!pl.fast) return launch_one<OP, false, 128, 128>(a, st);
   if (pl.packed && OP == OP_FWD) {  // small-channel forward: tail of every gathered run is masked
-    if (pl.bk == 32) {
-      if (pl.BN == 64 && pl.BM == 128) return launch_dma<OP_FWD, 128, 64, 32, 4, true>(a, st);
-      if (pl.BN == 128 && pl.BM == 128) return launch_dma<OP_FWD, 128, 128, 32, 4, true>(a, st);
+    if (pl.bk == 32 && pl.nst == 3) {
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP_FWD, 128, 128, 32, 3, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP_FWD, 128, 64, 32, 3, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP_FWD, 64, 128, 32, 3, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP_FWD, 64, 64, 32, 3, true>(a, st);
+    } else if (pl.bk == 32) {
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP_FWD, 128, 128, 32, 4, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP_FWD, 128, 64, 32, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP_FWD, 64, 128, 32, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP_FWD, 64, 64, 32, 4, true>(a, st);
     } else {
-      if (pl.BN == 64 && pl.BM == 128) return launch_dma<OP_FWD, 128, 64, 64, 4, true>(a, st);
-      if (pl.BN == 128 && pl.BM == 128) return launch_dma<OP_FWD, 128, 128, 64, 4, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP_FWD, 128, 128, 64, 4, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP_FWD, 128, 64, 64, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP_FWD, 64, 128, 64, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP_FWD, 64, 64, 64, 4, true>(a, st);
     }
     return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
   }
@@ -1015,13 +1055,11 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     unsigned short* xp = static_cast<unsigned short*>(ws);
     unsigned short* wp = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + pl.xp_bytes);
     const unsigned short* x = static_cast<const unsigned short*>(op == JZ_FWD ? A : B);
-    long long npix = (long long)d->N * pl.Hp * pl.Wp;
-    hipLaunchKernelGGL(pad_to_c4, dim3((unsigned)((npix + 255) / 256)), dim3(256), 0, st, x, xp, d->N, d->H, d->W, d->C,
-                       pl.Hp, pl.Wp, d->pad_h, d->pad_w);
+    const unsigned short* wsrc = op == JZ_FWD ? static_cast<const unsigned short*>(B) : nullptr;
+    hipLaunchKernelGGL(pad_to_c4, dim3((unsigned)((pl.Wp / 2 + 127) / 128), (unsigned)pl.Hp, (unsigned)(d->N + (wsrc ? 1 : 0))),
+                       dim3(128), 0, st, x, xp, d->N, d->H, d->W, d->C, pl.Hp, pl.Wp, d->pad_h, d->pad_w, wsrc,
+                       wsrc ? wp : nullptr, d->K, d->R, d->S, pl.KT);
     if (op == JZ_FWD) {
-      int nwp = d->K * d->R * pl.KT;
-      hipLaunchKernelGGL(pack_filter_c4, dim3((unsigned)((nwp + 255) / 256)), dim3(256), 0, st,
-                         static_cast<const unsigned short*>(B), wp, d->K, d->R, d->S, d->C, pl.KT);
       a.A = xp; a.bytesA = (unsigned)pl.xp_bytes;
       a.B = wp; a.bytesB = (unsigned)pl.wp_bytes;
     } else {
@@ -1042,8 +1080,11 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     while (lg < 5 && (2 << lg) <= a.splits && ((MN + 3) / 4 + (256 >> lg) - 1) / (256 >> lg) < 1024) ++lg;
     const long long per_block = 256 >> lg;
     unsigned blocks = (unsigned)(((MN + 3) / 4 + per_block - 1) / per_block);
-    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, a.Dpart, a.D16, MN, a.splits, lg);
+    // small-channel backward-weight: the reduction writes the real filter entries straight into dw
+    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, a.Dpart, dwp ? static_cast<unsigned short*>(D) : a.D16,
+                       MN, a.splits, lg, dwp ? pl.KT / 4 : 0, d->S, d->C);
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
+    dwp = nullptr;
   }
   if (dwp) {
     int ndw = d->K * d->R * d->S * d->C;

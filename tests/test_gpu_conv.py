@@ -230,6 +230,31 @@ def test_three_stage_ring_variants_against_the_oracle(jz, monkeypatch, tile):
         jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
 
 
+@pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
+@pytest.mark.parametrize("nst", ["4", "3"])
+def test_small_channel_kernel_variants_against_the_oracle(jz, monkeypatch, tile, nst):
+    # 3-channel stems run on a padded 4-channel copy: every masked forward variant, and backward-weight both with a split
+    # reduction (the reduction kernel writes the real filter entries) and without (separate unpacking kernel)
+    import jzt
+    import oracle
+    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
+    monkeypatch.setenv("JZ_IGEMM_NST", nst)
+    for (N, H, C, K, R, st, pad, splits) in ((3, 37, 3, 64, 7, 2, 3, "4"), (2, 23, 3, 72, 7, 2, 3, "1"), (4, 39, 3, 96, 11, 4, 0, "2"),
+                                             (4, 20, 4, 64, 5, 2, 2, "3"), (1, 30, 1, 64, 3, 2, 1, "2")):
+        monkeypatch.setenv("JZ_IGEMM_SPLITS", splits)
+        od = oracle.conv_desc(N, H, H, C, K, R, R, st, (pad, pad))
+        d = jz.conv_desc(N, H, H, C, K, R, R, st, (pad, pad))
+        assert "4-channel padded copy" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+        plan_bw = jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
+        assert "4-channel padded copy" in plan_bw and ("%s splits" % splits) in plan_bw, plan_bw
+        rng = inputs.rng_for(20, int(tile), int(nst), H, R)
+        x = inputs.normal_f16(rng, (N, H, H, C))
+        w = inputs.he_normal_f32(rng, (K, R, R, C), R * R * C).astype(np.float16)
+        dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+
+
 @pytest.mark.parametrize("B,I,O", [(64, 2048, 1000), (128, 1024, 520), (5, 24, 7), (1, 64, 64), (130, 192, 72)])
 def test_fully_connected_modes(jz, B, I, O):
     import jzt
