@@ -226,7 +226,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
           else
             vA[ii] = (unsigned)(((int)n * g.IH + ih0) * g.row_pitch + iw0 * g.pix_step + kc_chunk * 8) * 2u;
           unsigned inv = 0;
-          if (g.R * g.S > 1 || g.ph != 0 || g.pw != 0) {  // a single unpadded tap is always inside
+          // forward without padding reads inside the image at every tap ((OH - 1) sh + R <= IH); so does a single
+          // unpadded tap of backward-data
+          if (g.ph != 0 || g.pw != 0 || (OP == OP_BWD_DATA && g.R * g.S > 1)) {
             unsigned cm = 0;  // columns: bit s set when tap column s is outside
             for (int s = 0; s < g.S; ++s) cm |= ((unsigned)(iw0 + dir * s) >= (unsigned)g.IW ? 1u : 0u) << s;
             const unsigned full = g.S >= 32 ? OOB : (1u << g.S) - 1u;
