@@ -153,6 +153,20 @@ int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* fo
  * For tuning and bug reports; the wording is not part of the contract.  Same status codes as the workspace query. */
 int jz_conv2d_describe_plan(int op, const jz_conv_desc* desc, char* text, size_t text_bytes);
 
+/* Planner tuning hook (HOST state, process-wide, guarded by a mutex).  jz_conv2d_tune_set records, for the GEMM that
+ * `op` on `desc` maps to, which kernel variant to run: output tile tile_m x tile_n, k tile depth, wavefronts per
+ * workgroup, ring depth (LDS stages) and the number of splits of the reduction (not split at all where a split would be
+ * shorter than four k tiles).  Later calls for that shape use it in place of the built-in table of measured
+ * choices and of the cost model; the JZ_IGEMM_* environment overrides still win.  The variant must be one the library
+ * has (jz_conv2d_describe_plan shows the names: e.g. 128x128 tile, k tile 64, 8 wavefronts, ring 4), else
+ * JZ_ERR_UNSUPPORTED; shapes that run on the element-wise or per-load-arithmetic kernels cannot be tuned
+ * (JZ_ERR_UNSUPPORTED).  Results never depend on the choice beyond the summation order of the reduction.
+ * jz_conv2d_tune_clear forgets every recorded choice.  Used by `python -m paper_1807_11205_amd.tune --in-place`, which
+ * times candidates inside the whole training step rather than layer by layer. */
+int jz_conv2d_tune_set(int op, const jz_conv_desc* desc, int tile_m, int tile_n, int k_tile, int wavefronts, int ring,
+                       int splits);
+int jz_conv2d_tune_clear(void);
+
 /* Human-readable name of a status code; static storage. */
 const char* jz_status_string(int status);
 

@@ -20,7 +20,7 @@ JZ_FWD, JZ_BWD_DATA, JZ_BWD_WEIGHT = 0, 1, 2
 JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
 
 EXPORTS = [
-    "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
+    "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update",
     "jz_status_string", "jz_version",
@@ -146,6 +146,14 @@ def jz_conv2d_describe_plan(op: int, desc: jz_conv_desc) -> str:
     buf = ctypes.create_string_buffer(256)
     _check(lib().jz_conv2d_describe_plan(op, ctypes.byref(desc), buf, 256), "jz_conv2d_describe_plan")
     return buf.value.decode()
+
+
+def jz_conv2d_tune_set(op: int, desc: jz_conv_desc, tile_m: int, tile_n: int, k_tile: int, wavefronts: int, ring: int, splits: int):
+    _check(lib().jz_conv2d_tune_set(op, ctypes.byref(desc), tile_m, tile_n, k_tile, wavefronts, ring, splits), "jz_conv2d_tune_set")
+
+
+def jz_conv2d_tune_clear():
+    _check(lib().jz_conv2d_tune_clear(), "jz_conv2d_tune_clear")
 
 
 def jz_conv2d_fwd(desc, x16, w16, y16, ws=None, stream=None):

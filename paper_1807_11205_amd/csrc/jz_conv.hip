@@ -19,7 +19,9 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <mutex>
 #include <type_traits>
+#include <vector>
 
 #include "jz_igemm.h"
 #include "jz_internal.h"
@@ -741,6 +743,15 @@ const Tuned kTuned[] = {
     {2, 64, 224, 802816, 7, 0, 64, 64, 32, 4, 4, 256},
 };
 
+// Choices set at run time through jz_conv2d_tune_set: looked up before the table above (an in-place tuning run tries
+// candidates this way without rebuilding the library).
+std::mutex g_tune_mutex;
+std::vector<Tuned> g_tune_rt;
+
+bool same_key(const Tuned& x, const Tuned& y) {
+  return x.op == y.op && x.M == y.M && x.N == y.N && x.K == y.K && x.taps == y.taps && x.scatter == y.scatter;
+}
+
 // bk64_ok: the 64-deep k tile is usable for this layer; forced_bk: the k tile depth is fixed (register path, packed mode)
 void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   GemmArgs& a = pl->args;
@@ -751,14 +762,25 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
   int bS = 1;
   if (!pl->fast) forced_bk = BK;  // the element-wise kernel: one shape (the first variant's), 64-deep tiles, ~8x slower
   const Tuned* hit = nullptr;
+  Tuned rt_hit{};
   if (pl->fast && !pl->gen && (!forced_bk || pl->packed) && !ov.bk && !ov.tile && !ov.splits && !ov.waves && !ov.nst && !ov.notable) {
-    const int taps = a.g.R * a.g.S;
-    for (const Tuned& t : kTuned)
-      if (t.op == oi && t.M == a.M && t.N == a.N && t.K == a.Kred && t.taps == taps && t.scatter == a.sc_on &&
-          (forced_bk ? t.bk == forced_bk : (t.bk == 32 || bk64_ok))) {
-        hit = &t;
-        break;
-      }
+    const Tuned key{oi, a.M, a.N, a.Kred, a.g.R * a.g.S, a.sc_on, 0, 0, 0, 0, 0, 0};
+    auto usable = [&](const Tuned& t) { return same_key(t, key) && (forced_bk ? t.bk == forced_bk : (t.bk == 32 || bk64_ok)); };
+    {
+      std::lock_guard<std::mutex> lock(g_tune_mutex);
+      for (const Tuned& t : g_tune_rt)
+        if (usable(t)) {
+          rt_hit = t;
+          hit = &rt_hit;
+          break;
+        }
+    }
+    if (!hit)
+      for (const Tuned& t : kTuned)
+        if (usable(t)) {
+          hit = &t;
+          break;
+        }
   }
   if (hit) {
     pl->BM = hit->BM; pl->BN = hit->BN; pl->bk = hit->bk; pl->waves = hit->waves;
@@ -1120,6 +1142,38 @@ extern "C" int jz_conv2d_describe_plan(int op, const jz_conv_desc* desc, char* t
   int rc = make_plan(op, desc, &pl);
   if (rc != JZ_OK) return rc;
   plan_text(pl, text, text_bytes);
+  return JZ_OK;
+}
+
+extern "C" int jz_conv2d_tune_set(int op, const jz_conv_desc* desc, int tile_m, int tile_n, int k_tile, int wavefronts,
+                                  int ring, int splits) {
+  Plan pl;
+  int rc = make_plan(op, desc, &pl);
+  if (rc != JZ_OK) return rc;
+  if (!pl.fast || pl.gen || splits < 1) return JZ_ERR_UNSUPPORTED;  // those paths have one kernel shape each
+  const Variant* v = nullptr;
+  for (const Variant& c : kVariants)
+    if (c.BM == tile_m && c.BN == tile_n && c.bk == k_tile && c.waves == wavefronts && c.nst == ring) v = &c;
+  if (!v) return JZ_ERR_UNSUPPORTED;
+  // the small-channel path runs the 4-wavefront kernels of the four basic tiles at its own k tile depth only
+  if (pl.packed && (v->waves != 4 || v->BM > 128 || v->BN > 128 || k_tile != pl.bk || (ring == 3 && k_tile != 32)))
+    return JZ_ERR_UNSUPPORTED;
+  const GemmArgs& a = pl.args;
+  const Tuned t{op == JZ_FWD ? 0 : op == JZ_BWD_DATA ? 1 : 2, a.M, a.N, a.Kred, a.g.R * a.g.S, a.sc_on,
+                tile_m, tile_n, k_tile, wavefronts, ring, splits};
+  std::lock_guard<std::mutex> lock(g_tune_mutex);
+  for (Tuned& e : g_tune_rt)
+    if (same_key(e, t)) {
+      e = t;
+      return JZ_OK;
+    }
+  g_tune_rt.push_back(t);
+  return JZ_OK;
+}
+
+extern "C" int jz_conv2d_tune_clear(void) {
+  std::lock_guard<std::mutex> lock(g_tune_mutex);
+  g_tune_rt.clear();
   return JZ_OK;
 }
 

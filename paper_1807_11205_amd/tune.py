@@ -1,14 +1,22 @@
-"""Tuning sweep for the implicit-GEMM planner: python -m paper_1807_11205_amd.tune [--json FILE] [--write]
+"""Tuning sweep for the implicit-GEMM planner: python -m paper_1807_11205_amd.tune [--json FILE] [--write] [--in-place]
 
 For every distinct convolution shape of ResNet-50 (batch 64) and each of forward / backward-data / backward-weight it
 times every kernel variant (output tile, k tile depth, wavefronts per workgroup) at every admissible split of the
 reduction, through the planner's JZ_IGEMM_* overrides, with the caches flushed before each timed launch (inside a
 training step every layer finds them cold).  `--write` turns the measurements into csrc/jz_tuned.inc, the table the
 planner consults before its cost model; `--json FILE` re-uses saved measurements instead of running on the GPU.
+
+`--in-place` refines those choices inside the whole training step of bench.py (three streams, the network's own
+dependency order): a layer that runs beside others does not always want the variant that is fastest alone (fewer
+splits leave compute units and bandwidth to its neighbours).  For every layer shape, heaviest first, it tries the few
+best variants of the layer-by-layer sweep and smaller split counts through jz_conv2d_tune_set, times the GEMM phase of
+the step and keeps a change only if a second measurement confirms it; it starts from the choices compiled into the
+library, so it can be repeated.
 """
 import argparse
 import json
 import os
+import re
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
@@ -114,20 +122,126 @@ def sweep(path):
     return out
 
 
-def write_table(recs, path):
+def write_table(recs, path, choice=None):
+    """choice: {(layer, op): "tile.bk.waves.ring/splits"} from the in-place pass; default: the fastest alone."""
     lines = ["// Generated by `python -m paper_1807_11205_amd.tune --write` from cold-cache timings on one MI355X (ResNet-50 layer",
-             "// shapes at batch 64).  {op, M, N, K, taps, scatter, BM, BN, k tile, wavefronts, ring depth, splits}; the planner looks a GEMM",
-             "// up here first and falls back to its cost model."]
+             "// shapes at batch 64; with --in-place: refined inside the whole training step).  {op, M, N, K, taps, scatter, BM, BN,",
+             "// k tile, wavefronts, ring depth, splits}; the planner looks a GEMM up here first and falls back to its cost model."]
     for r in recs:
         cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
         best = min(cands, key=cands.get)
+        if choice and (r["layer"], r["op"]) in choice:
+            best = choice[(r["layer"], r["op"])]
         fam, sp = best.split("/")
         tile, bk, wv, nst = (int(v) for v in fam.split(".")[:4])
         M, N, K, taps, sc = gemm_dims(r)
-        lines.append("{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s},  // %s %s: %.1f us" % (
-            OPS.index(r["op"]), M, N, K, taps, sc, tile // 1000, tile % 1000, bk, wv, nst, sp, r["layer"], r["op"], cands[best]))
+        note = "%.1f us alone" % cands[best] if best in cands else "chosen in the step"
+        lines.append("{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s},  // %s %s: %s" % (
+            OPS.index(r["op"]), M, N, K, taps, sc, tile // 1000, tile % 1000, bk, wv, nst, sp, r["layer"], r["op"], note))
     with open(path, "w") as f:
         f.write("\n".join(lines) + "\n")
+
+
+def in_place(recs, steps=60, top=4, gain=0.0015, passes=2):
+    """Coordinate descent over the layer shapes with the GEMM phase of the bench step as the objective."""
+    import torch
+    from . import api, shapes
+    sys.path.insert(0, os.path.dirname(PKG))
+    import bench
+    api.lib()
+    torch.cuda.set_device(0)
+    wl = bench.ResNet50Step(batch=BATCH)
+    big = 1 << 30
+    wl.ws = torch.empty(big, dtype=torch.uint8, device="cuda:0")          # room for any split count
+    wl.side_ws = [torch.empty(big, dtype=torch.uint8, device="cuda:0") for _ in range(3)]
+    for _ in range(12):                                                     # the loss-scale back-off of bench.py
+        wl.step()
+        torch.cuda.synchronize()
+        if int(wl.found_inf.item()) == 0:
+            break
+        wl.halve_loss_scale()
+    stream = torch.cuda.Stream()
+    side = [torch.cuda.Stream() for _ in range(2)]
+    ops = {"fwd": api.JZ_FWD, "bwd_data": api.JZ_BWD_DATA, "bwd_weight": api.JZ_BWD_WEIGHT}
+
+    def measure():
+        with torch.cuda.stream(stream):
+            for _ in range(3):
+                wl.run_gemms(side)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(steps):
+                wl.run_gemms(side)
+            e1.record(stream)
+            stream.synchronize()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def apply(d, op, key):
+        fam, sp = key.split("/")
+        tile, bk, wv, nst = (int(v) for v in fam.split("."))
+        try:
+            api.jz_conv2d_tune_set(op, d, tile // 1000, tile % 1000, bk, wv, nst, int(sp))
+        except api.JzError:
+            return False
+        plan = api.jz_conv2d_describe_plan(op, d)
+        # (the split count the plan reports can be a little lower: splits that would be empty are dropped)
+        return ("tile %dx%dx%d, %d wavefronts, ring %d," % (tile // 1000, tile % 1000, bk, wv, nst)) in plan and \
+            api.jz_conv2d_workspace_bytes(op, d) <= big
+
+    count = {}
+    for c in shapes.resnet50_convs():
+        count[(c.H, c.C, c.K, c.R, c.stride)] = count.get((c.H, c.C, c.K, c.R, c.stride), 0) + 1
+    work = []
+    for r in recs:
+        cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
+        best = min(cands, key=cands.get)
+        work.append((cands[best] * count[(r["H"], r["C"], r["K"], r["R"], r["stride"])], r, cands, best))
+    work.sort(key=lambda w: -w[0])
+
+    def current(d, op):                                                     # what the library would run now, as a key
+        m = re.search(r"tile (\d+)x(\d+)x(\d+), (\d+) wavefronts, ring (\d+), \d+ x \d+ tiles, (\d+) splits", api.jz_conv2d_describe_plan(op, d))
+        bm, bn, bk, wv, nst, sp = (int(v) for v in m.groups())
+        return "%d.%d.%d.%d/%d" % (bm * 1000 + bn, bk, wv, nst, sp)
+
+    choice = {}
+    base = min(measure(), measure())
+    print("in-place: GEMM phase %.4f ms with the library's current choices" % base, flush=True)
+    for p in range(passes):
+        changed = 0
+        for _, r, cands, alone in work:
+            d = api.conv_desc(BATCH, r["H"], r["H"], r["C"], r["K"], r["R"], r["R"], r["stride"], (r["R"] - 1) // 2)
+            op = ops[r["op"]]
+            start = current(d, op)
+            fam, sp = start.split("/")
+            tries = [k for k in sorted(cands, key=cands.get)[:top] if k != start]
+            for f in (1.5, 0.75, 0.5, 0.33):                                # the current variant with other split counts
+                n = max((s for s in SPLITS if s <= max(1.0, int(sp) * f + 0.01)), default=1)
+                k = "%s/%d" % (fam, n)
+                if n != int(sp) and k not in tries:
+                    tries.append(k)
+            cur, cur_t = start, base
+            for k in tries:
+                if not apply(d, op, k) or current(d, op) == start:
+                    continue
+                t = measure()
+                if t < cur_t * (1.0 - gain):
+                    t2 = measure()                                          # confirm before believing it
+                    if t2 < cur_t * (1.0 - gain):
+                        cur, cur_t = k, max(t, t2)
+            apply(d, op, cur)
+            if cur != start:
+                choice[(r["layer"], r["op"])] = cur
+                base = cur_t
+                changed += 1
+            elif (r["layer"], r["op"]) not in choice:
+                choice[(r["layer"], r["op"])] = start
+            print("pass %d %s %s: %s -> %s  GEMM phase %.4f ms" % (p + 1, r["layer"], r["op"], start, cur, base), flush=True)
+        if not changed:
+            break
+    final = min(measure(), measure())
+    print("in-place: GEMM phase %.4f ms after refinement" % final, flush=True)
+    return choice
 
 
 def main():
@@ -135,10 +249,15 @@ def main():
     ap.add_argument("--json", default=None, help="saved measurements to use instead of running the sweep")
     ap.add_argument("--out-json", default="gpurun_out/tune_sweep.json")
     ap.add_argument("--write", action="store_true", help="write csrc/jz_tuned.inc")
+    ap.add_argument("--in-place", action="store_true", help="refine the choices inside the whole step of bench.py")
+    ap.add_argument("--table", default=os.path.join(PKG, "csrc", "jz_tuned.inc"), help="where --write puts the table")
     a = ap.parse_args()
     recs = json.load(open(a.json)) if a.json else sweep(a.out_json)
+    choice = None
+    if a.in_place:
+        choice = in_place(recs)
     if a.write:
-        write_table(recs, os.path.join(PKG, "csrc", "jz_tuned.inc"))
+        write_table(recs, a.table, choice)
     tp = sum(r["all"]["planner"] for r in recs)
     tb = sum(r["best_us"] for r in recs)
     print("sum over distinct layer shapes: planner %.0f us, best variant %.0f us" % (tp, tb), file=sys.stderr)

@@ -104,3 +104,28 @@ def test_tuned_table_is_used_for_the_benchmark_shapes(jzlib):
     finally:
         os.environ.pop("JZ_IGEMM_TILE", None)
     assert "tile 64x64x" in forced      # an override bypasses the table
+
+
+def test_run_time_tuning_hook_changes_the_plan_and_can_be_cleared(jzlib):
+    d = jzlib.conv_desc(64, 14, 14, 256, 256, 3, 3, 1, 1)
+    before = jzlib.jz_conv2d_describe_plan(jzlib.JZ_FWD, d)
+    try:
+        jzlib.jz_conv2d_tune_set(jzlib.JZ_FWD, d, 64, 64, 32, 4, 3, 2)
+        assert "tile 64x64x32, 4 wavefronts, ring 3" in jzlib.jz_conv2d_describe_plan(jzlib.JZ_FWD, d)
+        assert "2 splits" in jzlib.jz_conv2d_describe_plan(jzlib.JZ_FWD, d)
+        jzlib.jz_conv2d_tune_set(jzlib.JZ_FWD, d, 256, 128, 64, 8, 3, 1)      # replaces the entry for this shape
+        assert "tile 256x128x64, 8 wavefronts, ring 3" in jzlib.jz_conv2d_describe_plan(jzlib.JZ_FWD, d)
+        assert jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_DATA, d) != ""       # other ops of the layer are untouched
+        with pytest.raises(jzlib.JzError):
+            jzlib.jz_conv2d_tune_set(jzlib.JZ_FWD, d, 96, 96, 32, 4, 4, 1)    # no such kernel
+        with pytest.raises(jzlib.JzError):
+            jzlib.jz_conv2d_tune_set(jzlib.JZ_FWD, jzlib.conv_desc(2, 9, 7, 3, 5, 3, 2, (2, 1), (1, 0)), 64, 64, 32, 4, 4, 1)  # element-wise path
+        # the 3-channel stem runs the 4-wavefront kernels at its own k tile depth
+        stem = jzlib.conv_desc(64, 224, 224, 3, 64, 7, 7, 2, 3)
+        jzlib.jz_conv2d_tune_set(jzlib.JZ_BWD_WEIGHT, stem, 64, 128, 32, 4, 4, 64)
+        assert "tile 64x128x32" in jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, stem)
+        with pytest.raises(jzlib.JzError):
+            jzlib.jz_conv2d_tune_set(jzlib.JZ_BWD_WEIGHT, stem, 128, 128, 64, 8, 4, 64)
+    finally:
+        jzlib.jz_conv2d_tune_clear()
+    assert jzlib.jz_conv2d_describe_plan(jzlib.JZ_FWD, d) == before
