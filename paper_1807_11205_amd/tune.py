@@ -142,7 +142,7 @@ def write_table(recs, path, choice=None):
         f.write("\n".join(lines) + "\n")
 
 
-def in_place(recs, steps=60, top=4, gain=0.0015, passes=2):
+def in_place(recs, steps=60, top=3, gain=0.0015, passes=2):
     """Coordinate descent over the layer shapes with the GEMM phase of the bench step as the objective."""
     import torch
     from . import api, shapes
@@ -192,11 +192,18 @@ def in_place(recs, steps=60, top=4, gain=0.0015, passes=2):
     count = {}
     for c in shapes.resnet50_convs():
         count[(c.H, c.C, c.K, c.R, c.stride)] = count.get((c.H, c.C, c.K, c.R, c.stride), 0) + 1
+    pad_of = {(c.H, c.C, c.K, c.R, c.stride): c.pad for c in shapes.resnet50_convs()}
     work = []
     for r in recs:
         cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
         best = min(cands, key=cands.get)
         work.append((cands[best] * count[(r["H"], r["C"], r["K"], r["R"], r["stride"])], r, cands, best))
+    # the 3-channel stem is not part of the layer-by-layer sweep (it runs on a padded copy): a few candidates by hand;
+    # its entries live beside the generated table, so the result is only reported
+    stem = dict(layer="stem", H=224, C=3, K=64, R=7, stride=2, by_hand=True)
+    work.append((63.0, dict(stem, op="fwd"), {"128064.32.4.3/1": 62.8, "128064.32.4.4/1": 68.1, "64064.32.4.3/1": 69.6}, "128064.32.4.3/1"))
+    work.append((67.0, dict(stem, op="bwd_weight"), {"64064.32.4.4/256": 67.0, "64128.32.4.4/384": 69.0, "128064.32.4.4/192": 88.7},
+                 "64064.32.4.4/256"))
     work.sort(key=lambda w: -w[0])
 
     def current(d, op):                                                     # what the library would run now, as a key
@@ -210,16 +217,24 @@ def in_place(recs, steps=60, top=4, gain=0.0015, passes=2):
     for p in range(passes):
         changed = 0
         for _, r, cands, alone in work:
-            d = api.conv_desc(BATCH, r["H"], r["H"], r["C"], r["K"], r["R"], r["R"], r["stride"], (r["R"] - 1) // 2)
+            d = api.conv_desc(BATCH, r["H"], r["H"], r["C"], r["K"], r["R"], r["R"], r["stride"],
+                              pad_of[(r["H"], r["C"], r["K"], r["R"], r["stride"])])
             op = ops[r["op"]]
             start = current(d, op)
             fam, sp = start.split("/")
-            tries = [k for k in sorted(cands, key=cands.get)[:top] if k != start]
-            for f in (1.5, 0.75, 0.5, 0.33):                                # the current variant with other split counts
-                n = max((s for s in SPLITS if s <= max(1.0, int(sp) * f + 0.01)), default=1)
-                k = "%s/%d" % (fam, n)
-                if n != int(sp) and k not in tries:
-                    tries.append(k)
+            snap = lambda x: max((s for s in SPLITS if s <= max(1.0, x + 0.01)), default=1)
+            fams = {}                                                       # variant -> (its best time alone, at which split)
+            for k, v in cands.items():
+                f, n = k.split("/")
+                if f not in fams or v < fams[f][0]:
+                    fams[f] = (v, int(n))
+            tries = []
+            for f in sorted(fams, key=lambda f: fams[f][0])[:top]:          # the best variants alone, also with fewer splits
+                for scale in (1.0, 0.5, 0.25):
+                    tries.append("%s/%d" % (f, snap(fams[f][1] * scale)))
+            for scale in (1.5, 0.75, 0.5, 0.33):                            # the current variant with other split counts
+                tries.append("%s/%d" % (fam, snap(int(sp) * scale)))
+            tries = [k for i, k in enumerate(tries) if k != start and k not in tries[:i]]
             cur, cur_t = start, base
             for k in tries:
                 if not apply(d, op, k) or current(d, op) == start:
@@ -231,11 +246,10 @@ def in_place(recs, steps=60, top=4, gain=0.0015, passes=2):
                         cur, cur_t = k, max(t, t2)
             apply(d, op, cur)
             if cur != start:
-                choice[(r["layer"], r["op"])] = cur
                 base = cur_t
                 changed += 1
-            elif (r["layer"], r["op"]) not in choice:
-                choice[(r["layer"], r["op"])] = start
+            if not r.get("by_hand"):
+                choice[(r["layer"], r["op"])] = cur
             print("pass %d %s %s: %s -> %s  GEMM phase %.4f ms" % (p + 1, r["layer"], r["op"], start, cur, base), flush=True)
         if not changed:
             break
