@@ -830,6 +830,9 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
 }
 
 void finish_geometry(ConvGeom& g) {
+  g.tap_rep = 0;
+  if (g.R * g.S <= 32)
+    for (int r = 0; r < g.R; ++r) g.tap_rep |= 1u << (r * g.S);
   g.d_ohow = make_fastdiv((unsigned)(g.OH * g.OW));
   g.d_ow = make_fastdiv((unsigned)g.OW);
   g.d_ic = make_fastdiv((unsigned)g.IC);

@@ -47,6 +47,7 @@ struct ConvGeom {
   // there IC is the length of that run (the k tile), S = 1, pix_step = 4 and runs of neighbouring pixels overlap.
   int row_pitch, pix_step, s_step;
   int kvalid;  // small-channel forward only: elements of a k tile beyond this are not part of the filter row
+  unsigned tap_rep;  // bit r * S set for every filter row r (when R * S <= 32): spreads a column mask over the rows
   FastDiv d_ohow, d_ow, d_ic, d_s, d_sh, d_sw;
 };
 

@@ -117,6 +117,10 @@ __device__ __forceinline__ void jz_dma16s(__amdgpu_buffer_rsrc_t rsrc, lds_byte*
 //     sit between the MFMAs instead of in one block in front of them.
 // GEN = true keeps the plain per-load tap arithmetic for the shapes the masks do not cover (more than 32 taps;
 // strided multi-tap backward-data, whose source pixel is not an affine function of the tap).
+// the k lowest bits, k in [0, 32]
+__device__ __forceinline__ unsigned low_bits(int k) { return k >= 32 ? 0xffffffffu : (1u << k) - 1u; }
+__device__ __forceinline__ int clamp_to(int x, int hi) { return x < 0 ? 0 : (x > hi ? hi : x); }
+
 template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2, bool GEN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   static_assert(TBK == 32 || TBK == 64, "k tile depth");
@@ -193,50 +197,90 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   unsigned vA[LA], invA[LA], vB[LB];
   int ga1[LA], ga2[LA];  // GEN: the row's pixel coordinates, as the per-load arithmetic wants them
   (void)invA; (void)ga1; (void)ga2;
-  if (OP != OP_BWD_WEIGHT) {  // A rows are pixels of the (n, OH, OW) grid
+  if (OP != OP_BWD_WEIGHT && GEN) {  // A rows are pixels of the (n, OH, OW) grid
 #pragma unroll
     for (int ii = 0; ii < LA; ++ii) {
       int m = m0 + NW * KC_RPI * ii + kc_row;
-      vA[ii] = 0; invA[ii] = OOB; ga1[ii] = -(1 << 28); ga2[ii] = -(1 << 28);
+      vA[ii] = 0; ga1[ii] = -(1 << 28); ga2[ii] = -(1 << 28);
       if (m < a.M) {
         unsigned n = fd_div((unsigned)m, g.d_ohow);
         unsigned rem = (unsigned)m - n * (unsigned)(g.OH * g.OW);
         int oh = (int)fd_div(rem, g.d_ow);
         int ow = (int)rem - oh * g.OW;
-        if (GEN) {
-          if (OP == OP_FWD) {
-            ga1[ii] = oh * g.sh - g.ph;
-            ga2[ii] = ow * g.sw - g.pw;
-            vA[ii] = (unsigned)(((int)n * g.IH + ga1[ii]) * g.row_pitch + ga2[ii] * g.pix_step + kc_chunk * 8) * 2u;
-          } else {
-            vA[ii] = n * (unsigned)(g.IH * g.row_pitch);
-            ga1[ii] = oh + g.ph;
-            ga2[ii] = ow + g.pw;
-          }
+        if (OP == OP_FWD) {
+          ga1[ii] = oh * g.sh - g.ph;
+          ga2[ii] = ow * g.sw - g.pw;
+          vA[ii] = (unsigned)(((int)n * g.IH + ga1[ii]) * g.row_pitch + ga2[ii] * g.pix_step + kc_chunk * 8) * 2u;
         } else {
-          // first source row / column and their step per filter tap: forward reads (oh sh - ph + r, ow sw - pw + s),
-          // backward-data with unit stride reads (oh + ph - r, ow + pw - s)
-          const int ih0 = OP == OP_FWD ? oh * g.sh - g.ph : oh + g.ph;
-          const int iw0 = OP == OP_FWD ? ow * g.sw - g.pw : ow + g.pw;
-          const int dir = OP == OP_FWD ? 1 : -1;
-          // offset of the pixel the per-tile scalar offset counts from: tap (0,0) for forward, tap (R-1,S-1) for
-          // backward-data; both plus the descriptor margin, which makes it non-negative
-          if (OP == OP_FWD)
-            vA[ii] = (unsigned)(((int)n * g.IH + ih0) * g.row_pitch + iw0 * g.pix_step + kc_chunk * 8) * 2u + biasA;
-          else
-            vA[ii] = (unsigned)(((int)n * g.IH + ih0) * g.row_pitch + iw0 * g.pix_step + kc_chunk * 8) * 2u;
-          unsigned inv = 0;
-          // forward without padding reads inside the image at every tap ((OH - 1) sh + R <= IH); so does a single
-          // unpadded tap of backward-data
-          if (g.ph != 0 || g.pw != 0 || (OP == OP_BWD_DATA && g.R * g.S > 1)) {
-            unsigned cm = 0;  // columns: bit s set when tap column s is outside
-            for (int s = 0; s < g.S; ++s) cm |= ((unsigned)(iw0 + dir * s) >= (unsigned)g.IW ? 1u : 0u) << s;
-            const unsigned full = g.S >= 32 ? OOB : (1u << g.S) - 1u;
-            for (int r = 0; r < g.R; ++r)
-              inv |= ((unsigned)(ih0 + dir * r) >= (unsigned)g.IH ? full : cm) << (r * g.S);
-          }
-          invA[ii] = inv;
+          vA[ii] = n * (unsigned)(g.IH * g.row_pitch);
+          ga1[ii] = oh + g.ph;
+          ga2[ii] = ow + g.pw;
         }
+      }
+    }
+  } else if (OP != OP_BWD_WEIGHT) {
+    // Row ii of a thread is pixel m0 + kc_row + STR * ii of the (n, OH, OW) grid.  The first one is decomposed by
+    // division; the others follow by adding the stride's own decomposition STR = sa OH OW + sb OW + sc with one carry
+    // per digit (sc < OW, sb < OH), and the byte offset follows by adding what those digit steps are worth: a
+    // handful of additions and selects per row instead of two divisions and five multiplications.
+    // Forward reads source pixel (oh sh - ph + r, ow sw - pw + s) for tap (r, s); backward-data (unit stride)
+    // reads (oh + ph - r, ow + pw - s).
+    constexpr unsigned STR = NW * KC_RPI;
+    const int shh = OP == OP_FWD ? g.sh : 1, sww = OP == OP_FWD ? g.sw : 1;
+    const int offh = OP == OP_FWD ? -g.ph : g.ph, offw = OP == OP_FWD ? -g.pw : g.pw;
+    const int dir = OP == OP_FWD ? 1 : -1;
+    const unsigned sa = fd_div(STR, g.d_ohow);
+    const unsigned srem = STR - sa * (unsigned)(g.OH * g.OW);
+    const int sb = (int)fd_div(srem, g.d_ow);
+    const int sc = (int)srem - sb * g.OW;
+    const unsigned Pn = (unsigned)(g.IH * g.row_pitch) * 2u;   // bytes per image, per source row step, per column step
+    const unsigned Ph = (unsigned)(shh * g.row_pitch) * 2u;
+    const unsigned Pw = (unsigned)(sww * g.pix_step) * 2u;
+    const unsigned dV = sa * Pn + (unsigned)sb * Ph + (unsigned)sc * Pw;
+    const unsigned k1 = Ph - (unsigned)g.OW * Pw;               // a carry out of the column digit
+    const unsigned k2 = Pn - (unsigned)g.OH * Ph;               // a carry out of the row digit
+    // a single unpadded tap is always inside, and so is every tap of a forward pass without padding
+    // ((OH - 1) sh + R <= IH)
+    const bool masks = g.ph != 0 || g.pw != 0 || (OP == OP_BWD_DATA && g.R * g.S > 1);
+    const unsigned full = g.S >= 32 ? OOB : (1u << g.S) - 1u;
+
+    int m = m0 + kc_row;
+    const unsigned n0img = fd_div((unsigned)m, g.d_ohow);
+    const unsigned rem = (unsigned)m - n0img * (unsigned)(g.OH * g.OW);
+    int oh = (int)fd_div(rem, g.d_ow);
+    int ow = (int)rem - oh * g.OW;
+    // offset of the pixel the per-tile scalar offset counts from: tap (0,0) for forward, tap (R-1,S-1) for
+    // backward-data; forward adds the descriptor margin, which makes it non-negative
+    unsigned v = (unsigned)(((int)n0img * g.IH + oh * shh + offh) * g.row_pitch + (ow * sww + offw) * g.pix_step + kc_chunk * 8) * 2u +
+                 (OP == OP_FWD ? biasA : 0u);
+#pragma unroll
+    for (int ii = 0; ii < LA; ++ii) {
+      if (ii > 0) {
+        m += (int)STR;
+        ow += sc;
+        const bool c1 = ow >= g.OW;
+        ow -= c1 ? g.OW : 0;
+        oh += sb + (c1 ? 1 : 0);
+        const bool c2 = oh >= g.OH;
+        oh -= c2 ? g.OH : 0;
+        v += dV + (c1 ? k1 : 0u) + (c2 ? k2 : 0u);
+      }
+      vA[ii] = 0; invA[ii] = OOB;
+      if (m < a.M) {
+        vA[ii] = v;
+        unsigned inv = 0;
+        if (masks) {
+          // Along one axis the taps that fall outside are a run at the start and a run at the end of the filter:
+          // position p0 + dir t is below 0 for the first `lo` taps and at or beyond the size from tap `hi` on
+          // (dir = -1: the other way round).  Columns give a mask cm of S bits that is copied into every row's slot by
+          // one multiplication (tap_rep has bit r S set for every r); rows that are outside fill their whole slots.
+          const int ih0 = __mul24(oh, shh) + offh, iw0 = __mul24(ow, sww) + offw;
+          const int lo_w = dir > 0 ? -iw0 : iw0 - g.IW + 1, hi_w = dir > 0 ? g.IW - iw0 : iw0 + 1;
+          const int lo_h = dir > 0 ? -ih0 : ih0 - g.IH + 1, hi_h = dir > 0 ? g.IH - ih0 : ih0 + 1;
+          const unsigned cm = low_bits(clamp_to(lo_w, g.S)) | (full & ~low_bits(clamp_to(hi_w, g.S)));
+          inv = cm * g.tap_rep | low_bits(clamp_to(lo_h, g.R) * g.S) | (low_bits(g.R * g.S) & ~low_bits(clamp_to(hi_h, g.R) * g.S));
+        }
+        invA[ii] = inv;
       }
     }
   }

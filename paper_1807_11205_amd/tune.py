@@ -142,7 +142,7 @@ def write_table(recs, path, choice=None):
         f.write("\n".join(lines) + "\n")
 
 
-def in_place(recs, steps=60, top=3, gain=0.0015, passes=2):
+def in_place(recs, steps=60, top=3, gain=0.0015, passes=2, n_side=2):
     """Coordinate descent over the layer shapes with the GEMM phase of the bench step as the objective."""
     import torch
     from . import api, shapes
@@ -161,7 +161,7 @@ def in_place(recs, steps=60, top=3, gain=0.0015, passes=2):
             break
         wl.halve_loss_scale()
     stream = torch.cuda.Stream()
-    side = [torch.cuda.Stream() for _ in range(2)]
+    side = [torch.cuda.Stream() for _ in range(n_side)]
     ops = {"fwd": api.JZ_FWD, "bwd_data": api.JZ_BWD_DATA, "bwd_weight": api.JZ_BWD_WEIGHT}
 
     def measure():
@@ -264,12 +264,13 @@ def main():
     ap.add_argument("--out-json", default="gpurun_out/tune_sweep.json")
     ap.add_argument("--write", action="store_true", help="write csrc/jz_tuned.inc")
     ap.add_argument("--in-place", action="store_true", help="refine the choices inside the whole step of bench.py")
+    ap.add_argument("--streams", type=int, default=3, help="--in-place: streams of the step (as bench.py --streams)")
     ap.add_argument("--table", default=os.path.join(PKG, "csrc", "jz_tuned.inc"), help="where --write puts the table")
     a = ap.parse_args()
     recs = json.load(open(a.json)) if a.json else sweep(a.out_json)
     choice = None
     if a.in_place:
-        choice = in_place(recs)
+        choice = in_place(recs, n_side=a.streams - 1)
     if a.write:
         write_table(recs, a.table, choice)
     tp = sum(r["all"]["planner"] for r in recs)
