@@ -135,6 +135,7 @@ class ResNet50Step:
         ev = lambda: torch.cuda.Event()
         pending = None
         block_in = None
+        names = {L["name"] for L in self.layers}
         for L in self.layers:                                   # forward
             if n_side and L["kind"] == "conv" and L["name"].endswith("p"):
                 prog += [("wait", block_in, 1), ("launch", self._bound(L, api.JZ_FWD, self.side_ws[0]), 1)]
@@ -145,8 +146,9 @@ class ResNet50Step:
                 if pending is not None:                         # the residual add of the previous block needs its shortcut
                     prog.append(("wait", pending, 0))
                     pending = None
-                block_in = ev()
-                prog.append(("record", block_in, 0))
+                if L["name"][:-1] + "p" in names:               # only a block with a projection shortcut has a second reader
+                    block_in = ev()                             # (an event record costs the stream 4-6 us)
+                    prog.append(("record", block_in, 0))
             prog.append(("launch", self._bound(L, api.JZ_FWD, self.ws), 0))
         if pending is not None:
             prog.append(("wait", pending, 0))
