@@ -728,6 +728,11 @@ const Variant kVariants[] = {
     {128, 64, 32, 4, 1024, {0.243, 0.220, 0.307}, {8.3, 10.3, 8.0}, 3},
     {64, 128, 32, 4, 1024, {0.246, 0.214, 0.336}, {8.3, 10.3, 8.0}, 3},
     {64, 64, 32, 4, 1536, {0.202, 0.179, 0.272}, {8.3, 10.3, 8.0}, 3},
+    // 8 wavefronts and two or three workgroups per compute unit (32-deep tiles, 72 / 64 / 48 KB of LDS): the neighbour
+    // works while one workgroup waits at its barrier
+    {256, 128, 32, 8, 512, {0.380, 0.363, 0.415}, {8.3, 10.3, 8.0}, 3},
+    {128, 128, 32, 8, 512, {0.306, 0.284, 0.415}, {8.3, 10.3, 8.0}, 4},
+    {128, 128, 32, 8, 768, {0.306, 0.284, 0.415}, {8.3, 10.3, 8.0}, 3},
 };
 
 // Measured choices for known GEMM shapes (written by `python -m paper_1807_11205_amd.tune --write`): the per-k-tile model
@@ -798,6 +803,7 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk, const Overrides& ov) {
       if (ov.waves && ov.waves != v.waves) continue;
       if (ov.nst && ov.nst != v.nst) continue;
       if (v.nst == 3 && v.bk == 32 && ov.nst != 3) continue;  // short rings: from the table of measured choices or on request
+      if (v.waves == 8 && v.BM == 128 && v.bk == 32 && ov.waves != 8) continue;  // likewise (the model has no fit for it)
       const int vbk = forced_bk ? forced_bk : v.bk;
       if (v.nst == 3 && vbk != 32) continue;  // the short rings exist for 32-deep tiles
       const int nkt = (a.Kred + vbk - 1) / vbk;
@@ -1031,7 +1037,10 @@ int launch_op(const Plan& pl, hipStream_t st) {
     if (pl.BM == 256 && pl.BN == 256 && pl.bk == 32) return launch_dma<OP, 256, 256, 32, 4, false, 2, 4>(a, st);  // 2x4 wavefronts of 128x64
     if (pl.BM == 256 && pl.BN == 128 && pl.bk == 64) return launch_dma<OP, 256, 128, 64, 3, false, 4, 2>(a, st);
     if (pl.BM == 128 && pl.BN == 128 && pl.bk == 64 && pl.waves == 8) return launch_dma<OP, 128, 128, 64, 4, false, 4, 2>(a, st);
+    if (pl.BM == 256 && pl.BN == 128 && pl.bk == 32 && pl.nst == 3) return launch_dma<OP, 256, 128, 32, 3, false, 4, 2>(a, st);
     if (pl.BM == 256 && pl.BN == 128 && pl.bk == 32) return launch_dma<OP, 256, 128, 32, 4, false, 4, 2>(a, st);  // 4x2 wavefronts of 64x64
+    if (pl.BM == 128 && pl.BN == 128 && pl.bk == 32 && pl.waves == 8 && pl.nst == 3) return launch_dma<OP, 128, 128, 32, 3, false, 4, 2>(a, st);
+    if (pl.BM == 128 && pl.BN == 128 && pl.bk == 32 && pl.waves == 8) return launch_dma<OP, 128, 128, 32, 4, false, 4, 2>(a, st);
     if (pl.bk == 64) {
       if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 64, 4>(a, st);
       if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 64, 4>(a, st);

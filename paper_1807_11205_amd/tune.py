@@ -23,7 +23,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 # (tile, k tile depth, wavefronts, ring depth)
 VARIANTS = [(128128, 32, 4, 4), (128064, 32, 4, 4), (64128, 32, 4, 4), (64064, 32, 4, 4), (128128, 64, 8, 4), (256128, 64, 8, 3),
             (256128, 32, 8, 4), (256256, 32, 8, 4), (128128, 64, 4, 4), (128064, 64, 4, 4), (64128, 64, 4, 4), (64064, 64, 4, 4),
-            (128128, 32, 4, 3), (128064, 32, 4, 3), (64128, 32, 4, 3), (64064, 32, 4, 3)]
+            (128128, 32, 4, 3), (128064, 32, 4, 3), (64128, 32, 4, 3), (64064, 32, 4, 3),
+            (256128, 32, 8, 3), (128128, 32, 8, 4), (128128, 32, 8, 3)]
 SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128]
 OPS = ("fwd", "bwd_data", "bwd_weight")
 BATCH = 64
@@ -43,7 +44,7 @@ def gemm_dims(rec):
     return K, R * R * C, BATCH * P * P, R * R, 0
 
 
-def sweep(path):
+def sweep(path, variants=VARIANTS):
     import torch
     from . import api, shapes
     h, dev = torch.float16, "cuda:0"
@@ -92,7 +93,7 @@ def sweep(path):
             res = {"planner": round(timeit(run), 1)}
             os.environ["JZ_IGEMM_NOTABLE"] = "1"
             res["model"] = round(timeit(run), 1)
-            for (t, bk, wv, nst) in VARIANTS:
+            for (t, bk, wv, nst) in variants:
                 os.environ["JZ_IGEMM_TILE"], os.environ["JZ_IGEMM_BK"], os.environ["JZ_IGEMM_WAVES"] = str(t), str(bk), str(wv)
                 os.environ["JZ_IGEMM_NST"] = str(nst)
                 prev_need = None
@@ -266,8 +267,26 @@ def main():
     ap.add_argument("--in-place", action="store_true", help="refine the choices inside the whole step of bench.py")
     ap.add_argument("--streams", type=int, default=3, help="--in-place: streams of the step (as bench.py --streams)")
     ap.add_argument("--table", default=os.path.join(PKG, "csrc", "jz_tuned.inc"), help="where --write puts the table")
+    ap.add_argument("--only", default=None, help="sweep only these variants, e.g. 256128.32.8.3,128128.32.8.4; with --json: "
+                                                 "add the new timings to those saved measurements")
     a = ap.parse_args()
-    recs = json.load(open(a.json)) if a.json else sweep(a.out_json)
+    if a.only:
+        sel = [tuple(int(x) for x in v.split(".")) for v in a.only.split(",")]
+        assert all(v in VARIANTS for v in sel), "unknown variant"
+        fresh = sweep(a.out_json, sel)
+        recs = json.load(open(a.json)) if a.json else fresh
+        if a.json:
+            by = {(r["layer"], r["op"]): r for r in fresh}
+            for r in recs:
+                extra = by[(r["layer"], r["op"])]["all"]
+                r["all"].update({k: v for k, v in extra.items() if k not in ("planner", "model")})
+                cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
+                r["best"] = min(cands, key=cands.get)
+                r["best_us"] = cands[r["best"]]
+            with open(a.out_json, "w") as f:
+                json.dump(recs, f)
+    else:
+        recs = json.load(open(a.json)) if a.json else sweep(a.out_json)
     choice = None
     if a.in_place:
         choice = in_place(recs, n_side=a.streams - 1)

@@ -230,6 +230,30 @@ def test_three_stage_ring_variants_against_the_oracle(jz, monkeypatch, tile):
         jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
 
 
+@pytest.mark.parametrize("tile,nst", [("256128", "3"), ("128128", "4"), ("128128", "3")])
+def test_eight_wavefront_32_deep_variants_against_the_oracle(jz, monkeypatch, tile, nst):
+    # 8 wavefronts on 32-deep tiles with rings short enough for two or three workgroups per compute unit
+    import jzt
+    import oracle
+    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
+    monkeypatch.setenv("JZ_IGEMM_BK", "32")
+    monkeypatch.setenv("JZ_IGEMM_WAVES", "8")
+    monkeypatch.setenv("JZ_IGEMM_NST", nst)
+    for (N, H, W, C, K, R, pad) in ((3, 15, 15, 128, 320, 3, 1), (5, 12, 12, 64, 192, 1, 0), (2, 9, 9, 32, 64, 1, 0)):
+        od = oracle.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
+        d = jz.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
+        want = "tile %sx%sx32, 8 wavefronts, ring %s" % (tile[:3], tile[3:], nst)
+        for op in (jz.JZ_FWD, jz.JZ_BWD_DATA, jz.JZ_BWD_WEIGHT):
+            assert want in jz.jz_conv2d_describe_plan(op, d)
+        rng = inputs.rng_for(21, int(tile), int(nst), C, R)
+        x = inputs.normal_f16(rng, (N, H, W, C))
+        w = inputs.he_normal_f32(rng, (K, R, R, C), R * R * C).astype(np.float16)
+        dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
+        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+
+
 @pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
 @pytest.mark.parametrize("nst", ["4", "3"])
 def test_small_channel_kernel_variants_against_the_oracle(jz, monkeypatch, tile, nst):
