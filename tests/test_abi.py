@@ -71,7 +71,8 @@ def test_describe_plan_for_every_resnet50_and_alexnet_layer(jzlib):
     import re
     from paper_1807_11205_amd import shapes
     known = {(128, 128, 32, 4), (128, 64, 32, 4), (64, 128, 32, 4), (64, 64, 32, 4), (128, 128, 64, 8), (256, 128, 64, 8),
-             (256, 128, 32, 8), (256, 256, 32, 8), (128, 128, 64, 4), (128, 64, 64, 4), (64, 128, 64, 4), (64, 64, 64, 4)}
+             (256, 128, 32, 8), (256, 256, 32, 8), (128, 128, 64, 4), (128, 64, 64, 4), (64, 128, 64, 4), (64, 64, 64, 4),
+             (128, 128, 32, 8)}
     layers = [(64, c) for c in shapes.resnet50_convs()] + [(128, c) for c in shapes.alexnet_convs()]
     for notable in ("0", "1"):
         os.environ["JZ_IGEMM_NOTABLE"] = notable
