@@ -187,7 +187,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   auto mc_k = [&](int rows, int ii) { int cpr = rows / 8; return (NW * ii + wave) * (64 / cpr) + lane / cpr; };
   auto mc_chunk = [&](int rows, int k) {
     int cpr = rows / 8;
-    int swz = cpr >= 16 ? 2 * (k & 7) : 2 * (k & 3);
+    int swz = cpr >= 16 ? 4 * (k & 3) : 2 * (k & 3);
     return (lane % cpr) ^ swz;
   };
 
@@ -445,7 +445,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
         for (int hf = 0; hf < 2; ++hf) {
           int k = 8 * (gi >> 1) + 4 * hf + j;
           int c = (wm * WTM + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
-          int swz = CPR >= 16 ? 2 * (k & 7) : 2 * (k & 3);
+          int swz = CPR >= 16 ? 4 * (k & 3) : 2 * (k & 3);
           adA[t * 2 + hf] = (unsigned)(k * (BM * 2) + ((c ^ swz) * 16) + (c4 & 1) * 8);
         }
     }
@@ -461,7 +461,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
         for (int hf = 0; hf < 2; ++hf) {
           int k = 8 * (gi >> 1) + 4 * hf + j;
           int c = (wn * WTN + 32 * t + 16 * (gi & 1) + 4 * c4) / 8;
-          int swz = CPR >= 16 ? 2 * (k & 7) : 2 * (k & 3);
+          int swz = CPR >= 16 ? 4 * (k & 3) : 2 * (k & 3);
           adB[t * 2 + hf] = (unsigned)(A_BYTES + k * (BN * 2) + ((c ^ swz) * 16) + (c4 & 1) * 8);
         }
     }
