@@ -286,6 +286,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   }
   int sb1 = 0, sb2 = 0, sbc = 0;
   (void)sb1; (void)sb2; (void)sbc;
+  // backward-weight, gathered x: per load the pixel's row and column and the byte offset of its tap, advanced per tile
+  int xp[LB], xq[LB], bw_tp = 0, bw_tq = 0;
+  unsigned xoff[LB], bw_dv = 0, bw_k1 = 0, bw_k2 = 0;
+  (void)xp; (void)xq; (void)xoff; (void)bw_tp; (void)bw_tq; (void)bw_dv; (void)bw_k1; (void)bw_k2;
   if (OP == OP_FWD) {
 #pragma unroll
     for (int ii = 0; ii < LB; ++ii) {
@@ -317,6 +321,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
     // arithmetic at all (per-lane offset fixed, per-tile offset scalar)
 #pragma unroll
     for (int ii = 0; ii < LB; ++ii) vB[ii] = (a.bw_linear && nn < a.N) ? (unsigned)(mc_k(BN, ii) * g.IC + nn) * 2u : OOB;
+    // Any other layer: load ii of k tile kt reads, for output pixel j = kt TBK + k-row, the input pixel at this lane's
+    // tap.  The pixel of the first tile is decomposed by division here; from tile to tile j grows by TBK, so its
+    // (image, row, column) digits and the byte offset advance by TBK's own digits with one carry each (as the rows
+    // of the gathered operand do in the other two passes): no division and no slow multiplication inside the k loop.
+    if (!a.bw_linear) {
+      const unsigned ta = fd_div((unsigned)TBK, g.d_ohow);
+      const unsigned trem = (unsigned)TBK - ta * (unsigned)(g.OH * g.OW);
+      bw_tp = (int)fd_div(trem, g.d_ow);
+      bw_tq = (int)trem - bw_tp * g.OW;
+      const unsigned Pn = (unsigned)(g.IH * g.row_pitch) * 2u, Ph = (unsigned)(g.sh * g.row_pitch) * 2u,
+                     Pw = (unsigned)(g.sw * g.pix_step) * 2u;
+      bw_dv = ta * Pn + (unsigned)bw_tp * Ph + (unsigned)bw_tq * Pw;
+      bw_k1 = Ph - (unsigned)g.OW * Pw;
+      bw_k2 = Pn - (unsigned)g.OH * Ph;
+#pragma unroll
+      for (int ii = 0; ii < LB; ++ii) {
+        const unsigned j = (unsigned)(kt_begin * TBK + mc_k(BN, ii));
+        const unsigned n = fd_div(j, g.d_ohow);
+        const unsigned rem = j - n * (unsigned)(g.OH * g.OW);
+        const unsigned pp = fd_div(rem, g.d_ow);
+        xp[ii] = (int)pp;
+        xq[ii] = (int)(rem - pp * (unsigned)g.OW);
+        xoff[ii] = ((n * (unsigned)g.IH + pp * (unsigned)g.sh + (unsigned)sb1) * (unsigned)g.row_pitch +
+                    ((unsigned)(xq[ii] * g.sw) + (unsigned)sb2) * (unsigned)g.pix_step + (unsigned)sbc) * 2u;
+      }
+    }
     // dy[(n,p,q)][k_out], chunk = 8 consecutive k_out: row j = k0 + k of the tile at (mm + j M) * 2
     int mm = m0 + mc_chunk(BM, mc_k(BM, 0)) * 8;
 #pragma unroll
@@ -395,16 +425,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
         } else if (a.bw_linear) {  // x rows j = k0 + k of a plain matrix
           const bool ok = c.k0 + mc_k(BN, ii) < a.Kred;
           jz_dma16s(rsrcB, dst, ok ? vB[ii] : OOB, c.soffB);
-        } else {  // x at this lane's tap for output pixel j
-          int j = c.k0 + mc_k(BN, ii);
-          unsigned n = fd_div((unsigned)j, g.d_ohow);
-          unsigned rem = (unsigned)j - n * (unsigned)(g.OH * g.OW);
-          int p = (int)fd_div(rem, g.d_ow);
-          int q = (int)rem - p * g.OW;
-          int ih = p * g.sh + sb1, iw = q * g.sw + sb2;
-          bool ok = j < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
-          unsigned off = (unsigned)(((int)n * g.IH + ih) * g.row_pitch + iw * g.pix_step + sbc) * 2u;
-          jz_dma16(rsrcB, dst, ok ? off : OOB);
+        } else {  // x at this lane's tap for output pixel j = k0 + k-row
+          const int ih = __mul24(xp[ii], g.sh) + sb1, iw = __mul24(xq[ii], g.sw) + sb2;
+          const bool ok = c.k0 + mc_k(BN, ii) < a.Kred && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW;
+          jz_dma16(rsrcB, dst, ok ? xoff[ii] : OOB);
+          // on to the pixel of the next tile
+          xq[ii] += bw_tq;
+          const bool c1 = xq[ii] >= g.OW;
+          xq[ii] -= c1 ? g.OW : 0;
+          xp[ii] += bw_tp + (c1 ? 1 : 0);
+          const bool c2 = xp[ii] >= g.OH;
+          xp[ii] -= c2 ? g.OH : 0;
+          xoff[ii] += bw_dv + (c1 ? bw_k1 : 0u) + (c2 ? bw_k2 : 0u);
         }
       }
     }
