@@ -143,7 +143,7 @@ def write_table(recs, path, choice=None):
         f.write("\n".join(lines) + "\n")
 
 
-def in_place(recs, steps=60, top=3, gain=0.0015, passes=2, n_side=2):
+def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2):
     """Coordinate descent over the layer shapes with the GEMM phase of the bench step as the objective."""
     import torch
     from . import api, shapes
