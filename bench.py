@@ -254,6 +254,96 @@ def per_layer_report(wl, iters=20):
     return rows
 
 
+def alexnet_workload(args):
+    """configs[3]: the AlexNet-shaped layers (five convolutions, ungrouped, and the three FC GEMMs) at N = 128, forward,
+    backward-data and backward-weight of every layer on independent seeded N(0,1) inputs, He-normal weights.  Same launch
+    scheme as the ResNet-50 step: forward and the backward-data chain in network order on one stream, backward-weight
+    round-robin on the side streams.  One JSON line; no LARS phase (the configuration names none)."""
+    B, h, dev = args.batch, torch.float16, "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    randn = lambda n, std=1.0: (torch.randn(n, generator=gen, device=dev) * std).to(h)
+    layers, flops, ws_bytes = [], 0, 0
+    for cs in shapes.alexnet_convs():
+        d = api.conv_desc(B, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+        nx, ny, nw = B * cs.H * cs.H * cs.C, B * cs.P * cs.P * cs.K, cs.K * cs.R * cs.R * cs.C
+        layers.append(dict(kind="conv", name=cs.name, d=d, first=cs.first, x=randn(nx), dy=randn(ny),
+                           w=randn(nw, float(np.sqrt(2.0 / (cs.R * cs.R * cs.C)))), y=torch.empty(ny, dtype=h, device=dev),
+                           dx=None if cs.first else torch.empty(nx, dtype=h, device=dev), dw=torch.empty(nw, dtype=h, device=dev)))
+        ws_bytes = max([ws_bytes] + [api.jz_conv2d_workspace_bytes(op, d) for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)])
+        flops += 2 * cs.macs(B) * (2 if cs.first else 3)
+    for fc in shapes.ALEXNET_FCS:
+        layers.append(dict(kind="fc", name=fc.name, I=fc.I, O=fc.O, first=False, x=randn(B * fc.I), dy=randn(B * fc.O),
+                           w=randn(fc.I * fc.O, float(np.sqrt(2.0 / fc.I))), y=torch.empty(B * fc.O, dtype=h, device=dev),
+                           dx=torch.empty(B * fc.I, dtype=h, device=dev), dw=torch.empty(fc.I * fc.O, dtype=h, device=dev)))
+        ws_bytes = max([ws_bytes] + [api.jz_gemm_fc_workspace_bytes(op, B, fc.I, fc.O) for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)])
+        flops += 2 * fc.macs(B) * 3
+    n_side = max(0, min(args.streams, 4) - 1)
+    wss = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev) for _ in range(n_side + 1)]
+
+    def bound(L, op, ws):
+        if L["kind"] == "conv":
+            a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("x", "dy", "dw")}[op]
+            return api.bind_conv2d(op, L["d"], L[a], L[b], L[o], ws)
+        a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("dy", "x", "dw")}[op]
+        return api.bind_gemm_fc(op, B, L["I"], L["O"], L[a], L[b], L[o], ws)
+
+    prog = [("launch", bound(L, api.JZ_FWD, wss[0]), 0) for L in layers]
+    ready = torch.cuda.Event()
+    prog.append(("record", ready, 0))
+    for k, L in enumerate(reversed(layers)):
+        si = 1 + k % n_side if n_side else 0
+        if n_side:
+            prog.append(("wait", ready, si))
+        prog.append(("launch", bound(L, api.JZ_BWD_WEIGHT, wss[si]), si))
+        if not L["first"]:
+            prog.append(("launch", bound(L, api.JZ_BWD_DATA, wss[0]), 0))
+            if n_side:
+                ready = torch.cuda.Event()
+                prog.append(("record", ready, 0))
+    for si in range(1, n_side + 1):
+        done = torch.cuda.Event()
+        prog += [("record", done, si), ("wait", done, 0)]
+    stream = torch.cuda.Stream()
+    streams = [stream] + [torch.cuda.Stream() for _ in range(n_side)]
+
+    def run():
+        for kind, obj, si in prog:
+            if kind == "launch":
+                obj(streams[si])
+            elif kind == "record":
+                obj.record(streams[si])
+            else:
+                streams[si].wait_event(obj)
+
+    with torch.cuda.stream(stream):
+        for _ in range(max(args.warmup, 1)):
+            run()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(args.steps):
+            run()
+        e1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    ms = wall * 1e3 / args.steps
+    tflops = flops / (e0.elapsed_time(e1) / args.steps * 1e-3) / 1e12
+    n_launch = sum(1 for e in prog if e[0] == "launch")
+    print(json.dumps({
+        "metric": "AlexNet-shaped layers N=%d fp16 fwd+bwd images/s" % B, "value": B / (ms * 1e-3), "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "configs[3]: AlexNet-shaped layers (5 convs ungrouped + 3 FC), fwd + bwd_data + bwd_weight per layer on "
+                               "independent seeded N(0,1) inputs", "batch": B, "launch": "eager", "streams": args.streams},
+        "roofline": {"kernel": "igemm_kernel (all %d conv/FC launches of a step)" % n_launch, "bound": "mfma", "achieved": tflops,
+                     "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "flop_per_step": flops}}))
+
+
 def cpu_baseline(sample_batch=8):
     """The fp64 oracle, as it stands, on the host cores: the same 53-conv + FC stack at a small batch, plus LARS."""
     import oracle
@@ -291,7 +381,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--batch", type=int, default=None, help="default: 64 (resnet50), 128 (alexnet)")
+    ap.add_argument("--workload", default="resnet50", choices=("resnet50", "alexnet"),
+                    help="resnet50: the full step the headline metric is quoted on; alexnet: the AlexNet-shaped layers of configs[3]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
     ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
@@ -314,6 +406,11 @@ def main():
         sys.exit(2)
     api.lib()
     torch.cuda.set_device(0)
+    if args.batch is None:
+        args.batch = 64 if args.workload == "resnet50" else 128
+    if args.workload == "alexnet":
+        alexnet_workload(args)
+        return
     wl = ResNet50Step(batch=args.batch)
 
     # loss-scale back-off: halve S until the weight gradients stay inside fp16 and the update is not skipped

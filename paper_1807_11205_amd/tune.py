@@ -33,21 +33,24 @@ BATCH = 64
 def gemm_dims(rec):
     """(M, N, K, taps, scatter) of the GEMM the library runs for this record (see jz_igemm.h)."""
     H, C, K, R, st = rec["H"], rec["C"], rec["K"], rec["R"], rec["stride"]
-    pad = (R - 1) // 2
+    pad, B = rec.get("pad", (R - 1) // 2), rec.get("batch", BATCH)
     P = (H + 2 * pad - R) // st + 1
     if rec["op"] == "fwd":
-        return BATCH * P * P, K, R * R * C, R * R, 0
+        return B * P * P, K, R * R * C, R * R, 0
     if rec["op"] == "bwd_data":
         if R == 1 and st > 1:
-            return BATCH * P * P, C, K, 1, 1
-        return BATCH * H * H, C, R * R * K, R * R, 0
-    return K, R * R * C, BATCH * P * P, R * R, 0
+            return B * P * P, C, K, 1, 1
+        return B * H * H, C, R * R * K, R * R, 0
+    return K, R * R * C, B * P * P, R * R, 0
 
 
-def sweep(path, variants=VARIANTS):
-    import torch
-    from . import api, shapes
-    h, dev = torch.float16, "cuda:0"
+def model_layers(model):
+    """(batch, layers) swept for a model: every distinct convolution shape except the 3-channel stem (it runs on a padded
+    copy and has its own entries), fully connected layers as 1x1 convolutions over a 1x1 image."""
+    from . import shapes
+    if model == "alexnet":
+        convs = [c for c in shapes.alexnet_convs() if not c.first]
+        return 128, convs + [shapes.ConvShape(f.name, 1, f.I, f.O, 1, 1, 0) for f in shapes.ALEXNET_FCS]
     seen, layers = set(), []
     for c in shapes.resnet50_convs():
         key = (c.H, c.C, c.K, c.R, c.stride)
@@ -55,6 +58,14 @@ def sweep(path, variants=VARIANTS):
             continue
         seen.add(key)
         layers.append(c)
+    return BATCH, layers
+
+
+def sweep(path, variants=VARIANTS, model="resnet50"):
+    import torch
+    from . import api
+    h, dev = torch.float16, "cuda:0"
+    BATCH, layers = model_layers(model)
     junk = torch.zeros(192 << 20, dtype=torch.float32, device=dev)
     ws = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
 
@@ -113,7 +124,7 @@ def sweep(path, variants=VARIANTS):
                     res["%d.%d.%d.%d/%d" % (t, bk, wv, nst, sp)] = round(timeit(run), 1)
             cands = [k for k in res if k not in ("planner", "model")]
             best = min(cands, key=res.get)
-            out.append(dict(layer=cs.name, H=cs.H, C=cs.C, K=cs.K, R=cs.R, stride=cs.stride, op=opn, best=best,
+            out.append(dict(layer=cs.name, H=cs.H, C=cs.C, K=cs.K, R=cs.R, stride=cs.stride, pad=cs.pad, batch=BATCH, op=opn, best=best,
                             best_us=res[best], all=res))
             print(cs.name, opn, "planner", res["planner"], "model", res["model"], "best", best, res[best], flush=True)
             with open(path, "w") as f:
@@ -126,8 +137,9 @@ def sweep(path, variants=VARIANTS):
 def write_table(recs, path, choice=None):
     """choice: {(layer, op): "tile.bk.waves.ring/splits"} from the in-place pass; default: the fastest alone."""
     lines = ["// Generated by `python -m paper_1807_11205_amd.tune --write` from cold-cache timings on one MI355X (ResNet-50 layer",
-             "// shapes at batch 64; with --in-place: refined inside the whole training step).  {op, M, N, K, taps, scatter, BM, BN,",
-             "// k tile, wavefronts, ring depth, splits}; the planner looks a GEMM up here first and falls back to its cost model."]
+             "// shapes at batch 64, or with --model alexnet the AlexNet-shaped layers at batch 128; with --in-place: refined inside",
+             "// the whole training step).  {op, M, N, K, taps, scatter, BM, BN, k tile, wavefronts, ring depth, splits}; the planner",
+             "// looks a GEMM up here first and falls back to its cost model."]
     for r in recs:
         cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
         best = min(cands, key=cands.get)
@@ -267,13 +279,14 @@ def main():
     ap.add_argument("--in-place", action="store_true", help="refine the choices inside the whole step of bench.py")
     ap.add_argument("--streams", type=int, default=3, help="--in-place: streams of the step (as bench.py --streams)")
     ap.add_argument("--table", default=os.path.join(PKG, "csrc", "jz_tuned.inc"), help="where --write puts the table")
+    ap.add_argument("--model", default="resnet50", choices=("resnet50", "alexnet"), help="whose layer shapes to sweep")
     ap.add_argument("--only", default=None, help="sweep only these variants, e.g. 256128.32.8.3,128128.32.8.4; with --json: "
                                                  "add the new timings to those saved measurements")
     a = ap.parse_args()
     if a.only:
         sel = [tuple(int(x) for x in v.split(".")) for v in a.only.split(",")]
         assert all(v in VARIANTS for v in sel), "unknown variant"
-        fresh = sweep(a.out_json, sel)
+        fresh = sweep(a.out_json, sel, a.model)
         recs = json.load(open(a.json)) if a.json else fresh
         if a.json:
             by = {(r["layer"], r["op"]): r for r in fresh}
@@ -286,7 +299,7 @@ def main():
             with open(a.out_json, "w") as f:
                 json.dump(recs, f)
     else:
-        recs = json.load(open(a.json)) if a.json else sweep(a.out_json)
+        recs = json.load(open(a.json)) if a.json else sweep(a.out_json, VARIANTS, a.model)
     choice = None
     if a.in_place:
         choice = in_place(recs, n_side=a.streams - 1)
