@@ -130,3 +130,32 @@ def test_run_time_tuning_hook_changes_the_plan_and_can_be_cleared(jzlib):
     finally:
         jzlib.jz_conv2d_tune_clear()
     assert jzlib.jz_conv2d_describe_plan(jzlib.JZ_FWD, d) == before
+
+
+def test_every_table_entry_belongs_to_a_layer_and_is_what_the_planner_runs(jzlib):
+    # the generated tables are keyed by GEMM dimensions: a key that no layer produces would silently never be used, and
+    # an entry the planner cannot honour (no such kernel) would silently fall back to the cost model
+    from paper_1807_11205_amd import tune
+    pkg = os.path.dirname(os.path.abspath(tune.__file__))
+    ops = {"fwd": jzlib.JZ_FWD, "bwd_data": jzlib.JZ_BWD_DATA, "bwd_weight": jzlib.JZ_BWD_WEIGHT}
+    for model, inc in (("resnet50", "jz_tuned.inc"), ("alexnet", "jz_tuned_alexnet.inc")):
+        batch, layers = tune.model_layers(model)
+        by_name = {cs.name: cs for cs in layers}
+        entries = 0
+        for line in open(os.path.join(pkg, "csrc", inc)):
+            m = re.match(r"\{(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+)\},\s*// (\S+) (\S+):", line)
+            if not m:
+                assert line.startswith("//") or not line.strip(), line
+                continue
+            entries += 1
+            op, M, N, K, taps, sc, bm, bn, bk, wv, nst, sp = (int(v) for v in m.groups()[:12])
+            cs = by_name[m.group(13)]
+            opn = m.group(14)
+            assert tune.OPS.index(opn) == op
+            rec = dict(H=cs.H, C=cs.C, K=cs.K, R=cs.R, stride=cs.stride, pad=cs.pad, batch=batch, op=opn)
+            assert tune.gemm_dims(rec) == (M, N, K, taps, sc), line
+            d = jzlib.conv_desc(batch, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+            plan = jzlib.jz_conv2d_describe_plan(ops[opn], d)
+            assert "M %d N %d K %d:" % (M, N, K) in plan, (line, plan)
+            assert "tile %dx%dx%d, %d wavefronts, ring %d," % (bm, bn, bk, wv, nst) in plan, (line, plan)
+        assert entries == 3 * len(layers) - sum(1 for cs in layers if cs.first), (model, entries)
