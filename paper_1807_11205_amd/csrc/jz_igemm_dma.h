@@ -510,7 +510,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   // read the operands of k step KS of the stage at byte address sb
   auto read_frags = [&](unsigned sb, auto ks_tag, half8 (&fa)[TM], half8 (&fb)[TN]) {
     constexpr int KS = decltype(ks_tag)::value;
-    if (A_KC) {
+    if constexpr (A_KC) {
       fa[0] = lds_read_b128<0>(sb + adA[KS]);
       if constexpr (TM > 1) fa[1] = lds_read_b128<32 * RB>(sb + adA[KS]);
       if constexpr (TM > 2) fa[2] = lds_read_b128<64 * RB>(sb + adA[KS]);
@@ -523,7 +523,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
         fa[t] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
     }
-    if (B_KC) {
+    if constexpr (B_KC) {
       fb[0] = lds_read_b128<0>(sb + adB[KS]);
       if constexpr (TN > 1) fb[1] = lds_read_b128<32 * RB>(sb + adB[KS]);
       if constexpr (TN > 2) fb[2] = lds_read_b128<64 * RB>(sb + adB[KS]);
