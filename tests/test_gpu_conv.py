@@ -279,6 +279,34 @@ def test_small_channel_kernel_variants_against_the_oracle(jz, monkeypatch, tile,
         jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
 
 
+def test_run_time_tuning_hook_runs_the_chosen_kernel_correctly(jz):
+    # a choice recorded with jz_conv2d_tune_set is what runs (no environment override involved), and the result still
+    # agrees with the oracle; clearing restores the planner's own choice
+    import jzt
+    import oracle
+    N, H, W, C, K, R, S, st, pad = 2, 14, 14, 128, 256, 3, 3, 1, 1
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
+    rng = inputs.rng_for(22)
+    x = inputs.normal_f16(rng, (N, H, W, C))
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+    before = jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
+    try:
+        jz.jz_conv2d_tune_set(jz.JZ_FWD, d, 256, 128, 32, 8, 3, 2)
+        jz.jz_conv2d_tune_set(jz.JZ_BWD_DATA, d, 64, 128, 64, 4, 4, 1)
+        jz.jz_conv2d_tune_set(jz.JZ_BWD_WEIGHT, d, 128, 128, 32, 8, 4, 3)
+        assert "tile 256x128x32, 8 wavefronts, ring 3" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+        assert "tile 128x128x32, 8 wavefronts, ring 4" in jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
+        assert " 3 splits" in jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
+        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
+        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
+        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+    finally:
+        jz.jz_conv2d_tune_clear()
+    assert jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d) == before
+
+
 @pytest.mark.parametrize("B,I,O", [(64, 2048, 1000), (128, 1024, 520), (5, 24, 7), (1, 64, 64), (130, 192, 72)])
 def test_fully_connected_modes(jz, B, I, O):
     import jzt
