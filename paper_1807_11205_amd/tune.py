@@ -274,7 +274,7 @@ def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--json", default=None, help="saved measurements to use instead of running the sweep")
-    ap.add_argument("--out-json", default="gpurun_out/tune_sweep.json")
+    ap.add_argument("--out-json", default="tune_sweep.json", help="where the sweep saves its measurements")
     ap.add_argument("--write", action="store_true", help="write csrc/jz_tuned.inc")
     ap.add_argument("--in-place", action="store_true", help="refine the choices inside the whole step of bench.py")
     ap.add_argument("--streams", type=int, default=3, help="--in-place: streams of the step (as bench.py --streams)")
