@@ -148,6 +148,30 @@ int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes, void* hip
 int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
                       size_t ws_bytes, void* hip_stream);
 
+/* Batch normalization in training mode with an optional ReLU behind it (Section 4.2 of the paper writes the layer as
+ * x^ = (x - mean_B) / sqrt(var_B + eps), y = gamma * x^ + beta; mean_B and var_B are the mean and the plain (biased)
+ * variance of the mini-batch, per channel, over all rows = N*H*W positions).  Not part of the convolution / LARS hot path
+ * the benchmark times; the first piece of the layers that sit between the convolutions.
+ *   x16, y16, dy16, dx16: DEVICE FP16 [rows][channels] (NHWC flattened), 16-byte aligned; channels a multiple of 8, <= 2048
+ *   gamma, beta, save_mean, save_invstd: DEVICE FP32 [channels] (master precision), 16-byte aligned
+ *   dgamma16, dbeta16: DEVICE FP16 [channels]: the parameter gradients as the optimizer's FP16 gradient buffer takes them
+ *                      (they carry whatever loss scale dy16 carries)
+ *   ws: DEVICE workspace of jz_bn_workspace_bytes(rows, channels) bytes (per-slab partial sums and per-channel
+ *       coefficients); contents need not survive between the forward and the backward call
+ * jz_bn_relu_fwd: y = gamma * (x - mean) * invstd + beta, then max(., 0) when relu != 0, rounded once to FP16; writes the
+ *   statistics it used (invstd = 1 / sqrt(var + eps)) to save_mean / save_invstd.  Sums are FP32 within a slab of rows
+ *   and FP64 across slabs, in an order that depends only on (rows, channels): results are deterministic.
+ * jz_bn_relu_bwd: with g = dy (relu == 0) or dy where y16 > 0 and 0 elsewhere (relu != 0; y16 is the forward output):
+ *   dbeta = sum g, dgamma = sum g * x^, dx = gamma * invstd * (g - dbeta / rows - x^ * dgamma / rows).  y16 may be NULL
+ *   when relu == 0.
+ * Status codes as for the convolutions (JZ_ERR_UNSUPPORTED for channel counts outside the range above). */
+int jz_bn_workspace_bytes(int64_t rows, int channels, size_t* bytes);
+int jz_bn_relu_fwd(int64_t rows, int channels, const void* x16, const float* gamma, const float* beta, float eps, int relu,
+                   void* y16, float* save_mean, float* save_invstd, void* ws, size_t ws_bytes, void* hip_stream);
+int jz_bn_relu_bwd(int64_t rows, int channels, const void* x16, const void* y16, const void* dy16, const float* gamma,
+                   const float* save_mean, const float* save_invstd, int relu, void* dx16, void* dgamma16, void* dbeta16,
+                   void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Writes into `text` (HOST, NUL-terminated, at most text_bytes) one line saying how the library would run this
  * operation: GEMM dimensions, kernel variant (output tile, k tile depth, wavefronts), tiles, split of the reduction.
  * For tuning and bug reports; the wording is not part of the contract.  Same status codes as the workspace query. */

@@ -23,6 +23,7 @@ EXPORTS = [
     "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update",
+    "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd",
     "jz_status_string", "jz_version",
 ]
 
@@ -83,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.jz_lars_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.jz_lars_prepare.argtypes = [pp, vp, sz, vp]
         L.jz_lars_mp_update.argtypes = [pp, ctypes.POINTER(jz_lars_hparams), vp, vp, sz, vp]
+        i64, cf = ctypes.c_int64, ctypes.c_float
+        L.jz_bn_workspace_bytes.argtypes = [i64, ci, ctypes.POINTER(sz)]
+        L.jz_bn_relu_fwd.argtypes = [i64, ci, vp, vp, vp, cf, ci, vp, vp, vp, vp, sz, vp]
+        L.jz_bn_relu_bwd.argtypes = [i64, ci, vp, vp, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
         L.jz_status_string.argtypes = [ci]
         L.jz_status_string.restype = ctypes.c_char_p
         L.jz_version.argtypes = []
@@ -146,6 +151,33 @@ def jz_conv2d_describe_plan(op: int, desc: jz_conv_desc) -> str:
     buf = ctypes.create_string_buffer(256)
     _check(lib().jz_conv2d_describe_plan(op, ctypes.byref(desc), buf, 256), "jz_conv2d_describe_plan")
     return buf.value.decode()
+
+
+def jz_bn_workspace_bytes(rows: int, channels: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().jz_bn_workspace_bytes(rows, channels, ctypes.byref(n)), "jz_bn_workspace_bytes")
+    return n.value
+
+
+def jz_bn_relu_fwd(rows, channels, x16, gamma, beta, eps, relu, y16, save_mean, save_invstd, ws, stream=None):
+    """y16 = [relu](gamma * (x16 - mean) * invstd + beta) with the mini-batch statistics, which are written to save_*."""
+    h, f = torch.float16, torch.float32
+    wp, wn = _ws(ws)
+    _check(lib().jz_bn_relu_fwd(rows, channels, _dev_ptr(x16, h, rows * channels, "x16"), _dev_ptr(gamma, f, channels, "gamma"),
+                                _dev_ptr(beta, f, channels, "beta"), float(eps), int(bool(relu)),
+                                _dev_ptr(y16, h, rows * channels, "y16"), _dev_ptr(save_mean, f, channels, "save_mean"),
+                                _dev_ptr(save_invstd, f, channels, "save_invstd"), wp, wn, _stream(stream)), "jz_bn_relu_fwd")
+
+
+def jz_bn_relu_bwd(rows, channels, x16, y16, dy16, gamma, save_mean, save_invstd, relu, dx16, dgamma16, dbeta16, ws, stream=None):
+    """dx16, dgamma16, dbeta16 of the layer above; y16 (the forward output) is the ReLU mask and may be None without ReLU."""
+    h, f = torch.float16, torch.float32
+    wp, wn = _ws(ws)
+    _check(lib().jz_bn_relu_bwd(rows, channels, _dev_ptr(x16, h, rows * channels, "x16"), _dev_ptr(y16, h, rows * channels, "y16"),
+                                _dev_ptr(dy16, h, rows * channels, "dy16"), _dev_ptr(gamma, f, channels, "gamma"),
+                                _dev_ptr(save_mean, f, channels, "save_mean"), _dev_ptr(save_invstd, f, channels, "save_invstd"),
+                                int(bool(relu)), _dev_ptr(dx16, h, rows * channels, "dx16"), _dev_ptr(dgamma16, h, channels, "dgamma16"),
+                                _dev_ptr(dbeta16, h, channels, "dbeta16"), wp, wn, _stream(stream)), "jz_bn_relu_bwd")
 
 
 def jz_conv2d_tune_set(op: int, desc: jz_conv_desc, tile_m: int, tile_n: int, k_tile: int, wavefronts: int, ring: int, splits: int):

@@ -1,0 +1,350 @@
+// Training-mode batch normalization with an optional ReLU, forward and backward, for gfx950 (Jia et al. 2018,
+// Section 4.2: x^ = (x - mean_B) / sqrt(var_B + eps), y = gamma x^ + beta, statistics per channel over the mini-batch).
+//
+// Activations are FP16 [rows][C] (NHWC with rows = N*H*W), gamma / beta / the saved statistics FP32, all sums FP32 per
+// workgroup slab and FP64 across slabs.  Every pass is bound by HBM, so each direction is three stream-ordered launches:
+//
+//   forward   bn_stats      a workgroup owns a slab of rows: per channel sum(x) and sum(x^2) of the slab (no atomics)
+//             bn_fwd_final  per channel: the slabs' sums added in a fixed order in FP64 -> mean, 1/sqrt(var + eps), and the
+//                           affine form y = a x + b (a = gamma invstd, b = beta - mean a) for the next pass
+//             bn_apply      y = [max(., 0)](a x + b), 16 bytes per lane in and out
+//   backward  bn_bwd_stats  per slab and channel: sum(g) and sum(g x^), g = dy masked by (y > 0) when the ReLU is on
+//             bn_bwd_final  dbeta = sum g, dgamma = sum g x^ (FP16 copies for the optimizer's gradient buffer)
+//             bn_bwd_apply  dx = gamma invstd (g - dbeta/M - x^ dgamma/M)
+//
+// A lane always handles 8 consecutive channels (one 16-byte access); the C/8 lanes of a row sit side by side, so a
+// wavefront reads whole rows contiguously.  Results are deterministic: the order of every sum depends only on
+// (rows, C).
+#include <hip/hip_runtime.h>
+
+#include "jz_internal.h"
+
+namespace {
+
+constexpr int BN_THREADS = 256;
+constexpr int BN_MAX_C = 2048;       // C / 8 lanes of a row have to fit one workgroup
+constexpr int BN_TARGET_SLABS = 1024;  // four per compute unit
+constexpr int BN_FIN_C = 8;            // channels a finalize workgroup handles; its 256 / 8 = 32 lanes per channel share the slabs
+
+size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+
+struct BnPlan {
+  int64_t rows = 0;
+  int C = 0, cpr = 0;        // 16-byte chunks per row
+  int rpp = 0;               // rows one pass of a workgroup covers (BN_THREADS / cpr; lanes beyond rpp * cpr idle)
+  int64_t rows_per_slab = 0; // a multiple of rpp
+  int slabs = 0;
+  size_t off_part = 0, off_coef = 0, total = 0;  // workspace: [slabs][2][C] float partial sums, [4][C] float coefficients
+};
+
+int make_bn_plan(int64_t rows, int channels, BnPlan* p) {
+  if (rows <= 0 || channels <= 0) return JZ_ERR_SHAPE;
+  if (channels % 8 != 0 || channels > BN_MAX_C) return JZ_ERR_UNSUPPORTED;
+  if (rows * (int64_t)channels >= (int64_t(1) << 40)) return JZ_ERR_UNSUPPORTED;
+  p->rows = rows;
+  p->C = channels;
+  p->cpr = channels / 8;
+  p->rpp = BN_THREADS / p->cpr;
+  int64_t per = (rows + BN_TARGET_SLABS - 1) / BN_TARGET_SLABS;
+  per = (per + p->rpp - 1) / p->rpp * p->rpp;
+  p->rows_per_slab = per;
+  p->slabs = (int)((rows + per - 1) / per);
+  p->off_part = 0;
+  p->off_coef = up256((size_t)p->slabs * 2 * channels * sizeof(float));
+  p->total = p->off_coef + up256((size_t)4 * channels * sizeof(float));
+  return JZ_OK;
+}
+
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+  const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    _Float16 lo, hi;
+    unsigned short a = (unsigned short)(w[i] & 0xffffu), b = (unsigned short)(w[i] >> 16);
+    __builtin_memcpy(&lo, &a, 2);
+    __builtin_memcpy(&hi, &b, 2);
+    f[2 * i] = (float)lo;
+    f[2 * i + 1] = (float)hi;
+  }
+}
+
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  unsigned w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    _Float16 lo = (_Float16)f[2 * i], hi = (_Float16)f[2 * i + 1];  // round to nearest even
+    unsigned short a, b;
+    __builtin_memcpy(&a, &lo, 2);
+    __builtin_memcpy(&b, &hi, 2);
+    w[i] = (unsigned)a | ((unsigned)b << 16);
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Sums over a slab of rows, for the 8 channels of each lane: s0 and s1 are whatever `term` produces per element.
+// The rpp lanes that share a channel chunk (one per row of a pass) are then added in row order through LDS, and the
+// slab's 2 x C sums are stored.  MODE 0: (x, x^2).  MODE 1: (g, g x^) with g = dy [* (y > 0)].
+template <int MODE>
+__global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__ x, const uint4* __restrict__ y,
+                                                      const uint4* __restrict__ dy, const float* __restrict__ mean,
+                                                      const float* __restrict__ invstd, float* __restrict__ part, int64_t rows,
+                                                      int C, int cpr, int rpp, int64_t rows_per_slab, int relu) {
+  __shared__ float red[2][BN_THREADS][8];
+  const int tid = threadIdx.x;
+  const int chunk = tid % cpr, rsub = tid / cpr;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  int64_t r1 = r0 + rows_per_slab;
+  if (r1 > rows) r1 = rows;
+  float s0[8], s1[8], mu[8], is[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    s0[e] = 0.f; s1[e] = 0.f; mu[e] = 0.f; is[e] = 0.f;
+  }
+  if (MODE == 1 && rsub < rpp) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      mu[e] = mean[chunk * 8 + e];
+      is[e] = invstd[chunk * 8 + e];
+    }
+  }
+  for (int64_t r = r0 + rsub; rsub < rpp && r < r1; r += rpp) {
+    const size_t idx = (size_t)r * cpr + chunk;
+    float xv[8];
+    unpack8(x[idx], xv);
+    if (MODE == 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        s0[e] += xv[e];
+        s1[e] += xv[e] * xv[e];
+      }
+    } else {
+      float gv[8];
+      unpack8(dy[idx], gv);
+      if (relu) {
+        float yv[8];
+        unpack8(y[idx], yv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gv[e] = yv[e] > 0.f ? gv[e] : 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        s0[e] += gv[e];
+        s1[e] += gv[e] * ((xv[e] - mu[e]) * is[e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    red[0][tid][e] = s0[e];
+    red[1][tid][e] = s1[e];
+  }
+  __syncthreads();
+  if (rsub == 0) {
+    for (int j = 1; j < rpp; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        s0[e] += red[0][j * cpr + chunk][e];
+        s1[e] += red[1][j * cpr + chunk][e];
+      }
+    float* p0 = part + ((size_t)blockIdx.x * 2) * C + chunk * 8;
+    float* p1 = p0 + C;
+    *reinterpret_cast<float4*>(p0) = make_float4(s0[0], s0[1], s0[2], s0[3]);
+    *reinterpret_cast<float4*>(p0 + 4) = make_float4(s0[4], s0[5], s0[6], s0[7]);
+    *reinterpret_cast<float4*>(p1) = make_float4(s1[0], s1[1], s1[2], s1[3]);
+    *reinterpret_cast<float4*>(p1 + 4) = make_float4(s1[4], s1[5], s1[6], s1[7]);
+  }
+}
+
+// The two sums of channel c over all slabs, FP64: lane js of the channel's 32 lanes adds slabs js, js + 32, ... in that order,
+// then lane 0 adds the 32 lane sums in lane order (deterministic).  Returns true on the lane that holds the totals.
+__device__ __forceinline__ bool bn_slab_totals(const float* __restrict__ part, int slabs, int C, int c, double& s, double& q) {
+  __shared__ double red[2][BN_THREADS];
+  constexpr int LANES = BN_THREADS / BN_FIN_C;
+  const int js = threadIdx.x / BN_FIN_C;
+  s = 0.0;
+  q = 0.0;
+  if (c < C)
+    for (int k = js; k < slabs; k += LANES) {
+      s += (double)part[((size_t)k * 2) * C + c];
+      q += (double)part[((size_t)k * 2 + 1) * C + c];
+    }
+  red[0][threadIdx.x] = s;
+  red[1][threadIdx.x] = q;
+  __syncthreads();
+  if (js != 0 || c >= C) return false;
+  for (int l = 1; l < LANES; ++l) {
+    s += red[0][l * BN_FIN_C + threadIdx.x];
+    q += red[1][l * BN_FIN_C + threadIdx.x];
+  }
+  return true;
+}
+
+__global__ __launch_bounds__(BN_THREADS) void bn_fwd_final(const float* __restrict__ part, int slabs, int C, double inv_rows,
+                                                          float eps, const float* __restrict__ gamma,
+                                                          const float* __restrict__ beta, float* __restrict__ save_mean,
+                                                          float* __restrict__ save_invstd, float* __restrict__ coef) {
+  const int c = blockIdx.x * BN_FIN_C + threadIdx.x % BN_FIN_C;
+  double s, q;
+  if (!bn_slab_totals(part, slabs, C, c, s, q)) return;
+  const double m = s * inv_rows;
+  double var = q * inv_rows - m * m;
+  if (var < 0.0) var = 0.0;
+  const double is = 1.0 / sqrt(var + (double)eps);
+  const float mf = (float)m, isf = (float)is;
+  save_mean[c] = mf;
+  save_invstd[c] = isf;
+  const float a = gamma[c] * isf;
+  coef[c] = a;
+  coef[C + c] = beta[c] - mf * a;
+}
+
+__global__ __launch_bounds__(BN_THREADS) void bn_apply(const uint4* __restrict__ x, uint4* __restrict__ y,
+                                                      const float* __restrict__ coef, int64_t n_chunks, int C, int cpr, int relu) {
+  const int64_t stride = (int64_t)gridDim.x * BN_THREADS;
+  for (int64_t i = (int64_t)blockIdx.x * BN_THREADS + threadIdx.x; i < n_chunks; i += stride) {
+    const int chunk = (int)(i % cpr);
+    float a[8], b[8], v[8];
+    const float4* ca = reinterpret_cast<const float4*>(coef + chunk * 8);
+    const float4* cb = reinterpret_cast<const float4*>(coef + C + chunk * 8);
+    float4 t0 = ca[0], t1 = ca[1], u0 = cb[0], u1 = cb[1];
+    a[0] = t0.x; a[1] = t0.y; a[2] = t0.z; a[3] = t0.w; a[4] = t1.x; a[5] = t1.y; a[6] = t1.z; a[7] = t1.w;
+    b[0] = u0.x; b[1] = u0.y; b[2] = u0.z; b[3] = u0.w; b[4] = u1.x; b[5] = u1.y; b[6] = u1.z; b[7] = u1.w;
+    unpack8(x[i], v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float z = v[e] * a[e] + b[e];
+      v[e] = (relu && !(z > 0.f)) ? 0.f : z;
+    }
+    y[i] = pack8(v);
+  }
+}
+
+__global__ __launch_bounds__(BN_THREADS) void bn_bwd_final(const float* __restrict__ part, int slabs, int C, double inv_rows,
+                                                          const float* __restrict__ gamma, const float* __restrict__ invstd,
+                                                          unsigned short* __restrict__ dgamma16, unsigned short* __restrict__ dbeta16,
+                                                          float* __restrict__ coef) {
+  const int c = blockIdx.x * BN_FIN_C + threadIdx.x % BN_FIN_C;
+  double sb, sg;
+  if (!bn_slab_totals(part, slabs, C, c, sb, sg)) return;
+  _Float16 hg = (_Float16)(float)sg, hb = (_Float16)(float)sb;
+  unsigned short ug, ub;
+  __builtin_memcpy(&ug, &hg, 2);
+  __builtin_memcpy(&ub, &hb, 2);
+  dgamma16[c] = ug;
+  dbeta16[c] = ub;
+  coef[c] = gamma[c] * invstd[c];            // a
+  coef[C + c] = (float)(sb * inv_rows);      // dbeta / M
+  coef[2 * C + c] = (float)(sg * inv_rows);  // dgamma / M
+}
+
+__global__ __launch_bounds__(BN_THREADS) void bn_bwd_apply(const uint4* __restrict__ x, const uint4* __restrict__ y,
+                                                          const uint4* __restrict__ dy, uint4* __restrict__ dx,
+                                                          const float* __restrict__ mean, const float* __restrict__ invstd,
+                                                          const float* __restrict__ coef, int64_t n_chunks, int C, int cpr, int relu) {
+  const int64_t stride = (int64_t)gridDim.x * BN_THREADS;
+  for (int64_t i = (int64_t)blockIdx.x * BN_THREADS + threadIdx.x; i < n_chunks; i += stride) {
+    const int c0 = (int)(i % cpr) * 8;
+    float xv[8], gv[8], out[8];
+    unpack8(x[i], xv);
+    unpack8(dy[i], gv);
+    if (relu) {
+      float yv[8];
+      unpack8(y[i], yv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) gv[e] = yv[e] > 0.f ? gv[e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float xh = (xv[e] - mean[c0 + e]) * invstd[c0 + e];
+      out[e] = coef[c0 + e] * (gv[e] - coef[C + c0 + e] - xh * coef[2 * C + c0 + e]);
+    }
+    dx[i] = pack8(out);
+  }
+}
+
+unsigned apply_grid(int64_t n_chunks) {
+  int64_t b = (n_chunks + BN_THREADS - 1) / BN_THREADS;
+  const int64_t cap = 256 * 16;  // 16 workgroups per compute unit, grid-stride beyond that
+  return (unsigned)(b < cap ? b : cap);
+}
+
+}  // namespace
+
+extern "C" int jz_bn_workspace_bytes(int64_t rows, int channels, size_t* bytes) {
+  if (!bytes) return JZ_ERR_NULL;
+  BnPlan p;
+  int rc = make_bn_plan(rows, channels, &p);
+  if (rc != JZ_OK) return rc;
+  *bytes = p.total;
+  return JZ_OK;
+}
+
+extern "C" int jz_bn_relu_fwd(int64_t rows, int channels, const void* x16, const float* gamma, const float* beta, float eps,
+                              int relu, void* y16, float* save_mean, float* save_invstd, void* ws, size_t ws_bytes,
+                              void* hip_stream) {
+  BnPlan p;
+  int rc = make_bn_plan(rows, channels, &p);
+  if (rc != JZ_OK) return rc;
+  if (!(eps >= 0.f)) return JZ_ERR_SHAPE;
+  if (!x16 || !gamma || !beta || !y16 || !save_mean || !save_invstd) return JZ_ERR_NULL;
+  if (!ws || ws_bytes < p.total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(x16) || !jz::aligned16(y16) || !jz::aligned16(ws) || !jz::aligned16(gamma) || !jz::aligned16(beta) ||
+      !jz::aligned16(save_mean) || !jz::aligned16(save_invstd))
+    return JZ_ERR_ALIGN;
+  const size_t nb = (size_t)rows * channels * 2, nc = (size_t)channels * 4;
+  if (jz::overlaps(y16, nb, x16, nb) || jz::overlaps(ws, p.total, x16, nb) || jz::overlaps(ws, p.total, y16, nb) ||
+      jz::overlaps(save_mean, nc, x16, nb) || jz::overlaps(save_invstd, nc, x16, nb) || jz::overlaps(save_mean, nc, save_invstd, nc) ||
+      jz::overlaps(save_mean, nc, y16, nb) || jz::overlaps(save_invstd, nc, y16, nb))
+    return JZ_ERR_ALIAS;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_part);
+  float* coef = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_coef);
+  const uint4* x = static_cast<const uint4*>(x16);
+  hipLaunchKernelGGL(bn_stats<0>, dim3((unsigned)p.slabs), dim3(BN_THREADS), 0, st, x, nullptr, nullptr, nullptr, nullptr, part,
+                     rows, channels, p.cpr, p.rpp, p.rows_per_slab, 0);
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  hipLaunchKernelGGL(bn_fwd_final, dim3((unsigned)((channels + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part,
+                     p.slabs, channels, 1.0 / (double)rows, eps, gamma, beta, save_mean, save_invstd, coef);
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  const int64_t n_chunks = rows * p.cpr;
+  hipLaunchKernelGGL(bn_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, static_cast<uint4*>(y16), coef, n_chunks,
+                     channels, p.cpr, relu ? 1 : 0);
+  return jz::launch_status();
+}
+
+extern "C" int jz_bn_relu_bwd(int64_t rows, int channels, const void* x16, const void* y16, const void* dy16,
+                              const float* gamma, const float* save_mean, const float* save_invstd, int relu, void* dx16,
+                              void* dgamma16, void* dbeta16, void* ws, size_t ws_bytes, void* hip_stream) {
+  BnPlan p;
+  int rc = make_bn_plan(rows, channels, &p);
+  if (rc != JZ_OK) return rc;
+  if (!x16 || !dy16 || !gamma || !save_mean || !save_invstd || !dx16 || !dgamma16 || !dbeta16 || (relu && !y16)) return JZ_ERR_NULL;
+  if (!ws || ws_bytes < p.total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(x16) || !jz::aligned16(dy16) || !jz::aligned16(dx16) || !jz::aligned16(ws) || (relu && !jz::aligned16(y16)) ||
+      !jz::aligned16(gamma) || !jz::aligned16(save_mean) || !jz::aligned16(save_invstd))
+    return JZ_ERR_ALIGN;
+  const size_t nb = (size_t)rows * channels * 2, nh = (size_t)channels * 2;
+  if (jz::overlaps(dx16, nb, x16, nb) || jz::overlaps(dx16, nb, dy16, nb) || (relu && jz::overlaps(dx16, nb, y16, nb)) ||
+      jz::overlaps(ws, p.total, x16, nb) || jz::overlaps(ws, p.total, dy16, nb) || jz::overlaps(ws, p.total, dx16, nb) ||
+      (relu && jz::overlaps(ws, p.total, y16, nb)) || jz::overlaps(dgamma16, nh, dbeta16, nh) || jz::overlaps(dgamma16, nh, dx16, nb) ||
+      jz::overlaps(dbeta16, nh, dx16, nb) || jz::overlaps(dgamma16, nh, x16, nb) || jz::overlaps(dbeta16, nh, x16, nb) ||
+      jz::overlaps(dgamma16, nh, dy16, nb) || jz::overlaps(dbeta16, nh, dy16, nb))
+    return JZ_ERR_ALIAS;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_part);
+  float* coef = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_coef);
+  const uint4* x = static_cast<const uint4*>(x16);
+  const uint4* y = static_cast<const uint4*>(y16);
+  const uint4* dy = static_cast<const uint4*>(dy16);
+  hipLaunchKernelGGL(bn_stats<1>, dim3((unsigned)p.slabs), dim3(BN_THREADS), 0, st, x, y, dy, save_mean, save_invstd, part, rows,
+                     channels, p.cpr, p.rpp, p.rows_per_slab, relu ? 1 : 0);
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  hipLaunchKernelGGL(bn_bwd_final, dim3((unsigned)((channels + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part,
+                     p.slabs, channels, 1.0 / (double)rows, gamma, save_invstd, static_cast<unsigned short*>(dgamma16),
+                     static_cast<unsigned short*>(dbeta16), coef);
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  const int64_t n_chunks = rows * p.cpr;
+  hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, y, dy, static_cast<uint4*>(dx16),
+                     save_mean, save_invstd, coef, n_chunks, channels, p.cpr, relu ? 1 : 0);
+  return jz::launch_status();
+}
