@@ -344,6 +344,56 @@ def alexnet_workload(args):
                      "flop_per_step": flops}}))
 
 
+def bn_workload(args):
+    """The 53 batch-normalization + ReLU layers of ResNet-50 v1 at N = 64 (one behind every convolution, on that
+    convolution's output shape), forward of all, then backward of all in reverse order, on independent seeded inputs.
+    HBM-bound: algorithmic bytes are 4 per element forward (x read, y written) and 8 backward (x, y, dy read, dx written)."""
+    B, h, dev = args.batch, torch.float16, "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    layers, elems, ws_bytes = [], 0, 16
+    for cs in shapes.resnet50_convs():
+        rows, C = B * cs.P * cs.P, cs.K
+        n = rows * C
+        layers.append(dict(rows=rows, C=C, x=(torch.randn(n, generator=gen, device=dev) * 1.5 + 0.3).to(h),
+                           dy=torch.randn(n, generator=gen, device=dev).to(h), y=torch.empty(n, dtype=h, device=dev),
+                           dx=torch.empty(n, dtype=h, device=dev), gamma=torch.ones(C, device=dev), beta=torch.zeros(C, device=dev),
+                           mean=torch.empty(C, device=dev), invstd=torch.empty(C, device=dev),
+                           dg=torch.empty(C, dtype=h, device=dev), db=torch.empty(C, dtype=h, device=dev)))
+        elems += n
+        ws_bytes = max(ws_bytes, api.jz_bn_workspace_bytes(rows, C))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def run():
+        for L in layers:
+            api.jz_bn_relu_fwd(L["rows"], L["C"], L["x"], L["gamma"], L["beta"], 1e-5, True, L["y"], L["mean"], L["invstd"], ws)
+        for L in reversed(layers):
+            api.jz_bn_relu_bwd(L["rows"], L["C"], L["x"], L["y"], L["dy"], L["gamma"], L["mean"], L["invstd"], True, L["dx"],
+                               L["dg"], L["db"], ws)
+
+    for _ in range(max(args.warmup, 1)):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    gbps = 12.0 * elems / (e0.elapsed_time(e1) / args.steps * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "ResNet-50 N=%d batch-norm + ReLU fwd+bwd GB/s (algorithmic)" % B, "value": gbps, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 storage, f32 statistics (f64 across slabs)", "data": "synthetic",
+        "config": {"workload": "the 53 batch-normalization + ReLU layers of ResNet-50 v1 (training mode), forward then backward, "
+                               "independent seeded inputs", "batch": B, "elements_per_pass": elems, "launch": "eager", "streams": 1},
+        "roofline": {"kernel": "bn_stats / bn_apply / bn_bwd_apply (6 launches per layer)", "bound": "hbm", "achieved": gbps,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "bytes_per_element": 12}}))
+
+
 def cpu_baseline(sample_batch=8):
     """The fp64 oracle, as it stands, on the host cores: the same 53-conv + FC stack at a small batch, plus LARS."""
     import oracle
@@ -382,8 +432,9 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=None, help="default: 64 (resnet50), 128 (alexnet)")
-    ap.add_argument("--workload", default="resnet50", choices=("resnet50", "alexnet"),
-                    help="resnet50: the full step the headline metric is quoted on; alexnet: the AlexNet-shaped layers of configs[3]")
+    ap.add_argument("--workload", default="resnet50", choices=("resnet50", "alexnet", "bn"),
+                    help="resnet50: the full step the headline metric is quoted on; alexnet: the AlexNet-shaped layers of configs[3]; "
+                         "bn: the batch-normalization + ReLU layers of ResNet-50 (not part of the headline step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
     ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
@@ -407,9 +458,12 @@ def main():
     api.lib()
     torch.cuda.set_device(0)
     if args.batch is None:
-        args.batch = 64 if args.workload == "resnet50" else 128
+        args.batch = 128 if args.workload == "alexnet" else 64
     if args.workload == "alexnet":
         alexnet_workload(args)
+        return
+    if args.workload == "bn":
+        bn_workload(args)
         return
     wl = ResNet50Step(batch=args.batch)
 

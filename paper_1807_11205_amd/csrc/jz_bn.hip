@@ -10,7 +10,7 @@
 //             bn_apply      y = [max(., 0)](a x + b), 16 bytes per lane in and out
 //   backward  bn_bwd_stats  per slab and channel: sum(g) and sum(g x^), g = dy masked by (y > 0) when the ReLU is on
 //             bn_bwd_final  dbeta = sum g, dgamma = sum g x^ (FP16 copies for the optimizer's gradient buffer)
-//             bn_bwd_apply  dx = gamma invstd (g - dbeta/M - x^ dgamma/M)
+//             bn_bwd_apply  dx = gamma invstd (g - dbeta/M - x^ dgamma/M), evaluated as a g + P x + Q per channel
 //
 // A lane always handles 8 consecutive channels (one 16-byte access); the C/8 lanes of a row sit side by side, so a
 // wavefront reads whole rows contiguously.  Results are deterministic: the order of every sum depends only on
@@ -45,7 +45,9 @@ int make_bn_plan(int64_t rows, int channels, BnPlan* p) {
   p->C = channels;
   p->cpr = channels / 8;
   p->rpp = BN_THREADS / p->cpr;
+  // at most BN_TARGET_SLABS slabs, and at least 16 passes of the workgroup per slab (small tensors get fewer slabs)
   int64_t per = (rows + BN_TARGET_SLABS - 1) / BN_TARGET_SLABS;
+  if (per < 16 * (int64_t)p->rpp) per = 16 * (int64_t)p->rpp;
   per = (per + p->rpp - 1) / p->rpp * p->rpp;
   p->rows_per_slab = per;
   p->slabs = (int)((rows + per - 1) / per);
@@ -107,29 +109,50 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
       is[e] = invstd[chunk * 8 + e];
     }
   }
-  for (int64_t r = r0 + rsub; rsub < rpp && r < r1; r += rpp) {
-    const size_t idx = (size_t)r * cpr + chunk;
-    float xv[8];
-    unpack8(x[idx], xv);
-    if (MODE == 0) {
+  // U rows of a lane are requested together (the loop is bound by memory latency otherwise)
+  constexpr int U = MODE == 0 ? 4 : 2;
+  for (int64_t r = r0 + rsub; rsub < rpp && r < r1; r += (int64_t)U * rpp) {
+    uint4 qx[U], qd[U], qy[U];
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        s0[e] += xv[e];
-        s1[e] += xv[e] * xv[e];
+    for (int u = 0; u < U; ++u) {
+      const int64_t ru = r + (int64_t)u * rpp;
+      const bool in = ru < r1;
+      const size_t idx = (size_t)(in ? ru : r) * cpr + chunk;
+      qx[u] = x[idx];
+      if (MODE == 1) {
+        qd[u] = dy[idx];
+        qy[u] = relu ? y[idx] : zero;
       }
-    } else {
-      float gv[8];
-      unpack8(dy[idx], gv);
-      if (relu) {
-        float yv[8];
-        unpack8(y[idx], yv);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) gv[e] = yv[e] > 0.f ? gv[e] : 0.f;
+      if (!in) {            // rows beyond the slab add nothing (x = 0 and g = 0 contribute zero to every sum)
+        qx[u] = zero;
+        if (MODE == 1) qd[u] = zero;
       }
+    }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        s0[e] += gv[e];
-        s1[e] += gv[e] * ((xv[e] - mu[e]) * is[e]);
+    for (int u = 0; u < U; ++u) {
+      float xv[8];
+      unpack8(qx[u], xv);
+      if (MODE == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          s0[e] += xv[e];
+          s1[e] += xv[e] * xv[e];
+        }
+      } else {
+        float gv[8];
+        unpack8(qd[u], gv);
+        if (relu) {
+          float yv[8];
+          unpack8(qy[u], yv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) gv[e] = yv[e] > 0.f ? gv[e] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          s0[e] += gv[e];
+          s1[e] += gv[e] * ((xv[e] - mu[e]) * is[e]);
+        }
       }
     }
   }
@@ -164,9 +187,20 @@ __device__ __forceinline__ bool bn_slab_totals(const float* __restrict__ part, i
   s = 0.0;
   q = 0.0;
   if (c < C)
-    for (int k = js; k < slabs; k += LANES) {
-      s += (double)part[((size_t)k * 2) * C + c];
-      q += (double)part[((size_t)k * 2 + 1) * C + c];
+    for (int k = js; k < slabs; k += 8 * LANES) {  // eight slabs' sums requested together, added in slab order
+      float a[8], b[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int ku = k + u * LANES;
+        const bool in = ku < slabs;
+        a[u] = in ? part[((size_t)ku * 2) * C + c] : 0.f;
+        b[u] = in ? part[((size_t)ku * 2 + 1) * C + c] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        s += (double)a[u];
+        q += (double)b[u];
+      }
     }
   red[0][threadIdx.x] = s;
   red[1][threadIdx.x] = q;
@@ -220,9 +254,9 @@ __global__ __launch_bounds__(BN_THREADS) void bn_apply(const uint4* __restrict__
 }
 
 __global__ __launch_bounds__(BN_THREADS) void bn_bwd_final(const float* __restrict__ part, int slabs, int C, double inv_rows,
-                                                          const float* __restrict__ gamma, const float* __restrict__ invstd,
-                                                          unsigned short* __restrict__ dgamma16, unsigned short* __restrict__ dbeta16,
-                                                          float* __restrict__ coef) {
+                                                          const float* __restrict__ gamma, const float* __restrict__ mean,
+                                                          const float* __restrict__ invstd, unsigned short* __restrict__ dgamma16,
+                                                          unsigned short* __restrict__ dbeta16, float* __restrict__ coef) {
   const int c = blockIdx.x * BN_FIN_C + threadIdx.x % BN_FIN_C;
   double sb, sg;
   if (!bn_slab_totals(part, slabs, C, c, sb, sg)) return;
@@ -232,32 +266,41 @@ __global__ __launch_bounds__(BN_THREADS) void bn_bwd_final(const float* __restri
   __builtin_memcpy(&ub, &hb, 2);
   dgamma16[c] = ug;
   dbeta16[c] = ub;
-  coef[c] = gamma[c] * invstd[c];            // a
-  coef[C + c] = (float)(sb * inv_rows);      // dbeta / M
-  coef[2 * C + c] = (float)(sg * inv_rows);  // dgamma / M
+  // dx = a (g - dbeta/M - x^ dgamma/M) with x^ = (x - mean) invstd, as dx = a g + P x + Q
+  const double a = (double)gamma[c] * (double)invstd[c];
+  const double t = a * (sg * inv_rows) * (double)invstd[c];
+  coef[c] = (float)a;
+  coef[C + c] = (float)(-t);
+  coef[2 * C + c] = (float)(t * (double)mean[c] - a * (sb * inv_rows));
+}
+
+__device__ __forceinline__ void load8(const float* p, float (&f)[8]) {
+  const float4 t0 = reinterpret_cast<const float4*>(p)[0], t1 = reinterpret_cast<const float4*>(p)[1];
+  f[0] = t0.x; f[1] = t0.y; f[2] = t0.z; f[3] = t0.w; f[4] = t1.x; f[5] = t1.y; f[6] = t1.z; f[7] = t1.w;
 }
 
 __global__ __launch_bounds__(BN_THREADS) void bn_bwd_apply(const uint4* __restrict__ x, const uint4* __restrict__ y,
                                                           const uint4* __restrict__ dy, uint4* __restrict__ dx,
-                                                          const float* __restrict__ mean, const float* __restrict__ invstd,
                                                           const float* __restrict__ coef, int64_t n_chunks, int C, int cpr, int relu) {
   const int64_t stride = (int64_t)gridDim.x * BN_THREADS;
   for (int64_t i = (int64_t)blockIdx.x * BN_THREADS + threadIdx.x; i < n_chunks; i += stride) {
     const int c0 = (int)(i % cpr) * 8;
-    float xv[8], gv[8], out[8];
-    unpack8(x[i], xv);
-    unpack8(dy[i], gv);
+    const uint4 qx = x[i], qd = dy[i];
+    const uint4 qy = relu ? y[i] : make_uint4(0u, 0u, 0u, 0u);
+    float a[8], pc[8], qc[8], xv[8], gv[8], out[8];
+    load8(coef + c0, a);
+    load8(coef + C + c0, pc);
+    load8(coef + 2 * C + c0, qc);
+    unpack8(qx, xv);
+    unpack8(qd, gv);
     if (relu) {
       float yv[8];
-      unpack8(y[i], yv);
+      unpack8(qy, yv);
 #pragma unroll
       for (int e = 0; e < 8; ++e) gv[e] = yv[e] > 0.f ? gv[e] : 0.f;
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float xh = (xv[e] - mean[c0 + e]) * invstd[c0 + e];
-      out[e] = coef[c0 + e] * (gv[e] - coef[C + c0 + e] - xh * coef[2 * C + c0 + e]);
-    }
+    for (int e = 0; e < 8; ++e) out[e] = a[e] * gv[e] + (pc[e] * xv[e] + qc[e]);
     dx[i] = pack8(out);
   }
 }
@@ -340,11 +383,11 @@ extern "C" int jz_bn_relu_bwd(int64_t rows, int channels, const void* x16, const
                      channels, p.cpr, p.rpp, p.rows_per_slab, relu ? 1 : 0);
   if ((rc = jz::launch_status()) != JZ_OK) return rc;
   hipLaunchKernelGGL(bn_bwd_final, dim3((unsigned)((channels + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part,
-                     p.slabs, channels, 1.0 / (double)rows, gamma, save_invstd, static_cast<unsigned short*>(dgamma16),
+                     p.slabs, channels, 1.0 / (double)rows, gamma, save_mean, save_invstd, static_cast<unsigned short*>(dgamma16),
                      static_cast<unsigned short*>(dbeta16), coef);
   if ((rc = jz::launch_status()) != JZ_OK) return rc;
   const int64_t n_chunks = rows * p.cpr;
-  hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, y, dy, static_cast<uint4*>(dx16),
-                     save_mean, save_invstd, coef, n_chunks, channels, p.cpr, relu ? 1 : 0);
+  hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, y, dy, static_cast<uint4*>(dx16), coef,
+                     n_chunks, channels, p.cpr, relu ? 1 : 0);
   return jz::launch_status();
 }
