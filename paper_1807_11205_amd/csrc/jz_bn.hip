@@ -24,7 +24,7 @@ namespace {
 constexpr int BN_THREADS = 256;
 constexpr int BN_MAX_C = 2048;       // C / 8 lanes of a row have to fit one workgroup
 constexpr int BN_TARGET_SLABS = 1024;  // four per compute unit
-constexpr int BN_FIN_C = 8;            // channels a finalize workgroup handles; its 256 / 8 = 32 lanes per channel share the slabs
+constexpr int BN_FIN_C = 4;            // channels a finalize workgroup handles; its 256 / 4 = 64 lanes per channel share the slabs
 
 size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
     }
   }
   // U rows of a lane are requested together (the loop is bound by memory latency otherwise)
-  constexpr int U = MODE == 0 ? 4 : 2;
+  constexpr int U = MODE == 0 ? 8 : 4;
   for (int64_t r = r0 + rsub; rsub < rpp && r < r1; r += (int64_t)U * rpp) {
     uint4 qx[U], qd[U], qy[U];
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
@@ -178,8 +178,8 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
   }
 }
 
-// The two sums of channel c over all slabs, FP64: lane js of the channel's 32 lanes adds slabs js, js + 32, ... in that order,
-// then lane 0 adds the 32 lane sums in lane order (deterministic).  Returns true on the lane that holds the totals.
+// The two sums of channel c over all slabs, FP64: lane js of the channel's 64 lanes adds slabs js, js + 64, ... in that order,
+// then lane 0 adds the 64 lane sums in lane order (deterministic).  Returns true on the lane that holds the totals.
 __device__ __forceinline__ bool bn_slab_totals(const float* __restrict__ part, int slabs, int C, int c, double& s, double& q) {
   __shared__ double red[2][BN_THREADS];
   constexpr int LANES = BN_THREADS / BN_FIN_C;
@@ -190,12 +190,18 @@ __device__ __forceinline__ bool bn_slab_totals(const float* __restrict__ part, i
     for (int k = js; k < slabs; k += 8 * LANES) {  // eight slabs' sums requested together, added in slab order
       float a[8], b[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < 8; ++u) {  // all sixteen loads first (clamped index), the selection afterwards
         const int ku = k + u * LANES;
-        const bool in = ku < slabs;
-        a[u] = in ? part[((size_t)ku * 2) * C + c] : 0.f;
-        b[u] = in ? part[((size_t)ku * 2 + 1) * C + c] : 0.f;
+        const int kc = ku < slabs ? ku : k;
+        a[u] = part[((size_t)kc * 2) * C + c];
+        b[u] = part[((size_t)kc * 2 + 1) * C + c];
       }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (k + u * LANES >= slabs) {
+          a[u] = 0.f;
+          b[u] = 0.f;
+        }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         s += (double)a[u];
