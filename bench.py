@@ -29,6 +29,7 @@ HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
 LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32 4 + w16 2
 # HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very workload (default batch and
 # variant), scaled by the same counters' readings for a 1 GiB copy; the runs are summarised under profiles/.
+MEASURED_BN_HBM_BYTES_PER_STEP = 13.94e9     # bench.py --workload bn at N = 64 (profiles/bench_bn_resnet50_n64_kernel_stats.txt)
 MEASURED_GEMM_HBM_BYTES_PER_STEP = 9.61e9   # all conv/FC launches with their split-K reductions and packing kernels
 MEASURED_LARS_HBM_BYTES_PER_UPDATE = 562e6   # gradient norm pass 51 MB + update pass 511 MB
 
@@ -390,7 +391,10 @@ def bn_workload(args):
         "config": {"workload": "the 53 batch-normalization + ReLU layers of ResNet-50 v1 (training mode), forward then backward, "
                                "independent seeded inputs", "batch": B, "elements_per_pass": elems, "launch": "eager", "streams": 1},
         "roofline": {"kernel": "bn_stats / bn_apply / bn_bwd_apply (6 launches per layer)", "bound": "hbm", "achieved": gbps,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_BN_HBM_BYTES_PER_STEP if B == 64 else None,
+                     "traffic_note": "HBM bytes per step (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled): every "
+                                     "direction is two passes over the tensors, 20 bytes per element against 12 algorithmic",
                      "bytes_per_element": 12}}))
 
 

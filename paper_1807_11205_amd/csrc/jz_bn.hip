@@ -23,8 +23,9 @@ namespace {
 
 constexpr int BN_THREADS = 256;
 constexpr int BN_MAX_C = 2048;       // C / 8 lanes of a row have to fit one workgroup
-constexpr int BN_TARGET_SLABS = 1024;  // four per compute unit
-constexpr int BN_FIN_C = 4;            // channels a finalize workgroup handles; its 256 / 4 = 64 lanes per channel share the slabs
+constexpr int BN_TARGET_SLABS = 512;   // two per compute unit
+constexpr int BN_FIN_C = 8;            // channels a finalize workgroup handles (32 contiguous bytes of every slab's sums);
+                                       // its 256 / 8 = 32 lanes per channel share the slabs
 
 size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -45,9 +46,11 @@ int make_bn_plan(int64_t rows, int channels, BnPlan* p) {
   p->C = channels;
   p->cpr = channels / 8;
   p->rpp = BN_THREADS / p->cpr;
-  // at most BN_TARGET_SLABS slabs, and at least 16 passes of the workgroup per slab (small tensors get fewer slabs)
+  // at most BN_TARGET_SLABS slabs, and at least 16 passes of the workgroup and 64 rows per slab: small tensors get fewer
+  // slabs, so that the partial sums stay small beside the tensor
   int64_t per = (rows + BN_TARGET_SLABS - 1) / BN_TARGET_SLABS;
   if (per < 16 * (int64_t)p->rpp) per = 16 * (int64_t)p->rpp;
+  if (per < 64) per = 64;
   per = (per + p->rpp - 1) / p->rpp * p->rpp;
   p->rows_per_slab = per;
   p->slabs = (int)((rows + per - 1) / per);
@@ -178,8 +181,8 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
   }
 }
 
-// The two sums of channel c over all slabs, FP64: lane js of the channel's 64 lanes adds slabs js, js + 64, ... in that order,
-// then lane 0 adds the 64 lane sums in lane order (deterministic).  Returns true on the lane that holds the totals.
+// The two sums of channel c over all slabs, FP64: lane js of the channel's 32 lanes adds slabs js, js + 32, ... in that order,
+// then lane 0 adds the 32 lane sums in lane order (deterministic).  Returns true on the lane that holds the totals.
 __device__ __forceinline__ bool bn_slab_totals(const float* __restrict__ part, int slabs, int C, int c, double& s, double& q) {
   __shared__ double red[2][BN_THREADS];
   constexpr int LANES = BN_THREADS / BN_FIN_C;
