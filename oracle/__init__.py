@@ -6,6 +6,7 @@ this package.  It shares nothing with the HIP library and never imports it.
 * conv / FC: fp64 direct definitions in C (``jz_oracle.c``), called via ctypes.
 * LARS: the mixed-precision update of Section 4.1 / Eq. 1, step by step in
   fp64 numpy (``lars.py``).
+* the dynamic loss-scale controller around that update (``loss_scale.py``).
 * batch normalization + ReLU (Section 4.2's formulas) and its gradient, fp64 numpy (``bn.py``).
 """
 import ctypes
@@ -15,6 +16,7 @@ import numpy as np
 
 from .bn import bn_relu_bwd, bn_relu_fwd  # noqa: F401
 from .lars import lars_mp_update, lars_trust_ratio  # noqa: F401
+from .loss_scale import loss_scale_step  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
