@@ -41,6 +41,7 @@ class ResNet50Step:
         self.N = batch
         self.dev = device
         self.loss_scale = float(loss_scale)
+        self.ls_state = self.ls_policy = None
         gen = torch.Generator(device=device)
         gen.manual_seed(seed)
         self.gen = gen
@@ -187,7 +188,17 @@ class ResNet50Step:
                 streams[si].wait_event(obj)
 
     def run_lars(self):
-        api.jz_lars_mp_update(self.ps, self.hparams(), self.found_inf, self.lars_ws)
+        if self.ls_state is not None:
+            api.jz_lars_mp_update_dyn(self.ps, self.hparams(), self.ls_policy, self.ls_state, self.found_inf, self.lars_ws)
+        else:
+            api.jz_lars_mp_update(self.ps, self.hparams(), self.found_inf, self.lars_ws)
+
+    def use_dynamic_loss_scale(self):
+        """The update reads S from device memory and the controller kernel runs behind it.  The growth interval is set
+        beyond the run's length so that S stays at the value the synthetic gradients were scaled with."""
+        self.ls_state = torch.zeros(2, dtype=torch.int32, device=self.found_inf.device)
+        self.ls_policy = api.loss_scale_policy(growth_interval=1 << 30)
+        api.jz_loss_scale_init(self.ls_state, self.loss_scale)
 
     def step(self):
         self.run_gemms()
@@ -444,6 +455,8 @@ def main():
     ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
                     "for the projection shortcuts (forward) and the backward-weight launches (at most 4)")
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a HIP graph (1) or launch eagerly (0); eager launches measured faster here")
+    ap.add_argument("--dynamic-loss-scale", action="store_true",
+                    help="time jz_lars_mp_update_dyn (loss scale and its controller on the device) instead of jz_lars_mp_update")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run ten 1 GiB device-to-device copies and exit: the known-size kernel that the HBM byte counters "
                          "(FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc) are scaled by")
@@ -480,6 +493,8 @@ def main():
         wl.halve_loss_scale()
     assert int(wl.found_inf.item()) == 0, "loss-scale back-off did not clear the overflow flag"
     wl.reset_state()
+    if args.dynamic_loss_scale:
+        wl.use_dynamic_loss_scale()
 
     if args.per_layer:
         per_layer_report(wl)
@@ -544,7 +559,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[4]: ResNet-50 v1, 53 convs + FC, fwd + bwd_data + bwd_weight per layer on "
                                "independent seeded N(0,1) inputs, then fused LARS over 161 tensors / 25,557,032 params",
-                   "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "launch": "hip graph" if graphs else "eager", "streams": args.streams},
+                   "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "loss_scale_control": "device" if args.dynamic_loss_scale else "fixed", "launch": "hip graph" if graphs else "eager", "streams": args.streams},
         "pct_fp16_mfma_peak": 100.0 * (wl.flops / (ms_per_step * 1e-3) / 1e12) / FP16_MFMA_PEAK_TFLOPS,
         "roofline": {"kernel": "igemm_kernel (all %d conv/FC launches of a step)" % n_gemm, "bound": "mfma",
                      "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -148,6 +148,34 @@ int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes, void* hip
 int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
                       size_t ws_bytes, void* hip_stream);
 
+/* Dynamic loss scaling around the LARS update.  Section 4.1 multiplies the loss by a scale S so that small gradients
+ * survive FP16 and divides by S before the update; Section 5.3 calls this required at large batch sizes and gives no
+ * policy.  The policy here is the usual one: an update that found Inf/NaN is skipped (as jz_lars_mp_update does) and
+ * S <- max(S * backoff_factor, min_scale); after growth_interval clean updates in a row S <- min(S * growth_factor,
+ * max_scale).  S lives in DEVICE memory, so a training loop never has to read the overflow flag back: the next
+ * backward pass multiplies its loss gradient by state->scale on the device.
+ *   jz_loss_scale_init:    writes {initial_scale, 0} to *state_dev (DEVICE, 8-byte aligned) on the stream.
+ *   jz_lars_mp_update_dyn: jz_lars_mp_update with S read from state_dev->scale on the device (hp->loss_scale is
+ *                          ignored), followed by the controller step above (inside the last kernel of the update: no
+ *                          further launch; a call whose workspace header does not match, found_inf = -1, leaves the
+ *                          state as it was).  state_dev must not overlap any other buffer.  Everything else (workspace, prepare,
+ *                          found_inf_dev, status codes) as for jz_lars_mp_update; JZ_ERR_SHAPE for a policy with
+ *                          growth_factor < 1, backoff_factor outside (0, 1], growth_interval < 1 or min_scale > max_scale. */
+typedef struct {
+  float scale;    /* S */
+  int good_steps; /* clean updates since S last changed */
+} jz_loss_scale_state;
+typedef struct {
+  float growth_factor;  /* >= 1, e.g. 2 */
+  float backoff_factor; /* in (0, 1], e.g. 0.5 */
+  int growth_interval;  /* >= 1, e.g. 2000 */
+  float min_scale;      /* > 0 */
+  float max_scale;      /* >= min_scale */
+} jz_loss_scale_policy;
+int jz_loss_scale_init(jz_loss_scale_state* state_dev, float initial_scale, void* hip_stream);
+int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* policy,
+                          jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Batch normalization in training mode with an optional ReLU behind it (Section 4.2 of the paper writes the layer as
  * x^ = (x - mean_B) / sqrt(var_B + eps), y = gamma * x^ + beta; mean_B and var_B are the mean and the plain (biased)
  * variance of the mini-batch, per channel, over all rows = N*H*W positions).  Not part of the convolution / LARS hot path

@@ -22,7 +22,7 @@ JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
 EXPORTS = [
     "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
-    "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update",
+    "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
     "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd",
     "jz_status_string", "jz_version",
 ]
@@ -48,6 +48,11 @@ class jz_conv_desc(ctypes.Structure):
 
 class jz_lars_hparams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_float) for n in ("lr", "momentum", "weight_decay", "trust_coef", "loss_scale")]
+
+
+class jz_loss_scale_policy(ctypes.Structure):
+    _fields_ = [("growth_factor", ctypes.c_float), ("backoff_factor", ctypes.c_float), ("growth_interval", ctypes.c_int),
+                ("min_scale", ctypes.c_float), ("max_scale", ctypes.c_float)]
 
 
 class jz_param_set(ctypes.Structure):
@@ -84,6 +89,9 @@ def lib() -> ctypes.CDLL:
         L.jz_lars_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.jz_lars_prepare.argtypes = [pp, vp, sz, vp]
         L.jz_lars_mp_update.argtypes = [pp, ctypes.POINTER(jz_lars_hparams), vp, vp, sz, vp]
+        L.jz_loss_scale_init.argtypes = [vp, ctypes.c_float, vp]
+        L.jz_lars_mp_update_dyn.argtypes = [pp, ctypes.POINTER(jz_lars_hparams), ctypes.POINTER(jz_loss_scale_policy), vp, vp,
+                                            vp, sz, vp]
         i64, cf = ctypes.c_int64, ctypes.c_float
         L.jz_bn_workspace_bytes.argtypes = [i64, ci, ctypes.POINTER(sz)]
         L.jz_bn_relu_fwd.argtypes = [i64, ci, vp, vp, vp, cf, ci, vp, vp, vp, vp, sz, vp]
@@ -302,6 +310,37 @@ def jz_lars_mp_update(ps: ParamSet, hp: jz_lars_hparams, found_inf: torch.Tensor
     wp, wn = _ws(ws)
     _check(lib().jz_lars_mp_update(ctypes.byref(ps.c), ctypes.byref(hp), found_inf.data_ptr(), wp, wn, _stream(stream)),
            "jz_lars_mp_update")
+
+
+def _ls_state(state: torch.Tensor) -> int:
+    # jz_loss_scale_state {float scale; int good_steps;} held in a two-element int32 GPU tensor
+    if not state.is_cuda or state.dtype != torch.int32 or state.numel() != 2 or not state.is_contiguous():
+        raise TypeError("the loss-scale state must be a contiguous two-element int32 GPU tensor")
+    return state.data_ptr()
+
+
+def jz_loss_scale_init(state: torch.Tensor, initial_scale: float, stream=None):
+    _check(lib().jz_loss_scale_init(_ls_state(state), float(initial_scale), _stream(stream)), "jz_loss_scale_init")
+
+
+def loss_scale_state(state: torch.Tensor):
+    """(scale, good_steps) read back from the device state (synchronizes)."""
+    h = state.cpu()
+    return float(h[:1].view(torch.float32).item()), int(h[1].item())
+
+
+def loss_scale_policy(growth_factor=2.0, backoff_factor=0.5, growth_interval=2000, min_scale=1.0,
+                      max_scale=65536.0) -> jz_loss_scale_policy:
+    return jz_loss_scale_policy(growth_factor, backoff_factor, growth_interval, min_scale, max_scale)
+
+
+def jz_lars_mp_update_dyn(ps: ParamSet, hp: jz_lars_hparams, policy: jz_loss_scale_policy, state: torch.Tensor,
+                          found_inf: torch.Tensor, ws: torch.Tensor, stream=None):
+    if not found_inf.is_cuda or found_inf.dtype != torch.int32 or found_inf.numel() != 1:
+        raise TypeError("found_inf must be a one-element int32 GPU tensor")
+    wp, wn = _ws(ws)
+    _check(lib().jz_lars_mp_update_dyn(ctypes.byref(ps.c), ctypes.byref(hp), ctypes.byref(policy), _ls_state(state),
+                                       found_inf.data_ptr(), wp, wn, _stream(stream)), "jz_lars_mp_update_dyn")
 
 
 def lars_hparams(lr, momentum, weight_decay, trust_coef, loss_scale) -> jz_lars_hparams:

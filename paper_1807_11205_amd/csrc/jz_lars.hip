@@ -285,10 +285,15 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_reduce(Tables tb, const flo
   }
 }
 
-__global__ __launch_bounds__(LARS_THREADS) void lars_finalize(Tables tb, float lr, float eta, float loss_scale) {
+// scale_dev != nullptr: the loss scale lives on the device (dynamic loss scaling) and replaces the argument
+__global__ __launch_bounds__(LARS_THREADS) void lars_finalize(Tables tb, float lr, float eta, float loss_scale,
+                                                              const float* __restrict__ scale_dev) {
   __shared__ double red[4];
+  if (scale_dev) loss_scale = *scale_dev;
   if (!table_ok(tb)) return;
   const int t = blockIdx.x;
+  // the update kernel adjusts the device-resident scale itself, so its workgroups take 1/S from here instead
+  if (scale_dev && t == 0 && threadIdx.x == 0) tb.state[1] = __float_as_int(1.0f / loss_scale);
   const int c0 = tb.chunk_begin[t] * LARS_WAVES, c1 = tb.chunk_begin[t + 1] * LARS_WAVES;
   double sw = 0.0, sg = 0.0;
   int bad = 0;
@@ -322,6 +327,27 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_finalize(Tables tb, float l
   }
 }
 
+// Dynamic loss scaling (Sections 4.1 and 5.3 name the loss scale; the policy is the usual skip / shrink / grow one).
+struct DynScale {
+  jz_loss_scale_state* st;  // nullptr: fixed loss scale
+  float growth, backoff;
+  int interval;
+  float lo, hi;
+};
+__device__ __forceinline__ void loss_scale_step(const DynScale& d, int overflow) {
+  float sc = d.st->scale;
+  int good = d.st->good_steps;
+  if (overflow) {
+    sc = fmaxf(sc * d.backoff, d.lo);
+    good = 0;
+  } else if (++good >= d.interval) {
+    sc = fminf(sc * d.growth, d.hi);
+    good = 0;
+  }
+  d.st->scale = sc;
+  d.st->good_steps = good;
+}
+
 __device__ __forceinline__ void lars_step(float& w, float& v, unsigned short gbits, float coef, float lam, float m,
                                           float inv_s, unsigned short& w16) {
   float g = half_bits_to_float(gbits) * inv_s;  // un-scale
@@ -336,7 +362,8 @@ __device__ __forceinline__ void lars_step(float& w, float& v, unsigned short gbi
 __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __restrict__ w, float* __restrict__ v,
                                                             const unsigned short* __restrict__ g16,
                                                             unsigned short* __restrict__ w16, float m, float wd,
-                                                            float inv_s, int* __restrict__ found_inf) {
+                                                            float inv_s, int* __restrict__ found_inf, DynScale dyn) {
+  if (dyn.st) inv_s = __int_as_float(tb.state[1]);  // written by lars_finalize (not used when there is no tensor)
   // the header, this workgroup's chunk record and the tensor flags are requested together; nothing read through the
   // tables is used before the header has been checked
   const int cidx = (int)blockIdx.x < tb.n_chunks ? tb.n_chunks - 1 - (int)blockIdx.x : 0;
@@ -351,6 +378,7 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *found_inf = f ? 1 : 0;
     tb.state[0] = 1;  // skipped or not, psum_w describes the master weights as this launch leaves them
+    if (dyn.st) loss_scale_step(dyn, f);  // no workgroup of this launch reads dyn.st->scale
   }
   if (f) return;  // overflow under loss scaling: the step is skipped as a whole
   if ((int)blockIdx.x >= tb.n_chunks) return;
@@ -415,6 +443,13 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   }
   sw = wave_sum(sw);
   if ((threadIdx.x & 63) == 0) tb.psum_w[c * LARS_WAVES + (threadIdx.x >> 6)] = sw;
+}
+
+__global__ void loss_scale_init(jz_loss_scale_state* __restrict__ st, float scale) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    st->scale = scale;
+    st->good_steps = 0;
+  }
 }
 
 Tables make_tables(const Layout& L, void* ws, uint64_t sum) {
@@ -493,13 +528,24 @@ extern "C" int jz_lars_prepare(const jz_param_set* ps, void* ws, size_t ws_bytes
   return JZ_OK;
 }
 
-extern "C" int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
-                                 size_t ws_bytes, void* hip_stream) {
+namespace {
+
+// the update with a fixed loss scale (state == nullptr: hp->loss_scale) or with a device-resident one that the
+// controller adjusts afterwards
+int lars_run(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* pol, jz_loss_scale_state* state,
+             int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream) {
   if (!hp || !found_inf_dev) return JZ_ERR_NULL;
   Layout L;
   int rc = make_layout(ps, &L);
   if (rc != JZ_OK) return rc;
-  if (!(hp->loss_scale > 0.0f) || !(hp->loss_scale < 3.0e38f)) return JZ_ERR_SHAPE;
+  if (!state && (!(hp->loss_scale > 0.0f) || !(hp->loss_scale < 3.0e38f))) return JZ_ERR_SHAPE;
+  if (state) {
+    if (!pol) return JZ_ERR_NULL;
+    if (!(pol->growth_factor >= 1.0f) || !(pol->backoff_factor > 0.0f) || !(pol->backoff_factor <= 1.0f) ||
+        pol->growth_interval < 1 || !(pol->min_scale > 0.0f) || !(pol->max_scale >= pol->min_scale) || !(pol->max_scale < 3.0e38f))
+      return JZ_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(state) & 7u) return JZ_ERR_ALIGN;
+  }
   if (L.P > 0 && (!ps->master_w || !ps->momentum || !ps->grad16 || !ps->weight16)) return JZ_ERR_NULL;
   if (!ws || ws_bytes < L.total) return JZ_ERR_WORKSPACE;
   if (!jz::aligned16(ws) || !jz::aligned16(ps->master_w) || !jz::aligned16(ps->momentum) ||
@@ -515,20 +561,51 @@ extern "C" int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* 
       if (jz::overlaps(bufs[i], lens[i], bufs[j], lens[j])) return JZ_ERR_ALIAS;
   }
   if (jz::overlaps(found_inf_dev, sizeof(int), ws, L.total)) return JZ_ERR_ALIAS;
+  if (state) {
+    if (jz::overlaps(state, sizeof(*state), ws, L.total) || jz::overlaps(state, sizeof(*state), found_inf_dev, sizeof(int)))
+      return JZ_ERR_ALIAS;
+    for (int i = 0; i < 4; ++i)
+      if (jz::overlaps(bufs[i], lens[i], state, sizeof(*state))) return JZ_ERR_ALIAS;
+  }
   uint64_t sum = table_checksum(ps);
   if (!is_prepared(ws, sum)) return JZ_ERR_NOT_PREPARED;
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   Tables tb = make_tables(L, ws, sum);
   const unsigned short* g16 = static_cast<const unsigned short*>(ps->grad16);
+  const float* scale_dev = state ? &state->scale : nullptr;
+  DynScale dyn{state, 1.0f, 1.0f, 1, 1.0f, 1.0f};
+  if (state) dyn = DynScale{state, pol->growth_factor, pol->backoff_factor, pol->growth_interval, pol->min_scale, pol->max_scale};
   if (L.n_chunks > 0)
     hipLaunchKernelGGL(lars_reduce, dim3((unsigned)L.n_chunks), dim3(LARS_THREADS), 0, st, tb, ps->master_w, g16);
   if (L.T > 0)
     hipLaunchKernelGGL(lars_finalize, dim3((unsigned)L.T), dim3(LARS_THREADS), 0, st, tb, hp->lr, hp->trust_coef,
-                       hp->loss_scale);
+                       state ? 1.0f : hp->loss_scale, scale_dev);
   // at least one workgroup so that the flag is always written
   hipLaunchKernelGGL(lars_update, dim3((unsigned)(L.n_chunks > 0 ? L.n_chunks : 1)), dim3(LARS_THREADS), 0, st, tb,
                      ps->master_w, ps->momentum, g16, static_cast<unsigned short*>(ps->weight16), hp->momentum,
-                     hp->weight_decay, 1.0f / hp->loss_scale, found_inf_dev);
+                     hp->weight_decay, state ? 1.0f : 1.0f / hp->loss_scale, found_inf_dev, dyn);
+  return jz::launch_status();
+}
+
+}  // namespace
+
+extern "C" int jz_lars_mp_update(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
+                                 size_t ws_bytes, void* hip_stream) {
+  return lars_run(ps, hp, nullptr, nullptr, found_inf_dev, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* policy,
+                                     jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes,
+                                     void* hip_stream) {
+  if (!state_dev) return JZ_ERR_NULL;
+  return lars_run(ps, hp, policy, state_dev, found_inf_dev, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int jz_loss_scale_init(jz_loss_scale_state* state_dev, float initial_scale, void* hip_stream) {
+  if (!state_dev) return JZ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(state_dev) & 7u) return JZ_ERR_ALIGN;
+  if (!(initial_scale > 0.0f) || !(initial_scale < 3.0e38f)) return JZ_ERR_SHAPE;
+  hipLaunchKernelGGL(loss_scale_init, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), state_dev, initial_scale);
   return jz::launch_status();
 }

@@ -1,0 +1,178 @@
+"""GPU parity of the dynamic loss-scale path (jz_loss_scale_init + jz_lars_mp_update_dyn, through the C ABI) against
+the oracle chain: oracle.lars_mp_update with the current scale, then oracle.loss_scale_step with its overflow flag."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1807_11205_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jz():
+    from paper_1807_11205_amd import api
+    api.lib()
+    assert torch.cuda.is_available()
+    return api
+
+
+class DynRun:
+    def __init__(self, api, ps, initial_scale, **policy):
+        import jzt
+        self.api, self.r = api, jzt.LarsRun(ps)
+        self.state = torch.zeros(2, dtype=torch.int32, device="cuda")
+        self.policy_kw = policy
+        self.policy = api.loss_scale_policy(**policy)
+        api.jz_loss_scale_init(self.state, initial_scale)
+
+    def step(self, **over):
+        api, r = self.api, self.r
+        hp = dict(inputs.HPARAMS)
+        hp.update(over)
+        # the loss_scale field is ignored by the dynamic entry point: a wrong value here must not matter
+        api.jz_lars_mp_update_dyn(r.ps, api.lars_hparams(hp["lr"], hp["momentum"], hp["weight_decay"], hp["trust_coef"], 3.0),
+                                  self.policy, self.state, r.flag, r.ws)
+        torch.cuda.synchronize()
+        return r.w.cpu().numpy(), r.v.cpu().numpy(), r.w16.cpu().numpy(), int(r.flag.item())
+
+
+def run_chain(api, sizes, flags, initial_scale, bad_steps, n_steps, seed, lr_of_step=None, **policy):
+    """n_steps updates; the gradient of step i is unit-scale noise times the CURRENT oracle scale (as a backward pass
+    that multiplies its loss gradient by S would produce), with an Inf planted at the steps in bad_steps."""
+    import jzt
+    ps = inputs.random_param_set((3, seed), sizes, loss_scale=initial_scale, flags=flags)
+    d = DynRun(api, ps, initial_scale, **policy)
+    scale, good = float(initial_scale), 0
+    trace = []
+    for i in range(n_steps):
+        assert api.loss_scale_state(d.state) == (scale, good), "state before step %d" % i
+        g = inputs.normal_f16(inputs.rng_for(3, seed, i), (ps.P,), std=1e-3).astype(np.float32) * np.float32(scale)
+        with np.errstate(over="ignore"):
+            g = g.astype(np.float16)
+        if i in bad_steps:
+            g[(i * 7919) % ps.P] = bad_steps[i]
+        ps.grad16 = g
+        d.r.g.copy_(torch.from_numpy(g))
+        over = {} if lr_of_step is None else dict(lr=lr_of_step(i))
+        got = d.step(**over)
+        out = jzt.check_lars_against_oracle(ps, got, loss_scale=scale, **over)
+        expect_flag = int(not np.all(np.isfinite(g.astype(np.float64))))
+        assert got[3] == expect_flag
+        scale, good = oracle.loss_scale_step(scale, good, got[3], **policy)
+        trace.append((scale, good))
+        if not out["flag"]:
+            ps.master_w, ps.momentum, ps.weight16 = got[0].copy(), got[1].copy(), got[2].copy()
+    assert api.loss_scale_state(d.state) == (scale, good)
+    return trace
+
+
+def test_shrink_on_overflow_and_grow_after_clean_steps(jz):
+    pol = dict(growth_factor=2.0, backoff_factor=0.5, growth_interval=3, min_scale=1.0, max_scale=65536.0)
+    tr = run_chain(jz, [70000, 64, 64, 4097], [3, 2, 2, 1], 1024.0, {1: np.inf, 2: np.nan, 7: -np.inf}, 10, 1, **pol)
+    # 1024 -> (ok) -> 512 -> 256 -> three clean -> 512 -> (ok) -> 256 -> (ok, ok)
+    assert [s for s, _ in tr] == [1024.0, 512.0, 256.0, 256.0, 256.0, 512.0, 512.0, 256.0, 256.0, 256.0]
+    assert [g for _, g in tr] == [1, 0, 0, 1, 2, 0, 1, 0, 1, 2]
+
+
+def test_scale_stays_inside_its_bounds(jz):
+    pol = dict(growth_factor=4.0, backoff_factor=0.25, growth_interval=1, min_scale=8.0, max_scale=100.0)
+    tr = run_chain(jz, [5000, 33], [3, 0], 16.0, {0: np.inf, 1: np.inf}, 5, 2, **pol)
+    assert [s for s, _ in tr] == [8.0, 8.0, 32.0, 100.0, 100.0]
+
+
+def test_factors_that_are_not_powers_of_two(jz):
+    pol = dict(growth_factor=1.5, backoff_factor=0.7, growth_interval=2, min_scale=1.0, max_scale=1e6)
+    run_chain(jz, [12345, 100], [3, 3], 1000.0, {2: np.nan}, 7, 3, **pol)
+
+
+def test_learning_rate_that_changes_every_step(jz):
+    """The learning rate is a per-call value, so a schedule is the caller's: linear warm-up over four steps, then a
+    polynomial decay, with an overflow in the middle (the skipped step consumes its schedule slot)."""
+    pol = dict(growth_factor=2.0, backoff_factor=0.5, growth_interval=4, min_scale=1.0, max_scale=65536.0)
+    lr = lambda i: 3.2 * (i + 1) / 4 if i < 4 else 3.2 * (1.0 - (i - 4) / 8.0) ** 2
+    run_chain(jz, [40000, 128, 128, 1000], [3, 2, 2, 3], 256.0, {5: np.inf}, 12, 8, lr_of_step=lr, **pol)
+
+
+def test_overflow_produced_by_the_scale_itself_is_caught_and_recovers(jz):
+    """A scale so large that the scaled FP16 gradient saturates: the steps are skipped and the scale halves until the
+    gradient fits again, after which updates go through."""
+    import jzt
+    pol = dict(growth_factor=2.0, backoff_factor=0.5, growth_interval=1000, min_scale=1.0, max_scale=2.0 ** 24)
+    ps = inputs.random_param_set((3, 4), [20000, 256], loss_scale=1.0, flags=[3, 2])
+    d = DynRun(jz, ps, 2.0 ** 22, **pol)
+    base = inputs.normal_f16(inputs.rng_for(3, 4, 99), (ps.P,), std=0.02).astype(np.float32)   # max about 0.09
+    scale, good, skipped_steps = 2.0 ** 22, 0, 0
+    for i in range(8):
+        with np.errstate(over="ignore"):
+            g = (base * np.float32(scale)).astype(np.float16)
+        ps.grad16 = g
+        d.r.g.copy_(torch.from_numpy(g))
+        got = d.step()
+        out = jzt.check_lars_against_oracle(ps, got, loss_scale=scale)
+        scale, good = oracle.loss_scale_step(scale, good, got[3], **pol)
+        skipped_steps += got[3]
+        assert jz.loss_scale_state(d.state) == (scale, good)
+        if not out["flag"]:
+            ps.master_w, ps.momentum, ps.weight16 = got[0].copy(), got[1].copy(), got[2].copy()
+    assert 2 <= skipped_steps <= 6 and good == 8 - skipped_steps and scale == 2.0 ** (22 - skipped_steps)
+
+
+def test_fixed_and_dynamic_entry_points_agree_bit_for_bit(jz):
+    import jzt
+    ps = inputs.random_param_set((3, 5), [30000, 77, 4096], loss_scale=512.0, flags=[3, 2, 1])
+    a = jzt.LarsRun(ps).step()
+    d = DynRun(jz, ps, 512.0)
+    b = d.step()
+    for x, y in zip(a[:3], b[:3]):
+        assert np.array_equal(jzt.bits(x) if x.dtype == np.float16 else x.view(np.uint32), jzt.bits(y) if y.dtype == np.float16 else y.view(np.uint32))
+    assert a[3] == b[3] == 0 and jz.loss_scale_state(d.state) == (512.0, 1)
+
+
+def test_overwritten_workspace_leaves_the_state_alone(jz):
+    """A workspace whose header was overwritten on the device: the kernels refuse (flag -1, nothing updated) and the
+    controller must not count that call as a step."""
+    ps = inputs.random_param_set((3, 6), [1000, 50], loss_scale=64.0)
+    d = DynRun(jz, ps, 64.0, growth_interval=1)
+    first = d.step()
+    assert first[3] == 0 and jz.loss_scale_state(d.state) == (128.0, 0)
+    d.r.ws.zero_()
+    again = d.step()
+    assert again[3] == -1 and jz.loss_scale_state(d.state) == (128.0, 0)
+    for x, y in zip(first[:3], again[:3]):
+        assert np.array_equal(x.view(np.uint16 if x.dtype == np.float16 else np.uint32),
+                              y.view(np.uint16 if y.dtype == np.float16 else np.uint32))
+
+
+def test_argument_errors(jz):
+    import jzt
+    ps = inputs.random_param_set((3, 7), [1000], loss_scale=64.0)
+    d = DynRun(jz, ps, 64.0)
+    L = jz.lib()
+    hp = jz.lars_hparams(0.1, 0.9, 1e-4, 0.001, 1.0)
+    sp, fp, wp, wn = d.state.data_ptr(), d.r.flag.data_ptr(), d.r.ws.data_ptr(), d.r.ws.numel()
+    c = ctypes.byref
+
+    def call(policy=d.policy, state=sp, flag=fp):
+        return L.jz_lars_mp_update_dyn(c(d.r.ps.c), c(hp), c(policy) if policy is not None else None, state, flag, wp, wn, None)
+
+    assert call(state=None) == jz.JZ_ERR_NULL
+    assert call(policy=None) == jz.JZ_ERR_NULL
+    assert call(state=sp + 4) == jz.JZ_ERR_ALIGN
+    assert call(state=d.r.w.data_ptr()) == jz.JZ_ERR_ALIAS
+    assert call(state=wp) == jz.JZ_ERR_ALIAS
+    for bad in (dict(growth_factor=0.5), dict(backoff_factor=0.0), dict(backoff_factor=1.5), dict(growth_interval=0),
+                dict(min_scale=0.0), dict(min_scale=4.0, max_scale=2.0), dict(max_scale=float("inf")),
+                dict(growth_factor=float("nan"))):
+        assert call(policy=jz.loss_scale_policy(**bad)) == jz.JZ_ERR_SHAPE, bad
+    assert L.jz_loss_scale_init(None, 1.0, None) == jz.JZ_ERR_NULL
+    assert L.jz_loss_scale_init(sp + 4, 1.0, None) == jz.JZ_ERR_ALIGN
+    for s in (0.0, -1.0, float("inf"), float("nan")):
+        assert L.jz_loss_scale_init(sp, s, None) == jz.JZ_ERR_SHAPE
+    torch.cuda.synchronize()
+    assert jz.loss_scale_state(d.state) == (64.0, 0)
+    assert call() == jz.JZ_OK
+    torch.cuda.synchronize()
