@@ -8,6 +8,7 @@ this package.  It shares nothing with the HIP library and never imports it.
   fp64 numpy (``lars.py``).
 * the dynamic loss-scale controller around that update (``loss_scale.py``).
 * batch normalization + ReLU (Section 4.2's formulas) and its gradient, fp64 numpy (``bn.py``).
+* the small layers between the convolutions (residual add, pooling, bias, softmax loss), fp64 numpy (``layers.py``).
 """
 import ctypes
 import os
@@ -15,6 +16,8 @@ import os
 import numpy as np
 
 from .bn import bn_relu_bwd, bn_relu_fwd  # noqa: F401
+from .layers import (add_fwd, avgpool_bwd, avgpool_fwd, bias_add, bias_grad, maxpool_bwd, maxpool_fwd, pool_out,  # noqa: F401
+                     relu_bwd, softmax_xent)
 from .lars import lars_mp_update, lars_trust_ratio  # noqa: F401
 from .loss_scale import loss_scale_step  # noqa: F401
 
