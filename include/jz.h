@@ -176,6 +176,38 @@ int jz_loss_scale_init(jz_loss_scale_state* state_dev, float initial_scale, void
 int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* policy,
                           jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* The small layers between the convolutions of a ResNet-style network (the paper trains stock ResNet-50 / AlexNet,
+ * Section 5, and does not restate them), on FP16 NHWC DEVICE tensors, the storage type Section 4.1 gives every forward
+ * and backward tensor.  Each is its textbook definition evaluated in FP32 with one rounding to FP16 on the store;
+ * element counts and channel counts must be multiples of 8, tensor pointers 16-byte aligned (JZ_ERR_SHAPE /
+ * JZ_ERR_ALIGN otherwise); nothing is allocated, everything is enqueued on hip_stream; empty inputs are JZ_OK.
+ *   jz_add_fwd      y = a + b, followed by max(., 0) when relu != 0 (the residual connection).  y may be a or b.
+ *   jz_relu_bwd     dx = dy where the forward output y is > 0, else 0.  dx may be dy.
+ *   jz_maxpool_fwd  x[N,H,W,C] -> y[N,P,Q,C], P = (H + 2 pad - window) / stride + 1 (same for Q); padding never wins.
+ *   jz_maxpool_bwd  dx[N,H,W,C] from x and dy[N,P,Q,C]: each dy goes to the first maximum of its window in (row, column)
+ *                   order; a position that wins several windows gets their sum (FP32, window order).  pad < window <= 16.
+ *   jz_avgpool_fwd  global average: x[N,HW,C] -> y[N,C] = sum over the HW positions (FP32, in order) / HW.
+ *   jz_avgpool_bwd  dy[N,C] -> dx[N,HW,C] = dy / HW at every position.
+ *   jz_bias_add     out[rows,C] = y[rows,C] + b[C].  out may be y.
+ *   jz_bias_grad    db[C] = sum over rows of dy[rows,C] (FP32, fixed order: deterministic).  Meant for a fully connected
+ *                   layer's bias (rows = batch size); it uses C/32 workgroups whatever rows is.
+ *   jz_softmax_xent_bwd  z[rows,classes] FP16 logits, labels_dev[rows] int32 (DEVICE): loss_dev[n] = log(sum_j exp z_nj) -
+ *                   z_n,label (FP32, DEVICE) and dz = S * (softmax(z_n) - onehot(label_n)) / rows in FP16, the gradient of the
+ *                   batch-mean loss times the loss scale S of Section 4.1.  S is state_dev->scale when state_dev (DEVICE,
+ *                   as in jz_lars_mp_update_dyn) is not NULL, else loss_scale.  A label outside [0, classes) gives a NaN loss
+ *                   and a zero gradient row.  classes need not be a multiple of 8 here (2-byte alignment suffices). */
+int jz_add_fwd(int64_t n, const void* a16, const void* b16, int relu, void* y16, void* hip_stream);
+int jz_relu_bwd(int64_t n, const void* y16, const void* dy16, void* dx16, void* hip_stream);
+int jz_maxpool_fwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, void* y16, void* hip_stream);
+int jz_maxpool_bwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, const void* dy16, void* dx16,
+                   void* hip_stream);
+int jz_avgpool_fwd(int N, int HW, int C, const void* x16, void* y16, void* hip_stream);
+int jz_avgpool_bwd(int N, int HW, int C, const void* dy16, void* dx16, void* hip_stream);
+int jz_bias_add(int64_t rows, int C, const void* y16, const void* b16, void* out16, void* hip_stream);
+int jz_bias_grad(int64_t rows, int C, const void* dy16, void* db16, void* hip_stream);
+int jz_softmax_xent_bwd(int rows, int classes, const void* z16, const int* labels_dev, float loss_scale,
+                        const jz_loss_scale_state* state_dev, void* dz16, float* loss_dev, void* hip_stream);
+
 /* Batch normalization in training mode with an optional ReLU behind it (Section 4.2 of the paper writes the layer as
  * x^ = (x - mean_B) / sqrt(var_B + eps), y = gamma * x^ + beta; mean_B and var_B are the mean and the plain (biased)
  * variance of the mini-batch, per channel, over all rows = N*H*W positions).  Not part of the convolution / LARS hot path

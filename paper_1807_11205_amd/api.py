@@ -23,6 +23,8 @@ EXPORTS = [
     "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
+    "jz_add_fwd", "jz_relu_bwd", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
+    "jz_bias_grad", "jz_softmax_xent_bwd",
     "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd",
     "jz_status_string", "jz_version",
 ]
@@ -96,6 +98,15 @@ def lib() -> ctypes.CDLL:
         L.jz_bn_workspace_bytes.argtypes = [i64, ci, ctypes.POINTER(sz)]
         L.jz_bn_relu_fwd.argtypes = [i64, ci, vp, vp, vp, cf, ci, vp, vp, vp, vp, sz, vp]
         L.jz_bn_relu_bwd.argtypes = [i64, ci, vp, vp, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
+        L.jz_add_fwd.argtypes = [i64, vp, vp, ci, vp, vp]
+        L.jz_relu_bwd.argtypes = [i64, vp, vp, vp, vp]
+        L.jz_maxpool_fwd.argtypes = [ci] * 7 + [vp, vp, vp]
+        L.jz_maxpool_bwd.argtypes = [ci] * 7 + [vp, vp, vp, vp]
+        L.jz_avgpool_fwd.argtypes = [ci, ci, ci, vp, vp, vp]
+        L.jz_avgpool_bwd.argtypes = [ci, ci, ci, vp, vp, vp]
+        L.jz_bias_add.argtypes = [i64, ci, vp, vp, vp, vp]
+        L.jz_bias_grad.argtypes = [i64, ci, vp, vp, vp]
+        L.jz_softmax_xent_bwd.argtypes = [ci, ci, vp, vp, cf, vp, vp, vp, vp]
         L.jz_status_string.argtypes = [ci]
         L.jz_status_string.restype = ctypes.c_char_p
         L.jz_version.argtypes = []
@@ -345,3 +356,60 @@ def jz_lars_mp_update_dyn(ps: ParamSet, hp: jz_lars_hparams, policy: jz_loss_sca
 
 def lars_hparams(lr, momentum, weight_decay, trust_coef, loss_scale) -> jz_lars_hparams:
     return jz_lars_hparams(lr, momentum, weight_decay, trust_coef, loss_scale)
+
+
+# ---------------------------------------------------------------------------------------------
+# the small layers between the convolutions (FP16 NHWC tensors; marshalling only)
+# ---------------------------------------------------------------------------------------------
+def _h(t: torch.Tensor, n: int, what: str) -> int:
+    return _dev_ptr(t, torch.float16, n, what)
+
+
+def jz_add_fwd(a, b, y, relu=True, stream=None):
+    n = a.numel()
+    _check(lib().jz_add_fwd(n, _h(a, n, "a"), _h(b, n, "b"), int(bool(relu)), _h(y, n, "y"), _stream(stream)), "jz_add_fwd")
+
+
+def jz_relu_bwd(y, dy, dx, stream=None):
+    n = y.numel()
+    _check(lib().jz_relu_bwd(n, _h(y, n, "y"), _h(dy, n, "dy"), _h(dx, n, "dx"), _stream(stream)), "jz_relu_bwd")
+
+
+def pool_out(size, window, stride, pad):
+    return (size + 2 * pad - window) // stride + 1
+
+
+def jz_maxpool_fwd(N, H, W, C, window, stride, pad, x, y, stream=None):
+    P, Q = pool_out(H, window, stride, pad), pool_out(W, window, stride, pad)
+    _check(lib().jz_maxpool_fwd(N, H, W, C, window, stride, pad, _h(x, N * H * W * C, "x"), _h(y, N * P * Q * C, "y"),
+                                _stream(stream)), "jz_maxpool_fwd")
+
+
+def jz_maxpool_bwd(N, H, W, C, window, stride, pad, x, dy, dx, stream=None):
+    P, Q = pool_out(H, window, stride, pad), pool_out(W, window, stride, pad)
+    _check(lib().jz_maxpool_bwd(N, H, W, C, window, stride, pad, _h(x, N * H * W * C, "x"), _h(dy, N * P * Q * C, "dy"),
+                                _h(dx, N * H * W * C, "dx"), _stream(stream)), "jz_maxpool_bwd")
+
+
+def jz_avgpool_fwd(N, HW, C, x, y, stream=None):
+    _check(lib().jz_avgpool_fwd(N, HW, C, _h(x, N * HW * C, "x"), _h(y, N * C, "y"), _stream(stream)), "jz_avgpool_fwd")
+
+
+def jz_avgpool_bwd(N, HW, C, dy, dx, stream=None):
+    _check(lib().jz_avgpool_bwd(N, HW, C, _h(dy, N * C, "dy"), _h(dx, N * HW * C, "dx"), _stream(stream)), "jz_avgpool_bwd")
+
+
+def jz_bias_add(rows, C, y, b, out, stream=None):
+    _check(lib().jz_bias_add(rows, C, _h(y, rows * C, "y"), _h(b, C, "b"), _h(out, rows * C, "out"), _stream(stream)), "jz_bias_add")
+
+
+def jz_bias_grad(rows, C, dy, db, stream=None):
+    _check(lib().jz_bias_grad(rows, C, _h(dy, rows * C, "dy"), _h(db, C, "db"), _stream(stream)), "jz_bias_grad")
+
+
+def jz_softmax_xent_bwd(rows, classes, z, labels, dz, loss, loss_scale=1.0, state=None, stream=None):
+    if not labels.is_cuda or labels.dtype != torch.int32 or labels.numel() != rows or not labels.is_contiguous():
+        raise TypeError("labels must be a contiguous int32 GPU tensor with one entry per row")
+    _check(lib().jz_softmax_xent_bwd(rows, classes, _h(z, rows * classes, "z"), labels.data_ptr(), float(loss_scale),
+                                     _ls_state(state) if state is not None else None, _h(dz, rows * classes, "dz"),
+                                     _dev_ptr(loss, torch.float32, rows, "loss"), _stream(stream)), "jz_softmax_xent_bwd")
