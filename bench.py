@@ -409,6 +409,53 @@ def bn_workload(args):
                      "bytes_per_element": 12}}))
 
 
+def chain_workload(args):
+    """One complete, chained training step of ResNet-50 v1 (every tensor produced by the launch before it): forward with
+    training-mode batch normalization, ReLU, pooling and residual adds, softmax cross-entropy gradient times the loss
+    scale, backward into the fused FP16 gradient buffer, LARS update with the dynamic loss scale on the device.  One
+    stream, eager launches, the same fixed synthetic batch every step."""
+    from paper_1807_11205_amd import resnet50
+    net = resnet50.ResNet50Chain(batch=args.batch, image=224, initial_loss_scale=65536.0,
+                                 policy=dict(growth_interval=1 << 30, max_scale=2.0 ** 24))
+    skipped = 0
+    for _ in range(24):                                   # let the controller bring the scale down until steps go through
+        net.step()
+        torch.cuda.synchronize()
+        if int(net.found_inf.item()) == 0:
+            break
+        skipped += 1
+    assert int(net.found_inf.item()) == 0, "the loss scale did not settle"
+    for _ in range(max(args.warmup, 1)):
+        net.step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e in ev:
+        e[0].record(); net.forward(); e[1].record(); net.backward(); e[2].record(); net.update(); e[3].record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert int(net.found_inf.item()) == 0
+    ph = [float(np.mean([e[i].elapsed_time(e[i + 1]) for e in ev])) for i in range(3)]
+    gpu_ms = float(np.mean([e[0].elapsed_time(e[3]) for e in ev]))
+    tflops = net.flops_per_step() / (gpu_ms * 1e-3) / 1e12
+    kinds = {}
+    for op in net.trace:
+        kinds[op.kind] = kinds.get(op.kind, 0) + 1
+    print(json.dumps({
+        "metric": "ResNet-50 N=%d chained training step images/s" % args.batch, "value": args.batch / (ms * 1e-3), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 storage, f32 accumulate, f32 master weights", "data": "synthetic",
+        "config": {"workload": "ResNet-50 v1 chained step: conv + batch norm + ReLU + pooling + residual adds + classifier + "
+                               "softmax loss gradient, backward, LARS with dynamic loss scale", "batch": args.batch, "image": 224,
+                   "launch": "eager", "streams": 1, "launches_per_step": len(net.trace), "launches_by_kind": kinds,
+                   "loss_scale": api.loss_scale_state(net.ls_state)[0], "steps_skipped_while_the_scale_settled": skipped,
+                   "mean_loss": net.mean_loss()},
+        "phases_ms": {"forward_and_loss": ph[0], "backward": ph[1], "lars_update": ph[2], "gpu_total": gpu_ms},
+        "roofline": {"kernel": "whole step (GEMM flops of the convolutions and the classifier over the step's GPU time)",
+                     "bound": "mfma", "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None}}))
+
+
 def cpu_baseline(sample_batch=8):
     """The fp64 oracle, as it stands, on the host cores: the same 53-conv + FC stack at a small batch, plus LARS."""
     import oracle
@@ -447,9 +494,10 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=None, help="default: 64 (resnet50), 128 (alexnet)")
-    ap.add_argument("--workload", default="resnet50", choices=("resnet50", "alexnet", "bn"),
+    ap.add_argument("--workload", default="resnet50", choices=("resnet50", "alexnet", "bn", "chain"),
                     help="resnet50: the full step the headline metric is quoted on; alexnet: the AlexNet-shaped layers of configs[3]; "
-                         "bn: the batch-normalization + ReLU layers of ResNet-50 (not part of the headline step)")
+                         "bn: the batch-normalization + ReLU layers of ResNet-50 (not part of the headline step); chain: a complete chained "
+                         "ResNet-50 training step with every layer between the convolutions (not the headline step either)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
     ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
@@ -481,6 +529,9 @@ def main():
         return
     if args.workload == "bn":
         bn_workload(args)
+        return
+    if args.workload == "chain":
+        chain_workload(args)
         return
     wl = ResNet50Step(batch=args.batch)
 

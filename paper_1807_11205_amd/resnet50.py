@@ -1,0 +1,237 @@
+"""A chained ResNet-50 training step as a sequence of libjz calls (sequencing and buffer bookkeeping only: every
+arithmetic step runs in the library's kernels).
+
+One step = forward through the 53 convolutions with training-mode batch normalization (+ ReLU), the stem max pool,
+the residual adds, the global average pool and the classifier; softmax cross-entropy gradient times the loss scale
+(Section 4.1 of Jia et al. 2018); backward through all of it into the fused FP16 gradient buffer; the mixed-precision
+LARS update with the device-resident dynamic loss scale.  The network is the stock ResNet-50 the paper trains
+(Table 3); gamma, beta and the bias are exempt from weight decay (Section 4.2) through the parameter flags.
+
+Every intermediate tensor has a buffer of its own and every launch is recorded in `self.trace` with the tensors it
+read and wrote, so that a test can check each launch against an independent implementation on the inputs that launch
+actually saw.
+"""
+from typing import List
+
+import numpy as np
+import torch
+
+from . import api, inputs, shapes
+
+BN_EPS = 1e-5
+
+
+class Op:
+    """One library call of the step: what it is, the tensors it reads and writes, and the launch itself."""
+
+    __slots__ = ("kind", "name", "params", "ins", "outs", "call")
+
+    def __init__(self, kind, name, params, ins, outs, call):
+        self.kind, self.name, self.params, self.ins, self.outs, self.call = kind, name, params, ins, outs, call
+
+
+class ResNet50Chain:
+    def __init__(self, batch=64, image=224, variant="v1", seed=180711205, initial_loss_scale=1024.0, hparams=None,
+                 policy=None, device="cuda:0"):
+        self.N, self.image, self.device = int(batch), int(image), torch.device(device)
+        self.convs = shapes.resnet50_convs(variant, image)
+        self.fc = shapes.RESNET50_FC
+        self.hp = dict(inputs.HPARAMS)
+        self.hp.update(hparams or {})
+        h, f = torch.float16, torch.float32
+        dev = self.device
+
+        # parameters: FP32 master weights, momentum, FP16 working copy and FP16 gradients, one fused buffer each
+        host = inputs.resnet50_param_set(loss_scale=1.0, seed_key=(seed % 1000003,), variant=variant)
+        self.tensors = shapes.resnet50_param_tensors(variant)
+        self.offsets = [int(o) for o in host.offsets]
+        self.flags = [int(x) for x in host.flags]
+        self.master = torch.from_numpy(host.master_w).to(dev)
+        self.momentum = torch.zeros_like(self.master)
+        self.w16 = self.master.to(h)
+        self.grad = torch.zeros(self.master.numel(), dtype=h, device=dev)
+        self.index = {name: i for i, (name, _, _, _) in enumerate(self.tensors)}
+        self.ps = api.ParamSet(self.offsets, self.flags, self.master, self.momentum, self.grad, self.w16)
+        self.lars_ws = torch.zeros(max(api.jz_lars_workspace_bytes(self.ps), 16), dtype=torch.uint8, device=dev)
+        api.jz_lars_prepare(self.ps, self.lars_ws)
+        self.found_inf = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.ls_state = torch.zeros(2, dtype=torch.int32, device=dev)
+        self.policy = api.loss_scale_policy(**(policy or {}))
+        api.jz_loss_scale_init(self.ls_state, initial_loss_scale)
+
+        # data: a fixed synthetic batch
+        g = torch.Generator(device="cpu").manual_seed(seed)
+        self.x = torch.randn(self.N * image * image * 3, generator=g, dtype=f).to(h).to(dev)
+        self.labels = torch.randint(0, self.fc.O, (self.N,), generator=g, dtype=torch.int32).to(dev)
+        self.loss = torch.zeros(self.N, dtype=f, device=dev)
+
+        self._ws_bytes = 16
+        self._pending_ws = []
+        self.fwd_ops: List[Op] = []
+        self.bwd_ops: List[Op] = []
+        self._build()
+        self.ws = torch.zeros(self._ws_bytes, dtype=torch.uint8, device=dev)
+        for bind in self._pending_ws:
+            bind(self.ws)
+        self.trace = self.fwd_ops + self.bwd_ops + [self._lars_op()]
+
+    # ---- buffers and parameter views --------------------------------------------------------------------------------
+    def _buf(self, n, dtype=torch.float16):
+        return torch.zeros(int(n), dtype=dtype, device=self.device)
+
+    def _param(self, buf, name):
+        i = self.index[name]
+        return buf[self.offsets[i]:self.offsets[i + 1]]
+
+    # ---- op constructors ---------------------------------------------------------------------------------------------
+    def _later(self, make):
+        """Calls that need the shared workspace are bound once its size is known."""
+        box = {}
+        self._pending_ws.append(lambda ws: box.__setitem__("call", make(ws)))
+        return lambda stream=None: box["call"](stream)
+
+    def _conv(self, op, cs, a, b, out, name):
+        d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+        self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
+        kind = {api.JZ_FWD: "conv_fwd", api.JZ_BWD_DATA: "conv_bwd_data", api.JZ_BWD_WEIGHT: "conv_bwd_weight"}[op]
+        return Op(kind, name, dict(desc=d), [a, b], [out], self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, ws)))
+
+    def _fc(self, mode, a, b, out, name):
+        B, I, O = self.N, self.fc.I, self.fc.O
+        self._ws_bytes = max(self._ws_bytes, api.jz_gemm_fc_workspace_bytes(mode, B, I, O))
+        kind = {api.JZ_FWD: "fc_fwd", api.JZ_BWD_DATA: "fc_bwd_data", api.JZ_BWD_WEIGHT: "fc_bwd_weight"}[mode]
+        return Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)))
+
+    def _bn_fwd(self, cs, x, y, relu, name):
+        rows, C = self.N * cs.P * cs.P, cs.K
+        gamma, beta = self._param(self.master, cs.name + ".gamma"), self._param(self.master, cs.name + ".beta")
+        mean, invstd = self._buf(C, torch.float32), self._buf(C, torch.float32)
+        self._ws_bytes = max(self._ws_bytes, api.jz_bn_workspace_bytes(rows, C))
+        call = lambda stream=None: api.jz_bn_relu_fwd(rows, C, x, gamma, beta, BN_EPS, relu, y, mean, invstd, self.ws, stream)
+        return Op("bn_fwd", name, dict(rows=rows, C=C, relu=relu, eps=BN_EPS), [x, gamma, beta], [y, mean, invstd], call), mean, invstd
+
+    def _bn_bwd(self, cs, x, y, dy, mean, invstd, dx, relu, name):
+        rows, C = self.N * cs.P * cs.P, cs.K
+        gamma = self._param(self.master, cs.name + ".gamma")
+        dgamma, dbeta = self._param(self.grad, cs.name + ".gamma"), self._param(self.grad, cs.name + ".beta")
+        call = lambda stream=None: api.jz_bn_relu_bwd(rows, C, x, y if relu else None, dy, gamma, mean, invstd, relu, dx, dgamma, dbeta,
+                                                      self.ws, stream)
+        return Op("bn_bwd", name, dict(rows=rows, C=C, relu=relu), [x, y, dy, gamma, mean, invstd], [dx, dgamma, dbeta], call)
+
+    # ---- the network -------------------------------------------------------------------------------------------------
+    def _build(self):
+        N, F = self.N, self.fwd_ops
+        segments = []                            # backward ops per network segment, each list in execution order
+        by_name = {cs.name: cs for cs in self.convs}
+        W = lambda cs: self._param(self.w16, cs.name + ".w")
+        DW = lambda cs: self._param(self.grad, cs.name + ".w")
+
+        def conv_bn(cs, x_in, dx_in, relu, dz=None):
+            """conv -> batch norm (-> ReLU), appended to the forward list.  Returns (z, dz, back): the output, the buffer
+            the consumer of z writes z's gradient to, and this pair's backward ops in execution order.  dx_in is where
+            the gradient with respect to x_in goes (None for the first layer)."""
+            n_out = N * cs.P * cs.P * cs.K
+            c, z, dc = self._buf(n_out), self._buf(n_out), self._buf(n_out)
+            dz = self._buf(n_out) if dz is None else dz
+            F.append(self._conv(api.JZ_FWD, cs, x_in, W(cs), c, cs.name))
+            op, mean, invstd = self._bn_fwd(cs, c, z, relu, cs.name + ".bn")
+            F.append(op)
+            back = [self._bn_bwd(cs, c, z if relu else None, dz, mean, invstd, dc, relu, cs.name + ".bn"),
+                    self._conv(api.JZ_BWD_WEIGHT, cs, x_in, dc, DW(cs), cs.name)]
+            if dx_in is not None:
+                back.append(self._conv(api.JZ_BWD_DATA, cs, dc, W(cs), dx_in, cs.name))
+            return z, dz, back
+
+        def add_op(name, a, b, out, relu):
+            return Op("add_fwd", name, dict(relu=relu), [a, b], [out], lambda stream=None: api.jz_add_fwd(a, b, out, relu, stream))
+
+        stem = self.convs[0]
+        a0, da0, back_stem = conv_bn(stem, self.x, None, True)
+        Hp = stem.P
+        Hq = api.pool_out(Hp, 3, 2, 1)
+        pool = dict(N=N, H=Hp, W=Hp, C=64, window=3, stride=2, pad=1)
+        cur, dcur = self._buf(N * Hq * Hq * 64), self._buf(N * Hq * Hq * 64)
+        F.append(Op("maxpool_fwd", "pool1", pool, [a0], [cur],
+                    lambda stream=None, y=cur: api.jz_maxpool_fwd(N, Hp, Hp, 64, 3, 2, 1, a0, y, stream)))
+        segments.append([Op("maxpool_bwd", "pool1", pool, [a0, dcur], [da0],
+                            lambda stream=None, dy=dcur: api.jz_maxpool_bwd(N, Hp, Hp, 64, 3, 2, 1, a0, dy, da0, stream))] + back_stem)
+
+        blocks = sorted({cs.name[:-1] for cs in self.convs[1:]}, key=lambda n: (int(n[1]), int(n[3:])))
+        for nm in blocks:
+            a, b, c = by_name[nm + "a"], by_name[nm + "b"], by_name[nm + "c"]
+            p = by_name.get(nm + "p")
+            x_in, dx_out = cur, dcur                       # dx_out: gradient of the block input, read by the segment below
+            dxa = self._buf(x_in.numel())                  # branch a's contribution to it
+            n_out = N * c.P * c.P * c.K
+            ds = self._buf(n_out)                          # gradient of the sum in front of the block's last ReLU
+            za, dza, back_a = conv_bn(a, x_in, dxa, True)
+            zb, dzb, back_b = conv_bn(b, za, dza, True)
+            zc, _, back_c = conv_bn(c, zb, dzb, False, dz=ds)
+            if p is not None:
+                dxp = self._buf(x_in.numel())
+                shortcut, _, back_p = conv_bn(p, x_in, dxp, False, dz=ds)
+                dshort = dxp
+            else:
+                shortcut, back_p, dshort = x_in, [], ds
+            out, dout = self._buf(n_out), self._buf(n_out)
+            F.append(add_op(nm + ".add", zc, shortcut, out, True))
+            relu_b = Op("relu_bwd", nm + ".add", {}, [out, dout], [ds],
+                        lambda stream=None, y=out, dy=dout, dx=ds: api.jz_relu_bwd(y, dy, dx, stream))
+            segments.append([relu_b] + back_c + back_b + back_a + back_p + [add_op(nm + ".dx", dxa, dshort, dx_out, False)])
+            cur, dcur = out, dout
+
+        last = by_name[blocks[-1] + "c"]
+        HW, C = last.P * last.P, last.K
+        pooled, dpooled = self._buf(N * C), self._buf(N * C)
+        F.append(Op("avgpool_fwd", "pool5", dict(N=N, HW=HW, C=C), [cur], [pooled],
+                    lambda stream=None, x=cur: api.jz_avgpool_fwd(N, HW, C, x, pooled, stream)))
+        O = self.fc.O
+        fw, fb = self._param(self.w16, "fc.w"), self._param(self.w16, "fc.b")
+        dfw, dfb = self._param(self.grad, "fc.w"), self._param(self.grad, "fc.b")
+        raw, self.logits, self.dlogits = self._buf(N * O), self._buf(N * O), self._buf(N * O)
+        F.append(self._fc(api.JZ_FWD, pooled, fw, raw, "fc"))
+        F.append(Op("bias_add", "fc.b", dict(rows=N, C=O), [raw, fb], [self.logits],
+                    lambda stream=None: api.jz_bias_add(N, O, raw, fb, self.logits, stream)))
+        F.append(Op("softmax_xent", "loss", dict(rows=N, classes=O), [self.logits, self.labels, self.ls_state], [self.dlogits, self.loss],
+                    lambda stream=None: api.jz_softmax_xent_bwd(N, O, self.logits, self.labels, self.dlogits, self.loss,
+                                                                state=self.ls_state, stream=stream)))
+        segments.append([Op("bias_grad", "fc.b", dict(rows=N, C=O), [self.dlogits], [dfb],
+                            lambda stream=None: api.jz_bias_grad(N, O, self.dlogits, dfb, stream)),
+                         self._fc(api.JZ_BWD_WEIGHT, self.dlogits, pooled, dfw, "fc"),
+                         self._fc(api.JZ_BWD_DATA, self.dlogits, fw, dpooled, "fc"),
+                         Op("avgpool_bwd", "pool5", dict(N=N, HW=HW, C=C), [dpooled], [dcur],
+                            lambda stream=None, dx=dcur: api.jz_avgpool_bwd(N, HW, C, dpooled, dx, stream))])
+        for seg in reversed(segments):
+            self.bwd_ops.extend(seg)
+
+    def _lars_op(self):
+        hp = api.lars_hparams(self.hp["lr"], self.hp["momentum"], self.hp["weight_decay"], self.hp["trust_coef"], 1.0)
+        call = lambda stream=None: api.jz_lars_mp_update_dyn(self.ps, hp, self.policy, self.ls_state, self.found_inf, self.lars_ws, stream)
+        return Op("lars_dyn", "update", dict(hp=dict(self.hp)), [self.master, self.momentum, self.grad, self.w16, self.ls_state],
+                  [self.master, self.momentum, self.w16, self.found_inf, self.ls_state], call)
+
+    # ---- running -----------------------------------------------------------------------------------------------------
+    def forward(self, stream=None):
+        for op in self.fwd_ops:
+            op.call(stream)
+
+    def backward(self, stream=None):
+        for op in self.bwd_ops:
+            op.call(stream)
+
+    def update(self, stream=None):
+        self.trace[-1].call(stream)
+
+    def step(self, stream=None):
+        for op in self.trace:
+            op.call(stream)
+
+    def mean_loss(self) -> float:
+        torch.cuda.synchronize()
+        return float(self.loss.double().mean().item())
+
+    def flops_per_step(self) -> float:
+        """Multiply-adds x 2 of the convolution / classifier GEMMs: forward, backward-data (not for the first layer) and
+        backward-weight."""
+        macs = sum(cs.macs(self.N) * (2 if cs.first else 3) for cs in self.convs) + 3 * self.fc.macs(self.N)
+        return 2.0 * macs

@@ -43,17 +43,18 @@ class FcShape:
         return self.I * self.O
 
 
-def resnet50_convs(variant: str = "v1") -> List[ConvShape]:
+def resnet50_convs(variant: str = "v1", image: int = 224) -> List[ConvShape]:
     """The 53 convolutions of ResNet-50 in forward order.
 
     v1 (He et al. 2016, the network the paper cites) puts the stride-2 step of
     stages 3-5 on the first 1x1 of the first bottleneck; "v1.5" moves it to
     the 3x3.  Each bottleneck lists a (1x1), b (3x3), c (1x1), then the 1x1
-    projection shortcut when the block has one.
+    projection shortcut when the block has one.  image (a multiple of 32) is the
+    input height = width; the paper's is 224, smaller ones serve tests.
     """
-    assert variant in ("v1", "v1.5")
-    L = [ConvShape("stem", 224, 3, 64, 7, 2, 3, first=True)]
-    h, cin = 56, 64   # after the 3x3/2 max-pool
+    assert variant in ("v1", "v1.5") and image % 32 == 0 and image >= 32
+    L = [ConvShape("stem", image, 3, 64, 7, 2, 3, first=True)]
+    h, cin = image // 4, 64   # after the 3x3/2 max-pool
     for stage, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3)), start=2):
         cout = 4 * width
         for b in range(blocks):

@@ -1,0 +1,155 @@
+"""The chained ResNet-50 step (paper_1807_11205_amd/resnet50.py: forward, loss gradient, backward, LARS update with the
+dynamic loss scale, every tensor produced by the launch before it) against the oracle, launch by launch: each launch's
+outputs are compared with the oracle evaluated on the inputs that launch actually read on the GPU, with the bar of
+that operation's own parity test.  Small image and batch so that the fp64 oracle finishes in seconds; the network,
+its 161 parameter tensors and the order of the launches are those of the full-size step."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1807_11205_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jz():
+    from paper_1807_11205_amd import api
+    api.lib()
+    assert torch.cuda.is_available()
+    return api
+
+
+def np16(t):
+    return t.detach().cpu().numpy()
+
+
+def rel_l2(got, ref):
+    got, ref = np.asarray(got, np.float64).ravel(), np.asarray(ref, np.float64).ravel()
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
+
+
+def one_step_of_fp16(got16, ref64, ref16, what):
+    g, r16 = got16.ravel(), np.asarray(ref16).ravel()
+    diff = np.nonzero(g.view(np.uint16) != r16.view(np.uint16))[0]
+    if diff.size:
+        up, dn = np.nextafter(r16[diff], np.float16(np.inf)), np.nextafter(r16[diff], np.float16(-np.inf))
+        assert np.all((g[diff] == up) | (g[diff] == dn)), what
+    assert diff.size <= 0.01 * g.size + 2, what
+    assert rel_l2(g, ref64) <= 1e-3, what
+
+
+def check_op(op, counts):
+    import jzt
+    k, p = op.kind, op.params
+    what = "%s %s" % (k, op.name)
+    ins = [None if t is None else np16(t) for t in op.ins]
+    outs = [np16(t) for t in op.outs]
+    counts[k] = counts.get(k, 0) + 1
+    if k.startswith("conv_"):
+        d = p["desc"]
+        od = oracle.conv_desc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
+        fn = {"conv_fwd": oracle.conv_fwd, "conv_bwd_data": oracle.conv_bwd_data, "conv_bwd_weight": oracle.conv_bwd_weight}[k]
+        jzt.check_half_output(outs[0], fn(od, ins[0], ins[1]), tol=1e-3, what=what)
+    elif k.startswith("fc_"):
+        fn = {"fc_fwd": oracle.fc_fwd, "fc_bwd_data": oracle.fc_bwd_data, "fc_bwd_weight": oracle.fc_bwd_weight}[k]
+        jzt.check_half_output(outs[0], fn(p["B"], p["I"], p["O"], ins[0], ins[1]), tol=1e-3, what=what)
+    elif k == "bn_fwd":
+        rows, C = p["rows"], p["C"]
+        y64, _, m64, i64 = oracle.bn_relu_fwd(ins[0].reshape(rows, C), ins[1], ins[2], p["eps"], relu=p["relu"])
+        assert np.all(np.abs(outs[1] - m64) <= 1e-5 * (np.abs(m64) + 1.0 / i64)), what
+        assert np.all(np.abs(outs[2] - i64) <= 1e-4 * i64), what
+        assert rel_l2(outs[0], y64) <= 1e-3, what
+    elif k == "bn_bwd":
+        rows, C = p["rows"], p["C"]
+        x, dy = ins[0].reshape(rows, C), ins[2].reshape(rows, C)
+        y = ins[1].reshape(rows, C) if p["relu"] else None
+        dx64, _, dg64, db64, _, _ = oracle.bn_relu_bwd(x, y, dy, ins[3], ins[4], ins[5], relu=p["relu"])
+        assert rel_l2(outs[0], dx64) <= 1e-3, what
+        # gamma / beta gradients: FP32 sums rounded to FP16; the floor is the rounding noise of a sum of `rows` terms
+        rms = float(np.sqrt(np.mean(dy.astype(np.float64) ** 2)))
+        floor = np.sqrt(rows) * rms * 2.5e-3 + 2.0 ** -24
+        for got, ref in ((outs[1], dg64), (outs[2], db64)):
+            err = np.abs(got.astype(np.float64) - ref)
+            assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor)), what
+    elif k == "add_fwd":
+        assert np.array_equal(outs[0].view(np.uint16), oracle.add_fwd(ins[0], ins[1], relu=p["relu"])[1].view(np.uint16)), what
+    elif k == "relu_bwd":
+        assert np.array_equal(outs[0].view(np.uint16), oracle.relu_bwd(ins[0], ins[1]).view(np.uint16)), what
+    elif k == "maxpool_fwd":
+        x = ins[0].reshape(p["N"], p["H"], p["W"], p["C"])
+        assert np.array_equal(outs[0].view(np.uint16), oracle.maxpool_fwd(x, p["window"], p["stride"], p["pad"])[0].ravel().view(np.uint16)), what
+    elif k == "maxpool_bwd":
+        x = ins[0].reshape(p["N"], p["H"], p["W"], p["C"])
+        P = oracle.pool_out(p["H"], p["window"], p["stride"], p["pad"])
+        r64, r16 = oracle.maxpool_bwd(x, ins[1].reshape(p["N"], P, P, p["C"]), p["window"], p["stride"], p["pad"])
+        one_step_of_fp16(outs[0], r64, r16, what)
+    elif k == "avgpool_fwd":
+        r64, r16 = oracle.avgpool_fwd(ins[0].reshape(p["N"], p["HW"], 1, p["C"]))
+        one_step_of_fp16(outs[0], r64, r16, what)
+    elif k == "avgpool_bwd":
+        r64, r16 = oracle.avgpool_bwd(ins[0].reshape(p["N"], p["C"]), p["HW"], 1)
+        one_step_of_fp16(outs[0], r64, r16, what)
+    elif k == "bias_add":
+        assert np.array_equal(outs[0].view(np.uint16), oracle.bias_add(ins[0].reshape(p["rows"], p["C"]), ins[1])[1].ravel().view(np.uint16)), what
+    elif k == "bias_grad":
+        r64, r16 = oracle.bias_grad(ins[0].reshape(p["rows"], p["C"]))
+        one_step_of_fp16(outs[0], r64, r16, what)
+    elif k == "softmax_xent":
+        S = float(ins[2][:1].view(np.float32)[0])
+        l64, d64, _ = oracle.softmax_xent(ins[0].reshape(p["rows"], p["classes"]), ins[1], S)
+        assert np.allclose(outs[1], l64, rtol=2e-6, atol=2e-5), what
+        err = np.abs(outs[0].astype(np.float64).reshape(d64.shape) - d64)
+        assert np.all(err <= 2.0 ** -10 * np.abs(d64) + 2.0 ** -25), what
+    else:
+        raise AssertionError("no check for " + k)
+
+
+def test_every_launch_of_a_chained_step_against_the_oracle(jz):
+    import jzt
+    from paper_1807_11205_amd import resnet50
+    net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=256.0, policy=dict(growth_interval=1))
+    assert len(net.fwd_ops) == 53 * 2 + 1 + 16 + 1 + 3 and net.trace[-1].kind == "lars_dyn"
+    for op in net.trace[:-1]:
+        op.call()
+    torch.cuda.synchronize()
+    counts = {}
+    for op in net.trace[:-1]:
+        check_op(op, counts)
+    assert counts["conv_fwd"] == 53 and counts["conv_bwd_weight"] == 53 and counts["conv_bwd_data"] == 52
+    assert counts["bn_fwd"] == 53 and counts["bn_bwd"] == 53 and counts["add_fwd"] == 32 and counts["relu_bwd"] == 16
+    # every parameter tensor received a gradient from this step (none was left at its initial zero)
+    g = np16(net.grad)
+    for i, (name, _, _, _) in enumerate(net.tensors):
+        assert np.any(g[net.offsets[i]:net.offsets[i + 1]] != 0), name
+    # the update: LARS against the oracle with the scale the step ran with, then the controller
+    before = inputs.ParamSet(names=[t[0] for t in net.tensors], offsets=np.asarray(net.offsets, np.int64),
+                             flags=np.asarray(net.flags, np.uint8), master_w=np16(net.master), momentum=np16(net.momentum),
+                             grad16=g, weight16=np16(net.w16), loss_scale=256.0)
+    net.update()
+    torch.cuda.synchronize()
+    got = (np16(net.master), np16(net.momentum), np16(net.w16), int(net.found_inf.item()))
+    out = jzt.check_lars_against_oracle(before, got, loss_scale=256.0, **net.hp)
+    assert out["flag"] == 0
+    assert jz.loss_scale_state(net.ls_state) == oracle.loss_scale_step(256.0, 0, 0, growth_interval=1)
+
+
+def test_the_chained_step_learns_a_fixed_batch(jz):
+    """Twenty steps on one fixed batch of eight images: the initial loss scale is too large, so the first steps overflow
+    and are skipped while the controller (on the device throughout) halves the scale; from then on no step is skipped
+    and the network memorises the batch: the mean loss falls from about log(1000) to well under 1."""
+    from paper_1807_11205_amd import resnet50
+    net = resnet50.ResNet50Chain(batch=8, image=64, initial_loss_scale=65536.0, hparams=dict(lr=2.0),
+                                 policy=dict(growth_interval=1000, max_scale=2.0 ** 24))
+    losses, flags = [], []
+    for _ in range(20):
+        net.step()
+        losses.append(net.mean_loss())
+        flags.append(int(net.found_inf.item()))
+    print("losses", ["%.3f" % v for v in losses], "flags", flags, "scale", jz.loss_scale_state(net.ls_state), flush=True)
+    assert abs(losses[0] - np.log(1000.0)) < 1.5
+    assert all(np.isfinite(losses)) and all(f in (0, 1) for f in flags) and sum(flags[-10:]) == 0
+    assert 1 <= sum(flags) <= 10 and losses[sum(flags)] == losses[0]        # skipped steps change nothing
+    assert losses[-1] < 1.0 and min(losses) == min(losses[-6:])
