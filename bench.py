@@ -412,8 +412,9 @@ def bn_workload(args):
 def chain_workload(args):
     """One complete, chained training step of ResNet-50 v1 (every tensor produced by the launch before it): forward with
     training-mode batch normalization, ReLU, pooling and residual adds, softmax cross-entropy gradient times the loss
-    scale, backward into the fused FP16 gradient buffer, LARS update with the dynamic loss scale on the device.  One
-    stream, eager launches, the same fixed synthetic batch every step."""
+    scale, backward into the fused FP16 gradient buffer, LARS update with the dynamic loss scale on the device.  Eager
+    launches, the weight-gradient GEMMs on a side stream (--streams 1: everything on one), the same fixed synthetic
+    batch every step."""
     from paper_1807_11205_amd import resnet50
     net = resnet50.ResNet50Chain(batch=args.batch, image=224, initial_loss_scale=65536.0,
                                  policy=dict(growth_interval=1 << 30, max_scale=2.0 ** 24))
@@ -429,9 +430,13 @@ def chain_workload(args):
         net.step()
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    side = torch.cuda.Stream() if args.streams > 1 else None
+    for _ in range(2):
+        net.step(side=side)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for e in ev:
-        e[0].record(); net.forward(); e[1].record(); net.backward(); e[2].record(); net.update(); e[3].record()
+        e[0].record(); net.forward(); e[1].record(); net.backward(side=side); e[2].record(); net.update(); e[3].record()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     assert int(net.found_inf.item()) == 0
@@ -447,7 +452,7 @@ def chain_workload(args):
         "vs_baseline": None, "dtype": "f16 storage, f32 accumulate, f32 master weights", "data": "synthetic",
         "config": {"workload": "ResNet-50 v1 chained step: conv + batch norm + ReLU + pooling + residual adds + classifier + "
                                "softmax loss gradient, backward, LARS with dynamic loss scale", "batch": args.batch, "image": 224,
-                   "launch": "eager", "streams": 1, "launches_per_step": len(net.trace), "launches_by_kind": kinds,
+                   "launch": "eager", "streams": 2 if side is not None else 1, "launches_per_step": len(net.trace), "launches_by_kind": kinds,
                    "loss_scale": api.loss_scale_state(net.ls_state)[0], "steps_skipped_while_the_scale_settled": skipped,
                    "mean_loss": net.mean_loss()},
         "phases_ms": {"forward_and_loss": ph[0], "backward": ph[1], "lars_update": ph[2], "gpu_total": gpu_ms},

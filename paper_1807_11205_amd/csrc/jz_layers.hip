@@ -87,7 +87,10 @@ struct PoolGeom {
   int N, H, W, C8, P, Q, window, stride, pad;
 };
 
+// WIN > 0: window size known at compile time (loops unrolled, the window's loads in flight together); 0: g.window
+template <int WIN>
 __global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __restrict__ x, uint4* __restrict__ y, PoolGeom g) {
+  const int window = WIN > 0 ? WIN : g.window;
   const int64_t total = (int64_t)g.N * g.P * g.Q * g.C8;
   for (int64_t i = (int64_t)blockIdx.x * LY_THREADS + threadIdx.x; i < total; i += (int64_t)gridDim.x * LY_THREADS) {
     const int c = (int)(i % g.C8);
@@ -98,17 +101,20 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __
     const int n = (int)(t / g.P);
     float best[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bool have = false;
-    for (int r = 0; r < g.window; ++r) {
-      const int h = p * g.stride - g.pad + r;
-      if (h < 0 || h >= g.H) continue;
-      for (int s = 0; s < g.window; ++s) {
-        const int w = q * g.stride - g.pad + s;
-        if (w < 0 || w >= g.W) continue;
-        float v[8];
-        unpack8(x[(((int64_t)n * g.H + h) * g.W + w) * g.C8 + c], v);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) best[k] = (!have || v[k] > best[k]) ? v[k] : best[k];
-        have = true;
+    for (int r = 0; r < window; ++r) {
+      const int h = p * g.stride - g.pad + r;
+#pragma unroll
+      for (int s = 0; s < window; ++s) {
+        const int w = q * g.stride - g.pad + s;
+        // a position outside the image is read at the nearest inside one and ignored: no branch around the load
+        const bool ok = h >= 0 && h < g.H && w >= 0 && w < g.W;
+        const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h), wc = w < 0 ? 0 : (w >= g.W ? g.W - 1 : w);
+        float v[8];
+        unpack8(x[(((int64_t)n * g.H + hc) * g.W + wc) * g.C8 + c], v);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) best[k] = (ok && (!have || v[k] > best[k])) ? v[k] : best[k];
+        have = have || ok;
       }
     }
     y[i] = pack8(best);
@@ -117,8 +123,10 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __
 
 // one thread per input position and 8 channels: it looks at every window that contains the position, finds that
 // window's first maximum again and takes the window's dy if the position is it
+template <int WIN>
 __global__ __launch_bounds__(LY_THREADS) void maxpool_bwd_kernel(const uint4* __restrict__ x, const uint4* __restrict__ dy,
                                                                  uint4* __restrict__ dx, PoolGeom g) {
+  const int window = WIN > 0 ? WIN : g.window;
   const int64_t total = (int64_t)g.N * g.H * g.W * g.C8;
   for (int64_t i = (int64_t)blockIdx.x * LY_THREADS + threadIdx.x; i < total; i += (int64_t)gridDim.x * LY_THREADS) {
     const int c = (int)(i % g.C8);
@@ -131,11 +139,11 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_bwd_kernel(const uint4* __
 #pragma unroll
     for (int k = 0; k < 8; ++k) acc[k] = 0.f;
     // windows p with p*stride - pad <= h0 <= p*stride - pad + window - 1
-    int p_lo = h0 + g.pad - g.window + 1;
+    int p_lo = h0 + g.pad - window + 1;
     p_lo = p_lo <= 0 ? 0 : (p_lo + g.stride - 1) / g.stride;
     int p_hi = (h0 + g.pad) / g.stride;
     if (p_hi > g.P - 1) p_hi = g.P - 1;
-    int q_lo = w0 + g.pad - g.window + 1;
+    int q_lo = w0 + g.pad - window + 1;
     q_lo = q_lo <= 0 ? 0 : (q_lo + g.stride - 1) / g.stride;
     int q_hi = (w0 + g.pad) / g.stride;
     if (q_hi > g.Q - 1) q_hi = g.Q - 1;
@@ -144,22 +152,24 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_bwd_kernel(const uint4* __
         float best[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         bool mine[8] = {false, false, false, false, false, false, false, false};
         bool have = false;
-        for (int r = 0; r < g.window; ++r) {
+#pragma unroll
+        for (int r = 0; r < window; ++r) {
           const int h = p * g.stride - g.pad + r;
-          if (h < 0 || h >= g.H) continue;
-          for (int s = 0; s < g.window; ++s) {
+#pragma unroll
+          for (int s = 0; s < window; ++s) {
             const int w = q * g.stride - g.pad + s;
-            if (w < 0 || w >= g.W) continue;
+            const bool ok = h >= 0 && h < g.H && w >= 0 && w < g.W;
+            const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h), wc = w < 0 ? 0 : (w >= g.W ? g.W - 1 : w);
             float v[8];
-            unpack8(x[(((int64_t)n * g.H + h) * g.W + w) * g.C8 + c], v);
+            unpack8(x[(((int64_t)n * g.H + hc) * g.W + wc) * g.C8 + c], v);
             const bool here = h == h0 && w == w0;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-              const bool better = !have || v[k] > best[k];
+              const bool better = ok && (!have || v[k] > best[k]);
               best[k] = better ? v[k] : best[k];
               mine[k] = better ? here : mine[k];
             }
-            have = true;
+            have = have || ok;
           }
         }
         float gy[8];
@@ -355,8 +365,14 @@ extern "C" int jz_maxpool_fwd(int N, int H, int W, int C, int window, int stride
   if (!jz::aligned16(x16) || !jz::aligned16(y16)) return JZ_ERR_ALIGN;
   const size_t nx = (size_t)N * H * W * C * 2, ny = (size_t)N * g.P * g.Q * C * 2;
   if (jz::overlaps(x16, nx, y16, ny)) return JZ_ERR_ALIAS;
-  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for((int64_t)N * g.P * g.Q * g.C8)), dim3(LY_THREADS), 0,
-                     static_cast<hipStream_t>(hip_stream), static_cast<const uint4*>(x16), static_cast<uint4*>(y16), g);
+  const dim3 grid(grid_for((int64_t)N * g.P * g.Q * g.C8));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (window == 3)
+    hipLaunchKernelGGL(maxpool_fwd_kernel<3>, grid, dim3(LY_THREADS), 0, st, static_cast<const uint4*>(x16), static_cast<uint4*>(y16), g);
+  else if (window == 2)
+    hipLaunchKernelGGL(maxpool_fwd_kernel<2>, grid, dim3(LY_THREADS), 0, st, static_cast<const uint4*>(x16), static_cast<uint4*>(y16), g);
+  else
+    hipLaunchKernelGGL(maxpool_fwd_kernel<0>, grid, dim3(LY_THREADS), 0, st, static_cast<const uint4*>(x16), static_cast<uint4*>(y16), g);
   return jz::launch_status();
 }
 
@@ -370,9 +386,15 @@ extern "C" int jz_maxpool_bwd(int N, int H, int W, int C, int window, int stride
   if (!jz::aligned16(x16) || !jz::aligned16(dy16) || !jz::aligned16(dx16)) return JZ_ERR_ALIGN;
   const size_t nx = (size_t)N * H * W * C * 2, ny = (size_t)N * g.P * g.Q * C * 2;
   if (jz::overlaps(dx16, nx, x16, nx) || jz::overlaps(dx16, nx, dy16, ny)) return JZ_ERR_ALIAS;
-  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for((int64_t)N * H * W * g.C8)), dim3(LY_THREADS), 0,
-                     static_cast<hipStream_t>(hip_stream), static_cast<const uint4*>(x16), static_cast<const uint4*>(dy16),
-                     static_cast<uint4*>(dx16), g);
+  const dim3 grid(grid_for((int64_t)N * H * W * g.C8));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const uint4 *x = static_cast<const uint4*>(x16), *dy = static_cast<const uint4*>(dy16);
+  if (window == 3)
+    hipLaunchKernelGGL(maxpool_bwd_kernel<3>, grid, dim3(LY_THREADS), 0, st, x, dy, static_cast<uint4*>(dx16), g);
+  else if (window == 2)
+    hipLaunchKernelGGL(maxpool_bwd_kernel<2>, grid, dim3(LY_THREADS), 0, st, x, dy, static_cast<uint4*>(dx16), g);
+  else
+    hipLaunchKernelGGL(maxpool_bwd_kernel<0>, grid, dim3(LY_THREADS), 0, st, x, dy, static_cast<uint4*>(dx16), g);
   return jz::launch_status();
 }
 

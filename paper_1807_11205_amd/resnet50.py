@@ -24,10 +24,11 @@ BN_EPS = 1e-5
 class Op:
     """One library call of the step: what it is, the tensors it reads and writes, and the launch itself."""
 
-    __slots__ = ("kind", "name", "params", "ins", "outs", "call")
+    __slots__ = ("kind", "name", "params", "ins", "outs", "call", "side_call")
 
-    def __init__(self, kind, name, params, ins, outs, call):
+    def __init__(self, kind, name, params, ins, outs, call, side_call=None):
         self.kind, self.name, self.params, self.ins, self.outs, self.call = kind, name, params, ins, outs, call
+        self.side_call = side_call      # the same launch bound to the side stream's workspace (weight gradients only)
 
 
 class ResNet50Chain:
@@ -71,6 +72,8 @@ class ResNet50Chain:
         self.bwd_ops: List[Op] = []
         self._build()
         self.ws = torch.zeros(self._ws_bytes, dtype=torch.uint8, device=dev)
+        self.side_ws = torch.zeros(self._ws_bytes, dtype=torch.uint8, device=dev)
+        self._events = {}
         for bind in self._pending_ws:
             bind(self.ws)
         self.trace = self.fwd_ops + self.bwd_ops + [self._lars_op()]
@@ -94,13 +97,15 @@ class ResNet50Chain:
         d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
         self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
         kind = {api.JZ_FWD: "conv_fwd", api.JZ_BWD_DATA: "conv_bwd_data", api.JZ_BWD_WEIGHT: "conv_bwd_weight"}[op]
-        return Op(kind, name, dict(desc=d), [a, b], [out], self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, ws)))
+        side = self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, self.side_ws)) if op == api.JZ_BWD_WEIGHT else None
+        return Op(kind, name, dict(desc=d), [a, b], [out], self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, ws)), side)
 
     def _fc(self, mode, a, b, out, name):
         B, I, O = self.N, self.fc.I, self.fc.O
         self._ws_bytes = max(self._ws_bytes, api.jz_gemm_fc_workspace_bytes(mode, B, I, O))
         kind = {api.JZ_FWD: "fc_fwd", api.JZ_BWD_DATA: "fc_bwd_data", api.JZ_BWD_WEIGHT: "fc_bwd_weight"}[mode]
-        return Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)))
+        side = self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, self.side_ws)) if mode == api.JZ_BWD_WEIGHT else None
+        return Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)), side)
 
     def _bn_fwd(self, cs, x, y, relu, name):
         rows, C = self.N * cs.P * cs.P, cs.K
@@ -215,16 +220,37 @@ class ResNet50Chain:
         for op in self.fwd_ops:
             op.call(stream)
 
-    def backward(self, stream=None):
-        for op in self.bwd_ops:
-            op.call(stream)
+    def backward(self, stream=None, side=None):
+        """With a side stream the weight-gradient GEMMs (which nothing in the backward pass waits for) run there,
+        beside the chain of activation gradients; the caller's stream waits for them at the end."""
+        if side is None:
+            for op in self.bwd_ops:
+                op.call(stream)
+            return
+        main = stream if stream is not None else torch.cuda.current_stream()
+        for i, op in enumerate(self.bwd_ops):
+            if op.side_call is None:
+                op.call(main)
+                continue
+            ev = self._events.get(i)
+            if ev is None:
+                ev = self._events[i] = torch.cuda.Event()
+            ev.record(main)                 # the gradient this GEMM reads has just been produced on the main stream
+            side.wait_event(ev)
+            op.side_call(side)
+        done = self._events.get("done")
+        if done is None:
+            done = self._events["done"] = torch.cuda.Event()
+        done.record(side)
+        main.wait_event(done)
 
     def update(self, stream=None):
         self.trace[-1].call(stream)
 
-    def step(self, stream=None):
-        for op in self.trace:
-            op.call(stream)
+    def step(self, stream=None, side=None):
+        self.forward(stream)
+        self.backward(stream, side)
+        self.update(stream)
 
     def mean_loss(self) -> float:
         torch.cuda.synchronize()

@@ -153,3 +153,20 @@ def test_the_chained_step_learns_a_fixed_batch(jz):
     assert all(np.isfinite(losses)) and all(f in (0, 1) for f in flags) and sum(flags[-10:]) == 0
     assert 1 <= sum(flags) <= 10 and losses[sum(flags)] == losses[0]        # skipped steps change nothing
     assert losses[-1] < 1.0 and min(losses) == min(losses[-6:])
+
+
+def test_side_stream_schedule_gives_the_same_bits(jz):
+    """The weight-gradient GEMMs on a side stream: same launches, same order of every reduction, so three steps leave
+    exactly the same parameters as on one stream."""
+    from paper_1807_11205_amd import resnet50
+    out = []
+    for use_side in (False, True):
+        net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=512.0, hparams=dict(lr=1.0))
+        side = torch.cuda.Stream() if use_side else None
+        for _ in range(3):
+            net.step(side=side)
+        torch.cuda.synchronize()
+        out.append((np16(net.master), np16(net.momentum), np16(net.w16), np16(net.grad), net.mean_loss()))
+    for a, b in zip(out[0][:4], out[1][:4]):
+        assert np.array_equal(a.view(np.uint32 if a.dtype == np.float32 else np.uint16), b.view(np.uint32 if b.dtype == np.float32 else np.uint16))
+    assert out[0][4] == out[1][4]
