@@ -417,7 +417,7 @@ def chain_workload(args):
     batch every step."""
     from paper_1807_11205_amd import resnet50
     net = resnet50.ResNet50Chain(batch=args.batch, image=224, initial_loss_scale=65536.0,
-                                 policy=dict(growth_interval=1 << 30, max_scale=2.0 ** 24))
+                                 policy=dict(growth_interval=1 << 30, max_scale=2.0 ** 24), fused=not args.unfused)
     skipped = 0
     for _ in range(24):                                   # let the controller bring the scale down until steps go through
         net.step()
@@ -453,6 +453,7 @@ def chain_workload(args):
         "config": {"workload": "ResNet-50 v1 chained step: conv + batch norm + ReLU + pooling + residual adds + classifier + "
                                "softmax loss gradient, backward, LARS with dynamic loss scale", "batch": args.batch, "image": 224,
                    "launch": "eager", "streams": 2 if side is not None else 1, "launches_per_step": len(net.trace), "launches_by_kind": kinds,
+                   "conv_bn_forward": "one call, statistics in the convolution epilogue" if net.fused else "two calls",
                    "loss_scale": api.loss_scale_state(net.ls_state)[0], "steps_skipped_while_the_scale_settled": skipped,
                    "mean_loss": net.mean_loss()},
         "phases_ms": {"forward_and_loss": ph[0], "backward": ph[1], "lars_update": ph[2], "gpu_total": gpu_ms},
@@ -508,6 +509,7 @@ def main():
     ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
                     "for the projection shortcuts (forward) and the backward-weight launches (at most 4)")
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a HIP graph (1) or launch eagerly (0); eager launches measured faster here")
+    ap.add_argument("--unfused", action="store_true", help="chain workload: convolution and batch normalization as two calls")
     ap.add_argument("--dynamic-loss-scale", action="store_true",
                     help="time jz_lars_mp_update_dyn (loss scale and its controller on the device) instead of jz_lars_mp_update")
     ap.add_argument("--calibrate-copy", action="store_true",

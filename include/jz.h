@@ -176,6 +176,18 @@ int jz_loss_scale_init(jz_loss_scale_state* state_dev, float initial_scale, void
 int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* policy,
                           jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Forward convolution followed by training-mode batch normalization (+ ReLU) in one call: conv_out16 = x16 (*) w16 exactly
+ * as jz_conv2d_fwd writes it, y16 / save_mean / save_invstd exactly as jz_bn_relu_fwd would compute them from conv_out16
+ * (Section 4.2's formulas on the FP16 tensor of Section 4.1), but the per-channel sums of the statistics are taken in
+ * the convolution kernel's epilogue, from the FP16 values it stores, instead of by a pass of their own over conv_out16
+ * (when the planner's kernel for this shape cannot do that, e.g. a split reduction, the pass is run: same results up
+ * to the order of the FP32 partial sums).  conv_out16 is kept because the backward pass needs it.  Workspace from
+ * jz_conv2d_bn_relu_fwd_workspace_bytes; other arguments, checks and status codes as for the two separate calls. */
+int jz_conv2d_bn_relu_fwd_workspace_bytes(const jz_conv_desc* desc, size_t* bytes);
+int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void* w16, const float* gamma, const float* beta,
+                          float eps, int relu, void* conv_out16, void* y16, float* save_mean, float* save_invstd, void* ws,
+                          size_t ws_bytes, void* hip_stream);
+
 /* The small layers between the convolutions of a ResNet-style network (the paper trains stock ResNet-50 / AlexNet,
  * Section 5, and does not restate them), on FP16 NHWC DEVICE tensors, the storage type Section 4.1 gives every forward
  * and backward tensor.  Each is its textbook definition evaluated in FP32 with one rounding to FP16 on the store;

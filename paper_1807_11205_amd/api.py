@@ -24,7 +24,7 @@ EXPORTS = [
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
     "jz_add_fwd", "jz_relu_bwd", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
-    "jz_bias_grad", "jz_softmax_xent_bwd",
+    "jz_bias_grad", "jz_softmax_xent_bwd", "jz_conv2d_bn_relu_fwd_workspace_bytes", "jz_conv2d_bn_relu_fwd",
     "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd",
     "jz_status_string", "jz_version",
 ]
@@ -107,6 +107,8 @@ def lib() -> ctypes.CDLL:
         L.jz_bias_add.argtypes = [i64, ci, vp, vp, vp, vp]
         L.jz_bias_grad.argtypes = [i64, ci, vp, vp, vp]
         L.jz_softmax_xent_bwd.argtypes = [ci, ci, vp, vp, cf, vp, vp, vp, vp]
+        L.jz_conv2d_bn_relu_fwd_workspace_bytes.argtypes = [dp, ctypes.POINTER(sz)]
+        L.jz_conv2d_bn_relu_fwd.argtypes = [dp, vp, vp, vp, vp, cf, ci, vp, vp, vp, vp, vp, sz, vp]
         L.jz_status_string.argtypes = [ci]
         L.jz_status_string.restype = ctypes.c_char_p
         L.jz_version.argtypes = []
@@ -413,3 +415,20 @@ def jz_softmax_xent_bwd(rows, classes, z, labels, dz, loss, loss_scale=1.0, stat
     _check(lib().jz_softmax_xent_bwd(rows, classes, _h(z, rows * classes, "z"), labels.data_ptr(), float(loss_scale),
                                      _ls_state(state) if state is not None else None, _h(dz, rows * classes, "dz"),
                                      _dev_ptr(loss, torch.float32, rows, "loss"), _stream(stream)), "jz_softmax_xent_bwd")
+
+
+def jz_conv2d_bn_relu_fwd_workspace_bytes(desc: jz_conv_desc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().jz_conv2d_bn_relu_fwd_workspace_bytes(ctypes.byref(desc), ctypes.byref(n)), "jz_conv2d_bn_relu_fwd_workspace_bytes")
+    return n.value
+
+
+def jz_conv2d_bn_relu_fwd(desc, x16, w16, gamma, beta, eps, relu, conv_out16, y16, save_mean, save_invstd, ws, stream=None):
+    d, h, f = desc, torch.float16, torch.float32
+    n_out = d.N * d.P * d.Q * d.K
+    wp, wn = _ws(ws)
+    _check(lib().jz_conv2d_bn_relu_fwd(ctypes.byref(d), _dev_ptr(x16, h, d.N * d.H * d.W * d.C, "x16"),
+                                       _dev_ptr(w16, h, d.K * d.R * d.S * d.C, "w16"), _dev_ptr(gamma, f, d.K, "gamma"),
+                                       _dev_ptr(beta, f, d.K, "beta"), float(eps), int(bool(relu)), _dev_ptr(conv_out16, h, n_out, "conv_out16"),
+                                       _dev_ptr(y16, h, n_out, "y16"), _dev_ptr(save_mean, f, d.K, "save_mean"),
+                                       _dev_ptr(save_invstd, f, d.K, "save_invstd"), wp, wn, _stream(stream)), "jz_conv2d_bn_relu_fwd")

@@ -400,3 +400,87 @@ extern "C" int jz_bn_relu_bwd(int64_t rows, int channels, const void* x16, const
                      n_chunks, channels, p.cpr, relu ? 1 : 0);
   return jz::launch_status();
 }
+
+// ---- convolution + batch normalization (+ ReLU), forward, with the statistics taken in the convolution's epilogue ----
+namespace {
+
+struct ConvBnPlan {
+  BnPlan bn;
+  size_t conv_ws = 0;   // the convolution's own workspace, at offset 0
+  int tiles_m = 0;      // > 0: the convolution kernel leaves [tiles_m][2][C] column sums; 0: a statistics pass is needed
+  size_t off_bn = 0, total = 0;
+};
+
+int make_conv_bn_plan(const jz_conv_desc* d, ConvBnPlan* p) {
+  int rc = jz::conv_fwd_stats_plan(d, &p->conv_ws, &p->tiles_m);
+  if (rc != JZ_OK) return rc;
+  const int P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1, Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+  rc = make_bn_plan((int64_t)d->N * P * Q, d->K, &p->bn);
+  if (rc != JZ_OK) return rc;
+  const int slabs = p->tiles_m > p->bn.slabs ? p->tiles_m : p->bn.slabs;
+  p->off_bn = up256(p->conv_ws);
+  // the batch-norm part of the workspace, laid out like BnPlan's but with room for either number of partial sums
+  p->bn.off_part = 0;
+  p->bn.off_coef = up256((size_t)slabs * 2 * d->K * sizeof(float));
+  p->bn.total = p->bn.off_coef + up256((size_t)4 * d->K * sizeof(float));
+  p->total = p->off_bn + p->bn.total;
+  return JZ_OK;
+}
+
+}  // namespace
+
+extern "C" int jz_conv2d_bn_relu_fwd_workspace_bytes(const jz_conv_desc* desc, size_t* bytes) {
+  if (!bytes) return JZ_ERR_NULL;
+  ConvBnPlan p;
+  int rc = make_conv_bn_plan(desc, &p);
+  if (rc != JZ_OK) return rc;
+  *bytes = p.total;
+  return JZ_OK;
+}
+
+extern "C" int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void* w16, const float* gamma,
+                                     const float* beta, float eps, int relu, void* conv_out16, void* y16, float* save_mean,
+                                     float* save_invstd, void* ws, size_t ws_bytes, void* hip_stream) {
+  ConvBnPlan p;
+  int rc = make_conv_bn_plan(desc, &p);
+  if (rc != JZ_OK) return rc;
+  if (!(eps >= 0.f)) return JZ_ERR_SHAPE;
+  if (!x16 || !w16 || !gamma || !beta || !conv_out16 || !y16 || !save_mean || !save_invstd) return JZ_ERR_NULL;
+  if (!ws || ws_bytes < p.total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(y16) || !jz::aligned16(ws) || !jz::aligned16(gamma) || !jz::aligned16(beta) || !jz::aligned16(save_mean) ||
+      !jz::aligned16(save_invstd))
+    return JZ_ERR_ALIGN;
+  const int64_t rows = p.bn.rows;
+  const int C = p.bn.C;
+  const size_t nb = (size_t)rows * C * 2, nc = (size_t)C * 4;
+  const size_t nx = (size_t)desc->N * desc->H * desc->W * desc->C * 2, nw = (size_t)desc->K * desc->R * desc->S * desc->C * 2;
+  if (jz::overlaps(y16, nb, conv_out16, nb) || jz::overlaps(y16, nb, x16, nx) || jz::overlaps(y16, nb, w16, nw) ||
+      jz::overlaps(ws, p.total, y16, nb) || jz::overlaps(save_mean, nc, save_invstd, nc))
+    return JZ_ERR_ALIAS;
+  for (const float* sv : {save_mean, save_invstd})
+    if (jz::overlaps(sv, nc, y16, nb) || jz::overlaps(sv, nc, conv_out16, nb) || jz::overlaps(sv, nc, x16, nx) ||
+        jz::overlaps(sv, nc, w16, nw) || jz::overlaps(sv, nc, ws, p.total))
+      return JZ_ERR_ALIAS;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* bws = static_cast<char*>(ws) + p.off_bn;
+  float* part = reinterpret_cast<float*>(bws + p.bn.off_part);
+  float* coef = reinterpret_cast<float*>(bws + p.bn.off_coef);
+  // the convolution (its own checks cover x, w, conv_out and its part of the workspace)
+  rc = jz::conv_fwd_run(desc, x16, w16, conv_out16, ws, p.conv_ws, p.tiles_m > 0 ? part : nullptr, hip_stream);
+  if (rc != JZ_OK) return rc;
+  const uint4* c = static_cast<const uint4*>(conv_out16);
+  int slabs = p.tiles_m;
+  if (slabs == 0) {  // this convolution kernel cannot leave the sums: one more pass over its output
+    slabs = p.bn.slabs;
+    hipLaunchKernelGGL(bn_stats<0>, dim3((unsigned)slabs), dim3(BN_THREADS), 0, st, c, nullptr, nullptr, nullptr, nullptr, part,
+                       rows, C, p.bn.cpr, p.bn.rpp, p.bn.rows_per_slab, 0);
+    if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  }
+  hipLaunchKernelGGL(bn_fwd_final, dim3((unsigned)((C + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part, slabs, C,
+                     1.0 / (double)rows, eps, gamma, beta, save_mean, save_invstd, coef);
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  const int64_t n_chunks = rows * p.bn.cpr;
+  hipLaunchKernelGGL(bn_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, c, static_cast<uint4*>(y16), coef, n_chunks, C,
+                     p.bn.cpr, relu ? 1 : 0);
+  return jz::launch_status();
+}

@@ -127,7 +127,7 @@ constexpr int fp32_slabs(int bm, int bn, int wtm, int lds_bytes) {
   return 0;
 }
 
-template <int BM, int BN, int TM, int TN, int NTHREADS, int EPASS = 1, int LDS_BYTES = 0>
+template <int BM, int BN, int TM, int TN, int NTHREADS, int EPASS = 1, int LDS_BYTES = 0, bool STATS = false>
 __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&acc)[TM][TN], unsigned short* lds, int m0,
                                                     int n0, int split, int tid, int lane, int wrow, int wcol) {
   // ---- epilogue ------------------------------------------------------------------------------
@@ -206,6 +206,13 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
   static_assert(RPB % CRPP == 0, "slab rows must divide among the store passes");
   const int cch = tid % CCH, crow = tid / CCH;
   const bool nvec = (a.N & 7) == 0;
+  // optional per-tile column sums of what is stored (for a batch normalization behind a forward convolution): a thread
+  // stores the same 8 columns of every row it handles, so it keeps their sums; they are combined below
+  // (a template argument: as a run-time branch in every kernel it cost the step 5 %)
+  static_assert(!STATS || LDS_BYTES >= 64 * NTHREADS, "the ring has to hold the partial sums");
+  constexpr bool CAN_STATS = STATS;
+  constexpr bool stats = STATS;
+  float ssum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, ssq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ps = 0; ps < EPASS; ++ps) {
     if (ps > 0) __syncthreads();  // the previous slab has been stored
@@ -233,6 +240,19 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
       int m = m0 + ps * RPB + row, n = n0 + cch * 8;
       if (m >= a.M || n >= a.N) continue;
       const unsigned short* src = sC + row * LDC + cch * 8;
+      if constexpr (stats) {
+        const uint4 pk = *reinterpret_cast<const uint4*>(src);  // one 16-byte LDS read (columns beyond N hold zeros' worth
+        const unsigned pw[4] = {pk.x, pk.y, pk.z, pk.w};          // of padding and are never written out)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const unsigned short hb = (unsigned short)(e & 1 ? pw[e >> 1] >> 16 : pw[e >> 1] & 0xffffu);
+          _Float16 hv;
+          __builtin_memcpy(&hv, &hb, 2);
+          const float v = (float)hv;
+          ssum[e] += v;
+          ssq[e] += v * v;
+        }
+      }
       size_t drow = (size_t)m;
       if (a.sc_on) {  // row m = (n, p, q) of the strided grid goes to input pixel (n, p * sh, q * sw)
         unsigned nimg = fd_div((unsigned)m, a.g.d_ohow);
@@ -257,6 +277,31 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
         *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
       } else {
         for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = src[e];
+      }
+    }
+  }
+  if constexpr (CAN_STATS) {
+    {
+      // [CRPP][BN] pairs in LDS, then one thread per column adds the CRPP row groups in a fixed order
+      __syncthreads();  // the staged tile has been read
+      float* sS = reinterpret_cast<float*>(lds);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        sS[((crow * BN) + cch * 8 + e) * 2] = ssum[e];
+        sS[((crow * BN) + cch * 8 + e) * 2 + 1] = ssq[e];
+      }
+      __syncthreads();
+      float* out = a.stats + (size_t)(m0 / BM) * 2 * a.N;
+      for (int col = tid; col < BN; col += NTHREADS) {
+        float s1 = 0.f, s2 = 0.f;
+        for (int r = 0; r < CRPP; ++r) {
+          s1 += sS[(r * BN + col) * 2];
+          s2 += sS[(r * BN + col) * 2 + 1];
+        }
+        if (n0 + col < a.N) {
+          out[n0 + col] = s1;
+          out[a.N + n0 + col] = s2;
+        }
       }
     }
   }
@@ -1005,23 +1050,28 @@ int launch_dma(const GemmArgs& a, hipStream_t st) {
 template <int OP>
 int launch_op(const Plan& pl, hipStream_t st) {
   const GemmArgs& a = pl.args;
-  if (!pl.fast) return launch_one<OP, false, 128, 128>(a, st);
-  if (pl.packed && OP == OP_FWD) {  // small-channel forward: tail of every gathered run is masked
+  constexpr bool IS_FWD = OP == OP_FWD || OP == OP_FWD_STATS;
+  if constexpr (OP == OP_FWD_STATS) {
+    if (!pl.fast || use_register_path()) return JZ_ERR_UNSUPPORTED;  // only the ring kernels come in this form
+  } else {
+    if (!pl.fast) return launch_one<OP, false, 128, 128>(a, st);
+  }
+  if (pl.packed && IS_FWD) {  // small-channel forward: tail of every gathered run is masked
     if (pl.bk == 32 && pl.nst == 3) {
-      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP_FWD, 128, 128, 32, 3, true>(a, st);
-      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP_FWD, 128, 64, 32, 3, true>(a, st);
-      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP_FWD, 64, 128, 32, 3, true>(a, st);
-      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP_FWD, 64, 64, 32, 3, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 3, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 3, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 3, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP, 64, 64, 32, 3, true>(a, st);
     } else if (pl.bk == 32) {
-      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP_FWD, 128, 128, 32, 4, true>(a, st);
-      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP_FWD, 128, 64, 32, 4, true>(a, st);
-      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP_FWD, 64, 128, 32, 4, true>(a, st);
-      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP_FWD, 64, 64, 32, 4, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP, 64, 64, 32, 4, true>(a, st);
     } else {
-      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP_FWD, 128, 128, 64, 4, true>(a, st);
-      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP_FWD, 128, 64, 64, 4, true>(a, st);
-      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP_FWD, 64, 128, 64, 4, true>(a, st);
-      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP_FWD, 64, 64, 64, 4, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 64, 4, true>(a, st);
+      if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 64, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 64, 4, true>(a, st);
+      if (pl.BM == 64 && pl.BN == 64) return launch_dma<OP, 64, 64, 64, 4, true>(a, st);
     }
     return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
   }
@@ -1059,17 +1109,28 @@ int launch_op(const Plan& pl, hipStream_t st) {
     if (pl.BM == 64 && pl.BN == 128) return launch_dma<OP, 64, 128, 32, 4>(a, st);
     return launch_dma<OP, 64, 64, 32, 4>(a, st);
   }
-  if (pl.BM == 128 && pl.BN == 128) return launch_one<OP, true, 128, 128>(a, st);
-  if (pl.BM == 128 && pl.BN == 64) return launch_one<OP, true, 128, 64>(a, st);
-  if (pl.BM == 64 && pl.BN == 128) return launch_one<OP, true, 64, 128>(a, st);
-  return launch_one<OP, true, 64, 64>(a, st);
+  if constexpr (OP == OP_FWD_STATS) {
+    return JZ_ERR_UNSUPPORTED;
+  } else {
+    if (pl.BM == 128 && pl.BN == 128) return launch_one<OP, true, 128, 128>(a, st);
+    if (pl.BM == 128 && pl.BN == 64) return launch_one<OP, true, 128, 64>(a, st);
+    if (pl.BM == 64 && pl.BN == 128) return launch_one<OP, true, 64, 128>(a, st);
+    return launch_one<OP, true, 64, 64>(a, st);
+  }
+}
+
+// a forward plan whose kernel can leave the per-tile column sums: the ring kernels (their LDS holds the sums), no split
+bool plan_leaves_stats(const Plan& pl) {
+  return pl.op == JZ_FWD && pl.fast && !use_register_path() && pl.args.splits == 1;
 }
 
 // A, B in the kernel's order: FWD (x, w), BWD_DATA (dy, w), BWD_WEIGHT (dy, x)
-int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, void* ws, size_t ws_bytes, void* stream) {
+int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, void* ws, size_t ws_bytes, void* stream,
+        float* stats = nullptr) {
   Plan pl;
   int rc = make_plan(op, d, &pl);
   if (rc != JZ_OK) return rc;
+  if (stats && !plan_leaves_stats(pl)) return JZ_ERR_UNSUPPORTED;
   if (!A || !B || !D) return JZ_ERR_NULL;
   if (!aligned16(A) || !aligned16(B) || !aligned16(D) || (ws && !aligned16(ws))) return JZ_ERR_ALIGN;
   if (overlaps(D, pl.bytesD, A, pl.bytesA) || overlaps(D, pl.bytesD, B, pl.bytesB)) return JZ_ERR_ALIAS;
@@ -1085,6 +1146,7 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
   a.bytesA = (unsigned)pl.bytesA;
   a.bytesB = (unsigned)pl.bytesB;
   a.Dpart = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_offset);
+  a.stats = stats;
   unsigned short* dwp = nullptr;
   if (pl.packed) {
     unsigned short* xp = static_cast<unsigned short*>(ws);
@@ -1104,7 +1166,7 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     }
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
   }
-  if (op == JZ_FWD) rc = launch_op<OP_FWD>(pl, st);
+  if (op == JZ_FWD) rc = stats ? launch_op<OP_FWD_STATS>(pl, st) : launch_op<OP_FWD>(pl, st);
   else if (op == JZ_BWD_DATA) rc = launch_op<OP_BWD_DATA>(pl, st);
   else rc = launch_op<OP_BWD_WEIGHT>(pl, st);
   if (rc != JZ_OK) return rc;
@@ -1139,6 +1201,20 @@ int fc_desc(int mode, int batch, int in_features, int out_features, jz_conv_desc
 }
 
 }  // namespace
+
+// for the fused convolution + batch normalization entry point (jz_bn.hip)
+int jz::conv_fwd_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* tiles_m) {
+  Plan pl;
+  int rc = make_plan(JZ_FWD, d, &pl);
+  if (rc != JZ_OK) return rc;
+  *conv_ws_bytes = pl.ws_bytes;
+  *tiles_m = plan_leaves_stats(pl) ? pl.args.tiles_m : 0;
+  return JZ_OK;
+}
+int jz::conv_fwd_run(const jz_conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, float* stats,
+                     void* stream) {
+  return run(JZ_FWD, d, x, w, y, ws, ws_bytes, stream, stats);
+}
 
 extern "C" int jz_conv2d_workspace_bytes(int op, const jz_conv_desc* desc, size_t* bytes) {
   if (!bytes) return JZ_ERR_NULL;

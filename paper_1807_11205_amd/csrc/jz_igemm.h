@@ -16,7 +16,8 @@
 
 namespace jz {
 
-enum { OP_FWD = 0, OP_BWD_DATA = 1, OP_BWD_WEIGHT = 2 };
+enum { OP_FWD = 0, OP_BWD_DATA = 1, OP_BWD_WEIGHT = 2,
+       OP_FWD_STATS = 3 };  // forward whose epilogue also leaves per-tile column sums (kernel template argument only)
 
 // Division by a run-time constant through multiply-high (Granlund-Montgomery style), exact for n < 2^31.
 struct FastDiv {
@@ -56,6 +57,7 @@ struct GemmArgs {
   const unsigned short* B;
   unsigned short* D16;  // [M][N] fp16, written when splits == 1
   float* Dpart;         // [splits][M][N] fp32 partial sums, written when splits > 1
+  float* stats;         // optional, splits == 1 only: [tiles_m][2][N] column sums of the stored FP16 tile and of its squares
   unsigned bytesA, bytesB;  // sizes of the A / B tensors: the bounds of their buffer descriptors
   int M, N, Kred;
   int nkt;           // number of k tiles = ceil(Kred / BK)

@@ -121,8 +121,10 @@ __device__ __forceinline__ void jz_dma16s(__amdgpu_buffer_rsrc_t rsrc, lds_byte*
 __device__ __forceinline__ unsigned low_bits(int k) { return k >= 32 ? 0xffffffffu : (1u << k) - 1u; }
 __device__ __forceinline__ int clamp_to(int x, int hi) { return x < 0 ? 0 : (x > hi ? hi : x); }
 
-template <int OP, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2, bool GEN = false>
+template <int OP_ARG, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2, bool GEN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
+  constexpr bool STATS = OP_ARG == OP_FWD_STATS;  // the forward kernel with column sums in its epilogue
+  constexpr int OP = STATS ? OP_FWD : OP_ARG;
   static_assert(TBK == 32 || TBK == 64, "k tile depth");
   static_assert(!GEN || OP != OP_BWD_WEIGHT, "backward-weight has no generic variant");
   constexpr bool A_KC = OP != OP_BWD_WEIGHT;  // A has k contiguous in memory
@@ -663,6 +665,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
   __syncthreads();  // the epilogue reuses the ring as its staging tile
 
   constexpr int ring_bytes = NST * STAGE, epi_bytes = BM / dma_epass(BM, BN) * (BN + 8) * 2;
-  igemm_epilogue_impl<BM, BN, TM, TN, NT, dma_epass(BM, BN), (ring_bytes > epi_bytes ? ring_bytes : epi_bytes)>(
+  igemm_epilogue_impl<BM, BN, TM, TN, NT, dma_epass(BM, BN), (ring_bytes > epi_bytes ? ring_bytes : epi_bytes), STATS>(
       a, acc, lds, m0, n0, split, tid, lane, wm * WTM, wn * WTN);
 }

@@ -101,10 +101,10 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __
     const int n = (int)(t / g.P);
     float best[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bool have = false;
-#pragma unroll
+#pragma unroll(WIN > 0 ? WIN : 1)
     for (int r = 0; r < window; ++r) {
       const int h = p * g.stride - g.pad + r;
-#pragma unroll
+#pragma unroll(WIN > 0 ? WIN : 1)
       for (int s = 0; s < window; ++s) {
         const int w = q * g.stride - g.pad + s;
         // a position outside the image is read at the nearest inside one and ignored: no branch around the load
@@ -152,10 +152,10 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_bwd_kernel(const uint4* __
         float best[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         bool mine[8] = {false, false, false, false, false, false, false, false};
         bool have = false;
-#pragma unroll
+#pragma unroll(WIN > 0 ? WIN : 1)
         for (int r = 0; r < window; ++r) {
           const int h = p * g.stride - g.pad + r;
-#pragma unroll
+#pragma unroll(WIN > 0 ? WIN : 1)
           for (int s = 0; s < window; ++s) {
             const int w = q * g.stride - g.pad + s;
             const bool ok = h >= 0 && h < g.H && w >= 0 && w < g.W;

@@ -33,8 +33,10 @@ class Op:
 
 class ResNet50Chain:
     def __init__(self, batch=64, image=224, variant="v1", seed=180711205, initial_loss_scale=1024.0, hparams=None,
-                 policy=None, device="cuda:0"):
-        self.N, self.image, self.device = int(batch), int(image), torch.device(device)
+                 policy=None, device="cuda:0", fused=True):
+        """fused: forward convolution + batch normalization as one call (statistics in the convolution's epilogue)
+        instead of two."""
+        self.N, self.image, self.device, self.fused = int(batch), int(image), torch.device(device), bool(fused)
         self.convs = shapes.resnet50_convs(variant, image)
         self.fc = shapes.RESNET50_FC
         self.hp = dict(inputs.HPARAMS)
@@ -115,6 +117,16 @@ class ResNet50Chain:
         call = lambda stream=None: api.jz_bn_relu_fwd(rows, C, x, gamma, beta, BN_EPS, relu, y, mean, invstd, self.ws, stream)
         return Op("bn_fwd", name, dict(rows=rows, C=C, relu=relu, eps=BN_EPS), [x, gamma, beta], [y, mean, invstd], call), mean, invstd
 
+    def _conv_bn_fwd(self, cs, x, w, c, y, relu):
+        d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+        rows, C = self.N * cs.P * cs.P, cs.K
+        gamma, beta = self._param(self.master, cs.name + ".gamma"), self._param(self.master, cs.name + ".beta")
+        mean, invstd = self._buf(C, torch.float32), self._buf(C, torch.float32)
+        self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_bn_relu_fwd_workspace_bytes(d))
+        call = lambda stream=None: api.jz_conv2d_bn_relu_fwd(d, x, w, gamma, beta, BN_EPS, relu, c, y, mean, invstd, self.ws, stream)
+        return Op("conv_bn_fwd", cs.name, dict(desc=d, rows=rows, C=C, relu=relu, eps=BN_EPS), [x, w, gamma, beta],
+                  [c, y, mean, invstd], call), mean, invstd
+
     def _bn_bwd(self, cs, x, y, dy, mean, invstd, dx, relu, name):
         rows, C = self.N * cs.P * cs.P, cs.K
         gamma = self._param(self.master, cs.name + ".gamma")
@@ -138,9 +150,13 @@ class ResNet50Chain:
             n_out = N * cs.P * cs.P * cs.K
             c, z, dc = self._buf(n_out), self._buf(n_out), self._buf(n_out)
             dz = self._buf(n_out) if dz is None else dz
-            F.append(self._conv(api.JZ_FWD, cs, x_in, W(cs), c, cs.name))
-            op, mean, invstd = self._bn_fwd(cs, c, z, relu, cs.name + ".bn")
-            F.append(op)
+            if self.fused:
+                op, mean, invstd = self._conv_bn_fwd(cs, x_in, W(cs), c, z, relu)
+                F.append(op)
+            else:
+                F.append(self._conv(api.JZ_FWD, cs, x_in, W(cs), c, cs.name))
+                op, mean, invstd = self._bn_fwd(cs, c, z, relu, cs.name + ".bn")
+                F.append(op)
             back = [self._bn_bwd(cs, c, z if relu else None, dz, mean, invstd, dc, relu, cs.name + ".bn"),
                     self._conv(api.JZ_BWD_WEIGHT, cs, x_in, dc, DW(cs), cs.name)]
             if dx_in is not None:
