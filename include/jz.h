@@ -196,8 +196,12 @@ int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void*
  *   jz_add_fwd      y = a + b, followed by max(., 0) when relu != 0 (the residual connection).  y may be a or b.
  *   jz_relu_bwd     dx = dy where the forward output y is > 0, else 0.  dx may be dy.
  *   jz_maxpool_fwd  x[N,H,W,C] -> y[N,P,Q,C], P = (H + 2 pad - window) / stride + 1 (same for Q); padding never wins.
- *   jz_maxpool_bwd  dx[N,H,W,C] from x and dy[N,P,Q,C]: each dy goes to the first maximum of its window in (row, column)
- *                   order; a position that wins several windows gets their sum (FP32, window order).  pad < window <= 16.
+ *                   arg8 (may be NULL; DEVICE, 8-byte aligned, one byte per output element) receives the position
+ *                   r * window + s inside its window of each output's first maximum in (row, column) order.
+ *   jz_maxpool_bwd  dx[N,H,W,C] from dy[N,P,Q,C]: each dy goes to the first maximum of its window; a position that wins
+ *                   several windows gets their sum (FP32, window order).  With arg8 from the forward call the winners
+ *                   are taken from it and x16 may be NULL; with arg8 == NULL they are derived again from x16 (same
+ *                   result, several times the arithmetic).  pad < window <= 16.
  *   jz_avgpool_fwd  global average: x[N,HW,C] -> y[N,C] = sum over the HW positions (FP32, in order) / HW.
  *   jz_avgpool_bwd  dy[N,C] -> dx[N,HW,C] = dy / HW at every position.
  *   jz_bias_add     out[rows,C] = y[rows,C] + b[C].  out may be y.
@@ -210,9 +214,10 @@ int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void*
  *                   and a zero gradient row.  classes need not be a multiple of 8 here (2-byte alignment suffices). */
 int jz_add_fwd(int64_t n, const void* a16, const void* b16, int relu, void* y16, void* hip_stream);
 int jz_relu_bwd(int64_t n, const void* y16, const void* dy16, void* dx16, void* hip_stream);
-int jz_maxpool_fwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, void* y16, void* hip_stream);
-int jz_maxpool_bwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, const void* dy16, void* dx16,
+int jz_maxpool_fwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, void* y16, void* arg8,
                    void* hip_stream);
+int jz_maxpool_bwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, const void* arg8,
+                   const void* dy16, void* dx16, void* hip_stream);
 int jz_avgpool_fwd(int N, int HW, int C, const void* x16, void* y16, void* hip_stream);
 int jz_avgpool_bwd(int N, int HW, int C, const void* dy16, void* dx16, void* hip_stream);
 int jz_bias_add(int64_t rows, int C, const void* y16, const void* b16, void* out16, void* hip_stream);

@@ -100,8 +100,8 @@ def lib() -> ctypes.CDLL:
         L.jz_bn_relu_bwd.argtypes = [i64, ci, vp, vp, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
         L.jz_add_fwd.argtypes = [i64, vp, vp, ci, vp, vp]
         L.jz_relu_bwd.argtypes = [i64, vp, vp, vp, vp]
-        L.jz_maxpool_fwd.argtypes = [ci] * 7 + [vp, vp, vp]
-        L.jz_maxpool_bwd.argtypes = [ci] * 7 + [vp, vp, vp, vp]
+        L.jz_maxpool_fwd.argtypes = [ci] * 7 + [vp, vp, vp, vp]
+        L.jz_maxpool_bwd.argtypes = [ci] * 7 + [vp, vp, vp, vp, vp]
         L.jz_avgpool_fwd.argtypes = [ci, ci, ci, vp, vp, vp]
         L.jz_avgpool_bwd.argtypes = [ci, ci, ci, vp, vp, vp]
         L.jz_bias_add.argtypes = [i64, ci, vp, vp, vp, vp]
@@ -381,15 +381,18 @@ def pool_out(size, window, stride, pad):
     return (size + 2 * pad - window) // stride + 1
 
 
-def jz_maxpool_fwd(N, H, W, C, window, stride, pad, x, y, stream=None):
+def jz_maxpool_fwd(N, H, W, C, window, stride, pad, x, y, arg=None, stream=None):
+    """arg: optional uint8 tensor, one entry per output element, that receives each window's winner for jz_maxpool_bwd."""
     P, Q = pool_out(H, window, stride, pad), pool_out(W, window, stride, pad)
     _check(lib().jz_maxpool_fwd(N, H, W, C, window, stride, pad, _h(x, N * H * W * C, "x"), _h(y, N * P * Q * C, "y"),
-                                _stream(stream)), "jz_maxpool_fwd")
+                                _dev_ptr(arg, torch.uint8, N * P * Q * C, "arg"), _stream(stream)), "jz_maxpool_fwd")
 
 
-def jz_maxpool_bwd(N, H, W, C, window, stride, pad, x, dy, dx, stream=None):
+def jz_maxpool_bwd(N, H, W, C, window, stride, pad, x, dy, dx, arg=None, stream=None):
+    """With arg (from jz_maxpool_fwd) x may be None."""
     P, Q = pool_out(H, window, stride, pad), pool_out(W, window, stride, pad)
-    _check(lib().jz_maxpool_bwd(N, H, W, C, window, stride, pad, _h(x, N * H * W * C, "x"), _h(dy, N * P * Q * C, "dy"),
+    _check(lib().jz_maxpool_bwd(N, H, W, C, window, stride, pad, _dev_ptr(x, torch.float16, N * H * W * C, "x"),
+                                _dev_ptr(arg, torch.uint8, N * P * Q * C, "arg"), _h(dy, N * P * Q * C, "dy"),
                                 _h(dx, N * H * W * C, "dx"), _stream(stream)), "jz_maxpool_bwd")
 
 

@@ -89,7 +89,8 @@ struct PoolGeom {
 
 // WIN > 0: window size known at compile time (loops unrolled, the window's loads in flight together); 0: g.window
 template <int WIN>
-__global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __restrict__ x, uint4* __restrict__ y, PoolGeom g) {
+__global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __restrict__ x, uint4* __restrict__ y,
+                                                                 uint2* __restrict__ arg, PoolGeom g) {
   const int window = WIN > 0 ? WIN : g.window;
   const int64_t total = (int64_t)g.N * g.P * g.Q * g.C8;
   for (int64_t i = (int64_t)blockIdx.x * LY_THREADS + threadIdx.x; i < total; i += (int64_t)gridDim.x * LY_THREADS) {
@@ -100,6 +101,7 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __
     const int p = (int)(t % g.P);
     const int n = (int)(t / g.P);
     float best[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    unsigned win[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // position r * window + s of the first maximum
     bool have = false;
 #pragma unroll(WIN > 0 ? WIN : 1)
     for (int r = 0; r < window; ++r) {
@@ -113,11 +115,17 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_fwd_kernel(const uint4* __
         float v[8];
         unpack8(x[(((int64_t)n * g.H + hc) * g.W + wc) * g.C8 + c], v);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) best[k] = (ok && (!have || v[k] > best[k])) ? v[k] : best[k];
+        for (int k = 0; k < 8; ++k) {
+          const bool better = ok && (!have || v[k] > best[k]);
+          best[k] = better ? v[k] : best[k];
+          win[k] = better ? (unsigned)(r * window + s) : win[k];
+        }
         have = have || ok;
       }
     }
     y[i] = pack8(best);
+    if (arg)
+      arg[i] = make_uint2(win[0] | (win[1] << 8) | (win[2] << 16) | (win[3] << 24), win[4] | (win[5] << 8) | (win[6] << 16) | (win[7] << 24));
   }
 }
 
@@ -176,6 +184,43 @@ __global__ __launch_bounds__(LY_THREADS) void maxpool_bwd_kernel(const uint4* __
         unpack8(dy[(((int64_t)n * g.P + p) * g.Q + q) * g.C8 + c], gy);
 #pragma unroll
         for (int k = 0; k < 8; ++k) acc[k] += (have && mine[k]) ? gy[k] : 0.f;
+      }
+    dx[i] = pack8(acc);
+  }
+}
+
+// the same gather from the winners the forward pass saved: nothing is re-derived, x is not read
+__global__ __launch_bounds__(LY_THREADS) void maxpool_bwd_arg_kernel(const uint2* __restrict__ arg, const uint4* __restrict__ dy,
+                                                                     uint4* __restrict__ dx, PoolGeom g) {
+  const int64_t total = (int64_t)g.N * g.H * g.W * g.C8;
+  for (int64_t i = (int64_t)blockIdx.x * LY_THREADS + threadIdx.x; i < total; i += (int64_t)gridDim.x * LY_THREADS) {
+    const int c = (int)(i % g.C8);
+    int64_t t = i / g.C8;
+    const int w0 = (int)(t % g.W);
+    t /= g.W;
+    const int h0 = (int)(t % g.H);
+    const int n = (int)(t / g.H);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int p_lo = h0 + g.pad - g.window + 1;
+    p_lo = p_lo <= 0 ? 0 : (p_lo + g.stride - 1) / g.stride;
+    int p_hi = (h0 + g.pad) / g.stride;
+    if (p_hi > g.P - 1) p_hi = g.P - 1;
+    int q_lo = w0 + g.pad - g.window + 1;
+    q_lo = q_lo <= 0 ? 0 : (q_lo + g.stride - 1) / g.stride;
+    int q_hi = (w0 + g.pad) / g.stride;
+    if (q_hi > g.Q - 1) q_hi = g.Q - 1;
+    for (int p = p_lo; p <= p_hi; ++p)
+      for (int q = q_lo; q <= q_hi; ++q) {
+        const unsigned me = (unsigned)((h0 - (p * g.stride - g.pad)) * g.window + (w0 - (q * g.stride - g.pad)));
+        const int64_t o = (((int64_t)n * g.P + p) * g.Q + q) * g.C8 + c;
+        const uint2 a = arg[o];
+        float gy[8];
+        unpack8(dy[o], gy);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const unsigned wk = ((k < 4 ? a.x : a.y) >> (8 * (k & 3))) & 0xffu;
+          acc[k] += wk == me ? gy[k] : 0.f;
+        }
       }
     dx[i] = pack8(acc);
   }
@@ -356,45 +401,51 @@ extern "C" int jz_relu_bwd(int64_t n, const void* y16, const void* dy16, void* d
 }
 
 extern "C" int jz_maxpool_fwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, void* y16,
-                              void* hip_stream) {
+                              void* arg8, void* hip_stream) {
   PoolGeom g;
   int rc = make_pool(N, H, W, C, window, stride, pad, &g);
   if (rc != JZ_OK) return rc;
   if (N == 0) return JZ_OK;
   if (!x16 || !y16) return JZ_ERR_NULL;
-  if (!jz::aligned16(x16) || !jz::aligned16(y16)) return JZ_ERR_ALIGN;
+  if (!jz::aligned16(x16) || !jz::aligned16(y16) || (reinterpret_cast<uintptr_t>(arg8) & 7u)) return JZ_ERR_ALIGN;
   const size_t nx = (size_t)N * H * W * C * 2, ny = (size_t)N * g.P * g.Q * C * 2;
-  if (jz::overlaps(x16, nx, y16, ny)) return JZ_ERR_ALIAS;
+  if (jz::overlaps(x16, nx, y16, ny) || jz::overlaps(arg8, ny / 2, x16, nx) || jz::overlaps(arg8, ny / 2, y16, ny)) return JZ_ERR_ALIAS;
   const dim3 grid(grid_for((int64_t)N * g.P * g.Q * g.C8));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const uint4* x = static_cast<const uint4*>(x16);
+  uint4* y = static_cast<uint4*>(y16);
+  uint2* arg = static_cast<uint2*>(arg8);
   if (window == 3)
-    hipLaunchKernelGGL(maxpool_fwd_kernel<3>, grid, dim3(LY_THREADS), 0, st, static_cast<const uint4*>(x16), static_cast<uint4*>(y16), g);
+    hipLaunchKernelGGL(maxpool_fwd_kernel<3>, grid, dim3(LY_THREADS), 0, st, x, y, arg, g);
   else if (window == 2)
-    hipLaunchKernelGGL(maxpool_fwd_kernel<2>, grid, dim3(LY_THREADS), 0, st, static_cast<const uint4*>(x16), static_cast<uint4*>(y16), g);
+    hipLaunchKernelGGL(maxpool_fwd_kernel<2>, grid, dim3(LY_THREADS), 0, st, x, y, arg, g);
   else
-    hipLaunchKernelGGL(maxpool_fwd_kernel<0>, grid, dim3(LY_THREADS), 0, st, static_cast<const uint4*>(x16), static_cast<uint4*>(y16), g);
+    hipLaunchKernelGGL(maxpool_fwd_kernel<0>, grid, dim3(LY_THREADS), 0, st, x, y, arg, g);
   return jz::launch_status();
 }
 
-extern "C" int jz_maxpool_bwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, const void* dy16,
-                              void* dx16, void* hip_stream) {
+extern "C" int jz_maxpool_bwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, const void* arg8,
+                              const void* dy16, void* dx16, void* hip_stream) {
   PoolGeom g;
   int rc = make_pool(N, H, W, C, window, stride, pad, &g);
   if (rc != JZ_OK) return rc;
   if (N == 0) return JZ_OK;
-  if (!x16 || !dy16 || !dx16) return JZ_ERR_NULL;
-  if (!jz::aligned16(x16) || !jz::aligned16(dy16) || !jz::aligned16(dx16)) return JZ_ERR_ALIGN;
+  if ((!x16 && !arg8) || !dy16 || !dx16) return JZ_ERR_NULL;
+  if (!jz::aligned16(x16) || !jz::aligned16(dy16) || !jz::aligned16(dx16) || (reinterpret_cast<uintptr_t>(arg8) & 7u)) return JZ_ERR_ALIGN;
   const size_t nx = (size_t)N * H * W * C * 2, ny = (size_t)N * g.P * g.Q * C * 2;
-  if (jz::overlaps(dx16, nx, x16, nx) || jz::overlaps(dx16, nx, dy16, ny)) return JZ_ERR_ALIAS;
+  if (jz::overlaps(dx16, nx, x16, nx) || jz::overlaps(dx16, nx, dy16, ny) || jz::overlaps(dx16, nx, arg8, ny / 2)) return JZ_ERR_ALIAS;
   const dim3 grid(grid_for((int64_t)N * H * W * g.C8));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const uint4 *x = static_cast<const uint4*>(x16), *dy = static_cast<const uint4*>(dy16);
-  if (window == 3)
-    hipLaunchKernelGGL(maxpool_bwd_kernel<3>, grid, dim3(LY_THREADS), 0, st, x, dy, static_cast<uint4*>(dx16), g);
+  uint4* dx = static_cast<uint4*>(dx16);
+  if (arg8)  // the winners are known: x is not needed
+    hipLaunchKernelGGL(maxpool_bwd_arg_kernel, grid, dim3(LY_THREADS), 0, st, static_cast<const uint2*>(arg8), dy, dx, g);
+  else if (window == 3)
+    hipLaunchKernelGGL(maxpool_bwd_kernel<3>, grid, dim3(LY_THREADS), 0, st, x, dy, dx, g);
   else if (window == 2)
-    hipLaunchKernelGGL(maxpool_bwd_kernel<2>, grid, dim3(LY_THREADS), 0, st, x, dy, static_cast<uint4*>(dx16), g);
+    hipLaunchKernelGGL(maxpool_bwd_kernel<2>, grid, dim3(LY_THREADS), 0, st, x, dy, dx, g);
   else
-    hipLaunchKernelGGL(maxpool_bwd_kernel<0>, grid, dim3(LY_THREADS), 0, st, x, dy, static_cast<uint4*>(dx16), g);
+    hipLaunchKernelGGL(maxpool_bwd_kernel<0>, grid, dim3(LY_THREADS), 0, st, x, dy, dx, g);
   return jz::launch_status();
 }
 

@@ -172,10 +172,11 @@ class ResNet50Chain:
         Hq = api.pool_out(Hp, 3, 2, 1)
         pool = dict(N=N, H=Hp, W=Hp, C=64, window=3, stride=2, pad=1)
         cur, dcur = self._buf(N * Hq * Hq * 64), self._buf(N * Hq * Hq * 64)
-        F.append(Op("maxpool_fwd", "pool1", pool, [a0], [cur],
-                    lambda stream=None, y=cur: api.jz_maxpool_fwd(N, Hp, Hp, 64, 3, 2, 1, a0, y, stream)))
-        segments.append([Op("maxpool_bwd", "pool1", pool, [a0, dcur], [da0],
-                            lambda stream=None, dy=dcur: api.jz_maxpool_bwd(N, Hp, Hp, 64, 3, 2, 1, a0, dy, da0, stream))] + back_stem)
+        arg = self._buf(N * Hq * Hq * 64, torch.uint8)     # each window's winner, saved for the backward pass
+        F.append(Op("maxpool_fwd", "pool1", pool, [a0], [cur, arg],
+                    lambda stream=None, y=cur: api.jz_maxpool_fwd(N, Hp, Hp, 64, 3, 2, 1, a0, y, arg, stream)))
+        segments.append([Op("maxpool_bwd", "pool1", pool, [a0, dcur, arg], [da0],
+                            lambda stream=None, dy=dcur: api.jz_maxpool_bwd(N, Hp, Hp, 64, 3, 2, 1, None, dy, da0, arg, stream))] + back_stem)
 
         blocks = sorted({cs.name[:-1] for cs in self.convs[1:]}, key=lambda n: (int(n[1]), int(n[3:])))
         for nm in blocks:

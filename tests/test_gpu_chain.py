@@ -89,7 +89,13 @@ def check_op(op, counts):
         assert np.array_equal(outs[0].view(np.uint16), oracle.relu_bwd(ins[0], ins[1]).view(np.uint16)), what
     elif k == "maxpool_fwd":
         x = ins[0].reshape(p["N"], p["H"], p["W"], p["C"])
-        assert np.array_equal(outs[0].view(np.uint16), oracle.maxpool_fwd(x, p["window"], p["stride"], p["pad"])[0].ravel().view(np.uint16)), what
+        ry, rarg = oracle.maxpool_fwd(x, p["window"], p["stride"], p["pad"])
+        assert np.array_equal(outs[0].view(np.uint16), ry.ravel().view(np.uint16)), what
+        a = outs[1].reshape(ry.shape).astype(np.int64)
+        P = ry.shape[1]
+        pp, qq = np.arange(P)[None, :, None, None], np.arange(P)[None, None, :, None]
+        flat = (pp * p["stride"] - p["pad"] + a // p["window"]) * p["W"] + (qq * p["stride"] - p["pad"] + a % p["window"])
+        assert np.array_equal(flat, rarg), what
     elif k == "maxpool_bwd":
         x = ins[0].reshape(p["N"], p["H"], p["W"], p["C"])
         P = oracle.pool_out(p["H"], p["window"], p["stride"], p["pad"])

@@ -95,16 +95,28 @@ def test_maxpool_forward_and_backward(jz, N, H, W, C, window, stride, pad):
     x[0, :, :, 1] = np.round(x[0, :, :, 1])
     P, Q = oracle.pool_out(H, window, stride, pad), oracle.pool_out(W, window, stride, pad)
     y = torch.empty(N * P * Q * C, dtype=torch.float16, device="cuda")
+    y2 = torch.empty_like(y)
+    arg = torch.full((N * P * Q * C,), 255, dtype=torch.uint8, device="cuda")
     tx = dev(x.ravel())
     jz.jz_maxpool_fwd(N, H, W, C, window, stride, pad, tx, y)
-    ry, _ = oracle.maxpool_fwd(x, window, stride, pad)
-    assert same_bits(host(y).reshape(ry.shape), ry)
+    jz.jz_maxpool_fwd(N, H, W, C, window, stride, pad, tx, y2, arg)
+    ry, rarg = oracle.maxpool_fwd(x, window, stride, pad)
+    assert same_bits(host(y).reshape(ry.shape), ry) and same_bits(host(y2).reshape(ry.shape), ry)
+    # the saved winner (position r * window + s inside the window) names the oracle's first maximum exactly
+    a = host(arg).reshape(ry.shape).astype(np.int64)
+    pp, qq = np.arange(P)[None, :, None, None], np.arange(Q)[None, None, :, None]
+    flat = (pp * stride - pad + a // window) * W + (qq * stride - pad + a % window)
+    assert np.array_equal(flat, rarg)
     dy = h16((6, N, H, W, C), ry.shape, 4.0)
     dx = torch.empty(N * H * W * C, dtype=torch.float16, device="cuda")
     jz.jz_maxpool_bwd(N, H, W, C, window, stride, pad, tx, dev(dy.ravel()), dx)
     r64, r16 = oracle.maxpool_bwd(x, dy, window, stride, pad)
     got = host(dx)
     within_one_step(got, r64, r16, "maxpool dx")
+    # from the saved winners, without x: the same bits as the re-derivation
+    dx2 = torch.empty_like(dx)
+    jz.jz_maxpool_bwd(N, H, W, C, window, stride, pad, None, dev(dy.ravel()), dx2, arg)
+    assert same_bits(host(dx2), got)
     # no gradient lost: the column sums of dx and dy agree (fp64 sums of the FP16 values, up to the roundings of summed cells)
     assert np.allclose(got.reshape(N, -1, C).astype(np.float64).sum(axis=1), dy.reshape(N, -1, C).astype(np.float64).sum(axis=1),
                        rtol=2e-3, atol=0.5)
@@ -200,12 +212,16 @@ def test_argument_errors(jz):
     assert L.jz_add_fwd(0, None, None, 1, None, None) == jz.JZ_OK
     assert L.jz_relu_bwd(64, p, q, p, None) == jz.JZ_ERR_ALIAS              # dx must not be y
     assert L.jz_relu_bwd(64, p, q, q, None) == jz.JZ_OK
-    assert L.jz_maxpool_fwd(1, 8, 8, 12, 3, 2, 1, p, q, None) == jz.JZ_ERR_SHAPE      # C not a multiple of 8
-    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 3, p, q, None) == jz.JZ_ERR_SHAPE       # pad >= window
-    assert L.jz_maxpool_fwd(1, 2, 2, 8, 5, 1, 1, p, q, None) == jz.JZ_ERR_SHAPE       # window larger than the padded image
-    assert L.jz_maxpool_fwd(1, 40, 40, 8, 17, 1, 0, p, q, None) == jz.JZ_ERR_UNSUPPORTED
-    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 1, p, p, None) == jz.JZ_ERR_ALIAS
-    assert L.jz_maxpool_bwd(1, 8, 8, 8, 3, 2, 1, p, q, p, None) == jz.JZ_ERR_ALIAS
+    assert L.jz_maxpool_fwd(1, 8, 8, 12, 3, 2, 1, p, q, None, None) == jz.JZ_ERR_SHAPE      # C not a multiple of 8
+    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 3, p, q, None, None) == jz.JZ_ERR_SHAPE       # pad >= window
+    assert L.jz_maxpool_fwd(1, 2, 2, 8, 5, 1, 1, p, q, None, None) == jz.JZ_ERR_SHAPE       # window larger than the padded image
+    assert L.jz_maxpool_fwd(1, 40, 40, 8, 17, 1, 0, p, q, None, None) == jz.JZ_ERR_UNSUPPORTED
+    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 1, p, p, None, None) == jz.JZ_ERR_ALIAS
+    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 1, p, q, q, None) == jz.JZ_ERR_ALIAS          # the winners must not overlap y
+    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 1, p, q, r + 4, None) == jz.JZ_ERR_ALIGN
+    assert L.jz_maxpool_bwd(1, 8, 8, 8, 3, 2, 1, p, None, q, p, None) == jz.JZ_ERR_ALIAS
+    assert L.jz_maxpool_bwd(1, 8, 8, 8, 3, 2, 1, None, None, q, r, None) == jz.JZ_ERR_NULL  # neither x nor the winners
+    assert L.jz_maxpool_bwd(1, 8, 8, 8, 3, 2, 1, None, p, q, r, None) == jz.JZ_OK
     assert L.jz_avgpool_fwd(2, 0, 8, p, q, None) == jz.JZ_ERR_SHAPE
     assert L.jz_avgpool_bwd(2, 4, 8, p, p, None) == jz.JZ_ERR_ALIAS
     assert L.jz_bias_add(4, 8, p, p, q, None) == jz.JZ_OK                   # the bias may alias the input, not the output
