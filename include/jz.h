@@ -181,12 +181,14 @@ int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, con
  * (Section 4.2's formulas on the FP16 tensor of Section 4.1), but the per-channel sums of the statistics are taken in
  * the convolution kernel's epilogue, from the FP16 values it stores, instead of by a pass of their own over conv_out16
  * (when the planner's kernel for this shape cannot do that, e.g. a split reduction, the pass is run: same results up
- * to the order of the FP32 partial sums).  conv_out16 is kept because the backward pass needs it.  Workspace from
+ * to the order of the FP32 partial sums).  residual16 (may be NULL; same shape as y16, must not overlap an output): the
+ * tensor a bottleneck block adds in front of its last ReLU, y = [relu](bn(conv_out) + residual), added in FP32 before
+ * the single rounding of y.  conv_out16 is kept because the backward pass needs it.  Workspace from
  * jz_conv2d_bn_relu_fwd_workspace_bytes; other arguments, checks and status codes as for the two separate calls. */
 int jz_conv2d_bn_relu_fwd_workspace_bytes(const jz_conv_desc* desc, size_t* bytes);
 int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void* w16, const float* gamma, const float* beta,
-                          float eps, int relu, void* conv_out16, void* y16, float* save_mean, float* save_invstd, void* ws,
-                          size_t ws_bytes, void* hip_stream);
+                          float eps, const void* residual16, int relu, void* conv_out16, void* y16, float* save_mean,
+                          float* save_invstd, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* The small layers between the convolutions of a ResNet-style network (the paper trains stock ResNet-50 / AlexNet,
  * Section 5, and does not restate them), on FP16 NHWC DEVICE tensors, the storage type Section 4.1 gives every forward

@@ -15,7 +15,7 @@ import os
 
 import numpy as np
 
-from .bn import bn_relu_bwd, bn_relu_fwd  # noqa: F401
+from .bn import bn_add_relu_fwd, bn_relu_bwd, bn_relu_fwd  # noqa: F401
 from .layers import (add_fwd, avgpool_bwd, avgpool_fwd, bias_add, bias_grad, maxpool_bwd, maxpool_fwd, pool_out,  # noqa: F401
                      relu_bwd, softmax_xent)
 from .lars import lars_mp_update, lars_trust_ratio  # noqa: F401

@@ -43,6 +43,17 @@ def bn_relu_fwd(x16, gamma32, beta32, eps, relu=True):
     return y, y16, mean, invstd
 
 
+def bn_add_relu_fwd(x16, res16, gamma32, beta32, eps, relu=True):
+    """The end of a bottleneck block: y = [relu](bn(x) + res), the sum formed before the one rounding to FP16.
+    Returns (y64, y16, mean64, invstd64)."""
+    z, _, mean, invstd = bn_relu_fwd(x16, gamma32, beta32, eps, relu=False)
+    y = z + _f16(res16).astype(np.float64)
+    if relu:
+        y = np.maximum(y, 0.0)
+    with np.errstate(over="ignore"):
+        return y, y.astype(np.float16), mean, invstd
+
+
 def bn_relu_bwd(x16, y16, dy16, gamma32, mean32, invstd32, relu=True):
     """Gradient of the map above for the saved statistics (FP32 values, widened).  Returns
     (dx64, dx16, dgamma64, dbeta64, dgamma16, dbeta16)."""

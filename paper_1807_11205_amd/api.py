@@ -108,7 +108,7 @@ def lib() -> ctypes.CDLL:
         L.jz_bias_grad.argtypes = [i64, ci, vp, vp, vp]
         L.jz_softmax_xent_bwd.argtypes = [ci, ci, vp, vp, cf, vp, vp, vp, vp]
         L.jz_conv2d_bn_relu_fwd_workspace_bytes.argtypes = [dp, ctypes.POINTER(sz)]
-        L.jz_conv2d_bn_relu_fwd.argtypes = [dp, vp, vp, vp, vp, cf, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.jz_conv2d_bn_relu_fwd.argtypes = [dp, vp, vp, vp, vp, cf, vp, ci, vp, vp, vp, vp, vp, sz, vp]
         L.jz_status_string.argtypes = [ci]
         L.jz_status_string.restype = ctypes.c_char_p
         L.jz_version.argtypes = []
@@ -426,12 +426,15 @@ def jz_conv2d_bn_relu_fwd_workspace_bytes(desc: jz_conv_desc) -> int:
     return n.value
 
 
-def jz_conv2d_bn_relu_fwd(desc, x16, w16, gamma, beta, eps, relu, conv_out16, y16, save_mean, save_invstd, ws, stream=None):
+def jz_conv2d_bn_relu_fwd(desc, x16, w16, gamma, beta, eps, relu, conv_out16, y16, save_mean, save_invstd, ws, residual16=None,
+                          stream=None):
+    """y16 = [relu](bn(conv(x16, w16)) [+ residual16]); conv_out16 receives the convolution output."""
     d, h, f = desc, torch.float16, torch.float32
     n_out = d.N * d.P * d.Q * d.K
     wp, wn = _ws(ws)
     _check(lib().jz_conv2d_bn_relu_fwd(ctypes.byref(d), _dev_ptr(x16, h, d.N * d.H * d.W * d.C, "x16"),
                                        _dev_ptr(w16, h, d.K * d.R * d.S * d.C, "w16"), _dev_ptr(gamma, f, d.K, "gamma"),
-                                       _dev_ptr(beta, f, d.K, "beta"), float(eps), int(bool(relu)), _dev_ptr(conv_out16, h, n_out, "conv_out16"),
+                                       _dev_ptr(beta, f, d.K, "beta"), float(eps), _dev_ptr(residual16, h, n_out, "residual16"),
+                                       int(bool(relu)), _dev_ptr(conv_out16, h, n_out, "conv_out16"),
                                        _dev_ptr(y16, h, n_out, "y16"), _dev_ptr(save_mean, f, d.K, "save_mean"),
                                        _dev_ptr(save_invstd, f, d.K, "save_invstd"), wp, wn, _stream(stream)), "jz_conv2d_bn_relu_fwd")

@@ -241,8 +241,11 @@ __global__ __launch_bounds__(BN_THREADS) void bn_fwd_final(const float* __restri
   coef[C + c] = beta[c] - mf * a;
 }
 
-__global__ __launch_bounds__(BN_THREADS) void bn_apply(const uint4* __restrict__ x, uint4* __restrict__ y,
-                                                      const float* __restrict__ coef, int64_t n_chunks, int C, int cpr, int relu) {
+// RES: a residual tensor is added in front of the ReLU (the end of a bottleneck block)
+template <int RES>
+__global__ __launch_bounds__(BN_THREADS) void bn_apply(const uint4* __restrict__ x, const uint4* __restrict__ res,
+                                                      uint4* __restrict__ y, const float* __restrict__ coef, int64_t n_chunks, int C,
+                                                      int cpr, int relu) {
   const int64_t stride = (int64_t)gridDim.x * BN_THREADS;
   for (int64_t i = (int64_t)blockIdx.x * BN_THREADS + threadIdx.x; i < n_chunks; i += stride) {
     const int chunk = (int)(i % cpr);
@@ -253,9 +256,12 @@ __global__ __launch_bounds__(BN_THREADS) void bn_apply(const uint4* __restrict__
     a[0] = t0.x; a[1] = t0.y; a[2] = t0.z; a[3] = t0.w; a[4] = t1.x; a[5] = t1.y; a[6] = t1.z; a[7] = t1.w;
     b[0] = u0.x; b[1] = u0.y; b[2] = u0.z; b[3] = u0.w; b[4] = u1.x; b[5] = u1.y; b[6] = u1.z; b[7] = u1.w;
     unpack8(x[i], v);
+    float rv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (RES) unpack8(res[i], rv);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float z = v[e] * a[e] + b[e];
+      if (RES) z += rv[e];
       v[e] = (relu && !(z > 0.f)) ? 0.f : z;
     }
     y[i] = pack8(v);
@@ -359,8 +365,8 @@ extern "C" int jz_bn_relu_fwd(int64_t rows, int channels, const void* x16, const
                      p.slabs, channels, 1.0 / (double)rows, eps, gamma, beta, save_mean, save_invstd, coef);
   if ((rc = jz::launch_status()) != JZ_OK) return rc;
   const int64_t n_chunks = rows * p.cpr;
-  hipLaunchKernelGGL(bn_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, static_cast<uint4*>(y16), coef, n_chunks,
-                     channels, p.cpr, relu ? 1 : 0);
+  hipLaunchKernelGGL(bn_apply<0>, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, nullptr, static_cast<uint4*>(y16), coef,
+                     n_chunks, channels, p.cpr, relu ? 1 : 0);
   return jz::launch_status();
 }
 
@@ -439,8 +445,8 @@ extern "C" int jz_conv2d_bn_relu_fwd_workspace_bytes(const jz_conv_desc* desc, s
 }
 
 extern "C" int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void* w16, const float* gamma,
-                                     const float* beta, float eps, int relu, void* conv_out16, void* y16, float* save_mean,
-                                     float* save_invstd, void* ws, size_t ws_bytes, void* hip_stream) {
+                                     const float* beta, float eps, const void* residual16, int relu, void* conv_out16, void* y16,
+                                     float* save_mean, float* save_invstd, void* ws, size_t ws_bytes, void* hip_stream) {
   ConvBnPlan p;
   int rc = make_conv_bn_plan(desc, &p);
   if (rc != JZ_OK) return rc;
@@ -448,18 +454,19 @@ extern "C" int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, 
   if (!x16 || !w16 || !gamma || !beta || !conv_out16 || !y16 || !save_mean || !save_invstd) return JZ_ERR_NULL;
   if (!ws || ws_bytes < p.total) return JZ_ERR_WORKSPACE;
   if (!jz::aligned16(y16) || !jz::aligned16(ws) || !jz::aligned16(gamma) || !jz::aligned16(beta) || !jz::aligned16(save_mean) ||
-      !jz::aligned16(save_invstd))
+      !jz::aligned16(save_invstd) || !jz::aligned16(residual16))
     return JZ_ERR_ALIGN;
   const int64_t rows = p.bn.rows;
   const int C = p.bn.C;
   const size_t nb = (size_t)rows * C * 2, nc = (size_t)C * 4;
   const size_t nx = (size_t)desc->N * desc->H * desc->W * desc->C * 2, nw = (size_t)desc->K * desc->R * desc->S * desc->C * 2;
   if (jz::overlaps(y16, nb, conv_out16, nb) || jz::overlaps(y16, nb, x16, nx) || jz::overlaps(y16, nb, w16, nw) ||
-      jz::overlaps(ws, p.total, y16, nb) || jz::overlaps(save_mean, nc, save_invstd, nc))
+      jz::overlaps(ws, p.total, y16, nb) || jz::overlaps(save_mean, nc, save_invstd, nc) || jz::overlaps(y16, nb, residual16, nb) ||
+      jz::overlaps(conv_out16, nb, residual16, nb) || jz::overlaps(ws, p.total, residual16, nb))
     return JZ_ERR_ALIAS;
   for (const float* sv : {save_mean, save_invstd})
     if (jz::overlaps(sv, nc, y16, nb) || jz::overlaps(sv, nc, conv_out16, nb) || jz::overlaps(sv, nc, x16, nx) ||
-        jz::overlaps(sv, nc, w16, nw) || jz::overlaps(sv, nc, ws, p.total))
+        jz::overlaps(sv, nc, w16, nw) || jz::overlaps(sv, nc, ws, p.total) || jz::overlaps(sv, nc, residual16, nb))
       return JZ_ERR_ALIAS;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* bws = static_cast<char*>(ws) + p.off_bn;
@@ -480,7 +487,11 @@ extern "C" int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, 
                      1.0 / (double)rows, eps, gamma, beta, save_mean, save_invstd, coef);
   if ((rc = jz::launch_status()) != JZ_OK) return rc;
   const int64_t n_chunks = rows * p.bn.cpr;
-  hipLaunchKernelGGL(bn_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, c, static_cast<uint4*>(y16), coef, n_chunks, C,
-                     p.bn.cpr, relu ? 1 : 0);
+  if (residual16)
+    hipLaunchKernelGGL(bn_apply<1>, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, c, static_cast<const uint4*>(residual16),
+                       static_cast<uint4*>(y16), coef, n_chunks, C, p.bn.cpr, relu ? 1 : 0);
+  else
+    hipLaunchKernelGGL(bn_apply<0>, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, c, nullptr, static_cast<uint4*>(y16), coef,
+                       n_chunks, C, p.bn.cpr, relu ? 1 : 0);
   return jz::launch_status();
 }

@@ -117,14 +117,15 @@ class ResNet50Chain:
         call = lambda stream=None: api.jz_bn_relu_fwd(rows, C, x, gamma, beta, BN_EPS, relu, y, mean, invstd, self.ws, stream)
         return Op("bn_fwd", name, dict(rows=rows, C=C, relu=relu, eps=BN_EPS), [x, gamma, beta], [y, mean, invstd], call), mean, invstd
 
-    def _conv_bn_fwd(self, cs, x, w, c, y, relu):
+    def _conv_bn_fwd(self, cs, x, w, c, y, relu, residual=None):
         d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
         rows, C = self.N * cs.P * cs.P, cs.K
         gamma, beta = self._param(self.master, cs.name + ".gamma"), self._param(self.master, cs.name + ".beta")
         mean, invstd = self._buf(C, torch.float32), self._buf(C, torch.float32)
         self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_bn_relu_fwd_workspace_bytes(d))
-        call = lambda stream=None: api.jz_conv2d_bn_relu_fwd(d, x, w, gamma, beta, BN_EPS, relu, c, y, mean, invstd, self.ws, stream)
-        return Op("conv_bn_fwd", cs.name, dict(desc=d, rows=rows, C=C, relu=relu, eps=BN_EPS), [x, w, gamma, beta],
+        call = lambda stream=None: api.jz_conv2d_bn_relu_fwd(d, x, w, gamma, beta, BN_EPS, relu, c, y, mean, invstd, self.ws, residual,
+                                                             stream)
+        return Op("conv_bn_fwd", cs.name, dict(desc=d, rows=rows, C=C, relu=relu, eps=BN_EPS), [x, w, gamma, beta, residual],
                   [c, y, mean, invstd], call), mean, invstd
 
     def _bn_bwd(self, cs, x, y, dy, mean, invstd, dx, relu, name):
@@ -143,15 +144,15 @@ class ResNet50Chain:
         W = lambda cs: self._param(self.w16, cs.name + ".w")
         DW = lambda cs: self._param(self.grad, cs.name + ".w")
 
-        def conv_bn(cs, x_in, dx_in, relu, dz=None):
+        def conv_bn(cs, x_in, dx_in, relu, dz=None, residual=None):
             """conv -> batch norm (-> ReLU), appended to the forward list.  Returns (z, dz, back): the output, the buffer
             the consumer of z writes z's gradient to, and this pair's backward ops in execution order.  dx_in is where
             the gradient with respect to x_in goes (None for the first layer)."""
             n_out = N * cs.P * cs.P * cs.K
             c, z, dc = self._buf(n_out), self._buf(n_out), self._buf(n_out)
             dz = self._buf(n_out) if dz is None else dz
-            if self.fused:
-                op, mean, invstd = self._conv_bn_fwd(cs, x_in, W(cs), c, z, relu)
+            if self.fused:     # with a residual: z = relu(bn(c) + residual), the block's output
+                op, mean, invstd = self._conv_bn_fwd(cs, x_in, W(cs), c, z, relu or residual is not None, residual)
                 F.append(op)
             else:
                 F.append(self._conv(api.JZ_FWD, cs, x_in, W(cs), c, cs.name))
@@ -188,15 +189,19 @@ class ResNet50Chain:
             ds = self._buf(n_out)                          # gradient of the sum in front of the block's last ReLU
             za, dza, back_a = conv_bn(a, x_in, dxa, True)
             zb, dzb, back_b = conv_bn(b, za, dza, True)
-            zc, _, back_c = conv_bn(c, zb, dzb, False, dz=ds)
             if p is not None:
                 dxp = self._buf(x_in.numel())
                 shortcut, _, back_p = conv_bn(p, x_in, dxp, False, dz=ds)
                 dshort = dxp
             else:
                 shortcut, back_p, dshort = x_in, [], ds
-            out, dout = self._buf(n_out), self._buf(n_out)
-            F.append(add_op(nm + ".add", zc, shortcut, out, True))
+            dout = self._buf(n_out)
+            if self.fused:     # the residual add and the block's ReLU happen in the normalization pass of branch c
+                out, _, back_c = conv_bn(c, zb, dzb, False, dz=ds, residual=shortcut)
+            else:
+                zc, _, back_c = conv_bn(c, zb, dzb, False, dz=ds)
+                out = self._buf(n_out)
+                F.append(add_op(nm + ".add", zc, shortcut, out, True))
             relu_b = Op("relu_bwd", nm + ".add", {}, [out, dout], [ds],
                         lambda stream=None, y=out, dy=dout, dx=ds: api.jz_relu_bwd(y, dy, dx, stream))
             segments.append([relu_b] + back_c + back_b + back_a + back_p + [add_op(nm + ".dx", dxa, dshort, dx_out, False)])

@@ -58,7 +58,10 @@ def check_op(op, counts):
         od = oracle.conv_desc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
         jzt.check_half_output(outs[0], oracle.conv_fwd(od, ins[0], ins[1]), tol=1e-3, what=what)
         rows, C = p["rows"], p["C"]
-        y64, _, m64, i64 = oracle.bn_relu_fwd(outs[0].reshape(rows, C), ins[2], ins[3], p["eps"], relu=p["relu"])
+        if ins[4] is None:
+            y64, _, m64, i64 = oracle.bn_relu_fwd(outs[0].reshape(rows, C), ins[2], ins[3], p["eps"], relu=p["relu"])
+        else:
+            y64, _, m64, i64 = oracle.bn_add_relu_fwd(outs[0].reshape(rows, C), ins[4].reshape(rows, C), ins[2], ins[3], p["eps"], relu=p["relu"])
         assert np.all(np.abs(outs[2] - m64) <= 1e-5 * (np.abs(m64) + 1.0 / i64)), what
         assert np.all(np.abs(outs[3] - i64) <= 1e-4 * i64), what
         assert rel_l2(outs[1], y64) <= 1e-3, what
@@ -127,7 +130,7 @@ def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused):
     import jzt
     from paper_1807_11205_amd import resnet50
     net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=256.0, policy=dict(growth_interval=1), fused=fused)
-    assert len(net.fwd_ops) == 53 * (1 if fused else 2) + 1 + 16 + 1 + 3 and net.trace[-1].kind == "lars_dyn"
+    assert len(net.fwd_ops) == (53 if fused else 53 * 2 + 16) + 1 + 1 + 3 and net.trace[-1].kind == "lars_dyn"
     for op in net.trace[:-1]:
         op.call()
     torch.cuda.synchronize()
@@ -136,7 +139,7 @@ def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused):
         check_op(op, counts)
     assert counts.get("conv_bn_fwd", 0) + counts.get("conv_fwd", 0) == 53 and counts.get("conv_fwd", 0) == counts.get("bn_fwd", 0)
     assert counts["conv_bwd_weight"] == 53 and counts["conv_bwd_data"] == 52
-    assert counts["bn_bwd"] == 53 and counts["add_fwd"] == 32 and counts["relu_bwd"] == 16
+    assert counts["bn_bwd"] == 53 and counts["add_fwd"] == (16 if fused else 32) and counts["relu_bwd"] == 16
     # every parameter tensor received a gradient from this step (none was left at its initial zero)
     g = np16(net.grad)
     for i, (name, _, _, _) in enumerate(net.tensors):

@@ -21,7 +21,7 @@ def jz():
     return api
 
 
-def run_case(jz, N, H, C, K, R, stride, pad, relu=True, key=0, eps=1e-5):
+def run_case(jz, N, H, C, K, R, stride, pad, relu=True, key=0, eps=1e-5, residual=False):
     import jzt
     rng = inputs.rng_for(41, key, N, H, C, K, R)
     x = inputs.normal_f16(rng, (N * H * H * C,))
@@ -38,11 +38,15 @@ def run_case(jz, N, H, C, K, R, stride, pad, relu=True, key=0, eps=1e-5):
     y = torch.full((rows * K,), float("nan"), dtype=torch.float16, device="cuda")
     mean = torch.empty(K, dtype=torch.float32, device="cuda"); invstd = torch.empty_like(mean)
     ws = torch.full((max(jz.jz_conv2d_bn_relu_fwd_workspace_bytes(d), 16),), 0xCD, dtype=torch.uint8, device="cuda")
-    jz.jz_conv2d_bn_relu_fwd(d, X, W, G, B, eps, relu, c, y, mean, invstd, ws)
+    res = inputs.normal_f16(rng, (rows * K,), std=1.5) if residual else None
+    jz.jz_conv2d_bn_relu_fwd(d, X, W, G, B, eps, relu, c, y, mean, invstd, ws, jzt.to_dev(res) if residual else None)
     torch.cuda.synchronize()
     c_np = c.cpu().numpy()
     assert np.array_equal(c_np.view(np.uint16), c_ref.cpu().numpy().view(np.uint16)), "convolution output differs from jz_conv2d_fwd"
-    y64, _, m64, i64 = oracle.bn_relu_fwd(c_np.reshape(rows, K), gamma, beta, eps, relu=relu)
+    if residual:
+        y64, _, m64, i64 = oracle.bn_add_relu_fwd(c_np.reshape(rows, K), res.reshape(rows, K), gamma, beta, eps, relu=relu)
+    else:
+        y64, _, m64, i64 = oracle.bn_relu_fwd(c_np.reshape(rows, K), gamma, beta, eps, relu=relu)
     mg, ig = mean.cpu().numpy(), invstd.cpu().numpy()
     assert np.all(np.abs(mg - m64) <= 1e-5 * (np.abs(m64) + 1.0 / i64)), float(np.max(np.abs(mg - m64)))
     assert np.all(np.abs(ig - i64) <= 1e-4 * i64), float(np.max(np.abs(ig - i64) / i64))
@@ -65,6 +69,7 @@ SHAPES = [
 @pytest.mark.parametrize("relu", [True, False])
 def test_fused_statistics_against_the_oracle(jz, N, H, C, K, R, stride, pad, relu):
     run_case(jz, N, H, C, K, R, stride, pad, relu=relu)
+    run_case(jz, N, H, C, K, R, stride, pad, relu=relu, residual=True, key=7)
 
 
 @pytest.mark.parametrize("tile,bk,waves,nst", [("128128", "32", "4", "4"), ("128064", "32", "4", "4"), ("64128", "32", "4", "3"), ("64064", "64", "4", "4"),
@@ -106,13 +111,15 @@ def test_argument_errors(jz):
     def call(**o):
         a = dict(x=ptr(x), w=ptr(w), g=ptr(g), b=ptr(b), eps=1e-5, c=ptr(c), y=ptr(y), m=ptr(m), s=ptr(s), ws=ptr(ws), n=n.value)
         a.update(o)
-        return L.jz_conv2d_bn_relu_fwd(ctypes.byref(d), a["x"], a["w"], a["g"], a["b"], a["eps"], 1, a["c"], a["y"], a["m"], a["s"], a["ws"], a["n"], None)
+        return L.jz_conv2d_bn_relu_fwd(ctypes.byref(d), a["x"], a["w"], a["g"], a["b"], a["eps"], a.get("r"), 1, a["c"], a["y"], a["m"], a["s"],
+                                       a["ws"], a["n"], None)
 
     assert call(x=None) == jz.JZ_ERR_NULL and call(y=None) == jz.JZ_ERR_NULL and call(m=None) == jz.JZ_ERR_NULL
     assert call(eps=-1.0) == jz.JZ_ERR_SHAPE
     assert call(n=n.value - 1) == jz.JZ_ERR_WORKSPACE and call(ws=None) == jz.JZ_ERR_WORKSPACE
     assert call(y=ptr(c)) == jz.JZ_ERR_ALIAS and call(s=ptr(m)) == jz.JZ_ERR_ALIAS and call(y=ptr(x)) == jz.JZ_ERR_ALIAS
     assert call(y=ptr(y) + 2) == jz.JZ_ERR_ALIGN
+    assert call(r=ptr(y)) == jz.JZ_ERR_ALIAS and call(r=ptr(c)) == jz.JZ_ERR_ALIAS and call(r=ptr(x) + 2) == jz.JZ_ERR_ALIGN
     assert call() == jz.JZ_OK
     torch.cuda.synchronize()
     dbad = jz.conv_desc(2, 8, 8, 16, 36, 3, 3, 1, 1)      # 36 channels: not a multiple of 8 for the normalization

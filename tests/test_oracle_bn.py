@@ -112,3 +112,22 @@ def test_backward_invariants_and_mask():
     assert np.array_equal(dx16, dx.astype(np.float16)) and np.array_equal(dg16, dgamma.astype(np.float16)) and np.array_equal(db16, dbeta.astype(np.float16))
     # gamma = 0 stops all gradient to x
     assert np.all(oracle.bn_relu_bwd(x, y16, dy, np.zeros(16, np.float32), m32, i32, relu=False)[0] == 0)
+
+
+def test_residual_variant_adds_before_the_relu_and_rounds_once():
+    x, gamma, beta, _ = _case(21, 9, 4, shift=0.3, scale=1.5)
+    res = np.random.default_rng(22).standard_normal((9, 4)).astype(np.float16)
+    eps = 1e-4
+    z = oracle.bn_relu_fwd(x, gamma, beta, eps, relu=False)[0]
+    y, y16, mean, invstd = oracle.bn_add_relu_fwd(x, res, gamma, beta, eps, relu=True)
+    for r in range(9):
+        for c in range(4):
+            assert y[r, c] == max(z[r, c] + float(res[r, c]), 0.0)
+    assert np.array_equal(y16, y.astype(np.float16))
+    # the sum is NOT rounded in between: a residual that cancels z to within an FP16 step of z leaves the small remainder
+    big = (-z).astype(np.float16)
+    y2 = oracle.bn_add_relu_fwd(x, big, gamma, beta, eps, relu=False)[0]
+    assert np.array_equal(y2, z + big.astype(np.float64)) and np.any(y2 != 0) and np.all(np.abs(y2) <= np.abs(z) * 2.0 ** -10 + 1e-7)
+    # zero residual: the plain layer; statistics never depend on the residual
+    y3, _, m3, i3 = oracle.bn_add_relu_fwd(x, np.zeros_like(res), gamma, beta, eps, relu=True)
+    assert np.array_equal(y3, oracle.bn_relu_fwd(x, gamma, beta, eps, relu=True)[0]) and np.array_equal(m3, mean) and np.array_equal(i3, invstd)
