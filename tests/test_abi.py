@@ -159,3 +159,61 @@ def test_every_table_entry_belongs_to_a_layer_and_is_what_the_planner_runs(jzlib
             assert "M %d N %d K %d:" % (M, N, K) in plan, (line, plan)
             assert "tile %dx%dx%d, %d wavefronts, ring %d," % (bm, bn, bk, wv, nst) in plan, (line, plan)
         assert entries == 3 * len(layers) - sum(1 for cs in layers if cs.first), (model, entries)
+
+
+def test_layer_entry_points_validate_on_the_host_before_any_launch(jzlib):
+    """Shape, null, alignment and aliasing mistakes are caught from the arguments alone (the pointers below are never
+    dereferenced: every call returns before a launch), and empty inputs are accepted without touching the GPU."""
+    L, E = jzlib.lib(), jzlib
+    A, B, C_ = 0x10000000, 0x20000000, 0x30000000       # fake, well separated, 16-byte aligned device addresses
+    f = ctypes.c_float
+    assert L.jz_add_fwd(0, None, None, 1, None, None) == E.JZ_OK
+    assert L.jz_add_fwd(12, A, B, 1, C_, None) == E.JZ_ERR_SHAPE
+    assert L.jz_add_fwd(16, A, None, 1, C_, None) == E.JZ_ERR_NULL
+    assert L.jz_add_fwd(16, A, B + 8, 1, C_, None) == E.JZ_ERR_ALIGN
+    assert L.jz_add_fwd(64, A, B, 0, A + 32, None) == E.JZ_ERR_ALIAS
+    assert L.jz_relu_bwd(0, None, None, None, None) == E.JZ_OK
+    assert L.jz_relu_bwd(64, A, B, A, None) == E.JZ_ERR_ALIAS
+    assert L.jz_maxpool_fwd(0, 8, 8, 8, 3, 2, 1, None, None, None, None) == E.JZ_OK
+    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 0, 1, A, B, None, None) == E.JZ_ERR_SHAPE
+    assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 1, A, B, C_ + 4, None) == E.JZ_ERR_ALIGN
+    assert L.jz_maxpool_bwd(1, 8, 8, 8, 3, 2, 1, None, None, A, B, None) == E.JZ_ERR_NULL
+    assert L.jz_avgpool_fwd(0, 49, 2048, None, None, None) == E.JZ_OK
+    assert L.jz_avgpool_fwd(2, 49, 2044, A, B, None) == E.JZ_ERR_SHAPE
+    assert L.jz_avgpool_bwd(2, 49, 2048, None, B, None) == E.JZ_ERR_NULL
+    assert L.jz_bias_add(0, 8, None, None, None, None) == E.JZ_OK
+    assert L.jz_bias_add(4, 8, A, B, B, None) == E.JZ_ERR_ALIAS
+    assert L.jz_bias_grad(4, 8, A, None, None) == E.JZ_ERR_NULL
+    assert L.jz_softmax_xent_bwd(0, 1000, None, None, f(1.0), None, None, None, None) == E.JZ_OK
+    assert L.jz_softmax_xent_bwd(4, 1000, A, B, f(-1.0), None, C_, C_ + 0x100000, None) == E.JZ_ERR_SHAPE
+    assert L.jz_softmax_xent_bwd(4, 1000, A, B, f(1.0), None, A, C_, None) == E.JZ_ERR_ALIAS
+    assert L.jz_softmax_xent_bwd(4, 1000, A, B, f(1.0), 0x40000004, C_, C_ + 0x100000, None) == E.JZ_ERR_ALIGN
+    assert L.jz_loss_scale_init(None, f(1.0), None) == E.JZ_ERR_NULL
+    assert L.jz_loss_scale_init(A, f(0.0), None) == E.JZ_ERR_SHAPE
+    assert L.jz_loss_scale_init(A + 4, f(1.0), None) == E.JZ_ERR_ALIGN
+
+
+def test_fused_convolution_batch_norm_workspace_and_validation(jzlib):
+    L, E = jzlib.lib(), jzlib
+    n, m = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    for cs_args in ((64, 56, 56, 64, 64, 3, 3, 1, 1), (64, 56, 56, 64, 256, 1, 1, 1, 0), (64, 224, 224, 3, 64, 7, 7, 2, 3)):
+        d = jzlib.conv_desc(*cs_args)
+        assert L.jz_conv2d_bn_relu_fwd_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == E.JZ_OK
+        assert L.jz_conv2d_workspace_bytes(E.JZ_FWD, ctypes.byref(d), ctypes.byref(m)) == E.JZ_OK
+        # room for the convolution's own workspace, the per-tile (or per-slab) sums and the coefficients
+        assert n.value >= m.value + 4 * d.K * 4 and n.value < m.value + (64 << 20)
+    d = jzlib.conv_desc(2, 8, 8, 16, 4096, 1, 1, 1, 0)                  # more channels than the normalization handles
+    assert L.jz_conv2d_bn_relu_fwd_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == E.JZ_ERR_UNSUPPORTED
+    d = jzlib.conv_desc(2, 8, 8, 16, 32, 3, 3, 1, 1)
+    assert L.jz_conv2d_bn_relu_fwd_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == E.JZ_OK
+    A = 0x10000000
+    f = ctypes.c_float
+    args = lambda **o: [o.get(k, A + i * 0x1000000) for i, k in enumerate(("x", "w", "g", "b"))]
+    assert L.jz_conv2d_bn_relu_fwd(ctypes.byref(d), *args(), f(1e-5), None, 1, A + 0x5000000, None, A + 0x7000000, A + 0x8000000,
+                                   A + 0x9000000, n.value, None) == E.JZ_ERR_NULL
+    assert L.jz_conv2d_bn_relu_fwd(ctypes.byref(d), *args(), f(-1.0), None, 1, A + 0x5000000, A + 0x6000000, A + 0x7000000, A + 0x8000000,
+                                   A + 0x9000000, n.value, None) == E.JZ_ERR_SHAPE
+    assert L.jz_conv2d_bn_relu_fwd(ctypes.byref(d), *args(), f(1e-5), None, 1, A + 0x5000000, A + 0x6000000, A + 0x7000000, A + 0x8000000,
+                                   A + 0x9000000, n.value - 1, None) == E.JZ_ERR_WORKSPACE
+    assert L.jz_conv2d_bn_relu_fwd(ctypes.byref(d), *args(), f(1e-5), A + 0x6000000, 1, A + 0x5000000, A + 0x6000000, A + 0x7000000,
+                                   A + 0x8000000, A + 0x9000000, n.value, None) == E.JZ_ERR_ALIAS
