@@ -190,3 +190,66 @@ def test_side_stream_schedule_gives_the_same_bits(jz):
     for a, b in zip(out[0][:4], out[1][:4]):
         assert np.array_equal(a.view(np.uint32 if a.dtype == np.float32 else np.uint16), b.view(np.uint32 if b.dtype == np.float32 else np.uint16))
     assert out[0][4] == out[1][4]
+
+
+def test_full_size_chained_step_on_sampled_outputs(jz):
+    """The step bench.py --workload chain times (N = 64, 224x224, fused calls): the GPU computes whole tensors, the oracle
+    (a) a seeded sample of convolution outputs one by one, on the operands that launch read, (b) whole tensors of the
+    cheap layers, exactly, and (c) the statistics, gamma / beta gradients and outputs of three batch normalizations."""
+    import jzt
+    from paper_1807_11205_amd import resnet50
+    net = resnet50.ResNet50Chain(batch=64, image=224, initial_loss_scale=1024.0)
+    net.forward(); net.backward()
+    torch.cuda.synchronize()
+    assert np.isfinite(net.mean_loss())
+    rng = np.random.default_rng(5)
+    ops = {(o.kind, o.name): o for o in net.trace}
+    odesc = lambda d: oracle.conv_desc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
+
+    # (a) sampled convolution outputs: forward (inside the fused call), backward-data, backward-weight
+    for name in ("stem", "s2b1c", "s2b1p", "s3b1a", "s4b3b", "s5b3c"):
+        op = ops[("conv_bn_fwd", name)]
+        d = op.params["desc"]
+        x, w, c = np16(op.ins[0]), np16(op.ins[1]), np16(op.outs[0])
+        idx = rng.integers(0, c.size, size=8192)
+        jzt.check_half_output(c[idx], oracle.conv_fwd_at(odesc(d), x, w, idx), 1e-3, "fwd " + name)
+        ow = ops[("conv_bwd_weight", name)]
+        dw = np16(ow.outs[0])
+        n = int(max(256, min(dw.size, 3e8 // (d.N * d.P * d.Q))))
+        idx = rng.integers(0, dw.size, size=n)
+        jzt.check_half_output(dw[idx], oracle.conv_bwd_weight_at(odesc(d), np16(ow.ins[0]), np16(ow.ins[1]), idx), 1e-3, "bwd_weight " + name)
+        if name != "stem":
+            od_ = ops[("conv_bwd_data", name)]
+            dx = np16(od_.outs[0])
+            idx = rng.integers(0, dx.size, size=8192)
+            jzt.check_half_output(dx[idx], oracle.conv_bwd_data_at(odesc(d), np16(od_.ins[0]), np16(od_.ins[1]), idx), 1e-3, "bwd_data " + name)
+
+    # (b) whole tensors of the cheap layers (per-image layers on the first images, where the oracle loops in Python)
+    counts = {}
+    for key in (("relu_bwd", "s2b1.add"), ("add_fwd", "s2b2.dx"), ("add_fwd", "s5b1.dx"), ("avgpool_fwd", "pool5"), ("avgpool_bwd", "pool5"),
+                ("bias_add", "fc.b"), ("bias_grad", "fc.b"), ("softmax_xent", "loss"), ("fc_fwd", "fc"), ("fc_bwd_data", "fc"), ("fc_bwd_weight", "fc")):
+        check_op(ops[key], counts)
+    mp, mb = ops[("maxpool_fwd", "pool1")], ops[("maxpool_bwd", "pool1")]
+    p = mp.params
+    n2, per_in, per_out = 2, p["H"] * p["W"] * p["C"], 56 * 56 * p["C"]
+    x = np16(mp.ins[0])[:n2 * per_in].reshape(n2, p["H"], p["W"], p["C"])
+    ry, rarg = oracle.maxpool_fwd(x, 3, 2, 1)
+    assert np.array_equal(np16(mp.outs[0])[:n2 * per_out].view(np.uint16), ry.ravel().view(np.uint16))
+    r64, r16 = oracle.maxpool_bwd(x, np16(mb.ins[1])[:n2 * per_out].reshape(n2, 56, 56, p["C"]), 3, 2, 1)
+    one_step_of_fp16(np16(mb.outs[0])[:n2 * per_in], r64, r16, "maxpool_bwd")
+
+    # (c) batch normalization on whole tensors: a plain one, one with the residual, and their backward passes
+    for name in ("s2b1a", "s4b1a", "s5b3c"):
+        op = ops[("conv_bn_fwd", name)]
+        rows, C = op.params["rows"], op.params["C"]
+        c = np16(op.outs[0]).reshape(rows, C)
+        if op.ins[4] is None:
+            y64, _, m64, i64 = oracle.bn_relu_fwd(c, np16(op.ins[2]), np16(op.ins[3]), op.params["eps"], relu=op.params["relu"])
+        else:
+            y64, _, m64, i64 = oracle.bn_add_relu_fwd(c, np16(op.ins[4]).reshape(rows, C), np16(op.ins[2]), np16(op.ins[3]), op.params["eps"],
+                                                      relu=op.params["relu"])
+        assert np.all(np.abs(np16(op.outs[2]) - m64) <= 1e-5 * (np.abs(m64) + 1.0 / i64)), name
+        assert np.all(np.abs(np16(op.outs[3]) - i64) <= 1e-4 * i64), name
+        assert rel_l2(np16(op.outs[1]), y64) <= 1e-3, name
+        del y64
+        check_op(ops[("bn_bwd", name + ".bn")], counts)
