@@ -28,7 +28,7 @@ class Op:
 
     def __init__(self, kind, name, params, ins, outs, call, side_call=None):
         self.kind, self.name, self.params, self.ins, self.outs, self.call = kind, name, params, ins, outs, call
-        self.side_call = side_call      # the same launch bound to the side stream's workspace (weight gradients only)
+        self.side_call = side_call      # weight gradients only: workspace -> the same launch bound to that workspace
 
 
 class ResNet50Chain:
@@ -74,7 +74,8 @@ class ResNet50Chain:
         self.bwd_ops: List[Op] = []
         self._build()
         self.ws = torch.zeros(self._ws_bytes, dtype=torch.uint8, device=dev)
-        self.side_ws = torch.zeros(self._ws_bytes, dtype=torch.uint8, device=dev)
+        self.side_ws = []               # one workspace per side stream, made on first use
+        self._side_calls = {}
         self._events = {}
         for bind in self._pending_ws:
             bind(self.ws)
@@ -99,14 +100,14 @@ class ResNet50Chain:
         d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
         self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
         kind = {api.JZ_FWD: "conv_fwd", api.JZ_BWD_DATA: "conv_bwd_data", api.JZ_BWD_WEIGHT: "conv_bwd_weight"}[op]
-        side = self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, self.side_ws)) if op == api.JZ_BWD_WEIGHT else None
+        side = (lambda ws: api.bind_conv2d(op, d, a, b, out, ws)) if op == api.JZ_BWD_WEIGHT else None
         return Op(kind, name, dict(desc=d), [a, b], [out], self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, ws)), side)
 
     def _fc(self, mode, a, b, out, name):
         B, I, O = self.N, self.fc.I, self.fc.O
         self._ws_bytes = max(self._ws_bytes, api.jz_gemm_fc_workspace_bytes(mode, B, I, O))
         kind = {api.JZ_FWD: "fc_fwd", api.JZ_BWD_DATA: "fc_bwd_data", api.JZ_BWD_WEIGHT: "fc_bwd_weight"}[mode]
-        side = self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, self.side_ws)) if mode == api.JZ_BWD_WEIGHT else None
+        side = (lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)) if mode == api.JZ_BWD_WEIGHT else None
         return Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)), side)
 
     def _bn_fwd(self, cs, x, y, relu, name):
@@ -243,28 +244,38 @@ class ResNet50Chain:
             op.call(stream)
 
     def backward(self, stream=None, side=None):
-        """With a side stream the weight-gradient GEMMs (which nothing in the backward pass waits for) run there,
-        beside the chain of activation gradients; the caller's stream waits for them at the end."""
+        """With side streams (one stream or a list) the weight-gradient GEMMs, which nothing in the backward pass waits
+        for, run there round-robin beside the chain of activation gradients; the caller's stream waits for them at the end."""
         if side is None:
             for op in self.bwd_ops:
                 op.call(stream)
             return
+        sides = list(side) if isinstance(side, (list, tuple)) else [side]
+        while len(self.side_ws) < len(sides):
+            self.side_ws.append(torch.zeros(self._ws_bytes, dtype=torch.uint8, device=self.device))
         main = stream if stream is not None else torch.cuda.current_stream()
+        k = 0
         for i, op in enumerate(self.bwd_ops):
             if op.side_call is None:
                 op.call(main)
                 continue
+            j = k % len(sides)
+            k += 1
+            call = self._side_calls.get((i, j))
+            if call is None:
+                call = self._side_calls[(i, j)] = op.side_call(self.side_ws[j])
             ev = self._events.get(i)
             if ev is None:
                 ev = self._events[i] = torch.cuda.Event()
             ev.record(main)                 # the gradient this GEMM reads has just been produced on the main stream
-            side.wait_event(ev)
-            op.side_call(side)
-        done = self._events.get("done")
-        if done is None:
-            done = self._events["done"] = torch.cuda.Event()
-        done.record(side)
-        main.wait_event(done)
+            sides[j].wait_event(ev)
+            call(sides[j])
+        for j, s_ in enumerate(sides):
+            done = self._events.get(("done", j))
+            if done is None:
+                done = self._events[("done", j)] = torch.cuda.Event()
+            done.record(s_)
+            main.wait_event(done)
 
     def update(self, stream=None):
         self.trace[-1].call(stream)
