@@ -30,6 +30,7 @@ LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32
 # HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very workload (default batch and
 # variant), scaled by the same counters' readings for a 1 GiB copy; the runs are summarised under profiles/.
 MEASURED_BN_HBM_BYTES_PER_STEP = 13.94e9     # bench.py --workload bn at N = 64 (profiles/bench_bn_resnet50_n64_kernel_stats.txt)
+MEASURED_CHAIN_HBM_BYTES_PER_STEP = 26.24e9   # --workload chain, N = 64, fused calls (profiles/bench_chain_resnet50_n64_hbm_traffic.txt)
 MEASURED_GEMM_HBM_BYTES_PER_STEP = 9.61e9   # all conv/FC launches with their split-K reductions and packing kernels
 MEASURED_LARS_HBM_BYTES_PER_UPDATE = 562e6   # gradient norm pass 51 MB + update pass 511 MB
 
@@ -460,7 +461,11 @@ def chain_workload(args):
         "phases_ms": {"forward_and_loss": ph[0], "backward": ph[1], "lars_update": ph[2], "gpu_total": gpu_ms},
         "roofline": {"kernel": "whole step (GEMM flops of the convolutions and the classifier over the step's GPU time)",
                      "bound": "mfma", "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None}}))
+                     "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None},
+        "hbm": ({"bytes_per_step": MEASURED_CHAIN_HBM_BYTES_PER_STEP, "achieved": MEASURED_CHAIN_HBM_BYTES_PER_STEP / (gpu_ms * 1e-3) / 1e9,
+                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": MEASURED_CHAIN_HBM_BYTES_PER_STEP / (gpu_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                 "note": "HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (copy-kernel scaled) over this step's time"}
+                if args.batch == 64 and net.fused else None)}))
 
 
 def cpu_baseline(sample_batch=8):
