@@ -285,6 +285,14 @@ class ResNet50Chain:
         self.backward(stream, side)
         self.update(stream)
 
+    def set_batch(self, images16: torch.Tensor, labels: torch.Tensor, stream=None):
+        """Copies a new mini-batch (FP16 NHWC images, int32 labels) into the buffers the launches are bound to."""
+        if images16.dtype != torch.float16 or images16.numel() != self.x.numel() or labels.numel() != self.N:
+            raise ValueError("expected %d FP16 image values and %d labels" % (self.x.numel(), self.N))
+        with torch.cuda.stream(stream if stream is not None else torch.cuda.current_stream()):
+            self.x.copy_(images16.reshape(-1), non_blocking=True)
+            self.labels.copy_(labels.reshape(-1).to(torch.int32), non_blocking=True)
+
     def mean_loss(self) -> float:
         torch.cuda.synchronize()
         return float(self.loss.double().mean().item())

@@ -253,3 +253,20 @@ def test_full_size_chained_step_on_sampled_outputs(jz):
         assert rel_l2(np16(op.outs[1]), y64) <= 1e-3, name
         del y64
         check_op(ops[("bn_bwd", name + ".bn")], counts)
+
+
+def test_a_new_batch_changes_the_step_and_the_old_one_reproduces_it(jz):
+    from paper_1807_11205_amd import resnet50
+    net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=128.0)
+    x0, l0 = net.x.clone(), net.labels.clone()
+    net.forward(); net.backward(); torch.cuda.synchronize()
+    g0, loss0 = np16(net.grad).copy(), net.mean_loss()
+    gen = torch.Generator().manual_seed(9)
+    net.set_batch(torch.randn(x0.numel(), generator=gen).to(torch.float16).cuda(), torch.randint(0, 1000, (4,), generator=gen).cuda())
+    net.forward(); net.backward(); torch.cuda.synchronize()
+    assert net.mean_loss() != loss0 and not np.array_equal(np16(net.grad).view(np.uint16), g0.view(np.uint16))
+    net.set_batch(x0, l0)
+    net.forward(); net.backward(); torch.cuda.synchronize()
+    assert net.mean_loss() == loss0 and np.array_equal(np16(net.grad).view(np.uint16), g0.view(np.uint16))
+    with pytest.raises(ValueError):
+        net.set_batch(x0[:-8], l0)
