@@ -32,7 +32,8 @@ size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 struct BnPlan {
   int64_t rows = 0;
   int C = 0, cpr = 0;        // 16-byte chunks per row
-  int rpp = 0;               // rows one pass of a workgroup covers (BN_THREADS / cpr; lanes beyond rpp * cpr idle)
+  int csplit = 1;            // workgroups that share a slab of rows, each with cpr / csplit of the chunks (wide, short tensors)
+  int rpp = 0;               // rows one pass of a workgroup covers (BN_THREADS / (cpr / csplit); lanes beyond that idle)
   int64_t rows_per_slab = 0; // a multiple of rpp
   int slabs = 0;
   size_t off_part = 0, off_coef = 0, total = 0;  // workspace: [slabs][2][C] float partial sums, [4][C] float coefficients
@@ -45,15 +46,23 @@ int make_bn_plan(int64_t rows, int channels, BnPlan* p) {
   p->rows = rows;
   p->C = channels;
   p->cpr = channels / 8;
-  p->rpp = BN_THREADS / p->cpr;
   // at most BN_TARGET_SLABS slabs, and at least 16 passes of the workgroup and 64 rows per slab: small tensors get fewer
-  // slabs, so that the partial sums stay small beside the tensor
-  int64_t per = (rows + BN_TARGET_SLABS - 1) / BN_TARGET_SLABS;
-  if (per < 16 * (int64_t)p->rpp) per = 16 * (int64_t)p->rpp;
-  if (per < 64) per = 64;
-  per = (per + p->rpp - 1) / p->rpp * p->rpp;
-  p->rows_per_slab = per;
-  p->slabs = (int)((rows + per - 1) / per);
+  // slabs, so that the partial sums stay small beside the tensor.  A wide tensor with few rows would then leave most of
+  // the chip idle (2048 channels x 3136 rows: 49 slabs), so its slabs are shared by csplit workgroups that take a range
+  // of at least 32 chunks (512 contiguous bytes of a row) each: more workgroups, the same number of partial sums.
+  for (int cs = 1;; cs *= 2) {
+    const int cpr_l = p->cpr / cs;
+    p->csplit = cs;
+    p->rpp = BN_THREADS / cpr_l;
+    int64_t per = (rows + BN_TARGET_SLABS - 1) / BN_TARGET_SLABS;
+    const int64_t min_passes = cs > 1 ? 8 : 16;
+    if (per < min_passes * (int64_t)p->rpp) per = min_passes * (int64_t)p->rpp;
+    if (per < 64) per = 64;
+    per = (per + p->rpp - 1) / p->rpp * p->rpp;
+    p->rows_per_slab = per;
+    p->slabs = (int)((rows + per - 1) / per);
+    if ((int64_t)p->slabs * cs >= 384 || cs == 8 || cpr_l % 2 != 0 || cpr_l / 2 < 32) break;
+  }
   p->off_part = 0;
   p->off_coef = up256((size_t)p->slabs * 2 * channels * sizeof(float));
   p->total = p->off_coef + up256((size_t)4 * channels * sizeof(float));
@@ -93,11 +102,14 @@ template <int MODE>
 __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__ x, const uint4* __restrict__ y,
                                                       const uint4* __restrict__ dy, const float* __restrict__ mean,
                                                       const float* __restrict__ invstd, float* __restrict__ part, int64_t rows,
-                                                      int C, int cpr, int rpp, int64_t rows_per_slab, int relu) {
+                                                      int C, int cpr, int rpp, int64_t rows_per_slab, int relu, int csplit) {
   __shared__ float red[2][BN_THREADS][8];
   const int tid = threadIdx.x;
-  const int chunk = tid % cpr, rsub = tid / cpr;
-  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  const int cpr_l = cpr / csplit;  // chunks of a row this workgroup handles: [cfirst, cfirst + cpr_l)
+  const int slab = blockIdx.x / csplit, cfirst = (blockIdx.x % csplit) * cpr_l;
+  const int chunk_l = tid % cpr_l, rsub = tid / cpr_l;
+  const int chunk = cfirst + chunk_l;
+  const int64_t r0 = (int64_t)slab * rows_per_slab;
   int64_t r1 = r0 + rows_per_slab;
   if (r1 > rows) r1 = rows;
   float s0[8], s1[8], mu[8], is[8];
@@ -169,10 +181,10 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
     for (int j = 1; j < rpp; ++j)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        s0[e] += red[0][j * cpr + chunk][e];
-        s1[e] += red[1][j * cpr + chunk][e];
+        s0[e] += red[0][j * cpr_l + chunk_l][e];
+        s1[e] += red[1][j * cpr_l + chunk_l][e];
       }
-    float* p0 = part + ((size_t)blockIdx.x * 2) * C + chunk * 8;
+    float* p0 = part + ((size_t)slab * 2) * C + chunk * 8;
     float* p1 = p0 + C;
     *reinterpret_cast<float4*>(p0) = make_float4(s0[0], s0[1], s0[2], s0[3]);
     *reinterpret_cast<float4*>(p0 + 4) = make_float4(s0[4], s0[5], s0[6], s0[7]);
@@ -358,8 +370,8 @@ extern "C" int jz_bn_relu_fwd(int64_t rows, int channels, const void* x16, const
   float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_part);
   float* coef = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_coef);
   const uint4* x = static_cast<const uint4*>(x16);
-  hipLaunchKernelGGL(bn_stats<0>, dim3((unsigned)p.slabs), dim3(BN_THREADS), 0, st, x, nullptr, nullptr, nullptr, nullptr, part,
-                     rows, channels, p.cpr, p.rpp, p.rows_per_slab, 0);
+  hipLaunchKernelGGL(bn_stats<0>, dim3((unsigned)(p.slabs * p.csplit)), dim3(BN_THREADS), 0, st, x, nullptr, nullptr, nullptr, nullptr,
+                     part, rows, channels, p.cpr, p.rpp, p.rows_per_slab, 0, p.csplit);
   if ((rc = jz::launch_status()) != JZ_OK) return rc;
   hipLaunchKernelGGL(bn_fwd_final, dim3((unsigned)((channels + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part,
                      p.slabs, channels, 1.0 / (double)rows, eps, gamma, beta, save_mean, save_invstd, coef);
@@ -394,8 +406,8 @@ extern "C" int jz_bn_relu_bwd(int64_t rows, int channels, const void* x16, const
   const uint4* x = static_cast<const uint4*>(x16);
   const uint4* y = static_cast<const uint4*>(y16);
   const uint4* dy = static_cast<const uint4*>(dy16);
-  hipLaunchKernelGGL(bn_stats<1>, dim3((unsigned)p.slabs), dim3(BN_THREADS), 0, st, x, y, dy, save_mean, save_invstd, part, rows,
-                     channels, p.cpr, p.rpp, p.rows_per_slab, relu ? 1 : 0);
+  hipLaunchKernelGGL(bn_stats<1>, dim3((unsigned)(p.slabs * p.csplit)), dim3(BN_THREADS), 0, st, x, y, dy, save_mean, save_invstd, part, rows,
+                     channels, p.cpr, p.rpp, p.rows_per_slab, relu ? 1 : 0, p.csplit);
   if ((rc = jz::launch_status()) != JZ_OK) return rc;
   hipLaunchKernelGGL(bn_bwd_final, dim3((unsigned)((channels + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part,
                      p.slabs, channels, 1.0 / (double)rows, gamma, save_mean, save_invstd, static_cast<unsigned short*>(dgamma16),
@@ -479,8 +491,8 @@ extern "C" int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, 
   int slabs = p.tiles_m;
   if (slabs == 0) {  // this convolution kernel cannot leave the sums: one more pass over its output
     slabs = p.bn.slabs;
-    hipLaunchKernelGGL(bn_stats<0>, dim3((unsigned)slabs), dim3(BN_THREADS), 0, st, c, nullptr, nullptr, nullptr, nullptr, part,
-                       rows, C, p.bn.cpr, p.bn.rpp, p.bn.rows_per_slab, 0);
+    hipLaunchKernelGGL(bn_stats<0>, dim3((unsigned)(slabs * p.bn.csplit)), dim3(BN_THREADS), 0, st, c, nullptr, nullptr, nullptr, nullptr,
+                       part, rows, C, p.bn.cpr, p.bn.rpp, p.bn.rows_per_slab, 0, p.bn.csplit);
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
   }
   hipLaunchKernelGGL(bn_fwd_final, dim3((unsigned)((C + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part, slabs, C,
