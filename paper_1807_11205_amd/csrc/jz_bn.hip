@@ -54,14 +54,17 @@ int make_bn_plan(int64_t rows, int channels, BnPlan* p) {
     const int cpr_l = p->cpr / cs;
     p->csplit = cs;
     p->rpp = BN_THREADS / cpr_l;
-    int64_t per = (rows + BN_TARGET_SLABS - 1) / BN_TARGET_SLABS;
-    const int64_t min_passes = cs > 1 ? 8 : 16;
-    if (per < min_passes * (int64_t)p->rpp) per = min_passes * (int64_t)p->rpp;
-    if (per < 64) per = 64;
-    per = (per + p->rpp - 1) / p->rpp * p->rpp;
-    p->rows_per_slab = per;
-    p->slabs = (int)((rows + per - 1) / per);
-    if ((int64_t)p->slabs * cs >= 384 || cs == 8 || cpr_l % 2 != 0 || cpr_l / 2 < 32) break;
+    // fewer passes per workgroup (16, 8, 4) until at least 256 workgroups exist
+    for (int min_passes = 16; min_passes >= 4; min_passes /= 2) {
+      int64_t per = (rows + BN_TARGET_SLABS - 1) / BN_TARGET_SLABS;
+      if (per < min_passes * (int64_t)p->rpp) per = min_passes * (int64_t)p->rpp;
+      if (per < 32) per = 32;
+      per = (per + p->rpp - 1) / p->rpp * p->rpp;
+      p->rows_per_slab = per;
+      p->slabs = (int)((rows + per - 1) / per);
+      if ((int64_t)p->slabs * cs >= 256) break;
+    }
+    if ((int64_t)p->slabs * cs >= 256 || cs == 8 || cpr_l % 2 != 0 || cpr_l / 2 < 32) break;
   }
   p->off_part = 0;
   p->off_coef = up256((size_t)p->slabs * 2 * channels * sizeof(float));
