@@ -197,6 +197,8 @@ int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void*
  * JZ_ERR_ALIGN otherwise); nothing is allocated, everything is enqueued on hip_stream; empty inputs are JZ_OK.
  *   jz_add_fwd      y = a + b, followed by max(., 0) when relu != 0 (the residual connection).  y may be a or b.
  *   jz_relu_bwd     dx = dy where the forward output y is > 0, else 0.  dx may be dy.
+ *   jz_relu_bwd_sum dx = RNE16(dya + dyb) where y > 0, else 0: the same as jz_add_fwd (no ReLU) followed by jz_relu_bwd, bit for
+ *                   bit, in one pass (a block output whose gradient arrives from two consumers).  dx may be dya or dyb.
  *   jz_maxpool_fwd  x[N,H,W,C] -> y[N,P,Q,C], P = (H + 2 pad - window) / stride + 1 (same for Q); padding never wins.
  *                   arg8 (may be NULL; DEVICE, 8-byte aligned, one byte per output element) receives the position
  *                   r * window + s inside its window of each output's first maximum in (row, column) order.
@@ -216,6 +218,7 @@ int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, const void*
  *                   and a zero gradient row.  classes need not be a multiple of 8 here (2-byte alignment suffices). */
 int jz_add_fwd(int64_t n, const void* a16, const void* b16, int relu, void* y16, void* hip_stream);
 int jz_relu_bwd(int64_t n, const void* y16, const void* dy16, void* dx16, void* hip_stream);
+int jz_relu_bwd_sum(int64_t n, const void* y16, const void* dya16, const void* dyb16, void* dx16, void* hip_stream);
 int jz_maxpool_fwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, void* y16, void* arg8,
                    void* hip_stream);
 int jz_maxpool_bwd(int N, int H, int W, int C, int window, int stride, int pad, const void* x16, const void* arg8,

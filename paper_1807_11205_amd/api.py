@@ -23,7 +23,7 @@ EXPORTS = [
     "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
-    "jz_add_fwd", "jz_relu_bwd", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
+    "jz_add_fwd", "jz_relu_bwd", "jz_relu_bwd_sum", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
     "jz_bias_grad", "jz_softmax_xent_bwd", "jz_conv2d_bn_relu_fwd_workspace_bytes", "jz_conv2d_bn_relu_fwd",
     "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd",
     "jz_status_string", "jz_version",
@@ -100,6 +100,7 @@ def lib() -> ctypes.CDLL:
         L.jz_bn_relu_bwd.argtypes = [i64, ci, vp, vp, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
         L.jz_add_fwd.argtypes = [i64, vp, vp, ci, vp, vp]
         L.jz_relu_bwd.argtypes = [i64, vp, vp, vp, vp]
+        L.jz_relu_bwd_sum.argtypes = [i64, vp, vp, vp, vp, vp]
         L.jz_maxpool_fwd.argtypes = [ci] * 7 + [vp, vp, vp, vp]
         L.jz_maxpool_bwd.argtypes = [ci] * 7 + [vp, vp, vp, vp, vp]
         L.jz_avgpool_fwd.argtypes = [ci, ci, ci, vp, vp, vp]
@@ -375,6 +376,11 @@ def jz_add_fwd(a, b, y, relu=True, stream=None):
 def jz_relu_bwd(y, dy, dx, stream=None):
     n = y.numel()
     _check(lib().jz_relu_bwd(n, _h(y, n, "y"), _h(dy, n, "dy"), _h(dx, n, "dx"), _stream(stream)), "jz_relu_bwd")
+
+
+def jz_relu_bwd_sum(y, dya, dyb, dx, stream=None):
+    n = y.numel()
+    _check(lib().jz_relu_bwd_sum(n, _h(y, n, "y"), _h(dya, n, "dya"), _h(dyb, n, "dyb"), _h(dx, n, "dx"), _stream(stream)), "jz_relu_bwd_sum")
 
 
 def pool_out(size, window, stride, pad):

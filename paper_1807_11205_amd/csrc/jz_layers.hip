@@ -65,6 +65,26 @@ __global__ __launch_bounds__(LY_THREADS) void add_kernel(const uint4* __restrict
   }
 }
 
+// dx = (y > 0) ? RNE16(dya + dyb) : 0: a block output whose gradient arrives as two contributions (the next block's
+// first convolution and its shortcut); the sum is exact in FP32 and rounded once, as a separate add would round it
+__global__ __launch_bounds__(LY_THREADS) void relu_bwd_sum_kernel(const uint4* __restrict__ y, const uint4* __restrict__ dya,
+                                                                  const uint4* __restrict__ dyb, uint4* __restrict__ dx, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * LY_THREADS + threadIdx.x; i < n8; i += (int64_t)gridDim.x * LY_THREADS) {
+    float fy[8], fa[8], fb[8];
+    unpack8(y[i], fy);
+    unpack8(dya[i], fa);
+    unpack8(dyb[i], fb);
+    float s[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s[k] = fa[k] + fb[k];
+    const uint4 o = pack8(s);
+    unsigned ow[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) ow[k] = (fy[2 * k] > 0.f ? (ow[k] & 0xffffu) : 0u) | (fy[2 * k + 1] > 0.f ? (ow[k] & 0xffff0000u) : 0u);
+    dx[i] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+  }
+}
+
 __global__ __launch_bounds__(LY_THREADS) void relu_bwd_kernel(const uint4* __restrict__ y, const uint4* __restrict__ dy,
                                                               uint4* __restrict__ dx, int64_t n8) {
   for (int64_t i = (int64_t)blockIdx.x * LY_THREADS + threadIdx.x; i < n8; i += (int64_t)gridDim.x * LY_THREADS) {
@@ -397,6 +417,22 @@ extern "C" int jz_relu_bwd(int64_t n, const void* y16, const void* dy16, void* d
   if (jz::overlaps(dx16, nb, y16, nb) || (dx16 != dy16 && jz::overlaps(dx16, nb, dy16, nb))) return JZ_ERR_ALIAS;
   hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid_for(n / 8)), dim3(LY_THREADS), 0, static_cast<hipStream_t>(hip_stream),
                      static_cast<const uint4*>(y16), static_cast<const uint4*>(dy16), static_cast<uint4*>(dx16), n / 8);
+  return jz::launch_status();
+}
+
+extern "C" int jz_relu_bwd_sum(int64_t n, const void* y16, const void* dya16, const void* dyb16, void* dx16, void* hip_stream) {
+  int rc = check_elems(n);
+  if (rc != JZ_OK) return rc;
+  if (n == 0) return JZ_OK;
+  if (!y16 || !dya16 || !dyb16 || !dx16) return JZ_ERR_NULL;
+  if (!jz::aligned16(y16) || !jz::aligned16(dya16) || !jz::aligned16(dyb16) || !jz::aligned16(dx16)) return JZ_ERR_ALIGN;
+  const size_t nb = (size_t)n * 2;
+  if (jz::overlaps(dx16, nb, y16, nb) || (dx16 != dya16 && jz::overlaps(dx16, nb, dya16, nb)) ||
+      (dx16 != dyb16 && jz::overlaps(dx16, nb, dyb16, nb)))
+    return JZ_ERR_ALIAS;
+  hipLaunchKernelGGL(relu_bwd_sum_kernel, dim3(grid_for(n / 8)), dim3(LY_THREADS), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const uint4*>(y16), static_cast<const uint4*>(dya16), static_cast<const uint4*>(dyb16),
+                     static_cast<uint4*>(dx16), n / 8);
   return jz::launch_status();
 }
 

@@ -181,6 +181,7 @@ class ResNet50Chain:
                             lambda stream=None, dy=dcur: api.jz_maxpool_bwd(N, Hp, Hp, 64, 3, 2, 1, None, dy, da0, arg, stream))] + back_stem)
 
         blocks = sorted({cs.name[:-1] for cs in self.convs[1:]}, key=lambda n: (int(n[1]), int(n[3:])))
+        below = None      # the block underneath: (its backward segment, its output, the buffer for the gradient of its sum)
         for nm in blocks:
             a, b, c = by_name[nm + "a"], by_name[nm + "b"], by_name[nm + "c"]
             p = by_name.get(nm + "p")
@@ -205,7 +206,17 @@ class ResNet50Chain:
                 F.append(add_op(nm + ".add", zc, shortcut, out, True))
             relu_b = Op("relu_bwd", nm + ".add", {}, [out, dout], [ds],
                         lambda stream=None, y=out, dy=dout, dx=ds: api.jz_relu_bwd(y, dy, dx, stream))
-            segments.append([relu_b] + back_c + back_b + back_a + back_p + [add_op(nm + ".dx", dxa, dshort, dx_out, False)])
+            seg = [relu_b] + back_c + back_b + back_a + back_p
+            if self.fused and below is not None:
+                # the two contributions to this block's input gradient are added inside the ReLU gradient of the block
+                # underneath (which runs after this segment) instead of by a launch of their own
+                b_seg, b_out, b_ds = below
+                b_seg[0] = Op("relu_bwd_sum", b_seg[0].name, {}, [b_out, dxa, dshort], [b_ds],
+                              lambda stream=None, y=b_out, a_=dxa, b_=dshort, dx=b_ds: api.jz_relu_bwd_sum(y, a_, b_, dx, stream))
+            else:
+                seg.append(add_op(nm + ".dx", dxa, dshort, dx_out, False))
+            segments.append(seg)
+            below = (seg, out, ds)
             cur, dcur = out, dout
 
         last = by_name[blocks[-1] + "c"]

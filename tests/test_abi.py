@@ -174,6 +174,9 @@ def test_layer_entry_points_validate_on_the_host_before_any_launch(jzlib):
     assert L.jz_add_fwd(64, A, B, 0, A + 32, None) == E.JZ_ERR_ALIAS
     assert L.jz_relu_bwd(0, None, None, None, None) == E.JZ_OK
     assert L.jz_relu_bwd(64, A, B, A, None) == E.JZ_ERR_ALIAS
+    assert L.jz_relu_bwd_sum(0, None, None, None, None, None) == E.JZ_OK
+    assert L.jz_relu_bwd_sum(64, A, B, None, C_, None) == E.JZ_ERR_NULL
+    assert L.jz_relu_bwd_sum(64, A, B, C_, A, None) == E.JZ_ERR_ALIAS      # dx must not be y
     assert L.jz_maxpool_fwd(0, 8, 8, 8, 3, 2, 1, None, None, None, None) == E.JZ_OK
     assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 0, 1, A, B, None, None) == E.JZ_ERR_SHAPE
     assert L.jz_maxpool_fwd(1, 8, 8, 8, 3, 2, 1, A, B, C_ + 4, None) == E.JZ_ERR_ALIGN

@@ -90,6 +90,9 @@ def check_op(op, counts):
         assert np.array_equal(outs[0].view(np.uint16), oracle.add_fwd(ins[0], ins[1], relu=p["relu"])[1].view(np.uint16)), what
     elif k == "relu_bwd":
         assert np.array_equal(outs[0].view(np.uint16), oracle.relu_bwd(ins[0], ins[1]).view(np.uint16)), what
+    elif k == "relu_bwd_sum":
+        want = oracle.relu_bwd(ins[0], oracle.add_fwd(ins[1], ins[2], relu=False)[1])
+        assert np.array_equal(outs[0].view(np.uint16), want.view(np.uint16)), what
     elif k == "maxpool_fwd":
         x = ins[0].reshape(p["N"], p["H"], p["W"], p["C"])
         ry, rarg = oracle.maxpool_fwd(x, p["window"], p["stride"], p["pad"])
@@ -139,7 +142,8 @@ def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused):
         check_op(op, counts)
     assert counts.get("conv_bn_fwd", 0) + counts.get("conv_fwd", 0) == 53 and counts.get("conv_fwd", 0) == counts.get("bn_fwd", 0)
     assert counts["conv_bwd_weight"] == 53 and counts["conv_bwd_data"] == 52
-    assert counts["bn_bwd"] == 53 and counts["add_fwd"] == (16 if fused else 32) and counts["relu_bwd"] == 16
+    assert counts["bn_bwd"] == 53 and counts["add_fwd"] == (1 if fused else 32)
+    assert counts["relu_bwd"] + counts.get("relu_bwd_sum", 0) == 16 and counts.get("relu_bwd_sum", 0) == (15 if fused else 0)
     # every parameter tensor received a gradient from this step (none was left at its initial zero)
     g = np16(net.grad)
     for i, (name, _, _, _) in enumerate(net.tensors):
@@ -226,7 +230,7 @@ def test_full_size_chained_step_on_sampled_outputs(jz):
 
     # (b) whole tensors of the cheap layers (per-image layers on the first images, where the oracle loops in Python)
     counts = {}
-    for key in (("relu_bwd", "s2b1.add"), ("add_fwd", "s2b2.dx"), ("add_fwd", "s5b1.dx"), ("avgpool_fwd", "pool5"), ("avgpool_bwd", "pool5"),
+    for key in (("relu_bwd_sum", "s2b1.add"), ("relu_bwd_sum", "s4b6.add"), ("relu_bwd", "s5b3.add"), ("add_fwd", "s2b1.dx"), ("avgpool_fwd", "pool5"), ("avgpool_bwd", "pool5"),
                 ("bias_add", "fc.b"), ("bias_grad", "fc.b"), ("softmax_xent", "loss"), ("fc_fwd", "fc"), ("fc_bwd_data", "fc"), ("fc_bwd_weight", "fc")):
         check_op(ops[key], counts)
     mp, mb = ops[("maxpool_fwd", "pool1")], ops[("maxpool_bwd", "pool1")]

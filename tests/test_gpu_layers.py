@@ -81,6 +81,16 @@ def test_relu_gradient_is_bit_exact(jz, n):
     tdy = dev(dy)
     jz.jz_relu_bwd(dev(y), tdy, tdy)                                              # in place on dy
     assert same_bits(host(tdy), oracle.relu_bwd(y, dy))
+    # two gradient contributions: the add (one rounding, may overflow to Inf) and the mask in one pass
+    dy2 = h16((44, n), (n,), 8.0)
+    dy2[:8] = np.array([65504, -65504, 1, 2, 3, 4, 5, 6], np.float16); dy[:8] = np.array([65504, -65504, 1, 2, 3, 4, 5, 6], np.float16)
+    y[6:8] = np.float16(1.0)
+    want = oracle.relu_bwd(y, oracle.add_fwd(dy, dy2, relu=False)[1])
+    jz.jz_relu_bwd_sum(dev(y), dev(dy), dev(dy2), dx)
+    assert same_bits(host(dx), want)
+    ta = dev(dy)
+    jz.jz_relu_bwd_sum(dev(y), ta, dev(dy2), ta)
+    assert same_bits(host(ta), want)
 
 
 POOLS = [(2, 112, 112, 64, 3, 2, 1),      # the ResNet-50 stem pool at a small batch
