@@ -274,3 +274,35 @@ def test_a_new_batch_changes_the_step_and_the_old_one_reproduces_it(jz):
     assert net.mean_loss() == loss0 and np.array_equal(np16(net.grad).view(np.uint16), g0.view(np.uint16))
     with pytest.raises(ValueError):
         net.set_batch(x0[:-8], l0)
+
+
+def test_whole_step_replays_from_a_hip_graph_including_the_loss_scale_decisions(jz):
+    """With the loss scale and its controller on the device nothing in a step depends on the host, so the step can be
+    captured once and replayed: every replay (overflowing steps that are skipped and halve the scale, then clean steps)
+    leaves the same bits as the eager step on a second network, with eager work and synchronisations in between."""
+    from paper_1807_11205_amd import resnet50
+    kw = dict(batch=4, image=64, initial_loss_scale=2.0 ** 22, hparams=dict(lr=1.0), policy=dict(growth_interval=3, max_scale=2.0 ** 24))
+    net, ref = resnet50.ResNet50Chain(**kw), resnet50.ResNet50Chain(**kw)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        net.step(s)                      # first launches load the code objects: not inside a capture
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            net.step(s)
+        s.synchronize()
+    ref.step()
+    torch.cuda.synchronize()
+    flags = []
+    for k in range(8):
+        g.replay()
+        ref.step()
+        torch.cuda.synchronize()
+        flags.append(int(net.found_inf.item()))
+        assert flags[-1] == int(ref.found_inf.item())
+        assert jz.loss_scale_state(net.ls_state) == jz.loss_scale_state(ref.ls_state)
+        for a, b in ((net.master, ref.master), (net.momentum, ref.momentum), (net.w16, ref.w16), (net.grad, ref.grad)):
+            assert np.array_equal(np16(a).view(np.uint32 if a.dtype == torch.float32 else np.uint16),
+                                  np16(b).view(np.uint32 if b.dtype == torch.float32 else np.uint16)), "replay %d" % k
+        assert net.mean_loss() == ref.mean_loss()
+    assert 1 in flags and flags[-1] == 0       # the oversized scale overflowed at first, then settled
