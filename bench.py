@@ -418,7 +418,8 @@ def chain_workload(args):
     batch every step."""
     from paper_1807_11205_amd import resnet50
     net = resnet50.ResNet50Chain(batch=args.batch, image=224, initial_loss_scale=65536.0,
-                                 policy=dict(growth_interval=1 << 30, max_scale=2.0 ** 24), fused=not args.unfused)
+                                 policy=dict(growth_interval=1 << 30, max_scale=2.0 ** 24), fused=not args.unfused,
+                                 block_end=not args.no_block_end)
     skipped = 0
     for _ in range(24):                                   # let the controller bring the scale down until steps go through
         net.step()
@@ -515,6 +516,7 @@ def main():
     ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
                     "for the projection shortcuts (forward) and the backward-weight launches (at most 4)")
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a HIP graph (1) or launch eagerly (0); eager launches measured faster here")
+    ap.add_argument("--no-block-end", action="store_true", help="chain workload: ReLU gradient and batch-norm backward at a block's end as two calls")
     ap.add_argument("--unfused", action="store_true", help="chain workload: convolution and batch normalization as two calls")
     ap.add_argument("--dynamic-loss-scale", action="store_true",
                     help="time jz_lars_mp_update_dyn (loss scale and its controller on the device) instead of jz_lars_mp_update")

@@ -176,6 +176,15 @@ int jz_loss_scale_init(jz_loss_scale_state* state_dev, float initial_scale, void
 int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* policy,
                           jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* The backward pass at the end of a residual block, y_out = relu(bn(x) + shortcut), in one call: the gradient of the sum,
+ * g = RNE16(dya [+ dyb]) where y_out > 0 and 0 elsewhere (dyb may be NULL; two contributions arrive when the block above
+ * has two consumers of y_out), is formed inside the statistics pass of the batch-norm backward and written to g16 for
+ * the shortcut branch; dx16, dgamma16, dbeta16 are those of jz_bn_relu_bwd(relu = 0) on dy = g.  The same bits as
+ * jz_relu_bwd_sum (or jz_relu_bwd) followed by jz_bn_relu_bwd, one pass over g less.  Workspace: jz_bn_workspace_bytes. */
+int jz_bn_bwd_block_end(int64_t rows, int channels, const void* x16, const void* y_out16, const void* dya16, const void* dyb16,
+                        const float* gamma, const float* save_mean, const float* save_invstd, void* g16, void* dx16,
+                        void* dgamma16, void* dbeta16, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Forward convolution followed by training-mode batch normalization (+ ReLU) in one call: conv_out16 = x16 (*) w16 exactly
  * as jz_conv2d_fwd writes it, y16 / save_mean / save_invstd exactly as jz_bn_relu_fwd would compute them from conv_out16
  * (Section 4.2's formulas on the FP16 tensor of Section 4.1), but the per-channel sums of the statistics are taken in

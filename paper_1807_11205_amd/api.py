@@ -25,7 +25,7 @@ EXPORTS = [
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
     "jz_add_fwd", "jz_relu_bwd", "jz_relu_bwd_sum", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
     "jz_bias_grad", "jz_softmax_xent_bwd", "jz_conv2d_bn_relu_fwd_workspace_bytes", "jz_conv2d_bn_relu_fwd",
-    "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd",
+    "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd", "jz_bn_bwd_block_end",
     "jz_status_string", "jz_version",
 ]
 
@@ -99,6 +99,7 @@ def lib() -> ctypes.CDLL:
         L.jz_bn_relu_fwd.argtypes = [i64, ci, vp, vp, vp, cf, ci, vp, vp, vp, vp, sz, vp]
         L.jz_bn_relu_bwd.argtypes = [i64, ci, vp, vp, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
         L.jz_add_fwd.argtypes = [i64, vp, vp, ci, vp, vp]
+        L.jz_bn_bwd_block_end.argtypes = [i64, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jz_relu_bwd.argtypes = [i64, vp, vp, vp, vp]
         L.jz_relu_bwd_sum.argtypes = [i64, vp, vp, vp, vp, vp]
         L.jz_maxpool_fwd.argtypes = [ci] * 7 + [vp, vp, vp, vp]
@@ -200,6 +201,18 @@ def jz_bn_relu_bwd(rows, channels, x16, y16, dy16, gamma, save_mean, save_invstd
                                 _dev_ptr(save_mean, f, channels, "save_mean"), _dev_ptr(save_invstd, f, channels, "save_invstd"),
                                 int(bool(relu)), _dev_ptr(dx16, h, rows * channels, "dx16"), _dev_ptr(dgamma16, h, channels, "dgamma16"),
                                 _dev_ptr(dbeta16, h, channels, "dbeta16"), wp, wn, _stream(stream)), "jz_bn_relu_bwd")
+
+
+def jz_bn_bwd_block_end(rows, channels, x16, y_out16, dya16, dyb16, gamma, save_mean, save_invstd, g16, dx16, dgamma16, dbeta16, ws,
+                        stream=None):
+    """g16 = relu-masked (dya16 [+ dyb16]); dx16, dgamma16, dbeta16 = batch-norm backward (no ReLU) of dy = g16."""
+    h, f, n = torch.float16, torch.float32, rows * channels
+    wp, wn = _ws(ws)
+    _check(lib().jz_bn_bwd_block_end(rows, channels, _dev_ptr(x16, h, n, "x16"), _dev_ptr(y_out16, h, n, "y_out16"),
+                                     _dev_ptr(dya16, h, n, "dya16"), _dev_ptr(dyb16, h, n, "dyb16"), _dev_ptr(gamma, f, channels, "gamma"),
+                                     _dev_ptr(save_mean, f, channels, "save_mean"), _dev_ptr(save_invstd, f, channels, "save_invstd"),
+                                     _dev_ptr(g16, h, n, "g16"), _dev_ptr(dx16, h, n, "dx16"), _dev_ptr(dgamma16, h, channels, "dgamma16"),
+                                     _dev_ptr(dbeta16, h, channels, "dbeta16"), wp, wn, _stream(stream)), "jz_bn_bwd_block_end")
 
 
 def jz_conv2d_tune_set(op: int, desc: jz_conv_desc, tile_m: int, tile_n: int, k_tile: int, wavefronts: int, ring: int, splits: int):

@@ -100,12 +100,15 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
 
 // Sums over a slab of rows, for the 8 channels of each lane: s0 and s1 are whatever `term` produces per element.
 // The rpp lanes that share a channel chunk (one per row of a pass) are then added in row order through LDS, and the
-// slab's 2 x C sums are stored.  MODE 0: (x, x^2).  MODE 1: (g, g x^) with g = dy [* (y > 0)].
+// slab's 2 x C sums are stored.  MODE 0: (x, x^2).  MODE 1: (g, g x^) with g = dy [* (y > 0)].  MODE 2: the end of a
+// residual block: g = RNE16(dy [+ dy2]) where y > 0, else 0, is formed here, written to g_out for the other consumers of
+// that gradient, and summed as in MODE 1 (the sums see the rounded g, as a pass over g_out would).
 template <int MODE>
 __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__ x, const uint4* __restrict__ y,
                                                       const uint4* __restrict__ dy, const float* __restrict__ mean,
                                                       const float* __restrict__ invstd, float* __restrict__ part, int64_t rows,
-                                                      int C, int cpr, int rpp, int64_t rows_per_slab, int relu, int csplit) {
+                                                      int C, int cpr, int rpp, int64_t rows_per_slab, int relu, int csplit,
+                                                      const uint4* __restrict__ dy2 = nullptr, uint4* __restrict__ g_out = nullptr) {
   __shared__ float red[2][BN_THREADS][8];
   const int tid = threadIdx.x;
   const int cpr_l = cpr / csplit;  // chunks of a row this workgroup handles: [cfirst, cfirst + cpr_l)
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
   for (int e = 0; e < 8; ++e) {
     s0[e] = 0.f; s1[e] = 0.f; mu[e] = 0.f; is[e] = 0.f;
   }
-  if (MODE == 1 && rsub < rpp) {
+  if (MODE >= 1 && rsub < rpp) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       mu[e] = mean[chunk * 8 + e];
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
   // U rows of a lane are requested together (the loop is bound by memory latency otherwise)
   constexpr int U = MODE == 0 ? 8 : 4;
   for (int64_t r = r0 + rsub; rsub < rpp && r < r1; r += (int64_t)U * rpp) {
-    uint4 qx[U], qd[U], qy[U];
+    uint4 qx[U], qd[U], qy[U], qe[U];
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -138,13 +141,34 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
       const bool in = ru < r1;
       const size_t idx = (size_t)(in ? ru : r) * cpr + chunk;
       qx[u] = x[idx];
-      if (MODE == 1) {
+      if (MODE >= 1) {
         qd[u] = dy[idx];
-        qy[u] = relu ? y[idx] : zero;
+        qy[u] = (relu || MODE == 2) ? y[idx] : zero;
       }
+      if (MODE == 2) qe[u] = dy2 ? dy2[idx] : zero;
       if (!in) {            // rows beyond the slab add nothing (x = 0 and g = 0 contribute zero to every sum)
         qx[u] = zero;
-        if (MODE == 1) qd[u] = zero;
+        if (MODE >= 1) qd[u] = zero;
+        if (MODE == 2) qe[u] = zero;
+      }
+    }
+    if (MODE == 2) {        // form g, keep it as this row's dy, and store it
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float a[8], b[8], m[8];
+        unpack8(qd[u], a);
+        unpack8(qe[u], b);
+        unpack8(qy[u], m);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] += b[e];  // exact in FP32; pack8 rounds once
+        uint4 gq = pack8(a);
+        unsigned gw[4] = {gq.x, gq.y, gq.z, gq.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          gw[k] = (m[2 * k] > 0.f ? (gw[k] & 0xffffu) : 0u) | (m[2 * k + 1] > 0.f ? (gw[k] & 0xffff0000u) : 0u);
+        qd[u] = make_uint4(gw[0], gw[1], gw[2], gw[3]);
+        const int64_t ru = r + (int64_t)u * rpp;
+        if (ru < r1) g_out[(size_t)ru * cpr + chunk] = qd[u];
       }
     }
 #pragma unroll
@@ -160,7 +184,7 @@ __global__ __launch_bounds__(BN_THREADS) void bn_stats(const uint4* __restrict__
       } else {
         float gv[8];
         unpack8(qd[u], gv);
-        if (relu) {
+        if (MODE == 1 && relu) {
           float yv[8];
           unpack8(qy[u], yv);
 #pragma unroll
@@ -419,6 +443,46 @@ extern "C" int jz_bn_relu_bwd(int64_t rows, int channels, const void* x16, const
   const int64_t n_chunks = rows * p.cpr;
   hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, y, dy, static_cast<uint4*>(dx16), coef,
                      n_chunks, channels, p.cpr, relu ? 1 : 0);
+  return jz::launch_status();
+}
+
+extern "C" int jz_bn_bwd_block_end(int64_t rows, int channels, const void* x16, const void* y_out16, const void* dya16,
+                                   const void* dyb16, const float* gamma, const float* save_mean, const float* save_invstd,
+                                   void* g16, void* dx16, void* dgamma16, void* dbeta16, void* ws, size_t ws_bytes, void* hip_stream) {
+  BnPlan p;
+  int rc = make_bn_plan(rows, channels, &p);
+  if (rc != JZ_OK) return rc;
+  if (!x16 || !y_out16 || !dya16 || !gamma || !save_mean || !save_invstd || !g16 || !dx16 || !dgamma16 || !dbeta16) return JZ_ERR_NULL;
+  if (!ws || ws_bytes < p.total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(x16) || !jz::aligned16(y_out16) || !jz::aligned16(dya16) || !jz::aligned16(dyb16) || !jz::aligned16(g16) ||
+      !jz::aligned16(dx16) || !jz::aligned16(ws) || !jz::aligned16(gamma) || !jz::aligned16(save_mean) || !jz::aligned16(save_invstd))
+    return JZ_ERR_ALIGN;
+  const size_t nb = (size_t)rows * channels * 2, nh = (size_t)channels * 2;
+  const void* ins[4] = {x16, y_out16, dya16, dyb16};
+  void* outs[2] = {g16, dx16};
+  for (void* o : outs) {
+    for (const void* i : ins)
+      if (jz::overlaps(o, nb, i, nb)) return JZ_ERR_ALIAS;
+    if (jz::overlaps(o, nb, ws, p.total) || jz::overlaps(o, nb, dgamma16, nh) || jz::overlaps(o, nb, dbeta16, nh)) return JZ_ERR_ALIAS;
+  }
+  if (jz::overlaps(g16, nb, dx16, nb) || jz::overlaps(dgamma16, nh, dbeta16, nh)) return JZ_ERR_ALIAS;
+  for (const void* i : ins)
+    if (jz::overlaps(i, nb, ws, p.total) || jz::overlaps(i, nb, dgamma16, nh) || jz::overlaps(i, nb, dbeta16, nh)) return JZ_ERR_ALIAS;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_part);
+  float* coef = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_coef);
+  const uint4* x = static_cast<const uint4*>(x16);
+  hipLaunchKernelGGL(bn_stats<2>, dim3((unsigned)(p.slabs * p.csplit)), dim3(BN_THREADS), 0, st, x, static_cast<const uint4*>(y_out16),
+                     static_cast<const uint4*>(dya16), save_mean, save_invstd, part, rows, channels, p.cpr, p.rpp, p.rows_per_slab, 0,
+                     p.csplit, static_cast<const uint4*>(dyb16), static_cast<uint4*>(g16));
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  hipLaunchKernelGGL(bn_bwd_final, dim3((unsigned)((channels + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part,
+                     p.slabs, channels, 1.0 / (double)rows, gamma, save_mean, save_invstd, static_cast<unsigned short*>(dgamma16),
+                     static_cast<unsigned short*>(dbeta16), coef);
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  const int64_t n_chunks = rows * p.cpr;
+  hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, nullptr, static_cast<const uint4*>(g16),
+                     static_cast<uint4*>(dx16), coef, n_chunks, channels, p.cpr, 0);
   return jz::launch_status();
 }
 

@@ -33,10 +33,11 @@ class Op:
 
 class ResNet50Chain:
     def __init__(self, batch=64, image=224, variant="v1", seed=180711205, initial_loss_scale=1024.0, hparams=None,
-                 policy=None, device="cuda:0", fused=True):
+                 policy=None, device="cuda:0", fused=True, block_end=True):
         """fused: forward convolution + batch normalization as one call (statistics in the convolution's epilogue)
         instead of two."""
         self.N, self.image, self.device, self.fused = int(batch), int(image), torch.device(device), bool(fused)
+        self.block_end = bool(block_end) and self.fused
         self.convs = shapes.resnet50_convs(variant, image)
         self.fc = shapes.RESNET50_FC
         self.hp = dict(inputs.HPARAMS)
@@ -129,6 +130,19 @@ class ResNet50Chain:
         return Op("conv_bn_fwd", cs.name, dict(desc=d, rows=rows, C=C, relu=relu, eps=BN_EPS), [x, w, gamma, beta, residual],
                   [c, y, mean, invstd], call), mean, invstd
 
+    def _block_end(self, cs, x, mean, invstd, dx, end, name):
+        """ReLU gradient of the block output (one or two incoming contributions, named in `end`) and the batch-norm
+        backward of branch c in one call; end["g"] receives the gradient of the sum for the shortcut branch."""
+        rows, C = self.N * cs.P * cs.P, cs.K
+        gamma = self._param(self.master, cs.name + ".gamma")
+        dgamma, dbeta = self._param(self.grad, cs.name + ".gamma"), self._param(self.grad, cs.name + ".beta")
+        op = Op("bn_bwd_block_end", name, dict(rows=rows, C=C), [x, end["out"], end["dya"], end["dyb"], gamma, mean, invstd],
+                [end["g"], dx, dgamma, dbeta], None)
+        op.call = lambda stream=None: api.jz_bn_bwd_block_end(rows, C, x, end["out"], end["dya"], end["dyb"], gamma, mean, invstd, end["g"],
+                                                              dx, dgamma, dbeta, self.ws, stream)
+        end["op"] = op
+        return op
+
     def _bn_bwd(self, cs, x, y, dy, mean, invstd, dx, relu, name):
         rows, C = self.N * cs.P * cs.P, cs.K
         gamma = self._param(self.master, cs.name + ".gamma")
@@ -145,7 +159,7 @@ class ResNet50Chain:
         W = lambda cs: self._param(self.w16, cs.name + ".w")
         DW = lambda cs: self._param(self.grad, cs.name + ".w")
 
-        def conv_bn(cs, x_in, dx_in, relu, dz=None, residual=None):
+        def conv_bn(cs, x_in, dx_in, relu, dz=None, residual=None, end=None):
             """conv -> batch norm (-> ReLU), appended to the forward list.  Returns (z, dz, back): the output, the buffer
             the consumer of z writes z's gradient to, and this pair's backward ops in execution order.  dx_in is where
             the gradient with respect to x_in goes (None for the first layer)."""
@@ -159,8 +173,12 @@ class ResNet50Chain:
                 F.append(self._conv(api.JZ_FWD, cs, x_in, W(cs), c, cs.name))
                 op, mean, invstd = self._bn_fwd(cs, c, z, relu, cs.name + ".bn")
                 F.append(op)
-            back = [self._bn_bwd(cs, c, z if relu else None, dz, mean, invstd, dc, relu, cs.name + ".bn"),
-                    self._conv(api.JZ_BWD_WEIGHT, cs, x_in, dc, DW(cs), cs.name)]
+            if end is not None:   # block end: the ReLU gradient of z and this batch-norm backward are one call
+                end["out"] = z
+                first = self._block_end(cs, c, mean, invstd, dc, end, cs.name + ".bn")
+            else:
+                first = self._bn_bwd(cs, c, z if relu else None, dz, mean, invstd, dc, relu, cs.name + ".bn")
+            back = [first, self._conv(api.JZ_BWD_WEIGHT, cs, x_in, dc, DW(cs), cs.name)]
             if dx_in is not None:
                 back.append(self._conv(api.JZ_BWD_DATA, cs, dc, W(cs), dx_in, cs.name))
             return z, dz, back
@@ -198,25 +216,37 @@ class ResNet50Chain:
             else:
                 shortcut, back_p, dshort = x_in, [], ds
             dout = self._buf(n_out)
+            end = None
             if self.fused:     # the residual add and the block's ReLU happen in the normalization pass of branch c
-                out, _, back_c = conv_bn(c, zb, dzb, False, dz=ds, residual=shortcut)
+                end = dict(dya=dout, dyb=None, g=ds, at=(2, 3))
+                out, _, back_c = conv_bn(c, zb, dzb, False, dz=ds, residual=shortcut, end=end if self.block_end else None)
+                if self.block_end:     # ... and the ReLU gradient in the statistics pass of branch c's backward
+                    seg = back_c + back_b + back_a + back_p
+                else:
+                    op = Op("relu_bwd", nm + ".add", {}, [out, dout, None], [ds], None)
+                    op.call = lambda stream=None, e=end, y=out: (
+                        api.jz_relu_bwd_sum(y, e["dya"], e["dyb"], e["g"], stream) if e["dyb"] is not None
+                        else api.jz_relu_bwd(y, e["dya"], e["g"], stream))
+                    end["op"], end["at"] = op, (1, 2)
+                    seg = [op] + back_c + back_b + back_a + back_p
             else:
                 zc, _, back_c = conv_bn(c, zb, dzb, False, dz=ds)
                 out = self._buf(n_out)
                 F.append(add_op(nm + ".add", zc, shortcut, out, True))
-            relu_b = Op("relu_bwd", nm + ".add", {}, [out, dout], [ds],
-                        lambda stream=None, y=out, dy=dout, dx=ds: api.jz_relu_bwd(y, dy, dx, stream))
-            seg = [relu_b] + back_c + back_b + back_a + back_p
+                seg = [Op("relu_bwd", nm + ".add", {}, [out, dout], [ds],
+                          lambda stream=None, y=out, dy=dout, dx=ds: api.jz_relu_bwd(y, dy, dx, stream))] + back_c + back_b + back_a + back_p
             if self.fused and below is not None:
                 # the two contributions to this block's input gradient are added inside the ReLU gradient of the block
                 # underneath (which runs after this segment) instead of by a launch of their own
-                b_seg, b_out, b_ds = below
-                b_seg[0] = Op("relu_bwd_sum", b_seg[0].name, {}, [b_out, dxa, dshort], [b_ds],
-                              lambda stream=None, y=b_out, a_=dxa, b_=dshort, dx=b_ds: api.jz_relu_bwd_sum(y, a_, b_, dx, stream))
+                below["dya"], below["dyb"] = dxa, dshort
+                i, j = below["at"]
+                below["op"].ins[i], below["op"].ins[j] = dxa, dshort
+                if below["op"].kind == "relu_bwd":
+                    below["op"].kind = "relu_bwd_sum"
             else:
                 seg.append(add_op(nm + ".dx", dxa, dshort, dx_out, False))
             segments.append(seg)
-            below = (seg, out, ds)
+            below = end
             cur, dcur = out, dout
 
         last = by_name[blocks[-1] + "c"]

@@ -122,3 +122,46 @@ def test_bn_argument_errors(jz):
         jz.jz_bn_relu_fwd(rows, C, X, f(), f(), 1e-5, True, X, f(), f(), ws)                             # output aliases input
     with pytest.raises(jz.JzError):
         jz.jz_bn_relu_fwd(rows, C, X, f(), f(), -1.0, True, torch.empty_like(X), f(), f(), ws)          # negative eps
+
+
+@pytest.mark.parametrize("rows,C,two", [(2 * 14 * 14, 64, True), (5 * 7 * 7, 2048, True), (4099, 256, False), (3 * 9 * 9, 96, True), (1, 8, False)])
+def test_block_end_backward_equals_relu_gradient_then_batch_norm_backward(jz, rows, C, two):
+    """jz_bn_bwd_block_end against (a) the two separate calls, bit for bit, and (b) the oracle's composition."""
+    import jzt
+    import oracle
+    x, gamma, beta, dya = _inputs((9, rows, C), rows, C)
+    rng = inputs.rng_for(31, rows, C)
+    dyb = inputs.normal_f16(rng, (rows, C), std=4.0) if two else None
+    out = np.maximum(inputs.normal_f16(rng, (rows, C)), np.float16(0))           # the block's output: about half zeros
+    dev = jzt.DEV
+    X, G, B, OUT, DA = jzt.to_dev(x), jzt.to_dev(gamma), jzt.to_dev(beta), jzt.to_dev(out), jzt.to_dev(dya)
+    DB = jzt.to_dev(dyb) if two else None
+    Y = torch.empty_like(X)
+    mean = torch.empty(C, dtype=torch.float32, device=dev); invstd = torch.empty_like(mean)
+    ws = torch.empty(max(jz.jz_bn_workspace_bytes(rows, C), 16), dtype=torch.uint8, device=dev)
+    jz.jz_bn_relu_fwd(rows, C, X, G, B, 1e-5, False, Y, mean, invstd, ws)
+    res = []
+    for fused in (True, False):
+        g = torch.full_like(X, float("nan")); dx = torch.full_like(X, float("nan"))
+        dg = torch.empty(C, dtype=torch.float16, device=dev); db = torch.empty_like(dg)
+        ws.fill_(0xCD)
+        if fused:
+            jz.jz_bn_bwd_block_end(rows, C, X, OUT, DA, DB, G, mean, invstd, g, dx, dg, db, ws)
+        else:
+            if two:
+                jz.jz_relu_bwd_sum(OUT.reshape(-1), DA.reshape(-1), DB.reshape(-1), g.reshape(-1)) if rows * C % 8 == 0 else None
+            else:
+                jz.jz_relu_bwd(OUT.reshape(-1), DA.reshape(-1), g.reshape(-1))
+            jz.jz_bn_relu_bwd(rows, C, X, None, g, G, mean, invstd, False, dx, dg, db, ws)
+        torch.cuda.synchronize()
+        res.append([t.cpu().numpy() for t in (g, dx, dg, db)])
+    for a, b in zip(*res):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    g16 = oracle.relu_bwd(out, oracle.add_fwd(dya, dyb, relu=False)[1] if two else dya)
+    assert np.array_equal(res[0][0].view(np.uint16), g16.view(np.uint16))
+    dx64, _, dg64, db64, _, _ = oracle.bn_relu_bwd(x, None, g16, gamma, mean.cpu().numpy(), invstd.cpu().numpy(), relu=False)
+    assert jzt.rel_l2(res[0][1], dx64) <= 1e-3
+    floor = np.sqrt(rows) * 1e-2
+    for got, ref in ((res[0][2], dg64), (res[0][3], db64)):
+        err = np.abs(got.astype(np.float64) - ref)
+        assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor))
