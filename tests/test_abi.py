@@ -191,6 +191,17 @@ def test_layer_entry_points_validate_on_the_host_before_any_launch(jzlib):
     assert L.jz_softmax_xent_bwd(4, 1000, A, B, f(-1.0), None, C_, C_ + 0x100000, None) == E.JZ_ERR_SHAPE
     assert L.jz_softmax_xent_bwd(4, 1000, A, B, f(1.0), None, A, C_, None) == E.JZ_ERR_ALIAS
     assert L.jz_softmax_xent_bwd(4, 1000, A, B, f(1.0), 0x40000004, C_, C_ + 0x100000, None) == E.JZ_ERR_ALIGN
+    n = ctypes.c_size_t(0)
+    assert L.jz_bn_workspace_bytes(64, 16, ctypes.byref(n)) == E.JZ_OK
+    D = [0x10000000 + i * 0x1000000 for i in range(12)]
+    be = lambda **o: L.jz_bn_bwd_block_end(64, 16, o.get("x", D[0]), o.get("y", D[1]), o.get("a", D[2]), o.get("b", D[3]), D[4], D[5], D[6],
+                                           o.get("g", D[7]), o.get("dx", D[8]), D[9], D[9] + 0x1000, D[10], o.get("n", n.value), None)
+    assert be(y=None) == E.JZ_ERR_NULL and be(g=None) == E.JZ_ERR_NULL
+    assert be(n=n.value - 1) == E.JZ_ERR_WORKSPACE
+    assert be(b=D[3] + 2) == E.JZ_ERR_ALIGN
+    assert be(g=D[2]) == E.JZ_ERR_ALIAS and be(dx=D[7]) == E.JZ_ERR_ALIAS and be(g=D[0]) == E.JZ_ERR_ALIAS
+    assert L.jz_bn_bwd_block_end(64, 12, D[0], D[1], D[2], None, D[4], D[5], D[6], D[7], D[8], D[9], D[9] + 0x1000, D[10], n.value,
+                                 None) == E.JZ_ERR_UNSUPPORTED
     assert L.jz_loss_scale_init(None, f(1.0), None) == E.JZ_ERR_NULL
     assert L.jz_loss_scale_init(A, f(0.0), None) == E.JZ_ERR_SHAPE
     assert L.jz_loss_scale_init(A + 4, f(1.0), None) == E.JZ_ERR_ALIGN
