@@ -788,6 +788,9 @@ struct Tuned {
 const Tuned kTuned[] = {
 #include "jz_tuned.inc"
 #include "jz_tuned_alexnet.inc"
+#include "jz_tuned_resnet50_n128.inc"
+#include "jz_tuned_resnet50_n256.inc"
+#include "jz_tuned_resnet50_n32.inc"
     // the 3-channel stem of ResNet-50 at batch 64 on its padded 4-channel copy ("taps" = the 7 filter rows), measured
     // the same way: forward 62.8 us, backward-weight 67.0 us including the copy
     {0, 802816, 64, 224, 7, 0, 128, 64, 32, 4, 3, 1},

@@ -137,7 +137,7 @@ def sweep(path, variants=VARIANTS, model="resnet50"):
 def write_table(recs, path, choice=None):
     """choice: {(layer, op): "tile.bk.waves.ring/splits"} from the in-place pass; default: the fastest alone."""
     lines = ["// Generated by `python -m paper_1807_11205_amd.tune --write` from cold-cache timings on one MI355X (ResNet-50 layer",
-             "// shapes at batch 64, or with --model alexnet the AlexNet-shaped layers at batch 128; with --in-place: refined inside",
+             "// shapes at batch 64 or --batch, or with --model alexnet the AlexNet-shaped layers at batch 128; with --in-place: refined inside",
              "// the whole training step).  {op, M, N, K, taps, scatter, BM, BN, k tile, wavefronts, ring depth, splits}; the planner",
              "// looks a GEMM up here first and falls back to its cost model."]
     for r in recs:
@@ -282,7 +282,12 @@ def main():
     ap.add_argument("--model", default="resnet50", choices=("resnet50", "alexnet"), help="whose layer shapes to sweep")
     ap.add_argument("--only", default=None, help="sweep only these variants, e.g. 256128.32.8.3,128128.32.8.4; with --json: "
                                                  "add the new timings to those saved measurements")
+    ap.add_argument("--batch", type=int, default=None, help="resnet50: batch size of the swept shapes (default 64; the table is keyed "
+                                                            "by GEMM shape, so tables of several batch sizes can sit side by side)")
     a = ap.parse_args()
+    if a.batch:
+        global BATCH
+        BATCH = a.batch
     if a.only:
         sel = [tuple(int(x) for x in v.split(".")) for v in a.only.split(",")]
         assert all(v in VARIANTS for v in sel), "unknown variant"

@@ -138,8 +138,11 @@ def test_every_table_entry_belongs_to_a_layer_and_is_what_the_planner_runs(jzlib
     from paper_1807_11205_amd import tune
     pkg = os.path.dirname(os.path.abspath(tune.__file__))
     ops = {"fwd": jzlib.JZ_FWD, "bwd_data": jzlib.JZ_BWD_DATA, "bwd_weight": jzlib.JZ_BWD_WEIGHT}
-    for model, inc in (("resnet50", "jz_tuned.inc"), ("alexnet", "jz_tuned_alexnet.inc")):
+    for model, inc, other_batch in (("resnet50", "jz_tuned.inc", None), ("alexnet", "jz_tuned_alexnet.inc", None),
+                                    ("resnet50", "jz_tuned_resnet50_n32.inc", 32), ("resnet50", "jz_tuned_resnet50_n128.inc", 128),
+                                    ("resnet50", "jz_tuned_resnet50_n256.inc", 256)):
         batch, layers = tune.model_layers(model)
+        batch = other_batch or batch
         by_name = {cs.name: cs for cs in layers}
         entries = 0
         for line in open(os.path.join(pkg, "csrc", inc)):

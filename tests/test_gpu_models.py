@@ -71,6 +71,18 @@ def test_resnet50_layers_batch64_sampled(jz, cs):
     print(cs.name, {k: "%.2e" % v["rel_l2"] for k, v in res.items()})
 
 
+OTHER_BATCH = [(n, cs) for n in (32, 128) for cs in distinct(shapes.resnet50_convs())
+               if cs.name in ("s2b1b", "s2b1c", "s3b1a", "s3b1p", "s4b1b", "s5b1c", "s5b1b")]
+
+
+@pytest.mark.parametrize("n,cs", OTHER_BATCH, ids=lambda v: str(v) if isinstance(v, int) else v.name)
+def test_resnet50_layers_other_batch_sizes_sampled(jz, n, cs):
+    """Batch 32 and 128 have planner tables of their own (keyed by GEMM shape): a sample of layer kinds through them."""
+    import jzt
+    c = inputs.conv_case_for(cs, n, (6, n, cs.H, cs.C, cs.K, cs.R, cs.stride), loss_scale=1.0)
+    jzt.conv_all_ops_sampled(c, n_fwd=16384, n_bwd_data=16384, work_bwd_weight=2e8, seed=n + cs.H * 1000 + cs.C + cs.K)
+
+
 def test_resnet50_classifier_batch64(jz):
     import jzt
     import oracle
