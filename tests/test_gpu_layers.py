@@ -247,3 +247,39 @@ def test_argument_errors(jz):
     assert L.jz_softmax_xent_bwd(8, 16, p, lab.data_ptr(), f(1.0), None, p, loss.data_ptr(), None) == jz.JZ_ERR_ALIAS
     assert L.jz_softmax_xent_bwd(8, 16, p, lab.data_ptr(), f(1.0), None, q, loss.data_ptr(), None) == jz.JZ_OK
     torch.cuda.synchronize()
+
+
+def _pool_geometries():
+    rng = np.random.default_rng(2024)
+    out = []
+    while len(out) < 20:
+        window, stride = int(rng.integers(1, 8)), int(rng.integers(1, 5))
+        pad = int(rng.integers(0, window))
+        H, W = int(rng.integers(1, 21)), int(rng.integers(1, 21))
+        if window > H + 2 * pad or window > W + 2 * pad:
+            continue
+        out.append((int(rng.integers(1, 4)), H, W, 8 * int(rng.integers(1, 4)), window, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("N,H,W,C,window,stride,pad", _pool_geometries())
+def test_maxpool_seeded_geometries(jz, N, H, W, C, window, stride, pad):
+    """Window 1 to 7 (the compile-time 2 and 3 and the general kernel), strides larger than the window (positions no
+    window covers get zero gradient), padding up to window - 1, images smaller than the window."""
+    x = np.round(h16((20, N, H, W, C, window), (N, H, W, C)) * np.float16(2)) / np.float16(2)      # coarse values: many ties
+    P, Q = oracle.pool_out(H, window, stride, pad), oracle.pool_out(W, window, stride, pad)
+    y = torch.empty(N * P * Q * C, dtype=torch.float16, device="cuda")
+    arg = torch.empty(N * P * Q * C, dtype=torch.uint8, device="cuda")
+    tx = dev(x.ravel())
+    jz.jz_maxpool_fwd(N, H, W, C, window, stride, pad, tx, y, arg)
+    ry, rarg = oracle.maxpool_fwd(x, window, stride, pad)
+    assert same_bits(host(y).reshape(ry.shape), ry)
+    a = host(arg).reshape(ry.shape).astype(np.int64)
+    pp, qq = np.arange(P)[None, :, None, None], np.arange(Q)[None, None, :, None]
+    assert np.array_equal((pp * stride - pad + a // window) * W + (qq * stride - pad + a % window), rarg)
+    dy = np.round(h16((21, N, H, W, C, window), ry.shape, 4.0))                                    # integers: the sums are exact
+    r64, r16 = oracle.maxpool_bwd(x, dy, window, stride, pad)
+    for use_arg in (False, True):
+        dx = torch.full((N * H * W * C,), float("nan"), dtype=torch.float16, device="cuda")
+        jz.jz_maxpool_bwd(N, H, W, C, window, stride, pad, None if use_arg else tx, dev(dy.ravel()), dx, arg if use_arg else None)
+        assert same_bits(host(dx).reshape(r16.shape), r16), "winners from %s" % ("the forward pass" if use_arg else "x")
