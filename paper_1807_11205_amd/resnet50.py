@@ -199,7 +199,7 @@ class ResNet50Chain:
                             lambda stream=None, dy=dcur: api.jz_maxpool_bwd(N, Hp, Hp, 64, 3, 2, 1, None, dy, da0, arg, stream))] + back_stem)
 
         blocks = sorted({cs.name[:-1] for cs in self.convs[1:]}, key=lambda n: (int(n[1]), int(n[3:])))
-        below = None      # the block underneath: (its backward segment, its output, the buffer for the gradient of its sum)
+        below = None      # the block underneath (fused form): where its ReLU gradient takes its incoming gradient(s) from
         for nm in blocks:
             a, b, c = by_name[nm + "a"], by_name[nm + "b"], by_name[nm + "c"]
             p = by_name.get(nm + "p")
