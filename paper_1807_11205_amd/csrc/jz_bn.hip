@@ -552,7 +552,7 @@ extern "C" int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, 
   float* part = reinterpret_cast<float*>(bws + p.bn.off_part);
   float* coef = reinterpret_cast<float*>(bws + p.bn.off_coef);
   // the convolution (its own checks cover x, w, conv_out and its part of the workspace)
-  rc = jz::conv_fwd_run(desc, x16, w16, conv_out16, ws, p.conv_ws, p.tiles_m > 0 ? part : nullptr, hip_stream);
+  rc = jz::conv_fwd_run(desc, x16, w16, conv_out16, ws, p.conv_ws, p.tiles_m > 0 ? part : nullptr, p.tiles_m, hip_stream);
   if (rc != JZ_OK) return rc;
   const uint4* c = static_cast<const uint4*>(conv_out16);
   int slabs = p.tiles_m;

@@ -1129,11 +1129,13 @@ bool plan_leaves_stats(const Plan& pl) {
 
 // A, B in the kernel's order: FWD (x, w), BWD_DATA (dy, w), BWD_WEIGHT (dy, x)
 int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, void* ws, size_t ws_bytes, void* stream,
-        float* stats = nullptr) {
+        float* stats = nullptr, int stats_tiles_m = 0) {
   Plan pl;
   int rc = make_plan(op, d, &pl);
   if (rc != JZ_OK) return rc;
-  if (stats && !plan_leaves_stats(pl)) return JZ_ERR_UNSUPPORTED;
+  // the caller sized the buffer of the column sums from an earlier plan: it has to be this plan (the run-time tuning table
+  // may have been changed in between)
+  if (stats && (!plan_leaves_stats(pl) || pl.args.tiles_m != stats_tiles_m)) return JZ_ERR_UNSUPPORTED;
   if (!A || !B || !D) return JZ_ERR_NULL;
   if (!aligned16(A) || !aligned16(B) || !aligned16(D) || (ws && !aligned16(ws))) return JZ_ERR_ALIGN;
   if (overlaps(D, pl.bytesD, A, pl.bytesA) || overlaps(D, pl.bytesD, B, pl.bytesB)) return JZ_ERR_ALIAS;
@@ -1215,8 +1217,8 @@ int jz::conv_fwd_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* t
   return JZ_OK;
 }
 int jz::conv_fwd_run(const jz_conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, float* stats,
-                     void* stream) {
-  return run(JZ_FWD, d, x, w, y, ws, ws_bytes, stream, stats);
+                     int stats_tiles_m, void* stream) {
+  return run(JZ_FWD, d, x, w, y, ws, ws_bytes, stream, stats, stats_tiles_m);
 }
 
 extern "C" int jz_conv2d_workspace_bytes(int op, const jz_conv_desc* desc, size_t* bytes) {

@@ -18,10 +18,11 @@ inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
 
 // Forward convolution for the fused convolution + batch normalization entry point.  conv_fwd_stats_plan: the workspace
 // the convolution needs and, when its kernel can leave per-tile column sums of y and y^2, the number of row tiles (else
-// 0).  conv_fwd_run with stats != nullptr (only after a plan that said so) writes them as [tiles_m][2][K] floats.
+// 0).  conv_fwd_run with stats != nullptr (only after a plan that said so) writes them as [tiles_m][2][K] floats; it
+// returns JZ_ERR_UNSUPPORTED, before anything is launched, if the plan no longer has stats_tiles_m row tiles.
 int conv_fwd_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* tiles_m);
 int conv_fwd_run(const jz_conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, float* stats,
-                 void* stream);
+                 int stats_tiles_m, void* stream);
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? JZ_OK : JZ_ERR_LAUNCH; }
 
