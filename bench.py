@@ -30,7 +30,7 @@ LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32
 # HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very workload (default batch and
 # variant), scaled by the same counters' readings for a 1 GiB copy; the runs are summarised under profiles/.
 MEASURED_BN_HBM_BYTES_PER_STEP = 14.18e9     # bench.py --workload bn at N = 64 (profiles/bench_bn_resnet50_n64_kernel_stats.txt)
-MEASURED_CHAIN_HBM_BYTES_PER_STEP = 24.98e9   # --workload chain, N = 64, fused calls (profiles/bench_chain_resnet50_n64_hbm_traffic.txt)
+MEASURED_CHAIN_HBM_BYTES_PER_STEP = 24.27e9   # --workload chain, N = 64, fused calls (profiles/bench_chain_resnet50_n64_hbm_traffic.txt)
 MEASURED_GEMM_HBM_BYTES_PER_STEP = 9.61e9   # all conv/FC launches with their split-K reductions and packing kernels
 MEASURED_LARS_HBM_BYTES_PER_UPDATE = 562e6   # gradient norm pass 51 MB + update pass 511 MB
 
