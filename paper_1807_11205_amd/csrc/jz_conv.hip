@@ -281,28 +281,28 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
     }
   }
   if constexpr (CAN_STATS) {
-    {
-      // [CRPP][BN] pairs in LDS, then one thread per column adds the CRPP row groups in a fixed order
-      __syncthreads();  // the staged tile has been read
-      float* sS = reinterpret_cast<float*>(lds);
+    // [2][CRPP][BN] floats in LDS (sums, then sums of squares), then one thread per column and kind adds the CRPP row
+    // groups in a fixed order: the loads are independent and issued together, consecutive lanes read consecutive words
+    __syncthreads();  // the staged tile has been read
+    float* sS = reinterpret_cast<float*>(lds);
+    float* w0 = sS + (crow * BN + cch * 8);
+    float* w1 = w0 + CRPP * BN;
+    *reinterpret_cast<float4*>(w0) = make_float4(ssum[0], ssum[1], ssum[2], ssum[3]);
+    *reinterpret_cast<float4*>(w0 + 4) = make_float4(ssum[4], ssum[5], ssum[6], ssum[7]);
+    *reinterpret_cast<float4*>(w1) = make_float4(ssq[0], ssq[1], ssq[2], ssq[3]);
+    *reinterpret_cast<float4*>(w1 + 4) = make_float4(ssq[4], ssq[5], ssq[6], ssq[7]);
+    __syncthreads();
+    float* out = a.stats + (size_t)(m0 / BM) * 2 * a.N;
+    for (int v = tid; v < 2 * BN; v += NTHREADS) {
+      const int kind = v / BN, col = v - kind * BN;
+      const float* src = sS + kind * CRPP * BN + col;
+      float part[CRPP];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        sS[((crow * BN) + cch * 8 + e) * 2] = ssum[e];
-        sS[((crow * BN) + cch * 8 + e) * 2 + 1] = ssq[e];
-      }
-      __syncthreads();
-      float* out = a.stats + (size_t)(m0 / BM) * 2 * a.N;
-      for (int col = tid; col < BN; col += NTHREADS) {
-        float s1 = 0.f, s2 = 0.f;
-        for (int r = 0; r < CRPP; ++r) {
-          s1 += sS[(r * BN + col) * 2];
-          s2 += sS[(r * BN + col) * 2 + 1];
-        }
-        if (n0 + col < a.N) {
-          out[n0 + col] = s1;
-          out[a.N + n0 + col] = s2;
-        }
-      }
+      for (int r = 0; r < CRPP; ++r) part[r] = src[r * BN];
+      float s1 = 0.f;
+#pragma unroll
+      for (int r = 0; r < CRPP; ++r) s1 += part[r];
+      if (n0 + col < a.N) out[kind * a.N + n0 + col] = s1;
     }
   }
 }
