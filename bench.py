@@ -439,7 +439,7 @@ def chain_workload(args):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for e in ev:
-        e[0].record(); net.forward(); e[1].record(); net.backward(side=side); e[2].record(); net.update(); e[3].record()
+        e[0].record(); net.forward(side=side); e[1].record(); net.backward(side=side); e[2].record(); net.update(); e[3].record()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     assert int(net.found_inf.item()) == 0

@@ -24,20 +24,23 @@ BN_EPS = 1e-5
 class Op:
     """One library call of the step: what it is, the tensors it reads and writes, and the launch itself."""
 
-    __slots__ = ("kind", "name", "params", "ins", "outs", "call", "side_call")
+    __slots__ = ("kind", "name", "params", "ins", "outs", "call", "side_call", "lane", "joins_side")
 
     def __init__(self, kind, name, params, ins, outs, call, side_call=None):
         self.kind, self.name, self.params, self.ins, self.outs, self.call = kind, name, params, ins, outs, call
-        self.side_call = side_call      # weight gradients only: workspace -> the same launch bound to that workspace
+        self.side_call = side_call      # workspace -> the same launch bound to that workspace, for a side stream
+        self.lane = "main"              # "side": a weight gradient, "proj": the projection-shortcut branch (both may run on a side stream)
+        self.joins_side = False         # reads what the side stream's projection branch wrote: waits for it
 
 
 class ResNet50Chain:
     def __init__(self, batch=64, image=224, variant="v1", seed=180711205, initial_loss_scale=1024.0, hparams=None,
-                 policy=None, device="cuda:0", fused=True, block_end=True):
+                 policy=None, device="cuda:0", fused=True, block_end=True, proj_side=False):
         """fused: forward convolution + batch normalization as one call (statistics in the convolution's epilogue)
         instead of two."""
         self.N, self.image, self.device, self.fused = int(batch), int(image), torch.device(device), bool(fused)
         self.block_end = bool(block_end) and self.fused
+        self.proj_side = bool(proj_side)      # projection-shortcut branches on the side stream too (measured: no gain)
         self.convs = shapes.resnet50_convs(variant, image)
         self.fc = shapes.RESNET50_FC
         self.hp = dict(inputs.HPARAMS)
@@ -101,23 +104,30 @@ class ResNet50Chain:
         d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
         self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
         kind = {api.JZ_FWD: "conv_fwd", api.JZ_BWD_DATA: "conv_bwd_data", api.JZ_BWD_WEIGHT: "conv_bwd_weight"}[op]
-        side = (lambda ws: api.bind_conv2d(op, d, a, b, out, ws)) if op == api.JZ_BWD_WEIGHT else None
-        return Op(kind, name, dict(desc=d), [a, b], [out], self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, ws)), side)
+        o = Op(kind, name, dict(desc=d), [a, b], [out], self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, ws)),
+               lambda ws: api.bind_conv2d(op, d, a, b, out, ws))
+        if op == api.JZ_BWD_WEIGHT:
+            o.lane = "side"
+        return o
 
     def _fc(self, mode, a, b, out, name):
         B, I, O = self.N, self.fc.I, self.fc.O
         self._ws_bytes = max(self._ws_bytes, api.jz_gemm_fc_workspace_bytes(mode, B, I, O))
         kind = {api.JZ_FWD: "fc_fwd", api.JZ_BWD_DATA: "fc_bwd_data", api.JZ_BWD_WEIGHT: "fc_bwd_weight"}[mode]
-        side = (lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)) if mode == api.JZ_BWD_WEIGHT else None
-        return Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)), side)
+        o = Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)),
+               lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws))
+        if mode == api.JZ_BWD_WEIGHT:
+            o.lane = "side"
+        return o
 
     def _bn_fwd(self, cs, x, y, relu, name):
         rows, C = self.N * cs.P * cs.P, cs.K
         gamma, beta = self._param(self.master, cs.name + ".gamma"), self._param(self.master, cs.name + ".beta")
         mean, invstd = self._buf(C, torch.float32), self._buf(C, torch.float32)
         self._ws_bytes = max(self._ws_bytes, api.jz_bn_workspace_bytes(rows, C))
-        call = lambda stream=None: api.jz_bn_relu_fwd(rows, C, x, gamma, beta, BN_EPS, relu, y, mean, invstd, self.ws, stream)
-        return Op("bn_fwd", name, dict(rows=rows, C=C, relu=relu, eps=BN_EPS), [x, gamma, beta], [y, mean, invstd], call), mean, invstd
+        run = lambda ws, stream: api.jz_bn_relu_fwd(rows, C, x, gamma, beta, BN_EPS, relu, y, mean, invstd, ws, stream)
+        return Op("bn_fwd", name, dict(rows=rows, C=C, relu=relu, eps=BN_EPS), [x, gamma, beta], [y, mean, invstd],
+                  lambda stream=None: run(self.ws, stream), lambda ws: (lambda stream=None: run(ws, stream))), mean, invstd
 
     def _conv_bn_fwd(self, cs, x, w, c, y, relu, residual=None):
         d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
@@ -125,10 +135,10 @@ class ResNet50Chain:
         gamma, beta = self._param(self.master, cs.name + ".gamma"), self._param(self.master, cs.name + ".beta")
         mean, invstd = self._buf(C, torch.float32), self._buf(C, torch.float32)
         self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_bn_relu_fwd_workspace_bytes(d))
-        call = lambda stream=None: api.jz_conv2d_bn_relu_fwd(d, x, w, gamma, beta, BN_EPS, relu, c, y, mean, invstd, self.ws, residual,
-                                                             stream)
+        run = lambda ws, stream: api.jz_conv2d_bn_relu_fwd(d, x, w, gamma, beta, BN_EPS, relu, c, y, mean, invstd, ws, residual, stream)
         return Op("conv_bn_fwd", cs.name, dict(desc=d, rows=rows, C=C, relu=relu, eps=BN_EPS), [x, w, gamma, beta, residual],
-                  [c, y, mean, invstd], call), mean, invstd
+                  [c, y, mean, invstd], lambda stream=None: run(self.ws, stream),
+                  lambda ws: (lambda stream=None: run(ws, stream))), mean, invstd
 
     def _block_end(self, cs, x, mean, invstd, dx, end, name):
         """ReLU gradient of the block output (one or two incoming contributions, named in `end`) and the batch-norm
@@ -147,9 +157,10 @@ class ResNet50Chain:
         rows, C = self.N * cs.P * cs.P, cs.K
         gamma = self._param(self.master, cs.name + ".gamma")
         dgamma, dbeta = self._param(self.grad, cs.name + ".gamma"), self._param(self.grad, cs.name + ".beta")
-        call = lambda stream=None: api.jz_bn_relu_bwd(rows, C, x, y if relu else None, dy, gamma, mean, invstd, relu, dx, dgamma, dbeta,
-                                                      self.ws, stream)
-        return Op("bn_bwd", name, dict(rows=rows, C=C, relu=relu), [x, y, dy, gamma, mean, invstd], [dx, dgamma, dbeta], call)
+        run = lambda ws, stream: api.jz_bn_relu_bwd(rows, C, x, y if relu else None, dy, gamma, mean, invstd, relu, dx, dgamma, dbeta,
+                                                    ws, stream)
+        return Op("bn_bwd", name, dict(rows=rows, C=C, relu=relu), [x, y, dy, gamma, mean, invstd], [dx, dgamma, dbeta],
+                  lambda stream=None: run(self.ws, stream), lambda ws: (lambda stream=None: run(ws, stream)))
 
     # ---- the network -------------------------------------------------------------------------------------------------
     def _build(self):
@@ -207,44 +218,52 @@ class ResNet50Chain:
             dxa = self._buf(x_in.numel())                  # branch a's contribution to it
             n_out = N * c.P * c.P * c.K
             ds = self._buf(n_out)                          # gradient of the sum in front of the block's last ReLU
-            za, dza, back_a = conv_bn(a, x_in, dxa, True)
-            zb, dzb, back_b = conv_bn(b, za, dza, True)
-            if p is not None:
+            if p is not None:      # the projection shortcut first: on a side stream it runs beside branch a - b
                 dxp = self._buf(x_in.numel())
+                n_fwd = len(F)
                 shortcut, _, back_p = conv_bn(p, x_in, dxp, False, dz=ds)
+                for o in F[n_fwd:] + back_p:
+                    o.lane = "proj"
                 dshort = dxp
             else:
                 shortcut, back_p, dshort = x_in, [], ds
+            za, dza, back_a = conv_bn(a, x_in, dxa, True)
+            zb, dzb, back_b = conv_bn(b, za, dza, True)
             dout = self._buf(n_out)
             end = None
             if self.fused:     # the residual add and the block's ReLU happen in the normalization pass of branch c
                 end = dict(dya=dout, dyb=None, g=ds, at=(2, 3))
                 out, _, back_c = conv_bn(c, zb, dzb, False, dz=ds, residual=shortcut, end=end if self.block_end else None)
+                if back_p:
+                    F[-1].joins_side = True        # the residual is the projection branch's output
                 if self.block_end:     # ... and the ReLU gradient in the statistics pass of branch c's backward
-                    seg = back_c + back_b + back_a + back_p
+                    seg = back_c[:1] + back_p + back_c[1:] + back_b + back_a
                 else:
                     op = Op("relu_bwd", nm + ".add", {}, [out, dout, None], [ds], None)
                     op.call = lambda stream=None, e=end, y=out: (
                         api.jz_relu_bwd_sum(y, e["dya"], e["dyb"], e["g"], stream) if e["dyb"] is not None
                         else api.jz_relu_bwd(y, e["dya"], e["g"], stream))
                     end["op"], end["at"] = op, (1, 2)
-                    seg = [op] + back_c + back_b + back_a + back_p
+                    seg = [op] + back_p + back_c + back_b + back_a
             else:
                 zc, _, back_c = conv_bn(c, zb, dzb, False, dz=ds)
                 out = self._buf(n_out)
                 F.append(add_op(nm + ".add", zc, shortcut, out, True))
+                F[-1].joins_side = bool(back_p)
                 seg = [Op("relu_bwd", nm + ".add", {}, [out, dout], [ds],
-                          lambda stream=None, y=out, dy=dout, dx=ds: api.jz_relu_bwd(y, dy, dx, stream))] + back_c + back_b + back_a + back_p
+                          lambda stream=None, y=out, dy=dout, dx=ds: api.jz_relu_bwd(y, dy, dx, stream))] + back_p + back_c + back_b + back_a
             if self.fused and below is not None:
                 # the two contributions to this block's input gradient are added inside the ReLU gradient of the block
                 # underneath (which runs after this segment) instead of by a launch of their own
                 below["dya"], below["dyb"] = dxa, dshort
                 i, j = below["at"]
                 below["op"].ins[i], below["op"].ins[j] = dxa, dshort
+                below["op"].joins_side = bool(back_p)   # dshort then comes from the projection branch
                 if below["op"].kind == "relu_bwd":
                     below["op"].kind = "relu_bwd_sum"
             else:
                 seg.append(add_op(nm + ".dx", dxa, dshort, dx_out, False))
+                seg[-1].joins_side = bool(back_p)
             segments.append(seg)
             below = end
             cur, dcur = out, dout
@@ -272,6 +291,10 @@ class ResNet50Chain:
                             lambda stream=None, dx=dcur: api.jz_avgpool_bwd(N, HW, C, dpooled, dx, stream))])
         for seg in reversed(segments):
             self.bwd_ops.extend(seg)
+        if not self.proj_side:     # the projection branches stay on the main stream, their weight gradients go with the others
+            for o in self.fwd_ops + self.bwd_ops:
+                if o.lane == "proj":
+                    o.lane = "side" if o.kind.endswith("bwd_weight") else "main"
 
     def _lars_op(self):
         hp = api.lars_hparams(self.hp["lr"], self.hp["momentum"], self.hp["weight_decay"], self.hp["trust_coef"], 1.0)
@@ -280,49 +303,70 @@ class ResNet50Chain:
                   [self.master, self.momentum, self.w16, self.found_inf, self.ls_state], call)
 
     # ---- running -----------------------------------------------------------------------------------------------------
-    def forward(self, stream=None):
-        for op in self.fwd_ops:
-            op.call(stream)
-
-    def backward(self, stream=None, side=None):
-        """With side streams (one stream or a list) the weight-gradient GEMMs, which nothing in the backward pass waits
-        for, run there round-robin beside the chain of activation gradients; the caller's stream waits for them at the end."""
+    def _run(self, ops, stream, side, which):
+        """Launches ops in order; with side streams, those of lane "side" go there round-robin (each after an event that
+        says the main stream has produced what it reads), and an op that reads the projection branch's output first
+        waits for the side streams.  which: "fwd" or "bwd" (keys of the pre-created events)."""
         if side is None:
-            for op in self.bwd_ops:
+            for op in ops:
                 op.call(stream)
             return
         sides = list(side) if isinstance(side, (list, tuple)) else [side]
         while len(self.side_ws) < len(sides):
             self.side_ws.append(torch.zeros(self._ws_bytes, dtype=torch.uint8, device=self.device))
         main = stream if stream is not None else torch.cuda.current_stream()
-        k = 0
-        for i, op in enumerate(self.bwd_ops):
-            if op.side_call is None:
+
+        def event(key):
+            ev = self._events.get(key)
+            if ev is None:
+                ev = self._events[key] = torch.cuda.Event()
+            return ev
+
+        k, dirty = 0, [False] * len(sides)
+        for i, op in enumerate(ops):
+            if op.lane == "main":
+                if op.joins_side:
+                    for j, s_ in enumerate(sides):
+                        if dirty[j]:
+                            ev = event((which, "join", i, j))
+                            ev.record(s_)
+                            main.wait_event(ev)
                 op.call(main)
                 continue
-            j = k % len(sides)
-            k += 1
-            call = self._side_calls.get((i, j))
+            # weight gradients go round-robin; the projection branches (their weight gradients included) stay in order
+            # on the first side stream
+            j = 0
+            if op.lane == "side":
+                j = k % len(sides)
+                k += 1
+            call = self._side_calls.get((which, i, j))
             if call is None:
-                call = self._side_calls[(i, j)] = op.side_call(self.side_ws[j])
-            ev = self._events.get(i)
-            if ev is None:
-                ev = self._events[i] = torch.cuda.Event()
-            ev.record(main)                 # the gradient this GEMM reads has just been produced on the main stream
+                call = self._side_calls[(which, i, j)] = op.side_call(self.side_ws[j])
+            ev = event((which, i))
+            ev.record(main)                 # what this op reads has just been produced on the main stream
             sides[j].wait_event(ev)
             call(sides[j])
+            dirty[j] = True
         for j, s_ in enumerate(sides):
-            done = self._events.get(("done", j))
-            if done is None:
-                done = self._events[("done", j)] = torch.cuda.Event()
-            done.record(s_)
-            main.wait_event(done)
+            if dirty[j]:
+                done = event((which, "done", j))
+                done.record(s_)
+                main.wait_event(done)
+
+    def forward(self, stream=None, side=None):
+        """With side streams the projection-shortcut branch of a stage's first block runs beside branch a - b."""
+        self._run(self.fwd_ops, stream, side, "fwd")
+
+    def backward(self, stream=None, side=None):
+        """With side streams the weight-gradient GEMMs (which nothing in the backward pass waits for) and the backward
+        of the projection-shortcut branches run there, beside the chain of activation gradients."""
+        self._run(self.bwd_ops, stream, side, "bwd")
 
     def update(self, stream=None):
         self.trace[-1].call(stream)
 
     def step(self, stream=None, side=None):
-        self.forward(stream)
+        self.forward(stream, side)
         self.backward(stream, side)
         self.update(stream)
 

@@ -199,16 +199,17 @@ def test_side_stream_schedule_gives_the_same_bits(jz):
     exactly the same parameters as on one stream."""
     from paper_1807_11205_amd import resnet50
     out = []
-    for use_side in (False, True):
-        net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=512.0, hparams=dict(lr=1.0))
+    for use_side, proj in ((False, False), (True, False), (True, True)):
+        net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=512.0, hparams=dict(lr=1.0), proj_side=proj)
         side = torch.cuda.Stream() if use_side else None
         for _ in range(3):
             net.step(side=side)
         torch.cuda.synchronize()
         out.append((np16(net.master), np16(net.momentum), np16(net.w16), np16(net.grad), net.mean_loss()))
-    for a, b in zip(out[0][:4], out[1][:4]):
-        assert np.array_equal(a.view(np.uint32 if a.dtype == np.float32 else np.uint16), b.view(np.uint32 if b.dtype == np.float32 else np.uint16))
-    assert out[0][4] == out[1][4]
+    for other in out[1:]:
+        for a, b in zip(out[0][:4], other[:4]):
+            assert np.array_equal(a.view(np.uint32 if a.dtype == np.float32 else np.uint16), b.view(np.uint32 if b.dtype == np.float32 else np.uint16))
+        assert out[0][4] == other[4]
 
 
 def test_full_size_chained_step_on_sampled_outputs(jz):
