@@ -21,9 +21,12 @@
  *     return without synchronising.  Nothing is allocated or freed by the
  *     library; scratch comes from the caller's workspace `ws` (size from the matching
  *     *_workspace_bytes call; may be NULL when that size is 0).
- *   - Return value: JZ_OK or a negative JZ_ERR_* code.  On error nothing was enqueued
- *     and no output was touched.  Inf/NaN in data are not errors: they propagate per
- *     IEEE in the GEMMs, and in the LARS update they raise the overflow flag.
+ *   - Return value: JZ_OK or a negative JZ_ERR_* code.  Argument errors (every code but
+ *     JZ_ERR_LAUNCH) are found on the host before anything is enqueued: no output and no
+ *     workspace byte was touched.  JZ_ERR_LAUNCH means the HIP runtime refused a launch; an
+ *     entry point made of several launches may then have left outputs and the workspace
+ *     partially written.  Inf/NaN in data are not errors: they propagate per IEEE in the
+ *     GEMMs, and in the LARS update they raise the overflow flag.
  *   - Outputs must not overlap inputs or the workspace (checked for the pointers
  *     given; JZ_ERR_ALIAS), except the in-place state buffers of the LARS update.
  *   - Same inputs give bit-identical outputs from run to run (no float atomics).
@@ -42,7 +45,7 @@ enum {
   JZ_OK = 0,
   JZ_ERR_NULL = -1,        /* a required pointer is NULL */
   JZ_ERR_SHAPE = -2,       /* non-positive dimension, empty output, pad >= filter size, bad offsets table */
-  JZ_ERR_UNSUPPORTED = -3, /* valid but not implemented (e.g. a conv tensor with >= 2^30 elements) */
+  JZ_ERR_UNSUPPORTED = -3, /* valid but not implemented (e.g. a conv tensor with 2^30 or more elements) */
   JZ_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than *_workspace_bytes reports */
   JZ_ERR_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
   JZ_ERR_ALIAS = -6,       /* an output overlaps an input or the workspace */
@@ -272,14 +275,17 @@ int jz_conv2d_describe_plan(int op, const jz_conv_desc* desc, char* text, size_t
  * `op` on `desc` maps to, which kernel variant to run: output tile tile_m x tile_n, k tile depth, wavefronts per
  * workgroup, ring depth (LDS stages) and the number of splits of the reduction (not split at all where a split would be
  * shorter than four k tiles).  Later calls for that shape use it in place of the built-in table of measured
- * choices and of the cost model; the JZ_IGEMM_* environment overrides still win.  The variant must be one the library
- * has (jz_conv2d_describe_plan shows the names: e.g. 128x128 tile, k tile 64, 8 wavefronts, ring 4), else
- * JZ_ERR_UNSUPPORTED; shapes that run on the element-wise or per-load-arithmetic kernels cannot be tuned
- * (JZ_ERR_UNSUPPORTED).  Results never depend on the choice beyond the summation order of the reduction.
- * jz_conv2d_tune_clear forgets every recorded choice.  Used by `python -m paper_1807_11205_amd.tune --in-place`, which
- * times candidates inside the whole training step rather than layer by layer. */
+ * choices and of the cost model; nothing else overrides the planner (the library reads no environment variables).
+ * The variant must be one the library has (jz_conv2d_describe_plan shows the names: e.g. 128x128 tile, k tile 64,
+ * 8 wavefronts, ring 4), else JZ_ERR_UNSUPPORTED; shapes that gather with per-load tap arithmetic take the four
+ * 4-wavefront tiles, 32 deep, ring 4; shapes on the element-wise kernel cannot be tuned (JZ_ERR_UNSUPPORTED).
+ * Results never depend on the choice beyond the summation order of the reduction.
+ * jz_conv2d_tune_use_table(0) makes the planner skip its built-in table of measured choices (cost model only),
+ * jz_conv2d_tune_use_table(1) restores it.  jz_conv2d_tune_clear forgets every recorded choice and restores the
+ * table.  Used by the tests to force every kernel variant and by `python -m paper_1807_11205_amd.tune`. */
 int jz_conv2d_tune_set(int op, const jz_conv_desc* desc, int tile_m, int tile_n, int k_tile, int wavefronts, int ring,
                        int splits);
+int jz_conv2d_tune_use_table(int on);
 int jz_conv2d_tune_clear(void);
 
 /* Human-readable name of a status code; static storage. */

@@ -20,7 +20,7 @@ JZ_FWD, JZ_BWD_DATA, JZ_BWD_WEIGHT = 0, 1, 2
 JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
 
 EXPORTS = [
-    "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
+    "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_use_table", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
     "jz_add_fwd", "jz_relu_bwd", "jz_relu_bwd_sum", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
@@ -83,6 +83,9 @@ def lib() -> ctypes.CDLL:
         dp = ctypes.POINTER(jz_conv_desc)
         L.jz_conv2d_workspace_bytes.argtypes = [ci, dp, ctypes.POINTER(sz)]
         L.jz_conv2d_describe_plan.argtypes = [ci, dp, ctypes.c_char_p, sz]
+        L.jz_conv2d_tune_set.argtypes = [ci, dp, ci, ci, ci, ci, ci, ci]
+        L.jz_conv2d_tune_use_table.argtypes = [ci]
+        L.jz_conv2d_tune_clear.argtypes = []
         for name in ("jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight"):
             getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.jz_gemm_fc_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
@@ -217,6 +220,10 @@ def jz_bn_bwd_block_end(rows, channels, x16, y_out16, dya16, dyb16, gamma, save_
 
 def jz_conv2d_tune_set(op: int, desc: jz_conv_desc, tile_m: int, tile_n: int, k_tile: int, wavefronts: int, ring: int, splits: int):
     _check(lib().jz_conv2d_tune_set(op, ctypes.byref(desc), tile_m, tile_n, k_tile, wavefronts, ring, splits), "jz_conv2d_tune_set")
+
+
+def jz_conv2d_tune_use_table(on: bool):
+    _check(lib().jz_conv2d_tune_use_table(1 if on else 0), "jz_conv2d_tune_use_table")
 
 
 def jz_conv2d_tune_clear():

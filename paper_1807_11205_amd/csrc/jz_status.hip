@@ -16,4 +16,4 @@ extern "C" const char* jz_status_string(int status) {
   }
 }
 
-extern "C" int jz_version(void) { return 100; }
+extern "C" int jz_version(void) { return 110; }

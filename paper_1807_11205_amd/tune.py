@@ -2,7 +2,7 @@
 
 For every distinct convolution shape of ResNet-50 (batch 64) and each of forward / backward-data / backward-weight it
 times every kernel variant (output tile, k tile depth, wavefronts per workgroup) at every admissible split of the
-reduction, through the planner's JZ_IGEMM_* overrides, with the caches flushed before each timed launch (inside a
+reduction, through the planner's tuning hook (jz_conv2d_tune_set), with the caches flushed before each timed launch (inside a
 training step every layer finds them cold).  `--write` turns the measurements into csrc/jz_tuned.inc, the table the
 planner consults before its cost model; `--json FILE` re-uses saved measurements instead of running on the GPU.
 
@@ -84,7 +84,6 @@ def sweep(path, variants=VARIANTS, model="resnet50"):
         return best * 1e3
 
     out = []
-    names = ("JZ_IGEMM_TILE", "JZ_IGEMM_BK", "JZ_IGEMM_WAVES", "JZ_IGEMM_SPLITS", "JZ_IGEMM_NOTABLE", "JZ_IGEMM_NST")
     for cs in layers:
         d = api.conv_desc(BATCH, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
         x = torch.randn(BATCH * cs.H * cs.H * cs.C, device=dev).to(h)
@@ -99,21 +98,18 @@ def sweep(path, variants=VARIANTS, model="resnet50"):
                     api.jz_conv2d_bwd_data(d, dy, w, dx, ws)
                 else:
                     api.jz_conv2d_bwd_weight(d, x, dy, dw, ws)
-            for k in names:
-                os.environ.pop(k, None)
+            api.jz_conv2d_tune_clear()
             res = {"planner": round(timeit(run), 1)}
-            os.environ["JZ_IGEMM_NOTABLE"] = "1"
+            api.jz_conv2d_tune_use_table(False)
             res["model"] = round(timeit(run), 1)
             for (t, bk, wv, nst) in variants:
-                os.environ["JZ_IGEMM_TILE"], os.environ["JZ_IGEMM_BK"], os.environ["JZ_IGEMM_WAVES"] = str(t), str(bk), str(wv)
-                os.environ["JZ_IGEMM_NST"] = str(nst)
                 prev_need = None
                 for sp in SPLITS:
-                    os.environ["JZ_IGEMM_SPLITS"] = str(sp)
                     try:
+                        api.jz_conv2d_tune_set(op, d, t // 1000, t % 1000, bk, wv, nst, sp)
                         need = api.jz_conv2d_workspace_bytes(op, d)
                     except api.JzError:
-                        continue
+                        continue  # no such kernel for this layer
                     if need > ws.numel() or (sp > 1 and need in (0, prev_need)):
                         continue  # too large, or the planner could not honour this split count
                     prev_need = need
@@ -122,6 +118,7 @@ def sweep(path, variants=VARIANTS, model="resnet50"):
                     if want not in plan:
                         continue  # the planner could not honour this combination for this layer
                     res["%d.%d.%d.%d/%d" % (t, bk, wv, nst, sp)] = round(timeit(run), 1)
+            api.jz_conv2d_tune_clear()
             cands = [k for k in res if k not in ("planner", "model")]
             best = min(cands, key=res.get)
             out.append(dict(layer=cs.name, H=cs.H, C=cs.C, K=cs.K, R=cs.R, stride=cs.stride, pad=cs.pad, batch=BATCH, op=opn, best=best,
@@ -129,8 +126,6 @@ def sweep(path, variants=VARIANTS, model="resnet50"):
             print(cs.name, opn, "planner", res["planner"], "model", res["model"], "best", best, res[best], flush=True)
             with open(path, "w") as f:
                 json.dump(out, f)
-    for k in names:
-        os.environ.pop(k, None)
     return out
 
 

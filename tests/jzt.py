@@ -1,5 +1,7 @@
 """Helpers shared by the GPU parity tests: move seeded host inputs to the GPU, call libjz through its
 binding, bring results back, and compare against the CPU oracle with the stated tolerances."""
+from contextlib import contextmanager
+
 import numpy as np
 import torch
 
@@ -53,11 +55,15 @@ class LarsRun:
         return self.w.cpu().numpy(), self.v.cpu().numpy(), self.w16.cpu().numpy(), int(self.flag.item())
 
 
-def check_lars_against_oracle(ps: inputs.ParamSet, got, loss_scale=None, rtol=1e-6, **hp):
+def check_lars_against_oracle(ps: inputs.ParamSet, got, loss_scale=None, rtol=1e-6, plain_rtol=None, plain_floor=0.0, **hp):
     """The LARS parity bar: flag bit-exact; fp32 master weights and momentum within rtol element-wise;
     fp16 write-back == RNE16(own fp32 master) everywhere, and == the oracle's fp16 except where the fp64
     value sits within 2e-6 (relative to the operand scale, see below) of an fp16 rounding midpoint, where the
-    neighbouring fp16 value is allowed."""
+    neighbouring fp16 value is allowed.  plain_rtol: also assert the plain element-wise relative error
+    |w32 - w64| <= plain_rtol * |w64| (the stated 1e-6) on every element whose new value is at least plain_floor times
+    its operand scale (0: every element; a real training step has a few weights that the update happens to cancel, and
+    the one fp32 rounding of w - v, 6e-8 of the larger operand, is only within 1e-6 of a difference that is not more
+    than about ten times smaller than the operands: hence a floor of 0.1 there)."""
     kw = dict(inputs.HPARAMS)
     kw.update(hp)
     S = ps.loss_scale if loss_scale is None else loss_scale
@@ -90,9 +96,13 @@ def check_lars_against_oracle(ps: inputs.ParamSet, got, loss_scale=None, rtol=1e
         assert np.array_equal(np.nextafter(w16[diff], rw16[diff]), rw16[diff]), "w16 differs by more than one fp16 step"
         mid = 0.5 * (a + b)
         assert np.all(np.abs(w64[diff] - mid) <= 2e-6 * wscale[diff]), "w16 differs away from a rounding boundary"
+    keep = np.abs(w64) >= plain_floor * wscale
+    plain = float(np.max((ew / (np.abs(w64) + 1e-300))[keep], initial=0.0))
+    if plain_rtol is not None:
+        assert plain <= plain_rtol, "master weights: plain relative error %.3g > %.1g" % (plain, plain_rtol)
+        assert np.count_nonzero(~keep) <= 1e-3 * keep.size, "too many cancelled weights left out of the plain bound"
     return dict(flag=0, n_boundary=int(diff.size), max_rel_w=float(np.max(ew / (wscale + 1e-300), initial=0.0)),
-                max_rel_v=float(np.max(ev / (vscale + 1e-300), initial=0.0)),
-                max_rel_w_plain=float(np.max(ew / (np.abs(w64) + 1e-300), initial=0.0)))
+                max_rel_v=float(np.max(ev / (vscale + 1e-300), initial=0.0)), max_rel_w_plain=plain)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -130,14 +140,44 @@ def run_fc(mode, B, I, O, a, b, out_shape):
     return out.cpu().numpy()
 
 
+@contextmanager
+def forced_variant(d, tile_m, tile_n, k_tile, wavefronts, ring, splits=1, ops=(api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)):
+    """Make the planner run one kernel variant for the ops of layer `d` (jz_conv2d_tune_set), whatever it would have
+    picked; splits: one number or {op: number}.  Everything recorded is forgotten on exit."""
+    try:
+        for op in ops:
+            sp = splits.get(op, 1) if isinstance(splits, dict) else splits
+            api.jz_conv2d_tune_set(op, d, tile_m, tile_n, k_tile, wavefronts, ring, sp)
+            want = "tile %dx%dx%d, %d wavefronts, ring %d" % (tile_m, tile_n, k_tile, wavefronts, ring)
+            plan = api.jz_conv2d_describe_plan(op, d)
+            assert want in plan, (want, plan)
+        yield
+    finally:
+        api.jz_conv2d_tune_clear()
+
+
 FP16_OVERFLOW = 65520.0      # |v| >= this rounds to +-Inf
 
 
-def check_half_output(got16: np.ndarray, ref64: np.ndarray, tol=1e-3, what=""):
+ELEMENT_C = 8.0               # per-element bound: multiples of 2^-24 * sum|terms| allowed for fp32 accumulation
+
+
+def abs16(a: np.ndarray) -> np.ndarray:
+    """|a| of fp16 data as bit patterns (sign bit cleared): the oracle run on these gives sum |term| per output."""
+    return np.ascontiguousarray(a).view(np.uint16) & np.uint16(0x7FFF)
+
+
+def check_half_output(got16: np.ndarray, ref64: np.ndarray, tol=1e-3, what="", mag64=None):
     """The conv/FC parity bar: relative L2 error <= tol against the fp64 oracle over every entry that is finite in
     the oracle's fp16 rounding, and the +-Inf pattern of fp16 overflow must match exactly, except for entries whose
     exact magnitude lies within 2^-10 (relative) of the overflow threshold 65520, where fp32 accumulation order may
-    legitimately tip the rounding either way (such an entry must then be +-Inf or within 2^-9 of the exact value)."""
+    legitimately tip the rounding either way (such an entry must then be +-Inf or within 2^-9 of the exact value).
+
+    mag64 (the oracle evaluated on |inputs|: sum of |term| for every output) adds a bound on EVERY finite element:
+      |got - ref| <= 2^-10 |ref| + ELEMENT_C 2^-24 mag + 2^-24
+    one fp16 rounding (2^-11, doubled for a second rounding at an fp32 / fp16 midpoint), fp32 accumulation in any
+    order (each of the K - 1 additions errs by at most 2^-24 of a partial sum that is at most mag; as a random walk that
+    is about 0.6 * 2^-24 * mag in total, ELEMENT_C leaves six standard deviations), and the spacing of fp16 subnormals."""
     got = np.asarray(got16).astype(np.float64).ravel()
     ref = np.asarray(ref64, dtype=np.float64).ravel()
     assert got.shape == ref.shape, (got.shape, ref.shape)
@@ -155,42 +195,140 @@ def check_half_output(got16: np.ndarray, ref64: np.ndarray, tol=1e-3, what=""):
     fin = ~ref_inf & ~got_inf
     err = rel_l2(got[fin], ref[fin]) if np.any(fin) else 0.0
     assert err <= tol, "%s: relative L2 error %.3e > %.1e" % (what, err, tol)
-    return dict(rel_l2=err, n_inf=int(np.count_nonzero(ref_inf)), n_band=int(np.count_nonzero(band)))
+    worst = 0.0
+    if mag64 is not None:
+        mag_t = np.asarray(mag64, dtype=np.float64).ravel()
+        assert mag_t.shape == ref.shape
+        bound = 2.0 ** -10 * mag[fin] + ELEMENT_C * 2.0 ** -24 * mag_t[fin] + 2.0 ** -24
+        ratio = np.abs(got[fin] - ref[fin]) / bound
+        worst = float(np.max(ratio, initial=0.0))
+        bad = np.nonzero(ratio > 1.0)[0]
+        assert bad.size == 0, "%s: %d elements beyond the per-element bound, worst %.2f x at finite index %d (got %r, ref %r)" % (
+            what, bad.size, worst, int(bad[0]), got[fin][bad[0]], ref[fin][bad[0]])
+    return dict(rel_l2=err, n_inf=int(np.count_nonzero(ref_inf)), n_band=int(np.count_nonzero(band)), worst_elem=worst)
 
 
 def conv_all_ops_full(case, tol=1e-3, ops=(0, 1, 2)):
     """fwd / bwd_data / bwd_weight of one layer against the full-tensor oracle."""
     d, od = desc_of(case), odesc_of(case)
     res = {}
+    ax, aw, ady = abs16(case.x), abs16(case.w16), abs16(case.dy)
     if api.JZ_FWD in ops:
         y = run_conv(api.JZ_FWD, d, case.x, case.w16, (case.N, case.P, case.Q, case.K))
-        res["fwd"] = check_half_output(y, oracle.conv_fwd(od, case.x, case.w16), tol, "fwd")
+        res["fwd"] = check_half_output(y, oracle.conv_fwd(od, case.x, case.w16), tol, "fwd", oracle.conv_fwd(od, ax, aw))
     if api.JZ_BWD_DATA in ops:
         dx = run_conv(api.JZ_BWD_DATA, d, case.dy, case.w16, (case.N, case.H, case.W, case.C))
-        res["bwd_data"] = check_half_output(dx, oracle.conv_bwd_data(od, case.dy, case.w16), tol, "bwd_data")
+        res["bwd_data"] = check_half_output(dx, oracle.conv_bwd_data(od, case.dy, case.w16), tol, "bwd_data",
+                                            oracle.conv_bwd_data(od, ady, aw))
     if api.JZ_BWD_WEIGHT in ops:
         dw = run_conv(api.JZ_BWD_WEIGHT, d, case.x, case.dy, (case.K, case.R, case.S, case.C))
-        res["bwd_weight"] = check_half_output(dw, oracle.conv_bwd_weight(od, case.x, case.dy), tol, "bwd_weight")
+        res["bwd_weight"] = check_half_output(dw, oracle.conv_bwd_weight(od, case.x, case.dy), tol, "bwd_weight",
+                                              oracle.conv_bwd_weight(od, ax, ady))
     return res
 
 
-def conv_all_ops_sampled(case, n_fwd=65536, n_bwd_data=65536, work_bwd_weight=6e8, seed=0, tol=1e-3, skip_bwd_data=False):
-    """Full-size layer: the GPU computes whole tensors, the oracle a seeded sample of output elements one by one."""
+def plan_tiles(op, d):
+    """(tile_m, tile_n, tiles_m, tiles_n, splits, scatter) of the plan the library would run for `op` on `d`."""
+    import re
+    text = api.jz_conv2d_describe_plan(op, d)
+    m = re.search(r"tile (\d+)x(\d+)x\d+, \d+ wavefronts, ring \d+, (\d+) x (\d+) tiles, (\d+) splits", text)
+    assert m, text
+    return tuple(int(v) for v in m.groups()) + ("scatter epilogue" in text,)
+
+
+def structured_rows_cols(M, N, plan, max_row_tiles=1536):
+    """Rows and columns of the GEMM output where a tiling bug would show: the first and last row of (up to max_row_tiles,
+    evenly spaced, always the first and last two) row tiles, of the row tiles at which one XCD's run of consecutive
+    workgroups ends and the next begins, and the first and last column of every column tile (ragged last tiles
+    included by construction)."""
+    bm, bn, tm, tn, splits, _ = plan
+    assert tm == -(-M // bm) and tn == -(-N // bn), (M, N, plan)
+    tiles = set(range(tm)) if tm <= max_row_tiles else set(np.linspace(0, tm - 1, max_row_tiles).astype(int).tolist()) | {1, tm - 2}
+    grid = tm * tn * splits
+    q, rem = divmod(grid, 8)
+    for x in range(1, 8):                                 # first workgroup of XCD x's run and the one before it
+        for L in (x * q + min(x, rem), x * q + min(x, rem) - 1):
+            if 0 <= L < grid:
+                tiles.add((L % (tm * tn)) // tn)
+    rows = sorted({r for t in tiles for r in (t * bm, min((t + 1) * bm, M) - 1)})
+    cols = sorted({c for t in range(tn) for c in (t * bn, min((t + 1) * bn, N) - 1)})
+    return np.asarray(rows, np.int64), np.asarray(cols, np.int64)
+
+
+def conv_all_ops_sampled(case, n_fwd=65536, n_bwd_data=65536, seed=0, tol=1e-3, skip_bwd_data=False):
+    """Full-size layer in the launch configuration the planner picks for it: the GPU computes whole tensors; for the
+    forward and backward-data outputs the oracle computes, one by one, a seeded random sample PLUS the rows and columns
+    at the edges of the kernel's output tiles and XCD runs; the weight gradient (small output, long reduction, split
+    across workgroups) is compared as a WHOLE tensor.  Every compared element also has to meet the per-element bound."""
     d, od = desc_of(case), odesc_of(case)
     rng = np.random.default_rng(seed)
     res = {}
+    ax, aw, ady = abs16(case.x), abs16(case.w16), abs16(case.dy)
+
+    def sample(out, op, M, Ncol, to_flat):
+        rows, cols = structured_rows_cols(M, Ncol, plan_tiles(op, d))
+        edge = to_flat(np.repeat(rows, cols.size), np.tile(cols, rows.size))
+        return np.unique(np.concatenate([rng.integers(0, out.size, size=min(n_fwd if op == api.JZ_FWD else n_bwd_data, out.size)), edge]))
+
     y = run_conv(api.JZ_FWD, d, case.x, case.w16, (case.N, case.P, case.Q, case.K))
     assert not np.any(np.isnan(y)), "fwd: unwritten output"
-    idx = rng.integers(0, y.size, size=min(n_fwd, y.size))
-    res["fwd"] = check_half_output(y.ravel()[idx], oracle.conv_fwd_at(od, case.x, case.w16, idx), tol, "fwd")
+    idx = sample(y, api.JZ_FWD, case.N * case.P * case.Q, case.K, lambda r, c: r * case.K + c)
+    res["fwd"] = check_half_output(y.ravel()[idx], oracle.conv_fwd_at(od, case.x, case.w16, idx), tol, "fwd",
+                                   oracle.conv_fwd_at(od, ax, aw, idx))
+    res["fwd"]["n"] = int(idx.size)
     if not skip_bwd_data:
         dx = run_conv(api.JZ_BWD_DATA, d, case.dy, case.w16, (case.N, case.H, case.W, case.C))
         assert not np.any(np.isnan(dx)), "bwd_data: unwritten output"
-        idx = rng.integers(0, dx.size, size=min(n_bwd_data, dx.size))
-        res["bwd_data"] = check_half_output(dx.ravel()[idx], oracle.conv_bwd_data_at(od, case.dy, case.w16, idx), tol, "bwd_data")
+        if plan_tiles(api.JZ_BWD_DATA, d)[5]:
+            # strided 1x1 layer: the GEMM's rows are the output pixels (n, p, q); row m lands on input pixel
+            # (n, p * stride, q * stride), and the pixel diagonally behind it (when inside) must hold the zero
+            def to_flat(r, c):
+                n, rem = np.divmod(r, case.P * case.Q)
+                p, q = np.divmod(rem, case.Q)
+                hit = ((n * case.H + p * case.stride) * case.W + q * case.stride) * case.C + c
+                h1, w1 = np.minimum(p * case.stride + 1, case.H - 1), np.minimum(q * case.stride + 1, case.W - 1)
+                return np.concatenate([hit, ((n * case.H + h1) * case.W + w1) * case.C + c])
+            M = case.N * case.P * case.Q
+        else:
+            to_flat = lambda r, c: r * case.C + c
+            M = case.N * case.H * case.W
+        idx = sample(dx, api.JZ_BWD_DATA, M, case.C, to_flat)
+        res["bwd_data"] = check_half_output(dx.ravel()[idx], oracle.conv_bwd_data_at(od, case.dy, case.w16, idx), tol, "bwd_data",
+                                            oracle.conv_bwd_data_at(od, ady, aw, idx))
+        res["bwd_data"]["n"] = int(idx.size)
     dw = run_conv(api.JZ_BWD_WEIGHT, d, case.x, case.dy, (case.K, case.R, case.S, case.C))
-    assert not np.any(np.isnan(dw)), "bwd_weight: unwritten output"
-    n = int(max(256, min(dw.size, work_bwd_weight // (case.N * case.P * case.Q))))
-    idx = rng.integers(0, dw.size, size=n)
-    res["bwd_weight"] = check_half_output(dw.ravel()[idx], oracle.conv_bwd_weight_at(od, case.x, case.dy, idx), tol, "bwd_weight")
+    res["bwd_weight"] = check_half_output(dw, oracle.conv_bwd_weight(od, case.x, case.dy), tol, "bwd_weight (whole tensor)",
+                                          oracle.conv_bwd_weight(od, ax, ady))
+    res["bwd_weight"]["n"] = int(dw.size)
+    return res
+
+
+def fc_all_modes(B, I, O, c, tol=1e-3):
+    """The three fully connected GEMMs of one layer against the oracle's triple loops, norm-wise and element by element."""
+    ax, aw, ady = abs16(c.x), abs16(c.w16), abs16(c.dy)
+    res = {}
+    res["fwd"] = check_half_output(run_fc(api.JZ_FWD, B, I, O, c.x, c.w16, (B, O)), oracle.fc_fwd(B, I, O, c.x, c.w16), tol, "fc fwd",
+                                   oracle.fc_fwd(B, I, O, ax, aw))
+    res["bwd_data"] = check_half_output(run_fc(api.JZ_BWD_DATA, B, I, O, c.dy, c.w16, (B, I)), oracle.fc_bwd_data(B, I, O, c.dy, c.w16), tol,
+                                        "fc bwd_data", oracle.fc_bwd_data(B, I, O, ady, aw))
+    res["bwd_weight"] = check_half_output(run_fc(api.JZ_BWD_WEIGHT, B, I, O, c.dy, c.x, (O, I)), oracle.fc_bwd_weight(B, I, O, c.dy, c.x), tol,
+                                          "fc bwd_weight", oracle.fc_bwd_weight(B, I, O, ady, ax))
+    return res
+
+
+def all_ops_against_the_oracle(d, od, x, w, dy, ops=(api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT), tol=1e-3):
+    """fwd / bwd_data / bwd_weight of an arbitrary descriptor pair (library, oracle) on given arrays: whole tensors,
+    norm-wise and element by element."""
+    N, H, W, C, K, R, S = od.N, od.H, od.W, od.C, od.K, od.R, od.S
+    ax, aw, ady = abs16(x), abs16(w), abs16(dy)
+    res = {}
+    if api.JZ_FWD in ops:
+        res["fwd"] = check_half_output(run_conv(api.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), tol, "fwd",
+                                       oracle.conv_fwd(od, ax, aw))
+    if api.JZ_BWD_DATA in ops:
+        res["bwd_data"] = check_half_output(run_conv(api.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), tol,
+                                            "bwd_data", oracle.conv_bwd_data(od, ady, aw))
+    if api.JZ_BWD_WEIGHT in ops:
+        res["bwd_weight"] = check_half_output(run_conv(api.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), tol,
+                                              "bwd_weight", oracle.conv_bwd_weight(od, ax, ady))
     return res

@@ -74,8 +74,8 @@ def test_describe_plan_for_every_resnet50_and_alexnet_layer(jzlib):
              (256, 128, 32, 8), (256, 256, 32, 8), (128, 128, 64, 4), (128, 64, 64, 4), (64, 128, 64, 4), (64, 64, 64, 4),
              (128, 128, 32, 8)}
     layers = [(64, c) for c in shapes.resnet50_convs()] + [(128, c) for c in shapes.alexnet_convs()]
-    for notable in ("0", "1"):
-        os.environ["JZ_IGEMM_NOTABLE"] = notable
+    for use_table in (True, False):
+        jzlib.jz_conv2d_tune_use_table(use_table)
         try:
             for batch, cs in layers:
                 d = jzlib.conv_desc(batch, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
@@ -90,7 +90,28 @@ def test_describe_plan_for_every_resnet50_and_alexnet_layer(jzlib):
                     ws = jzlib.jz_conv2d_workspace_bytes(op, d)
                     assert (ws > 0) == (sp > 1 or "padded copy" in text), text
         finally:
-            os.environ.pop("JZ_IGEMM_NOTABLE", None)
+            jzlib.jz_conv2d_tune_clear()
+
+
+def test_tensor_size_limit_is_checked_on_the_host(jzlib):
+    # the kernels form byte offsets in 32 bits: a tensor of 2^30 or more elements is refused before any launch, through
+    # every query and for each of the three tensors of a layer; one element less is planned
+    L = jzlib.lib()
+    n = ctypes.c_size_t(0)
+    ok = jzlib.conv_desc(1, 1, 1 << 15, (1 << 15) - 8, 8, 1, 1)                   # x: 2^30 - 2^18 elements
+    big_x = jzlib.conv_desc(1, 1, 1 << 15, 1 << 15, 8, 1, 1)                      # x: exactly 2^30 elements
+    big_y = jzlib.conv_desc(1, 1, 1 << 15, 8, 1 << 15, 1, 1)                      # y: 2^30
+    big_w = jzlib.conv_desc(1, 1, 1, 1 << 15, 1 << 15, 1, 1)                      # w: 2^30
+    for op in (jzlib.JZ_FWD, jzlib.JZ_BWD_DATA, jzlib.JZ_BWD_WEIGHT):
+        assert L.jz_conv2d_workspace_bytes(op, ctypes.byref(ok), ctypes.byref(n)) == jzlib.JZ_OK
+        for d in (big_x, big_y, big_w):
+            assert L.jz_conv2d_workspace_bytes(op, ctypes.byref(d), ctypes.byref(n)) == jzlib.JZ_ERR_UNSUPPORTED
+            assert L.jz_conv2d_describe_plan(op, ctypes.byref(d), ctypes.create_string_buffer(256), 256) == jzlib.JZ_ERR_UNSUPPORTED
+    A = 0x10000000                                                               # never dereferenced: refused first
+    assert L.jz_conv2d_fwd(ctypes.byref(big_x), A, A + (1 << 32), A + (1 << 33), None, 0, None) == jzlib.JZ_ERR_UNSUPPORTED
+    # a padded multi-tap layer just under the limit: descriptor size + padding margin stay below 2^32 bytes
+    pad = jzlib.conv_desc(1, 1 << 10, (1 << 10) - 1, 1 << 10, 8, 3, 3, 1, 1)
+    assert L.jz_conv2d_workspace_bytes(jzlib.JZ_FWD, ctypes.byref(pad), ctypes.byref(n)) == jzlib.JZ_OK
 
 
 def test_tuned_table_is_used_for_the_benchmark_shapes(jzlib):
@@ -99,12 +120,16 @@ def test_tuned_table_is_used_for_the_benchmark_shapes(jzlib):
     d = jzlib.conv_desc(64, 14, 14, 256, 256, 3, 3, 1, 1)
     with_table = jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, d)
     assert "M 256 N 2304 K 12544" in with_table
-    os.environ["JZ_IGEMM_TILE"] = "64064"
+    assert "tile 128x128x64, 8 wavefronts, ring 4" in with_table   # the table's entry for this shape
+    # a shape next to it that is in no table gets the cost model's plan, and switching the table off must still plan
+    other = jzlib.conv_desc(48, 14, 14, 256, 256, 3, 3, 1, 1)
+    assert "M 256 N 2304 K 9408" in jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, other)
+    jzlib.jz_conv2d_tune_use_table(False)
     try:
-        forced = jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, d)
+        assert "M 256 N 2304 K 12544" in jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, d)
     finally:
-        os.environ.pop("JZ_IGEMM_TILE", None)
-    assert "tile 64x64x" in forced      # an override bypasses the table
+        jzlib.jz_conv2d_tune_clear()
+    assert jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_WEIGHT, d) == with_table
 
 
 def test_run_time_tuning_hook_changes_the_plan_and_can_be_cleared(jzlib):

@@ -44,6 +44,8 @@ GENERIC = [
     (3, 6, 6, 24, 40, 3, 3, 1, 1),           # channels multiple of 8 but not of 64
     (1, 1, 1, 5, 7, 1, 1, 1, 0),             # a single dot product per output
     (5, 4, 4, 130, 129, 1, 1, 1, 0),         # just over one tile in n and k
+    (8, 20, 20, 3, 5, 3, 3, 1, 1),           # long reduction (3200 pixels) into 5 x 27 weight gradients: the element-wise
+                                             # kernel splits it, and the partial-sum slabs are not 16-byte multiples
 ]
 
 
@@ -62,9 +64,9 @@ def test_generic_shapes(jz, cfg):
     x = inputs.normal_f16(rng, (N, H, W, C))
     w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
     dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=4.0)
-    jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
-    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+    if cfg[0] == 8:
+        assert " 1 splits" not in jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d) and "element-wise" in jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
+    res = jzt.all_ops_against_the_oracle(d, od, x, w, dy)
 
 
 VECTOR = [
@@ -98,10 +100,8 @@ def test_vector_path_shapes(jz, cfg):
     x = inputs.normal_f16(rng, (N, H, W, C))
     w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
     dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
-    r1 = jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-    r2 = jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
-    r3 = jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
-    print(r1["rel_l2"], r2["rel_l2"], r3["rel_l2"])
+    res = jzt.all_ops_against_the_oracle(d, od, x, w, dy)
+    print({k: (v["rel_l2"], v["worst_elem"]) for k, v in res.items()})
 
 
 def test_delta_filter_copies_the_input_bit_exactly(jz):
@@ -153,130 +153,99 @@ def test_same_inputs_give_identical_bits(jz):
 
 
 KERNEL_VARIANTS = [
-    # (JZ_IGEMM_TILE, JZ_IGEMM_BK, JZ_IGEMM_WAVES): every LDS-direct kernel variant, forced through the planner's
-    # debugging overrides so that each one is compared with the oracle whatever the planner would have picked
-    ("128128", "32", "4"), ("128064", "32", "4"), ("64128", "32", "4"), ("64064", "32", "4"),
-    ("128128", "64", "4"), ("128064", "64", "4"), ("64128", "64", "4"), ("64064", "64", "4"),
-    ("128128", "64", "8"), ("256128", "64", "8"), ("256128", "32", "8"), ("256256", "32", "8"),
+    # (tile_m, tile_n, k tile, wavefronts, ring): every LDS-direct kernel variant, forced through the planner's tuning
+    # hook so that each one is compared with the oracle whatever the planner would have picked
+    (128, 128, 32, 4, 4), (128, 64, 32, 4, 4), (64, 128, 32, 4, 4), (64, 64, 32, 4, 4),
+    (128, 128, 64, 4, 4), (128, 64, 64, 4, 4), (64, 128, 64, 4, 4), (64, 64, 64, 4, 4),
+    (128, 128, 64, 8, 4), (256, 128, 64, 8, 3), (256, 128, 32, 8, 4), (256, 256, 32, 8, 4),
 ]
 
 
-@pytest.mark.parametrize("tile,bk,waves", KERNEL_VARIANTS)
-def test_every_kernel_variant_against_the_oracle(jz, monkeypatch, tile, bk, waves):
+@pytest.mark.parametrize("splits", [1, 3])
+@pytest.mark.parametrize("variant", KERNEL_VARIANTS, ids=lambda v: "x".join(str(i) for i in v))
+def test_every_kernel_variant_against_the_oracle(jz, variant, splits):
     import jzt
     import oracle
-    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
-    monkeypatch.setenv("JZ_IGEMM_BK", bk)
-    monkeypatch.setenv("JZ_IGEMM_WAVES", waves)
     # M = 675 pixels (2.6 tiles of 256 rows), 128 -> 320 channels (1.25 tiles of 256 columns), 3x3 with padding
     N, H, W, C, K, R, S, st, pad = 3, 15, 15, 128, 320, 3, 3, 1, 1
     od = oracle.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
     d = jz.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
-    rng = inputs.rng_for(16, int(tile), int(bk), int(waves))
+    rng = inputs.rng_for(16, *variant)
     x = inputs.normal_f16(rng, (N, H, W, C))
     w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
     dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
-    jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
-    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+    with jzt.forced_variant(d, *variant, splits=splits):
+        if splits > 1:
+            assert "%d splits" % splits in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+        jzt.all_ops_against_the_oracle(d, od, x, w, dy)
+    if splits > 1:
+        return
     # a strided 1x1 layer: the scatter epilogue of backward-data, also in its slabbed form
     N, H, W, C, K = 2, 14, 14, 256, 128
     od = oracle.conv_desc(N, H, W, C, K, 1, 1, 2, (0, 0))
     d = jz.conv_desc(N, H, W, C, K, 1, 1, 2, (0, 0))
     w = inputs.he_normal_f32(rng, (K, 1, 1, C), C).astype(np.float16)
     dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
-    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data 1x1 s2")
+    with jzt.forced_variant(d, *variant, ops=(jz.JZ_BWD_DATA,)):
+        assert "scatter epilogue" in jz.jz_conv2d_describe_plan(jz.JZ_BWD_DATA, d)
+        jzt.all_ops_against_the_oracle(d, od, x, w, dy, ops=(jz.JZ_BWD_DATA,))   # x is not an input of this op
 
 
-@pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
-def test_register_staged_kernels_against_the_oracle(jz, monkeypatch, tile):
-    # the second, independent implementation of the vector path (global -> registers -> LDS, register transposes), kept
-    # for debugging behind JZ_IGEMM_PATH=reg: it has to agree with the oracle like the production kernels
-    import jzt
-    import oracle
-    monkeypatch.setenv("JZ_IGEMM_PATH", "reg")
-    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
-    N, H, W, C, K, R, S, st, pad = 3, 13, 13, 128, 192, 3, 3, 1, 1
-    od = oracle.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
-    d = jz.conv_desc(N, H, W, C, K, R, S, st, (pad, pad))
-    rng = inputs.rng_for(19, int(tile))
-    x = inputs.normal_f16(rng, (N, H, W, C))
-    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
-    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
-    jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
-    jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
-
-
-@pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
-def test_three_stage_ring_variants_against_the_oracle(jz, monkeypatch, tile):
+@pytest.mark.parametrize("tile", [(128, 128), (128, 64), (64, 128), (64, 64)], ids=lambda t: "%dx%d" % t)
+def test_three_stage_ring_variants_against_the_oracle(jz, tile):
     # the short-ring variants (three stages, three to six workgroups per compute unit), on a short and a long reduction
     import jzt
     import oracle
-    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
-    monkeypatch.setenv("JZ_IGEMM_BK", "32")
-    monkeypatch.setenv("JZ_IGEMM_WAVES", "4")
-    monkeypatch.setenv("JZ_IGEMM_NST", "3")
     for (N, H, W, C, K, R, pad) in ((5, 12, 12, 64, 192, 1, 0), (2, 13, 13, 128, 192, 3, 1), (1, 9, 9, 32, 64, 1, 0)):
         od = oracle.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
         d = jz.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
-        assert "ring 3" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
-        rng = inputs.rng_for(18, int(tile), C, R)
+        rng = inputs.rng_for(18, tile[0] * 1000 + tile[1], C, R)
         x = inputs.normal_f16(rng, (N, H, W, C))
         w = inputs.he_normal_f32(rng, (K, R, R, C), R * R * C).astype(np.float16)
         dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
-        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
-        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+        with jzt.forced_variant(d, tile[0], tile[1], 32, 4, 3, splits={jz.JZ_BWD_WEIGHT: 2}):
+            jzt.all_ops_against_the_oracle(d, od, x, w, dy)
 
 
-@pytest.mark.parametrize("tile,nst", [("256128", "3"), ("128128", "4"), ("128128", "3")])
-def test_eight_wavefront_32_deep_variants_against_the_oracle(jz, monkeypatch, tile, nst):
+@pytest.mark.parametrize("tile,nst", [((256, 128), 3), ((128, 128), 4), ((128, 128), 3)])
+def test_eight_wavefront_32_deep_variants_against_the_oracle(jz, tile, nst):
     # 8 wavefronts on 32-deep tiles with rings short enough for two or three workgroups per compute unit
     import jzt
     import oracle
-    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
-    monkeypatch.setenv("JZ_IGEMM_BK", "32")
-    monkeypatch.setenv("JZ_IGEMM_WAVES", "8")
-    monkeypatch.setenv("JZ_IGEMM_NST", nst)
     for (N, H, W, C, K, R, pad) in ((3, 15, 15, 128, 320, 3, 1), (5, 12, 12, 64, 192, 1, 0), (2, 9, 9, 32, 64, 1, 0)):
         od = oracle.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
         d = jz.conv_desc(N, H, W, C, K, R, R, 1, (pad, pad))
-        want = "tile %sx%sx32, 8 wavefronts, ring %s" % (tile[:3], tile[3:], nst)
-        for op in (jz.JZ_FWD, jz.JZ_BWD_DATA, jz.JZ_BWD_WEIGHT):
-            assert want in jz.jz_conv2d_describe_plan(op, d)
-        rng = inputs.rng_for(21, int(tile), int(nst), C, R)
+        rng = inputs.rng_for(21, tile[0] * 1000 + tile[1], nst, C, R)
         x = inputs.normal_f16(rng, (N, H, W, C))
         w = inputs.he_normal_f32(rng, (K, R, R, C), R * R * C).astype(np.float16)
         dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
-        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
-        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+        with jzt.forced_variant(d, tile[0], tile[1], 32, 8, nst, splits={jz.JZ_BWD_WEIGHT: 2}):
+            jzt.all_ops_against_the_oracle(d, od, x, w, dy)
 
 
-@pytest.mark.parametrize("tile", ["128128", "128064", "64128", "64064"])
-@pytest.mark.parametrize("nst", ["4", "3"])
-def test_small_channel_kernel_variants_against_the_oracle(jz, monkeypatch, tile, nst):
+@pytest.mark.parametrize("tile", [(128, 128), (128, 64), (64, 128), (64, 64)], ids=lambda t: "%dx%d" % t)
+@pytest.mark.parametrize("nst", [4, 3])
+def test_small_channel_kernel_variants_against_the_oracle(jz, tile, nst):
     # 3-channel stems run on a padded 4-channel copy: every masked forward variant, and backward-weight both with a split
     # reduction (the reduction kernel writes the real filter entries) and without (separate unpacking kernel)
     import jzt
     import oracle
-    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
-    monkeypatch.setenv("JZ_IGEMM_NST", nst)
-    for (N, H, C, K, R, st, pad, splits) in ((3, 37, 3, 64, 7, 2, 3, "4"), (2, 23, 3, 72, 7, 2, 3, "1"), (4, 39, 3, 96, 11, 4, 0, "2"),
-                                             (4, 20, 4, 64, 5, 2, 2, "3"), (1, 30, 1, 64, 3, 2, 1, "2")):
-        monkeypatch.setenv("JZ_IGEMM_SPLITS", splits)
+    for (N, H, C, K, R, st, pad, splits) in ((3, 37, 3, 64, 7, 2, 3, 4), (2, 23, 3, 72, 7, 2, 3, 1), (4, 39, 3, 96, 11, 4, 0, 2),
+                                             (4, 20, 4, 64, 5, 2, 2, 3), (1, 30, 1, 64, 3, 2, 1, 2)):
         od = oracle.conv_desc(N, H, H, C, K, R, R, st, (pad, pad))
         d = jz.conv_desc(N, H, H, C, K, R, R, st, (pad, pad))
-        assert "4-channel padded copy" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
-        plan_bw = jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
-        assert "4-channel padded copy" in plan_bw and ("%s splits" % splits) in plan_bw, plan_bw
-        rng = inputs.rng_for(20, int(tile), int(nst), H, R)
+        rng = inputs.rng_for(20, tile[0] * 1000 + tile[1], nst, H, R)
         x = inputs.normal_f16(rng, (N, H, H, C))
         w = inputs.he_normal_f32(rng, (K, R, R, C), R * R * C).astype(np.float16)
         dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
-        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, R, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+        bk_fwd = 32 if 4 * R <= 32 else 64           # one filter row of the padded copy is one k tile
+        with jzt.forced_variant(d, tile[0], tile[1], bk_fwd, 4, nst if bk_fwd == 32 else 4, ops=(jz.JZ_FWD,)):
+            assert "4-channel padded copy" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+            jzt.all_ops_against_the_oracle(d, od, x, w, dy, ops=(jz.JZ_FWD,))
+        with jzt.forced_variant(d, tile[0], tile[1], 32, 4, nst, splits=splits, ops=(jz.JZ_BWD_WEIGHT,)):
+            plan_bw = jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
+            assert "4-channel padded copy" in plan_bw and ("%d splits" % splits) in plan_bw, plan_bw
+            jzt.all_ops_against_the_oracle(d, od, x, w, dy, ops=(jz.JZ_BWD_WEIGHT,))
 
 
 def test_run_time_tuning_hook_runs_the_chosen_kernel_correctly(jz):
@@ -299,9 +268,7 @@ def test_run_time_tuning_hook_runs_the_chosen_kernel_correctly(jz):
         assert "tile 256x128x32, 8 wavefronts, ring 3" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
         assert "tile 128x128x32, 8 wavefronts, ring 4" in jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
         assert " 3 splits" in jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d)
-        jzt.check_half_output(jzt.run_conv(jz.JZ_FWD, d, x, w, (N, od.P, od.Q, K)), oracle.conv_fwd(od, x, w), what="fwd")
-        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_DATA, d, dy, w, (N, H, W, C)), oracle.conv_bwd_data(od, dy, w), what="bwd_data")
-        jzt.check_half_output(jzt.run_conv(jz.JZ_BWD_WEIGHT, d, x, dy, (K, R, S, C)), oracle.conv_bwd_weight(od, x, dy), what="bwd_weight")
+        res = jzt.all_ops_against_the_oracle(d, od, x, w, dy)
     finally:
         jz.jz_conv2d_tune_clear()
     assert jz.jz_conv2d_describe_plan(jz.JZ_BWD_WEIGHT, d) == before
@@ -312,9 +279,7 @@ def test_fully_connected_modes(jz, B, I, O):
     import jzt
     import oracle
     c = inputs.fc_case((15, B, I, O), B, I, O, loss_scale=32.0)
-    jzt.check_half_output(jzt.run_fc(jz.JZ_FWD, B, I, O, c.x, c.w16, (B, O)), oracle.fc_fwd(B, I, O, c.x, c.w16), what="fc fwd")
-    jzt.check_half_output(jzt.run_fc(jz.JZ_BWD_DATA, B, I, O, c.dy, c.w16, (B, I)), oracle.fc_bwd_data(B, I, O, c.dy, c.w16), what="fc bwd_data")
-    jzt.check_half_output(jzt.run_fc(jz.JZ_BWD_WEIGHT, B, I, O, c.dy, c.x, (O, I)), oracle.fc_bwd_weight(B, I, O, c.dy, c.x), what="fc bwd_weight")
+    jzt.fc_all_modes(B, I, O, c)
 
 
 def test_fc_equals_one_by_one_conv_bit_for_bit(jz):

@@ -1,8 +1,8 @@
 """GPU parity of jz_conv2d_bn_relu_fwd (forward convolution with the batch-norm statistics taken in its epilogue): the
 convolution output must be the bits jz_conv2d_fwd writes, and mean / invstd / y must meet the bars of the stand-alone
 batch normalization against the oracle evaluated on that convolution output.  Every kernel variant is forced through
-the planner's overrides, and the shapes that cannot take the sums in the epilogue (split reduction, register path)
-must give the same results through the fallback pass."""
+the planner's tuning hook, and a shape that cannot take the sums in the epilogue (split reduction) must give the same
+results through the fallback pass."""
 import numpy as np
 import pytest
 import torch
@@ -21,8 +21,11 @@ def jz():
     return api
 
 
-def run_case(jz, N, H, C, K, R, stride, pad, relu=True, key=0, eps=1e-5, residual=False):
+def run_case(jz, N, H, C, K, R, stride, pad, relu=True, key=0, eps=1e-5, residual=False, variant=None, splits=1):
     import jzt
+    if variant is not None:
+        with jzt.forced_variant(jz.conv_desc(N, H, H, C, K, R, R, stride, pad), *variant, splits=splits, ops=(jz.JZ_FWD,)):
+            return run_case(jz, N, H, C, K, R, stride, pad, relu, key, eps, residual)
     rng = inputs.rng_for(41, key, N, H, C, K, R)
     x = inputs.normal_f16(rng, (N * H * H * C,))
     w = inputs.normal_f16(rng, (K * R * R * C,), std=(2.0 / (R * R * C)) ** 0.5)
@@ -72,25 +75,16 @@ def test_fused_statistics_against_the_oracle(jz, N, H, C, K, R, stride, pad, rel
     run_case(jz, N, H, C, K, R, stride, pad, relu=relu, residual=True, key=7)
 
 
-@pytest.mark.parametrize("tile,bk,waves,nst", [("128128", "32", "4", "4"), ("128064", "32", "4", "4"), ("64128", "32", "4", "3"), ("64064", "64", "4", "4"),
-                                               ("128128", "64", "4", "4"), ("256128", "32", "8", "4"), ("256128", "64", "8", "3"),
-                                               ("256256", "32", "8", "4"), ("128128", "32", "8", "3"), ("128128", "64", "8", "4")])
-def test_every_kernel_variant_leaves_the_same_statistics(jz, monkeypatch, tile, bk, waves, nst):
-    monkeypatch.setenv("JZ_IGEMM_TILE", tile)
-    monkeypatch.setenv("JZ_IGEMM_BK", bk)
-    monkeypatch.setenv("JZ_IGEMM_WAVES", waves)
-    if nst == "3":
-        monkeypatch.setenv("JZ_IGEMM_NST", nst)
-    run_case(jz, 5, 24, 64, 192, 3, 1, 1, key=1)       # 2880 rows: 22.5 tiles of 128, 11.25 of 256
-    run_case(jz, 2, 10, 128, 72, 1, 1, 0, key=2)       # 200 rows, 72 channels: ragged both ways
+@pytest.mark.parametrize("variant", [(128, 128, 32, 4, 4), (128, 64, 32, 4, 4), (64, 128, 32, 4, 3), (64, 64, 64, 4, 4),
+                                     (128, 128, 64, 4, 4), (256, 128, 32, 8, 4), (256, 128, 64, 8, 3), (256, 256, 32, 8, 4),
+                                     (128, 128, 32, 8, 3), (128, 128, 64, 8, 4)], ids=lambda v: "x".join(str(i) for i in v))
+def test_every_kernel_variant_leaves_the_same_statistics(jz, variant):
+    run_case(jz, 5, 24, 64, 192, 3, 1, 1, key=1, variant=variant)       # 2880 rows: 22.5 tiles of 128, 11.25 of 256
+    run_case(jz, 2, 10, 128, 72, 1, 1, 0, key=2, variant=variant)       # 200 rows, 72 channels: ragged both ways
 
 
-def test_split_reduction_and_register_path_fall_back_to_the_statistics_pass(jz, monkeypatch):
-    monkeypatch.setenv("JZ_IGEMM_SPLITS", "3")
-    run_case(jz, 2, 14, 256, 64, 3, 1, 1, key=3)
-    monkeypatch.delenv("JZ_IGEMM_SPLITS")
-    monkeypatch.setenv("JZ_IGEMM_PATH", "reg")
-    run_case(jz, 2, 14, 256, 64, 3, 1, 1, key=4)
+def test_split_reduction_falls_back_to_the_statistics_pass(jz):
+    run_case(jz, 2, 14, 256, 64, 3, 1, 1, key=3, variant=(128, 64, 32, 4, 4), splits=3)
 
 
 def test_argument_errors(jz):
