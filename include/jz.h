@@ -91,6 +91,18 @@ int jz_conv2d_bwd_data(const jz_conv_desc* desc, const void* dy16, const void* w
 int jz_conv2d_bwd_weight(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16, void* ws,
                          size_t ws_bytes, void* hip_stream);
 
+/* jz_conv2d_bwd_weight for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and therefore have no workspace to pass: same kernels, same bits, with the
+ * scratch (split-K partial sums, the padded copy of a small-channel layer) in a fixed array of
+ * JZ_STATIC_SCRATCH_BYTES inside the library.  Every GPU the library runs on holds its own copy of that array for the
+ * life of the process.  Calls nothing that allocates.  JZ_ERR_WORKSPACE when the layer needs more scratch than the
+ * array holds (jz_conv2d_workspace_bytes(JZ_BWD_WEIGHT, ...) says how much); other status codes as
+ * jz_conv2d_bwd_weight.  All calls on one GPU share the array: calls that may overlap in time on one GPU (different
+ * streams, different threads) race on it and must be ordered by the caller; nothing in it needs clearing between
+ * calls (every byte that is read was written by the same call). */
+#define JZ_STATIC_SCRATCH_BYTES (64u << 20)
+int jz_conv2d_bwd_weight_static(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16, void* hip_stream);
+
 /* Fully connected layer, the classifier GEMMs of AlexNet / ResNet-50 (Table 3's models), same
  * FP16-storage / FP32-accumulate rule.  Row-major x[batch,in], w[out,in], y[batch,out]:
  *   JZ_FWD        out16 = y  = RNE16(x  * w^T)   a16 = x  [batch,in],  b16 = w [out,in]

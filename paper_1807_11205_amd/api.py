@@ -20,7 +20,7 @@ JZ_FWD, JZ_BWD_DATA, JZ_BWD_WEIGHT = 0, 1, 2
 JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
 
 EXPORTS = [
-    "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_use_table", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight",
+    "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_use_table", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight", "jz_conv2d_bwd_weight_static",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
     "jz_add_fwd", "jz_relu_bwd", "jz_relu_bwd_sum", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
@@ -88,6 +88,7 @@ def lib() -> ctypes.CDLL:
         L.jz_conv2d_tune_clear.argtypes = []
         for name in ("jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight"):
             getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.jz_conv2d_bwd_weight_static.argtypes = [dp, vp, vp, vp, vp]
         L.jz_gemm_fc_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
         L.jz_gemm_fc.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
         pp = ctypes.POINTER(jz_param_set)
@@ -254,6 +255,18 @@ def jz_conv2d_bwd_weight(desc, x16, dy16, dw16, ws=None, stream=None):
                                       _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
                                       _dev_ptr(dw16, h, d.K * d.R * d.S * d.C, "dw16"), wp, wn, _stream(stream)),
            "jz_conv2d_bwd_weight")
+
+
+JZ_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def jz_conv2d_bwd_weight_static(desc, x16, dy16, dw16, stream=None):
+    """jz_conv2d_bwd_weight without a workspace argument: scratch in the library's own fixed array."""
+    d, h = desc, torch.float16
+    _check(lib().jz_conv2d_bwd_weight_static(ctypes.byref(d), _dev_ptr(x16, h, d.N * d.H * d.W * d.C, "x16"),
+                                             _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
+                                             _dev_ptr(dw16, h, d.K * d.R * d.S * d.C, "dw16"), _stream(stream)),
+           "jz_conv2d_bwd_weight_static")
 
 
 class BoundCall:

@@ -608,6 +608,47 @@ extern "C" int jz_conv2d_bwd_weight(const jz_conv_desc* desc, const void* x16, c
   return run(JZ_BWD_WEIGHT, desc, dy16, x16, dw16, ws, ws_bytes, hip_stream);  // A = dy, B = x
 }
 
+// ---- backward-weight without a caller workspace ---------------------------------------------------------------
+// For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops): the same
+// kernels, with the split-K partial sums (and the padded copy of a small-channel layer) in a fixed array that lives
+// in the library's code object.  Every GPU the library runs on holds its own copy of the array at its own address for
+// the life of the process; host code must not use the array's name as an address, so the address is looked up once
+// per device and kept.
+#define JZ_SCRATCH_LEN ((size_t)JZ_STATIC_SCRATCH_BYTES)
+constexpr size_t kStaticScratchBytes = JZ_SCRATCH_LEN;
+static __device__ __align__(256) unsigned char scratch[JZ_SCRATCH_LEN];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return JZ_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return JZ_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return JZ_OK;
+}
+
+extern "C" int jz_conv2d_bwd_weight_static(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16,
+                                           void* hip_stream) {
+  Plan pl;
+  int rc = make_plan(JZ_BWD_WEIGHT, desc, &pl);
+  if (rc != JZ_OK) return rc;
+  if (pl.ws_bytes > kStaticScratchBytes) return JZ_ERR_WORKSPACE;  // the layer needs more scratch than the array holds
+  void* ws = nullptr;
+  if (pl.ws_bytes > 0 && (rc = static_scratch(&ws)) != JZ_OK) return rc;
+  return run(JZ_BWD_WEIGHT, desc, dy16, x16, dw16, ws, ws ? kStaticScratchBytes : 0, hip_stream);  // A = dy, B = x
+}
+
 extern "C" int jz_gemm_fc_workspace_bytes(int mode, int batch, int in_features, int out_features, size_t* bytes) {
   jz_conv_desc d;
   int rc = fc_desc(mode, batch, in_features, out_features, &d);
