@@ -3,7 +3,8 @@
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import
 this package.  It shares nothing with the HIP library and never imports it.
 
-* conv / FC: fp64 direct definitions in C (``jz_oracle.c``), called via ctypes.
+* conv / FC: fp64 direct definitions in C (``jz_oracle.c``), called via ctypes; inputs are fp16 bit patterns (the
+  mixed-precision path) or float32 arrays (the single-precision variant of Section 5.4 / Table 9): same loops.
 * LARS: the mixed-precision update of Section 4.1 / Eq. 1, step by step in
   fp64 numpy (``lars.py``).
 * the dynamic loss-scale controller around that update (``loss_scale.py``).
@@ -101,91 +102,99 @@ def round_to_half(values) -> np.ndarray:
     return out
 
 
-def conv_fwd(d: ConvDesc, x16, w16) -> np.ndarray:
-    x, w = _bits(x16), _bits(w16)
+def _operands(a, b):
+    """Two inputs of one dtype: fp16 (float16 or uint16 bit patterns) or float32.  Returns (a, b, ctype, name suffix)."""
+    a, b = np.asarray(a), np.asarray(b)
+    if a.dtype == np.float32 or b.dtype == np.float32:
+        if a.dtype != np.float32 or b.dtype != np.float32:
+            raise TypeError("oracle inputs must both be float32 or both be fp16, got %s and %s" % (a.dtype, b.dtype))
+        return np.ascontiguousarray(a), np.ascontiguousarray(b), ctypes.c_float, "_f32"
+    return _bits(a), _bits(b), ctypes.c_uint16, ""
+
+
+def conv_fwd(d: ConvDesc, x, w) -> np.ndarray:
+    x, w, ty, sfx = _operands(x, w)
     _chk(x, d.N * d.H * d.W * d.C, "x")
     _chk(w, d.K * d.R * d.S * d.C, "w")
     y = np.empty((d.N, d.P, d.Q, d.K), np.float64)
-    rc = lib().orc_conv_fwd(ctypes.byref(d), _p(x, ctypes.c_uint16), _p(w, ctypes.c_uint16), _p(y, ctypes.c_double))
+    rc = getattr(lib(), "orc_conv_fwd" + sfx)(ctypes.byref(d), _p(x, ty), _p(w, ty), _p(y, ctypes.c_double))
     assert rc == 0
     return y
 
 
-def conv_bwd_data(d: ConvDesc, dy16, w16) -> np.ndarray:
-    dy, w = _bits(dy16), _bits(w16)
+def conv_bwd_data(d: ConvDesc, dy, w) -> np.ndarray:
+    dy, w, ty, sfx = _operands(dy, w)
     _chk(dy, d.N * d.P * d.Q * d.K, "dy")
     _chk(w, d.K * d.R * d.S * d.C, "w")
     dx = np.empty((d.N, d.H, d.W, d.C), np.float64)
-    rc = lib().orc_conv_bwd_data(ctypes.byref(d), _p(dy, ctypes.c_uint16), _p(w, ctypes.c_uint16), _p(dx, ctypes.c_double))
+    rc = getattr(lib(), "orc_conv_bwd_data" + sfx)(ctypes.byref(d), _p(dy, ty), _p(w, ty), _p(dx, ctypes.c_double))
     assert rc == 0
     return dx
 
 
-def conv_bwd_weight(d: ConvDesc, x16, dy16) -> np.ndarray:
-    x, dy = _bits(x16), _bits(dy16)
+def conv_bwd_weight(d: ConvDesc, x, dy) -> np.ndarray:
+    x, dy, ty, sfx = _operands(x, dy)
     _chk(x, d.N * d.H * d.W * d.C, "x")
     _chk(dy, d.N * d.P * d.Q * d.K, "dy")
     dw = np.empty((d.K, d.R, d.S, d.C), np.float64)
-    rc = lib().orc_conv_bwd_weight(ctypes.byref(d), _p(x, ctypes.c_uint16), _p(dy, ctypes.c_uint16), _p(dw, ctypes.c_double))
+    rc = getattr(lib(), "orc_conv_bwd_weight" + sfx)(ctypes.byref(d), _p(x, ty), _p(dy, ty), _p(dw, ctypes.c_double))
     assert rc == 0
     return dw
 
 
-def _at(fn, d, a, b, idx):
+def _at(name, d, a, b, idx):
+    a, b, ty, sfx = _operands(a, b)
     idx = np.ascontiguousarray(idx, dtype=np.int64)
     out = np.empty(idx.shape, np.float64)
-    rc = fn(ctypes.byref(d), _p(a, ctypes.c_uint16), _p(b, ctypes.c_uint16), _p(idx, ctypes.c_int64),
-            ctypes.c_int64(idx.size), _p(out, ctypes.c_double))
+    rc = getattr(lib(), name + sfx)(ctypes.byref(d), _p(a, ty), _p(b, ty), _p(idx, ctypes.c_int64), ctypes.c_int64(idx.size),
+                                    _p(out, ctypes.c_double))
     assert rc == 0
     return out
 
 
-def conv_fwd_at(d, x16, w16, flat_idx):
+def conv_fwd_at(d, x, w, flat_idx):
     """Selected elements of y (flat NPQK indices), each by the plain definition."""
-    x, w = _bits(x16), _bits(w16)
-    _chk(x, d.N * d.H * d.W * d.C, "x")
-    _chk(w, d.K * d.R * d.S * d.C, "w")
-    return _at(lib().orc_conv_fwd_at, d, x, w, flat_idx)
+    _chk(np.asarray(x), d.N * d.H * d.W * d.C, "x")
+    _chk(np.asarray(w), d.K * d.R * d.S * d.C, "w")
+    return _at("orc_conv_fwd_at", d, x, w, flat_idx)
 
 
-def conv_bwd_data_at(d, dy16, w16, flat_idx):
+def conv_bwd_data_at(d, dy, w, flat_idx):
     """Selected elements of dx (flat NHWC indices)."""
-    dy, w = _bits(dy16), _bits(w16)
-    _chk(dy, d.N * d.P * d.Q * d.K, "dy")
-    _chk(w, d.K * d.R * d.S * d.C, "w")
-    return _at(lib().orc_conv_bwd_data_at, d, dy, w, flat_idx)
+    _chk(np.asarray(dy), d.N * d.P * d.Q * d.K, "dy")
+    _chk(np.asarray(w), d.K * d.R * d.S * d.C, "w")
+    return _at("orc_conv_bwd_data_at", d, dy, w, flat_idx)
 
 
-def conv_bwd_weight_at(d, x16, dy16, flat_idx):
+def conv_bwd_weight_at(d, x, dy, flat_idx):
     """Selected elements of dw (flat KRSC indices)."""
-    x, dy = _bits(x16), _bits(dy16)
-    _chk(x, d.N * d.H * d.W * d.C, "x")
-    _chk(dy, d.N * d.P * d.Q * d.K, "dy")
-    return _at(lib().orc_conv_bwd_weight_at, d, x, dy, flat_idx)
+    _chk(np.asarray(x), d.N * d.H * d.W * d.C, "x")
+    _chk(np.asarray(dy), d.N * d.P * d.Q * d.K, "dy")
+    return _at("orc_conv_bwd_weight_at", d, x, dy, flat_idx)
 
 
-def fc_fwd(B, I, O, x16, w16) -> np.ndarray:
-    x, w = _bits(x16), _bits(w16)
+def fc_fwd(B, I, O, x, w) -> np.ndarray:
+    x, w, ty, sfx = _operands(x, w)
     _chk(x, B * I, "x")
     _chk(w, O * I, "w")
     y = np.empty((B, O), np.float64)
-    assert lib().orc_fc_fwd(B, I, O, _p(x, ctypes.c_uint16), _p(w, ctypes.c_uint16), _p(y, ctypes.c_double)) == 0
+    assert getattr(lib(), "orc_fc_fwd" + sfx)(B, I, O, _p(x, ty), _p(w, ty), _p(y, ctypes.c_double)) == 0
     return y
 
 
-def fc_bwd_data(B, I, O, dy16, w16) -> np.ndarray:
-    dy, w = _bits(dy16), _bits(w16)
+def fc_bwd_data(B, I, O, dy, w) -> np.ndarray:
+    dy, w, ty, sfx = _operands(dy, w)
     _chk(dy, B * O, "dy")
     _chk(w, O * I, "w")
     dx = np.empty((B, I), np.float64)
-    assert lib().orc_fc_bwd_data(B, I, O, _p(dy, ctypes.c_uint16), _p(w, ctypes.c_uint16), _p(dx, ctypes.c_double)) == 0
+    assert getattr(lib(), "orc_fc_bwd_data" + sfx)(B, I, O, _p(dy, ty), _p(w, ty), _p(dx, ctypes.c_double)) == 0
     return dx
 
 
-def fc_bwd_weight(B, I, O, dy16, x16) -> np.ndarray:
-    dy, x = _bits(dy16), _bits(x16)
+def fc_bwd_weight(B, I, O, dy, x) -> np.ndarray:
+    dy, x, ty, sfx = _operands(dy, x)
     _chk(dy, B * O, "dy")
     _chk(x, B * I, "x")
     dw = np.empty((O, I), np.float64)
-    assert lib().orc_fc_bwd_weight(B, I, O, _p(dy, ctypes.c_uint16), _p(x, ctypes.c_uint16), _p(dw, ctypes.c_double)) == 0
+    assert getattr(lib(), "orc_fc_bwd_weight" + sfx)(B, I, O, _p(dy, ty), _p(x, ty), _p(dw, ctypes.c_double)) == 0
     return dw
