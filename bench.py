@@ -25,20 +25,20 @@ import torch
 from paper_1807_11205_amd import api, inputs, shapes
 
 FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
+FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix peak
 HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
 LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32 4 + w16 2
-# HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very workload (default batch and
-# variant), scaled by the same counters' readings for a 1 GiB copy; the runs are summarised under profiles/.
-MEASURED_BN_HBM_BYTES_PER_STEP = 14.18e9     # bench.py --workload bn at N = 64 (profiles/bench_bn_resnet50_n64_kernel_stats.txt)
-MEASURED_CHAIN_HBM_BYTES_PER_STEP = 24.27e9   # --workload chain, N = 64, fused calls (profiles/bench_chain_resnet50_n64_hbm_traffic.txt)
-MEASURED_GEMM_HBM_BYTES_PER_STEP = 9.61e9   # all conv/FC launches with their split-K reductions and packing kernels
-MEASURED_LARS_HBM_BYTES_PER_UPDATE = 562e6   # gradient norm pass 51 MB + update pass 511 MB
+# HBM bytes per step are never literals here: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries live under profiles/,
+# and the headline line quotes one only when it was taken with the kernel plans of the run (measured_traffic).
 
 
 class ResNet50Step:
     """All device buffers of one ResNet-50 N=batch step and the launch sequence."""
 
-    def __init__(self, batch=64, loss_scale=1024.0, seed=180711205, variant="v1", device="cuda:0"):
+    def __init__(self, batch=64, loss_scale=1024.0, seed=180711205, variant="v1", device="cuda:0", dtype="f16"):
+        """dtype "f32": the single-precision variant of the GEMM phase (float32 activations, filters = the master weights,
+        float32 weight gradients in a buffer of their own; the LARS update still runs on the fp16 gradient buffer)."""
+        self.f32 = dtype == "f32"
         self.N = batch
         self.dev = device
         self.loss_scale = float(loss_scale)
@@ -52,10 +52,10 @@ class ResNet50Step:
         self.offsets = shapes.offsets_of(tensors)
         self.flags = [t[3] for t in tensors]
         P = self.offsets[-1]
-        h = torch.float16
+        h = torch.float32 if self.f32 else torch.float16
 
-        def randn(n, std=1.0):
-            return (torch.randn(n, generator=gen, device=device, dtype=torch.float32) * std).to(h)
+        def randn(n, std=1.0, dt=None):
+            return (torch.randn(n, generator=gen, device=device, dtype=torch.float32) * std).to(dt or h)
 
         # fused flat parameter state: fp32 master (He-normal filters, gamma 1, beta 0, bias 0), momentum 0, fp16 copies
         self.master = torch.zeros(P, dtype=torch.float32, device=device)
@@ -67,10 +67,14 @@ class ResNet50Step:
             elif kind == "gamma":
                 self.master[a:b] = 1.0
         self.momentum = torch.zeros(P, dtype=torch.float32, device=device)
-        self.w16 = self.master.to(h)
+        self.w16 = self.master.to(torch.float16)
         # gradients of batch-norm and bias tensors are not produced on this path: fixed synthetic values ~ N(0,1e-3)*S
-        self.grad = randn(P, 1e-3 * self.loss_scale)
+        self.grad = randn(P, 1e-3 * self.loss_scale, torch.float16)
+        self.grad32 = torch.zeros(P, dtype=torch.float32, device=device) if self.f32 else None
         self.master0, self.w16_0 = self.master.clone(), self.w16.clone()
+        wsrc, gdst = (self.master, self.grad32) if self.f32 else (self.w16, self.grad)
+        ws_conv = api.jz_conv2d_f32_workspace_bytes if self.f32 else api.jz_conv2d_workspace_bytes
+        ws_fc = api.jz_gemm_fc_f32_workspace_bytes if self.f32 else api.jz_gemm_fc_workspace_bytes
 
         self.layers = []
         ws_bytes = 0
@@ -83,9 +87,9 @@ class ResNet50Step:
                      x=randn(batch * cs.H * cs.H * cs.C), dy=randn(batch * cs.P * cs.P * cs.K, self.loss_scale),
                      y=torch.empty(batch * cs.P * cs.P * cs.K, dtype=h, device=device),
                      dx=None if cs.first else torch.empty(batch * cs.H * cs.H * cs.C, dtype=h, device=device),
-                     w=self.w16[a:b], dw=self.grad[a:b], calls={})
+                     w=wsrc[a:b], dw=gdst[a:b], calls={})
             for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
-                ws_bytes = max(ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
+                ws_bytes = max(ws_bytes, ws_conv(op, d))
             self.flops += 2 * cs.macs(batch) * (2 if cs.first else 3)
             self.layers.append(L)
         ti = 3 * len(self.convs)
@@ -93,9 +97,9 @@ class ResNet50Step:
         B, I, O = batch, self.fc.I, self.fc.O
         self.layers.append(dict(kind="fc", name="fc", x=randn(B * I), dy=randn(B * O, self.loss_scale),
                                 y=torch.empty(B * O, dtype=h, device=device), dx=torch.empty(B * I, dtype=h, device=device),
-                                w=self.w16[a:b], dw=self.grad[a:b], calls={}))
+                                w=wsrc[a:b], dw=gdst[a:b], calls={}))
         for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
-            ws_bytes = max(ws_bytes, api.jz_gemm_fc_workspace_bytes(op, B, I, O))
+            ws_bytes = max(ws_bytes, ws_fc(op, B, I, O))
         self.flops += 2 * self.fc.macs(batch) * 3
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)
         self.side_ws = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device) for _ in range(3)]
@@ -118,10 +122,10 @@ class ResNet50Step:
         if key not in L["calls"]:
             if L["kind"] == "conv":
                 a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("x", "dy", "dw")}[op]
-                L["calls"][key] = api.bind_conv2d(op, L["d"], L[a], L[b], L[o], ws)
+                L["calls"][key] = (api.bind_conv2d_f32 if self.f32 else api.bind_conv2d)(op, L["d"], L[a], L[b], L[o], ws)
             else:
                 a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("dy", "x", "dw")}[op]
-                L["calls"][key] = api.bind_gemm_fc(op, B, I, O, L[a], L[b], L[o], ws)
+                L["calls"][key] = (api.bind_gemm_fc_f32 if self.f32 else api.bind_gemm_fc)(op, B, I, O, L[a], L[b], L[o], ws)
         return L["calls"][key]
 
     def build_program(self, n_side):
@@ -218,12 +222,16 @@ class ResNet50Step:
         self.momentum.zero_()
 
 
-def per_layer_report(wl, iters=20):
-    """Time every launch of the step on its own (HIP events, `iters` back-to-back repeats) and print one line per
-    layer and op: time, TFLOP/s, the layer's own roofline min(MFMA peak, flop / compulsory bytes * HBM peak) and the
-    fraction of it reached.  Compulsory bytes = both inputs read once + the output written once."""
+def per_layer_report(wl, iters=20, out_path=None, peak=FP16_MFMA_PEAK_TFLOPS):
+    """Time every launch of the step on its own (HIP events) and print one line per layer and op: time warm (`iters`
+    back-to-back repeats) and cold (caches flushed by a 768 MB read before each of three launches, the fastest: inside
+    the step every layer finds its operands cold), TFLOP/s, the layer's own roofline min(matrix peak, flop / compulsory
+    bytes * HBM peak), the fraction of it reached (warm), and the kernel plan.  Compulsory bytes = both inputs read
+    once + the output written once.  Returns the rows as dicts; out_path: also written there as a text table."""
     B, I, O = wl.N, wl.fc.I, wl.fc.O
     rows = []
+    junk = torch.zeros(192 << 20, dtype=torch.float32, device=wl.dev)
+    esz = 4 if wl.f32 else 2
 
     def timeit(fn):
         fn()
@@ -234,36 +242,59 @@ def per_layer_report(wl, iters=20):
             fn()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        warm = e0.elapsed_time(e1) / iters
+        cold = 1e9
+        for _ in range(3):
+            junk.sum()      # read-only pass over 768 MB: evicts L2 and the last-level cache without leaving dirty lines
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            cold = min(cold, e0.elapsed_time(e1))
+        return warm, cold
 
+    lines = ["# per-layer, per-op timing of the %s step (ResNet-50 v1, N = %d): every launch alone on an idle GPU" % ("fp32" if wl.f32 else "fp16", wl.N),
+             "# us warm = mean of %d back-to-back launches; us cold = fastest of 3 launches behind a 768 MB cache flush;" % iters,
+             "# roofline = min(%.1f TFLOP/s, flop / (bytes of both inputs + output) * 8 TB/s); frac = warm TFLOP/s / roofline;" % peak,
+             "# us@roof = the time that roofline allows; plan = the library's kernel choice (jz_conv2d_describe_plan)",
+             "# layer   shape                    op          us warm  us cold  TFLOP/s  roofline  frac   us@roof  plan"]
+    opname = {api.JZ_FWD: "fwd", api.JZ_BWD_DATA: "bwd_data", api.JZ_BWD_WEIGHT: "bwd_weight"}
     for L in wl.layers:
         if L["kind"] == "conv":
             d = L["d"]
             macs = d.N * d.P * d.Q * d.K * d.R * d.S * d.C
-            ops = [("fwd", lambda: api.jz_conv2d_fwd(d, L["x"], L["w"], L["y"], wl.ws))]
-            if not L["first"]:
-                ops.append(("bwd_data", lambda: api.jz_conv2d_bwd_data(d, L["dy"], L["w"], L["dx"], wl.ws)))
-            ops.append(("bwd_weight", lambda: api.jz_conv2d_bwd_weight(d, L["x"], L["dy"], L["dw"], wl.ws)))
-            nbytes = 2 * (L["x"].numel() + L["w"].numel() + L["y"].numel())
             desc = "%dx%d %d->%d %dx%d s%d" % (d.H, d.W, d.C, d.K, d.R, d.S, d.stride_h)
         else:
+            d = api.conv_desc(B, 1, 1, I, O, 1, 1)
             macs = B * I * O
-            ops = [("fwd", lambda: api.jz_gemm_fc(api.JZ_FWD, B, I, O, L["x"], L["w"], L["y"], wl.ws)),
-                   ("bwd_data", lambda: api.jz_gemm_fc(api.JZ_BWD_DATA, B, I, O, L["dy"], L["w"], L["dx"], wl.ws)),
-                   ("bwd_weight", lambda: api.jz_gemm_fc(api.JZ_BWD_WEIGHT, B, I, O, L["dy"], L["x"], L["dw"], wl.ws))]
-            nbytes = 2 * (L["x"].numel() + L["w"].numel() + L["y"].numel())
             desc = "fc %d->%d" % (I, O)
-        for name, fn in ops:
-            ms = timeit(fn)
-            tf = 2 * macs / (ms * 1e-3) / 1e12
-            roof = min(FP16_MFMA_PEAK_TFLOPS, 2 * macs / nbytes * HBM_PEAK_GBPS / 1e3)
-            rows.append((L["name"], desc, name, ms, tf, roof, tf / roof))
-            print("%-7s %-24s %-10s %8.1f us %8.1f TFLOP/s  roofline %7.1f  frac %.3f" % (L["name"], desc, name, ms * 1e3, tf, roof, tf / roof),
-                  file=sys.stderr, flush=True)
-    tot = sum(r[3] for r in rows)
-    print("sum of per-launch times: %.3f ms" % tot, file=sys.stderr)
+        nbytes = esz * (L["x"].numel() + L["w"].numel() + L["y"].numel())
+        for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
+            if op == api.JZ_BWD_DATA and L.get("first"):
+                continue
+            call = wl._bound(L, op, wl.ws)
+            warm, cold = timeit(call)
+            tf = 2 * macs / (warm * 1e-3) / 1e12
+            roof = min(peak, 2 * macs / nbytes * HBM_PEAK_GBPS / 1e3)
+            plan = "" if wl.f32 else api.jz_conv2d_describe_plan(op, d).split(": ", 1)[1]
+            r = dict(layer=L["name"], shape=desc, op=opname[op], us=warm * 1e3, us_cold=cold * 1e3, tflops=tf, roofline_tflops=roof,
+                     frac=tf / roof, us_roofline=2 * macs / roof / 1e6, plan=plan)
+            rows.append(r)
+            line = "%-7s %-24s %-10s %8.1f %8.1f %8.1f %9.1f %6.3f %8.1f  %s" % (r["layer"], desc, r["op"], r["us"], r["us_cold"], tf, roof,
+                                                                               r["frac"], r["us_roofline"], plan)
+            lines.append(line)
+            print(line, file=sys.stderr, flush=True)
+    lines.append("# sums over the step's launches (us): warm %.1f, cold %.1f, at the per-layer rooflines %.1f" % (
+        sum(r["us"] for r in rows), sum(r["us_cold"] for r in rows), sum(r["us_roofline"] for r in rows)))
     for opn in ("fwd", "bwd_data", "bwd_weight"):
-        print("  %-10s %.3f ms" % (opn, sum(r[3] for r in rows if r[2] == opn)), file=sys.stderr)
+        sel = [r for r in rows if r["op"] == opn]
+        lines.append("#   %-10s warm %.1f  cold %.1f  roofline %.1f" % (opn, sum(r["us"] for r in sel), sum(r["us_cold"] for r in sel),
+                                                                        sum(r["us_roofline"] for r in sel)))
+    for ln in lines[-4:]:
+        print(ln, file=sys.stderr)
+    if out_path:
+        with open(out_path, "w") as f:
+            f.write("\n".join(lines) + "\n")
     return rows
 
 
@@ -404,9 +435,9 @@ def bn_workload(args):
                                "independent seeded inputs", "batch": B, "elements_per_pass": elems, "launch": "eager", "streams": 1},
         "roofline": {"kernel": "bn_stats / bn_apply / bn_bwd_apply (6 launches per layer)", "bound": "hbm", "achieved": gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_BN_HBM_BYTES_PER_STEP if B == 64 else None,
-                     "traffic_note": "HBM bytes per step (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled): every "
-                                     "direction is two passes over the tensors, 20 bytes per element against 12 algorithmic",
+                     "traffic": None,
+                     "traffic_note": "not measured in this run; profiles/bench_bn_resnet50_n64_kernel_stats.txt holds the HBM-counter "
+                                     "summary of this workload (20.9 bytes per element moved against 12 algorithmic when it was taken)",
                      "bytes_per_element": 12}}))
 
 
@@ -463,10 +494,8 @@ def chain_workload(args):
         "roofline": {"kernel": "whole step (GEMM flops of the convolutions and the classifier over the step's GPU time)",
                      "bound": "mfma", "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None},
-        "hbm": ({"bytes_per_step": MEASURED_CHAIN_HBM_BYTES_PER_STEP, "achieved": MEASURED_CHAIN_HBM_BYTES_PER_STEP / (gpu_ms * 1e-3) / 1e9,
-                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": MEASURED_CHAIN_HBM_BYTES_PER_STEP / (gpu_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                 "note": "HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (copy-kernel scaled) over this step's time"}
-                if args.batch == 64 and net.fused else None)}))
+        "hbm": {"bytes_per_step": None, "note": "not measured in this run; profiles/bench_chain_resnet50_n64_hbm_traffic.txt holds the "
+                                                  "HBM-counter summary of this workload"}}))
 
 
 def cpu_baseline(sample_batch=8):
@@ -501,6 +530,87 @@ def cpu_baseline(sample_batch=8):
             "lars_gbps": LARS_BYTES_PER_PARAM * ps.P / lars_s / 1e9}
 
 
+def time_steps(wl, stream, side, steps, warmup, graph=0):
+    """`warmup` untimed steps, then `steps` timed ones: host wall clock around all of them (the reported ms_per_step)
+    and HIP events on the launch stream around the GEMM phase and the LARS update of every step."""
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    with torch.cuda.stream(stream):
+        for _ in range(max(warmup, 1)):
+            wl.run_gemms(side)
+            wl.run_lars()
+        stream.synchronize()
+        graphs = None
+        if graph:
+            # two graphs (GEMM phase, LARS phase) so that HIP events can separate the phases between replays
+            g1, g2 = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g1, stream=stream):
+                wl.run_gemms(side)
+            with torch.cuda.graph(g2, stream=stream):
+                wl.run_lars()
+            graphs = (g1, g2)
+            for _ in range(2):
+                g1.replay(); g2.replay()
+            stream.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            ev[k][0].record(stream)
+            if graphs:
+                graphs[0].replay()
+            else:
+                wl.run_gemms(side)
+            ev[k][1].record(stream)
+            if graphs:
+                graphs[1].replay()
+            else:
+                wl.run_lars()
+            ev[k][2].record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    assert int(wl.found_inf.item()) == 0
+    g = np.array([e[0].elapsed_time(e[1]) for e in ev])
+    l = np.array([e[1].elapsed_time(e[2]) for e in ev])
+    return {"wall_ms": wall * 1e3 / steps, "gemm_ms": float(g.mean()), "gemm_ms_median": float(np.median(g)), "gemm_ms_min": float(g.min()),
+            "lars_ms": float(l.mean()), "lars_ms_median": float(np.median(l)), "lars_ms_min": float(l.min()),
+            "step_ms_mean": float((g + l).mean()), "step_ms_median": float(np.median(g + l)), "step_ms_min": float((g + l).min())}
+
+
+def plans_digest(wl):
+    """A fingerprint of how the library would run every launch of the step (kernel variant, tiles, splits per layer and
+    op): a traffic figure measured under one set of plans says nothing about another."""
+    import hashlib
+    hsh = hashlib.sha256()
+    B, I, O = wl.N, wl.fc.I, wl.fc.O
+    for L in wl.layers:
+        for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
+            if L.get("first") and op == api.JZ_BWD_DATA:
+                continue
+            d = L["d"] if L["kind"] == "conv" else api.conv_desc(B, 1, 1, I, O, 1, 1)
+            hsh.update(api.jz_conv2d_describe_plan(op, d).encode())
+    return hsh.hexdigest()[:16]
+
+
+TRAFFIC_PROFILE = "profiles/bench_resnet50_n64_hbm_traffic.txt"
+
+
+def measured_traffic(wl):
+    """HBM bytes per step from the rocprofv3 counter summary under profiles/ (FETCH_SIZE / WRITE_SIZE, copy-kernel
+    scaled), but only if that summary was taken with the kernel plans this run uses: the summary records their digest."""
+    import os
+    import re
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), TRAFFIC_PROFILE)
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    m = re.search(r"^# machine-readable: plans_digest=(\w+) gemm_phase_hbm_bytes_per_step=([\d.e+]+) lars_hbm_bytes_per_update=([\d.e+]+)", text, re.M)
+    if not m or m.group(1) != plans_digest(wl):
+        return None
+    return {"bytes": float(m.group(2)), "lars_bytes": float(m.group(3)),
+            "note": "HBM bytes per step of all these launches from %s (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled), "
+                    "taken with the same kernel plans as this run (digest %s)" % (TRAFFIC_PROFILE, m.group(1))}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -513,6 +623,12 @@ def main():
                          "ResNet-50 training step with every layer between the convolutions (not the headline step either)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
+    ap.add_argument("--per-layer-file", default=None, help="write the per-layer table (time, TFLOP/s, the layer's own roofline, "
+                    "fraction, kernel plan) to this file as well; implies --per-layer")
+    ap.add_argument("--dtype", default="f16", choices=("f16", "f32"), help="f16: the mixed-precision path (the headline); f32: the "
+                    "single-precision variant of the same step (Table 9's comparison)")
+    ap.add_argument("--no-fp32", action="store_true", help="skip the short single-precision run that the default line reports beside the headline")
+    ap.add_argument("--plans-digest", action="store_true", help="print the fingerprint of this workload's kernel plans and exit")
     ap.add_argument("--streams", type=int, default=3, help="1: everything in order on one stream; n > 1: n-1 side streams "
                     "for the projection shortcuts (forward) and the backward-weight launches (at most 4)")
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a HIP graph (1) or launch eagerly (0); eager launches measured faster here")
@@ -537,6 +653,9 @@ def main():
         sys.exit(2)
     api.lib()
     torch.cuda.set_device(0)
+    if args.plans_digest:
+        print(plans_digest(ResNet50Step(batch=args.batch or 64)))
+        return
     if args.batch is None:
         args.batch = 128 if args.workload == "alexnet" else 64
     if args.workload == "alexnet":
@@ -548,7 +667,7 @@ def main():
     if args.workload == "chain":
         chain_workload(args)
         return
-    wl = ResNet50Step(batch=args.batch)
+    wl = ResNet50Step(batch=args.batch, dtype=args.dtype)
 
     # loss-scale back-off: halve S until the weight gradients stay inside fp16 and the update is not skipped
     for _ in range(12):
@@ -562,82 +681,66 @@ def main():
     if args.dynamic_loss_scale:
         wl.use_dynamic_loss_scale()
 
-    if args.per_layer:
-        per_layer_report(wl)
+    rows = None
+    if args.per_layer or args.per_layer_file:
+        rows = per_layer_report(wl, out_path=args.per_layer_file, peak=FP32_MFMA_PEAK_TFLOPS if wl.f32 else FP16_MFMA_PEAK_TFLOPS)
         wl.reset_state()
 
     stream = torch.cuda.Stream()
     side = [torch.cuda.Stream() for _ in range(max(0, min(args.streams, 4) - 1))]
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    with torch.cuda.stream(stream):
-        for _ in range(max(args.warmup, 1)):
-            wl.run_gemms(side)
-            wl.run_lars()
-        stream.synchronize()
-        graphs = None
-        if args.graph:
-            # two graphs (GEMM phase, LARS phase) so that HIP events can separate the phases between replays
-            g1, g2 = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g1, stream=stream):
-                wl.run_gemms(side)
-            with torch.cuda.graph(g2, stream=stream):
-                wl.run_lars()
-            graphs = (g1, g2)
-            for _ in range(2):
-                g1.replay(); g2.replay()
-            stream.synchronize()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            ev[k][0].record(stream)
-            if graphs:
-                graphs[0].replay()
-            else:
-                wl.run_gemms(side)
-            ev[k][1].record(stream)
-            if graphs:
-                graphs[1].replay()
-            else:
-                wl.run_lars()
-            ev[k][2].record(stream)
-        stream.synchronize()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-    assert int(wl.found_inf.item()) == 0
-    gemm_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    lars_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-    ms_per_step = wall * 1e3 / args.steps
-    n_gemm = 0
-    for L in wl.layers:
-        n_gemm += 3 if not L.get("first") else 2
-    default_workload = args.batch == 64
+    t = time_steps(wl, stream, side, args.steps, args.warmup, graph=args.graph)
+    gemm_ms, lars_ms, ms_per_step = t["gemm_ms"], t["lars_ms"], t["wall_ms"]
+    n_gemm = sum(3 if not L.get("first") else 2 for L in wl.layers)
+    default_workload = args.batch == 64 and not wl.f32
+    peak = FP32_MFMA_PEAK_TFLOPS if wl.f32 else FP16_MFMA_PEAK_TFLOPS
     tflops = wl.flops / (gemm_ms * 1e-3) / 1e12
     lars_gbps = LARS_BYTES_PER_PARAM * wl.P / (lars_ms * 1e-3) / 1e9
+    traffic = measured_traffic(wl) if default_workload else None
     out = {
-        "metric": "ResNet-50 N=64 fp16 fwd+bwd images/s",
+        "metric": "ResNet-50 N=64 fp16 fwd+bwd images/s" if not wl.f32 else "ResNet-50 N=%d fp32 fwd+bwd images/s" % args.batch,
         "value": args.batch / (ms_per_step * 1e-3),
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16 storage, f32 accumulate (LARS in f32, norms f64)",
+        "dtype": "f32 storage, f32 accumulate (LARS as in the mixed-precision step)" if wl.f32 else
+                 "f16 storage, f32 accumulate (LARS in f32, norms f64)",
         "data": "synthetic",
         "config": {"workload": "configs[4]: ResNet-50 v1, 53 convs + FC, fwd + bwd_data + bwd_weight per layer on "
                                "independent seeded N(0,1) inputs, then fused LARS over 161 tensors / 25,557,032 params",
-                   "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "loss_scale_control": "device" if args.dynamic_loss_scale else "fixed", "launch": "hip graph" if graphs else "eager", "streams": args.streams},
+                   "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "loss_scale_control": "device" if args.dynamic_loss_scale else "fixed", "launch": "hip graph" if args.graph else "eager", "streams": args.streams},
+        "ms_per_step_stats": {"gpu_mean": t["step_ms_mean"], "gpu_median": t["step_ms_median"], "gpu_min": t["step_ms_min"],
+                              "note": "per-step HIP-event times (GEMM phase + LARS) over the timed steps; ms_per_step is host wall clock / steps"},
         "pct_fp16_mfma_peak": 100.0 * (wl.flops / (ms_per_step * 1e-3) / 1e12) / FP16_MFMA_PEAK_TFLOPS,
-        "roofline": {"kernel": "igemm_kernel (all %d conv/FC launches of a step)" % n_gemm, "bound": "mfma",
-                     "achieved": tflops, "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops / FP16_MFMA_PEAK_TFLOPS,
-                     "traffic": MEASURED_GEMM_HBM_BYTES_PER_STEP if default_workload else None,
-                     "traffic_note": "HBM bytes per step of all these launches (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-"
-                                     "kernel scaled); algorithmic 2(|x|+|w|+|y|) per pass is 7.99e9",
-                     "flop_per_step": wl.flops, "ms_per_step_gemm_phase": gemm_ms, "avg_launch_us": gemm_ms * 1e3 / n_gemm},
+        "roofline": {"kernel": "%s (all %d conv/FC launches of a step)" % ("igemm_f32_kernel" if wl.f32 else "igemm_dma_kernel", n_gemm),
+                     "bound": "mfma", "achieved": tflops, "peak": peak, "unit": "TFLOP/s", "frac": tflops / peak,
+                     "traffic": traffic["bytes"] if traffic else None,
+                     "traffic_note": (traffic["note"] if traffic else "no HBM-counter summary under profiles/ matches this run's kernel plans") +
+                                     "; algorithmic 2(|x|+|w|+|y|) per pass is 7.99e9 at fp16 storage",
+                     "flop_per_step": wl.flops, "ms_per_step_gemm_phase": gemm_ms, "ms_gemm_phase_median": t["gemm_ms_median"],
+                     "ms_gemm_phase_min": t["gemm_ms_min"], "avg_launch_us": gemm_ms * 1e3 / n_gemm},
         "lars": {"bound": "hbm", "achieved": lars_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": lars_gbps / HBM_PEAK_GBPS,
                  "bytes_per_param": LARS_BYTES_PER_PARAM, "params": wl.P, "us_per_update": lars_ms * 1e3,
-                 "traffic": MEASURED_LARS_HBM_BYTES_PER_UPDATE if default_workload else None},
+                 "us_per_update_median": t["lars_ms_median"] * 1e3, "us_per_update_min": t["lars_ms_min"] * 1e3,
+                 "traffic": traffic["lars_bytes"] if traffic else None},
     }
+    if rows is not None:
+        worst = sorted(rows, key=lambda r: r["us"] - r["us_roofline"], reverse=True)[:10]
+        out["per_layer_worst"] = [{k: r[k] for k in ("layer", "shape", "op", "us", "us_roofline", "tflops", "roofline_tflops", "frac", "plan")}
+                                  for r in worst]
+    if not wl.f32 and not args.no_fp32:
+        # Table 9's comparison on this chip: the same step with the single-precision kernels (a short run of its own)
+        wl32 = ResNet50Step(batch=args.batch, dtype="f32")
+        t32 = time_steps(wl32, stream, side, max(3, args.steps // 4), 2)
+        v32 = args.batch / (t32["wall_ms"] * 1e-3)
+        tf32 = wl32.flops / (t32["gemm_ms"] * 1e-3) / 1e12
+        out["fp32_variant"] = {"value": v32, "unit": "images/s", "ms_per_step": t32["wall_ms"], "steps": max(3, args.steps // 4),
+                               "achieved": tf32, "peak": FP32_MFMA_PEAK_TFLOPS, "frac": tf32 / FP32_MFMA_PEAK_TFLOPS,
+                               "mixed_over_fp32": out["value"] / v32,
+                               "paper_table9": {"fp32_images_per_s": 172, "mixed_images_per_s": 218, "ratio": 218.0 / 172.0,
+                                                "hardware": "one Tesla P40 node (no FP16 matrix units)"}}
+        del wl32
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

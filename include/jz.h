@@ -112,6 +112,24 @@ int jz_gemm_fc_workspace_bytes(int mode, int batch, int in_features, int out_fea
 int jz_gemm_fc(int mode, int batch, int in_features, int out_features, const void* a16, const void* b16, void* out16,
                void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- the same four operations in single precision (Section 5.4, Table 9: the FP32 side of the paper's FP32 versus
+ * mixed-precision throughput comparison) --------------------------------------------------------------------------
+ * FP32 storage, FP32 products and sums (v_mfma_f32_32x32x2_f32), no rounding to FP16 anywhere: same definitions, same
+ * layouts (NHWC / KRSC / NPQK), same GEMM view, same conventions and status codes as the FP16 entry points above, with
+ * float tensors (DEVICE, 16-byte aligned).  Split reductions leave FP32 partial sums in `ws` and are added in index
+ * order (deterministic).  Meant as the baseline the mixed-precision path is compared with: one kernel family sized
+ * for the FP32 matrix peak, no table of tuned variants. */
+int jz_conv2d_f32_workspace_bytes(int op, const jz_conv_desc* desc, size_t* bytes);
+int jz_conv2d_fwd_f32(const jz_conv_desc* desc, const float* x32, const float* w32, float* y32, void* ws, size_t ws_bytes,
+                      void* hip_stream);
+int jz_conv2d_bwd_data_f32(const jz_conv_desc* desc, const float* dy32, const float* w32, float* dx32, void* ws,
+                           size_t ws_bytes, void* hip_stream);
+int jz_conv2d_bwd_weight_f32(const jz_conv_desc* desc, const float* x32, const float* dy32, float* dw32, void* ws,
+                             size_t ws_bytes, void* hip_stream);
+int jz_gemm_fc_f32_workspace_bytes(int mode, int batch, int in_features, int out_features, size_t* bytes);
+int jz_gemm_fc_f32(int mode, int batch, int in_features, int out_features, const float* a32, const float* b32, float* out32,
+                   void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ---- mixed-precision LARS update (Section 4.1, Eq. 1, Fig. 2) -------------------------------------------- */
 
 enum {

@@ -22,6 +22,8 @@ JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
 EXPORTS = [
     "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_use_table", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight", "jz_conv2d_bwd_weight_static",
     "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
+    "jz_conv2d_f32_workspace_bytes", "jz_conv2d_fwd_f32", "jz_conv2d_bwd_data_f32", "jz_conv2d_bwd_weight_f32",
+    "jz_gemm_fc_f32_workspace_bytes", "jz_gemm_fc_f32",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
     "jz_add_fwd", "jz_relu_bwd", "jz_relu_bwd_sum", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
     "jz_bias_grad", "jz_softmax_xent_bwd", "jz_conv2d_bn_relu_fwd_workspace_bytes", "jz_conv2d_bn_relu_fwd",
@@ -89,6 +91,11 @@ def lib() -> ctypes.CDLL:
         for name in ("jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight"):
             getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.jz_conv2d_bwd_weight_static.argtypes = [dp, vp, vp, vp, vp]
+        L.jz_conv2d_f32_workspace_bytes.argtypes = [ci, dp, ctypes.POINTER(sz)]
+        for name in ("jz_conv2d_fwd_f32", "jz_conv2d_bwd_data_f32", "jz_conv2d_bwd_weight_f32"):
+            getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.jz_gemm_fc_f32_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
+        L.jz_gemm_fc_f32.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
         L.jz_gemm_fc_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
         L.jz_gemm_fc.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
         pp = ctypes.POINTER(jz_param_set)
@@ -255,6 +262,52 @@ def jz_conv2d_bwd_weight(desc, x16, dy16, dw16, ws=None, stream=None):
                                       _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
                                       _dev_ptr(dw16, h, d.K * d.R * d.S * d.C, "dw16"), wp, wn, _stream(stream)),
            "jz_conv2d_bwd_weight")
+
+
+# ---- the single-precision variant (same operations, float tensors) ----------------------------------------------------
+def jz_conv2d_f32_workspace_bytes(op: int, desc: jz_conv_desc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().jz_conv2d_f32_workspace_bytes(op, ctypes.byref(desc), ctypes.byref(n)), "jz_conv2d_f32_workspace_bytes")
+    return n.value
+
+
+def jz_conv2d_f32(op: int, desc: jz_conv_desc, a32, b32, out32, ws=None, stream=None):
+    """op JZ_FWD: (x, w) -> y; JZ_BWD_DATA: (dy, w) -> dx; JZ_BWD_WEIGHT: (x, dy) -> dw; float32 GPU tensors."""
+    d, f = desc, torch.float32
+    nx, ny, nw = d.N * d.H * d.W * d.C, d.N * d.P * d.Q * d.K, d.K * d.R * d.S * d.C
+    na, nb, no = {JZ_FWD: (nx, nw, ny), JZ_BWD_DATA: (ny, nw, nx), JZ_BWD_WEIGHT: (nx, ny, nw)}[op]
+    fn = {JZ_FWD: lib().jz_conv2d_fwd_f32, JZ_BWD_DATA: lib().jz_conv2d_bwd_data_f32, JZ_BWD_WEIGHT: lib().jz_conv2d_bwd_weight_f32}[op]
+    wp, wn = _ws(ws)
+    _check(fn(ctypes.byref(d), _dev_ptr(a32, f, na, "first input"), _dev_ptr(b32, f, nb, "second input"), _dev_ptr(out32, f, no, "output"),
+              wp, wn, _stream(stream)), "jz_conv2d_f32")
+
+
+def jz_gemm_fc_f32_workspace_bytes(mode: int, batch: int, in_features: int, out_features: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().jz_gemm_fc_f32_workspace_bytes(mode, batch, in_features, out_features, ctypes.byref(n)), "jz_gemm_fc_f32_workspace_bytes")
+    return n.value
+
+
+def jz_gemm_fc_f32(mode: int, batch: int, in_features: int, out_features: int, a32, b32, out32, ws=None, stream=None):
+    """mode JZ_FWD: (x, w) -> y; JZ_BWD_DATA: (dy, w) -> dx; JZ_BWD_WEIGHT: (dy, x) -> dw; float32 GPU tensors."""
+    B, I, O, f = batch, in_features, out_features, torch.float32
+    na, nb, no = {JZ_FWD: (B * I, O * I, B * O), JZ_BWD_DATA: (B * O, O * I, B * I), JZ_BWD_WEIGHT: (B * O, B * I, O * I)}[mode]
+    wp, wn = _ws(ws)
+    _check(lib().jz_gemm_fc_f32(mode, B, I, O, _dev_ptr(a32, f, na, "first input"), _dev_ptr(b32, f, nb, "second input"),
+                                _dev_ptr(out32, f, no, "output"), wp, wn, _stream(stream)), "jz_gemm_fc_f32")
+
+
+def bind_conv2d_f32(op: int, desc: jz_conv_desc, a32, b32, out32, ws=None):
+    """Pre-marshalled jz_conv2d_*_f32 call (see BoundCall)."""
+    fn = {JZ_FWD: lib().jz_conv2d_fwd_f32, JZ_BWD_DATA: lib().jz_conv2d_bwd_data_f32, JZ_BWD_WEIGHT: lib().jz_conv2d_bwd_weight_f32}[op]
+    wp, wn = _ws(ws)
+    return BoundCall(fn, (ctypes.byref(desc), a32.data_ptr(), b32.data_ptr(), out32.data_ptr(), wp, wn), "jz_conv2d_f32", (desc, a32, b32, out32, ws))
+
+
+def bind_gemm_fc_f32(mode: int, batch: int, in_features: int, out_features: int, a32, b32, out32, ws=None):
+    wp, wn = _ws(ws)
+    return BoundCall(lib().jz_gemm_fc_f32, (mode, batch, in_features, out_features, a32.data_ptr(), b32.data_ptr(), out32.data_ptr(), wp, wn),
+                     "jz_gemm_fc_f32", (a32, b32, out32, ws))
 
 
 JZ_STATIC_SCRATCH_BYTES = 64 << 20
