@@ -35,10 +35,13 @@ LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32
 class ResNet50Step:
     """All device buffers of one ResNet-50 N=batch step and the launch sequence."""
 
-    def __init__(self, batch=64, loss_scale=1024.0, seed=180711205, variant="v1", device="cuda:0", dtype="f16"):
+    def __init__(self, batch=64, loss_scale=1024.0, seed=180711205, variant="v1", device="cuda:0", dtype="f16", lars_path="presummed"):
         """dtype "f32": the single-precision variant of the GEMM phase (float32 activations, filters = the master weights,
-        float32 weight gradients in a buffer of their own; the LARS update still runs on the fp16 gradient buffer)."""
+        float32 weight gradients in a buffer of their own; the LARS update still runs on the fp16 gradient buffer).
+        lars_path "presummed": the backward-weight launches leave each filter gradient's sum of squares in the optimiser's
+        workspace and the update is one launch; "three_launches": plain backward-weight, jz_lars_mp_update."""
         self.f32 = dtype == "f32"
+        self.presummed = lars_path == "presummed" and not self.f32
         self.N = batch
         self.dev = device
         self.loss_scale = float(loss_scale)
@@ -50,7 +53,8 @@ class ResNet50Step:
         self.fc = shapes.RESNET50_FC
         tensors = shapes.resnet50_param_tensors(variant)
         self.offsets = shapes.offsets_of(tensors)
-        self.flags = [t[3] for t in tensors]
+        # conv / FC weight gradients come with their sums of squares on the presummed path (bit 4 of the flags)
+        self.flags = [t[3] | (api.JZ_PARAM_GRAD_PRESUMMED if self.presummed and t[2] in ("conv", "fc") else 0) for t in tensors]
         P = self.offsets[-1]
         h = torch.float32 if self.f32 else torch.float16
 
@@ -83,7 +87,7 @@ class ResNet50Step:
             d = api.conv_desc(batch, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
             ti = 3 * li
             a, b = self.offsets[ti], self.offsets[ti + 1]
-            L = dict(kind="conv", name=cs.name, d=d, first=cs.first,
+            L = dict(kind="conv", name=cs.name, d=d, first=cs.first, tensor=ti,
                      x=randn(batch * cs.H * cs.H * cs.C), dy=randn(batch * cs.P * cs.P * cs.K, self.loss_scale),
                      y=torch.empty(batch * cs.P * cs.P * cs.K, dtype=h, device=device),
                      dx=None if cs.first else torch.empty(batch * cs.H * cs.H * cs.C, dtype=h, device=device),
@@ -95,7 +99,7 @@ class ResNet50Step:
         ti = 3 * len(self.convs)
         a, b = self.offsets[ti], self.offsets[ti + 1]
         B, I, O = batch, self.fc.I, self.fc.O
-        self.layers.append(dict(kind="fc", name="fc", x=randn(B * I), dy=randn(B * O, self.loss_scale),
+        self.layers.append(dict(kind="fc", name="fc", tensor=ti, x=randn(B * I), dy=randn(B * O, self.loss_scale),
                                 y=torch.empty(B * O, dtype=h, device=device), dx=torch.empty(B * I, dtype=h, device=device),
                                 w=wsrc[a:b], dw=gdst[a:b], calls={}))
         for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT):
@@ -120,7 +124,13 @@ class ResNet50Step:
         B, I, O = self.N, self.fc.I, self.fc.O
         key = (op, ws.data_ptr())
         if key not in L["calls"]:
-            if L["kind"] == "conv":
+            if self.presummed and op == api.JZ_BWD_WEIGHT:
+                sink = api.jz_lars_sumsq_sink(self.ps, self.lars_ws, L["tensor"])
+                if L["kind"] == "conv":
+                    L["calls"][key] = api.bind_conv2d_bwd_weight_sumsq(L["d"], L["x"], L["dy"], L["dw"], sink, ws)
+                else:
+                    L["calls"][key] = api.bind_gemm_fc_bwd_weight_sumsq(B, I, O, L["dy"], L["x"], L["dw"], sink, ws)
+            elif L["kind"] == "conv":
                 a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("x", "dy", "dw")}[op]
                 L["calls"][key] = (api.bind_conv2d_f32 if self.f32 else api.bind_conv2d)(op, L["d"], L[a], L[b], L[o], ws)
             else:
@@ -140,6 +150,11 @@ class ResNet50Step:
         backward-data chain stays on stream 0.  Each side stream has its own workspace."""
         prog = []
         ev = lambda: torch.cuda.Event()
+        if self.presummed:   # the step starts: clear the gradient sinks, add up the carried sums of squares of the weights
+            prog.append(("launch", lambda st: api.jz_lars_begin_step(self.ps, self.lars_ws, self.ls_state, stream=st), 0))
+        # the tensors no GEMM produces (batch-norm scale / shift, bias): their sums of squares once their gradients exist,
+        # i.e. behind the last backward-data launch
+        rest = [("launch", lambda st: api.jz_lars_grad_sumsq(self.ps, 0, self.ps.T, self.lars_ws, stream=st), 0)] if self.presummed else []
         pending = None
         block_in = None
         names = {L["name"] for L in self.layers}
@@ -164,7 +179,7 @@ class ResNet50Step:
                 if not L.get("first"):
                     prog.append(("launch", self._bound(L, api.JZ_BWD_DATA, self.ws), 0))
                 prog.append(("launch", self._bound(L, api.JZ_BWD_WEIGHT, self.ws), 0))
-            return prog
+            return prog + rest
         ready = ev()
         prog.append(("record", ready, 0))                       # the loss gradient exists
         for k, L in enumerate(reversed(self.layers)):
@@ -174,6 +189,7 @@ class ResNet50Step:
                 prog.append(("launch", self._bound(L, api.JZ_BWD_DATA, self.ws), 0))
                 ready = ev()
                 prog.append(("record", ready, 0))               # dy of the layer below exists
+        prog += rest
         for si in range(1, n_side + 1):
             done = ev()
             prog += [("record", done, si), ("wait", done, 0)]
@@ -193,7 +209,12 @@ class ResNet50Step:
                 streams[si].wait_event(obj)
 
     def run_lars(self):
-        if self.ls_state is not None:
+        if self.presummed:
+            if self.ls_state is not None:
+                api.jz_lars_mp_update_presummed_dyn(self.ps, self.hparams(), self.ls_policy, self.ls_state, self.found_inf, self.lars_ws)
+            else:
+                api.jz_lars_mp_update_presummed(self.ps, self.hparams(), self.found_inf, self.lars_ws)
+        elif self.ls_state is not None:
             api.jz_lars_mp_update_dyn(self.ps, self.hparams(), self.ls_policy, self.ls_state, self.found_inf, self.lars_ws)
         else:
             api.jz_lars_mp_update(self.ps, self.hparams(), self.found_inf, self.lars_ws)
@@ -204,6 +225,7 @@ class ResNet50Step:
         self.ls_state = torch.zeros(2, dtype=torch.int32, device=self.found_inf.device)
         self.ls_policy = api.loss_scale_policy(growth_interval=1 << 30)
         api.jz_loss_scale_init(self.ls_state, self.loss_scale)
+        self.programs = {}   # jz_lars_begin_step takes the state
 
     def step(self):
         self.run_gemms()
@@ -220,6 +242,7 @@ class ResNet50Step:
         self.master.copy_(self.master0)
         self.w16.copy_(self.w16_0)
         self.momentum.zero_()
+        api.jz_lars_prepare(self.ps, self.lars_ws)   # the master weights were written from outside: drop the carried sums
 
 
 def per_layer_report(wl, iters=20, out_path=None, peak=FP16_MFMA_PEAK_TFLOPS):
@@ -625,6 +648,9 @@ def main():
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
     ap.add_argument("--per-layer-file", default=None, help="write the per-layer table (time, TFLOP/s, the layer's own roofline, "
                     "fraction, kernel plan) to this file as well; implies --per-layer")
+    ap.add_argument("--lars-path", default="presummed", choices=("presummed", "three_launches"),
+                    help="presummed: the backward-weight launches leave each filter gradient's sum of squares with the optimiser "
+                         "and the update is one launch; three_launches: jz_lars_mp_update (reduce, rates, update)")
     ap.add_argument("--dtype", default="f16", choices=("f16", "f32"), help="f16: the mixed-precision path (the headline); f32: the "
                     "single-precision variant of the same step (Table 9's comparison)")
     ap.add_argument("--no-fp32", action="store_true", help="skip the short single-precision run that the default line reports beside the headline")
@@ -667,7 +693,7 @@ def main():
     if args.workload == "chain":
         chain_workload(args)
         return
-    wl = ResNet50Step(batch=args.batch, dtype=args.dtype)
+    wl = ResNet50Step(batch=args.batch, dtype=args.dtype, lars_path=args.lars_path)
 
     # loss-scale back-off: halve S until the weight gradients stay inside fp16 and the update is not skipped
     for _ in range(12):
@@ -721,6 +747,8 @@ def main():
                      "flop_per_step": wl.flops, "ms_per_step_gemm_phase": gemm_ms, "ms_gemm_phase_median": t["gemm_ms_median"],
                      "ms_gemm_phase_min": t["gemm_ms_min"], "avg_launch_us": gemm_ms * 1e3 / n_gemm},
         "lars": {"bound": "hbm", "achieved": lars_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": lars_gbps / HBM_PEAK_GBPS,
+                 "path": "one launch, gradient norms from the backward-weight kernels' sinks" if wl.presummed else
+                         "three launches (reduce, per-tensor rates, update)",
                  "bytes_per_param": LARS_BYTES_PER_PARAM, "params": wl.P, "us_per_update": lars_ms * 1e3,
                  "us_per_update_median": t["lars_ms_median"] * 1e3, "us_per_update_min": t["lars_ms_min"] * 1e3,
                  "traffic": traffic["lars_bytes"] if traffic else None},

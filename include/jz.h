@@ -91,6 +91,26 @@ int jz_conv2d_bwd_data(const jz_conv_desc* desc, const void* dy16, const void* w
 int jz_conv2d_bwd_weight(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16, void* ws,
                          size_t ws_bytes, void* hip_stream);
 
+/* The weight gradient together with its sum of squares.  Eq. 1 needs ||g_t|| of every tensor before the update can
+ * start; taking it here, while the gradient is being written, saves the optimiser a second pass over the gradients
+ * (jz_lars_mp_update_presummed below consumes it).  A sink is JZ_SUMSQ_SINK_BYTES of DEVICE memory, 128-byte aligned,
+ * plus one DEVICE int: 16 accumulators 128 bytes apart, each four unsigned 64-bit counters, counter i in units of
+ * 2^(20 i - 48).  A finite FP16 value is an integer multiple of 2^-24, so its square is an integer number of units of
+ * 2^-48: the kernels add those integers (carried into base-2^20 digits per workgroup, one atomic integer add per digit),
+ * hence the counters hold the EXACT sum of squares of the values written to dw16, whatever the order in which
+ * workgroups arrive and whatever kernel plan ran (bit-identical from run to run).  sum = (c3 2^60 + c2 2^40 + c1 2^20 +
+ * c0) 2^-48 with c_i the sum of counter i over the 16 accumulators.  The calls ADD to the sink (several calls may share
+ * one; the caller clears it: jz_lars_begin_step does for the sinks inside a LARS workspace) and set *nonfinite = 1 if an
+ * element of dw16 is +-Inf or NaN (they never clear it; the counters are then left as they were).  dw16 holds the same bits as from
+ * jz_conv2d_bwd_weight / jz_gemm_fc(JZ_BWD_WEIGHT).  JZ_ERR_ALIGN / JZ_ERR_ALIAS / JZ_ERR_NULL for a bad sink. */
+#define JZ_SUMSQ_SINK_BYTES 2048
+typedef struct {
+  void* sums;     /* DEVICE, JZ_SUMSQ_SINK_BYTES, 128-byte aligned */
+  int* nonfinite; /* DEVICE */
+} jz_sumsq_sink;
+int jz_conv2d_bwd_weight_sumsq(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16, void* ws,
+                               size_t ws_bytes, const jz_sumsq_sink* sink, void* hip_stream);
+
 /* jz_conv2d_bwd_weight for callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc) and therefore have no workspace to pass: same kernels, same bits, with the
  * scratch (split-K partial sums, the padded copy of a small-channel layer) in a fixed array of
@@ -111,6 +131,10 @@ int jz_conv2d_bwd_weight_static(const jz_conv_desc* desc, const void* x16, const
 int jz_gemm_fc_workspace_bytes(int mode, int batch, int in_features, int out_features, size_t* bytes);
 int jz_gemm_fc(int mode, int batch, int in_features, int out_features, const void* a16, const void* b16, void* out16,
                void* ws, size_t ws_bytes, void* hip_stream);
+
+/* jz_gemm_fc(JZ_BWD_WEIGHT, ...) with the gradient's sum of squares added to a sink (see jz_conv2d_bwd_weight_sumsq). */
+int jz_gemm_fc_bwd_weight_sumsq(int batch, int in_features, int out_features, const void* dy16, const void* x16, void* dw16,
+                                void* ws, size_t ws_bytes, const jz_sumsq_sink* sink, void* hip_stream);
 
 /* ---- the same four operations in single precision (Section 5.4, Table 9: the FP32 side of the paper's FP32 versus
  * mixed-precision throughput comparison) --------------------------------------------------------------------------
@@ -134,7 +158,10 @@ int jz_gemm_fc_f32(int mode, int batch, int in_features, int out_features, const
 
 enum {
   JZ_PARAM_WEIGHT_DECAY = 1, /* tensor is regularised (Eq. 2); clear for bias and batch-norm gamma/beta (Section 4.2) */
-  JZ_PARAM_LARS = 2          /* tensor uses the local rate of Eq. 1; clear = plain momentum SGD (rho = 1) */
+  JZ_PARAM_LARS = 2,         /* tensor uses the local rate of Eq. 1; clear = plain momentum SGD (rho = 1) */
+  JZ_PARAM_GRAD_PRESUMMED = 4 /* the kernel that produces this tensor's gradient also leaves its sum of squares in the
+                                 tensor's sink (jz_lars_sumsq_sink): jz_lars_grad_sumsq leaves the tensor out.  Ignored by
+                                 jz_lars_mp_update[_dyn], which read every gradient themselves. */
 };
 
 typedef struct {
@@ -208,6 +235,41 @@ typedef struct {
 int jz_loss_scale_init(jz_loss_scale_state* state_dev, float initial_scale, void* hip_stream);
 int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* policy,
                           jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* The update in ONE launch, for a training step whose gradient norms are taken where the gradients are produced
+ * (Section 4.1 / Eq. 1; jz_conv2d_bwd_weight_sumsq and jz_gemm_fc_bwd_weight_sumsq above).  The gradient is then read
+ * once, by the update itself: 20 bytes per parameter move instead of 22, and the two launches in front of the update
+ * (reduce, per-tensor rates) disappear from the end of the step.  One step, all on streams ordered as listed:
+ *
+ *   jz_lars_begin_step        after the previous update, before the first gradient of this step: clears every tensor's
+ *                             sink, adds up the sums of squares of the master weights that the previous update left
+ *                             (first step after jz_lars_prepare: squares the weights themselves), and, when state_dev
+ *                             is not NULL, notes the loss scale S the step runs with.  One small launch.
+ *   jz_lars_sumsq_sink        (host only, no launch) the sink of tensor t inside `ws`, to be handed to the kernel that
+ *                             produces that tensor's gradient.
+ *   jz_lars_grad_sumsq        the sum of squares and overflow check of those tensors in [first, first + num) whose
+ *                             JZ_PARAM_GRAD_PRESUMMED bit is clear, read from ps->grad16: for the tensors no producing
+ *                             kernel covers (batch-norm scale and shift, bias).  Any time after those gradients exist.
+ *                             ADDS to the sinks: call it once per tensor and step.
+ *   jz_lars_mp_update_presummed[_dyn]   the update of jz_lars_mp_update[_dyn]: same arithmetic per element, same flag,
+ *                             same skip rule, same loss-scale controller, with ||g_t||^2 from the sinks and ||w_t||^2
+ *                             from jz_lars_begin_step.  Every tensor's sink must hold exactly the sum of squares of that
+ *                             tensor's slice of grad16 (and *nonfinite != 0 iff the slice has an Inf / NaN).
+ *                             JZ_ERR_NOT_PREPARED unless jz_lars_begin_step ran on this workspace since the last presummed
+ *                             update, with the same state_dev (NULL for the fixed-scale call).
+ *
+ * Both update paths can be mixed on one workspace (each leaves the carried sums of squares of the weights valid for
+ * the other).  Bit-identical from run to run; the rates can differ from jz_lars_mp_update's in the last FP32 bit
+ * (the same FP64 partial sums are added as integers here, left to right there). */
+int jz_lars_begin_step(const jz_param_set* ps, const jz_loss_scale_state* state_dev, void* ws, size_t ws_bytes, void* hip_stream);
+int jz_lars_sumsq_sink(const jz_param_set* ps, void* ws, size_t ws_bytes, int64_t tensor, jz_sumsq_sink* sink);
+int jz_lars_grad_sumsq(const jz_param_set* ps, int64_t first_tensor, int64_t num_tensors, void* ws, size_t ws_bytes,
+                       void* hip_stream);
+int jz_lars_mp_update_presummed(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
+                                size_t ws_bytes, void* hip_stream);
+int jz_lars_mp_update_presummed_dyn(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* policy,
+                                    jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes,
+                                    void* hip_stream);
 
 /* The backward pass at the end of a residual block, y_out = relu(bn(x) + shortcut), in one call: the gradient of the sum,
  * g = RNE16(dya [+ dyb]) where y_out > 0 and 0 elsewhere (dyb may be NULL; two contributions arrive when the block above

@@ -17,14 +17,15 @@ JZ_OK = 0
 JZ_ERR_NULL, JZ_ERR_SHAPE, JZ_ERR_UNSUPPORTED, JZ_ERR_WORKSPACE = -1, -2, -3, -4
 JZ_ERR_ALIGN, JZ_ERR_ALIAS, JZ_ERR_LAUNCH, JZ_ERR_NOT_PREPARED = -5, -6, -7, -8
 JZ_FWD, JZ_BWD_DATA, JZ_BWD_WEIGHT = 0, 1, 2
-JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS = 1, 2
+JZ_PARAM_WEIGHT_DECAY, JZ_PARAM_LARS, JZ_PARAM_GRAD_PRESUMMED = 1, 2, 4
 
 EXPORTS = [
     "jz_conv2d_workspace_bytes", "jz_conv2d_describe_plan", "jz_conv2d_tune_set", "jz_conv2d_tune_use_table", "jz_conv2d_tune_clear", "jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight", "jz_conv2d_bwd_weight_static",
-    "jz_gemm_fc_workspace_bytes", "jz_gemm_fc",
+    "jz_conv2d_bwd_weight_sumsq", "jz_gemm_fc_workspace_bytes", "jz_gemm_fc", "jz_gemm_fc_bwd_weight_sumsq",
     "jz_conv2d_f32_workspace_bytes", "jz_conv2d_fwd_f32", "jz_conv2d_bwd_data_f32", "jz_conv2d_bwd_weight_f32",
     "jz_gemm_fc_f32_workspace_bytes", "jz_gemm_fc_f32",
     "jz_lars_workspace_bytes", "jz_lars_prepare", "jz_lars_mp_update", "jz_loss_scale_init", "jz_lars_mp_update_dyn",
+    "jz_lars_begin_step", "jz_lars_sumsq_sink", "jz_lars_grad_sumsq", "jz_lars_mp_update_presummed", "jz_lars_mp_update_presummed_dyn",
     "jz_add_fwd", "jz_relu_bwd", "jz_relu_bwd_sum", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
     "jz_bias_grad", "jz_softmax_xent_bwd", "jz_conv2d_bn_relu_fwd_workspace_bytes", "jz_conv2d_bn_relu_fwd",
     "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd", "jz_bn_bwd_block_end",
@@ -59,6 +60,13 @@ class jz_loss_scale_policy(ctypes.Structure):
                 ("min_scale", ctypes.c_float), ("max_scale", ctypes.c_float)]
 
 
+class jz_sumsq_sink(ctypes.Structure):
+    _fields_ = [("sums", ctypes.c_void_p), ("nonfinite", ctypes.c_void_p)]
+
+
+JZ_SUMSQ_SINK_BYTES = 2048
+
+
 class jz_param_set(ctypes.Structure):
     _fields_ = [
         ("num_tensors", ctypes.c_int64),
@@ -91,6 +99,9 @@ def lib() -> ctypes.CDLL:
         for name in ("jz_conv2d_fwd", "jz_conv2d_bwd_data", "jz_conv2d_bwd_weight"):
             getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.jz_conv2d_bwd_weight_static.argtypes = [dp, vp, vp, vp, vp]
+        sk = ctypes.POINTER(jz_sumsq_sink)
+        L.jz_conv2d_bwd_weight_sumsq.argtypes = [dp, vp, vp, vp, vp, sz, sk, vp]
+        L.jz_gemm_fc_bwd_weight_sumsq.argtypes = [ci, ci, ci, vp, vp, vp, vp, sz, sk, vp]
         L.jz_conv2d_f32_workspace_bytes.argtypes = [ci, dp, ctypes.POINTER(sz)]
         for name in ("jz_conv2d_fwd_f32", "jz_conv2d_bwd_data_f32", "jz_conv2d_bwd_weight_f32"):
             getattr(L, name).argtypes = [dp, vp, vp, vp, vp, sz, vp]
@@ -106,6 +117,12 @@ def lib() -> ctypes.CDLL:
         L.jz_lars_mp_update_dyn.argtypes = [pp, ctypes.POINTER(jz_lars_hparams), ctypes.POINTER(jz_loss_scale_policy), vp, vp,
                                             vp, sz, vp]
         i64, cf = ctypes.c_int64, ctypes.c_float
+        L.jz_lars_begin_step.argtypes = [pp, vp, vp, sz, vp]
+        L.jz_lars_sumsq_sink.argtypes = [pp, vp, sz, i64, sk]
+        L.jz_lars_grad_sumsq.argtypes = [pp, i64, i64, vp, sz, vp]
+        L.jz_lars_mp_update_presummed.argtypes = [pp, ctypes.POINTER(jz_lars_hparams), vp, vp, sz, vp]
+        L.jz_lars_mp_update_presummed_dyn.argtypes = [pp, ctypes.POINTER(jz_lars_hparams), ctypes.POINTER(jz_loss_scale_policy), vp, vp,
+                                                      vp, sz, vp]
         L.jz_bn_workspace_bytes.argtypes = [i64, ci, ctypes.POINTER(sz)]
         L.jz_bn_relu_fwd.argtypes = [i64, ci, vp, vp, vp, cf, ci, vp, vp, vp, vp, sz, vp]
         L.jz_bn_relu_bwd.argtypes = [i64, ci, vp, vp, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
@@ -441,6 +458,95 @@ def jz_lars_mp_update_dyn(ps: ParamSet, hp: jz_lars_hparams, policy: jz_loss_sca
     wp, wn = _ws(ws)
     _check(lib().jz_lars_mp_update_dyn(ctypes.byref(ps.c), ctypes.byref(hp), ctypes.byref(policy), _ls_state(state),
                                        found_inf.data_ptr(), wp, wn, _stream(stream)), "jz_lars_mp_update_dyn")
+
+
+# ---- the update in one launch: gradient norms taken where the gradients are produced --------------------------------------
+def sumsq_sink(sums: torch.Tensor, nonfinite: torch.Tensor) -> jz_sumsq_sink:
+    """A sink in caller-owned memory: `sums` int64[256] (2048 bytes, 128-byte aligned), `nonfinite` int32[1]; the caller keeps
+    both alive and clears them."""
+    if not sums.is_cuda or sums.dtype != torch.int64 or sums.numel() != JZ_SUMSQ_SINK_BYTES // 8 or not sums.is_contiguous():
+        raise TypeError("sums must be a contiguous 256-element int64 GPU tensor")
+    if not nonfinite.is_cuda or nonfinite.dtype != torch.int32 or nonfinite.numel() != 1:
+        raise TypeError("nonfinite must be a one-element int32 GPU tensor")
+    return jz_sumsq_sink(sums.data_ptr(), nonfinite.data_ptr())
+
+
+def sumsq_sink_units(sums: torch.Tensor) -> int:
+    """What a sink holds, read back (synchronizes), as an exact integer count of units of 2^-48: the 16 quadruples of
+    base-2^20 digit counters added as integers."""
+    a = sums.cpu().numpy().view(np.uint64).reshape(16, 16)
+    d = [sum(int(x) for x in a[:, i]) for i in range(4)]
+    return (d[3] << 60) + (d[2] << 40) + (d[1] << 20) + d[0]
+
+
+def jz_conv2d_bwd_weight_sumsq(desc, x16, dy16, dw16, sink: jz_sumsq_sink, ws=None, stream=None):
+    d, h = desc, torch.float16
+    wp, wn = _ws(ws)
+    _check(lib().jz_conv2d_bwd_weight_sumsq(ctypes.byref(d), _dev_ptr(x16, h, d.N * d.H * d.W * d.C, "x16"),
+                                            _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
+                                            _dev_ptr(dw16, h, d.K * d.R * d.S * d.C, "dw16"), wp, wn, ctypes.byref(sink),
+                                            _stream(stream)), "jz_conv2d_bwd_weight_sumsq")
+
+
+def jz_gemm_fc_bwd_weight_sumsq(batch, in_features, out_features, dy16, x16, dw16, sink: jz_sumsq_sink, ws=None, stream=None):
+    B, I, O, h = batch, in_features, out_features, torch.float16
+    wp, wn = _ws(ws)
+    _check(lib().jz_gemm_fc_bwd_weight_sumsq(B, I, O, _dev_ptr(dy16, h, B * O, "dy16"), _dev_ptr(x16, h, B * I, "x16"),
+                                             _dev_ptr(dw16, h, O * I, "dw16"), wp, wn, ctypes.byref(sink), _stream(stream)),
+           "jz_gemm_fc_bwd_weight_sumsq")
+
+
+def bind_conv2d_bwd_weight_sumsq(desc, x16, dy16, dw16, sink: jz_sumsq_sink, ws=None) -> BoundCall:
+    d, h = desc, torch.float16
+    wp, wn = _ws(ws)
+    args = (ctypes.byref(d), _dev_ptr(x16, h, d.N * d.H * d.W * d.C, "x16"), _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
+            _dev_ptr(dw16, h, d.K * d.R * d.S * d.C, "dw16"), wp, wn, ctypes.byref(sink))
+    return BoundCall(lib().jz_conv2d_bwd_weight_sumsq, args, "jz_conv2d_bwd_weight_sumsq", (d, x16, dy16, dw16, ws, sink))
+
+
+def bind_gemm_fc_bwd_weight_sumsq(batch, in_features, out_features, dy16, x16, dw16, sink: jz_sumsq_sink, ws=None) -> BoundCall:
+    B, I, O, h = batch, in_features, out_features, torch.float16
+    wp, wn = _ws(ws)
+    args = (B, I, O, _dev_ptr(dy16, h, B * O, "dy16"), _dev_ptr(x16, h, B * I, "x16"), _dev_ptr(dw16, h, O * I, "dw16"), wp, wn,
+            ctypes.byref(sink))
+    return BoundCall(lib().jz_gemm_fc_bwd_weight_sumsq, args, "jz_gemm_fc_bwd_weight_sumsq", (dy16, x16, dw16, ws, sink))
+
+
+def jz_lars_begin_step(ps: ParamSet, ws: torch.Tensor, state: Optional[torch.Tensor] = None, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().jz_lars_begin_step(ctypes.byref(ps.c), _ls_state(state) if state is not None else None, wp, wn, _stream(stream)),
+           "jz_lars_begin_step")
+
+
+def jz_lars_sumsq_sink(ps: ParamSet, ws: torch.Tensor, tensor: int) -> jz_sumsq_sink:
+    """The sink of tensor `tensor` inside the LARS workspace (host only; valid while `ws` is)."""
+    wp, wn = _ws(ws)
+    sink = jz_sumsq_sink()
+    _check(lib().jz_lars_sumsq_sink(ctypes.byref(ps.c), wp, wn, int(tensor), ctypes.byref(sink)), "jz_lars_sumsq_sink")
+    return sink
+
+
+def jz_lars_grad_sumsq(ps: ParamSet, first_tensor: int, num_tensors: int, ws: torch.Tensor, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().jz_lars_grad_sumsq(ctypes.byref(ps.c), int(first_tensor), int(num_tensors), wp, wn, _stream(stream)),
+           "jz_lars_grad_sumsq")
+
+
+def jz_lars_mp_update_presummed(ps: ParamSet, hp: jz_lars_hparams, found_inf: torch.Tensor, ws: torch.Tensor, stream=None):
+    if not found_inf.is_cuda or found_inf.dtype != torch.int32 or found_inf.numel() != 1:
+        raise TypeError("found_inf must be a one-element int32 GPU tensor")
+    wp, wn = _ws(ws)
+    _check(lib().jz_lars_mp_update_presummed(ctypes.byref(ps.c), ctypes.byref(hp), found_inf.data_ptr(), wp, wn, _stream(stream)),
+           "jz_lars_mp_update_presummed")
+
+
+def jz_lars_mp_update_presummed_dyn(ps: ParamSet, hp: jz_lars_hparams, policy: jz_loss_scale_policy, state: torch.Tensor,
+                                    found_inf: torch.Tensor, ws: torch.Tensor, stream=None):
+    if not found_inf.is_cuda or found_inf.dtype != torch.int32 or found_inf.numel() != 1:
+        raise TypeError("found_inf must be a one-element int32 GPU tensor")
+    wp, wn = _ws(ws)
+    _check(lib().jz_lars_mp_update_presummed_dyn(ctypes.byref(ps.c), ctypes.byref(hp), ctypes.byref(policy), _ls_state(state),
+                                                 found_inf.data_ptr(), wp, wn, _stream(stream)), "jz_lars_mp_update_presummed_dyn")
 
 
 def lars_hparams(lr, momentum, weight_decay, trust_coef, loss_scale) -> jz_lars_hparams:

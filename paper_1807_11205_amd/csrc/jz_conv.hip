@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "jz_conv_plan.h"
+#include "jz_sumsq.h"
 
 namespace {
 using namespace jz;
@@ -154,6 +155,107 @@ __global__ __launch_bounds__(256) void splitk_reduce(const float* __restrict__ p
       out[i + e] = bts;
     }
   }
+}
+
+// splitk_reduce that also leaves the sum of squares of the FP16 values it writes (and whether any of them is Inf / NaN)
+// in a sink: the weight gradient's norm for Eq. 1, taken while the gradient is still in registers.  Same sums, same order,
+// same bits in `out` as splitk_reduce.  A workgroup walks several slabs of outputs (grid stride) and contributes once, so
+// that the number of atomic additions per tensor stays in the hundreds.
+__global__ __launch_bounds__(256) void splitk_reduce_sumsq(const float* __restrict__ part, unsigned short* __restrict__ out,
+                                                           long long MN, int splits, int lg, int KT4, int S, int C,
+                                                           long long slabs, jz::SumsqSink sink) {
+  __shared__ float4 red[256];
+  __shared__ unsigned long long wsum[12];
+  const int G = 1 << lg, Q = 256 >> lg;
+  const int q = threadIdx.x & (Q - 1), g = threadIdx.x >> (8 - lg);
+  jz::SumsqAcc sq;
+  int bad = 0;
+  for (long long slab = blockIdx.x; slab < slabs; slab += gridDim.x) {
+    const long long i = (slab * Q + q) * 4;
+    const bool full = i + 3 < MN && (MN & 3) == 0;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < MN) {
+      if (full) {
+        int k = g;
+        for (; k + 3 * G < splits; k += 4 * G) {
+          float4 t0 = *reinterpret_cast<const float4*>(part + (size_t)k * MN + i);
+          float4 t1 = *reinterpret_cast<const float4*>(part + (size_t)(k + G) * MN + i);
+          float4 t2 = *reinterpret_cast<const float4*>(part + (size_t)(k + 2 * G) * MN + i);
+          float4 t3 = *reinterpret_cast<const float4*>(part + (size_t)(k + 3 * G) * MN + i);
+          s.x += t0.x; s.y += t0.y; s.z += t0.z; s.w += t0.w;
+          s.x += t1.x; s.y += t1.y; s.z += t1.z; s.w += t1.w;
+          s.x += t2.x; s.y += t2.y; s.z += t2.z; s.w += t2.w;
+          s.x += t3.x; s.y += t3.y; s.z += t3.z; s.w += t3.w;
+        }
+        for (; k < splits; k += G) {
+          float4 t = *reinterpret_cast<const float4*>(part + (size_t)k * MN + i);
+          s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+      } else {
+        float* sv = reinterpret_cast<float*>(&s);
+        for (int k = g; k < splits; k += G)
+          for (int e = 0; e < 4 && i + e < MN; ++e) sv[e] += part[(size_t)k * MN + i + e];
+      }
+    }
+    if (G > 1) {
+      __syncthreads();  // the previous slab's sums have been read
+      red[threadIdx.x] = s;
+      __syncthreads();
+      if (g == 0)
+        for (int gg = 1; gg < G; ++gg) {
+          float4 t = red[gg * Q + q];
+          s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+    }
+    if (g != 0 || i >= MN) continue;
+    _Float16 h[4] = {(_Float16)s.x, (_Float16)s.y, (_Float16)s.z, (_Float16)s.w};
+    unsigned short hb[4];
+    __builtin_memcpy(hb, h, 8);
+    int nst = 0;  // how many of the four are real outputs
+    if (KT4 > 0) {
+      const long long grp = i >> 2, kr = grp / KT4;
+      const int sx = (int)(grp - kr * KT4);
+      if (sx < S) {
+        nst = C < 4 ? C : 4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (c < C) out[(kr * S + sx) * C + c] = hb[c];
+      }
+    } else if (full) {
+      nst = 4;
+      uint2 pk;
+      __builtin_memcpy(&pk, h, 8);
+      *reinterpret_cast<uint2*>(out + i) = pk;
+    } else {
+      for (int e = 0; e < 4 && i + e < MN; ++e) {
+        out[i + e] = hb[e];
+        nst = e + 1;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (e < nst) bad |= jz::sumsq_acc_add(sq, hb[e]);
+  }
+  jz::sumsq_block_flush(sq, bad, sink, blockIdx.x, wsum);
+}
+
+// sum of squares of n FP16 values into a sink (gradients whose producing kernel has no fused form)
+__global__ __launch_bounds__(256) void sumsq_half(const unsigned short* __restrict__ g16, long long n, jz::SumsqSink sink) {
+  __shared__ unsigned long long wsum[12];
+  jz::SumsqAcc sq;
+  int bad = 0;
+  const long long groups = n >> 3;  // 16-byte groups; g16 is 16-byte aligned
+  for (long long j = (long long)blockIdx.x * 256 + threadIdx.x; j < groups; j += (long long)gridDim.x * 256) {
+    const uint4 v = *reinterpret_cast<const uint4*>(g16 + j * 8);
+    const unsigned wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bad |= jz::sumsq_acc_add(sq, (unsigned short)(wv[e >> 1] >> ((e & 1) * 16)));
+  }
+  if (blockIdx.x == 0) {  // the tail, at most 7 elements
+    const long long i = (groups << 3) + threadIdx.x;
+    if (i < n) bad |= jz::sumsq_acc_add(sq, g16[i]);
+  }
+  jz::sumsq_block_flush(sq, bad, sink, blockIdx.x, wsum);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -442,7 +544,7 @@ bool plan_leaves_stats(const Plan& pl) {
 
 // A, B in the kernel's order: FWD (x, w), BWD_DATA (dy, w), BWD_WEIGHT (dy, x)
 int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, void* ws, size_t ws_bytes, void* stream,
-        float* stats = nullptr, int stats_tiles_m = 0) {
+        float* stats = nullptr, int stats_tiles_m = 0, const jz::SumsqSink* sink = nullptr) {
   Plan pl;
   int rc = make_plan(op, d, &pl);
   if (rc != JZ_OK) return rc;
@@ -496,8 +598,15 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     const long long per_block = 256 >> lg;
     unsigned blocks = (unsigned)(((MN + 3) / 4 + per_block - 1) / per_block);
     // small-channel backward-weight: the reduction writes the real filter entries straight into dw
-    hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, a.Dpart, dwp ? static_cast<unsigned short*>(D) : a.D16,
-                       MN, a.splits, lg, dwp ? pl.KT / 4 : 0, d->S, d->C);
+    if (sink) {
+      const unsigned grid = blocks < 512u ? blocks : 512u;
+      hipLaunchKernelGGL(splitk_reduce_sumsq, dim3(grid), dim3(256), 0, st, a.Dpart, dwp ? static_cast<unsigned short*>(D) : a.D16,
+                         MN, a.splits, lg, dwp ? pl.KT / 4 : 0, d->S, d->C, (long long)blocks, *sink);
+      sink = nullptr;  // taken
+    } else {
+      hipLaunchKernelGGL(splitk_reduce, dim3(blocks), dim3(256), 0, st, a.Dpart, dwp ? static_cast<unsigned short*>(D) : a.D16,
+                         MN, a.splits, lg, dwp ? pl.KT / 4 : 0, d->S, d->C);
+    }
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
     dwp = nullptr;
   }
@@ -505,8 +614,10 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     int ndw = d->K * d->R * d->S * d->C;
     hipLaunchKernelGGL(unpack_filter_c4, dim3((unsigned)((ndw + 255) / 256)), dim3(256), 0, st, dwp,
                        static_cast<unsigned short*>(D), d->K, d->R, d->S, d->C, pl.KT);
-    rc = jz::launch_status();
+    if ((rc = jz::launch_status()) != JZ_OK) return rc;
   }
+  // no split reduction to take the sum of squares in: one pass over the gradient just written (still in cache)
+  if (sink) rc = jz::sumsq_half_launch(static_cast<const unsigned short*>(D), (long long)d->K * d->R * d->S * d->C, *sink, st);
   return rc;
 }
 
@@ -608,6 +719,38 @@ extern "C" int jz_conv2d_bwd_weight(const jz_conv_desc* desc, const void* x16, c
   return run(JZ_BWD_WEIGHT, desc, dy16, x16, dw16, ws, ws_bytes, hip_stream);  // A = dy, B = x
 }
 
+// ---- backward-weight that also hands the gradient's sum of squares to the optimiser ---------------------------------
+namespace {
+int check_sink(const jz_sumsq_sink* sink, const void* dw, size_t dw_bytes, const void* ws, size_t ws_bytes, jz::SumsqSink* out) {
+  if (!sink || !sink->sums || !sink->nonfinite) return JZ_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(sink->sums) & 127u) || (reinterpret_cast<uintptr_t>(sink->nonfinite) & 3u)) return JZ_ERR_ALIGN;
+  if (overlaps(sink->sums, JZ_SUMSQ_SINK_BYTES, dw, dw_bytes) || overlaps(sink->nonfinite, sizeof(int), dw, dw_bytes) ||
+      overlaps(sink->sums, JZ_SUMSQ_SINK_BYTES, ws, ws_bytes) || overlaps(sink->nonfinite, sizeof(int), ws, ws_bytes) ||
+      overlaps(sink->sums, JZ_SUMSQ_SINK_BYTES, sink->nonfinite, sizeof(int)))
+    return JZ_ERR_ALIAS;
+  *out = jz::SumsqSink{static_cast<unsigned long long*>(sink->sums), sink->nonfinite};
+  return JZ_OK;
+}
+}  // namespace
+
+int jz::sumsq_half_launch(const unsigned short* g16, long long n, const jz::SumsqSink& sink, hipStream_t st) {
+  if (n <= 0) return JZ_OK;
+  long long want = (n / 8 + 255) / 256;  // one 16-byte group per thread and pass; at most 2^20 elements per workgroup
+  const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 1024 ? 1024 : want));
+  hipLaunchKernelGGL(sumsq_half, dim3(grid), dim3(256), 0, st, g16, n, sink);
+  return jz::launch_status();
+}
+
+extern "C" int jz_conv2d_bwd_weight_sumsq(const jz_conv_desc* desc, const void* x16, const void* dy16, void* dw16, void* ws,
+                                          size_t ws_bytes, const jz_sumsq_sink* sink, void* hip_stream) {
+  Plan pl;
+  int rc = make_plan(JZ_BWD_WEIGHT, desc, &pl);
+  if (rc != JZ_OK) return rc;
+  jz::SumsqSink sk;
+  if ((rc = check_sink(sink, dw16, pl.bytesD, ws, pl.ws_bytes, &sk)) != JZ_OK) return rc;
+  return run(JZ_BWD_WEIGHT, desc, dy16, x16, dw16, ws, ws_bytes, hip_stream, nullptr, 0, &sk);
+}
+
 // ---- backward-weight without a caller workspace ---------------------------------------------------------------
 // For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops): the same
 // kernels, with the split-K partial sums (and the padded copy of a small-channel layer) in a fixed array that lives
@@ -663,4 +806,12 @@ extern "C" int jz_gemm_fc(int mode, int batch, int in_features, int out_features
   if (rc != JZ_OK) return rc;
   // FWD: (x, w) ; BWD_DATA: (dy, w) ; BWD_WEIGHT: (dy, x) -- already the kernel's (A, B) order in every mode
   return run(mode, &d, a16, b16, out16, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int jz_gemm_fc_bwd_weight_sumsq(int batch, int in_features, int out_features, const void* dy16, const void* x16,
+                                           void* dw16, void* ws, size_t ws_bytes, const jz_sumsq_sink* sink, void* hip_stream) {
+  jz_conv_desc d;
+  int rc = fc_desc(JZ_BWD_WEIGHT, batch, in_features, out_features, &d);
+  if (rc != JZ_OK) return rc;
+  return jz_conv2d_bwd_weight_sumsq(&d, x16, dy16, dw16, ws, ws_bytes, sink, hip_stream);
 }

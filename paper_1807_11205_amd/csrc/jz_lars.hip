@@ -14,12 +14,23 @@
 //                  tail the reduce pass touched last is still in the last-level cache; skips everything
 //                  when any tensor raised the flag.  While writing w it accumulates the chunk's sum of w^2,
 //                  which the next update's reduce pass then need not read w for.
+//
+// When the kernels that produce the gradients also leave each tensor's sum of squares (jz_sumsq.h), the first two
+// launches have nothing left to do at update time and the update is one launch ("presummed"):
+//
+//   lars_begin       at the start of a step, one workgroup per tensor: adds the partial sums of w^2 the last update left
+//                    (or, for a fresh workspace, squares the tensor itself), clears the tensor's gradient sink
+//   lars_grad_sumsq  the reduce pass for the tensors no other kernel covers (batch-norm scale / shift, bias), any time
+//                    after their gradients exist
+//   lars_update<true>  every wavefront forms lr*rho_t of its chunk's tensor itself from the sink and the sum lars_begin
+//                    left; otherwise the same kernel
 #include <hip/hip_runtime.h>
 
 #include <mutex>
 #include <vector>
 
 #include "jz_internal.h"
+#include "jz_sumsq.h"
 
 namespace {
 
@@ -44,7 +55,8 @@ struct Layout {
   size_t off_header = 0, off_offsets = 0, off_chunk_begin = 0, off_flags = 0, off_chunk_tensor = 0, off_chunk_rec = 0;
   size_t off_state = 0;
   size_t static_bytes = 0;  // everything up to here is written by prepare
-  size_t off_psum_w = 0, off_psum_g = 0, off_pflag = 0, off_coef = 0, off_tflag = 0, total = 0;
+  size_t off_psum_w = 0, off_psum_g = 0, off_pflag = 0, off_coef = 0, off_tflag = 0;
+  size_t off_gsum = 0, off_gflag = 0, off_wsum = 0, total = 0;  // presummed path: gradient sinks, their flags, sum of w^2
 };
 
 size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -82,6 +94,9 @@ int make_layout(const jz_param_set* ps, Layout* L) {
   L->off_pflag = o;         o = up256(o + sizeof(int) * parts);
   L->off_coef = o;          o = up256(o + sizeof(float) * (L->T ? L->T : 1));
   L->off_tflag = o;         o = up256(o + sizeof(int) * (L->T ? L->T : 1));
+  L->off_gsum = o;          o = up256(o + jz::kSumsqSinkBytes * (L->T ? L->T : 1));
+  L->off_gflag = o;         o = up256(o + sizeof(int) * (L->T ? L->T : 1));
+  L->off_wsum = o;          o = up256(o + sizeof(double) * (L->T ? L->T : 1));
   L->total = o;
   return JZ_OK;
 }
@@ -99,7 +114,8 @@ uint64_t table_checksum(const jz_param_set* ps) {  // FNV-1a over T, offsets and
 }
 
 // host-side note of which workspace holds which table (the device header is checked as well)
-struct Prepared { void* ws; uint64_t sum; };
+// begun: jz_lars_begin_step has run since the last presummed update (and with which loss-scale state)
+struct Prepared { void* ws; uint64_t sum; bool begun; const void* begun_state; };
 std::mutex g_mu;
 Prepared g_prepared[64];
 int g_next = 0;
@@ -107,9 +123,20 @@ int g_next = 0;
 void remember(void* ws, uint64_t sum) {
   std::lock_guard<std::mutex> lk(g_mu);
   for (auto& e : g_prepared)
-    if (e.ws == ws) { e.sum = sum; return; }
-  g_prepared[g_next] = {ws, sum};
+    if (e.ws == ws) { e = {ws, sum, false, nullptr}; return; }
+  g_prepared[g_next] = {ws, sum, false, nullptr};
   g_next = (g_next + 1) % 64;
+}
+void set_begun(void* ws, bool begun, const void* state) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  for (auto& e : g_prepared)
+    if (e.ws == ws) { e.begun = begun; e.begun_state = state; }
+}
+bool has_begun(void* ws, const void* state) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  for (auto& e : g_prepared)
+    if (e.ws == ws) return e.begun && e.begun_state == state;
+  return false;
 }
 bool is_prepared(void* ws, uint64_t sum) {
   std::lock_guard<std::mutex> lk(g_mu);
@@ -125,12 +152,16 @@ struct Tables {
   const int* flags;
   const int* chunk_tensor;
   const ChunkRec* chunk_rec;
-  int* state;    // [0]: 1 when psum_w holds the sums of squares of the current master weights
+  int* state;    // [0]: 1 when psum_w holds the sums of squares of the current master weights; [1], [2]: 1/S and S as
+                 // float bits when the loss scale lives on the device (written by a launch before the update)
   double* psum_w;  // [n_chunks][LARS_WAVES] partial sums of w^2: one per wavefront, so that no kernel needs a barrier
   double* psum_g;  // same for the (loss-scaled) gradient
   int* pflag;      // same: non-finite gradient seen
   float* coef;  // lr * rho_t
   int* tflag;
+  unsigned long long* gsum;  // [T][kSumsqSubs * kSumsqSubStride]: gradient sum-of-squares sinks
+  int* gflag;                // [T]: non-finite gradient reported to the sink
+  double* wsum;              // [T]: sum of squares of the master weights, written by lars_begin
   int T, n_chunks;
   uint64_t checksum;
 };
@@ -217,6 +248,33 @@ __device__ __forceinline__ void chunk_body(int64_t s, int64_t e, int64_t* b0, in
   if (a > e) a = e;
   *b0 = a;
   *b1 = a + ((e - a) & ~int64_t(7));
+}
+
+// One thread's share of a chunk's sum of w^2, in the order lars_reduce and lars_update add it (the 8-element groups in
+// turn, then at most one head / tail element).
+__device__ __forceinline__ double chunk_thread_sumsq_w(const ChunkRec& rec, const float* __restrict__ w) {
+  int t;
+  int64_t s, e, b0, b1;
+  chunk_range(rec, &t, &s, &e);
+  chunk_body(s, e, &b0, &b1);
+  double sw = 0.0;
+#pragma unroll
+  for (int k = 0; k < LARS_IT; ++k) {
+    int64_t i = b0 + (int64_t)(k * LARS_THREADS + threadIdx.x) * 8;
+    if (i < b1) {
+      const float4 a = *reinterpret_cast<const float4*>(w + i), b = *reinterpret_cast<const float4*>(w + i + 4);
+      const float wv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sw = fma((double)wv[j], (double)wv[j], sw);
+    }
+  }
+  int64_t nh = b0 - s, nt = e - b1;
+  int64_t k = threadIdx.x;
+  if (k < nh + nt) {
+    int64_t i = (k < nh) ? s + k : b1 + (k - nh);
+    sw = fma((double)w[i], (double)w[i], sw);
+  }
+  return sw;
 }
 
 __global__ __launch_bounds__(LARS_THREADS) void lars_reduce(Tables tb, const float* __restrict__ w,
@@ -327,6 +385,75 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_finalize(Tables tb, float l
   }
 }
 
+// Start of a step on the presummed path, one workgroup per tensor (see the top of the file).
+__global__ __launch_bounds__(LARS_THREADS) void lars_begin(Tables tb, const float* __restrict__ w,
+                                                           const float* __restrict__ scale_dev) {
+  __shared__ double red[4];
+  if (!table_ok(tb)) return;
+  const int t = blockIdx.x;
+  const bool have_w = tb.state[0] != 0;  // written by an earlier launch
+  static_assert(jz::kSumsqSubs * jz::kSumsqSubStride == LARS_THREADS, "one 64-bit word of the sink per thread");
+  tb.gsum[(size_t)t * LARS_THREADS + threadIdx.x] = 0ull;
+  if (threadIdx.x == 0) tb.gflag[t] = 0;
+  if (scale_dev && t == 0 && threadIdx.x == 0) {  // the update adjusts the device-resident scale itself: it reads S from here
+    const float S = *scale_dev;
+    tb.state[1] = __float_as_int(1.0f / S);
+    tb.state[2] = __float_as_int(S);
+  }
+  const int c0 = tb.chunk_begin[t] * LARS_WAVES, c1 = tb.chunk_begin[t + 1] * LARS_WAVES;
+  if (!have_w) {
+    // Fresh workspace: leave in psum_w what lars_reduce would (same elements per thread, same order), chunk by chunk, so
+    // that the sum below is the same bits whether the partial sums were carried or are recomputed here.  One workgroup
+    // per tensor makes this slow for large tensors; it runs once per jz_lars_prepare.
+    for (int c = tb.chunk_begin[t]; c < tb.chunk_begin[t + 1]; ++c) {
+      const double p = wave_sum(chunk_thread_sumsq_w(tb.chunk_rec[c], w));
+      if ((threadIdx.x & 63) == 0) tb.psum_w[c * LARS_WAVES + (threadIdx.x >> 6)] = p;
+    }
+    __threadfence_block();
+    __syncthreads();
+  }
+  // Loads that go past the compute unit's own cache: in the fresh case a partial sum written above may share a cache
+  // line with a neighbouring tensor's, which another workgroup on this compute unit may have pulled in before the write.
+  double sw = 0.0;
+  for (int c = c0 + (int)threadIdx.x; c < c1; c += LARS_THREADS)
+    sw += __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(tb.psum_w + c),
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  sw = block_sum(sw, red);
+  if (threadIdx.x == 0) tb.wsum[t] = sw;
+}
+
+// The gradient reduce pass into the sinks, one workgroup per chunk, for chunks chunk0 .. chunk0 + gridDim.x - 1.
+__global__ __launch_bounds__(LARS_THREADS) void lars_grad_sumsq(Tables tb, const unsigned short* __restrict__ g16, int chunk0) {
+  __shared__ unsigned long long red[3 * LARS_WAVES];
+  const int c = chunk0 + (int)blockIdx.x;
+  const ChunkRec rec = tb.chunk_rec[c];
+  if (!table_ok(tb)) return;
+  int t;
+  int64_t s, e, b0, b1;
+  chunk_range(rec, &t, &s, &e);
+  if (tb.flags[t] & JZ_PARAM_GRAD_PRESUMMED) return;  // its producer fills the sink
+  chunk_body(s, e, &b0, &b1);
+  jz::SumsqAcc sg;
+  int bad = 0;
+#pragma unroll
+  for (int k = 0; k < LARS_IT; ++k) {
+    int64_t i = b0 + (int64_t)(k * LARS_THREADS + threadIdx.x) * 8;
+    if (i < b1) {
+      const uint4 gq = *reinterpret_cast<const uint4*>(g16 + i);
+      const unsigned gw[4] = {gq.x, gq.y, gq.z, gq.w};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) bad |= jz::sumsq_acc_add(sg, (unsigned short)(gw[j >> 1] >> ((j & 1) * 16)));
+    }
+  }
+  {
+    int64_t nh = b0 - s, nt = e - b1;
+    int64_t k = threadIdx.x;
+    if (k < nh + nt) bad |= jz::sumsq_acc_add(sg, g16[(k < nh) ? s + k : b1 + (k - nh)]);
+  }
+  jz::SumsqSink sink{tb.gsum + (size_t)t * LARS_THREADS, tb.gflag + t};
+  jz::sumsq_block_flush(sg, bad, sink, (unsigned)(c - tb.chunk_begin[t]), red);
+}
+
 // Dynamic loss scaling (Sections 4.1 and 5.3 name the loss scale; the policy is the usual skip / shrink / grow one).
 struct DynScale {
   jz_loss_scale_state* st;  // nullptr: fixed loss scale
@@ -359,17 +486,35 @@ __device__ __forceinline__ void lars_step(float& w, float& v, unsigned short gbi
   w16 = float_to_half_bits(wn);                 // cast back for the next forward pass
 }
 
+// PRE: the presummed path -- no lars_finalize ran; every wavefront forms its tensor's lr*rho_t itself (lr, eta and, for a
+// fixed loss scale, S come as arguments) and the overflow flags are those of the sinks.
+template <bool PRE>
 __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __restrict__ w, float* __restrict__ v,
                                                             const unsigned short* __restrict__ g16,
                                                             unsigned short* __restrict__ w16, float m, float wd,
-                                                            float inv_s, int* __restrict__ found_inf, DynScale dyn) {
-  if (dyn.st) inv_s = __int_as_float(tb.state[1]);  // written by lars_finalize (not used when there is no tensor)
+                                                            float inv_s, int* __restrict__ found_inf, DynScale dyn,
+                                                            float lr, float eta, float loss_scale) {
+  if (dyn.st) {  // written by lars_finalize / lars_begin (not used when there is no tensor)
+    inv_s = __int_as_float(tb.state[1]);
+    if (PRE) loss_scale = __int_as_float(tb.state[2]);
+  }
   // the header, this workgroup's chunk record and the tensor flags are requested together; nothing read through the
   // tables is used before the header has been checked
   const int cidx = (int)blockIdx.x < tb.n_chunks ? tb.n_chunks - 1 - (int)blockIdx.x : 0;
   const ChunkRec rec = tb.n_chunks > 0 ? tb.chunk_rec[cidx] : ChunkRec{0, 0, 0};
   int f = 0;  // every wavefront looks at all tensor flags itself: no barrier anywhere in this kernel
-  for (int t = threadIdx.x & 63; t < tb.T; t += 64) f |= tb.tflag[t];
+  for (int t = threadIdx.x & 63; t < tb.T; t += 64) f |= PRE ? tb.gflag[t] : tb.tflag[t];
+  // PRE: this lane's share of the tensor's gradient sink (the tensor index is garbage if the header is: clamp it)
+  unsigned long long d0 = 0, d1 = 0, d2 = 0, d3 = 0;
+  double sw_t = 0.0;
+  if (PRE && tb.n_chunks > 0) {
+    const int ts = rec.tensor >= 0 && rec.tensor < tb.T ? rec.tensor : 0;
+    if ((threadIdx.x & 63) < jz::kSumsqSubs) {
+      const unsigned long long* a = tb.gsum + ((size_t)ts * jz::kSumsqSubs + (threadIdx.x & 63)) * jz::kSumsqSubStride;
+      d0 = a[0]; d1 = a[1]; d2 = a[2]; d3 = a[3];
+    }
+    sw_t = tb.wsum[ts];
+  }
   if (!table_ok(tb)) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *found_inf = -1;
     return;
@@ -377,7 +522,9 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   f = __any(f);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *found_inf = f ? 1 : 0;
-    tb.state[0] = 1;  // skipped or not, psum_w describes the master weights as this launch leaves them
+    // psum_w describes the master weights as this launch leaves them: always when lars_reduce filled it in beforehand;
+    // on the presummed path only once an update has gone through (a skipped one writes no partial sums)
+    if (!PRE || !f) tb.state[0] = 1;
     if (dyn.st) loss_scale_step(dyn, f);  // no workgroup of this launch reads dyn.st->scale
   }
   if (f) return;  // overflow under loss scaling: the step is skipped as a whole
@@ -387,7 +534,22 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   int64_t s, e, b0, b1;
   chunk_range(rec, &t, &s, &e);
   chunk_body(s, e, &b0, &b1);
-  const float coef = tb.coef[t];
+  float coef;
+  if (PRE) {
+    for (int o = jz::kSumsqSubs / 2; o > 0; o >>= 1) {  // integer sums: the order does not matter
+      d0 += __shfl_xor(d0, o, 64);
+      d1 += __shfl_xor(d1, o, 64);
+      d2 += __shfl_xor(d2, o, 64);
+      d3 += __shfl_xor(d3, o, 64);
+    }
+    const double sg = jz::sumsq_value(__shfl(d0, 0, 64), __shfl(d1, 0, 64), __shfl(d2, 0, 64), __shfl(d3, 0, 64));
+    double rho = 1.0;
+    if ((tb.flags[t] & JZ_PARAM_LARS) && sw_t > 0.0 && sg > 0.0)
+      rho = (double)eta * sqrt(sw_t) / (sqrt(sg) / (double)loss_scale);  // Eq. 1 on the un-scaled gradient
+    coef = (float)((double)lr * rho);
+  } else {
+    coef = tb.coef[t];
+  }
   const float lam = (tb.flags[t] & JZ_PARAM_WEIGHT_DECAY) ? wd : 0.0f;
   float4 w0[LARS_IT], w1[LARS_IT], v0[LARS_IT], v1[LARS_IT];
   uint4 gq[LARS_IT];
@@ -467,6 +629,9 @@ Tables make_tables(const Layout& L, void* ws, uint64_t sum) {
   tb.pflag = reinterpret_cast<int*>(b + L.off_pflag);
   tb.coef = reinterpret_cast<float*>(b + L.off_coef);
   tb.tflag = reinterpret_cast<int*>(b + L.off_tflag);
+  tb.gsum = reinterpret_cast<unsigned long long*>(b + L.off_gsum);
+  tb.gflag = reinterpret_cast<int*>(b + L.off_gflag);
+  tb.wsum = reinterpret_cast<double*>(b + L.off_wsum);
   tb.T = (int)L.T;
   tb.n_chunks = (int)L.n_chunks;
   tb.checksum = sum;
@@ -533,7 +698,7 @@ namespace {
 // the update with a fixed loss scale (state == nullptr: hp->loss_scale) or with a device-resident one that the
 // controller adjusts afterwards
 int lars_run(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_scale_policy* pol, jz_loss_scale_state* state,
-             int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream) {
+             int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream, bool presummed = false) {
   if (!hp || !found_inf_dev) return JZ_ERR_NULL;
   Layout L;
   int rc = make_layout(ps, &L);
@@ -569,6 +734,8 @@ int lars_run(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_sc
   }
   uint64_t sum = table_checksum(ps);
   if (!is_prepared(ws, sum)) return JZ_ERR_NOT_PREPARED;
+  // the presummed update consumes what jz_lars_begin_step set up (with the same loss-scale state) and the sinks filled since
+  if (presummed && !has_begun(ws, state)) return JZ_ERR_NOT_PREPARED;
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   Tables tb = make_tables(L, ws, sum);
@@ -576,16 +743,35 @@ int lars_run(const jz_param_set* ps, const jz_lars_hparams* hp, const jz_loss_sc
   const float* scale_dev = state ? &state->scale : nullptr;
   DynScale dyn{state, 1.0f, 1.0f, 1, 1.0f, 1.0f};
   if (state) dyn = DynScale{state, pol->growth_factor, pol->backoff_factor, pol->growth_interval, pol->min_scale, pol->max_scale};
+  if (presummed) {
+    set_begun(ws, false, nullptr);
+    hipLaunchKernelGGL(lars_update<true>, dim3((unsigned)(L.n_chunks > 0 ? L.n_chunks : 1)), dim3(LARS_THREADS), 0, st, tb,
+                       ps->master_w, ps->momentum, g16, static_cast<unsigned short*>(ps->weight16), hp->momentum,
+                       hp->weight_decay, state ? 1.0f : 1.0f / hp->loss_scale, found_inf_dev, dyn, hp->lr, hp->trust_coef,
+                       state ? 1.0f : hp->loss_scale);
+    return jz::launch_status();
+  }
   if (L.n_chunks > 0)
     hipLaunchKernelGGL(lars_reduce, dim3((unsigned)L.n_chunks), dim3(LARS_THREADS), 0, st, tb, ps->master_w, g16);
   if (L.T > 0)
     hipLaunchKernelGGL(lars_finalize, dim3((unsigned)L.T), dim3(LARS_THREADS), 0, st, tb, hp->lr, hp->trust_coef,
                        state ? 1.0f : hp->loss_scale, scale_dev);
   // at least one workgroup so that the flag is always written
-  hipLaunchKernelGGL(lars_update, dim3((unsigned)(L.n_chunks > 0 ? L.n_chunks : 1)), dim3(LARS_THREADS), 0, st, tb,
+  hipLaunchKernelGGL(lars_update<false>, dim3((unsigned)(L.n_chunks > 0 ? L.n_chunks : 1)), dim3(LARS_THREADS), 0, st, tb,
                      ps->master_w, ps->momentum, g16, static_cast<unsigned short*>(ps->weight16), hp->momentum,
-                     hp->weight_decay, state ? 1.0f : 1.0f / hp->loss_scale, found_inf_dev, dyn);
+                     hp->weight_decay, state ? 1.0f : 1.0f / hp->loss_scale, found_inf_dev, dyn, 0.0f, 0.0f, 1.0f);
   return jz::launch_status();
+}
+
+// what the entry points of the presummed path have in common: the table, the workspace and that it was prepared
+int presummed_common(const jz_param_set* ps, void* ws, size_t ws_bytes, Layout* L, uint64_t* sum) {
+  int rc = make_layout(ps, L);
+  if (rc != JZ_OK) return rc;
+  if (!ws || ws_bytes < L->total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(ws)) return JZ_ERR_ALIGN;
+  *sum = table_checksum(ps);
+  if (!is_prepared(ws, *sum)) return JZ_ERR_NOT_PREPARED;
+  return JZ_OK;
 }
 
 }  // namespace
@@ -600,6 +786,73 @@ extern "C" int jz_lars_mp_update_dyn(const jz_param_set* ps, const jz_lars_hpara
                                      void* hip_stream) {
   if (!state_dev) return JZ_ERR_NULL;
   return lars_run(ps, hp, policy, state_dev, found_inf_dev, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int jz_lars_sumsq_sink(const jz_param_set* ps, void* ws, size_t ws_bytes, int64_t tensor, jz_sumsq_sink* sink) {
+  if (!sink) return JZ_ERR_NULL;
+  Layout L;
+  uint64_t sum;
+  int rc = presummed_common(ps, ws, ws_bytes, &L, &sum);
+  if (rc != JZ_OK) return rc;
+  if (tensor < 0 || tensor >= L.T) return JZ_ERR_SHAPE;
+  static_assert(JZ_SUMSQ_SINK_BYTES == jz::kSumsqSinkBytes, "public and internal sink size");
+  char* b = static_cast<char*>(ws);
+  sink->sums = b + L.off_gsum + (size_t)tensor * jz::kSumsqSinkBytes;
+  sink->nonfinite = reinterpret_cast<int*>(b + L.off_gflag) + tensor;
+  return JZ_OK;
+}
+
+extern "C" int jz_lars_begin_step(const jz_param_set* ps, const jz_loss_scale_state* state_dev, void* ws, size_t ws_bytes,
+                                  void* hip_stream) {
+  Layout L;
+  uint64_t sum;
+  int rc = presummed_common(ps, ws, ws_bytes, &L, &sum);
+  if (rc != JZ_OK) return rc;
+  if (L.P > 0 && !ps->master_w) return JZ_ERR_NULL;
+  if (!jz::aligned16(ps->master_w) || (reinterpret_cast<uintptr_t>(state_dev) & 7u)) return JZ_ERR_ALIGN;
+  if (jz::overlaps(ps->master_w, 4 * (size_t)L.P, ws, L.total) || jz::overlaps(state_dev, sizeof(*state_dev), ws, L.total))
+    return JZ_ERR_ALIAS;
+  if (L.T > 0) {
+    hipLaunchKernelGGL(lars_begin, dim3((unsigned)L.T), dim3(LARS_THREADS), 0, static_cast<hipStream_t>(hip_stream),
+                       make_tables(L, ws, sum), ps->master_w, state_dev ? &state_dev->scale : nullptr);
+    if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  }
+  set_begun(ws, true, state_dev);
+  return JZ_OK;
+}
+
+extern "C" int jz_lars_grad_sumsq(const jz_param_set* ps, int64_t first_tensor, int64_t num_tensors, void* ws, size_t ws_bytes,
+                                  void* hip_stream) {
+  Layout L;
+  uint64_t sum;
+  int rc = presummed_common(ps, ws, ws_bytes, &L, &sum);
+  if (rc != JZ_OK) return rc;
+  if (first_tensor < 0 || num_tensors < 0 || first_tensor + num_tensors > L.T) return JZ_ERR_SHAPE;
+  if (L.P > 0 && !ps->grad16) return JZ_ERR_NULL;
+  if (!jz::aligned16(ps->grad16)) return JZ_ERR_ALIGN;
+  if (jz::overlaps(ps->grad16, 2 * (size_t)L.P, ws, L.total)) return JZ_ERR_ALIAS;
+  int64_t c0 = 0, c1 = 0;  // chunks of tensors [first, first + num)
+  for (int64_t t = 0; t < first_tensor + num_tensors; ++t) {
+    const int64_t nc = (ps->offsets[t + 1] - ps->offsets[t] + LARS_CH - 1) / LARS_CH;
+    if (t < first_tensor) c0 += nc;
+    c1 += nc;
+  }
+  if (c1 > c0)
+    hipLaunchKernelGGL(lars_grad_sumsq, dim3((unsigned)(c1 - c0)), dim3(LARS_THREADS), 0, static_cast<hipStream_t>(hip_stream),
+                       make_tables(L, ws, sum), static_cast<const unsigned short*>(ps->grad16), (int)c0);
+  return jz::launch_status();
+}
+
+extern "C" int jz_lars_mp_update_presummed(const jz_param_set* ps, const jz_lars_hparams* hp, int* found_inf_dev, void* ws,
+                                           size_t ws_bytes, void* hip_stream) {
+  return lars_run(ps, hp, nullptr, nullptr, found_inf_dev, ws, ws_bytes, hip_stream, true);
+}
+
+extern "C" int jz_lars_mp_update_presummed_dyn(const jz_param_set* ps, const jz_lars_hparams* hp,
+                                               const jz_loss_scale_policy* policy, jz_loss_scale_state* state_dev,
+                                               int* found_inf_dev, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!state_dev) return JZ_ERR_NULL;
+  return lars_run(ps, hp, policy, state_dev, found_inf_dev, ws, ws_bytes, hip_stream, true);
 }
 
 extern "C" int jz_loss_scale_init(jz_loss_scale_state* state_dev, float initial_scale, void* hip_stream) {

@@ -35,9 +35,12 @@ class Op:
 
 class ResNet50Chain:
     def __init__(self, batch=64, image=224, variant="v1", seed=180711205, initial_loss_scale=1024.0, hparams=None,
-                 policy=None, device="cuda:0", fused=True, block_end=True, proj_side=False):
+                 policy=None, device="cuda:0", fused=True, block_end=True, proj_side=False, presummed=True):
         """fused: forward convolution + batch normalization as one call (statistics in the convolution's epilogue)
-        instead of two."""
+        instead of two.  presummed: the weight-gradient GEMMs leave each filter gradient's sum of squares in the optimiser's
+        workspace, the remaining tensors' sums are taken behind the last gradient of the backward pass, and the update is one
+        launch (else: the update's own reduce pass reads every gradient again, three launches)."""
+        self.presummed = bool(presummed)
         self.N, self.image, self.device, self.fused = int(batch), int(image), torch.device(device), bool(fused)
         self.block_end = bool(block_end) and self.fused
         self.proj_side = bool(proj_side)      # projection-shortcut branches on the side stream too (measured: no gain)
@@ -52,7 +55,8 @@ class ResNet50Chain:
         host = inputs.resnet50_param_set(loss_scale=1.0, seed_key=(seed % 1000003,), variant=variant)
         self.tensors = shapes.resnet50_param_tensors(variant)
         self.offsets = [int(o) for o in host.offsets]
-        self.flags = [int(x) for x in host.flags]
+        self.flags = [int(x) | (api.JZ_PARAM_GRAD_PRESUMMED if self.presummed and kind in ("conv", "fc") else 0)
+                      for x, (_, _, kind, _) in zip(host.flags, self.tensors)]
         self.master = torch.from_numpy(host.master_w).to(dev)
         self.momentum = torch.zeros_like(self.master)
         self.w16 = self.master.to(h)
@@ -77,6 +81,13 @@ class ResNet50Chain:
         self.fwd_ops: List[Op] = []
         self.bwd_ops: List[Op] = []
         self._build()
+        if self.presummed:
+            # first launch of a step: clear the gradient sinks, add up the carried sums of squares of the weights, note the
+            # loss scale; last launch of the backward pass: the tensors no GEMM produces (batch-norm scale / shift, bias)
+            self.fwd_ops.insert(0, Op("lars_begin", "begin", {}, [], [],
+                                      lambda stream=None: api.jz_lars_begin_step(self.ps, self.lars_ws, self.ls_state, stream)))
+            self.bwd_ops.append(Op("lars_grad_sumsq", "rest", {}, [self.grad], [],
+                                   lambda stream=None: api.jz_lars_grad_sumsq(self.ps, 0, self.ps.T, self.lars_ws, stream)))
         self.ws = torch.zeros(self._ws_bytes, dtype=torch.uint8, device=dev)
         self.side_ws = []               # one workspace per side stream, made on first use
         self._side_calls = {}
@@ -104,8 +115,11 @@ class ResNet50Chain:
         d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
         self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
         kind = {api.JZ_FWD: "conv_fwd", api.JZ_BWD_DATA: "conv_bwd_data", api.JZ_BWD_WEIGHT: "conv_bwd_weight"}[op]
-        o = Op(kind, name, dict(desc=d), [a, b], [out], self._later(lambda ws: api.bind_conv2d(op, d, a, b, out, ws)),
-               lambda ws: api.bind_conv2d(op, d, a, b, out, ws))
+        bind = lambda ws: api.bind_conv2d(op, d, a, b, out, ws)
+        if op == api.JZ_BWD_WEIGHT and self.presummed:
+            sink = api.jz_lars_sumsq_sink(self.ps, self.lars_ws, self.index[name + ".w"])
+            bind = lambda ws: api.bind_conv2d_bwd_weight_sumsq(d, a, b, out, sink, ws)
+        o = Op(kind, name, dict(desc=d), [a, b], [out], self._later(bind), bind)
         if op == api.JZ_BWD_WEIGHT:
             o.lane = "side"
         return o
@@ -114,8 +128,11 @@ class ResNet50Chain:
         B, I, O = self.N, self.fc.I, self.fc.O
         self._ws_bytes = max(self._ws_bytes, api.jz_gemm_fc_workspace_bytes(mode, B, I, O))
         kind = {api.JZ_FWD: "fc_fwd", api.JZ_BWD_DATA: "fc_bwd_data", api.JZ_BWD_WEIGHT: "fc_bwd_weight"}[mode]
-        o = Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)),
-               lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws))
+        bind = lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)
+        if mode == api.JZ_BWD_WEIGHT and self.presummed:
+            sink = api.jz_lars_sumsq_sink(self.ps, self.lars_ws, self.index[name + ".w"])
+            bind = lambda ws: api.bind_gemm_fc_bwd_weight_sumsq(B, I, O, a, b, out, sink, ws)
+        o = Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(bind), bind)
         if mode == api.JZ_BWD_WEIGHT:
             o.lane = "side"
         return o
@@ -298,7 +315,8 @@ class ResNet50Chain:
 
     def _lars_op(self):
         hp = api.lars_hparams(self.hp["lr"], self.hp["momentum"], self.hp["weight_decay"], self.hp["trust_coef"], 1.0)
-        call = lambda stream=None: api.jz_lars_mp_update_dyn(self.ps, hp, self.policy, self.ls_state, self.found_inf, self.lars_ws, stream)
+        fn = api.jz_lars_mp_update_presummed_dyn if self.presummed else api.jz_lars_mp_update_dyn
+        call = lambda stream=None: fn(self.ps, hp, self.policy, self.ls_state, self.found_inf, self.lars_ws, stream)
         return Op("lars_dyn", "update", dict(hp=dict(self.hp)), [self.master, self.momentum, self.grad, self.w16, self.ls_state],
                   [self.master, self.momentum, self.w16, self.found_inf, self.ls_state], call)
 

@@ -30,10 +30,36 @@ def rel_l2(got: np.ndarray, ref64: np.ndarray) -> float:
     return float(np.linalg.norm(g - r) / den) if den > 0 else float(np.linalg.norm(g))
 
 
+def exact_units(g16: np.ndarray) -> int:
+    """sum of squares of finite fp16 values as an exact integer count of units of 2^-48 (every fp16 value is an integer
+    multiple of 2^-24, below 2^40 of them): k = value * 2^24 is exact in fp64 and in int64; k^2 is split as
+    (hi 2^20 + lo)^2 so that every partial sum stays inside int64, and the three sums are combined as Python integers."""
+    k = np.abs(np.rint(g16.astype(np.float64).ravel() * 2.0 ** 24)).astype(np.int64)
+    hi, lo = k >> 20, k & 0xFFFFF
+    total = 0
+    for s in range(0, k.size, 1 << 20):     # 2^20 elements per slice: hi * hi < 2^40, so a slice's sum < 2^61
+        h, l = hi[s:s + (1 << 20)], lo[s:s + (1 << 20)]
+        total += (int(np.sum(h * h)) << 40) + (int(np.sum(2 * h * l)) << 20) + int(np.sum(l * l))
+    return total
+
+
+def sink_units(ps, ws, tensor) -> int:
+    """What the sink of `tensor` inside a LARS workspace holds (exact integer units of 2^-48) and its non-finite flag."""
+    sink = api.jz_lars_sumsq_sink(ps, ws, tensor)
+    base, fl = sink.sums - ws.data_ptr(), sink.nonfinite - ws.data_ptr()
+    return api.sumsq_sink_units(ws[base:base + api.JZ_SUMSQ_SINK_BYTES].view(torch.int64)), int(ws[fl:fl + 4].view(torch.int32).item())
+
+
+# which update LarsRun.step runs: "three_launches" (jz_lars_mp_update) or "presummed" (jz_lars_begin_step, jz_lars_grad_sumsq
+# over every tensor, jz_lars_mp_update_presummed); the LARS test modules run every test both ways
+LARS_PATH = "three_launches"
+
+
 class LarsRun:
     """Device copies of a fused parameter set plus a prepared workspace."""
 
-    def __init__(self, ps: inputs.ParamSet, weight16_init=None):
+    def __init__(self, ps: inputs.ParamSet, weight16_init=None, path=None):
+        self.path = LARS_PATH if path is None else path
         self.host = ps
         self.w = to_dev(ps.master_w)
         self.v = to_dev(ps.momentum)
@@ -49,8 +75,13 @@ class LarsRun:
         kw = dict(inputs.HPARAMS)
         kw.update(hp)
         S = self.host.loss_scale if loss_scale is None else loss_scale
-        api.jz_lars_mp_update(self.ps, api.lars_hparams(kw["lr"], kw["momentum"], kw["weight_decay"], kw["trust_coef"], S),
-                              self.flag, self.ws)
+        hpc = api.lars_hparams(kw["lr"], kw["momentum"], kw["weight_decay"], kw["trust_coef"], S)
+        if self.path == "presummed":
+            api.jz_lars_begin_step(self.ps, self.ws)
+            api.jz_lars_grad_sumsq(self.ps, 0, self.ps.T, self.ws)
+            api.jz_lars_mp_update_presummed(self.ps, hpc, self.flag, self.ws)
+        else:
+            api.jz_lars_mp_update(self.ps, hpc, self.flag, self.ws)
         torch.cuda.synchronize()
         return self.w.cpu().numpy(), self.v.cpu().numpy(), self.w16.cpu().numpy(), int(self.flag.item())
 

@@ -139,17 +139,20 @@ def check_op(op, counts):
         assert np.allclose(outs[1], l64, rtol=2e-6, atol=2e-5), what
         err = np.abs(outs[0].astype(np.float64).reshape(d64.shape) - d64)
         assert np.all(err <= 2.0 ** -10 * np.abs(d64) + 2.0 ** -25), what
+    elif k in ("lars_begin", "lars_grad_sumsq"):
+        pass        # what they leave in the optimiser's workspace is checked as a whole, behind the backward pass
     else:
         raise AssertionError("no check for " + k)
 
 
-@pytest.mark.parametrize("fused,block_end", [(True, True), (True, False), (False, False)])
-def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused, block_end):
+@pytest.mark.parametrize("fused,block_end,presummed", [(True, True, True), (True, True, False), (True, False, True), (False, False, True)])
+def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused, block_end, presummed):
     import jzt
     from paper_1807_11205_amd import resnet50
     net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=256.0, policy=dict(growth_interval=1), fused=fused,
-                                 block_end=block_end)
-    assert len(net.fwd_ops) == (53 if fused else 53 * 2 + 16) + 1 + 1 + 3 and net.trace[-1].kind == "lars_dyn"
+                                 block_end=block_end, presummed=presummed)
+    assert len(net.fwd_ops) == (53 if fused else 53 * 2 + 16) + 1 + 1 + 3 + (1 if presummed else 0) and net.trace[-1].kind == "lars_dyn"
+    assert (net.fwd_ops[0].kind == "lars_begin" and net.bwd_ops[-1].kind == "lars_grad_sumsq") == presummed
     for op in net.trace[:-1]:
         op.call()
     torch.cuda.synchronize()
@@ -165,6 +168,12 @@ def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused, block_end)
     g = np16(net.grad)
     for i, (name, _, _, _) in enumerate(net.tensors):
         assert np.any(g[net.offsets[i]:net.offsets[i + 1]] != 0), name
+    if presummed:
+        # every tensor's sink holds exactly the sum of squares of its gradient: the filters' from the weight-gradient GEMMs
+        # (split reduction, unsplit + separate pass, small-channel stem alike), the rest from the pass behind the backward
+        for i, (name, _, _, _) in enumerate(net.tensors):
+            units, bad = jzt.sink_units(net.ps, net.lars_ws, i)
+            assert bad == 0 and units == jzt.exact_units(g[net.offsets[i]:net.offsets[i + 1]]), name
     # the update: LARS against the oracle with the scale the step ran with, then the controller
     before = inputs.ParamSet(names=[t[0] for t in net.tensors], offsets=np.asarray(net.offsets, np.int64),
                              flags=np.asarray(net.flags, np.uint8), master_w=np16(net.master), momentum=np16(net.momentum),

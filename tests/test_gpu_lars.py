@@ -16,6 +16,15 @@ def jz():
     return api
 
 
+@pytest.fixture(autouse=True, params=["three_launches", "presummed"])
+def lars_path(request):
+    """Every test of this module runs on both update paths (see jzt.LARS_PATH)."""
+    import jzt
+    old, jzt.LARS_PATH = jzt.LARS_PATH, request.param
+    yield request.param
+    jzt.LARS_PATH = old
+
+
 def run_and_check(ps, plain_rtol=None, plain_floor=0.0, **hp):
     import jzt
     r = jzt.LarsRun(ps)

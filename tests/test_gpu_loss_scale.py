@@ -20,6 +20,15 @@ def jz():
     return api
 
 
+@pytest.fixture(autouse=True, params=["three_launches", "presummed"])
+def lars_path(request):
+    """Every test of this module runs on both update paths (see jzt.LARS_PATH)."""
+    import jzt
+    old, jzt.LARS_PATH = jzt.LARS_PATH, request.param
+    yield request.param
+    jzt.LARS_PATH = old
+
+
 class DynRun:
     def __init__(self, api, ps, initial_scale, **policy):
         import jzt
@@ -34,8 +43,13 @@ class DynRun:
         hp = dict(inputs.HPARAMS)
         hp.update(over)
         # the loss_scale field is ignored by the dynamic entry point: a wrong value here must not matter
-        api.jz_lars_mp_update_dyn(r.ps, api.lars_hparams(hp["lr"], hp["momentum"], hp["weight_decay"], hp["trust_coef"], 3.0),
-                                  self.policy, self.state, r.flag, r.ws)
+        hpc = api.lars_hparams(hp["lr"], hp["momentum"], hp["weight_decay"], hp["trust_coef"], 3.0)
+        if r.path == "presummed":
+            api.jz_lars_begin_step(r.ps, r.ws, self.state)
+            api.jz_lars_grad_sumsq(r.ps, 0, r.ps.T, r.ws)
+            api.jz_lars_mp_update_presummed_dyn(r.ps, hpc, self.policy, self.state, r.flag, r.ws)
+        else:
+            api.jz_lars_mp_update_dyn(r.ps, hpc, self.policy, self.state, r.flag, r.ws)
         torch.cuda.synchronize()
         return r.w.cpu().numpy(), r.v.cpu().numpy(), r.w16.cpu().numpy(), int(r.flag.item())
 
