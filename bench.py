@@ -35,13 +35,20 @@ LARS_BYTES_PER_PARAM = 20        # read w32 4 + g16 2 + v32 4, write w32 4 + v32
 class ResNet50Step:
     """All device buffers of one ResNet-50 N=batch step and the launch sequence."""
 
-    def __init__(self, batch=64, loss_scale=1024.0, seed=180711205, variant="v1", device="cuda:0", dtype="f16", lars_path="presummed"):
+    def __init__(self, batch=64, loss_scale=1024.0, seed=180711205, variant="v1", device="cuda:0", dtype="f16", lars_path="presummed",
+                 sumsq_from="split"):
         """dtype "f32": the single-precision variant of the GEMM phase (float32 activations, filters = the master weights,
         float32 weight gradients in a buffer of their own; the LARS update still runs on the fp16 gradient buffer).
-        lars_path "presummed": the backward-weight launches leave each filter gradient's sum of squares in the optimiser's
-        workspace and the update is one launch; "three_launches": plain backward-weight, jz_lars_mp_update."""
+        lars_path "presummed": the update is one launch (jz_lars_mp_update_presummed).  The gradient sums of squares it needs
+        come from two places.  sumsq_from "split": a backward-weight launch whose reduction is split leaves its gradient's
+        sum of squares in the optimiser's workspace from inside the kernel that adds the partial sums (the values are in
+        registers there); every other tensor (unsplit filters, batch-norm scale / shift, bias) is covered by one
+        jz_lars_grad_sumsq launch behind the last backward-data launch, beside the last backward-weight launches.
+        "all": every backward-weight launch leaves its sum (unsplit ones through a separate pass over the gradient).
+        "three_launches": plain backward-weight, jz_lars_mp_update."""
         self.f32 = dtype == "f32"
         self.presummed = lars_path == "presummed" and not self.f32
+        self.sumsq_from = sumsq_from
         self.N = batch
         self.dev = device
         self.loss_scale = float(loss_scale)
@@ -53,8 +60,7 @@ class ResNet50Step:
         self.fc = shapes.RESNET50_FC
         tensors = shapes.resnet50_param_tensors(variant)
         self.offsets = shapes.offsets_of(tensors)
-        # conv / FC weight gradients come with their sums of squares on the presummed path (bit 4 of the flags)
-        self.flags = [t[3] | (api.JZ_PARAM_GRAD_PRESUMMED if self.presummed and t[2] in ("conv", "fc") else 0) for t in tensors]
+        self.flags = [t[3] for t in tensors]   # the presummed path marks the tensors whose producer supplies the sum (below)
         P = self.offsets[-1]
         h = torch.float32 if self.f32 else torch.float16
 
@@ -108,6 +114,13 @@ class ResNet50Step:
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)
         self.side_ws = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device) for _ in range(3)]
 
+        if self.presummed:
+            for L in self.layers:
+                d = L["d"] if L["kind"] == "conv" else api.conv_desc(B, 1, 1, I, O, 1, 1)
+                split = ", 1 splits" not in api.jz_conv2d_describe_plan(api.JZ_BWD_WEIGHT, d)
+                L["sumsq"] = self.sumsq_from == "all" or (self.sumsq_from == "split" and split)
+                if L["sumsq"]:
+                    self.flags[L["tensor"]] |= api.JZ_PARAM_GRAD_PRESUMMED
         self.found_inf = torch.zeros(1, dtype=torch.int32, device=device)
         self.ps = api.ParamSet(self.offsets, self.flags, self.master, self.momentum, self.grad, self.w16)
         self.lars_ws = torch.zeros(api.jz_lars_workspace_bytes(self.ps), dtype=torch.uint8, device=device)
@@ -124,7 +137,7 @@ class ResNet50Step:
         B, I, O = self.N, self.fc.I, self.fc.O
         key = (op, ws.data_ptr())
         if key not in L["calls"]:
-            if self.presummed and op == api.JZ_BWD_WEIGHT:
+            if self.presummed and op == api.JZ_BWD_WEIGHT and L.get("sumsq"):
                 sink = api.jz_lars_sumsq_sink(self.ps, self.lars_ws, L["tensor"])
                 if L["kind"] == "conv":
                     L["calls"][key] = api.bind_conv2d_bwd_weight_sumsq(L["d"], L["x"], L["dy"], L["dw"], sink, ws)
@@ -150,17 +163,26 @@ class ResNet50Step:
         backward-data chain stays on stream 0.  Each side stream has its own workspace."""
         prog = []
         ev = lambda: torch.cuda.Event()
-        if self.presummed:   # the step starts: clear the gradient sinks, add up the carried sums of squares of the weights
-            prog.append(("launch", lambda st: api.jz_lars_begin_step(self.ps, self.lars_ws, self.ls_state, stream=st), 0))
-        # the tensors no GEMM produces (batch-norm scale / shift, bias): their sums of squares once their gradients exist,
-        # i.e. behind the last backward-data launch
-        rest = [("launch", lambda st: api.jz_lars_grad_sumsq(self.ps, 0, self.ps.T, self.lars_ws, stream=st), 0)] if self.presummed else []
+        names = [L["name"] for L in self.layers]
+        begin = ("launch", lambda st: api.jz_lars_begin_step(self.ps, self.lars_ws, self.ls_state, stream=st))
+        # every tensor whose sum of squares no backward-weight launch supplies, in one launch behind the last backward-data
+        # launch (their gradients exist by then, or are being written by launches this one is ordered behind)
+        rest = ("launch", lambda st: api.jz_lars_grad_sumsq(self.ps, 0, self.ps.T, self.lars_ws, stream=st), 0)
         pending = None
         block_in = None
-        names = {L["name"] for L in self.layers}
+        begun = not self.presummed
+        if self.presummed and not n_side:
+            prog.append(begin + (0,))   # the step starts: clear the gradient sinks, add up the carried sums of squares of the weights
+            begun = True
         for L in self.layers:                                   # forward
             if n_side and L["kind"] == "conv" and L["name"].endswith("p"):
                 prog += [("wait", block_in, 1), ("launch", self._bound(L, api.JZ_FWD, self.side_ws[0]), 1)]
+                if not begun:
+                    # jz_lars_begin_step costs the step nothing here: side stream 1 has nothing else to do, block_in orders
+                    # it behind the previous update, and the main stream waits for `pending` long before anything touches
+                    # a sink
+                    prog.append(begin + (1,))
+                    begun = True
                 pending = ev()
                 prog.append(("record", pending, 1))
                 continue
@@ -174,22 +196,34 @@ class ResNet50Step:
             prog.append(("launch", self._bound(L, api.JZ_FWD, self.ws), 0))
         if pending is not None:
             prog.append(("wait", pending, 0))
+        if not begun:
+            prog.append(begin + (0,))
         if not n_side:
             for L in reversed(self.layers):                     # backward, one stream
                 if not L.get("first"):
                     prog.append(("launch", self._bound(L, api.JZ_BWD_DATA, self.ws), 0))
                 prog.append(("launch", self._bound(L, api.JZ_BWD_WEIGHT, self.ws), 0))
-            return prog + rest
+            return prog + ([rest] if self.presummed else [])
         ready = ev()
         prog.append(("record", ready, 0))                       # the loss gradient exists
+        unsplit_done = {}
         for k, L in enumerate(reversed(self.layers)):
             si = 1 + k % n_side
             prog += [("wait", ready, si), ("launch", self._bound(L, api.JZ_BWD_WEIGHT, self.side_ws[si - 1]), si)]
+            if self.presummed and not L.get("sumsq"):
+                unsplit_done[si] = len(prog)                    # the last launch on this side stream that `rest` reads from
             if not L.get("first"):
                 prog.append(("launch", self._bound(L, api.JZ_BWD_DATA, self.ws), 0))
                 ready = ev()
                 prog.append(("record", ready, 0))               # dy of the layer below exists
-        prog += rest
+        if self.presummed:
+            # `rest` reads the unsplit filters' gradients: behind the last such launch of each side stream (they are early in
+            # the backward pass, so these waits do not hold the main stream up)
+            for si, pos in sorted(unsplit_done.items(), key=lambda kv: -kv[1]):
+                e = ev()
+                prog.insert(pos, ("record", e, si))
+                prog.append(("wait", e, 0))
+            prog.append(rest)
         for si in range(1, n_side + 1):
             done = ev()
             prog += [("record", done, si), ("wait", done, 0)]
@@ -645,12 +679,15 @@ def main():
                          "bn: the batch-normalization + ReLU layers of ResNet-50 (not part of the headline step); chain: a complete chained "
                          "ResNet-50 training step with every layer between the convolutions (not the headline step either)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-alt", action="store_true", help="skip the run with the other LARS update path")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
     ap.add_argument("--per-layer-file", default=None, help="write the per-layer table (time, TFLOP/s, the layer's own roofline, "
                     "fraction, kernel plan) to this file as well; implies --per-layer")
     ap.add_argument("--lars-path", default="presummed", choices=("presummed", "three_launches"),
                     help="presummed: the backward-weight launches leave each filter gradient's sum of squares with the optimiser "
                          "and the update is one launch; three_launches: jz_lars_mp_update (reduce, rates, update)")
+    ap.add_argument("--sumsq-from", default="split", choices=("split", "all"),
+                    help="presummed path: which backward-weight launches leave their gradient's sum of squares (see ResNet50Step)")
     ap.add_argument("--dtype", default="f16", choices=("f16", "f32"), help="f16: the mixed-precision path (the headline); f32: the "
                     "single-precision variant of the same step (Table 9's comparison)")
     ap.add_argument("--no-fp32", action="store_true", help="skip the short single-precision run that the default line reports beside the headline")
@@ -693,7 +730,7 @@ def main():
     if args.workload == "chain":
         chain_workload(args)
         return
-    wl = ResNet50Step(batch=args.batch, dtype=args.dtype, lars_path=args.lars_path)
+    wl = ResNet50Step(batch=args.batch, dtype=args.dtype, lars_path=args.lars_path, sumsq_from=args.sumsq_from)
 
     # loss-scale back-off: halve S until the weight gradients stay inside fp16 and the update is not skipped
     for _ in range(12):
@@ -757,6 +794,17 @@ def main():
         worst = sorted(rows, key=lambda r: r["us"] - r["us_roofline"], reverse=True)[:10]
         out["per_layer_worst"] = [{k: r[k] for k in ("layer", "shape", "op", "us", "us_roofline", "tflops", "roofline_tflops", "frac", "plan")}
                                   for r in worst]
+    if wl.presummed and not args.no_alt:
+        # the same step with the other update path (plain backward-weight launches, three-launch update), a run of its own:
+        # what the one-launch update costs the GEMM phase and what it saves behind it
+        wl3 = ResNet50Step(batch=args.batch, loss_scale=wl.loss_scale, lars_path="three_launches")   # the scale after back-off
+        if args.dynamic_loss_scale:
+            wl3.use_dynamic_loss_scale()
+        t3 = time_steps(wl3, stream, side, args.steps, args.warmup)
+        out["lars"]["three_launch_path"] = {"us_per_update": t3["lars_ms"] * 1e3, "ms_gemm_phase": t3["gemm_ms"], "ms_per_step": t3["wall_ms"],
+                                            "images_per_s": args.batch / (t3["wall_ms"] * 1e-3),
+                                            "note": "jz_lars_mp_update behind plain backward-weight launches, same run, same inputs"}
+        del wl3
     if not wl.f32 and not args.no_fp32:
         # Table 9's comparison on this chip: the same step with the single-precision kernels (a short run of its own)
         wl32 = ResNet50Step(batch=args.batch, dtype="f32")

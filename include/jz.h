@@ -94,16 +94,16 @@ int jz_conv2d_bwd_weight(const jz_conv_desc* desc, const void* x16, const void* 
 /* The weight gradient together with its sum of squares.  Eq. 1 needs ||g_t|| of every tensor before the update can
  * start; taking it here, while the gradient is being written, saves the optimiser a second pass over the gradients
  * (jz_lars_mp_update_presummed below consumes it).  A sink is JZ_SUMSQ_SINK_BYTES of DEVICE memory, 128-byte aligned,
- * plus one DEVICE int: 16 accumulators 128 bytes apart, each four unsigned 64-bit counters, counter i in units of
+ * plus one DEVICE int: 64 accumulators 128 bytes apart, each four unsigned 64-bit counters, counter i in units of
  * 2^(20 i - 48).  A finite FP16 value is an integer multiple of 2^-24, so its square is an integer number of units of
  * 2^-48: the kernels add those integers (carried into base-2^20 digits per workgroup, one atomic integer add per digit),
  * hence the counters hold the EXACT sum of squares of the values written to dw16, whatever the order in which
  * workgroups arrive and whatever kernel plan ran (bit-identical from run to run).  sum = (c3 2^60 + c2 2^40 + c1 2^20 +
- * c0) 2^-48 with c_i the sum of counter i over the 16 accumulators.  The calls ADD to the sink (several calls may share
+ * c0) 2^-48 with c_i the sum of counter i over the 64 accumulators.  The calls ADD to the sink (several calls may share
  * one; the caller clears it: jz_lars_begin_step does for the sinks inside a LARS workspace) and set *nonfinite = 1 if an
  * element of dw16 is +-Inf or NaN (they never clear it; the counters are then left as they were).  dw16 holds the same bits as from
  * jz_conv2d_bwd_weight / jz_gemm_fc(JZ_BWD_WEIGHT).  JZ_ERR_ALIGN / JZ_ERR_ALIAS / JZ_ERR_NULL for a bad sink. */
-#define JZ_SUMSQ_SINK_BYTES 2048
+#define JZ_SUMSQ_SINK_BYTES 8192
 typedef struct {
   void* sums;     /* DEVICE, JZ_SUMSQ_SINK_BYTES, 128-byte aligned */
   int* nonfinite; /* DEVICE */

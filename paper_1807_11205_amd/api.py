@@ -64,7 +64,7 @@ class jz_sumsq_sink(ctypes.Structure):
     _fields_ = [("sums", ctypes.c_void_p), ("nonfinite", ctypes.c_void_p)]
 
 
-JZ_SUMSQ_SINK_BYTES = 2048
+JZ_SUMSQ_SINK_BYTES = 8192
 
 
 class jz_param_set(ctypes.Structure):
@@ -462,19 +462,19 @@ def jz_lars_mp_update_dyn(ps: ParamSet, hp: jz_lars_hparams, policy: jz_loss_sca
 
 # ---- the update in one launch: gradient norms taken where the gradients are produced --------------------------------------
 def sumsq_sink(sums: torch.Tensor, nonfinite: torch.Tensor) -> jz_sumsq_sink:
-    """A sink in caller-owned memory: `sums` int64[256] (2048 bytes, 128-byte aligned), `nonfinite` int32[1]; the caller keeps
+    """A sink in caller-owned memory: `sums` int64[1024] (8192 bytes, 128-byte aligned), `nonfinite` int32[1]; the caller keeps
     both alive and clears them."""
     if not sums.is_cuda or sums.dtype != torch.int64 or sums.numel() != JZ_SUMSQ_SINK_BYTES // 8 or not sums.is_contiguous():
-        raise TypeError("sums must be a contiguous 256-element int64 GPU tensor")
+        raise TypeError("sums must be a contiguous 1024-element int64 GPU tensor")
     if not nonfinite.is_cuda or nonfinite.dtype != torch.int32 or nonfinite.numel() != 1:
         raise TypeError("nonfinite must be a one-element int32 GPU tensor")
     return jz_sumsq_sink(sums.data_ptr(), nonfinite.data_ptr())
 
 
 def sumsq_sink_units(sums: torch.Tensor) -> int:
-    """What a sink holds, read back (synchronizes), as an exact integer count of units of 2^-48: the 16 quadruples of
+    """What a sink holds, read back (synchronizes), as an exact integer count of units of 2^-48: the 64 quadruples of
     base-2^20 digit counters added as integers."""
-    a = sums.cpu().numpy().view(np.uint64).reshape(16, 16)
+    a = sums.cpu().numpy().view(np.uint64).reshape(64, 16)
     d = [sum(int(x) for x in a[:, i]) for i in range(4)]
     return (d[3] << 60) + (d[2] << 40) + (d[1] << 20) + d[0]
 

@@ -165,7 +165,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_sumsq(const float* __restri
                                                            long long MN, int splits, int lg, int KT4, int S, int C,
                                                            long long slabs, jz::SumsqSink sink) {
   __shared__ float4 red[256];
-  __shared__ unsigned long long wsum[12];
+  __shared__ unsigned long long wsum[5];
+  if (threadIdx.x < 5) wsum[threadIdx.x] = 0ull;
+  __syncthreads();
   const int G = 1 << lg, Q = 256 >> lg;
   const int q = threadIdx.x & (Q - 1), g = threadIdx.x >> (8 - lg);
   jz::SumsqAcc sq;
@@ -241,7 +243,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_sumsq(const float* __restri
 
 // sum of squares of n FP16 values into a sink (gradients whose producing kernel has no fused form)
 __global__ __launch_bounds__(256) void sumsq_half(const unsigned short* __restrict__ g16, long long n, jz::SumsqSink sink) {
-  __shared__ unsigned long long wsum[12];
+  __shared__ unsigned long long wsum[5];
+  if (threadIdx.x < 5) wsum[threadIdx.x] = 0ull;
+  __syncthreads();
   jz::SumsqAcc sq;
   int bad = 0;
   const long long groups = n >> 3;  // 16-byte groups; g16 is 16-byte aligned
@@ -599,7 +603,7 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     unsigned blocks = (unsigned)(((MN + 3) / 4 + per_block - 1) / per_block);
     // small-channel backward-weight: the reduction writes the real filter entries straight into dw
     if (sink) {
-      const unsigned grid = blocks < 512u ? blocks : 512u;
+      const unsigned grid = blocks < 2048u ? blocks : 2048u;  // at most 32 workgroups per counter quadruple of the sink
       hipLaunchKernelGGL(splitk_reduce_sumsq, dim3(grid), dim3(256), 0, st, a.Dpart, dwp ? static_cast<unsigned short*>(D) : a.D16,
                          MN, a.splits, lg, dwp ? pl.KT / 4 : 0, d->S, d->C, (long long)blocks, *sink);
       sink = nullptr;  // taken

@@ -392,8 +392,8 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_begin(Tables tb, const floa
   if (!table_ok(tb)) return;
   const int t = blockIdx.x;
   const bool have_w = tb.state[0] != 0;  // written by an earlier launch
-  static_assert(jz::kSumsqSubs * jz::kSumsqSubStride == LARS_THREADS, "one 64-bit word of the sink per thread");
-  tb.gsum[(size_t)t * LARS_THREADS + threadIdx.x] = 0ull;
+  constexpr int SINK_WORDS = jz::kSumsqSubs * jz::kSumsqSubStride;
+  for (int i = threadIdx.x; i < SINK_WORDS; i += LARS_THREADS) tb.gsum[(size_t)t * SINK_WORDS + i] = 0ull;
   if (threadIdx.x == 0) tb.gflag[t] = 0;
   if (scale_dev && t == 0 && threadIdx.x == 0) {  // the update adjusts the device-resident scale itself: it reads S from here
     const float S = *scale_dev;
@@ -424,10 +424,12 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_begin(Tables tb, const floa
 
 // The gradient reduce pass into the sinks, one workgroup per chunk, for chunks chunk0 .. chunk0 + gridDim.x - 1.
 __global__ __launch_bounds__(LARS_THREADS) void lars_grad_sumsq(Tables tb, const unsigned short* __restrict__ g16, int chunk0) {
-  __shared__ unsigned long long red[3 * LARS_WAVES];
+  __shared__ unsigned long long red[5];
   const int c = chunk0 + (int)blockIdx.x;
   const ChunkRec rec = tb.chunk_rec[c];
   if (!table_ok(tb)) return;
+  if (threadIdx.x < 5) red[threadIdx.x] = 0ull;
+  __syncthreads();
   int t;
   int64_t s, e, b0, b1;
   chunk_range(rec, &t, &s, &e);
@@ -450,7 +452,7 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_grad_sumsq(Tables tb, const
     int64_t k = threadIdx.x;
     if (k < nh + nt) bad |= jz::sumsq_acc_add(sg, g16[(k < nh) ? s + k : b1 + (k - nh)]);
   }
-  jz::SumsqSink sink{tb.gsum + (size_t)t * LARS_THREADS, tb.gflag + t};
+  jz::SumsqSink sink{tb.gsum + (size_t)t * (jz::kSumsqSubs * jz::kSumsqSubStride), tb.gflag + t};
   jz::sumsq_block_flush(sg, bad, sink, (unsigned)(c - tb.chunk_begin[t]), red);
 }
 
@@ -505,13 +507,17 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   int f = 0;  // every wavefront looks at all tensor flags itself: no barrier anywhere in this kernel
   for (int t = threadIdx.x & 63; t < tb.T; t += 64) f |= PRE ? tb.gflag[t] : tb.tflag[t];
   // PRE: this lane's share of the tensor's gradient sink (the tensor index is garbage if the header is: clamp it)
+  // the first wavefront reads the sink (one quadruple per lane) and hands the total to the others through LDS
+  __shared__ double sg_shared;
   unsigned long long d0 = 0, d1 = 0, d2 = 0, d3 = 0;
   double sw_t = 0.0;
   if (PRE && tb.n_chunks > 0) {
     const int ts = rec.tensor >= 0 && rec.tensor < tb.T ? rec.tensor : 0;
-    if ((threadIdx.x & 63) < jz::kSumsqSubs) {
-      const unsigned long long* a = tb.gsum + ((size_t)ts * jz::kSumsqSubs + (threadIdx.x & 63)) * jz::kSumsqSubStride;
-      d0 = a[0]; d1 = a[1]; d2 = a[2]; d3 = a[3];
+    static_assert(jz::kSumsqSubs == 64, "one counter quadruple per lane");
+    if (threadIdx.x < 64) {
+      const ulonglong2* a = reinterpret_cast<const ulonglong2*>(tb.gsum + ((size_t)ts * jz::kSumsqSubs + threadIdx.x) * jz::kSumsqSubStride);
+      const ulonglong2 lo = a[0], hi = a[1];
+      d0 = lo.x; d1 = lo.y; d2 = hi.x; d3 = hi.y;
     }
     sw_t = tb.wsum[ts];
   }
@@ -536,13 +542,15 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   chunk_body(s, e, &b0, &b1);
   float coef;
   if (PRE) {
-    for (int o = jz::kSumsqSubs / 2; o > 0; o >>= 1) {  // integer sums: the order does not matter
-      d0 += __shfl_xor(d0, o, 64);
-      d1 += __shfl_xor(d1, o, 64);
-      d2 += __shfl_xor(d2, o, 64);
-      d3 += __shfl_xor(d3, o, 64);
+    if (threadIdx.x < 64) {  // integer sums: the order does not matter
+      d0 = jz::wave_total_u64(d0);
+      d1 = jz::wave_total_u64(d1);
+      d2 = jz::wave_total_u64(d2);
+      d3 = jz::wave_total_u64(d3);
+      if (threadIdx.x == 63) sg_shared = jz::sumsq_value(d0, d1, d2, d3);
     }
-    const double sg = jz::sumsq_value(__shfl(d0, 0, 64), __shfl(d1, 0, 64), __shfl(d2, 0, 64), __shfl(d3, 0, 64));
+    __syncthreads();  // every wavefront of the workgroup is here: the returns above depend on nothing wave-specific
+    const double sg = sg_shared;
     double rho = 1.0;
     if ((tb.flags[t] & JZ_PARAM_LARS) && sw_t > 0.0 && sg > 0.0)
       rho = (double)eta * sqrt(sw_t) / (sqrt(sg) / (double)loss_scale);  // Eq. 1 on the un-scaled gradient

@@ -11,14 +11,14 @@
 // plan.  The three low counters take 2^44 contributions before they could overflow, the top one holds up to 2^76 units
 // (more than 2^31 elements of the largest FP16 value).
 //
-// Atomics on one address queue behind each other (about 12 ns each on MI355X), so a tensor has kSumsqSubs such
+// Atomics on one cache line queue behind each other (about 12 ns each on MI355X), so a tensor has kSumsqSubs such
 // counter quadruples, 128 bytes apart; a contributor picks one by its workgroup index and the reader adds them.
 #pragma once
 #include <hip/hip_runtime.h>
 
 namespace jz {
 
-constexpr int kSumsqSubs = 16;       // counter quadruples per tensor
+constexpr int kSumsqSubs = 64;       // counter quadruples per tensor: one per lane of the wavefront that reads them
 constexpr int kSumsqSubStride = 16;  // 64-bit words between quadruples (128 bytes: one cache line each)
 constexpr size_t kSumsqSinkBytes = (size_t)kSumsqSubs * kSumsqSubStride * 8;
 
@@ -45,34 +45,59 @@ __device__ __forceinline__ int sumsq_acc_add(SumsqAcc& s, unsigned short h) {
   return 0;
 }
 
+// one wavefront's total of a 64-bit value, valid in lane 63: row shifts, then the row broadcasts (data-parallel
+// primitives: a handful of cycles per step instead of a round trip through the LDS crossbar per shuffle)
+__device__ __forceinline__ unsigned long long wave_total_u64(unsigned long long v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  // dpp_ctrl: 0x111.. row_shr:n, 0x142 row_bcast:15, 0x143 row_bcast:31; rows / banks that take part per step as in the
+  // usual reduction (bound_ctrl false: lanes without a source keep adding 0 via the `old` operand)
+#define JZ_DPP_ADD64(ctrl, row_mask)                                                                          \
+  {                                                                                                           \
+    const unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);                                                \
+    const unsigned slo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)lo, ctrl, row_mask, 0xf, false);       \
+    const unsigned shi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)hi, ctrl, row_mask, 0xf, false);       \
+    v += ((unsigned long long)shi << 32) | slo;                                                               \
+  }
+  JZ_DPP_ADD64(0x111, 0xf)  // row_shr:1
+  JZ_DPP_ADD64(0x112, 0xf)  // row_shr:2
+  JZ_DPP_ADD64(0x114, 0xf)  // row_shr:4
+  JZ_DPP_ADD64(0x118, 0xf)  // row_shr:8   -> lane 15 of every row holds the row's total
+  JZ_DPP_ADD64(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+  JZ_DPP_ADD64(0x143, 0xc)  // row_bcast:31 into rows 2 and 3 -> lane 63 holds the wavefront's total
+#undef JZ_DPP_ADD64
+#endif
+  return v;
+}
+
 // Workgroup-wide: adds every thread's sums and contributes them to the sink (or raises its flag when any thread saw a
-// non-finite value: the update is then skipped as a whole and the counters are not touched).  Every thread of the
-// workgroup must call it; `lds` is scratch for 3 * (threads / 64) 64-bit words; at most 2^23 elements per workgroup.
+// non-finite value: the update is then skipped as a whole).  Every thread of the workgroup must call it, after a
+// barrier behind the last use of `lds`; `lds` is scratch for five 64-bit words that the caller has cleared BEFORE that
+// barrier; at most 2^22 elements per workgroup.  No barrier in here: each wavefront adds its totals to the words in LDS
+// and counts itself in, and the wavefront that finds every other one counted carries the digits and contributes.
+// No memory fence either: a fence would make the wavefront wait for the global stores it has just issued (a microsecond
+// or two) before it may count itself in, and it is not needed -- the LDS carries out one wavefront's operations in the
+// order they were issued, so a wavefront's sums are in LDS before its count is; the compiler is kept from reordering
+// the operations by the empty volatile statements.
 __device__ __forceinline__ void sumsq_block_flush(SumsqAcc s, int bad, const SumsqSink& sink, unsigned which,
                                                   unsigned long long* lds) {
-  for (int o = 32; o > 0; o >>= 1) {
-    s.aa += __shfl_down(s.aa, o, 64);
-    s.ab2 += __shfl_down(s.ab2, o, 64);
-    s.bb += __shfl_down(s.bb, o, 64);
-  }
-  bad = __syncthreads_or(bad);
-  const int nw = (int)(blockDim.x >> 6), wv = (int)(threadIdx.x >> 6);
-  if ((threadIdx.x & 63) == 0) {
-    lds[3 * wv + 0] = s.aa;
-    lds[3 * wv + 1] = s.ab2;
-    lds[3 * wv + 2] = s.bb;
-  }
-  __syncthreads();
-  if (threadIdx.x != 0) return;
-  if (bad) {
+  s.aa = wave_total_u64(s.aa);
+  s.ab2 = wave_total_u64(s.ab2);
+  s.bb = wave_total_u64(s.bb);
+  bad = __any(bad);
+  if ((threadIdx.x & 63) != 63) return;
+  const unsigned nw = blockDim.x >> 6;
+  atomicAdd(lds + 0, s.aa);
+  atomicAdd(lds + 1, s.ab2);
+  atomicAdd(lds + 2, s.bb);
+  if (bad) atomicAdd(lds + 3, 1ull);
+  asm volatile("" ::: "memory");
+  const unsigned long long arrived = atomicAdd(lds + 4, 1ull);
+  asm volatile("" ::: "memory");
+  if (arrived != nw - 1) return;
+  unsigned long long aa = atomicAdd(lds + 0, 0ull), ab2 = atomicAdd(lds + 1, 0ull), bb = atomicAdd(lds + 2, 0ull);
+  if (atomicAdd(lds + 3, 0ull) != 0) {
     *sink.nonfinite = 1;
     return;
-  }
-  unsigned long long aa = 0, ab2 = 0, bb = 0;
-  for (int w = 0; w < nw; ++w) {
-    aa += lds[3 * w + 0];
-    ab2 += lds[3 * w + 1];
-    bb += lds[3 * w + 2];
   }
   if ((aa | ab2 | bb) == 0) return;
   // total = aa 2^40 + ab2 2^20 + bb (units of 2^-48), carried into digits d0..d2 < 2^20 and the rest d3

@@ -37,9 +37,10 @@ class ResNet50Chain:
     def __init__(self, batch=64, image=224, variant="v1", seed=180711205, initial_loss_scale=1024.0, hparams=None,
                  policy=None, device="cuda:0", fused=True, block_end=True, proj_side=False, presummed=True):
         """fused: forward convolution + batch normalization as one call (statistics in the convolution's epilogue)
-        instead of two.  presummed: the weight-gradient GEMMs leave each filter gradient's sum of squares in the optimiser's
-        workspace, the remaining tensors' sums are taken behind the last gradient of the backward pass, and the update is one
-        launch (else: the update's own reduce pass reads every gradient again, three launches)."""
+        instead of two.  presummed: the weight-gradient GEMMs whose reduction is split leave their gradient's sum of squares
+        in the optimiser's workspace (from inside the kernel that adds the partial sums), the remaining tensors' sums are
+        taken by one launch behind the last gradient of the backward pass, and the update is one launch (else: the update's
+        own reduce pass reads every gradient again, three launches)."""
         self.presummed = bool(presummed)
         self.N, self.image, self.device, self.fused = int(batch), int(image), torch.device(device), bool(fused)
         self.block_end = bool(block_end) and self.fused
@@ -55,13 +56,20 @@ class ResNet50Chain:
         host = inputs.resnet50_param_set(loss_scale=1.0, seed_key=(seed % 1000003,), variant=variant)
         self.tensors = shapes.resnet50_param_tensors(variant)
         self.offsets = [int(o) for o in host.offsets]
-        self.flags = [int(x) | (api.JZ_PARAM_GRAD_PRESUMMED if self.presummed and kind in ("conv", "fc") else 0)
-                      for x, (_, _, kind, _) in zip(host.flags, self.tensors)]
+        self.flags = [int(x) for x in host.flags]
+        self.index = {name: i for i, (name, _, _, _) in enumerate(self.tensors)}
+        if self.presummed:      # filters whose weight-gradient reduction is split: their producer supplies the sum of squares
+            for cs in self.convs:
+                d = api.conv_desc(self.N, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+                if ", 1 splits" not in api.jz_conv2d_describe_plan(api.JZ_BWD_WEIGHT, d):
+                    self.flags[self.index[cs.name + ".w"]] |= api.JZ_PARAM_GRAD_PRESUMMED
+            d = api.conv_desc(self.N, 1, 1, self.fc.I, self.fc.O, 1, 1)
+            if ", 1 splits" not in api.jz_conv2d_describe_plan(api.JZ_BWD_WEIGHT, d):
+                self.flags[self.index["fc.w"]] |= api.JZ_PARAM_GRAD_PRESUMMED
         self.master = torch.from_numpy(host.master_w).to(dev)
         self.momentum = torch.zeros_like(self.master)
         self.w16 = self.master.to(h)
         self.grad = torch.zeros(self.master.numel(), dtype=h, device=dev)
-        self.index = {name: i for i, (name, _, _, _) in enumerate(self.tensors)}
         self.ps = api.ParamSet(self.offsets, self.flags, self.master, self.momentum, self.grad, self.w16)
         self.lars_ws = torch.zeros(max(api.jz_lars_workspace_bytes(self.ps), 16), dtype=torch.uint8, device=dev)
         api.jz_lars_prepare(self.ps, self.lars_ws)
@@ -116,7 +124,7 @@ class ResNet50Chain:
         self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_workspace_bytes(op, d))
         kind = {api.JZ_FWD: "conv_fwd", api.JZ_BWD_DATA: "conv_bwd_data", api.JZ_BWD_WEIGHT: "conv_bwd_weight"}[op]
         bind = lambda ws: api.bind_conv2d(op, d, a, b, out, ws)
-        if op == api.JZ_BWD_WEIGHT and self.presummed:
+        if op == api.JZ_BWD_WEIGHT and self.presummed and self.flags[self.index[name + ".w"]] & api.JZ_PARAM_GRAD_PRESUMMED:
             sink = api.jz_lars_sumsq_sink(self.ps, self.lars_ws, self.index[name + ".w"])
             bind = lambda ws: api.bind_conv2d_bwd_weight_sumsq(d, a, b, out, sink, ws)
         o = Op(kind, name, dict(desc=d), [a, b], [out], self._later(bind), bind)
@@ -129,7 +137,7 @@ class ResNet50Chain:
         self._ws_bytes = max(self._ws_bytes, api.jz_gemm_fc_workspace_bytes(mode, B, I, O))
         kind = {api.JZ_FWD: "fc_fwd", api.JZ_BWD_DATA: "fc_bwd_data", api.JZ_BWD_WEIGHT: "fc_bwd_weight"}[mode]
         bind = lambda ws: api.bind_gemm_fc(mode, B, I, O, a, b, out, ws)
-        if mode == api.JZ_BWD_WEIGHT and self.presummed:
+        if mode == api.JZ_BWD_WEIGHT and self.presummed and self.flags[self.index[name + ".w"]] & api.JZ_PARAM_GRAD_PRESUMMED:
             sink = api.jz_lars_sumsq_sink(self.ps, self.lars_ws, self.index[name + ".w"])
             bind = lambda ws: api.bind_gemm_fc_bwd_weight_sumsq(B, I, O, a, b, out, sink, ws)
         o = Op(kind, name, dict(B=B, I=I, O=O), [a, b], [out], self._later(bind), bind)

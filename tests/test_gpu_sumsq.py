@@ -29,10 +29,10 @@ def jz():
 
 
 def new_sink(jz):
-    # 2048 bytes, 128-byte aligned: a slice of a larger allocation that starts on such a boundary
-    raw = torch.zeros(256 + 16, dtype=torch.int64, device="cuda")
+    # 8192 bytes, 128-byte aligned: a slice of a larger allocation that starts on such a boundary
+    raw = torch.zeros(1024 + 16, dtype=torch.int64, device="cuda")
     skip = (-raw.data_ptr() // 8) % 16
-    sums = raw[skip:skip + 256]
+    sums = raw[skip:skip + 1024]
     assert sums.data_ptr() % 128 == 0
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
     return jz.sumsq_sink(sums, flag), sums, flag, raw
@@ -140,7 +140,7 @@ def test_grad_sumsq_fills_the_workspace_sinks(jz):
         sink = jz.jz_lars_sumsq_sink(r.ps, r.ws, t)
         base = sink.sums - r.ws.data_ptr()
         assert base % 128 == 0
-        sums = r.ws[base:base + 2048].view(torch.int64)
+        sums = r.ws[base:base + jz.JZ_SUMSQ_SINK_BYTES].view(torch.int64)
         fl = int(r.ws[sink.nonfinite - r.ws.data_ptr():sink.nonfinite - r.ws.data_ptr() + 4].view(torch.int32).item())
         g = ps.grad16[off[t]:off[t + 1]]
         assert fl == (1 if t == 1 else 0)
@@ -152,7 +152,7 @@ def test_grad_sumsq_fills_the_workspace_sinks(jz):
     for t in range(len(sizes)):
         sink = jz.jz_lars_sumsq_sink(r.ps, r.ws, t)
         base = sink.sums - r.ws.data_ptr()
-        assert int(r.ws[base:base + 2048].view(torch.int64).abs().sum().item()) == 0
+        assert int(r.ws[base:base + jz.JZ_SUMSQ_SINK_BYTES].view(torch.int64).abs().sum().item()) == 0
 
 
 def test_update_from_sinks_filled_by_the_producing_kernels(jz):
