@@ -311,6 +311,7 @@ def per_layer_report(wl, iters=20, out_path=None, peak=FP16_MFMA_PEAK_TFLOPS):
         return warm, cold
 
     lines = ["# per-layer, per-op timing of the %s step (ResNet-50 v1, N = %d): every launch alone on an idle GPU" % ("fp32" if wl.f32 else "fp16", wl.N),
+             "# command: python3 " + " ".join(sys.argv),
              "# us warm = mean of %d back-to-back launches; us cold = fastest of 3 launches behind a 768 MB cache flush;" % iters,
              "# roofline = min(%.1f TFLOP/s, flop / (bytes of both inputs + output) * 8 TB/s); frac = warm TFLOP/s / roofline;" % peak,
              "# us@roof = the time that roofline allows; plan = the library's kernel choice (jz_conv2d_describe_plan)",

@@ -31,9 +31,10 @@ constexpr int BK = 64;  // k tile depth of the element-wise kernel
 // (w'[k][r][4 s + c], zeros elsewhere); for backward-weight the GEMM produces dw' in that layout and the real
 // entries are copied out.
 
-// One launch does both copies.  Slices z < N of the grid: a workgroup of 128 threads covers 256 padded pixels of image
-// row (z, y), two per thread (one 16-byte store; Wp is even).  Slice z = N (present when wp != nullptr) repacks the
+// One launch does both copies.  Slices z < N of the grid: a workgroup of 128 threads covers 256 padded pixels of the
+// PAD_ROWS image rows (z, PAD_ROWS y ...), two pixels per thread and row (one 16-byte store; Wp is even).  Slice z = N (present when wp != nullptr) repacks the
 // filter: w[K][R][S][C] -> wp[K][R][KT] with wp[k][r][4 s + c] = w[k][r][s][c], zero elsewhere.
+constexpr int PAD_ROWS = 4;
 __global__ __launch_bounds__(128) void pad_to_c4(const unsigned short* __restrict__ x, unsigned short* __restrict__ xp,
                                                  int N, int H, int W, int C, int Hp, int Wp, int ph, int pw,
                                                  const unsigned short* __restrict__ w, unsigned short* __restrict__ wp,
@@ -49,26 +50,37 @@ __global__ __launch_bounds__(128) void pad_to_c4(const unsigned short* __restric
     }
     return;
   }
-  const int hp = blockIdx.y;
+  // PAD_ROWS image rows per workgroup: every load of a thread's rows is in flight before the first store
   const int wp0 = 2 * (blockIdx.x * 128 + threadIdx.x);
   if (wp0 >= Wp) return;
-  const int h = hp - ph;
-  unsigned short v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if ((unsigned)h < (unsigned)H) {
-    const unsigned short* row = x + ((size_t)z * H + h) * W * C;
+  unsigned short v[PAD_ROWS][8];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int wi = wp0 + p - pw;
-      if ((unsigned)wi < (unsigned)W) {
+  for (int rr = 0; rr < PAD_ROWS; ++rr) {
+    const int hp = blockIdx.y * PAD_ROWS + rr;
+    const int h = hp - ph;
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (c < C) v[4 * p + c] = row[(size_t)wi * C + c];
+    for (int e = 0; e < 8; ++e) v[rr][e] = 0;
+    if (hp < Hp && (unsigned)h < (unsigned)H) {
+      const unsigned short* row = x + ((size_t)z * H + h) * W * C;
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        const int wi = wp0 + p - pw;
+        if ((unsigned)wi < (unsigned)W) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (c < C) v[rr][4 * p + c] = row[(size_t)wi * C + c];
+        }
       }
     }
   }
-  uint4 pk = make_uint4((unsigned)v[0] | ((unsigned)v[1] << 16), (unsigned)v[2] | ((unsigned)v[3] << 16),
-                        (unsigned)v[4] | ((unsigned)v[5] << 16), (unsigned)v[6] | ((unsigned)v[7] << 16));
-  *reinterpret_cast<uint4*>(xp + (((size_t)z * Hp + hp) * Wp + wp0) * 4) = pk;
+#pragma unroll
+  for (int rr = 0; rr < PAD_ROWS; ++rr) {
+    const int hp = blockIdx.y * PAD_ROWS + rr;
+    if (hp >= Hp) break;
+    uint4 pk = make_uint4((unsigned)v[rr][0] | ((unsigned)v[rr][1] << 16), (unsigned)v[rr][2] | ((unsigned)v[rr][3] << 16),
+                          (unsigned)v[rr][4] | ((unsigned)v[rr][5] << 16), (unsigned)v[rr][6] | ((unsigned)v[rr][7] << 16));
+    *reinterpret_cast<uint4*>(xp + (((size_t)z * Hp + hp) * Wp + wp0) * 4) = pk;
+  }
 }
 
 // dwp[K][R][KT] -> dw[K][R][S][C]
@@ -577,7 +589,7 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     unsigned short* wp = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + pl.xp_bytes);
     const unsigned short* x = static_cast<const unsigned short*>(op == JZ_FWD ? A : B);
     const unsigned short* wsrc = op == JZ_FWD ? static_cast<const unsigned short*>(B) : nullptr;
-    hipLaunchKernelGGL(pad_to_c4, dim3((unsigned)((pl.Wp / 2 + 127) / 128), (unsigned)pl.Hp, (unsigned)(d->N + (wsrc ? 1 : 0))),
+    hipLaunchKernelGGL(pad_to_c4, dim3((unsigned)((pl.Wp / 2 + 127) / 128), (unsigned)((pl.Hp + PAD_ROWS - 1) / PAD_ROWS), (unsigned)(d->N + (wsrc ? 1 : 0))),
                        dim3(128), 0, st, x, xp, d->N, d->H, d->W, d->C, pl.Hp, pl.Wp, d->pad_h, d->pad_w, wsrc,
                        wsrc ? wp : nullptr, d->K, d->R, d->S, pl.KT);
     if (op == JZ_FWD) {
