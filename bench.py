@@ -279,13 +279,24 @@ class ResNet50Step:
         api.jz_lars_prepare(self.ps, self.lars_ws)   # the master weights were written from outside: drop the carried sums
 
 
+class _LayerView:
+    """What per_layer_report needs of a workload that is not a ResNet50Step: the layer records, how to bind a call."""
+
+    def __init__(self, layers, bound, ws, N, dev, title):
+        self.layers, self._bound_fn, self.ws, self.N, self.dev, self.title, self.f32, self.fc = layers, bound, ws, N, dev, title, False, None
+
+    def _bound(self, L, op, ws):
+        return self._bound_fn(L, op, ws)
+
+
 def per_layer_report(wl, iters=20, out_path=None, peak=FP16_MFMA_PEAK_TFLOPS):
     """Time every launch of the step on its own (HIP events) and print one line per layer and op: time warm (`iters`
     back-to-back repeats) and cold (caches flushed by a 768 MB read before each of three launches, the fastest: inside
     the step every layer finds its operands cold), TFLOP/s, the layer's own roofline min(matrix peak, flop / compulsory
     bytes * HBM peak), the fraction of it reached (warm), and the kernel plan.  Compulsory bytes = both inputs read
     once + the output written once.  Returns the rows as dicts; out_path: also written there as a text table."""
-    B, I, O = wl.N, wl.fc.I, wl.fc.O
+    B = wl.N
+    title = getattr(wl, "title", "ResNet-50 v1")
     rows = []
     junk = torch.zeros(192 << 20, dtype=torch.float32, device=wl.dev)
     esz = 4 if wl.f32 else 2
@@ -310,7 +321,7 @@ def per_layer_report(wl, iters=20, out_path=None, peak=FP16_MFMA_PEAK_TFLOPS):
             cold = min(cold, e0.elapsed_time(e1))
         return warm, cold
 
-    lines = ["# per-layer, per-op timing of the %s step (ResNet-50 v1, N = %d): every launch alone on an idle GPU" % ("fp32" if wl.f32 else "fp16", wl.N),
+    lines = ["# per-layer, per-op timing of the %s step (%s, N = %d): every launch alone on an idle GPU" % ("fp32" if wl.f32 else "fp16", title, wl.N),
              "# command: python3 " + " ".join(sys.argv),
              "# us warm = mean of %d back-to-back launches; us cold = fastest of 3 launches behind a 768 MB cache flush;" % iters,
              "# roofline = min(%.1f TFLOP/s, flop / (bytes of both inputs + output) * 8 TB/s); frac = warm TFLOP/s / roofline;" % peak,
@@ -323,6 +334,7 @@ def per_layer_report(wl, iters=20, out_path=None, peak=FP16_MFMA_PEAK_TFLOPS):
             macs = d.N * d.P * d.Q * d.K * d.R * d.S * d.C
             desc = "%dx%d %d->%d %dx%d s%d" % (d.H, d.W, d.C, d.K, d.R, d.S, d.stride_h)
         else:
+            I, O = (L["I"], L["O"]) if "I" in L else (wl.fc.I, wl.fc.O)
             d = api.conv_desc(B, 1, 1, I, O, 1, 1)
             macs = B * I * O
             desc = "fc %d->%d" % (I, O)
@@ -390,6 +402,9 @@ def alexnet_workload(args):
         a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("dy", "x", "dw")}[op]
         return api.bind_gemm_fc(op, B, L["I"], L["O"], L[a], L[b], L[o], ws)
 
+    rows = None
+    if args.per_layer or args.per_layer_file:
+        rows = per_layer_report(_LayerView(layers, bound, wss[0], B, dev, "AlexNet-shaped layers"), out_path=args.per_layer_file)
     prog = [("launch", bound(L, api.JZ_FWD, wss[0]), 0) for L in layers]
     ready = torch.cuda.Event()
     prog.append(("record", ready, 0))
@@ -435,7 +450,7 @@ def alexnet_workload(args):
     ms = wall * 1e3 / args.steps
     tflops = flops / (e0.elapsed_time(e1) / args.steps * 1e-3) / 1e12
     n_launch = sum(1 for e in prog if e[0] == "launch")
-    print(json.dumps({
+    out = {
         "metric": "AlexNet-shaped layers N=%d fp16 fwd+bwd images/s" % B, "value": B / (ms * 1e-3), "unit": "images/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
@@ -443,7 +458,12 @@ def alexnet_workload(args):
                                "independent seeded N(0,1) inputs", "batch": B, "launch": "eager", "streams": args.streams},
         "roofline": {"kernel": "igemm_kernel (all %d conv/FC launches of a step)" % n_launch, "bound": "mfma", "achieved": tflops,
                      "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / FP16_MFMA_PEAK_TFLOPS, "traffic": None,
-                     "flop_per_step": flops}}))
+                     "flop_per_step": flops}}
+    if rows is not None:
+        worst = sorted(rows, key=lambda r: r["us"] - r["us_roofline"], reverse=True)[:10]
+        out["per_layer_worst"] = [{k: r[k] for k in ("layer", "shape", "op", "us", "us_roofline", "tflops", "roofline_tflops", "frac", "plan")}
+                                  for r in worst]
+    print(json.dumps(out))
 
 
 def bn_workload(args):

@@ -528,9 +528,9 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_update(Tables tb, float* __
   f = __any(f);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *found_inf = f ? 1 : 0;
-    // psum_w describes the master weights as this launch leaves them: always when lars_reduce filled it in beforehand;
-    // on the presummed path only once an update has gone through (a skipped one writes no partial sums)
-    if (!PRE || !f) tb.state[0] = 1;
+    // skipped or not, psum_w describes the master weights as this launch leaves them: lars_reduce / lars_begin filled it in
+    // for the weights as they were, and an update that goes through rewrites every chunk's sums
+    tb.state[0] = 1;
     if (dyn.st) loss_scale_step(dyn, f);  // no workgroup of this launch reads dyn.st->scale
   }
   if (f) return;  // overflow under loss scaling: the step is skipped as a whole
