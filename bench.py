@@ -692,8 +692,8 @@ def measured_traffic(wl):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=None, help="default: 64 (resnet50), 128 (alexnet)")
     ap.add_argument("--workload", default="resnet50", choices=("resnet50", "alexnet", "bn", "chain"),
                     help="resnet50: the full step the headline metric is quoted on; alexnet: the AlexNet-shaped layers of configs[3]; "
@@ -799,6 +799,9 @@ def main():
         "pct_fp16_mfma_peak": 100.0 * (wl.flops / (ms_per_step * 1e-3) / 1e12) / FP16_MFMA_PEAK_TFLOPS,
         "roofline": {"kernel": "%s (all %d conv/FC launches of a step)" % ("igemm_f32_kernel" if wl.f32 else "igemm_dma_kernel", n_gemm),
                      "bound": "mfma", "achieved": tflops, "peak": peak, "unit": "TFLOP/s", "frac": tflops / peak,
+                     "peak_note": ("dense FP32 MFMA: 256 CU x 4 SIMD x 64 flop/clk (v_mfma_f32_32x32x2_f32) x 2.4 GHz = 157.3 TFLOP/s" if wl.f32 else
+                                   "dense FP16 MFMA, the published 2.5 PFLOP/s: 256 CU x 4 SIMD x 1024 flop/clk (v_mfma_f32_32x32x16_f16) x 2.4 GHz = 2.52; "
+                                   "a loop of nothing but MFMAs sustains 1.94 on this chip (effective clock 1.85 GHz)"),
                      "traffic": traffic["bytes"] if traffic else None,
                      "traffic_note": (traffic["note"] if traffic else "no HBM-counter summary under profiles/ matches this run's kernel plans") +
                                      "; algorithmic 2(|x|+|w|+|y|) per pass is 7.99e9 at fp16 storage",
