@@ -528,7 +528,7 @@ def chain_workload(args):
     from paper_1807_11205_amd import resnet50
     net = resnet50.ResNet50Chain(batch=args.batch, image=224, initial_loss_scale=65536.0,
                                  policy=dict(growth_interval=1 << 30, max_scale=2.0 ** 24), fused=not args.unfused,
-                                 block_end=not args.no_block_end)
+                                 block_end=not args.no_block_end, bwd_stats=not args.no_bwd_stats)
     skipped = 0
     for _ in range(24):                                   # let the controller bring the scale down until steps go through
         net.step()
@@ -717,6 +717,8 @@ def main():
                     "for the projection shortcuts (forward) and the backward-weight launches (at most 4)")
     ap.add_argument("--graph", type=int, default=0, help="replay the step from a HIP graph (1) or launch eagerly (0); eager launches measured faster here")
     ap.add_argument("--no-block-end", action="store_true", help="chain workload: ReLU gradient and batch-norm backward at a block's end as two calls")
+    ap.add_argument("--no-bwd-stats", action="store_true",
+                    help="chain workload: backward-data convolution and the batch-norm backward underneath it as two calls")
     ap.add_argument("--unfused", action="store_true", help="chain workload: convolution and batch normalization as two calls")
     ap.add_argument("--dynamic-loss-scale", action="store_true",
                     help="time jz_lars_mp_update_dyn (loss scale and its controller on the device) instead of jz_lars_mp_update")

@@ -271,6 +271,24 @@ int jz_lars_mp_update_presummed_dyn(const jz_param_set* ps, const jz_lars_hparam
                                     jz_loss_scale_state* state_dev, int* found_inf_dev, void* ws, size_t ws_bytes,
                                     void* hip_stream);
 
+/* Backward-data of a convolution together with the backward pass of the batch normalization + ReLU that produced the
+ * convolution's input (Section 4.2's layer; the counterpart of jz_conv2d_bn_relu_fwd):  y = relu(bn(c)) was the input of
+ * this convolution in the forward pass.  One call computes
+ *   dz      = jz_conv2d_bwd_data(desc, dy16, w16)              the gradient w.r.t. y, [N,H,W,C]
+ *   dc, dgamma, dbeta = jz_bn_relu_bwd(rows = N*H*W, C, x = bn_x16 (= c), y = bn_y16, dy = dz, relu = 1)
+ * with the statistics of the normalization's backward (sum g, sum g x^ over g = dz where y > 0) taken in the
+ * convolution's epilogue, while the dz tile is on chip, when the convolution's kernel allows it (not split, unit stride
+ * or no scatter form, C a multiple of 8); otherwise the statistics pass runs as in jz_bn_relu_bwd.  dz16 holds the same
+ * bits as from jz_conv2d_bwd_data; bn_dx16 / dgamma16 / dbeta16 meet jz_bn_relu_bwd's within the rounding of FP32 sums
+ * taken in another (fixed, deterministic) order.  bn_y16 is the tensor the forward pass fed to this convolution; bn_x16
+ * the normalization's input; gamma, save_mean, save_invstd as for jz_bn_relu_bwd.  Outputs must not overlap anything.
+ * Workspace: jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes.  Status codes as for the two calls it replaces. */
+int jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(const jz_conv_desc* desc, size_t* bytes);
+int jz_conv2d_bwd_data_bn_relu_bwd(const jz_conv_desc* desc, const void* dy16, const void* w16, const void* bn_x16,
+                                   const void* bn_y16, const float* gamma, const float* save_mean, const float* save_invstd,
+                                   void* dz16, void* bn_dx16, void* dgamma16, void* dbeta16, void* ws, size_t ws_bytes,
+                                   void* hip_stream);
+
 /* The backward pass at the end of a residual block, y_out = relu(bn(x) + shortcut), in one call: the gradient of the sum,
  * g = RNE16(dya [+ dyb]) where y_out > 0 and 0 elsewhere (dyb may be NULL; two contributions arrive when the block above
  * has two consumers of y_out), is formed inside the statistics pass of the batch-norm backward and written to g16 for

@@ -574,3 +574,100 @@ extern "C" int jz_conv2d_bn_relu_fwd(const jz_conv_desc* desc, const void* x16, 
                        n_chunks, C, p.bn.cpr, relu ? 1 : 0);
   return jz::launch_status();
 }
+
+// ---- backward-data of a convolution + the backward pass of the batch normalization + ReLU that produced its input ----
+// The statistics pass of the normalization's backward (sum g, sum g x^ over g = dz where y > 0) reads dz, y and x; here
+// the convolution's epilogue takes the sums while the dz tile is still on chip (it reads the matching y and x tiles), so
+// that pass and its launch disappear.
+namespace {
+
+struct ConvBnBwdPlan {
+  BnPlan bn;            // of the normalization: rows = N*H*W of the convolution's input, C = its channels
+  size_t conv_ws = 0;
+  int tiles_m = 0;      // > 0: the convolution kernel leaves [tiles_m][2][C] sums; 0: the statistics pass runs
+  size_t off_bn = 0, total = 0;
+};
+
+int make_conv_bn_bwd_plan(const jz_conv_desc* d, ConvBnBwdPlan* p) {
+  int rc = jz::conv_bwd_data_stats_plan(d, &p->conv_ws, &p->tiles_m);
+  if (rc != JZ_OK) return rc;
+  rc = make_bn_plan((int64_t)d->N * d->H * d->W, d->C, &p->bn);
+  if (rc != JZ_OK) return rc;
+  const int slabs = p->tiles_m > p->bn.slabs ? p->tiles_m : p->bn.slabs;
+  p->off_bn = up256(p->conv_ws);
+  p->bn.off_part = 0;
+  p->bn.off_coef = up256((size_t)slabs * 2 * d->C * sizeof(float));
+  p->bn.total = p->bn.off_coef + up256((size_t)4 * d->C * sizeof(float));
+  p->total = p->off_bn + p->bn.total;
+  return JZ_OK;
+}
+
+}  // namespace
+
+extern "C" int jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(const jz_conv_desc* desc, size_t* bytes) {
+  if (!bytes) return JZ_ERR_NULL;
+  ConvBnBwdPlan p;
+  int rc = make_conv_bn_bwd_plan(desc, &p);
+  if (rc != JZ_OK) return rc;
+  *bytes = p.total;
+  return JZ_OK;
+}
+
+extern "C" int jz_conv2d_bwd_data_bn_relu_bwd(const jz_conv_desc* desc, const void* dy16, const void* w16, const void* bn_x16,
+                                              const void* bn_y16, const float* gamma, const float* save_mean,
+                                              const float* save_invstd, void* dz16, void* bn_dx16, void* dgamma16, void* dbeta16,
+                                              void* ws, size_t ws_bytes, void* hip_stream) {
+  ConvBnBwdPlan p;
+  int rc = make_conv_bn_bwd_plan(desc, &p);
+  if (rc != JZ_OK) return rc;
+  if (!dy16 || !w16 || !bn_x16 || !bn_y16 || !gamma || !save_mean || !save_invstd || !dz16 || !bn_dx16 || !dgamma16 || !dbeta16)
+    return JZ_ERR_NULL;
+  if (!ws || ws_bytes < p.total) return JZ_ERR_WORKSPACE;
+  if (!jz::aligned16(bn_x16) || !jz::aligned16(bn_y16) || !jz::aligned16(bn_dx16) || !jz::aligned16(ws) || !jz::aligned16(gamma) ||
+      !jz::aligned16(save_mean) || !jz::aligned16(save_invstd))
+    return JZ_ERR_ALIGN;
+  const int64_t rows = p.bn.rows;
+  const int C = p.bn.C;
+  const size_t nb = (size_t)rows * C * 2, nh = (size_t)C * 2, nc = (size_t)C * 4;
+  const int P = (desc->H + 2 * desc->pad_h - desc->R) / desc->stride_h + 1, Q = (desc->W + 2 * desc->pad_w - desc->S) / desc->stride_w + 1;
+  const size_t ny = (size_t)desc->N * P * Q * desc->K * 2, nw = (size_t)desc->K * desc->R * desc->S * desc->C * 2;
+  // outputs against everything else (the convolution's own checks cover dy, w, dz and its part of the workspace)
+  const void* outs[4] = {dz16, bn_dx16, dgamma16, dbeta16};
+  const size_t outn[4] = {nb, nb, nh, nh};
+  const void* ins[7] = {dy16, w16, bn_x16, bn_y16, gamma, save_mean, save_invstd};
+  const size_t inn[7] = {ny, nw, nb, nb, nc, nc, nc};
+  for (int i = 0; i < 4; ++i) {
+    for (int j = 0; j < 7; ++j)
+      if (jz::overlaps(outs[i], outn[i], ins[j], inn[j])) return JZ_ERR_ALIAS;
+    for (int j = i + 1; j < 4; ++j)
+      if (jz::overlaps(outs[i], outn[i], outs[j], outn[j])) return JZ_ERR_ALIAS;
+    if (jz::overlaps(outs[i], outn[i], ws, p.total)) return JZ_ERR_ALIAS;
+  }
+  for (int j = 0; j < 7; ++j)
+    if (jz::overlaps(ins[j], inn[j], ws, p.total)) return JZ_ERR_ALIAS;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* bws = static_cast<char*>(ws) + p.off_bn;
+  float* part = reinterpret_cast<float*>(bws + p.bn.off_part);
+  float* coef = reinterpret_cast<float*>(bws + p.bn.off_coef);
+  const jz::BnBwdOperands bn{bn_x16, bn_y16, save_mean, save_invstd};
+  rc = jz::conv_bwd_data_run(desc, dy16, w16, dz16, ws, p.conv_ws, p.tiles_m > 0 ? part : nullptr, p.tiles_m, &bn, hip_stream);
+  if (rc != JZ_OK) return rc;
+  const uint4* x = static_cast<const uint4*>(bn_x16);
+  const uint4* y = static_cast<const uint4*>(bn_y16);
+  const uint4* dz = static_cast<const uint4*>(dz16);
+  int slabs = p.tiles_m;
+  if (slabs == 0) {  // this convolution kernel cannot leave the sums: the statistics pass over dz, y and x
+    slabs = p.bn.slabs;
+    hipLaunchKernelGGL(bn_stats<1>, dim3((unsigned)(slabs * p.bn.csplit)), dim3(BN_THREADS), 0, st, x, y, dz, save_mean, save_invstd, part,
+                       rows, C, p.bn.cpr, p.bn.rpp, p.bn.rows_per_slab, 1, p.bn.csplit);
+    if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  }
+  hipLaunchKernelGGL(bn_bwd_final, dim3((unsigned)((C + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part, slabs, C,
+                     1.0 / (double)rows, gamma, save_mean, save_invstd, static_cast<unsigned short*>(dgamma16),
+                     static_cast<unsigned short*>(dbeta16), coef);
+  if ((rc = jz::launch_status()) != JZ_OK) return rc;
+  const int64_t n_chunks = rows * p.bn.cpr;
+  hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, y, dz, static_cast<uint4*>(bn_dx16), coef,
+                     n_chunks, C, p.bn.cpr, 1);
+  return jz::launch_status();
+}

@@ -557,16 +557,22 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
 bool plan_leaves_stats(const Plan& pl) {
   return pl.op == JZ_FWD && pl.fast && pl.args.splits == 1;
 }
+// a backward-data plan whose kernel can leave the sums of a batch-norm backward: the ring kernels with masks, no split,
+// no scatter epilogue, whole 16-byte pieces of a row
+bool plan_leaves_bwd_stats(const Plan& pl) {
+  return pl.op == JZ_BWD_DATA && pl.fast && !pl.gen && pl.args.splits == 1 && !pl.args.sc_on && (pl.args.N & 7) == 0;
+}
 
 // A, B in the kernel's order: FWD (x, w), BWD_DATA (dy, w), BWD_WEIGHT (dy, x)
 int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, void* ws, size_t ws_bytes, void* stream,
-        float* stats = nullptr, int stats_tiles_m = 0, const jz::SumsqSink* sink = nullptr) {
+        float* stats = nullptr, int stats_tiles_m = 0, const jz::SumsqSink* sink = nullptr, const jz::BnBwdOperands* bn = nullptr) {
   Plan pl;
   int rc = make_plan(op, d, &pl);
   if (rc != JZ_OK) return rc;
   // the caller sized the buffer of the column sums from an earlier plan: it has to be this plan (the run-time tuning table
   // may have been changed in between)
-  if (stats && (!plan_leaves_stats(pl) || pl.args.tiles_m != stats_tiles_m)) return JZ_ERR_UNSUPPORTED;
+  if (stats && !(op == JZ_BWD_DATA ? plan_leaves_bwd_stats(pl) && bn != nullptr : plan_leaves_stats(pl))) return JZ_ERR_UNSUPPORTED;
+  if (stats && pl.args.tiles_m != stats_tiles_m) return JZ_ERR_UNSUPPORTED;
   if (!A || !B || !D) return JZ_ERR_NULL;
   if (!aligned16(A) || !aligned16(B) || !aligned16(D) || (ws && !aligned16(ws))) return JZ_ERR_ALIGN;
   if (overlaps(D, pl.bytesD, A, pl.bytesA) || overlaps(D, pl.bytesD, B, pl.bytesB)) return JZ_ERR_ALIAS;
@@ -583,6 +589,14 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
   a.bytesB = (unsigned)pl.bytesB;
   a.Dpart = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_offset);
   a.stats = stats;
+  a.st_y = a.st_c = nullptr;
+  a.st_mean = a.st_invstd = nullptr;
+  if (stats && op == JZ_BWD_DATA) {
+    a.st_y = static_cast<const unsigned short*>(bn->y16);
+    a.st_c = static_cast<const unsigned short*>(bn->x16);
+    a.st_mean = bn->mean;
+    a.st_invstd = bn->invstd;
+  }
   unsigned short* dwp = nullptr;
   if (pl.packed) {
     unsigned short* xp = static_cast<unsigned short*>(ws);
@@ -603,7 +617,7 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
   }
   if (op == JZ_FWD) rc = stats ? launch_fwd_stats(pl, st) : launch_fwd(pl, st);
-  else if (op == JZ_BWD_DATA) rc = launch_bwd_data(pl, st);
+  else if (op == JZ_BWD_DATA) rc = stats ? launch_bwd_data_stats(pl, st) : launch_bwd_data(pl, st);
   else rc = launch_bwd_weight(pl, st);
   if (rc != JZ_OK) return rc;
   if (a.splits > 1) {
@@ -659,6 +673,18 @@ int jz::conv_fwd_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* t
 int jz::conv_fwd_run(const jz_conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, float* stats,
                      int stats_tiles_m, void* stream) {
   return run(JZ_FWD, d, x, w, y, ws, ws_bytes, stream, stats, stats_tiles_m);
+}
+int jz::conv_bwd_data_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* tiles_m) {
+  Plan pl;
+  int rc = make_plan(JZ_BWD_DATA, d, &pl);
+  if (rc != JZ_OK) return rc;
+  *conv_ws_bytes = pl.ws_bytes;
+  *tiles_m = plan_leaves_bwd_stats(pl) ? pl.args.tiles_m : 0;
+  return JZ_OK;
+}
+int jz::conv_bwd_data_run(const jz_conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, float* stats,
+                          int stats_tiles_m, const BnBwdOperands* bn, void* stream) {
+  return run(JZ_BWD_DATA, d, dy, w, dx, ws, ws_bytes, stream, stats, stats_tiles_m, nullptr, bn);
 }
 
 extern "C" int jz_conv2d_workspace_bytes(int op, const jz_conv_desc* desc, size_t* bytes) {

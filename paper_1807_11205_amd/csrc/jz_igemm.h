@@ -17,7 +17,8 @@
 namespace jz {
 
 enum { OP_FWD = 0, OP_BWD_DATA = 1, OP_BWD_WEIGHT = 2,
-       OP_FWD_STATS = 3 };  // forward whose epilogue also leaves per-tile column sums (kernel template argument only)
+       OP_FWD_STATS = 3,        // forward whose epilogue also leaves per-tile column sums (kernel template arguments only)
+       OP_BWD_DATA_STATS = 4 }; // backward-data whose epilogue also leaves the sums a batch-norm backward needs
 
 // Division by a run-time constant through multiply-high (Granlund-Montgomery style), exact for n < 2^31.
 struct FastDiv {
@@ -58,6 +59,13 @@ struct GemmArgs {
   unsigned short* D16;  // [M][N] fp16, written when splits == 1
   float* Dpart;         // [splits][M][N] fp32 partial sums, written when splits > 1
   float* stats;         // optional, splits == 1 only: [tiles_m][2][N] column sums of the stored FP16 tile and of its squares
+                        // (OP_FWD_STATS), or of g and g x^ (OP_BWD_DATA_STATS) with g = the stored gradient where st_y > 0,
+                        // else 0, and x^ = (st_c - st_mean) st_invstd: the batch normalization + ReLU that produced the
+                        // convolution's input, st_c its input and st_y its output, both [M][N] like D16
+  const unsigned short* st_y;
+  const unsigned short* st_c;
+  const float* st_mean;
+  const float* st_invstd;
   unsigned bytesA, bytesB;  // sizes of the A / B tensors: the bounds of their buffer descriptors
   int M, N, Kred;
   int nkt;           // number of k tiles = ceil(Kred / BK)

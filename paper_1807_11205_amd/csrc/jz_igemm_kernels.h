@@ -92,7 +92,7 @@ constexpr int fp32_slabs(int bm, int bn, int wtm, int lds_bytes) {
   return 0;
 }
 
-template <int BM, int BN, int TM, int TN, int NTHREADS, int EPASS = 1, int LDS_BYTES = 0, bool STATS = false>
+template <int BM, int BN, int TM, int TN, int NTHREADS, int EPASS = 1, int LDS_BYTES = 0, int STATS = 0>
 __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&acc)[TM][TN], unsigned short* lds, int m0,
                                                     int n0, int split, int tid, int lane, int wrow, int wcol) {
   // ---- epilogue ------------------------------------------------------------------------------
@@ -171,13 +171,26 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
   static_assert(RPB % CRPP == 0, "slab rows must divide among the store passes");
   const int cch = tid % CCH, crow = tid / CCH;
   const bool nvec = (a.N & 7) == 0;
-  // optional per-tile column sums of what is stored (for a batch normalization behind a forward convolution): a thread
-  // stores the same 8 columns of every row it handles, so it keeps their sums; they are combined below
-  // (a template argument: as a run-time branch in every kernel it cost the step 5 %)
+  // optional per-tile column sums: a thread stores the same 8 columns of every row it handles, so it keeps their sums;
+  // they are combined below (a template argument: as a run-time branch in every kernel it cost the step 5 %).
+  // STATS 1 (a batch normalization behind a forward convolution): sums of what is stored and of its squares.
+  // STATS 2 (backward-data of a convolution whose input came out of batch normalization + ReLU): the sums that layer's
+  // backward pass needs, sum g and sum g x^ with g = the stored gradient where the ReLU was open (st_y > 0), else 0.
   static_assert(!STATS || LDS_BYTES >= 64 * NTHREADS, "the ring has to hold the partial sums");
-  constexpr bool CAN_STATS = STATS;
-  constexpr bool stats = STATS;
+  constexpr bool CAN_STATS = STATS != 0;
+  constexpr bool stats = STATS != 0;
   float ssum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, ssq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float st_mu[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, st_is[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if constexpr (STATS == 2) {
+    const int nn = n0 + cch * 8;  // N is a multiple of 8 in this mode
+    if (nn < a.N) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        st_mu[e] = a.st_mean[nn + e];
+        st_is[e] = a.st_invstd[nn + e];
+      }
+    }
+  }
 #pragma unroll
   for (int ps = 0; ps < EPASS; ++ps) {
     if (ps > 0) __syncthreads();  // the previous slab has been stored
@@ -208,14 +221,32 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
       if constexpr (stats) {
         const uint4 pk = *reinterpret_cast<const uint4*>(src);  // one 16-byte LDS read (columns beyond N hold zeros' worth
         const unsigned pw[4] = {pk.x, pk.y, pk.z, pk.w};          // of padding and are never written out)
+        unsigned yw[4] = {0u, 0u, 0u, 0u}, cw[4] = {0u, 0u, 0u, 0u};
+        if constexpr (STATS == 2) {  // the same 16 bytes of the normalization's output and input (no scatter in this mode)
+          const uint4 yq = *reinterpret_cast<const uint4*>(a.st_y + (size_t)m * a.N + n);
+          const uint4 cq = *reinterpret_cast<const uint4*>(a.st_c + (size_t)m * a.N + n);
+          yw[0] = yq.x; yw[1] = yq.y; yw[2] = yq.z; yw[3] = yq.w;
+          cw[0] = cq.x; cw[1] = cq.y; cw[2] = cq.z; cw[3] = cq.w;
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const unsigned short hb = (unsigned short)(e & 1 ? pw[e >> 1] >> 16 : pw[e >> 1] & 0xffffu);
           _Float16 hv;
           __builtin_memcpy(&hv, &hb, 2);
           const float v = (float)hv;
-          ssum[e] += v;
-          ssq[e] += v * v;
+          if constexpr (STATS == 1) {
+            ssum[e] += v;
+            ssq[e] += v * v;
+          } else {
+            const unsigned short yb = (unsigned short)(e & 1 ? yw[e >> 1] >> 16 : yw[e >> 1] & 0xffffu);
+            const unsigned short cb = (unsigned short)(e & 1 ? cw[e >> 1] >> 16 : cw[e >> 1] & 0xffffu);
+            _Float16 yv, cv;
+            __builtin_memcpy(&yv, &yb, 2);
+            __builtin_memcpy(&cv, &cb, 2);
+            const float g = (float)yv > 0.f ? v : 0.f;
+            ssum[e] += g;
+            ssq[e] += g * (((float)cv - st_mu[e]) * st_is[e]);
+          }
         }
       }
       size_t drow = (size_t)m;
@@ -430,6 +461,8 @@ int launch_op(const Plan& pl, hipStream_t st) {
   constexpr bool IS_FWD = OP == OP_FWD || OP == OP_FWD_STATS;
   if constexpr (OP == OP_FWD_STATS) {
     if (!pl.fast) return JZ_ERR_UNSUPPORTED;  // only the ring kernels come in this form
+  } else if constexpr (OP == OP_BWD_DATA_STATS) {
+    if (!pl.fast || pl.gen || a.sc_on || a.splits != 1 || (a.N & 7) != 0) return JZ_ERR_UNSUPPORTED;
   } else {
     if (!pl.fast) return launch_one<OP, 128, 128>(a, st);
   }
@@ -452,7 +485,7 @@ int launch_op(const Plan& pl, hipStream_t st) {
     }
     return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
   }
-  if constexpr (OP != OP_BWD_WEIGHT) {
+  if constexpr (OP != OP_BWD_WEIGHT && OP != OP_BWD_DATA_STATS) {
     if (pl.gen) {  // the planner offers the 4-wavefront 32-deep tiles in this mode
       if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4, false, 2, 2, true>(a, st);
       if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4, false, 2, 2, true>(a, st);

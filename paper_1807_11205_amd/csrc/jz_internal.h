@@ -24,6 +24,20 @@ int conv_fwd_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* tiles
 int conv_fwd_run(const jz_conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, float* stats,
                  int stats_tiles_m, void* stream);
 
+// Backward-data convolution for the fused "backward-data + batch-norm backward" entry point (jz_bn.hip): the layer whose
+// output (after batch normalization + ReLU) was this convolution's input.  conv_bwd_data_stats_plan: the convolution's
+// workspace and, when its kernel can leave per-tile sums of g and g x^ (g = dx where y > 0), the number of row tiles (else 0);
+// conv_bwd_data_run with stats != nullptr (only after a plan that said so) writes them as [tiles_m][2][C] floats.
+struct BnBwdOperands {
+  const void* x16;      // the normalization's input  [N,H,W,C] of the convolution's input shape
+  const void* y16;      // its output after the ReLU = the convolution's forward input
+  const float* mean;    // [C]
+  const float* invstd;  // [C]
+};
+int conv_bwd_data_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* tiles_m);
+int conv_bwd_data_run(const jz_conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, float* stats,
+                      int stats_tiles_m, const BnBwdOperands* bn, void* stream);
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? JZ_OK : JZ_ERR_LAUNCH; }
 
 }  // namespace jz

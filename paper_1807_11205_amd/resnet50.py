@@ -35,15 +35,17 @@ class Op:
 
 class ResNet50Chain:
     def __init__(self, batch=64, image=224, variant="v1", seed=180711205, initial_loss_scale=1024.0, hparams=None,
-                 policy=None, device="cuda:0", fused=True, block_end=True, proj_side=False, presummed=True):
+                 policy=None, device="cuda:0", fused=True, block_end=True, proj_side=False, presummed=True, bwd_stats=True):
         """fused: forward convolution + batch normalization as one call (statistics in the convolution's epilogue)
-        instead of two.  presummed: the weight-gradient GEMMs whose reduction is split leave their gradient's sum of squares
+        instead of two.  bwd_stats (with fused): a backward-data convolution and the batch-norm backward that consumes its
+        output as one call (the statistics of that backward in the convolution's epilogue).  presummed: the weight-gradient GEMMs whose reduction is split leave their gradient's sum of squares
         in the optimiser's workspace (from inside the kernel that adds the partial sums), the remaining tensors' sums are
         taken by one launch behind the last gradient of the backward pass, and the update is one launch (else: the update's
         own reduce pass reads every gradient again, three launches)."""
         self.presummed = bool(presummed)
         self.N, self.image, self.device, self.fused = int(batch), int(image), torch.device(device), bool(fused)
         self.block_end = bool(block_end) and self.fused
+        self.bwd_stats = bool(bwd_stats) and self.fused
         self.proj_side = bool(proj_side)      # projection-shortcut branches on the side stream too (measured: no gain)
         self.convs = shapes.resnet50_convs(variant, image)
         self.fc = shapes.RESNET50_FC
@@ -187,6 +189,32 @@ class ResNet50Chain:
         return Op("bn_bwd", name, dict(rows=rows, C=C, relu=relu), [x, y, dy, gamma, mean, invstd], [dx, dgamma, dbeta],
                   lambda stream=None: run(self.ws, stream), lambda ws: (lambda stream=None: run(ws, stream)))
 
+    def _fuse_bwd_pairs(self, seg):
+        """A backward-data convolution directly followed by the batch-norm (+ ReLU) backward that reads its output becomes
+        one call, jz_conv2d_bwd_data_bn_relu_bwd."""
+        out, i = [], 0
+        while i < len(seg):
+            a = seg[i]
+            b = seg[i + 1] if i + 1 < len(seg) else None
+            if (a.kind == "conv_bwd_data" and b is not None and b.kind == "bn_bwd" and b.params["relu"] and b.lane == a.lane == "main"
+                    and b.ins[2].data_ptr() == a.outs[0].data_ptr()):
+                d = a.params["desc"]
+                dy, w = a.ins
+                x, y, dz, gamma, mean, invstd = b.ins
+                dx, dgamma, dbeta = b.outs
+                self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(d))
+                run = lambda stream=None, t=(d, dy, w, x, y, gamma, mean, invstd, dz, dx, dgamma, dbeta): \
+                    api.jz_conv2d_bwd_data_bn_relu_bwd(*t, self.ws, stream)
+                op = Op("conv_bwd_data_bn_bwd", a.name + " + " + b.name, dict(desc=d, rows=b.params["rows"], C=b.params["C"]),
+                        [dy, w, x, y, gamma, mean, invstd], [dz, dx, dgamma, dbeta], run)
+                op.joins_side = a.joins_side or b.joins_side
+                out.append(op)
+                i += 2
+            else:
+                out.append(a)
+                i += 1
+        return out
+
     # ---- the network -------------------------------------------------------------------------------------------------
     def _build(self):
         N, F = self.N, self.fwd_ops
@@ -289,7 +317,7 @@ class ResNet50Chain:
             else:
                 seg.append(add_op(nm + ".dx", dxa, dshort, dx_out, False))
                 seg[-1].joins_side = bool(back_p)
-            segments.append(seg)
+            segments.append(self._fuse_bwd_pairs(seg) if self.bwd_stats else seg)
             below = end
             cur, dcur = out, dout
 

@@ -41,14 +41,14 @@ def one_step_of_fp16(got16, ref64, ref16, what):
     assert rel_l2(g, ref64) <= 1e-3, what
 
 
-def check_op(op, counts):
+def check_op(op, counts, check_conv=True):
     import jzt
     k, p = op.kind, op.params
     what = "%s %s" % (k, op.name)
     ins = [None if t is None else np16(t) for t in op.ins]
     outs = [np16(t) for t in op.outs]
     counts[k] = counts.get(k, 0) + 1
-    if k.startswith("conv_") and k != "conv_bn_fwd":
+    if k in ("conv_fwd", "conv_bwd_data", "conv_bwd_weight"):
         d = p["desc"]
         od = oracle.conv_desc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
         fn = {"conv_fwd": oracle.conv_fwd, "conv_bwd_data": oracle.conv_bwd_data, "conv_bwd_weight": oracle.conv_bwd_weight}[k]
@@ -88,6 +88,25 @@ def check_op(op, counts):
         for got, ref in ((outs[1], dg64), (outs[2], db64)):
             err = np.abs(got.astype(np.float64) - ref)
             assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor)), what
+    elif k == "conv_bwd_data_bn_bwd":
+        # the convolution's gradient like any backward-data launch, then the batch-norm backward on that gradient as it
+        # was written (ins: dy, w, bn x, bn y, gamma, mean, invstd; outs: dz, dx, dgamma, dbeta)
+        d = p["desc"]
+        od = oracle.conv_desc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
+        if check_conv:      # (at full size the caller samples this output instead)
+            jzt.check_half_output(outs[0], oracle.conv_bwd_data(od, ins[0], ins[1]), tol=1e-3, what=what,
+                                  mag64=oracle.conv_bwd_data(od, jzt.abs16(ins[0]), jzt.abs16(ins[1])))
+        rows, C = p["rows"], p["C"]
+        x, y, dz = ins[2].reshape(rows, C), ins[3].reshape(rows, C), outs[0].reshape(rows, C)
+        dx64, _, dg64, db64, _, _ = oracle.bn_relu_bwd(x, y, dz, ins[4], ins[5], ins[6], relu=True)
+        assert rel_l2(outs[1], dx64) <= 1e-3, what
+        rms = float(np.sqrt(np.mean(dz.astype(np.float64) ** 2)))
+        floor = np.sqrt(rows) * rms * 2.5e-3 + 2.0 ** -24
+        for got, ref in ((outs[2], dg64), (outs[3], db64)):
+            err = np.abs(got.astype(np.float64) - ref)
+            assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor)), what
+        counts["conv_bwd_data"] = counts.get("conv_bwd_data", 0) + 1
+        counts["bn_bwd"] = counts.get("bn_bwd", 0) + 1
     elif k == "add_fwd":
         assert np.array_equal(outs[0].view(np.uint16), oracle.add_fwd(ins[0], ins[1], relu=p["relu"])[1].view(np.uint16)), what
     elif k == "relu_bwd":
@@ -145,12 +164,13 @@ def check_op(op, counts):
         raise AssertionError("no check for " + k)
 
 
-@pytest.mark.parametrize("fused,block_end,presummed", [(True, True, True), (True, True, False), (True, False, True), (False, False, True)])
-def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused, block_end, presummed):
+@pytest.mark.parametrize("fused,block_end,presummed,bwd_stats", [(True, True, True, True), (True, True, True, False), (True, True, False, True),
+                                                                 (True, False, True, True), (False, False, True, False)])
+def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused, block_end, presummed, bwd_stats):
     import jzt
     from paper_1807_11205_amd import resnet50
     net = resnet50.ResNet50Chain(batch=4, image=64, initial_loss_scale=256.0, policy=dict(growth_interval=1), fused=fused,
-                                 block_end=block_end, presummed=presummed)
+                                 block_end=block_end, presummed=presummed, bwd_stats=bwd_stats)
     assert len(net.fwd_ops) == (53 if fused else 53 * 2 + 16) + 1 + 1 + 3 + (1 if presummed else 0) and net.trace[-1].kind == "lars_dyn"
     assert (net.fwd_ops[0].kind == "lars_begin" and net.bwd_ops[-1].kind == "lars_grad_sumsq") == presummed
     for op in net.trace[:-1]:
@@ -161,6 +181,7 @@ def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused, block_end,
         check_op(op, counts)
     assert counts.get("conv_bn_fwd", 0) + counts.get("conv_fwd", 0) == 53 and counts.get("conv_fwd", 0) == counts.get("bn_fwd", 0)
     assert counts["conv_bwd_weight"] == 53 and counts["conv_bwd_data"] == 52
+    assert counts.get("conv_bwd_data_bn_bwd", 0) == (32 if bwd_stats else 0)    # the a and b layers of the 16 blocks
     assert counts["bn_bwd"] + counts.get("bn_bwd_block_end", 0) == 53 and counts["add_fwd"] == (1 if fused else 32)
     assert counts.get("relu_bwd", 0) + counts.get("relu_bwd_sum", 0) + counts.get("bn_bwd_block_end", 0) == 16
     assert counts.get("bn_bwd_block_end", 0) == (16 if block_end else 0) and counts.get("relu_bwd_sum", 0) == (15 if fused and not block_end else 0)
@@ -250,7 +271,7 @@ def test_full_size_chained_step_on_sampled_outputs(jz):
         jzt.check_half_output(np16(ow.outs[0]), oracle.conv_bwd_weight(odesc(d), xw, dyw), 1e-3, "bwd_weight " + name,
                               mag64=oracle.conv_bwd_weight(odesc(d), jzt.abs16(xw), jzt.abs16(dyw)))
         if name != "stem":
-            od_ = ops[("conv_bwd_data", name)]
+            od_ = ops.get(("conv_bwd_data", name)) or next(o for o in net.trace if o.kind == "conv_bwd_data_bn_bwd" and o.name.startswith(name + " + "))
             dx = np16(od_.outs[0])
             idx = rng.integers(0, dx.size, size=8192)
             gy, ww = np16(od_.ins[0]), np16(od_.ins[1])
@@ -285,7 +306,11 @@ def test_full_size_chained_step_on_sampled_outputs(jz):
         assert np.all(np.abs(np16(op.outs[3]) - i64) <= 1e-4 * i64), name
         assert rel_l2(np16(op.outs[1]), y64) <= 1e-3, name
         del y64
-        check_op(ops[("bn_bwd_block_end" if name.endswith("c") else "bn_bwd", name + ".bn")], counts)
+        if name.endswith("c"):
+            check_op(ops[("bn_bwd_block_end", name + ".bn")], counts)
+        else:       # the a layers' backward is the second half of the call that holds the b layers' backward-data
+            check_op(next(o for o in net.trace if o.kind == "conv_bwd_data_bn_bwd" and o.name.endswith(" + " + name + ".bn")), counts,
+                     check_conv=False)
 
 
 def test_a_new_batch_changes_the_step_and_the_old_one_reproduces_it(jz):

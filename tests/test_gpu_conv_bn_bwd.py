@@ -1,0 +1,157 @@
+"""GPU parity of jz_conv2d_bwd_data_bn_relu_bwd (backward-data convolution with the statistics of the batch-norm
+backward underneath it taken in the convolution's epilogue): dz must be the bits jz_conv2d_bwd_data writes, and
+dx / dgamma / dbeta must meet the bars of the stand-alone batch-norm backward against the oracle evaluated on that dz.
+The normalization's forward tensors (y, mean, invstd) come from the oracle, so nothing the call reads was produced by
+the library.  Every kernel variant is forced through the planner's tuning hook; shapes whose kernel cannot leave the
+sums (split reduction, strided scatter form) must give the same results through the statistics pass."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1807_11205_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jz():
+    from paper_1807_11205_amd import api
+    api.lib()
+    assert torch.cuda.is_available()
+    return api
+
+
+def run_case(jz, N, H, C, K, R, stride, pad, key=0, eps=1e-5, variant=None, splits=1, dead_channels=0):
+    import jzt
+    d = jz.conv_desc(N, H, H, C, K, R, R, stride, pad)
+    if variant is not None:
+        with jzt.forced_variant(d, *variant, splits=splits, ops=(jz.JZ_BWD_DATA,)):
+            return run_case(jz, N, H, C, K, R, stride, pad, key, eps, dead_channels=dead_channels)
+    rng = inputs.rng_for(43, key, N, H, C, K, R)
+    rows = N * H * H
+    c = (rng.standard_normal((rows, C), dtype=np.float32) * np.float32(1.5) + np.float32(0.5) *
+         rng.standard_normal(C, dtype=np.float32)).astype(np.float16)
+    gamma = (1.0 + 0.3 * rng.standard_normal(C, dtype=np.float32)).astype(np.float32)
+    beta = (0.2 * rng.standard_normal(C, dtype=np.float32)).astype(np.float32)
+    if dead_channels:
+        beta[:dead_channels] = -100.0        # the ReLU is closed everywhere in these channels: their sums are exactly zero
+    _, y16, m64, i64 = oracle.bn_relu_fwd(c, gamma, beta, eps, relu=True)
+    mean, invstd = m64.astype(np.float32), i64.astype(np.float32)
+    w = inputs.normal_f16(rng, (K * R * R * C,), std=(2.0 / (R * R * C)) ** 0.5)
+    dy = inputs.normal_f16(rng, (N * d.P * d.Q * K,), std=4.0)
+    DY, W, CX, Y = jzt.to_dev(dy), jzt.to_dev(w), jzt.to_dev(c.ravel()), jzt.to_dev(np.ascontiguousarray(y16).ravel())
+    G, M, I = jzt.to_dev(gamma), jzt.to_dev(mean), jzt.to_dev(invstd)
+    dz_ref = torch.empty(rows * C, dtype=torch.float16, device="cuda")
+    ws0 = torch.zeros(max(jz.jz_conv2d_workspace_bytes(jz.JZ_BWD_DATA, d), 16), dtype=torch.uint8, device="cuda")
+    jz.bind_conv2d(jz.JZ_BWD_DATA, d, DY, W, dz_ref, ws0)()
+    nan16 = lambda n: torch.full((n,), float("nan"), dtype=torch.float16, device="cuda")
+    dz, dx, dg, db = nan16(rows * C), nan16(rows * C), nan16(C), nan16(C)
+    ws = torch.full((max(jz.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(d), 16),), 0xCD, dtype=torch.uint8, device="cuda")
+    jz.jz_conv2d_bwd_data_bn_relu_bwd(d, DY, W, CX, Y, G, M, I, dz, dx, dg, db, ws)
+    torch.cuda.synchronize()
+    dz_np = dz.cpu().numpy()
+    assert np.array_equal(dz_np.view(np.uint16), dz_ref.cpu().numpy().view(np.uint16)), "dz differs from jz_conv2d_bwd_data"
+    g2 = dz_np.reshape(rows, C)
+    dx64, _, dg64, db64, _, _ = oracle.bn_relu_bwd(c, y16.reshape(rows, C), g2, gamma, mean, invstd, relu=True)
+    assert jzt.rel_l2(dx.cpu().numpy(), dx64) <= 1e-3
+    rms = float(np.sqrt(np.mean(g2.astype(np.float64) ** 2)))
+    floor = np.sqrt(rows) * rms * 2.5e-3 + 2.0 ** -24
+    for got, ref in ((dg.cpu().numpy(), dg64), (db.cpu().numpy(), db64)):
+        err = np.abs(got.astype(np.float64) - ref)
+        assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor)), float(np.max(err / np.maximum(np.abs(ref), floor)))
+    if dead_channels:
+        assert np.all(dg.cpu().numpy()[:dead_channels] == 0) and np.all(db.cpu().numpy()[:dead_channels] == 0)
+        assert np.all(dx.cpu().numpy().reshape(rows, C)[:, :dead_channels] == 0)
+    return jz.jz_conv2d_describe_plan(jz.JZ_BWD_DATA, d)
+
+
+SHAPES = [
+    (2, 14, 64, 64, 3, 1, 1),        # 392 rows: ragged against every tile height
+    (3, 9, 96, 32, 3, 1, 1),         # C not a multiple of 64
+    (2, 28, 128, 256, 1, 1, 0),      # 1x1
+    (2, 28, 512, 256, 1, 2, 0),      # strided 1x1: the scatter form cannot leave the sums (statistics pass)
+    (1, 7, 2048, 512, 1, 1, 0),      # widest input, 49 rows
+    (4, 56, 64, 64, 3, 1, 1),        # several row tiles
+    (2, 12, 40, 24, 3, 1, 1),        # 40 channels: whole 16-byte pieces, not a multiple of 32
+    (2, 15, 64, 64, 3, 2, 1),        # strided 3x3: the per-load path (statistics pass)
+]
+
+
+@pytest.mark.parametrize("N,H,C,K,R,stride,pad", SHAPES)
+def test_fused_backward_statistics_against_the_oracle(jz, N, H, C, K, R, stride, pad):
+    run_case(jz, N, H, C, K, R, stride, pad)
+    run_case(jz, N, H, C, K, R, stride, pad, key=5, dead_channels=8)
+
+
+@pytest.mark.parametrize("variant", [(128, 128, 32, 4, 4), (128, 64, 32, 4, 4), (64, 128, 32, 4, 3), (64, 64, 64, 4, 4),
+                                     (128, 128, 64, 4, 4), (256, 128, 32, 8, 4), (256, 128, 64, 8, 3), (256, 256, 32, 8, 4),
+                                     (128, 128, 32, 8, 3), (128, 128, 64, 8, 4)], ids=lambda v: "x".join(str(i) for i in v))
+def test_every_kernel_variant_leaves_the_same_sums(jz, variant):
+    plan = run_case(jz, 5, 24, 192, 64, 3, 1, 1, key=1, variant=variant)       # 2880 rows: 22.5 tiles of 128, 11.25 of 256
+    assert "tile %dx%dx%d" % variant[:3] in plan, plan
+    run_case(jz, 2, 10, 72, 128, 1, 1, 0, key=2, variant=variant)              # 200 rows, 72 channels: ragged both ways
+
+
+def test_split_reduction_falls_back_to_the_statistics_pass(jz):
+    run_case(jz, 2, 14, 64, 256, 3, 1, 1, key=3, variant=(128, 64, 32, 4, 4), splits=3)
+
+
+def test_two_runs_agree_bit_for_bit(jz):
+    import jzt
+    N, H, C, K = 8, 28, 128, 128
+    d = jz.conv_desc(N, H, H, C, K, 3, 3, 1, 1)
+    rng = inputs.rng_for(43, 9)
+    rows = N * H * H
+    c = inputs.normal_f16(rng, (rows, C), std=1.5)
+    gamma = np.ones(C, np.float32); beta = np.zeros(C, np.float32)
+    _, y16, m64, i64 = oracle.bn_relu_fwd(c, gamma, beta, 1e-5, relu=True)
+    args = [jzt.to_dev(inputs.normal_f16(rng, (rows * K,), std=4.0)), jzt.to_dev(inputs.normal_f16(rng, (K * 9 * C,), std=0.05)),
+            jzt.to_dev(c.ravel()), jzt.to_dev(np.ascontiguousarray(y16).ravel()), jzt.to_dev(gamma), jzt.to_dev(m64.astype(np.float32)),
+            jzt.to_dev(i64.astype(np.float32))]
+    outs = []
+    for _ in range(2):
+        o = [torch.empty(rows * C, dtype=torch.float16, device="cuda"), torch.empty(rows * C, dtype=torch.float16, device="cuda"),
+             torch.empty(C, dtype=torch.float16, device="cuda"), torch.empty(C, dtype=torch.float16, device="cuda")]
+        ws = torch.zeros(jz.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+        jz.jz_conv2d_bwd_data_bn_relu_bwd(d, *args, *o, ws)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy().view(np.uint16) for t in o])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+
+
+def test_argument_errors(jz):
+    import ctypes
+    L = jz.lib()
+    d = jz.conv_desc(2, 8, 8, 16, 32, 3, 3, 1, 1)
+    n = ctypes.c_size_t(0)
+    assert L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(ctypes.byref(d), None) == jz.JZ_ERR_NULL
+    assert L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == jz.JZ_OK and n.value > 0
+    h, f = torch.float16, torch.float32
+    n_in, n_out = 2 * 8 * 8 * 16, 2 * 8 * 8 * 32
+    dy = torch.zeros(n_out, dtype=h, device="cuda"); w = torch.zeros(32 * 9 * 16, dtype=h, device="cuda")
+    x = torch.zeros(n_in, dtype=h, device="cuda"); y = torch.zeros(n_in, dtype=h, device="cuda")
+    dz = torch.zeros(n_in, dtype=h, device="cuda"); dx = torch.zeros(n_in, dtype=h, device="cuda")
+    g = torch.ones(16, dtype=f, device="cuda"); m = torch.zeros(16, dtype=f, device="cuda"); s = torch.ones(16, dtype=f, device="cuda")
+    dg = torch.zeros(16, dtype=h, device="cuda"); db = torch.zeros(16, dtype=h, device="cuda")
+    ws = torch.zeros(n.value, dtype=torch.uint8, device="cuda")
+    ptr = lambda t: t.data_ptr()
+
+    def call(**o):
+        a = dict(dy=ptr(dy), w=ptr(w), x=ptr(x), y=ptr(y), g=ptr(g), m=ptr(m), s=ptr(s), dz=ptr(dz), dx=ptr(dx), dg=ptr(dg), db=ptr(db),
+                 ws=ptr(ws), n=n.value)
+        a.update(o)
+        return L.jz_conv2d_bwd_data_bn_relu_bwd(ctypes.byref(d), a["dy"], a["w"], a["x"], a["y"], a["g"], a["m"], a["s"], a["dz"], a["dx"],
+                                                a["dg"], a["db"], a["ws"], a["n"], None)
+
+    for k in ("dy", "w", "x", "y", "g", "m", "s", "dz", "dx", "dg", "db"):
+        assert call(**{k: None}) == jz.JZ_ERR_NULL, k
+    assert call(n=n.value - 1) == jz.JZ_ERR_WORKSPACE and call(ws=None) == jz.JZ_ERR_WORKSPACE
+    assert call(dx=ptr(dz)) == jz.JZ_ERR_ALIAS and call(dz=ptr(x)) == jz.JZ_ERR_ALIAS and call(dx=ptr(y)) == jz.JZ_ERR_ALIAS
+    assert call(db=ptr(dg)) == jz.JZ_ERR_ALIAS
+    assert call(dx=ptr(dx) + 2) == jz.JZ_ERR_ALIGN and call(y=ptr(y) + 2) == jz.JZ_ERR_ALIGN
+    assert call() == jz.JZ_OK
+    torch.cuda.synchronize()
+    dbad = jz.conv_desc(2, 8, 8, 12, 32, 3, 3, 1, 1)      # 12 input channels: not a multiple of 8 for the normalization
+    assert L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(ctypes.byref(dbad), ctypes.byref(n)) == jz.JZ_ERR_UNSUPPORTED
