@@ -289,6 +289,21 @@ int jz_conv2d_bwd_data_bn_relu_bwd(const jz_conv_desc* desc, const void* dy16, c
                                    void* dz16, void* bn_dx16, void* dgamma16, void* dbeta16, void* ws, size_t ws_bytes,
                                    void* hip_stream);
 
+/* The same for a convolution whose input was the output of a residual block, y_out = relu(bn(x) + shortcut) (Section 4.2's
+ * layer at the end of a bottleneck block): this convolution's backward-data result is one contribution to the gradient of
+ * y_out, dyb16 the other (the shortcut consumer's; may be NULL).  One call computes
+ *   g16 = RNE16(RNE16(jz_conv2d_bwd_data(desc, dy16, w16)) [+ dyb16]) where y_out16 > 0, else 0        [N,H,W,C]
+ *   bn_dx16, dgamma16, dbeta16 = jz_bn_relu_bwd(rows = N*H*W, C, x = bn_x16, dy = g16, relu = 0)
+ * i.e. jz_conv2d_bwd_data followed by jz_bn_bwd_block_end, without the convolution's result ever being stored: the
+ * epilogue reads the matching tiles of dyb16, y_out16 and bn_x16, stores g and takes its sums.  g16 holds the same bits
+ * as from those two calls; the other outputs meet theirs within the rounding of FP32 sums taken in another (fixed) order.
+ * Kernels that cannot do this (split reduction, strided scatter form) run the two-call sequence inside the call.
+ * Workspace: jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes.  Status codes as for the two calls it replaces. */
+int jz_conv2d_bwd_data_block_end_bwd(const jz_conv_desc* desc, const void* dy16, const void* w16, const void* dyb16,
+                                     const void* bn_x16, const void* y_out16, const float* gamma, const float* save_mean,
+                                     const float* save_invstd, void* g16, void* bn_dx16, void* dgamma16, void* dbeta16, void* ws,
+                                     size_t ws_bytes, void* hip_stream);
+
 /* The backward pass at the end of a residual block, y_out = relu(bn(x) + shortcut), in one call: the gradient of the sum,
  * g = RNE16(dya [+ dyb]) where y_out > 0 and 0 elsewhere (dyb may be NULL; two contributions arrive when the block above
  * has two consumers of y_out), is formed inside the statistics pass of the batch-norm backward and written to g16 for

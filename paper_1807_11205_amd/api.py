@@ -28,7 +28,7 @@ EXPORTS = [
     "jz_lars_begin_step", "jz_lars_sumsq_sink", "jz_lars_grad_sumsq", "jz_lars_mp_update_presummed", "jz_lars_mp_update_presummed_dyn",
     "jz_add_fwd", "jz_relu_bwd", "jz_relu_bwd_sum", "jz_maxpool_fwd", "jz_maxpool_bwd", "jz_avgpool_fwd", "jz_avgpool_bwd", "jz_bias_add",
     "jz_bias_grad", "jz_softmax_xent_bwd", "jz_conv2d_bn_relu_fwd_workspace_bytes", "jz_conv2d_bn_relu_fwd",
-    "jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes", "jz_conv2d_bwd_data_bn_relu_bwd",
+    "jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes", "jz_conv2d_bwd_data_bn_relu_bwd", "jz_conv2d_bwd_data_block_end_bwd",
     "jz_bn_workspace_bytes", "jz_bn_relu_fwd", "jz_bn_relu_bwd", "jz_bn_bwd_block_end",
     "jz_status_string", "jz_version",
 ]
@@ -142,6 +142,7 @@ def lib() -> ctypes.CDLL:
         L.jz_conv2d_bn_relu_fwd.argtypes = [dp, vp, vp, vp, vp, cf, vp, ci, vp, vp, vp, vp, vp, sz, vp]
         L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes.argtypes = [dp, ctypes.POINTER(sz)]
         L.jz_conv2d_bwd_data_bn_relu_bwd.argtypes = [dp] + [vp] * 12 + [sz, vp]
+        L.jz_conv2d_bwd_data_block_end_bwd.argtypes = [dp] + [vp] * 13 + [sz, vp]
         L.jz_status_string.argtypes = [ci]
         L.jz_status_string.restype = ctypes.c_char_p
         L.jz_version.argtypes = []
@@ -662,3 +663,20 @@ def jz_conv2d_bwd_data_bn_relu_bwd(desc, dy16, w16, bn_x16, bn_y16, gamma, save_
                                                 _dev_ptr(dz16, h, n_in, "dz16"), _dev_ptr(bn_dx16, h, n_in, "bn_dx16"),
                                                 _dev_ptr(dgamma16, h, C, "dgamma16"), _dev_ptr(dbeta16, h, C, "dbeta16"), wp, wn,
                                                 _stream(stream)), "jz_conv2d_bwd_data_bn_relu_bwd")
+
+
+def jz_conv2d_bwd_data_block_end_bwd(desc, dy16, w16, dyb16, bn_x16, y_out16, gamma, save_mean, save_invstd, g16, bn_dx16, dgamma16, dbeta16,
+                                     ws, stream=None):
+    """g16 = relu-masked (bwd_data(dy16, w16) [+ dyb16]) by y_out16 > 0; bn_dx16, dgamma16, dbeta16 = batch-norm backward
+    (no ReLU, input bn_x16) of dy = g16."""
+    d, h, f = desc, torch.float16, torch.float32
+    n_in, C = d.N * d.H * d.W * d.C, d.C
+    wp, wn = _ws(ws)
+    _check(lib().jz_conv2d_bwd_data_block_end_bwd(ctypes.byref(d), _dev_ptr(dy16, h, d.N * d.P * d.Q * d.K, "dy16"),
+                                                  _dev_ptr(w16, h, d.K * d.R * d.S * d.C, "w16"), _dev_ptr(dyb16, h, n_in, "dyb16"),
+                                                  _dev_ptr(bn_x16, h, n_in, "bn_x16"), _dev_ptr(y_out16, h, n_in, "y_out16"),
+                                                  _dev_ptr(gamma, f, C, "gamma"), _dev_ptr(save_mean, f, C, "save_mean"),
+                                                  _dev_ptr(save_invstd, f, C, "save_invstd"), _dev_ptr(g16, h, n_in, "g16"),
+                                                  _dev_ptr(bn_dx16, h, n_in, "bn_dx16"), _dev_ptr(dgamma16, h, C, "dgamma16"),
+                                                  _dev_ptr(dbeta16, h, C, "dbeta16"), wp, wn, _stream(stream)),
+           "jz_conv2d_bwd_data_block_end_bwd")

@@ -613,53 +613,62 @@ extern "C" int jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(const jz_conv_desc
   return JZ_OK;
 }
 
-extern "C" int jz_conv2d_bwd_data_bn_relu_bwd(const jz_conv_desc* desc, const void* dy16, const void* w16, const void* bn_x16,
-                                              const void* bn_y16, const float* gamma, const float* save_mean,
-                                              const float* save_invstd, void* dz16, void* bn_dx16, void* dgamma16, void* dbeta16,
-                                              void* ws, size_t ws_bytes, void* hip_stream) {
+// block_end false: dz = bwd_data, then the backward of y = relu(bn(x)) for dy = dz.
+// block_end true:  y = relu(bn(x) + shortcut) is a residual block's output and bwd_data is one contribution to its gradient:
+//                  g = RNE16(bwd_data [+ add]) where y > 0, else 0, goes to `out`, then the backward of bn(x) (no ReLU) for dy = g.
+static int conv_bwd_data_bn_bwd(const jz_conv_desc* desc, const void* dy16, const void* w16, const void* bn_x16, const void* bn_y16,
+                                const void* add16, bool block_end, const float* gamma, const float* save_mean, const float* save_invstd,
+                                void* out16, void* bn_dx16, void* dgamma16, void* dbeta16, void* ws, size_t ws_bytes, void* hip_stream) {
   ConvBnBwdPlan p;
   int rc = make_conv_bn_bwd_plan(desc, &p);
   if (rc != JZ_OK) return rc;
-  if (!dy16 || !w16 || !bn_x16 || !bn_y16 || !gamma || !save_mean || !save_invstd || !dz16 || !bn_dx16 || !dgamma16 || !dbeta16)
+  if (!dy16 || !w16 || !bn_x16 || !bn_y16 || !gamma || !save_mean || !save_invstd || !out16 || !bn_dx16 || !dgamma16 || !dbeta16)
     return JZ_ERR_NULL;
   if (!ws || ws_bytes < p.total) return JZ_ERR_WORKSPACE;
-  if (!jz::aligned16(bn_x16) || !jz::aligned16(bn_y16) || !jz::aligned16(bn_dx16) || !jz::aligned16(ws) || !jz::aligned16(gamma) ||
-      !jz::aligned16(save_mean) || !jz::aligned16(save_invstd))
+  if (!jz::aligned16(bn_x16) || !jz::aligned16(bn_y16) || !jz::aligned16(add16) || !jz::aligned16(bn_dx16) || !jz::aligned16(ws) ||
+      !jz::aligned16(gamma) || !jz::aligned16(save_mean) || !jz::aligned16(save_invstd))
     return JZ_ERR_ALIGN;
   const int64_t rows = p.bn.rows;
   const int C = p.bn.C;
   const size_t nb = (size_t)rows * C * 2, nh = (size_t)C * 2, nc = (size_t)C * 4;
   const int P = (desc->H + 2 * desc->pad_h - desc->R) / desc->stride_h + 1, Q = (desc->W + 2 * desc->pad_w - desc->S) / desc->stride_w + 1;
   const size_t ny = (size_t)desc->N * P * Q * desc->K * 2, nw = (size_t)desc->K * desc->R * desc->S * desc->C * 2;
-  // outputs against everything else (the convolution's own checks cover dy, w, dz and its part of the workspace)
-  const void* outs[4] = {dz16, bn_dx16, dgamma16, dbeta16};
+  // outputs against everything else (the convolution's own checks cover dy, w, its output and its part of the workspace)
+  const void* outs[4] = {out16, bn_dx16, dgamma16, dbeta16};
   const size_t outn[4] = {nb, nb, nh, nh};
-  const void* ins[7] = {dy16, w16, bn_x16, bn_y16, gamma, save_mean, save_invstd};
-  const size_t inn[7] = {ny, nw, nb, nb, nc, nc, nc};
+  const void* ins[8] = {dy16, w16, bn_x16, bn_y16, gamma, save_mean, save_invstd, add16};
+  const size_t inn[8] = {ny, nw, nb, nb, nc, nc, nc, add16 ? nb : 0};
   for (int i = 0; i < 4; ++i) {
-    for (int j = 0; j < 7; ++j)
-      if (jz::overlaps(outs[i], outn[i], ins[j], inn[j])) return JZ_ERR_ALIAS;
+    for (int j = 0; j < 8; ++j)
+      if (inn[j] && jz::overlaps(outs[i], outn[i], ins[j], inn[j])) return JZ_ERR_ALIAS;
     for (int j = i + 1; j < 4; ++j)
       if (jz::overlaps(outs[i], outn[i], outs[j], outn[j])) return JZ_ERR_ALIAS;
     if (jz::overlaps(outs[i], outn[i], ws, p.total)) return JZ_ERR_ALIAS;
   }
-  for (int j = 0; j < 7; ++j)
-    if (jz::overlaps(ins[j], inn[j], ws, p.total)) return JZ_ERR_ALIAS;
+  for (int j = 0; j < 8; ++j)
+    if (inn[j] && jz::overlaps(ins[j], inn[j], ws, p.total)) return JZ_ERR_ALIAS;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* bws = static_cast<char*>(ws) + p.off_bn;
   float* part = reinterpret_cast<float*>(bws + p.bn.off_part);
   float* coef = reinterpret_cast<float*>(bws + p.bn.off_coef);
-  const jz::BnBwdOperands bn{bn_x16, bn_y16, save_mean, save_invstd};
-  rc = jz::conv_bwd_data_run(desc, dy16, w16, dz16, ws, p.conv_ws, p.tiles_m > 0 ? part : nullptr, p.tiles_m, &bn, hip_stream);
+  jz::BnBwdOperands bn{bn_x16, bn_y16, save_mean, save_invstd};
+  bn.block_end = block_end;
+  bn.add16 = add16;
+  rc = jz::conv_bwd_data_run(desc, dy16, w16, out16, ws, p.conv_ws, p.tiles_m > 0 ? part : nullptr, p.tiles_m, &bn, hip_stream);
   if (rc != JZ_OK) return rc;
   const uint4* x = static_cast<const uint4*>(bn_x16);
   const uint4* y = static_cast<const uint4*>(bn_y16);
-  const uint4* dz = static_cast<const uint4*>(dz16);
+  const uint4* dz = static_cast<const uint4*>(out16);
   int slabs = p.tiles_m;
-  if (slabs == 0) {  // this convolution kernel cannot leave the sums: the statistics pass over dz, y and x
+  if (slabs == 0) {  // this convolution kernel cannot leave the sums: the statistics pass, which then also forms g in place
     slabs = p.bn.slabs;
-    hipLaunchKernelGGL(bn_stats<1>, dim3((unsigned)(slabs * p.bn.csplit)), dim3(BN_THREADS), 0, st, x, y, dz, save_mean, save_invstd, part,
-                       rows, C, p.bn.cpr, p.bn.rpp, p.bn.rows_per_slab, 1, p.bn.csplit);
+    if (block_end)
+      hipLaunchKernelGGL(bn_stats<2>, dim3((unsigned)(slabs * p.bn.csplit)), dim3(BN_THREADS), 0, st, x, y, dz, save_mean, save_invstd, part,
+                         rows, C, p.bn.cpr, p.bn.rpp, p.bn.rows_per_slab, 0, p.bn.csplit, static_cast<const uint4*>(add16),
+                         static_cast<uint4*>(out16));
+    else
+      hipLaunchKernelGGL(bn_stats<1>, dim3((unsigned)(slabs * p.bn.csplit)), dim3(BN_THREADS), 0, st, x, y, dz, save_mean, save_invstd, part,
+                         rows, C, p.bn.cpr, p.bn.rpp, p.bn.rows_per_slab, 1, p.bn.csplit);
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
   }
   hipLaunchKernelGGL(bn_bwd_final, dim3((unsigned)((C + BN_FIN_C - 1) / BN_FIN_C)), dim3(BN_THREADS), 0, st, part, slabs, C,
@@ -667,7 +676,23 @@ extern "C" int jz_conv2d_bwd_data_bn_relu_bwd(const jz_conv_desc* desc, const vo
                      static_cast<unsigned short*>(dbeta16), coef);
   if ((rc = jz::launch_status()) != JZ_OK) return rc;
   const int64_t n_chunks = rows * p.bn.cpr;
-  hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, y, dz, static_cast<uint4*>(bn_dx16), coef,
-                     n_chunks, C, p.bn.cpr, 1);
+  hipLaunchKernelGGL(bn_bwd_apply, dim3(apply_grid(n_chunks)), dim3(BN_THREADS), 0, st, x, block_end ? nullptr : y, dz,
+                     static_cast<uint4*>(bn_dx16), coef, n_chunks, C, p.bn.cpr, block_end ? 0 : 1);
   return jz::launch_status();
+}
+
+extern "C" int jz_conv2d_bwd_data_bn_relu_bwd(const jz_conv_desc* desc, const void* dy16, const void* w16, const void* bn_x16,
+                                              const void* bn_y16, const float* gamma, const float* save_mean,
+                                              const float* save_invstd, void* dz16, void* bn_dx16, void* dgamma16, void* dbeta16,
+                                              void* ws, size_t ws_bytes, void* hip_stream) {
+  return conv_bwd_data_bn_bwd(desc, dy16, w16, bn_x16, bn_y16, nullptr, false, gamma, save_mean, save_invstd, dz16, bn_dx16, dgamma16,
+                              dbeta16, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int jz_conv2d_bwd_data_block_end_bwd(const jz_conv_desc* desc, const void* dy16, const void* w16, const void* dyb16,
+                                                const void* bn_x16, const void* y_out16, const float* gamma, const float* save_mean,
+                                                const float* save_invstd, void* g16, void* bn_dx16, void* dgamma16, void* dbeta16,
+                                                void* ws, size_t ws_bytes, void* hip_stream) {
+  return conv_bwd_data_bn_bwd(desc, dy16, w16, bn_x16, y_out16, dyb16, true, gamma, save_mean, save_invstd, g16, bn_dx16, dgamma16,
+                              dbeta16, ws, ws_bytes, hip_stream);
 }

@@ -589,9 +589,10 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
   a.bytesB = (unsigned)pl.bytesB;
   a.Dpart = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_offset);
   a.stats = stats;
-  a.st_y = a.st_c = nullptr;
+  a.st_y = a.st_c = a.st_add = nullptr;
   a.st_mean = a.st_invstd = nullptr;
   if (stats && op == JZ_BWD_DATA) {
+    a.st_add = static_cast<const unsigned short*>(bn->add16);
     a.st_y = static_cast<const unsigned short*>(bn->y16);
     a.st_c = static_cast<const unsigned short*>(bn->x16);
     a.st_mean = bn->mean;
@@ -617,7 +618,7 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     if ((rc = jz::launch_status()) != JZ_OK) return rc;
   }
   if (op == JZ_FWD) rc = stats ? launch_fwd_stats(pl, st) : launch_fwd(pl, st);
-  else if (op == JZ_BWD_DATA) rc = stats ? launch_bwd_data_stats(pl, st) : launch_bwd_data(pl, st);
+  else if (op == JZ_BWD_DATA) rc = !stats ? launch_bwd_data(pl, st) : bn->block_end ? launch_bwd_data_block_end(pl, st) : launch_bwd_data_stats(pl, st);
   else rc = launch_bwd_weight(pl, st);
   if (rc != JZ_OK) return rc;
   if (a.splits > 1) {

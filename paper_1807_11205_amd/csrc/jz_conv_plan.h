@@ -1,6 +1,6 @@
 // What the planner hands to the kernel launchers of the implicit-GEMM family: the GEMM view of one convolution /
 // fully connected operation with the kernel variant chosen for it.  The launchers live in one translation unit per
-// operation (jz_conv_fwd.hip, jz_conv_fwd_stats.hip, jz_conv_bwd_data.hip, jz_conv_bwd_data_stats.hip, jz_conv_bwd_weight.hip) so that they
+// operation (jz_conv_fwd.hip, jz_conv_fwd_stats.hip, jz_conv_bwd_data.hip, jz_conv_bwd_data_stats.hip, jz_conv_bwd_data_block_end.hip, jz_conv_bwd_weight.hip) so that they
 // compile in parallel; the planner and the entry points are in jz_conv.hip.
 #pragma once
 #include "jz_igemm.h"
@@ -29,6 +29,7 @@ struct Plan {
 int launch_fwd(const Plan& pl, hipStream_t st);
 int launch_fwd_stats(const Plan& pl, hipStream_t st);  // forward that also leaves per-tile column sums
 int launch_bwd_data_stats(const Plan& pl, hipStream_t st);  // backward-data that also leaves batch-norm backward sums
+int launch_bwd_data_block_end(const Plan& pl, hipStream_t st);  // ... of the block-end gradient it forms from its tile
 int launch_bwd_data(const Plan& pl, hipStream_t st);
 int launch_bwd_weight(const Plan& pl, hipStream_t st);
 

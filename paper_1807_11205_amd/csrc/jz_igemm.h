@@ -18,7 +18,8 @@ namespace jz {
 
 enum { OP_FWD = 0, OP_BWD_DATA = 1, OP_BWD_WEIGHT = 2,
        OP_FWD_STATS = 3,        // forward whose epilogue also leaves per-tile column sums (kernel template arguments only)
-       OP_BWD_DATA_STATS = 4 }; // backward-data whose epilogue also leaves the sums a batch-norm backward needs
+       OP_BWD_DATA_STATS = 4,   // backward-data whose epilogue also leaves the sums a batch-norm backward needs
+       OP_BWD_DATA_BLOCK_END = 5 };  // ... and first forms the gradient at the end of a residual block from its tile
 
 // Division by a run-time constant through multiply-high (Granlund-Montgomery style), exact for n < 2^31.
 struct FastDiv {
@@ -62,8 +63,12 @@ struct GemmArgs {
                         // (OP_FWD_STATS), or of g and g x^ (OP_BWD_DATA_STATS) with g = the stored gradient where st_y > 0,
                         // else 0, and x^ = (st_c - st_mean) st_invstd: the batch normalization + ReLU that produced the
                         // convolution's input, st_c its input and st_y its output, both [M][N] like D16
+                        // OP_BWD_DATA_BLOCK_END: the tile is one contribution to the gradient of a residual block's output
+                        // st_y = relu(bn(st_c) + shortcut); what is stored (and summed) is g = RNE16(tile [+ st_add]) where
+                        // st_y > 0, else 0
   const unsigned short* st_y;
   const unsigned short* st_c;
+  const unsigned short* st_add;  // optional second contribution, [M][N]
   const float* st_mean;
   const float* st_invstd;
   unsigned bytesA, bytesB;  // sizes of the A / B tensors: the bounds of their buffer descriptors

@@ -123,9 +123,10 @@ __device__ __forceinline__ int clamp_to(int x, int hi) { return x < 0 ? 0 : (x >
 
 template <int OP_ARG, int BM, int BN, int TBK, int NST, bool MASKA = false, int WGM = 2, int WGN = 2, bool GEN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
-  // the forward kernel with column sums in its epilogue (1), the backward-data kernel with batch-norm backward sums (2)
-  constexpr int STATS = OP_ARG == OP_FWD_STATS ? 1 : (OP_ARG == OP_BWD_DATA_STATS ? 2 : 0);
-  constexpr int OP = STATS == 1 ? OP_FWD : (STATS == 2 ? OP_BWD_DATA : OP_ARG);
+  // the forward kernel with column sums in its epilogue (1), the backward-data kernel with batch-norm backward sums (2),
+  // the same with the gradient of a residual block's end formed from the tile first (3)
+  constexpr int STATS = OP_ARG == OP_FWD_STATS ? 1 : (OP_ARG == OP_BWD_DATA_STATS ? 2 : (OP_ARG == OP_BWD_DATA_BLOCK_END ? 3 : 0));
+  constexpr int OP = STATS == 1 ? OP_FWD : (STATS >= 2 ? OP_BWD_DATA : OP_ARG);
   static_assert(TBK == 32 || TBK == 64, "k tile depth");
   static_assert(!GEN || OP != OP_BWD_WEIGHT, "backward-weight has no generic variant");
   constexpr bool A_KC = OP != OP_BWD_WEIGHT;  // A has k contiguous in memory

@@ -176,12 +176,14 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
   // STATS 1 (a batch normalization behind a forward convolution): sums of what is stored and of its squares.
   // STATS 2 (backward-data of a convolution whose input came out of batch normalization + ReLU): the sums that layer's
   // backward pass needs, sum g and sum g x^ with g = the stored gradient where the ReLU was open (st_y > 0), else 0.
+  // STATS 3 (backward-data whose output is one contribution to the gradient at the end of a residual block): what is
+  // stored is g = RNE16(tile [+ st_add]) where st_y > 0, else 0, and the sums are those of that g.
   static_assert(!STATS || LDS_BYTES >= 64 * NTHREADS, "the ring has to hold the partial sums");
   constexpr bool CAN_STATS = STATS != 0;
   constexpr bool stats = STATS != 0;
   float ssum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, ssq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float st_mu[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, st_is[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if constexpr (STATS == 2) {
+  if constexpr (STATS >= 2) {
     const int nn = n0 + cch * 8;  // N is a multiple of 8 in this mode
     if (nn < a.N) {
 #pragma unroll
@@ -221,12 +223,18 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
       if constexpr (stats) {
         const uint4 pk = *reinterpret_cast<const uint4*>(src);  // one 16-byte LDS read (columns beyond N hold zeros' worth
         const unsigned pw[4] = {pk.x, pk.y, pk.z, pk.w};          // of padding and are never written out)
-        unsigned yw[4] = {0u, 0u, 0u, 0u}, cw[4] = {0u, 0u, 0u, 0u};
-        if constexpr (STATS == 2) {  // the same 16 bytes of the normalization's output and input (no scatter in this mode)
+        unsigned yw[4] = {0u, 0u, 0u, 0u}, cw[4] = {0u, 0u, 0u, 0u}, dw[4] = {0u, 0u, 0u, 0u}, gw[4] = {0u, 0u, 0u, 0u};
+        if constexpr (STATS >= 2) {  // the same 16 bytes of the normalization's output and input (no scatter in this mode)
           const uint4 yq = *reinterpret_cast<const uint4*>(a.st_y + (size_t)m * a.N + n);
           const uint4 cq = *reinterpret_cast<const uint4*>(a.st_c + (size_t)m * a.N + n);
           yw[0] = yq.x; yw[1] = yq.y; yw[2] = yq.z; yw[3] = yq.w;
           cw[0] = cq.x; cw[1] = cq.y; cw[2] = cq.z; cw[3] = cq.w;
+          if constexpr (STATS == 3) {
+            if (a.st_add) {
+              const uint4 dq = *reinterpret_cast<const uint4*>(a.st_add + (size_t)m * a.N + n);
+              dw[0] = dq.x; dw[1] = dq.y; dw[2] = dq.z; dw[3] = dq.w;
+            }
+          }
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -243,10 +251,27 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
             _Float16 yv, cv;
             __builtin_memcpy(&yv, &yb, 2);
             __builtin_memcpy(&cv, &cb, 2);
-            const float g = (float)yv > 0.f ? v : 0.f;
+            float g = (float)yv > 0.f ? v : 0.f;
+            if constexpr (STATS == 3) {  // the sum of the two contributions is exact in FP32 and rounded once
+              const unsigned short db = (unsigned short)(e & 1 ? dw[e >> 1] >> 16 : dw[e >> 1] & 0xffffu);
+              _Float16 dv;
+              __builtin_memcpy(&dv, &db, 2);
+              const _Float16 gh = (_Float16)(v + (float)dv);
+              unsigned short gb;
+              __builtin_memcpy(&gb, &gh, 2);
+              if (!((float)yv > 0.f)) gb = 0;
+              gw[e >> 1] |= (unsigned)gb << ((e & 1) * 16);
+              _Float16 gm;
+              __builtin_memcpy(&gm, &gb, 2);
+              g = (float)gm;
+            }
             ssum[e] += g;
             ssq[e] += g * (((float)cv - st_mu[e]) * st_is[e]);
           }
+        }
+        if constexpr (STATS == 3) {  // g replaces the tile's values in the output
+          *reinterpret_cast<uint4*>(a.D16 + (size_t)m * a.N + n) = make_uint4(gw[0], gw[1], gw[2], gw[3]);
+          continue;
         }
       }
       size_t drow = (size_t)m;
@@ -461,7 +486,7 @@ int launch_op(const Plan& pl, hipStream_t st) {
   constexpr bool IS_FWD = OP == OP_FWD || OP == OP_FWD_STATS;
   if constexpr (OP == OP_FWD_STATS) {
     if (!pl.fast) return JZ_ERR_UNSUPPORTED;  // only the ring kernels come in this form
-  } else if constexpr (OP == OP_BWD_DATA_STATS) {
+  } else if constexpr (OP == OP_BWD_DATA_STATS || OP == OP_BWD_DATA_BLOCK_END) {
     if (!pl.fast || pl.gen || a.sc_on || a.splits != 1 || (a.N & 7) != 0) return JZ_ERR_UNSUPPORTED;
   } else {
     if (!pl.fast) return launch_one<OP, 128, 128>(a, st);
@@ -485,7 +510,7 @@ int launch_op(const Plan& pl, hipStream_t st) {
     }
     return JZ_ERR_UNSUPPORTED;  // the planner only offers the shapes above in this mode
   }
-  if constexpr (OP != OP_BWD_WEIGHT && OP != OP_BWD_DATA_STATS) {
+  if constexpr (OP != OP_BWD_WEIGHT && OP != OP_BWD_DATA_STATS && OP != OP_BWD_DATA_BLOCK_END) {
     if (pl.gen) {  // the planner offers the 4-wavefront 32-deep tiles in this mode
       if (pl.BM == 128 && pl.BN == 128) return launch_dma<OP, 128, 128, 32, 4, false, 2, 2, true>(a, st);
       if (pl.BM == 128 && pl.BN == 64) return launch_dma<OP, 128, 64, 32, 4, false, 2, 2, true>(a, st);

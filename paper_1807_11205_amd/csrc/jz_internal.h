@@ -33,6 +33,10 @@ struct BnBwdOperands {
   const void* y16;      // its output after the ReLU = the convolution's forward input
   const float* mean;    // [C]
   const float* invstd;  // [C]
+  // block end: y16 = relu(bn(x16) + shortcut) is a residual block's output and the convolution's result is one
+  // contribution to its gradient; what the convolution stores (and sums) is g = RNE16(result [+ add16]) where y16 > 0
+  bool block_end = false;
+  const void* add16 = nullptr;  // the other contribution, optional
 };
 int conv_bwd_data_stats_plan(const jz_conv_desc* d, size_t* conv_ws_bytes, int* tiles_m);
 int conv_bwd_data_run(const jz_conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, float* stats,

@@ -210,6 +210,22 @@ class ResNet50Chain:
                 op.joins_side = a.joins_side or b.joins_side
                 out.append(op)
                 i += 2
+            elif (a.kind == "conv_bwd_data" and b is not None and b.kind == "bn_bwd_block_end" and b.lane == a.lane == "main"
+                    and b.ins[2].data_ptr() == a.outs[0].data_ptr()):
+                # the first convolution of a block and the end of the block underneath: the convolution's result is one of the
+                # two contributions to that block's output gradient and is never stored
+                d = a.params["desc"]
+                dy, w = a.ins
+                x, y_out, _, dyb, gamma, mean, invstd = b.ins
+                g, dx, dgamma, dbeta = b.outs
+                self._ws_bytes = max(self._ws_bytes, api.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(d))
+                run = lambda stream=None, t=(d, dy, w, dyb, x, y_out, gamma, mean, invstd, g, dx, dgamma, dbeta): \
+                    api.jz_conv2d_bwd_data_block_end_bwd(*t, self.ws, stream)
+                op = Op("conv_bwd_data_block_end", a.name + " + " + b.name, dict(desc=d, rows=b.params["rows"], C=b.params["C"]),
+                        [dy, w, dyb, x, y_out, gamma, mean, invstd], [g, dx, dgamma, dbeta], run)
+                op.joins_side = a.joins_side or b.joins_side
+                out.append(op)
+                i += 2
             else:
                 out.append(a)
                 i += 1
@@ -344,6 +360,8 @@ class ResNet50Chain:
                             lambda stream=None, dx=dcur: api.jz_avgpool_bwd(N, HW, C, dpooled, dx, stream))])
         for seg in reversed(segments):
             self.bwd_ops.extend(seg)
+        if self.bwd_stats and self.block_end:     # pairs across block boundaries: a block's first convolution + the end of the block below
+            self.bwd_ops = self._fuse_bwd_pairs(self.bwd_ops)
         if not self.proj_side:     # the projection branches stay on the main stream, their weight gradients go with the others
             for o in self.fwd_ops + self.bwd_ops:
                 if o.lane == "proj":

@@ -107,6 +107,33 @@ def check_op(op, counts, check_conv=True):
             assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor)), what
         counts["conv_bwd_data"] = counts.get("conv_bwd_data", 0) + 1
         counts["bn_bwd"] = counts.get("bn_bwd", 0) + 1
+    elif k == "conv_bwd_data_block_end":
+        # ins: dy, w, dyb, bn x, y_out, gamma, mean, invstd; outs: g, dx, dgamma, dbeta.  The convolution's own result is
+        # never stored, so g is compared with what the oracle makes of the oracle's convolution: equal bits except where the
+        # convolution's FP16 rounding fell the other way (at most one FP16 step of the sum, on a small share of the elements)
+        d = p["desc"]
+        od = oracle.conv_desc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
+        rows, C = p["rows"], p["C"]
+        if check_conv:
+            dxa64 = oracle.conv_bwd_data(od, ins[0], ins[1])
+            dxa16 = np.asarray(dxa64, np.float64).astype(np.float16).ravel()
+            tot = oracle.add_fwd(dxa16, ins[2], relu=False)[1] if ins[2] is not None else dxa16
+            g_ref = oracle.relu_bwd(ins[4], tot)
+            mask = ins[4].ravel() > 0
+            assert np.array_equal(outs[0].ravel()[~mask].view(np.uint16), np.zeros(int((~mask).sum()), np.uint16)), what
+            exact64 = (np.asarray(dxa64, np.float64).ravel() + (ins[2].astype(np.float64).ravel() if ins[2] is not None else 0.0)) * mask
+            jzt.check_half_output(outs[0], exact64, tol=1e-3, what=what)
+            assert np.mean(outs[0].ravel().view(np.uint16) != g_ref.ravel().view(np.uint16)) <= 0.02, what
+        x, g = ins[3].reshape(rows, C), outs[0].reshape(rows, C)
+        dx64, _, dg64, db64, _, _ = oracle.bn_relu_bwd(x, None, g, ins[5], ins[6], ins[7], relu=False)
+        assert rel_l2(outs[1], dx64) <= 1e-3, what
+        rms = float(np.sqrt(np.mean(g.astype(np.float64) ** 2)))
+        floor = np.sqrt(rows) * rms * 2.5e-3 + 2.0 ** -24
+        for got, ref in ((outs[2], dg64), (outs[3], db64)):
+            err = np.abs(got.astype(np.float64) - ref)
+            assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor)), what
+        counts["conv_bwd_data"] = counts.get("conv_bwd_data", 0) + 1
+        counts["bn_bwd_block_end"] = counts.get("bn_bwd_block_end", 0) + 1
     elif k == "add_fwd":
         assert np.array_equal(outs[0].view(np.uint16), oracle.add_fwd(ins[0], ins[1], relu=p["relu"])[1].view(np.uint16)), what
     elif k == "relu_bwd":
@@ -182,6 +209,7 @@ def test_every_launch_of_a_chained_step_against_the_oracle(jz, fused, block_end,
     assert counts.get("conv_bn_fwd", 0) + counts.get("conv_fwd", 0) == 53 and counts.get("conv_fwd", 0) == counts.get("bn_fwd", 0)
     assert counts["conv_bwd_weight"] == 53 and counts["conv_bwd_data"] == 52
     assert counts.get("conv_bwd_data_bn_bwd", 0) == (32 if bwd_stats else 0)    # the a and b layers of the 16 blocks
+    assert counts.get("conv_bwd_data_block_end", 0) == (15 if bwd_stats and block_end else 0)   # every block end but the last
     assert counts["bn_bwd"] + counts.get("bn_bwd_block_end", 0) == 53 and counts["add_fwd"] == (1 if fused else 32)
     assert counts.get("relu_bwd", 0) + counts.get("relu_bwd_sum", 0) + counts.get("bn_bwd_block_end", 0) == 16
     assert counts.get("bn_bwd_block_end", 0) == (16 if block_end else 0) and counts.get("relu_bwd_sum", 0) == (15 if fused and not block_end else 0)
@@ -259,7 +287,7 @@ def test_full_size_chained_step_on_sampled_outputs(jz):
     odesc = lambda d: oracle.conv_desc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
 
     # (a) sampled convolution outputs: forward (inside the fused call), backward-data, backward-weight
-    for name in ("stem", "s2b1c", "s2b1p", "s3b1a", "s4b3b", "s5b3c"):
+    for name in ("stem", "s2b1c", "s2b1p", "s3b1a", "s4b2a", "s4b3b", "s5b3c"):
         op = ops[("conv_bn_fwd", name)]
         d = op.params["desc"]
         x, w, c = np16(op.ins[0]), np16(op.ins[1]), np16(op.outs[0])
@@ -271,16 +299,26 @@ def test_full_size_chained_step_on_sampled_outputs(jz):
         jzt.check_half_output(np16(ow.outs[0]), oracle.conv_bwd_weight(odesc(d), xw, dyw), 1e-3, "bwd_weight " + name,
                               mag64=oracle.conv_bwd_weight(odesc(d), jzt.abs16(xw), jzt.abs16(dyw)))
         if name != "stem":
-            od_ = ops.get(("conv_bwd_data", name)) or next(o for o in net.trace if o.kind == "conv_bwd_data_bn_bwd" and o.name.startswith(name + " + "))
+            od_ = ops.get(("conv_bwd_data", name)) or next(o for o in net.trace if o.kind in ("conv_bwd_data_bn_bwd", "conv_bwd_data_block_end")
+                                                           and o.name.startswith(name + " + "))
             dx = np16(od_.outs[0])
             idx = rng.integers(0, dx.size, size=8192)
             gy, ww = np16(od_.ins[0]), np16(od_.ins[1])
-            jzt.check_half_output(dx[idx], oracle.conv_bwd_data_at(odesc(d), gy, ww, idx), 1e-3, "bwd_data " + name,
-                                  mag64=oracle.conv_bwd_data_at(odesc(d), jzt.abs16(gy), jzt.abs16(ww), idx))
+            ref = oracle.conv_bwd_data_at(odesc(d), gy, ww, idx)
+            if od_.kind == "conv_bwd_data_block_end":
+                # the convolution's result exists only inside g = relu-masked (result + the shortcut's contribution): two
+                # roundings to FP16, so the norm-wise bar only
+                ref = (ref + np16(od_.ins[2])[idx].astype(np.float64)) * (np16(od_.ins[4])[idx] > 0)
+                jzt.check_half_output(dx[idx], ref, 1e-3, "bwd_data + block end " + name)
+            else:
+                jzt.check_half_output(dx[idx], ref, 1e-3, "bwd_data " + name,
+                                      mag64=oracle.conv_bwd_data_at(odesc(d), jzt.abs16(gy), jzt.abs16(ww), idx))
 
     # (b) whole tensors of the cheap layers (per-image layers on the first images, where the oracle loops in Python)
     counts = {}
-    for key in (("bn_bwd_block_end", "s4b6c.bn"), ("bn_bwd_block_end", "s5b3c.bn"), ("add_fwd", "s2b1.dx"), ("avgpool_fwd", "pool5"), ("avgpool_bwd", "pool5"),
+    fused_end = next(o for o in net.trace if o.kind == "conv_bwd_data_block_end" and o.name.endswith(" + s4b6c.bn"))
+    check_op(fused_end, counts, check_conv=False)       # (g of such calls is sampled under (a): s3b1a through the in-place pass, s4b2a from the epilogue)
+    for key in (("bn_bwd_block_end", "s5b3c.bn"), ("add_fwd", "s2b1.dx"), ("avgpool_fwd", "pool5"), ("avgpool_bwd", "pool5"),
                 ("bias_add", "fc.b"), ("bias_grad", "fc.b"), ("softmax_xent", "loss"), ("fc_fwd", "fc"), ("fc_bwd_data", "fc"), ("fc_bwd_weight", "fc")):
         check_op(ops[key], counts)
     mp, mb = ops[("maxpool_fwd", "pool1")], ops[("maxpool_bwd", "pool1")]

@@ -1,6 +1,8 @@
 """GPU parity of jz_conv2d_bwd_data_bn_relu_bwd (backward-data convolution with the statistics of the batch-norm
 backward underneath it taken in the convolution's epilogue): dz must be the bits jz_conv2d_bwd_data writes, and
 dx / dgamma / dbeta must meet the bars of the stand-alone batch-norm backward against the oracle evaluated on that dz.
+jz_conv2d_bwd_data_block_end_bwd (the same at the end of a residual block): g must be the bits the oracle's add and ReLU
+gradient make of jz_conv2d_bwd_data's output, the rest as above for dy = g.
 The normalization's forward tensors (y, mean, invstd) come from the oracle, so nothing the call reads was produced by
 the library.  Every kernel variant is forced through the planner's tuning hook; shapes whose kernel cannot leave the
 sums (split reduction, strided scatter form) must give the same results through the statistics pass."""
@@ -66,6 +68,51 @@ def run_case(jz, N, H, C, K, R, stride, pad, key=0, eps=1e-5, variant=None, spli
     return jz.jz_conv2d_describe_plan(jz.JZ_BWD_DATA, d)
 
 
+def run_block_end(jz, N, H, C, K, R, stride, pad, key=0, eps=1e-5, variant=None, splits=1, second=True):
+    import jzt
+    d = jz.conv_desc(N, H, H, C, K, R, R, stride, pad)
+    if variant is not None:
+        with jzt.forced_variant(d, *variant, splits=splits, ops=(jz.JZ_BWD_DATA,)):
+            return run_block_end(jz, N, H, C, K, R, stride, pad, key, eps, second=second)
+    rng = inputs.rng_for(47, key, N, H, C, K, R)
+    rows = N * H * H
+    c = (rng.standard_normal((rows, C), dtype=np.float32) * np.float32(1.5) + np.float32(0.5) *
+         rng.standard_normal(C, dtype=np.float32)).astype(np.float16)
+    gamma = (1.0 + 0.3 * rng.standard_normal(C, dtype=np.float32)).astype(np.float32)
+    beta = (0.2 * rng.standard_normal(C, dtype=np.float32)).astype(np.float32)
+    shortcut = inputs.normal_f16(rng, (rows, C), std=1.0)
+    _, y16, m64, i64 = oracle.bn_add_relu_fwd(c, shortcut, gamma, beta, eps, relu=True)     # the block's output
+    mean, invstd = m64.astype(np.float32), i64.astype(np.float32)
+    w = inputs.normal_f16(rng, (K * R * R * C,), std=(2.0 / (R * R * C)) ** 0.5)
+    dy = inputs.normal_f16(rng, (N * d.P * d.Q * K,), std=4.0)
+    dyb = inputs.normal_f16(rng, (rows * C,), std=3.0) if second else None
+    DY, W, CX, Y = jzt.to_dev(dy), jzt.to_dev(w), jzt.to_dev(c.ravel()), jzt.to_dev(np.ascontiguousarray(y16).ravel())
+    G, M, I = jzt.to_dev(gamma), jzt.to_dev(mean), jzt.to_dev(invstd)
+    DYB = jzt.to_dev(dyb) if second else None
+    dxa = torch.empty(rows * C, dtype=torch.float16, device="cuda")
+    ws0 = torch.zeros(max(jz.jz_conv2d_workspace_bytes(jz.JZ_BWD_DATA, d), 16), dtype=torch.uint8, device="cuda")
+    jz.bind_conv2d(jz.JZ_BWD_DATA, d, DY, W, dxa, ws0)()
+    nan16 = lambda n: torch.full((n,), float("nan"), dtype=torch.float16, device="cuda")
+    g, dx, dg, db = nan16(rows * C), nan16(rows * C), nan16(C), nan16(C)
+    ws = torch.full((max(jz.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(d), 16),), 0xCD, dtype=torch.uint8, device="cuda")
+    jz.jz_conv2d_bwd_data_block_end_bwd(d, DY, W, DYB, CX, Y, G, M, I, g, dx, dg, db, ws)
+    torch.cuda.synchronize()
+    dxa_np = dxa.cpu().numpy()
+    tot = oracle.add_fwd(dxa_np, dyb, relu=False)[1] if second else dxa_np
+    g16 = oracle.relu_bwd(np.ascontiguousarray(y16).ravel(), tot)
+    g_np = g.cpu().numpy()
+    assert np.array_equal(g_np.view(np.uint16), g16.view(np.uint16)), "g differs from add + ReLU gradient of jz_conv2d_bwd_data's output"
+    g2 = g16.reshape(rows, C)
+    dx64, _, dg64, db64, _, _ = oracle.bn_relu_bwd(c, None, g2, gamma, mean, invstd, relu=False)
+    assert jzt.rel_l2(dx.cpu().numpy(), dx64) <= 1e-3
+    rms = float(np.sqrt(np.mean(g2.astype(np.float64) ** 2)))
+    floor = np.sqrt(rows) * rms * 2.5e-3 + 2.0 ** -24
+    for got, ref in ((dg.cpu().numpy(), dg64), (db.cpu().numpy(), db64)):
+        err = np.abs(got.astype(np.float64) - ref)
+        assert np.all(err <= 2e-3 * np.maximum(np.abs(ref), floor)), float(np.max(err / np.maximum(np.abs(ref), floor)))
+    return jz.jz_conv2d_describe_plan(jz.JZ_BWD_DATA, d)
+
+
 SHAPES = [
     (2, 14, 64, 64, 3, 1, 1),        # 392 rows: ragged against every tile height
     (3, 9, 96, 32, 3, 1, 1),         # C not a multiple of 64
@@ -84,6 +131,12 @@ def test_fused_backward_statistics_against_the_oracle(jz, N, H, C, K, R, stride,
     run_case(jz, N, H, C, K, R, stride, pad, key=5, dead_channels=8)
 
 
+@pytest.mark.parametrize("N,H,C,K,R,stride,pad", SHAPES)
+def test_block_end_form_against_the_oracle(jz, N, H, C, K, R, stride, pad):
+    run_block_end(jz, N, H, C, K, R, stride, pad)
+    run_block_end(jz, N, H, C, K, R, stride, pad, key=5, second=False)
+
+
 @pytest.mark.parametrize("variant", [(128, 128, 32, 4, 4), (128, 64, 32, 4, 4), (64, 128, 32, 4, 3), (64, 64, 64, 4, 4),
                                      (128, 128, 64, 4, 4), (256, 128, 32, 8, 4), (256, 128, 64, 8, 3), (256, 256, 32, 8, 4),
                                      (128, 128, 32, 8, 3), (128, 128, 64, 8, 4)], ids=lambda v: "x".join(str(i) for i in v))
@@ -91,10 +144,13 @@ def test_every_kernel_variant_leaves_the_same_sums(jz, variant):
     plan = run_case(jz, 5, 24, 192, 64, 3, 1, 1, key=1, variant=variant)       # 2880 rows: 22.5 tiles of 128, 11.25 of 256
     assert "tile %dx%dx%d" % variant[:3] in plan, plan
     run_case(jz, 2, 10, 72, 128, 1, 1, 0, key=2, variant=variant)              # 200 rows, 72 channels: ragged both ways
+    run_block_end(jz, 3, 20, 256, 64, 1, 1, 0, key=3, variant=variant)         # 1200 rows of a block's first 1x1 layer
+    run_block_end(jz, 2, 10, 72, 128, 1, 1, 0, key=4, variant=variant)
 
 
 def test_split_reduction_falls_back_to_the_statistics_pass(jz):
     run_case(jz, 2, 14, 64, 256, 3, 1, 1, key=3, variant=(128, 64, 32, 4, 4), splits=3)
+    run_block_end(jz, 2, 14, 64, 256, 3, 1, 1, key=3, variant=(128, 64, 32, 4, 4), splits=3)
 
 
 def test_two_runs_agree_bit_for_bit(jz):
