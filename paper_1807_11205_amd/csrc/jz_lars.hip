@@ -415,9 +415,24 @@ __global__ __launch_bounds__(LARS_THREADS) void lars_begin(Tables tb, const floa
   // Loads that go past the compute unit's own cache: in the fresh case a partial sum written above may share a cache
   // line with a neighbouring tensor's, which another workgroup on this compute unit may have pulled in before the write.
   double sw = 0.0;
-  for (int c = c0 + (int)threadIdx.x; c < c1; c += LARS_THREADS)
-    sw += __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(tb.psum_w + c),
-                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  if (have_w) {
+    // carried sums, written by an earlier launch: plain loads, eight requested together, added in the same order as below
+    for (int c = c0 + (int)threadIdx.x; c < c1; c += 8 * LARS_THREADS) {
+      double v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int cu = c + u * LARS_THREADS;
+        v[u] = tb.psum_w[cu < c1 ? cu : c];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (c + u * LARS_THREADS < c1) sw += v[u];
+    }
+  } else {
+    for (int c = c0 + (int)threadIdx.x; c < c1; c += LARS_THREADS)
+      sw += __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(tb.psum_w + c),
+                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  }
   sw = block_sum(sw, red);
   if (threadIdx.x == 0) tb.wsum[t] = sw;
 }
