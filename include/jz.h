@@ -78,7 +78,8 @@ int jz_conv2d_fwd(const jz_conv_desc* desc, const void* x16, const void* w16, vo
  *   dx[n,h,w,c] = RNE16( sum over (p,q,k,r,s) with p*stride_h - pad_h + r == h and q*stride_w - pad_w + s == w
  *                        of dy[n,p,q,k] * w[k,r,s,c] ),
  * input pixels no output reads get 0.
- * dy16: in [N,P,Q,K] fp16 (loss-scaled); w16: in [K,R,S,C]; dx16: out [N,H,W,C] fp16, fully overwritten. */
+ * dy16: in [N,P,Q,K] fp16 (loss-scaled); w16: in [K,R,S,C]; dx16: out [N,H,W,C] fp16, fully overwritten.
+ * A strided layer with a filter of more than one tap needs workspace (a repacked copy of the filter). */
 int jz_conv2d_bwd_data(const jz_conv_desc* desc, const void* dy16, const void* w16, void* dx16, void* ws,
                        size_t ws_bytes, void* hip_stream);
 
@@ -403,7 +404,9 @@ int jz_conv2d_describe_plan(int op, const jz_conv_desc* desc, char* text, size_t
  * choices and of the cost model; nothing else overrides the planner (the library reads no environment variables).
  * The variant must be one the library has (jz_conv2d_describe_plan shows the names: e.g. 128x128 tile, k tile 64,
  * 8 wavefronts, ring 4), else JZ_ERR_UNSUPPORTED; shapes that gather with per-load tap arithmetic take the four
- * 4-wavefront tiles, 32 deep, ring 4; shapes on the element-wise kernel cannot be tuned (JZ_ERR_UNSUPPORTED).
+ * 4-wavefront tiles, 32 deep, ring 4; a strided multi-tap backward-data layer, which runs as one launch per parity
+ * class of its stride, takes the variant for every one of those launches (never split); shapes on the element-wise
+ * kernel cannot be tuned (JZ_ERR_UNSUPPORTED).
  * Results never depend on the choice beyond the summation order of the reduction.
  * jz_conv2d_tune_use_table(0) makes the planner skip its built-in table of measured choices (cost model only),
  * jz_conv2d_tune_use_table(1) restores it.  jz_conv2d_tune_clear forgets every recorded choice and restores the

@@ -288,6 +288,8 @@ size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 // caches; the fixed part is kept the same for all variants (per-variant fits of it were noise and chose worse).  The
 // 4-wavefront variants run two workgroups per compute unit (512 resident), the 8-wavefront ones a single workgroup
 // that owns the whole LDS (256 resident); the latter win when the grid cannot fill 512 slots anyway.
+constexpr int kMaxClasses = 16;  // parity classes of a stride (sh * sw) the backward-data decomposition handles
+
 struct Variant {
   int BM, BN, bk, waves, resident;
   double tt[3];  // per k tile: forward, backward-data, backward-weight
@@ -445,7 +447,7 @@ void plan_text(const Plan& pl, char* buf, size_t n) {
            a.N, a.Kred, pl.fast ? "vector" : "element-wise", pl.BM, pl.BN, pl.bk, pl.fast ? pl.waves : 4,
            pl.fast ? pl.nst : 2, a.tiles_m, a.tiles_n,
            a.splits, a.kt_per_split, pl.packed ? ", 4-channel padded copy" : "",
-           a.sc_on ? ", scatter epilogue" : pl.gen ? ", per-load tap arithmetic" : "");
+           a.sc_on ? ", scatter epilogue" : pl.classes ? ", one launch per parity class of the stride" : pl.gen ? ", per-load tap arithmetic" : "");
 }
 
 int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
@@ -497,7 +499,8 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
     pl->fast = d->K % 8 == 0 && d->C % 8 == 0;
     pl->bytesA = 2 * ny; pl->bytesB = 2 * nx; pl->bytesD = 2 * nw;  // A = dy, B = x
   }
-  a.sc_on = 0; a.sc_H = a.sc_W = 0; a.sc_sh = a.sc_sw = 1;
+  a.sc_on = 0; a.sc_H = a.sc_W = 0; a.sc_sh = a.sc_sw = 1; a.sc_oh = a.sc_ow = 0; a.sc_fill = 0;
+  g.always_mask = 0;
   a.bw_linear = (op == JZ_BWD_WEIGHT && d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 &&
                  d->pad_w == 0) ? 1 : 0;
   if (op == JZ_BWD_DATA && pl->fast && d->R == 1 && d->S == 1 && d->pad_h == 0 && d->pad_w == 0 &&
@@ -506,7 +509,7 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
     // runs over the N*P*Q output pixels as a stride-1 problem and the epilogue scatters its rows (and the zeros)
     a.M = d->N * P * Q;
     g.OH = P; g.OW = Q; g.sh = 1; g.sw = 1;
-    a.sc_on = 1; a.sc_H = d->H; a.sc_W = d->W; a.sc_sh = d->stride_h; a.sc_sw = d->stride_w;
+    a.sc_on = 1; a.sc_H = d->H; a.sc_W = d->W; a.sc_sh = d->stride_h; a.sc_sw = d->stride_w; a.sc_fill = 1;
   }
   g.row_pitch = g.IW * g.IC;
   g.pix_step = g.IC;
@@ -550,7 +553,77 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   const size_t part = a.splits > 1 ? (size_t)a.splits * a.M * a.N * sizeof(float) : 0;
   pl->part_offset = pl->packed ? pl->xp_bytes + pl->wp_bytes : 0;
   pl->ws_bytes = pl->part_offset + part;
+  // Strided multi-tap backward-data: input pixel (h, w) only meets the taps r = (h + ph) mod sh (+ sh, + 2 sh, ...) and
+  // likewise along w, so the pixels of one parity class (h mod sh, w mod sw) form a unit-stride backward-data problem
+  // on the dy grid with the filter's taps of that class: sh * sw launches of the mask kernels that together do the
+  // useful multiply-adds only (the per-load variant fetches and masks every tap for every pixel: sh * sw times the work).
+  // Every class needs a tap (R >= sh, S >= sw); the class filters are packed into the workspace by one small launch.
+  pl->classes = pl->gen && op == JZ_BWD_DATA && (d->stride_h > 1 || d->stride_w > 1) && d->R >= d->stride_h &&
+                d->S >= d->stride_w && d->stride_h * d->stride_w <= kMaxClasses &&
+                ((d->R + d->stride_h - 1) / d->stride_h) * ((d->S + d->stride_w - 1) / d->stride_w) <= 32;
+  if (pl->classes) pl->ws_bytes = up256((size_t)nw * 2);
   return JZ_OK;
+}
+
+// One parity class (ca, cb) of a strided multi-tap backward-data layer as a plan of its own (see make_plan).  base: the
+// layer's plan; w_off: where this class's packed filter starts in the workspace (elements); false: the class has no pixels.
+bool make_class_plan(const jz_conv_desc* d, const Plan& base, int ca, int cb, Plan* pl, size_t* w_elems) {
+  const int sh = d->stride_h, sw = d->stride_w;
+  const int P = out_dim(d->H, d->pad_h, d->R, sh), Q = out_dim(d->W, d->pad_w, d->S, sw);
+  const int Ha = (d->H - ca + sh - 1) / sh, Wb = (d->W - cb + sw - 1) / sw;     // pixels h = ca + sh i, w = cb + sw l
+  const int r0 = (ca + d->pad_h) % sh, s0 = (cb + d->pad_w) % sw;               // first tap of the class
+  const int Ra = (d->R - r0 + sh - 1) / sh, Sb = (d->S - s0 + sw - 1) / sw;     // taps r0 + sh j, s0 + sw i
+  *w_elems = (size_t)d->K * Ra * Sb * d->C;
+  if (Ha <= 0 || Wb <= 0) return false;
+  *pl = base;
+  pl->gen = false;
+  pl->classes = false;
+  GemmArgs& a = pl->args;
+  ConvGeom& g = a.g;
+  a.M = d->N * Ha * Wb; a.N = d->C; a.Kred = Ra * Sb * d->K;
+  g.IH = P; g.IW = Q; g.IC = d->K; g.OH = Ha; g.OW = Wb;
+  g.R = Ra; g.S = Sb; g.sh = 1; g.sw = 1;
+  g.ph = (ca + d->pad_h) / sh; g.pw = (cb + d->pad_w) / sw;   // dy row of tap j for pixel row i: i + ph - j
+  g.row_pitch = Q * d->K; g.pix_step = d->K; g.s_step = d->K;
+  g.kvalid = 0;
+  g.always_mask = 1;   // the class grid and the dy grid are not tied by the usual size formula
+  a.sc_on = 1; a.sc_H = d->H; a.sc_W = d->W; a.sc_sh = sh; a.sc_sw = sw; a.sc_oh = ca; a.sc_ow = cb; a.sc_fill = 0;
+  a.bw_linear = 0;
+  finish_geometry(g);
+  pl->bytesB = *w_elems * 2;
+  pl->bk = 32;
+  choose_tiling(pl, d->K % 64 == 0, 0);
+  pl->part_offset = 0;
+  pl->ws_bytes = 0;
+  return true;
+}
+
+// class filters: wp[class][k][j][i][c] = w[k][r0 + sh j][s0 + sw i][c], classes in (ca, cb) row-major order
+__global__ __launch_bounds__(256) void pack_class_filters(const unsigned short* __restrict__ w, unsigned short* __restrict__ wp,
+                                                          int K, int R, int S, int C, int sh, int sw, int ph, int pw) {
+  const long long n = (long long)K * R * S * C;
+  for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (long long)gridDim.x * 256) {
+    const int c = (int)(idx % C);
+    long long t = idx / C;
+    const int s_ = (int)(t % S); t /= S;
+    const int r = (int)(t % R);
+    const int k = (int)(t / R);
+    // the class this tap belongs to: r = (ca + ph) mod sh  <=>  ca = (r - ph) mod sh
+    const int ca = ((r - ph) % sh + sh) % sh, cb = ((s_ - pw) % sw + sw) % sw;
+    const int r0 = (ca + ph) % sh, s0 = (cb + pw) % sw;
+    const int j = (r - r0) / sh, i = (s_ - s0) / sw;
+    // offset of the class: the filters of all classes before it
+    long long off = 0;
+    for (int a2 = 0; a2 < sh; ++a2)
+      for (int b2 = 0; b2 < sw; ++b2) {
+        if (a2 * sw + b2 >= ca * sw + cb) break;
+        const int rr = (a2 + ph) % sh, ss = (b2 + pw) % sw;
+        off += (long long)K * ((R - rr + sh - 1) / sh) * ((S - ss + sw - 1) / sw) * C;
+      }
+    const int Ra = (R - r0 + sh - 1) / sh, Sb = (S - s0 + sw - 1) / sw;
+    (void)Ra;
+    wp[off + (((long long)k * ((R - r0 + sh - 1) / sh) + j) * Sb + i) * C + c] = w[idx];
+  }
 }
 
 // a forward plan whose kernel can leave the per-tile column sums: the ring kernels (their LDS holds the sums), no split
@@ -581,6 +654,36 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
                           overlaps(ws, pl.ws_bytes, D, pl.bytesD)))
     return JZ_ERR_ALIAS;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (pl.classes) {  // strided multi-tap backward-data: pack the class filters, then one unit-stride launch per class
+    unsigned short* wp = static_cast<unsigned short*>(ws);
+    const long long nwl = (long long)d->K * d->R * d->S * d->C;
+    const unsigned pgrid = (unsigned)((nwl + 255) / 256 < 2048 ? (nwl + 255) / 256 : 2048);
+    hipLaunchKernelGGL(pack_class_filters, dim3(pgrid), dim3(256), 0, st, static_cast<const unsigned short*>(B), wp, d->K, d->R, d->S,
+                       d->C, d->stride_h, d->stride_w, d->pad_h, d->pad_w);
+    if ((rc = jz::launch_status()) != JZ_OK) return rc;
+    size_t w_off = 0;
+    for (int ca = 0; ca < d->stride_h; ++ca)
+      for (int cb = 0; cb < d->stride_w; ++cb) {
+        Plan cp;
+        size_t w_elems = 0;
+        const bool any = make_class_plan(d, pl, ca, cb, &cp, &w_elems);
+        if (any) {
+          GemmArgs& c = cp.args;
+          c.A = static_cast<const unsigned short*>(A);
+          c.B = wp + w_off;
+          c.D16 = static_cast<unsigned short*>(D);
+          c.bytesA = (unsigned)pl.bytesA;
+          c.bytesB = (unsigned)(w_elems * 2);
+          c.Dpart = nullptr;
+          c.stats = nullptr;
+          c.st_y = c.st_c = c.st_add = nullptr;
+          c.st_mean = c.st_invstd = nullptr;
+          if ((rc = launch_bwd_data(cp, st)) != JZ_OK) return rc;
+        }
+        w_off += w_elems;
+      }
+    return JZ_OK;
+  }
   GemmArgs& a = pl.args;
   a.A = static_cast<const unsigned short*>(A);
   a.B = static_cast<const unsigned short*>(B);
@@ -702,6 +805,16 @@ extern "C" int jz_conv2d_describe_plan(int op, const jz_conv_desc* desc, char* t
   Plan pl;
   int rc = make_plan(op, desc, &pl);
   if (rc != JZ_OK) return rc;
+  if (pl.classes) {  // the launches of the parity classes: the first class stands for all (same filter shape up to a tap row / column)
+    Plan cp;
+    size_t w_elems;
+    if (make_class_plan(desc, pl, 0, 0, &cp, &w_elems)) {
+      cp.classes = true;
+      cp.args.sc_on = 0;
+      plan_text(cp, text, text_bytes);
+      return JZ_OK;
+    }
+  }
   plan_text(pl, text, text_bytes);
   return JZ_OK;
 }
@@ -716,6 +829,25 @@ extern "C" int jz_conv2d_tune_set(int op, const jz_conv_desc* desc, int tile_m, 
   for (const Variant& c : kVariants)
     if (c.BM == tile_m && c.BN == tile_n && c.bk == k_tile && c.waves == wavefronts && c.nst == ring) v = &c;
   if (!v) return JZ_ERR_UNSUPPORTED;
+  if (pl.classes) {  // the variant goes to every parity class's launch (their reductions are never split)
+    std::vector<Tuned> keys;
+    for (int ca = 0; ca < desc->stride_h; ++ca)
+      for (int cb = 0; cb < desc->stride_w; ++cb) {
+        Plan cp;
+        size_t w_elems;
+        if (!make_class_plan(desc, pl, ca, cb, &cp, &w_elems)) continue;
+        const GemmArgs& a = cp.args;
+        keys.push_back(Tuned{1, a.M, a.N, a.Kred, a.g.R * a.g.S, a.sc_on, tile_m, tile_n, k_tile, wavefronts, ring, 1});
+      }
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    for (const Tuned& t : keys) {
+      bool found = false;
+      for (Tuned& e : g_tune_rt)
+        if (same_key(e, t)) { e = t; found = true; }
+      if (!found) g_tune_rt.push_back(t);
+    }
+    return JZ_OK;
+  }
   // per-load tap arithmetic exists for the four basic 4-wavefront tiles, 32 deep, four-stage ring
   if (pl.gen && (v->waves != 4 || v->bk != 32 || v->nst != 4 || v->BM > 128 || v->BN > 128)) return JZ_ERR_UNSUPPORTED;
   // the small-channel path runs the 4-wavefront kernels of the four basic tiles at its own k tile depth only

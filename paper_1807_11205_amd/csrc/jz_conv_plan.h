@@ -13,6 +13,7 @@ struct Plan {
   bool fast = false;    // vector (16-byte) operand access possible
   bool packed = false;  // small-channel layer run on a 4-channel padded copy
   bool gen = false;     // gather with per-load tap arithmetic (more than 32 taps, strided multi-tap backward-data)
+  bool classes = false; // strided multi-tap backward-data as one unit-stride launch per parity class of the stride
   int BM = 128, BN = 128;
   int bk = 64;  // k tile depth of the kernel that will run
   int waves = 4, nst = 4;  // wavefronts per workgroup and ring depth (large tiles come in several variants)

@@ -50,6 +50,7 @@ struct ConvGeom {
   // there IC is the length of that run (the k tile), S = 1, pix_step = 4 and runs of neighbouring pixels overlap.
   int row_pitch, pix_step, s_step;
   int kvalid;  // small-channel forward only: elements of a k tile beyond this are not part of the filter row
+  int always_mask;  // build the per-row tap masks even for a single unpadded tap (grids whose sizes are not tied by a stride)
   unsigned tap_rep;  // bit r * S set for every filter row r (when R * S <= 32): spreads a column mask over the rows
   FastDiv d_ohow, d_ow, d_ic, d_s, d_sh, d_sw;
 };
@@ -78,8 +79,10 @@ struct GemmArgs {
   int splits;
   int tiles_m, tiles_n;
   FastDiv d_tiles_mn, d_tiles_n;  // workgroup id -> (split, tile row, tile column) without integer division code
-  // strided 1x1 backward-data: output row m = (n,p,q) is written to pixel (n, p*sc_sh, q*sc_sw) of an sc_H x sc_W image
-  int sc_on, sc_H, sc_W, sc_sh, sc_sw;
+  // strided backward-data: output row m = (n,p,q) is written to pixel (n, p*sc_sh + sc_oh, q*sc_sw + sc_ow) of an
+  // sc_H x sc_W image; sc_fill: the other pixels of each sc_sh x sc_sw cell receive zeros (strided 1x1 layers, where no
+  // output pixel reads them); without it the launch is one of sc_sh * sc_sw that cover the image between them
+  int sc_on, sc_H, sc_W, sc_sh, sc_sw, sc_oh, sc_ow, sc_fill;
   // backward-weight of a 1x1 unit-stride unpadded layer: reduction row j (a pixel) of x starts at j * IC, no gather
   int bw_linear;
   ConvGeom g;

@@ -245,7 +245,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(GemmArgs a) {
     const unsigned k2 = Pn - (unsigned)g.OH * Ph;               // a carry out of the row digit
     // a single unpadded tap is always inside, and so is every tap of a forward pass without padding
     // ((OH - 1) sh + R <= IH)
-    const bool masks = g.ph != 0 || g.pw != 0 || (OP == OP_BWD_DATA && g.R * g.S > 1);
+    const bool masks = g.ph != 0 || g.pw != 0 || (OP == OP_BWD_DATA && g.R * g.S > 1) || g.always_mask != 0;
     const unsigned full = g.S >= 32 ? OOB : (1u << g.S) - 1u;
 
     int m = m0 + kc_row;

@@ -275,14 +275,14 @@ __device__ __forceinline__ void igemm_epilogue_impl(const GemmArgs& a, f32x16 (&
         }
       }
       size_t drow = (size_t)m;
-      if (a.sc_on) {  // row m = (n, p, q) of the strided grid goes to input pixel (n, p * sh, q * sw)
+      if (a.sc_on) {  // row m = (n, p, q) of the strided grid goes to input pixel (n, p * sh + oh, q * sw + ow)
         unsigned nimg = fd_div((unsigned)m, a.g.d_ohow);
         unsigned rem = (unsigned)m - nimg * (unsigned)(a.g.OH * a.g.OW);
         unsigned p = fd_div(rem, a.g.d_ow);
         unsigned q = rem - p * (unsigned)a.g.OW;
-        drow = ((size_t)nimg * a.sc_H + p * a.sc_sh) * a.sc_W + q * a.sc_sw;
-        // the other pixels of this sh x sw cell are read by no output pixel: their gradient is zero
-        for (int i2 = 0; i2 < a.sc_sh; ++i2)
+        drow = ((size_t)nimg * a.sc_H + p * a.sc_sh + a.sc_oh) * a.sc_W + q * a.sc_sw + a.sc_ow;
+        // strided 1x1: the other pixels of this sh x sw cell are read by no output pixel: their gradient is zero
+        for (int i2 = 0; a.sc_fill && i2 < a.sc_sh; ++i2)
           for (int j2 = 0; j2 < a.sc_sw; ++j2) {
             if ((i2 | j2) == 0 || (int)(p * a.sc_sh) + i2 >= a.sc_H || (int)(q * a.sc_sw) + j2 >= a.sc_W) continue;
             unsigned short* z = a.D16 + (drow + (size_t)i2 * a.sc_W + j2) * a.N + n;

@@ -104,6 +104,63 @@ def test_vector_path_shapes(jz, cfg):
     print({k: (v["rel_l2"], v["worst_elem"]) for k, v in res.items()})
 
 
+STRIDED = [
+    # N, H, W, C, K, R, S, (stride_h, stride_w), (pad_h, pad_w): multi-tap strided layers, backward-data only
+    (2, 14, 14, 64, 64, 3, 3, (2, 2), (1, 1)),     # the v1.5 placement: classes of 1, 2, 2 and 4 taps
+    (2, 15, 13, 64, 96, 3, 3, (2, 2), (1, 1)),     # odd sizes: the classes' grids differ by one row / column
+    (2, 14, 14, 64, 64, 3, 3, (2, 2), (0, 0)),     # no padding: the last row of the odd class meets no output pixel
+    (1, 23, 23, 64, 64, 7, 7, (2, 2), (3, 3)),     # 49 taps, 16 / 12 / 12 / 9 per class
+    (2, 12, 12, 64, 96, 4, 4, (2, 2), (1, 1)),     # even filter
+    (2, 16, 16, 32, 64, 3, 3, (3, 3), (1, 1)),     # stride 3: nine single-tap classes
+    (2, 17, 11, 64, 160, 5, 5, (3, 2), (2, 1)),    # different strides and pads along the two axes
+    (2, 12, 12, 64, 64, 3, 3, (2, 1), (1, 1)),     # strided along h only
+    (2, 12, 12, 64, 64, 3, 5, (1, 2), (1, 2)),     # strided along w only
+    (2, 9, 9, 128, 96, 5, 3, (4, 2), (2, 1)),      # 8 classes
+    (2, 9, 9, 64, 40, 3, 3, (2, 2), (1, 1)),       # 40 output channels: no 16-byte k tiles, the element-wise kernel
+    (1, 13, 13, 64, 64, 2, 2, (3, 3), (0, 0)),     # filter smaller than the stride: some pixels meet no tap (per-load variant)
+    (3, 5, 5, 64, 64, 3, 3, (2, 2), (1, 1)),       # tiny grids: classes of 3x3, 3x2, 2x3 and 2x2 pixels
+]
+
+
+@pytest.mark.parametrize("cfg", STRIDED, ids=lambda c: "x".join(str(v) for v in c).replace(" ", ""))
+def test_strided_backward_data_parity_classes(jz, cfg):
+    """Strided multi-tap backward-data runs as one unit-stride launch per parity class of the stride: every input pixel is
+    written exactly once (the output is poisoned with NaN first) and meets the oracle element by element."""
+    import jzt
+    import oracle
+    N, H, W, C, K, R, S, st, pad = cfg
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, pad)
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, pad)
+    plan = jz.jz_conv2d_describe_plan(jz.JZ_BWD_DATA, d)
+    assert ("parity class" in plan) == (R >= st[0] and S >= st[1] and K % 32 == 0), plan
+    rng = inputs.rng_for(14, abs(hash(cfg)) % 10000)
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+    x = np.zeros((N, H, W, C), np.float16)      # (not used by backward-data)
+    jzt.all_ops_against_the_oracle(d, od, x, w, dy, ops=(jz.JZ_BWD_DATA,))
+    # all-ones data: every input pixel's value is the number of (tap, output pixel) pairs it meets, exactly
+    ones_w = np.ones((K, R, S, C), np.float16)
+    ones_dy = np.ones((N, od.P, od.Q, K), np.float16)
+    got = jzt.run_conv(jz.JZ_BWD_DATA, d, ones_dy, ones_w, (N, H, W, C)).astype(np.float64)
+    want = np.asarray(oracle.conv_bwd_data(od, ones_dy, ones_w), np.float64).reshape(got.shape)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("variant", [(128, 128, 32, 4, 4), (64, 64, 32, 4, 3), (128, 64, 64, 4, 4), (256, 128, 32, 8, 4), (128, 128, 64, 8, 4),
+                                     (256, 256, 32, 8, 4)], ids=lambda v: "x".join(str(i) for i in v))
+def test_parity_class_launches_in_every_kernel_family(jz, variant):
+    import jzt
+    import oracle
+    N, H, W, C, K, R, S, st, pad = 3, 30, 30, 64, 128, 3, 3, (2, 2), (1, 1)       # 675 pixels per class
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, pad)
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, pad)
+    rng = inputs.rng_for(15, *variant)
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    dy = inputs.normal_f16(rng, (N, od.P, od.Q, K), std=8.0)
+    with jzt.forced_variant(d, *variant, ops=(jz.JZ_BWD_DATA,)):
+        jzt.all_ops_against_the_oracle(d, od, np.zeros((N, H, W, C), np.float16), w, dy, ops=(jz.JZ_BWD_DATA,))
+
+
 def test_delta_filter_copies_the_input_bit_exactly(jz):
     import jzt
     rng = inputs.rng_for(12)
