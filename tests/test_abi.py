@@ -259,3 +259,55 @@ def test_fused_convolution_batch_norm_workspace_and_validation(jzlib):
                                    A + 0x9000000, n.value - 1, None) == E.JZ_ERR_WORKSPACE
     assert L.jz_conv2d_bn_relu_fwd(ctypes.byref(d), *args(), f(1e-5), A + 0x6000000, 1, A + 0x5000000, A + 0x6000000, A + 0x7000000,
                                    A + 0x8000000, A + 0x9000000, n.value, None) == E.JZ_ERR_ALIAS
+
+
+def test_fused_backward_data_batch_norm_validation_on_the_host(jzlib):
+    """jz_conv2d_bwd_data_bn_relu_bwd / jz_conv2d_bwd_data_block_end_bwd: workspace sizes and every argument mistake are
+    settled on the host (fake, well separated device addresses that are never dereferenced)."""
+    L, E = jzlib.lib(), jzlib
+    n, m = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    for cs_args in ((64, 56, 56, 64, 64, 3, 3, 1, 1), (64, 14, 14, 1024, 256, 1, 1, 1, 0), (64, 56, 56, 256, 128, 1, 1, 2, 0)):
+        d = jzlib.conv_desc(*cs_args)
+        assert L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == E.JZ_OK
+        assert L.jz_conv2d_workspace_bytes(E.JZ_BWD_DATA, ctypes.byref(d), ctypes.byref(m)) == E.JZ_OK
+        assert n.value >= m.value + 4 * d.C * 4 and n.value < m.value + (64 << 20)
+    assert L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(ctypes.byref(d), None) == E.JZ_ERR_NULL
+    d = jzlib.conv_desc(2, 8, 8, 4096, 32, 1, 1, 1, 0)                  # more channels than the normalization handles
+    assert L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == E.JZ_ERR_UNSUPPORTED
+    d = jzlib.conv_desc(2, 8, 8, 16, 32, 3, 3, 1, 1)
+    assert L.jz_conv2d_bwd_data_bn_relu_bwd_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == E.JZ_OK
+    D = [0x10000000 + i * 0x1000000 for i in range(14)]
+    names = ("dy", "w", "x", "y", "g", "m", "s", "dz", "dx", "dg", "db", "ws")
+
+    def plain(**o):
+        a = {k: D[i] for i, k in enumerate(names)}
+        a.update(o)
+        return L.jz_conv2d_bwd_data_bn_relu_bwd(ctypes.byref(d), a["dy"], a["w"], a["x"], a["y"], a["g"], a["m"], a["s"], a["dz"], a["dx"],
+                                                a["dg"], a["db"], a["ws"], o.get("n", n.value), None)
+
+    def end(**o):
+        a = {k: D[i] for i, k in enumerate(names)}
+        a["add"] = D[12]
+        a.update(o)
+        return L.jz_conv2d_bwd_data_block_end_bwd(ctypes.byref(d), a["dy"], a["w"], a["add"], a["x"], a["y"], a["g"], a["m"], a["s"], a["dz"],
+                                                  a["dx"], a["dg"], a["db"], a["ws"], o.get("n", n.value), None)
+
+    for call in (plain, end):
+        for k in names[:-1]:
+            assert call(**{k: None}) == E.JZ_ERR_NULL, k
+        assert call(ws=None) == E.JZ_ERR_WORKSPACE and call(n=n.value - 1) == E.JZ_ERR_WORKSPACE
+        assert call(x=D[2] + 2) == E.JZ_ERR_ALIGN and call(dx=D[8] + 8) == E.JZ_ERR_ALIGN
+        assert call(dx=D[7]) == E.JZ_ERR_ALIAS and call(dz=D[3]) == E.JZ_ERR_ALIAS and call(db=D[9]) == E.JZ_ERR_ALIAS
+        assert call(dz=D[11]) == E.JZ_ERR_ALIAS                        # an output inside the workspace
+    assert end(add=D[12] + 2) == E.JZ_ERR_ALIGN and end(add=D[7]) == E.JZ_ERR_ALIAS
+    # strided multi-tap backward-data asks for room for its repacked filter; the strided 1x1 form and unit stride do not
+    for cs_args, want in (((64, 56, 56, 128, 128, 3, 3, 2, 1), 128 * 9 * 128 * 2), ((64, 56, 56, 256, 128, 1, 1, 2, 0), 0),
+                          ((64, 28, 28, 128, 128, 3, 3, 1, 1), 0)):
+        d2 = jzlib.conv_desc(*cs_args)
+        assert L.jz_conv2d_workspace_bytes(E.JZ_BWD_DATA, ctypes.byref(d2), ctypes.byref(m)) == E.JZ_OK
+        assert m.value == want, (cs_args, m.value)
+    buf = ctypes.create_string_buffer(256)
+    d2 = jzlib.conv_desc(64, 56, 56, 128, 128, 3, 3, 2, 1)
+    assert L.jz_conv2d_describe_plan(E.JZ_BWD_DATA, ctypes.byref(d2), buf, 256) == E.JZ_OK and b"parity class" in buf.value
+    d2 = jzlib.conv_desc(4, 13, 13, 64, 64, 2, 2, 3, 0)               # a filter smaller than its stride keeps the per-load variant
+    assert L.jz_conv2d_describe_plan(E.JZ_BWD_DATA, ctypes.byref(d2), buf, 256) == E.JZ_OK and b"per-load" in buf.value
