@@ -38,7 +38,7 @@ constexpr int PAD_ROWS = 4;
 __global__ __launch_bounds__(128) void pad_to_c4(const unsigned short* __restrict__ x, unsigned short* __restrict__ xp,
                                                  int N, int H, int W, int C, int Hp, int Wp, int ph, int pw,
                                                  const unsigned short* __restrict__ w, unsigned short* __restrict__ wp,
-                                                 int K, int R, int S, int KT) {
+                                                 int K, int R, int S, int KT, int chunk_major) {
   const int z = blockIdx.z;
   if (z == N) {
     const int total = K * R * KT;
@@ -46,7 +46,10 @@ __global__ __launch_bounds__(128) void pad_to_c4(const unsigned short* __restric
     for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * 128 + threadIdx.x; i < total; i += stride) {
       int j = i % KT, kr = i / KT;
       int s = j >> 2, c = j & 3;
-      wp[i] = (s < S && c < C) ? w[((size_t)kr * S + s) * C + c] : (unsigned short)0;
+      // chunk_major (the patch kernel's layout): wq[r][j / 8][k][j % 8], 16-byte chunks of one filter row side by side per k
+      const int k = kr / R, r = kr - k * R;
+      const int dst = chunk_major ? ((r * (KT / 8) + (j >> 3)) * K + k) * 8 + (j & 7) : i;
+      wp[dst] = (s < S && c < C) ? w[((size_t)kr * S + s) * C + c] : (unsigned short)0;
     }
     return;
   }
@@ -376,6 +379,7 @@ void choose_tiling(Plan* pl, bool bk64_ok, int forced_bk) {
         if (usable(t)) {
           rt_hit = t;
           hit = &rt_hit;
+          pl->rt_forced = true;
           break;
         }
     }
@@ -441,8 +445,51 @@ void finish_geometry(ConvGeom& g) {
   g.d_sw = make_fastdiv((unsigned)g.sw);
 }
 
+// The patch kernel's view of a packed forward layer (jz_conv_stem.hip); false: the layer stays on the implicit-GEMM kernel
+// (output channels not a multiple of 32 or more than 128, filter + patch larger than the LDS).
+bool stem_fwd_setup(const Plan& pl, const jz_conv_desc* d, StemArgs* sa) {
+  if (!pl.packed || pl.op != JZ_FWD || d->K % 32 != 0 || d->K > 128) return false;
+  const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
+  StemArgs a;
+  a.NT = d->K / 32;
+  a.NKS = (4 * d->S + 15) / 16;
+  const int TM = stem_fwd_tm(a.NT);
+  if (TM == 0 || a.NKS < 1 || a.NKS > 4 || a.NKS * 16 > pl.KT) return false;
+  const int MB = 4 * TM * 32;
+  a.N = d->N; a.Hp = pl.Hp; a.Wp = pl.Wp; a.P = P; a.Q = Q; a.R = d->R; a.sh = d->stride_h; a.sw = d->stride_w;
+  a.xp_bytes = (unsigned)((size_t)d->N * pl.Hp * pl.Wp * 8);
+  a.wq_bytes = (unsigned)((size_t)d->R * a.NKS * 2 * d->K * 16);
+  if (a.wq_bytes > pl.wp_bytes) return false;
+  // output rows that MB consecutive pixels can touch, and the input rows under them
+  long long rows = ((long long)MB + Q - 2) / Q + 1;
+  if (rows > P) rows = P;
+  const size_t patch = (size_t)((rows - 1) * d->stride_h + d->R) * pl.Wp * 8;
+  const size_t staging = (size_t)4 * 32 * (d->K * 2 + 16);
+  const size_t lds_p = ((patch > staging ? patch : staging) + 4095) & ~size_t(4095);
+  const size_t lds_w = ((size_t)a.wq_bytes + 4095) & ~size_t(4095);
+  if (lds_w + lds_p > 160 * 1024) return false;
+  a.lds_w_bytes = (unsigned)lds_w;
+  a.lds_p_bytes = (unsigned)lds_p;
+  a.blocks_per_image = (P * Q + MB - 1) / MB;
+  const long long total = (long long)d->N * a.blocks_per_image;
+  if (total > 0x7fffffff) return false;
+  a.total_blocks = (int)total;
+  // workgroups per compute unit: what the LDS and the instance's register budget allow
+  const long long fit = (long long)((160 * 1024) / (lds_w + lds_p));
+  const long long slots = 256 * (fit < stem_fwd_wgs(a.NT) ? fit : (long long)stem_fwd_wgs(a.NT));
+  a.grid = (int)(total < slots ? total : slots);
+  *sa = a;
+  return true;
+}
+
 void plan_text(const Plan& pl, char* buf, size_t n) {
   const GemmArgs& a = pl.args;
+  if (pl.stem) {
+    const int mb = 128 * stem_fwd_tm(a.N / 32);
+    snprintf(buf, n, "op %d M %d N %d K %d: patch kernel, %d pixels x %d channels per block, %d blocks per image, filter resident in LDS, "
+             "4 wavefronts, 4-channel padded copy", pl.op, a.M, a.N, a.Kred, mb, a.N, (a.g.OH * a.g.OW + mb - 1) / mb);
+    return;
+  }
   snprintf(buf, n, "op %d M %d N %d K %d: %s tile %dx%dx%d, %d wavefronts, ring %d, %d x %d tiles, %d splits of %d k tiles%s%s", pl.op, a.M,
            a.N, a.Kred, pl.fast ? "vector" : "element-wise", pl.BM, pl.BN, pl.bk, pl.fast ? pl.waves : 4,
            pl.fast ? pl.nst : 2, a.tiles_m, a.tiles_n,
@@ -550,6 +597,10 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   pl->bk = bk;
   if (pl->packed && !forced_bk) forced_bk = 32;  // small-channel backward-weight: 4-wavefront 32-deep kernels
   choose_tiling(pl, bk64_ok, forced_bk);
+  if (pl->packed && op == JZ_FWD && !pl->rt_forced) {
+    StemArgs sa;
+    pl->stem = stem_fwd_setup(*pl, d, &sa);
+  }
   const size_t part = a.splits > 1 ? (size_t)a.splits * a.M * a.N * sizeof(float) : 0;
   pl->part_offset = pl->packed ? pl->xp_bytes + pl->wp_bytes : 0;
   pl->ws_bytes = pl->part_offset + part;
@@ -707,9 +758,18 @@ int run(int op, const jz_conv_desc* d, const void* A, const void* B, void* D, vo
     unsigned short* wp = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + pl.xp_bytes);
     const unsigned short* x = static_cast<const unsigned short*>(op == JZ_FWD ? A : B);
     const unsigned short* wsrc = op == JZ_FWD ? static_cast<const unsigned short*>(B) : nullptr;
+    StemArgs sa;
+    const bool stem = pl.stem && !stats && stem_fwd_setup(pl, d, &sa);
     hipLaunchKernelGGL(pad_to_c4, dim3((unsigned)((pl.Wp / 2 + 127) / 128), (unsigned)((pl.Hp + PAD_ROWS - 1) / PAD_ROWS), (unsigned)(d->N + (wsrc ? 1 : 0))),
                        dim3(128), 0, st, x, xp, d->N, d->H, d->W, d->C, pl.Hp, pl.Wp, d->pad_h, d->pad_w, wsrc,
-                       wsrc ? wp : nullptr, d->K, d->R, d->S, pl.KT);
+                       wsrc ? wp : nullptr, d->K, d->R, d->S, stem ? sa.NKS * 16 : pl.KT, stem ? 1 : 0);
+    if (stem) {
+      if ((rc = jz::launch_status()) != JZ_OK) return rc;
+      sa.xp = xp;
+      sa.wq = wp;
+      sa.y = static_cast<unsigned short*>(D);
+      return launch_stem_fwd(sa, st);
+    }
     if (op == JZ_FWD) {
       a.A = xp; a.bytesA = (unsigned)pl.xp_bytes;
       a.B = wp; a.bytesB = (unsigned)pl.wp_bytes;

@@ -262,16 +262,29 @@ def plan_tiles(op, d):
     """(tile_m, tile_n, tiles_m, tiles_n, splits, scatter) of the plan the library would run for `op` on `d`."""
     import re
     text = api.jz_conv2d_describe_plan(op, d)
+    m = re.search(r"patch kernel, (\d+) pixels x (\d+) channels per block, (\d+) blocks per image", text)
+    if m:   # blocks of consecutive pixels that never straddle an image: ("patch", pixels per block, channels, blocks per image)
+        return ("patch",) + tuple(int(v) for v in m.groups())
     m = re.search(r"tile (\d+)x(\d+)x\d+, \d+ wavefronts, ring \d+, (\d+) x (\d+) tiles, (\d+) splits", text)
     assert m, text
     return tuple(int(v) for v in m.groups()) + ("scatter epilogue" in text,)
 
 
-def structured_rows_cols(M, N, plan, max_row_tiles=1536):
+def structured_rows_cols(M, N, plan, max_row_tiles=1536, pq=None):
     """Rows and columns of the GEMM output where a tiling bug would show: the first and last row of (up to max_row_tiles,
     evenly spaced, always the first and last two) row tiles, of the row tiles at which one XCD's run of consecutive
     workgroups ends and the next begins, and the first and last column of every column tile (ragged last tiles
     included by construction)."""
+    if plan[0] == "patch":
+        # the forward kernel of small-channel layers: the first and last pixel of (up to max_row_tiles, evenly spaced) blocks,
+        # among them every image's ragged last block; the first and last channel of every 32-channel tile
+        _, mb, k, bpi = plan
+        assert k == N and M % pq == 0 and bpi == -(-pq // mb), (M, N, pq, plan)
+        nblk = (M // pq) * bpi
+        blocks = set(range(nblk)) if nblk <= max_row_tiles else set(np.linspace(0, nblk - 1, max_row_tiles).astype(int).tolist()) | {bpi - 1, nblk - bpi}
+        rows = sorted({r for b in blocks for r in ((b // bpi) * pq + (b % bpi) * mb, (b // bpi) * pq + min((b % bpi + 1) * mb, pq) - 1)})
+        cols = sorted({c for t in range(N // 32) for c in (t * 32, t * 32 + 31)})
+        return np.asarray(rows, np.int64), np.asarray(cols, np.int64)
     bm, bn, tm, tn, splits, _ = plan
     assert tm == -(-M // bm) and tn == -(-N // bn), (M, N, plan)
     tiles = set(range(tm)) if tm <= max_row_tiles else set(np.linspace(0, tm - 1, max_row_tiles).astype(int).tolist()) | {1, tm - 2}
@@ -297,7 +310,7 @@ def conv_all_ops_sampled(case, n_fwd=65536, n_bwd_data=65536, seed=0, tol=1e-3, 
     ax, aw, ady = abs16(case.x), abs16(case.w16), abs16(case.dy)
 
     def sample(out, op, M, Ncol, to_flat):
-        rows, cols = structured_rows_cols(M, Ncol, plan_tiles(op, d))
+        rows, cols = structured_rows_cols(M, Ncol, plan_tiles(op, d), pq=case.P * case.Q)
         edge = to_flat(np.repeat(rows, cols.size), np.tile(cols, rows.size))
         return np.unique(np.concatenate([rng.integers(0, out.size, size=min(n_fwd if op == api.JZ_FWD else n_bwd_data, out.size)), edge]))
 

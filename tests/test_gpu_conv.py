@@ -305,6 +305,71 @@ def test_small_channel_kernel_variants_against_the_oracle(jz, tile, nst):
             jzt.all_ops_against_the_oracle(d, od, x, w, dy, ops=(jz.JZ_BWD_WEIGHT,))
 
 
+PATCH_KERNEL = [
+    # N, H, W, C, K, R, S, stride, pad
+    (3, 37, 37, 3, 64, 7, 7, 2, 3),             # the ResNet stem's geometry: 361 pixels per image, one ragged block each
+    (2, 75, 75, 3, 64, 7, 7, 2, 3),             # 1444 pixels: three blocks per image, blocks that start mid-row
+    (4, 39, 39, 3, 96, 11, 11, 4, 0),           # the AlexNet stem's geometry: 3 channel tiles, stride 4
+    (2, 83, 83, 3, 96, 11, 11, 4, 2),           # 361 pixels in blocks of 256
+    (4, 20, 20, 4, 64, 5, 5, 2, 2),             # 4 real channels
+    (1, 30, 30, 1, 32, 3, 3, 2, 1),             # one channel, one channel tile, a single k step per filter row
+    (2, 41, 29, 3, 128, 7, 5, (3, 2), (3, 1)),  # 4 channel tiles, odd row stride, H != W, R != S, unequal pads
+    (2, 33, 45, 2, 64, 4, 6, (1, 4), (0, 2)),   # even filter sizes, unit row stride
+    (1, 40, 40, 3, 32, 13, 13, 2, 6),           # 13 taps per row: four k steps
+]
+
+
+@pytest.mark.parametrize("shape", PATCH_KERNEL, ids=lambda t: "x".join(str(v) for v in t[:9]).replace(" ", ""))
+def test_small_channel_forward_from_a_patch_in_lds(jz, shape):
+    # the forward pass of small-channel strided layers reads its operands out of an input patch in LDS (whole filter
+    # resident); whole output against the oracle, norm-wise and element by element
+    import jzt
+    import oracle
+    N, H, W, C, K, R, S, st, pad = shape
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, pad)
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, pad)
+    assert "patch kernel" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+    rng = inputs.rng_for(27, H, W, K, R)
+    x = inputs.normal_f16(rng, (N, H, W, C))
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    jzt.all_ops_against_the_oracle(d, od, x, w, np.zeros((N, od.P, od.Q, K), np.float16), ops=(jz.JZ_FWD,))
+
+
+def test_patch_kernel_workgroups_walk_through_several_blocks(jz):
+    # more blocks than resident workgroups (1080 blocks of 256 pixels, 768 workgroups): every workgroup reloads its patch and reuses the
+    # filter; all-ones inputs count the taps exactly, seeded inputs go against the oracle
+    import jzt
+    import oracle
+    N, H, W, C, K, R, S, st, pad = 60, 131, 131, 3, 64, 7, 7, 2, 3
+    od = oracle.conv_desc(N, H, W, C, K, R, S, st, pad)
+    d = jz.conv_desc(N, H, W, C, K, R, S, st, pad)
+    assert "patch kernel" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+    ones_x = np.ones((N, H, W, C), np.float16)
+    ones_w = np.ones((K, R, S, C), np.float16)
+    y = jzt.run_conv(jz.JZ_FWD, d, ones_x, ones_w, (N, od.P, od.Q, K)).astype(np.float64)
+    rows = np.minimum(np.arange(od.P) * 2 - 3 + R, H) - np.maximum(np.arange(od.P) * 2 - 3, 0)
+    cols = np.minimum(np.arange(od.Q) * 2 - 3 + S, W) - np.maximum(np.arange(od.Q) * 2 - 3, 0)
+    want = (rows[:, None] * cols[None, :] * C).astype(np.float64)
+    assert np.array_equal(y, np.broadcast_to(want[None, :, :, None], y.shape))
+    rng = inputs.rng_for(28)
+    x = inputs.normal_f16(rng, (N, H, W, C))
+    w = inputs.he_normal_f32(rng, (K, R, S, C), R * S * C).astype(np.float16)
+    jzt.all_ops_against_the_oracle(d, od, x, w, np.zeros((N, od.P, od.Q, K), np.float16), ops=(jz.JZ_FWD,))
+
+
+def test_small_channel_layers_the_patch_kernel_does_not_take(jz):
+    # output channels that are no multiple of 32 stay on the implicit-GEMM kernel, and so does a layer with a variant
+    # set through the tuning hook
+    d = jz.conv_desc(2, 23, 23, 3, 72, 7, 7, 2, 3)
+    assert "patch kernel" not in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+    d = jz.conv_desc(2, 23, 23, 3, 64, 7, 7, 2, 3)
+    assert "patch kernel" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+    import jzt
+    with jzt.forced_variant(d, 128, 64, 32, 4, 4, ops=(jz.JZ_FWD,)):
+        assert "patch kernel" not in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+    assert "patch kernel" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+
+
 def test_run_time_tuning_hook_runs_the_chosen_kernel_correctly(jz):
     # a choice recorded with jz_conv2d_tune_set is what runs (no environment override involved), and the result still
     # agrees with the oracle; clearing restores the planner's own choice
