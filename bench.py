@@ -368,70 +368,85 @@ def per_layer_report(wl, iters=20, out_path=None, peak=FP16_MFMA_PEAK_TFLOPS):
     return rows
 
 
-def alexnet_workload(args):
+class AlexNetStep:
     """configs[3]: the AlexNet-shaped layers (five convolutions, ungrouped, and the three FC GEMMs) at N = 128, forward,
     backward-data and backward-weight of every layer on independent seeded N(0,1) inputs, He-normal weights.  Same launch
     scheme as the ResNet-50 step: forward and the backward-data chain in network order on one stream, backward-weight
-    round-robin on the side streams.  One JSON line; no LARS phase (the configuration names none)."""
-    B, h, dev = args.batch, torch.float16, "cuda:0"
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(7)
-    randn = lambda n, std=1.0: (torch.randn(n, generator=gen, device=dev) * std).to(h)
-    layers, flops, ws_bytes = [], 0, 0
-    for cs in shapes.alexnet_convs():
-        d = api.conv_desc(B, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
-        nx, ny, nw = B * cs.H * cs.H * cs.C, B * cs.P * cs.P * cs.K, cs.K * cs.R * cs.R * cs.C
-        layers.append(dict(kind="conv", name=cs.name, d=d, first=cs.first, x=randn(nx), dy=randn(ny),
-                           w=randn(nw, float(np.sqrt(2.0 / (cs.R * cs.R * cs.C)))), y=torch.empty(ny, dtype=h, device=dev),
-                           dx=None if cs.first else torch.empty(nx, dtype=h, device=dev), dw=torch.empty(nw, dtype=h, device=dev)))
-        ws_bytes = max([ws_bytes] + [api.jz_conv2d_workspace_bytes(op, d) for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)])
-        flops += 2 * cs.macs(B) * (2 if cs.first else 3)
-    for fc in shapes.ALEXNET_FCS:
-        layers.append(dict(kind="fc", name=fc.name, I=fc.I, O=fc.O, first=False, x=randn(B * fc.I), dy=randn(B * fc.O),
-                           w=randn(fc.I * fc.O, float(np.sqrt(2.0 / fc.I))), y=torch.empty(B * fc.O, dtype=h, device=dev),
-                           dx=torch.empty(B * fc.I, dtype=h, device=dev), dw=torch.empty(fc.I * fc.O, dtype=h, device=dev)))
-        ws_bytes = max([ws_bytes] + [api.jz_gemm_fc_workspace_bytes(op, B, fc.I, fc.O) for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)])
-        flops += 2 * fc.macs(B) * 3
-    n_side = max(0, min(args.streams, 4) - 1)
-    wss = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev) for _ in range(n_side + 1)]
+    round-robin on the side streams.  ws_bytes: size of each stream's workspace (default: what the current plans need;
+    a tuning run that tries other split counts passes more)."""
 
-    def bound(L, op, ws):
+    def __init__(self, batch=128, n_side=2, ws_bytes=None):
+        B, h, dev = batch, torch.float16, "cuda:0"
+        self.N, self.dev, self.n_side = B, dev, n_side
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        randn = lambda n, std=1.0: (torch.randn(n, generator=gen, device=dev) * std).to(h)
+        layers, flops, need = [], 0, 0
+        for cs in shapes.alexnet_convs():
+            d = api.conv_desc(B, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+            nx, ny, nw = B * cs.H * cs.H * cs.C, B * cs.P * cs.P * cs.K, cs.K * cs.R * cs.R * cs.C
+            layers.append(dict(kind="conv", name=cs.name, d=d, first=cs.first, x=randn(nx), dy=randn(ny),
+                               w=randn(nw, float(np.sqrt(2.0 / (cs.R * cs.R * cs.C)))), y=torch.empty(ny, dtype=h, device=dev),
+                               dx=None if cs.first else torch.empty(nx, dtype=h, device=dev), dw=torch.empty(nw, dtype=h, device=dev)))
+            need = max([need] + [api.jz_conv2d_workspace_bytes(op, d) for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)])
+            flops += 2 * cs.macs(B) * (2 if cs.first else 3)
+        for fc in shapes.ALEXNET_FCS:
+            layers.append(dict(kind="fc", name=fc.name, I=fc.I, O=fc.O, first=False, x=randn(B * fc.I), dy=randn(B * fc.O),
+                               w=randn(fc.I * fc.O, float(np.sqrt(2.0 / fc.I))), y=torch.empty(B * fc.O, dtype=h, device=dev),
+                               dx=torch.empty(B * fc.I, dtype=h, device=dev), dw=torch.empty(fc.I * fc.O, dtype=h, device=dev)))
+            need = max([need] + [api.jz_gemm_fc_workspace_bytes(op, B, fc.I, fc.O) for op in (api.JZ_FWD, api.JZ_BWD_DATA, api.JZ_BWD_WEIGHT)])
+            flops += 2 * fc.macs(B) * 3
+        self.layers, self.flops = layers, flops
+        self.wss = [torch.empty(max(ws_bytes or need, 16), dtype=torch.uint8, device=dev) for _ in range(n_side + 1)]
+        prog = [("launch", self.bound(L, api.JZ_FWD, self.wss[0]), 0) for L in layers]
+        ready = torch.cuda.Event()
+        prog.append(("record", ready, 0))
+        for k, L in enumerate(reversed(layers)):
+            si = 1 + k % n_side if n_side else 0
+            if n_side:
+                prog.append(("wait", ready, si))
+            prog.append(("launch", self.bound(L, api.JZ_BWD_WEIGHT, self.wss[si]), si))
+            if not L["first"]:
+                prog.append(("launch", self.bound(L, api.JZ_BWD_DATA, self.wss[0]), 0))
+                if n_side:
+                    ready = torch.cuda.Event()
+                    prog.append(("record", ready, 0))
+        for si in range(1, n_side + 1):
+            done = torch.cuda.Event()
+            prog += [("record", done, si), ("wait", done, 0)]
+        self.prog = prog
+
+    def bound(self, L, op, ws):
         if L["kind"] == "conv":
             a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("x", "dy", "dw")}[op]
             return api.bind_conv2d(op, L["d"], L[a], L[b], L[o], ws)
         a, b, o = {api.JZ_FWD: ("x", "w", "y"), api.JZ_BWD_DATA: ("dy", "w", "dx"), api.JZ_BWD_WEIGHT: ("dy", "x", "dw")}[op]
-        return api.bind_gemm_fc(op, B, L["I"], L["O"], L[a], L[b], L[o], ws)
+        return api.bind_gemm_fc(op, self.N, L["I"], L["O"], L[a], L[b], L[o], ws)
 
-    rows = None
-    if args.per_layer or args.per_layer_file:
-        rows = per_layer_report(_LayerView(layers, bound, wss[0], B, dev, "AlexNet-shaped layers"), out_path=args.per_layer_file)
-    prog = [("launch", bound(L, api.JZ_FWD, wss[0]), 0) for L in layers]
-    ready = torch.cuda.Event()
-    prog.append(("record", ready, 0))
-    for k, L in enumerate(reversed(layers)):
-        si = 1 + k % n_side if n_side else 0
-        if n_side:
-            prog.append(("wait", ready, si))
-        prog.append(("launch", bound(L, api.JZ_BWD_WEIGHT, wss[si]), si))
-        if not L["first"]:
-            prog.append(("launch", bound(L, api.JZ_BWD_DATA, wss[0]), 0))
-            if n_side:
-                ready = torch.cuda.Event()
-                prog.append(("record", ready, 0))
-    for si in range(1, n_side + 1):
-        done = torch.cuda.Event()
-        prog += [("record", done, si), ("wait", done, 0)]
-    stream = torch.cuda.Stream()
-    streams = [stream] + [torch.cuda.Stream() for _ in range(n_side)]
-
-    def run():
-        for kind, obj, si in prog:
+    def run_gemms(self, sides=()):
+        """One step: main chain on the current stream, backward-weight launches on `sides` (as many as n_side)."""
+        streams = [torch.cuda.current_stream(), *sides]
+        for kind, obj, si in self.prog:
             if kind == "launch":
                 obj(streams[si])
             elif kind == "record":
                 obj.record(streams[si])
             else:
                 streams[si].wait_event(obj)
+
+
+def alexnet_workload(args):
+    """bench.py --workload alexnet: times AlexNetStep.  One JSON line; no LARS phase (the configuration names none)."""
+    B = args.batch
+    n_side = max(0, min(args.streams, 4) - 1)
+    wl = AlexNetStep(B, n_side)
+    layers, flops, prog = wl.layers, wl.flops, wl.prog
+    rows = None
+    if args.per_layer or args.per_layer_file:
+        rows = per_layer_report(_LayerView(layers, wl.bound, wl.wss[0], B, wl.dev, "AlexNet-shaped layers"), out_path=args.per_layer_file)
+    stream = torch.cuda.Stream()
+    sides = [torch.cuda.Stream() for _ in range(n_side)]
+    run = lambda: wl.run_gemms(sides)
 
     with torch.cuda.stream(stream):
         for _ in range(max(args.warmup, 1)):

@@ -338,9 +338,12 @@ const Tuned kTuned[] = {
 #include "jz_tuned_resnet50_n256.inc"
 #include "jz_tuned_resnet50_n32.inc"
     // the 3-channel stem of ResNet-50 at batch 64 on its padded 4-channel copy ("taps" = the 7 filter rows), measured
-    // the same way: forward 62.8 us, backward-weight 67.0 us including the copy
+    // the same way: forward 62.8 us (what the fused convolution + batch-norm call runs; the plain forward call takes the
+    // patch kernel), backward-weight 67.0 us including the copy
     {0, 802816, 64, 224, 7, 0, 128, 64, 32, 4, 3, 1},
     {2, 64, 224, 802816, 7, 0, 64, 64, 32, 4, 4, 256},
+    // backward-weight of the 11x11 stride-4 stem at batch 128, chosen inside the AlexNet step (tune.py --model alexnet --in-place)
+    {2, 96, 704, 387200, 11, 0, 128, 128, 32, 4, 3, 128},
 };
 
 // Choices set at run time through jz_conv2d_tune_set: looked up before the table above (an in-place tuning run tries

@@ -150,7 +150,7 @@ def write_table(recs, path, choice=None):
         f.write("\n".join(lines) + "\n")
 
 
-def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2):
+def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2, model="resnet50"):
     """Coordinate descent over the layer shapes with the GEMM phase of the bench step as the objective."""
     import torch
     from . import api, shapes
@@ -158,16 +158,21 @@ def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2):
     import bench
     api.lib()
     torch.cuda.set_device(0)
-    wl = bench.ResNet50Step(batch=BATCH)
     big = 1 << 30
-    wl.ws = torch.empty(big, dtype=torch.uint8, device="cuda:0")          # room for any split count
-    wl.side_ws = [torch.empty(big, dtype=torch.uint8, device="cuda:0") for _ in range(3)]
-    for _ in range(12):                                                     # the loss-scale back-off of bench.py
-        wl.step()
-        torch.cuda.synchronize()
-        if int(wl.found_inf.item()) == 0:
-            break
-        wl.halve_loss_scale()
+    if model == "alexnet":
+        batch = 128
+        wl = bench.AlexNetStep(batch, n_side, ws_bytes=big)                 # room for any split count
+    else:
+        batch = BATCH
+        wl = bench.ResNet50Step(batch=BATCH)
+        wl.ws = torch.empty(big, dtype=torch.uint8, device="cuda:0")
+        wl.side_ws = [torch.empty(big, dtype=torch.uint8, device="cuda:0") for _ in range(3)]
+        for _ in range(12):                                                 # the loss-scale back-off of bench.py
+            wl.step()
+            torch.cuda.synchronize()
+            if int(wl.found_inf.item()) == 0:
+                break
+            wl.halve_loss_scale()
     stream = torch.cuda.Stream()
     side = [torch.cuda.Stream() for _ in range(n_side)]
     ops = {"fwd": api.JZ_FWD, "bwd_data": api.JZ_BWD_DATA, "bwd_weight": api.JZ_BWD_WEIGHT}
@@ -197,21 +202,27 @@ def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2):
         return ("tile %dx%dx%d, %d wavefronts, ring %d," % (tile // 1000, tile % 1000, bk, wv, nst)) in plan and \
             api.jz_conv2d_workspace_bytes(op, d) <= big
 
+    convs = model_layers(model)[1] if model == "alexnet" else list(shapes.resnet50_convs())
     count = {}
-    for c in shapes.resnet50_convs():
+    for c in convs:
         count[(c.H, c.C, c.K, c.R, c.stride)] = count.get((c.H, c.C, c.K, c.R, c.stride), 0) + 1
-    pad_of = {(c.H, c.C, c.K, c.R, c.stride): c.pad for c in shapes.resnet50_convs()}
+    pad_of = {(c.H, c.C, c.K, c.R, c.stride): c.pad for c in convs}
     work = []
     for r in recs:
         cands = {k: v for k, v in r["all"].items() if k not in ("planner", "model")}
         best = min(cands, key=cands.get)
         work.append((cands[best] * count[(r["H"], r["C"], r["K"], r["R"], r["stride"])], r, cands, best))
-    # the 3-channel stem is not part of the layer-by-layer sweep (it runs on a padded copy): a few candidates by hand;
-    # its entries live beside the generated table, so the result is only reported
-    stem = dict(layer="stem", H=224, C=3, K=64, R=7, stride=2, by_hand=True)
-    work.append((63.0, dict(stem, op="fwd"), {"128064.32.4.3/1": 62.8, "128064.32.4.4/1": 68.1, "64064.32.4.3/1": 69.6}, "128064.32.4.3/1"))
-    work.append((67.0, dict(stem, op="bwd_weight"), {"64064.32.4.4/256": 67.0, "64128.32.4.4/384": 69.0, "128064.32.4.4/192": 88.7},
-                 "64064.32.4.4/256"))
+    # the 3-channel stems are not part of the layer-by-layer sweep (they run on a padded copy, forward on the patch
+    # kernel): a few candidates by hand; their entries live beside the generated tables, so the result is only reported
+    if model == "alexnet":
+        stem = dict(layer="conv1", H=227, C=3, K=96, R=11, stride=4, by_hand=True)
+        pad_of[(227, 3, 96, 11, 4)] = 0
+        work.append((140.0, dict(stem, op="bwd_weight"), {"128128.32.4.4/64": 143.0, "128128.32.4.3/128": 143.0, "128064.32.4.4/64": 150.0},
+                     "128128.32.4.4/64"))
+    else:
+        stem = dict(layer="stem", H=224, C=3, K=64, R=7, stride=2, by_hand=True)
+        work.append((67.0, dict(stem, op="bwd_weight"), {"64064.32.4.4/256": 67.0, "64128.32.4.4/384": 69.0, "128064.32.4.4/192": 88.7},
+                     "64064.32.4.4/256"))
     work.sort(key=lambda w: -w[0])
 
     def current(d, op):                                                     # what the library would run now, as a key
@@ -225,7 +236,7 @@ def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2):
     for p in range(passes):
         changed = 0
         for _, r, cands, alone in work:
-            d = api.conv_desc(BATCH, r["H"], r["H"], r["C"], r["K"], r["R"], r["R"], r["stride"],
+            d = api.conv_desc(batch, r["H"], r["H"], r["C"], r["K"], r["R"], r["R"], r["stride"],
                               pad_of[(r["H"], r["C"], r["K"], r["R"], r["stride"])])
             op = ops[r["op"]]
             start = current(d, op)
@@ -273,6 +284,9 @@ def main():
     ap.add_argument("--write", action="store_true", help="write csrc/jz_tuned.inc")
     ap.add_argument("--in-place", action="store_true", help="refine the choices inside the whole step of bench.py")
     ap.add_argument("--streams", type=int, default=3, help="--in-place: streams of the step (as bench.py --streams)")
+    ap.add_argument("--passes", type=int, default=2, help="--in-place: passes over the launches (stops early when a pass changes nothing)")
+    ap.add_argument("--top", type=int, default=3, help="--in-place: how many of a launch's best variants alone are tried in the step "
+                                                       "(the AlexNet table: 8; the step has 22 launches, each long enough to matter)")
     ap.add_argument("--table", default=os.path.join(PKG, "csrc", "jz_tuned.inc"), help="where --write puts the table")
     ap.add_argument("--model", default="resnet50", choices=("resnet50", "alexnet"), help="whose layer shapes to sweep")
     ap.add_argument("--only", default=None, help="sweep only these variants, e.g. 256128.32.8.3,128128.32.8.4; with --json: "
@@ -302,7 +316,7 @@ def main():
         recs = json.load(open(a.json)) if a.json else sweep(a.out_json, VARIANTS, a.model)
     choice = None
     if a.in_place:
-        choice = in_place(recs, n_side=a.streams - 1)
+        choice = in_place(recs, n_side=a.streams - 1, model=a.model, top=a.top, passes=a.passes)
     if a.write:
         write_table(recs, a.table, choice)
     tp = sum(r["all"]["planner"] for r in recs)
