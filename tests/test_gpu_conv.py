@@ -316,6 +316,9 @@ PATCH_KERNEL = [
     (2, 41, 29, 3, 128, 7, 5, (3, 2), (3, 1)),  # 4 channel tiles, odd row stride, H != W, R != S, unequal pads
     (2, 33, 45, 2, 64, 4, 6, (1, 4), (0, 2)),   # even filter sizes, unit row stride
     (1, 40, 40, 3, 32, 13, 13, 2, 6),           # 13 taps per row: four k steps
+    (1, 9, 9, 3, 32, 3, 3, 2, 1),               # 25 output pixels: less than one 32-pixel tile
+    (1, 12, 400, 3, 64, 3, 3, (1, 2), 1),       # wide and flat: a block is little more than one output row
+    (3, 21, 21, 3, 64, 7, 7, (4, 2), (3, 3)),   # row stride larger than the column stride, 6 x 11 output pixels
 ]
 
 
@@ -361,6 +364,10 @@ def test_small_channel_layers_the_patch_kernel_does_not_take(jz):
     # output channels that are no multiple of 32 stay on the implicit-GEMM kernel, and so does a layer with a variant
     # set through the tuning hook
     d = jz.conv_desc(2, 23, 23, 3, 72, 7, 7, 2, 3)
+    assert "patch kernel" not in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+    d = jz.conv_desc(1, 64, 600, 3, 128, 31, 15, 2, 0)          # a filter of 508 KB does not fit the LDS
+    assert "patch kernel" not in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
+    d = jz.conv_desc(1, 64, 64, 3, 160, 7, 7, 2, 3)             # more than 128 output channels
     assert "patch kernel" not in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
     d = jz.conv_desc(2, 23, 23, 3, 64, 7, 7, 2, 3)
     assert "patch kernel" in jz.jz_conv2d_describe_plan(jz.JZ_FWD, d)
