@@ -27,7 +27,8 @@ constexpr int BK = 64;  // k tile depth of the element-wise kernel
 // adjacent in memory, so the input is copied once into a zero-padded 4-channel image xp[N][H+2ph][Wp][4]; one filter
 // row of an output pixel is then ONE contiguous, 16-byte aligned run of 4*S halves starting at pixel q*stride_w
 // (needs an even stride_w), and the layer becomes an ordinary implicit GEMM whose "taps" are the R filter rows and
-// whose "channels" are that run, rounded up to the k tile (32 or 64).  The filter is repacked to match
+// whose "channels" are that run, rounded up to the k tile (32 or 64; backward-weight, where the runs are columns of the
+// GEMM: to whole 16-byte chunks).  The filter is repacked to match
 // (w'[k][r][4 s + c], zeros elsewhere); for backward-weight the GEMM produces dw' in that layout and the real
 // entries are copied out.
 
@@ -343,7 +344,7 @@ const Tuned kTuned[] = {
     {0, 802816, 64, 224, 7, 0, 128, 64, 32, 4, 3, 1},
     {2, 64, 224, 802816, 7, 0, 64, 64, 32, 4, 4, 256},
     // backward-weight of the 11x11 stride-4 stem at batch 128, chosen inside the AlexNet step (tune.py --model alexnet --in-place)
-    {2, 96, 704, 387200, 11, 0, 128, 128, 32, 4, 3, 128},
+    {2, 96, 528, 387200, 11, 0, 128, 128, 32, 4, 3, 128},
 };
 
 // Choices set at run time through jz_conv2d_tune_set: looked up before the table above (an in-place tuning run tries
@@ -568,7 +569,9 @@ int make_plan(int op, const jz_conv_desc* d, Plan* pl) {
   // small-channel layers: gather from a zero-padded 4-channel copy (see pad_to_c4)
   if (!pl->fast && op != JZ_BWD_DATA && d->C <= 4 && d->stride_w % 2 == 0 && 4 * d->S <= 64 &&
       d->R <= 32 && (op == JZ_FWD || d->K % 8 == 0)) {
-    const int KT = 4 * d->S <= 32 ? 32 : 64;
+    // forward: the run of a filter row is one k tile (32 or 64 halves); backward-weight: the runs are columns of the
+    // GEMM, whole 16-byte chunks suffice (an 11-tap row: 48 columns instead of 64, a quarter fewer columns to compute)
+    const int KT = op == JZ_BWD_WEIGHT ? (4 * d->S + 7) & ~7 : 4 * d->S <= 32 ? 32 : 64;
     int Hp = d->H + 2 * d->pad_h, Wp = d->W + 2 * d->pad_w;
     if (Wp < (Q - 1) * d->stride_w + KT / 4) Wp = (Q - 1) * d->stride_w + KT / 4;
     Wp = (Wp + 1) & ~1;  // rows stay 16-byte aligned

@@ -217,7 +217,7 @@ def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2, model="resn
     if model == "alexnet":
         stem = dict(layer="conv1", H=227, C=3, K=96, R=11, stride=4, by_hand=True)
         pad_of[(227, 3, 96, 11, 4)] = 0
-        work.append((140.0, dict(stem, op="bwd_weight"), {"128128.32.4.4/64": 143.0, "128128.32.4.3/128": 143.0, "128064.32.4.4/64": 150.0},
+        work.append((140.0, dict(stem, op="bwd_weight"), {"128128.32.4.4/64": 143.0, "128128.32.4.3/128": 143.0, "128064.32.4.4/64": 150.0, "128064.32.4.4/128": 150.0, "64128.32.4.4/128": 150.0, "64128.32.4.4/64": 150.0, "128128.32.4.4/128": 143.0, "128128.32.4.3/64": 143.0, "64064.32.4.4/128": 160.0},
                      "128128.32.4.4/64"))
     else:
         stem = dict(layer="stem", H=224, C=3, K=64, R=7, stride=2, by_hand=True)
