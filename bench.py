@@ -716,7 +716,9 @@ def main():
                          "ResNet-50 training step with every layer between the convolutions (not the headline step either)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-alt", action="store_true", help="skip the run with the other LARS update path")
-    ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr")
+    ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr (the ResNet-50 step does "
+                    "by default: its ten launches furthest from their rooflines go into the JSON line as per_layer_worst)")
+    ap.add_argument("--no-per-layer", action="store_true", help="ResNet-50 step: skip the per-layer table (about ten seconds)")
     ap.add_argument("--per-layer-file", default=None, help="write the per-layer table (time, TFLOP/s, the layer's own roofline, "
                     "fraction, kernel plan) to this file as well; implies --per-layer")
     ap.add_argument("--lars-path", default="presummed", choices=("presummed", "three_launches"),
@@ -783,7 +785,7 @@ def main():
         wl.use_dynamic_loss_scale()
 
     rows = None
-    if args.per_layer or args.per_layer_file:
+    if args.per_layer or args.per_layer_file or not args.no_per_layer:
         rows = per_layer_report(wl, out_path=args.per_layer_file, peak=FP32_MFMA_PEAK_TFLOPS if wl.f32 else FP16_MFMA_PEAK_TFLOPS)
         wl.reset_state()
 
