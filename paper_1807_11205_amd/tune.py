@@ -25,7 +25,7 @@ VARIANTS = [(128128, 32, 4, 4), (128064, 32, 4, 4), (64128, 32, 4, 4), (64064, 3
             (256128, 32, 8, 4), (256256, 32, 8, 4), (128128, 64, 4, 4), (128064, 64, 4, 4), (64128, 64, 4, 4), (64064, 64, 4, 4),
             (128128, 32, 4, 3), (128064, 32, 4, 3), (64128, 32, 4, 3), (64064, 32, 4, 3),
             (256128, 32, 8, 3), (128128, 32, 8, 4), (128128, 32, 8, 3)]
-SPLITS = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128]
+SPLITS = [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128]
 OPS = ("fwd", "bwd_data", "bwd_weight")
 BATCH = 64
 
