@@ -715,6 +715,9 @@ def main():
                          "bn: the batch-normalization + ReLU layers of ResNet-50 (not part of the headline step); chain: a complete chained "
                          "ResNet-50 training step with every layer between the convolutions (not the headline step either)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", default="v1", choices=("v1", "v1.5"),
+                    help="where a stage's stride 2 sits: v1 (the network the paper cites: on the first 1x1 of the stage's first block) or "
+                         "v1.5 (on its 3x3; 6 %% more multiply-adds; its shapes have no entries in the planner's table)")
     ap.add_argument("--no-alt", action="store_true", help="skip the run with the other LARS update path")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer, per-op timing table to stderr (the ResNet-50 step does "
                     "by default: its ten launches furthest from their rooflines go into the JSON line as per_layer_worst)")
@@ -770,7 +773,7 @@ def main():
     if args.workload == "chain":
         chain_workload(args)
         return
-    wl = ResNet50Step(batch=args.batch, dtype=args.dtype, lars_path=args.lars_path, sumsq_from=args.sumsq_from)
+    wl = ResNet50Step(batch=args.batch, dtype=args.dtype, lars_path=args.lars_path, sumsq_from=args.sumsq_from, variant=args.variant)
 
     # loss-scale back-off: halve S until the weight gradients stay inside fp16 and the update is not skipped
     for _ in range(12):
@@ -800,7 +803,7 @@ def main():
     lars_gbps = LARS_BYTES_PER_PARAM * wl.P / (lars_ms * 1e-3) / 1e9
     traffic = measured_traffic(wl) if default_workload else None
     out = {
-        "metric": "ResNet-50 N=64 fp16 fwd+bwd images/s" if not wl.f32 else "ResNet-50 N=%d fp32 fwd+bwd images/s" % args.batch,
+        "metric": "ResNet-50 N=%d %s fwd+bwd images/s" % (args.batch, "fp32" if wl.f32 else "fp16"),
         "value": args.batch / (ms_per_step * 1e-3),
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -810,8 +813,8 @@ def main():
         "dtype": "f32 storage, f32 accumulate (LARS as in the mixed-precision step)" if wl.f32 else
                  "f16 storage, f32 accumulate (LARS in f32, norms f64)",
         "data": "synthetic",
-        "config": {"workload": "configs[4]: ResNet-50 v1, 53 convs + FC, fwd + bwd_data + bwd_weight per layer on "
-                               "independent seeded N(0,1) inputs, then fused LARS over 161 tensors / 25,557,032 params",
+        "config": {"workload": "configs[4]: ResNet-50 %s, 53 convs + FC, fwd + bwd_data + bwd_weight per layer on "
+                               "independent seeded N(0,1) inputs, then fused LARS over 161 tensors / 25,557,032 params" % args.variant,
                    "batch": args.batch, "loss_scale_after_back_off": wl.loss_scale, "loss_scale_control": "device" if args.dynamic_loss_scale else "fixed", "launch": "hip graph" if args.graph else "eager", "streams": args.streams},
         "ms_per_step_stats": {"gpu_mean": t["step_ms_mean"], "gpu_median": t["step_ms_median"], "gpu_min": t["step_ms_min"],
                               "note": "per-step HIP-event times (GEMM phase + LARS) over the timed steps; ms_per_step is host wall clock / steps"},
@@ -840,7 +843,7 @@ def main():
     if wl.presummed and not args.no_alt:
         # the same step with the other update path (plain backward-weight launches, three-launch update), a run of its own:
         # what the one-launch update costs the GEMM phase and what it saves behind it
-        wl3 = ResNet50Step(batch=args.batch, loss_scale=wl.loss_scale, lars_path="three_launches")   # the scale after back-off
+        wl3 = ResNet50Step(batch=args.batch, loss_scale=wl.loss_scale, lars_path="three_launches", variant=args.variant)   # the scale after back-off
         if args.dynamic_loss_scale:
             wl3.use_dynamic_loss_scale()
         t3 = time_steps(wl3, stream, side, args.steps, args.warmup)
@@ -850,7 +853,7 @@ def main():
         del wl3
     if not wl.f32 and not args.no_fp32:
         # Table 9's comparison on this chip: the same step with the single-precision kernels (a short run of its own)
-        wl32 = ResNet50Step(batch=args.batch, dtype="f32")
+        wl32 = ResNet50Step(batch=args.batch, dtype="f32", variant=args.variant)
         t32 = time_steps(wl32, stream, side, max(3, args.steps // 4), 2)
         v32 = args.batch / (t32["wall_ms"] * 1e-3)
         tf32 = wl32.flops / (t32["gemm_ms"] * 1e-3) / 1e12

@@ -338,6 +338,7 @@ const Tuned kTuned[] = {
 #include "jz_tuned_resnet50_n128.inc"
 #include "jz_tuned_resnet50_n256.inc"
 #include "jz_tuned_resnet50_n32.inc"
+#include "jz_tuned_resnet50_v15.inc"
     // the 3-channel stem of ResNet-50 at batch 64 on its padded 4-channel copy ("taps" = the 7 filter rows), measured
     // the same way: forward 62.8 us (what the fused convolution + batch-norm call runs; the plain forward call takes the
     // patch kernel), backward-weight 67.0 us including the copy

@@ -28,6 +28,7 @@ VARIANTS = [(128128, 32, 4, 4), (128064, 32, 4, 4), (64128, 32, 4, 4), (64064, 3
 SPLITS = [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128]
 OPS = ("fwd", "bwd_data", "bwd_weight")
 BATCH = 64
+VARIANT = "v1"     # where ResNet-50's stride-2 steps sit (--variant)
 
 
 def gemm_dims(rec):
@@ -44,6 +45,21 @@ def gemm_dims(rec):
     return K, R * R * C, B * P * P, R * R, 0
 
 
+def class_dims(rec):
+    """(M, N, K, taps) of the GEMM of every parity class of a strided multi-tap backward-data layer (square image, filter,
+    stride): input pixels h = ca + s i, w = cb + s l meet the taps r = (ca + pad) mod s + s j (and likewise along w)."""
+    H, C, K, R, st = rec["H"], rec["C"], rec["K"], rec["R"], rec["stride"]
+    pad, B = rec.get("pad", (R - 1) // 2), rec.get("batch", BATCH)
+    out = []
+    for ca in range(st):
+        for cb in range(st):
+            ha, wb = -(-(H - ca) // st), -(-(H - cb) // st)
+            ra, sb = -(-(R - (ca + pad) % st) // st), -(-(R - (cb + pad) % st) // st)
+            if ha > 0 and wb > 0:
+                out.append((B * ha * wb, C, ra * sb * K, ra * sb))
+    return out
+
+
 def model_layers(model):
     """(batch, layers) swept for a model: every distinct convolution shape except the 3-channel stem (it runs on a padded
     copy and has its own entries), fully connected layers as 1x1 convolutions over a 1x1 image."""
@@ -52,7 +68,9 @@ def model_layers(model):
         convs = [c for c in shapes.alexnet_convs() if not c.first]
         return 128, convs + [shapes.ConvShape(f.name, 1, f.I, f.O, 1, 1, 0) for f in shapes.ALEXNET_FCS]
     seen, layers = set(), []
-    for c in shapes.resnet50_convs():
+    if VARIANT != "v1":     # only what the v1 table does not already hold
+        seen = {(c.H, c.C, c.K, c.R, c.stride) for c in shapes.resnet50_convs("v1")}
+    for c in shapes.resnet50_convs(VARIANT):
         key = (c.H, c.C, c.K, c.R, c.stride)
         if key in seen or c.first:
             continue
@@ -142,8 +160,18 @@ def write_table(recs, path, choice=None):
             best = choice[(r["layer"], r["op"])]
         fam, sp = best.split("/")
         tile, bk, wv, nst = (int(v) for v in fam.split(".")[:4])
-        M, N, K, taps, sc = gemm_dims(r)
         note = "%.1f us alone" % cands[best] if best in cands else "chosen in the step"
+        if r["op"] == "bwd_data" and r["R"] > 1 and r["stride"] > 1:
+            # one launch per parity class of the stride, each a unit-stride GEMM of its own with a scatter epilogue: the
+            # variant is recorded under every class's key (what jz_conv2d_tune_set does at run time), reductions unsplit
+            keys = []
+            for key in class_dims(r):
+                if key not in keys:
+                    keys.append(key)
+                    lines.append("{1, %d, %d, %d, %d, 1, %d, %d, %d, %d, %d, 1},  // %s bwd_data, a parity class: %s for the layer" % (
+                        key + (tile // 1000, tile % 1000, bk, wv, nst, r["layer"], note)))
+            continue
+        M, N, K, taps, sc = gemm_dims(r)
         lines.append("{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s},  // %s %s: %s" % (
             OPS.index(r["op"]), M, N, K, taps, sc, tile // 1000, tile % 1000, bk, wv, nst, sp, r["layer"], r["op"], note))
     with open(path, "w") as f:
@@ -164,7 +192,7 @@ def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2, model="resn
         wl = bench.AlexNetStep(batch, n_side, ws_bytes=big)                 # room for any split count
     else:
         batch = BATCH
-        wl = bench.ResNet50Step(batch=BATCH)
+        wl = bench.ResNet50Step(batch=BATCH, variant=VARIANT)
         wl.ws = torch.empty(big, dtype=torch.uint8, device="cuda:0")
         wl.side_ws = [torch.empty(big, dtype=torch.uint8, device="cuda:0") for _ in range(3)]
         for _ in range(12):                                                 # the loss-scale back-off of bench.py
@@ -202,7 +230,7 @@ def in_place(recs, steps=100, top=3, gain=0.001, passes=2, n_side=2, model="resn
         return ("tile %dx%dx%d, %d wavefronts, ring %d," % (tile // 1000, tile % 1000, bk, wv, nst)) in plan and \
             api.jz_conv2d_workspace_bytes(op, d) <= big
 
-    convs = model_layers(model)[1] if model == "alexnet" else list(shapes.resnet50_convs())
+    convs = model_layers(model)[1] if model == "alexnet" else list(shapes.resnet50_convs(VARIANT))
     count = {}
     for c in convs:
         count[(c.H, c.C, c.K, c.R, c.stride)] = count.get((c.H, c.C, c.K, c.R, c.stride), 0) + 1
@@ -296,10 +324,13 @@ def main():
                                                  "add the new timings to those saved measurements")
     ap.add_argument("--batch", type=int, default=None, help="resnet50: batch size of the swept shapes (default 64; the table is keyed "
                                                             "by GEMM shape, so tables of several batch sizes can sit side by side)")
+    ap.add_argument("--variant", default="v1", choices=("v1", "v1.5"), help="resnet50: the network variant whose shapes are swept (the table is "
+                                                                            "keyed by GEMM shape: a v1.5 table only needs the shapes v1 does not have)")
     a = ap.parse_args()
+    global BATCH, VARIANT
     if a.batch:
-        global BATCH
         BATCH = a.batch
+    VARIANT = a.variant
     if a.only:
         sel = [tuple(int(x) for x in v.split(".")) for v in a.only.split(",")]
         assert all(v in VARIANTS for v in sel), "unknown variant"

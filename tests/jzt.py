@@ -267,7 +267,30 @@ def plan_tiles(op, d):
         return ("patch",) + tuple(int(v) for v in m.groups())
     m = re.search(r"tile (\d+)x(\d+)x\d+, \d+ wavefronts, ring \d+, (\d+) x (\d+) tiles, (\d+) splits", text)
     assert m, text
+    if "parity class" in text:   # strided multi-tap backward-data: one launch per class, the text shows the first class's tiles
+        return ("classes", int(m.group(1)), int(m.group(2)))
     return tuple(int(v) for v in m.groups()) + ("scatter epilogue" in text,)
+
+
+def class_edge_pixels(case, bm, max_tiles_per_class=384):
+    """Flat input-pixel indices (n, h, w) at the first and last row of the row tiles of every parity class of a strided
+    multi-tap backward-data layer: class (ca, cb) holds the pixels h = ca + s i, w = cb + s l in (n, i, l) order."""
+    s_h = s_w = case.stride
+    rows = set()
+    for ca in range(s_h):
+        for cb in range(s_w):
+            ha, wb = -(-(case.H - ca) // s_h), -(-(case.W - cb) // s_w)
+            mc = case.N * ha * wb
+            if mc <= 0:
+                continue
+            tm = -(-mc // bm)
+            tiles = range(tm) if tm <= max_tiles_per_class else np.unique(np.linspace(0, tm - 1, max_tiles_per_class).astype(int))
+            for t in tiles:
+                for j in (int(t) * bm, min((int(t) + 1) * bm, mc) - 1):
+                    n, rem = divmod(j, ha * wb)
+                    i, l = divmod(rem, wb)
+                    rows.add((n * case.H + ca + s_h * i) * case.W + cb + s_w * l)
+    return np.asarray(sorted(rows), np.int64)
 
 
 def structured_rows_cols(M, N, plan, max_row_tiles=1536, pq=None):
@@ -323,7 +346,16 @@ def conv_all_ops_sampled(case, n_fwd=65536, n_bwd_data=65536, seed=0, tol=1e-3, 
     if not skip_bwd_data:
         dx = run_conv(api.JZ_BWD_DATA, d, case.dy, case.w16, (case.N, case.H, case.W, case.C))
         assert not np.any(np.isnan(dx)), "bwd_data: unwritten output"
-        if plan_tiles(api.JZ_BWD_DATA, d)[5]:
+        bd_plan = plan_tiles(api.JZ_BWD_DATA, d)
+        if bd_plan[0] == "classes":
+            rows = class_edge_pixels(case, bd_plan[1])
+            cols = np.asarray(sorted({c for t in range(-(-case.C // bd_plan[2])) for c in (t * bd_plan[2], min((t + 1) * bd_plan[2], case.C) - 1)}), np.int64)
+            edge = np.repeat(rows, cols.size) * case.C + np.tile(cols, rows.size)
+            idx = np.unique(np.concatenate([rng.integers(0, dx.size, size=min(n_bwd_data, dx.size)), edge]))
+            res["bwd_data"] = check_half_output(dx.ravel()[idx], oracle.conv_bwd_data_at(od, case.dy, case.w16, idx), tol, "bwd_data",
+                                                oracle.conv_bwd_data_at(od, ady, aw, idx))
+            res["bwd_data"]["n"] = int(idx.size)
+        elif bd_plan[5]:
             # strided 1x1 layer: the GEMM's rows are the output pixels (n, p, q); row m lands on input pixel
             # (n, p * stride, q * stride), and the pixel diagonally behind it (when inside) must hold the zero
             def to_flat(r, c):
@@ -336,10 +368,11 @@ def conv_all_ops_sampled(case, n_fwd=65536, n_bwd_data=65536, seed=0, tol=1e-3, 
         else:
             to_flat = lambda r, c: r * case.C + c
             M = case.N * case.H * case.W
-        idx = sample(dx, api.JZ_BWD_DATA, M, case.C, to_flat)
-        res["bwd_data"] = check_half_output(dx.ravel()[idx], oracle.conv_bwd_data_at(od, case.dy, case.w16, idx), tol, "bwd_data",
-                                            oracle.conv_bwd_data_at(od, ady, aw, idx))
-        res["bwd_data"]["n"] = int(idx.size)
+        if bd_plan[0] != "classes":
+            idx = sample(dx, api.JZ_BWD_DATA, M, case.C, to_flat)
+            res["bwd_data"] = check_half_output(dx.ravel()[idx], oracle.conv_bwd_data_at(od, case.dy, case.w16, idx), tol, "bwd_data",
+                                                oracle.conv_bwd_data_at(od, ady, aw, idx))
+            res["bwd_data"]["n"] = int(idx.size)
     dw = run_conv(api.JZ_BWD_WEIGHT, d, case.x, case.dy, (case.K, case.R, case.S, case.C))
     res["bwd_weight"] = check_half_output(dw, oracle.conv_bwd_weight(od, case.x, case.dy), tol, "bwd_weight (whole tensor)",
                                           oracle.conv_bwd_weight(od, ax, ady))

@@ -72,6 +72,22 @@ def test_resnet50_layers_batch64_sampled(jz, cs):
     assert res["bwd_weight"]["n"] == cs.weight_count()     # the whole weight gradient, not a sample
 
 
+V15_ONLY = [c for c in distinct(shapes.resnet50_convs("v1.5"))
+            if (c.H, c.C, c.K, c.R, c.stride) not in {(v.H, v.C, v.K, v.R, v.stride) for v in shapes.resnet50_convs()}]
+
+
+@pytest.mark.parametrize("cs", V15_ONLY, ids=lambda c: "%s_%dx%d_%d_%d_%dx%d_s%d" % (c.name, c.H, c.H, c.C, c.K, c.R, c.R, c.stride))
+def test_resnet50_v15_layers_batch64_sampled(jz, cs):
+    """The six shapes only the v1.5 placement of the stride has (stride 2 on the 3x3 of a stage's first block, whose
+    backward-data runs as one launch per parity class; the 1x1 in front of it at unit stride), through their table entries."""
+    import jzt
+    c = inputs.conv_case_for(cs, 64, (5, cs.H, cs.C, cs.K, cs.R, cs.stride), loss_scale=1.0)
+    res = jzt.conv_all_ops_sampled(c, seed=cs.H * 1000 + cs.C + cs.K + 15)
+    assert res["bwd_weight"]["n"] == cs.weight_count()
+    if cs.R > 1:
+        assert "parity class" in jz.jz_conv2d_describe_plan(jz.JZ_BWD_DATA, jzt.desc_of(c))
+
+
 OTHER_BATCH = [(n, cs) for n in (32, 128) for cs in distinct(shapes.resnet50_convs())
                if cs.name in ("s2b1b", "s2b1c", "s3b1a", "s3b1p", "s4b1b", "s5b1c", "s5b1b")]
 
