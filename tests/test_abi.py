@@ -316,3 +316,25 @@ def test_fused_backward_data_batch_norm_validation_on_the_host(jzlib):
     assert L.jz_conv2d_describe_plan(E.JZ_BWD_DATA, ctypes.byref(d2), buf, 256) == E.JZ_OK and b"parity class" in buf.value
     d2 = jzlib.conv_desc(4, 13, 13, 64, 64, 2, 2, 3, 0)               # a filter smaller than its stride keeps the per-load variant
     assert L.jz_conv2d_describe_plan(E.JZ_BWD_DATA, ctypes.byref(d2), buf, 256) == E.JZ_OK and b"per-load" in buf.value
+
+
+def test_parity_class_keys_of_the_tuner_match_the_planner(jzlib):
+    """tune.py records a strided multi-tap backward-data layer's choice under the GEMM key of every parity class; the
+    first class's key must be the GEMM the planner reports for the layer, and with the table built in the three such
+    layers of ResNet-50 v1.5 at batch 64 come out with the table's variant, not the cost model's."""
+    import re
+    from paper_1807_11205_amd import shapes, tune
+    strided = [c for c in shapes.resnet50_convs("v1.5") if c.R > 1 and c.stride > 1 and not c.first]
+    assert len(strided) == 3
+    table = open(os.path.join(os.path.dirname(tune.__file__), "csrc", "jz_tuned_resnet50_v15.inc")).read()
+    for cs in strided:
+        rec = dict(H=cs.H, C=cs.C, K=cs.K, R=cs.R, stride=cs.stride, pad=cs.pad, batch=64, op="bwd_data")
+        keys = tune.class_dims(rec)
+        assert len(keys) == 4 and sorted(k[3] for k in keys) == [1, 2, 2, 4]           # a 3x3 stride-2 filter: classes of 1, 2, 2, 4 taps
+        d = jzlib.conv_desc(64, cs.H, cs.H, cs.C, cs.K, cs.R, cs.R, cs.stride, cs.pad)
+        text = jzlib.jz_conv2d_describe_plan(jzlib.JZ_BWD_DATA, d)
+        assert "parity class" in text and ("M %d N %d K %d:" % keys[0][:3]) in text, text
+        row = re.search(r"\{1, %d, %d, %d, %d, 1, (\d+), (\d+), (\d+), (\d+), (\d+), 1\}" % keys[0], table)
+        assert row, keys[0]
+        bm, bn, bk, wv, nst = (int(v) for v in row.groups())
+        assert ("tile %dx%dx%d, %d wavefronts, ring %d," % (bm, bn, bk, wv, nst)) in text, text
